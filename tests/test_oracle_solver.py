@@ -1,0 +1,173 @@
+"""Pins for the oracle's pivoted Cholesky, preconditioner, PCG and stochastic log-determinant (CPU only)."""
+import numpy as np
+import pytest
+import scipy.linalg as sla
+from scipy.linalg import lapack
+
+import oracle as orc
+from workloads import make_workload, well_separated_points, rademacher
+
+
+def _setup(n=60, d=2, kind=orc.RBF, noise=0.05, ls=0.35, seed=11):
+    X = well_separated_points(seed, n, d)
+    h = orc.Hyper(kind, np.full(d, ls), 1.2, noise)
+    return X, h, orc.kernel_matrix(X, X, h), orc.khat(X, h)
+
+
+def test_pivoted_cholesky_full_rank_reproduces_K():
+    X, h, K, _ = _setup(n=40, ls=0.15)
+    L, piv = orc.pivoted_cholesky(K, 40)
+    assert L.shape == (40, 40) and sorted(piv.tolist()) == list(range(40))
+    assert np.linalg.norm(L @ L.T - K) / np.linalg.norm(K) <= 1e-10
+
+
+@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52])
+def test_pivoted_cholesky_invariants_and_greedy_pivots(kind):
+    X, h, K, _ = _setup(n=80, kind=kind)
+    k = 12
+    L, piv = orc.pivoted_cholesky(K, k)
+    assert piv[0] == 0                      # diag K = s everywhere: n-way tie -> lowest index
+    assert len(set(piv.tolist())) == k
+    # pivot rows are interpolated exactly
+    A = L @ L.T
+    assert np.allclose(A[piv, :], K[piv, :], atol=1e-12)
+    # residual diagonal non-negative, trace non-increasing, pivots = greedy arg-max of dense Schur complement
+    S = K.copy()
+    prev_trace = np.trace(S)
+    for m in range(k):
+        dg = np.diag(S).copy()
+        dg[piv[:m]] = -np.inf
+        assert int(np.argmax(dg)) == piv[m]
+        p = piv[m]
+        S = S - np.outer(S[:, p], S[p, :]) / S[p, p]
+        assert np.diag(S).min() >= -1e-12
+        assert np.trace(S) <= prev_trace + 1e-12
+        prev_trace = np.trace(S)
+        Lm = L[:, :m + 1]
+        assert np.allclose(K - Lm @ Lm.T, S, atol=1e-10)
+
+
+def test_pivoted_cholesky_matches_lapack_dpstrf():
+    X, h, K, _ = _setup(n=50, ls=0.2)
+    k = 50
+    L, piv = orc.pivoted_cholesky(K, k)
+    c, lpiv, rank, info = lapack.dpstrf(K, lower=1)
+    lpiv = lpiv - 1
+    # LAPACK swaps rows physically; selection order must agree while the maxima are well separated
+    assert list(piv[:15]) == list(lpiv[:15])
+    Lp = np.tril(c)
+    # rows of LAPACK's factor are in pivoted order: L_lapack[j,:] corresponds to original row lpiv[j]
+    assert np.allclose(L[lpiv][:, :15], Lp[:, :15], atol=1e-9)
+
+
+def test_pivoted_cholesky_early_stop():
+    X = np.tile(np.array([[0.2, 0.4]], np.float32), (10, 1))      # rank-1 K
+    h = orc.Hyper(orc.RBF, [1.0, 1.0], 1.0, 0.0)
+    L, piv = orc.pivoted_cholesky(orc.kernel_matrix(X, X, h), 5, tol_abs=1e-12)
+    assert L.shape[1] == 1 and piv.tolist() == [0]
+
+
+def test_preconditioner_woodbury_and_determinant_lemma():
+    X, h, K, Kh = _setup(n=70)
+    L, _ = orc.pivoted_cholesky(K, 9)
+    R = np.random.default_rng(0).standard_normal((70, 3))
+    s2 = h.noise
+    small = s2 * np.eye(9) + L.T @ L
+    woodbury = (R - L @ np.linalg.solve(small, L.T @ R)) / s2
+    assert np.allclose(orc.precond_solve(L, s2, R), woodbury, atol=1e-9)
+    lemma = np.linalg.slogdet(small)[1] + (70 - 9) * np.log(s2)
+    assert abs(orc.precond_logdet(L, s2) - lemma) < 1e-9
+    P = orc.precond_matrix(L, s2)
+    assert np.allclose(orc.precond_solve(L, s2, P), np.eye(70), atol=1e-9)
+
+
+def test_pcg_matches_cholesky_and_terminates():
+    X, h, K, Kh = _setup(n=60)
+    b = np.random.default_rng(3).standard_normal(60)
+    ref = orc.chol_solve(Kh, b)
+    assert np.allclose(Kh @ ref, b, atol=1e-10)
+    assert np.allclose(ref, np.linalg.solve(Kh, b), atol=1e-9)
+    res = orc.pcg(Kh, b, None, max_iter=200, tol=1e-13)
+    assert np.allclose(res["u"], ref, rtol=1e-8, atol=1e-10)
+    assert res["rel_resid"][-1] <= 1e-13
+    # tolerance controls the gap to the exact solve, monotonically in tol
+    errs = []
+    for tol in (1e-1, 1e-3, 1e-6):
+        u = orc.pcg(Kh, b, None, 500, tol)["u"]
+        errs.append(np.linalg.norm(u - ref))
+        assert np.linalg.norm(Kh @ u - b) / np.linalg.norm(b) <= tol * 1.0001
+    assert errs[0] > errs[1] > errs[2]
+    # exact preconditioner -> one iteration
+    one = orc.pcg(Kh, b, np.linalg.inv(Kh), 50, 1e-10)
+    assert len(one["alphas"]) == 1 and np.allclose(one["u"], ref, atol=1e-9)
+    # preconditioned and plain systems share the solution (Method, 'Preconditioning'), in fewer iterations
+    L, _ = orc.pivoted_cholesky(K, 10)
+    Pinv = np.linalg.inv(orc.precond_matrix(L, h.noise))
+    pre = orc.pcg(Kh, b, Pinv, 200, 1e-10)
+    plain = orc.pcg(Kh, b, None, 200, 1e-10)
+    assert np.allclose(pre["u"], plain["u"], atol=1e-7)
+    assert len(pre["alphas"]) < len(plain["alphas"])
+
+
+def test_cg_tridiagonal_is_lanczos_of_preconditioned_operator():
+    X, h, K, Kh = _setup(n=30, ls=0.25, noise=0.3)
+    n = 30
+    L, _ = orc.pivoted_cholesky(K, 4)
+    P = orc.precond_matrix(L, h.noise)
+    Pinv = np.linalg.inv(P)
+    z = np.random.default_rng(8).standard_normal(n)
+    res = orc.pcg(Kh, z, Pinv, max_iter=n, tol=1e-15)
+    T = orc.tridiag_from_cg(res["alphas"], res["betas"])
+    # Ritz values inside the spectrum of P^{-1/2} Khat P^{-1/2}
+    w, Q = np.linalg.eigh(P)
+    Pmh = Q @ np.diag(w ** -0.5) @ Q.T
+    M = Pmh @ Kh @ Pmh
+    lam = np.linalg.eigvalsh(M)
+    ritz = np.linalg.eigvalsh(T)
+    assert ritz.min() >= lam.min() * (1 - 1e-8) and ritz.max() <= lam.max() * (1 + 1e-8)
+    # Gauss quadrature exact after full Lanczos: gamma0 e1^T log(T) e1 = z^T P^{-1/2} log(M) P^{-1/2} z
+    lm, Qm = np.linalg.eigh(M)
+    logM = Qm @ np.diag(np.log(lm)) @ Qm.T
+    exact = z @ Pmh @ logM @ Pmh @ z
+    # (the Krylov space is exhausted once the residual vanishes, which happens within n steps)
+    assert res["rel_resid"][-1] < 1e-12 and len(res["alphas"]) <= n
+    assert abs(res["gamma0"] * orc.slq_quadrature(T) - exact) <= 1e-6 * abs(exact) + 1e-8
+    # identity e1^T T^{-1} e1 * gamma0 = z^T Khat^{-1} z  (CG solves the system through T)
+    e1 = np.zeros(len(T)); e1[0] = 1
+    assert abs(res["gamma0"] * (e1 @ np.linalg.solve(T, e1)) - z @ orc.chol_solve(Kh, z)) < 1e-8
+
+
+def test_slq_logdet_within_monte_carlo_error():
+    w = make_workload("C1", n=256)
+    h = orc.Hyper(w.kernel_type, w.lengthscales, w.outputscale, 0.1)
+    Kh = orc.khat(w.X, h)
+    exact = orc.logdet(Kh)
+    assert abs(exact - np.linalg.slogdet(Kh)[1]) < 1e-8
+    rng = np.random.default_rng(4)
+    tp = 512
+    # no preconditioner: identity-covariance Rademacher probes
+    est, terms = orc.slq_logdet(Kh, rademacher(rng, (256, tp)), max_iter=256)
+    se = terms.std(ddof=1) / np.sqrt(tp)
+    assert abs(est - exact) <= 4 * se + 1e-6
+    # with preconditioner: probes need covariance P
+    L, _ = orc.pivoted_cholesky(orc.kernel_matrix(w.X, w.X, h), 8)
+    Z = orc.probes_with_cov_P(L, h.noise, rademacher(rng, (8, tp)), rademacher(rng, (256, tp)))
+    est2, terms2 = orc.slq_logdet(Kh, Z, L, h.noise, max_iter=256)
+    se2 = terms2.std(ddof=1) / np.sqrt(tp)
+    assert abs(est2 - exact) <= 4 * se2 + 1e-6
+    assert se2 < se          # the preconditioner removes variance
+
+
+def test_stochastic_mll_terms_within_monte_carlo_error():
+    rng = np.random.default_rng(6)
+    n, d, tp = 120, 2, 400
+    X = well_separated_points(21, n, d)
+    y = np.sin(5 * X[:, 0]) + 0.2 * rng.standard_normal(n)
+    h = orc.Hyper(orc.MATERN32, [0.3, 0.6], 1.1, 0.2)
+    K = orc.kernel_matrix(X, X, h)
+    L, _ = orc.pivoted_cholesky(K, 6)
+    Z = orc.probes_with_cov_P(L, h.noise, rademacher(rng, (6, tp)), rademacher(rng, (n, tp)))
+    out = orc.mll_stochastic_terms(X, y, h, Z, L)
+    assert abs(out["mll"] - orc.mll(X, y, h)) < 0.5
+    g = orc.mll_grad(X, y, h)
+    assert np.all(np.abs(out["grad"] - g) <= 0.15 * np.abs(g) + 0.5)
