@@ -1,0 +1,132 @@
+/*
+ * egp.h -- C ABI of libegp: the hot path of exact Gaussian-process training on one MI355X (gfx950).
+ *
+ * The kernel matrix K(X,X) is touched only through products with it; its tiles are formed on the fly
+ * in registers and never stored in device memory (paper, Method: "O(n) memory MVM-based inference" and
+ * "Partitioned kernel MVMs"). That product drives a batched preconditioned conjugate-gradient solver
+ * with a partial pivoted-Cholesky preconditioner (paper, Background: "Conjugate gradients"; Method:
+ * "Preconditioning", "PCG Convergence Criteria").
+ *
+ * Conventions common to every entry point
+ *   - "device" pointers are HIP device memory on the current device, 16-byte aligned, owned by the
+ *     caller; the library never allocates or frees device memory and keeps no pointer after return.
+ *   - "host" pointers are ordinary host memory, read or written during the call only.
+ *   - X is row-major n x d fp32. V, B, U, out are row-major n x t fp32 (t contiguous).
+ *   - ws is a device workspace of at least egp_*_ws_bytes(...) bytes (256-byte aligned); its content
+ *     on entry is ignored and on return is unspecified.
+ *   - stream is a hipStream_t passed as void* (NULL = the default stream). Work is enqueued on it;
+ *     entry points that return host results synchronise on it before returning.
+ *   - Return value: 0 on success, a negative egp_status_t otherwise; egp_last_error() then returns a
+ *     thread-local, statically stored message. Nothing is written to outputs on EGP_ERR_ARG / EGP_ERR_WS.
+ *   - Inputs are never modified.
+ */
+#ifndef EGP_H
+#define EGP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  EGP_OK = 0,
+  EGP_ERR_ARG = -1,       /* null / misaligned pointer, size out of range, bad enum, non-positive scale */
+  EGP_ERR_WS = -2,        /* workspace too small */
+  EGP_ERR_DEVICE = -3,    /* a HIP call failed; message holds hipGetErrorString */
+  EGP_ERR_BREAKDOWN = -4  /* non-positive curvature d^T Khat d in CG, or non-finite values */
+} egp_status_t;
+
+/* Stationary kernels named by the paper (Background: RBF and Matern; Experiment details: Matern-3/2;
+ * appendix: independent lengthscales). k(x,x') = outputscale * g(r), r^2 = sum_k ((x_k-x'_k)/l_k)^2,
+ *   RBF       g = exp(-r^2/2)
+ *   MATERN32  g = (1 + sqrt3 r) exp(-sqrt3 r)
+ *   MATERN52  g = (1 + sqrt5 r + 5 r^2/3) exp(-sqrt5 r)                                             */
+typedef enum { EGP_RBF = 0, EGP_MATERN32 = 1, EGP_MATERN52 = 2 } egp_kernel_t;
+
+#define EGP_D_MAX 63     /* largest input dimension */
+#define EGP_T_MAX 1024   /* largest number of right-hand-side columns */
+#define EGP_RANK_MAX 256 /* largest preconditioner rank */
+
+typedef struct {
+  int32_t kernel_type;        /* egp_kernel_t */
+  int32_t d;                  /* 1..EGP_D_MAX */
+  const float* lengthscales;  /* host, d values > 0 (a shared lengthscale is d equal values) */
+  float outputscale;          /* s > 0 */
+  float noise;                /* sigma^2 >= 0, the value added to the diagonal: Khat = K + noise*I
+                                 (paper, Background, Notation) */
+} egp_hyper_t;
+
+/* Rank-k preconditioner P = L L^T + noise*I (paper, Method, "Preconditioning").
+ * Buffers are the caller's; egp_piv_chol_precond fills them, egp_mbcg reads them. */
+typedef struct {
+  int32_t rank;      /* in: capacity of L / pivots / small; out: steps actually taken (<= capacity) */
+  float* L;          /* device, [capacity][n]: column m of the factor is contiguous (row-major k x n) */
+  int32_t* pivots;   /* host, capacity entries: original row indices in selection order */
+  double* small;     /* host, capacity*capacity + 1 doubles: lower Cholesky factor (row-major rank x rank)
+                        of noise*I + L^T L, followed at index capacity*capacity by log|P| */
+  float* small_dev;  /* device, capacity*capacity floats: inverse of noise*I + L^T L (row-major
+                        rank x rank), used by the solver to apply P^{-1} */
+} egp_precond_t;
+
+/* out = Khat V = K(X,X) V + noise V, K never materialised (paper, Method, "Partitioned kernel MVMs":
+ * row blocks of the kernel matrix are formed, multiplied and discarded; here a block lives in
+ * registers). noise = 0 gives K V. t in 1..EGP_T_MAX. Asynchronous on `stream`. */
+int egp_kmm(const float* X /*device n x d*/, int64_t n, const float* V /*device n x t*/, int32_t t,
+            const egp_hyper_t* h /*host*/, float* out /*device n x t*/, void* ws, size_t ws_bytes,
+            void* stream);
+size_t egp_kmm_ws_bytes(int64_t n, int32_t d, int32_t t);
+
+/* dout[k] = (dK/dl_k) V for k = 0..d-1, dout laid out [d][n][t]: the products the marginal-likelihood
+ * gradient needs (paper, Eq. 2). dK/dl_k [i,j] = s h(r_ij) (x_ik-x_jk)^2 / l_k^3 with h = g for RBF,
+ * 3 exp(-sqrt3 r) for MATERN32, (5/3)(1+sqrt5 r) exp(-sqrt5 r) for MATERN52. t in 1..16.
+ * Asynchronous on `stream`. */
+int egp_kmm_grad(const float* X, int64_t n, const float* V, int32_t t, const egp_hyper_t* h,
+                 float* dout /*device d x n x t*/, void* ws, size_t ws_bytes, void* stream);
+size_t egp_kmm_grad_ws_bytes(int64_t n, int32_t d, int32_t t);
+
+/* Partial pivoted Cholesky of the noise-free K from `rank` kernel rows computed on the fly (paper,
+ * Method, "Preconditioning": a rank-k preconditioner needs only k kernel rows and is built once
+ * before CG). Greedy diagonal pivoting, ties to the lowest index; stops early when the largest
+ * remaining residual diagonal is <= tol_abs. Fills P (see egp_precond_t; P->rank must hold the
+ * capacity = requested rank on entry, 1..min(n, EGP_RANK_MAX)). Synchronises on `stream`. */
+int egp_piv_chol_precond(const float* X, int64_t n, const egp_hyper_t* h, float tol_abs,
+                         egp_precond_t* P, void* ws, size_t ws_bytes, void* stream);
+size_t egp_piv_chol_precond_ws_bytes(int64_t n, int32_t d, int32_t rank);
+
+/* Batched preconditioned CG on Khat U = B for all t columns at once (paper, Background, "Conjugate
+ * gradients" and the modified PCG it cites; Method: four vectors u, r, p, z per column).
+ * Starts from U = 0. After every completed iteration the relative residuals ||r_c|| / ||b_c|| of the
+ * recurrence residual are read back; the solve stops when their maximum is <= tol or after max_iter
+ * iterations (not reaching tol is not an error). P = NULL runs plain CG.
+ *   U          device n x t, the solutions
+ *   cg_coef    host, [max_iter][2][t] doubles: alpha_j and beta_j per column (beta_j of the last
+ *              iteration is 0); from these the caller builds the Lanczos tridiagonals
+ *              T[j,j] = 1/alpha_j + beta_{j-1}/alpha_{j-1}, T[j,j+1] = sqrt(beta_j)/alpha_j.  May be NULL.
+ *   gamma0     host, t doubles: b_c^T P^{-1} b_c (quadrature weights). May be NULL.
+ *   iters_done host, one int32
+ *   rel_resid  host, t floats, relative residuals after the last iteration
+ * t in 1..33. Synchronises on `stream`. */
+int egp_mbcg(const float* X, int64_t n, const float* B, int32_t t, const egp_hyper_t* h,
+             const egp_precond_t* P, int32_t max_iter, float tol, float* U, double* cg_coef,
+             double* gamma0, int32_t* iters_done, float* rel_resid, void* ws, size_t ws_bytes,
+             void* stream);
+size_t egp_mbcg_ws_bytes(int64_t n, int32_t d, int32_t t, int32_t rank);
+
+/* Z = P^{-1} R with P = L L^T + noise*I through the Woodbury identity, R and Z device n x t.
+ * Exposed so that probe vectors and trace terms can be formed outside the solver. Asynchronous. */
+int egp_precond_apply(const egp_precond_t* P, int64_t n, float noise, const float* R, int32_t t,
+                      float* Z, void* ws, size_t ws_bytes, void* stream);
+size_t egp_precond_apply_ws_bytes(int64_t n, int32_t t, int32_t rank);
+
+/* Message of the last failing call on this thread ("" if none). */
+const char* egp_last_error(void);
+
+/* Library version, "major.minor". */
+const char* egp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EGP_H */

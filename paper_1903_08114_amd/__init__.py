@@ -1,0 +1,7 @@
+"""MI355X-native exact-GP hot path: fused kernel-matrix multiply, pivoted-Cholesky preconditioner, mBCG.
+
+Thin ctypes binding over libegp.so (argument marshalling only; every step runs in HIP kernels).
+"""
+from .binding import (EGP_RBF, EGP_MATERN32, EGP_MATERN52, EgpError, Precond, kmm, lib, lib_path)
+
+__all__ = ["EGP_RBF", "EGP_MATERN32", "EGP_MATERN52", "EgpError", "Precond", "kmm", "lib", "lib_path"]

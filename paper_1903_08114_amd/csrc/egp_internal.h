@@ -1,0 +1,53 @@
+// Internal declarations shared by the translation units of libegp (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "egp.h"
+
+namespace egp {
+
+// ---- error plumbing -------------------------------------------------------------------------
+int fail(int code, const char* fmt, ...);
+#define EGP_HIP(call)                                                                       \
+  do {                                                                                      \
+    hipError_t e_ = (call);                                                                 \
+    if (e_ != hipSuccess)                                                                   \
+      return ::egp::fail(EGP_ERR_DEVICE, "%s failed: %s", #call, hipGetErrorString(e_));    \
+  } while (0)
+
+inline size_t round_up(size_t x, size_t m) { return (x + m - 1) / m * m; }
+
+// ---- packed operand geometry ----------------------------------------------------------------
+// Points are grouped in tiles of 16. A tile of the packed point array holds KS "k-steps" of 64 floats:
+// element (s, lane) with lane = 16*q + p is scaled feature 4*s + q of point p of the tile; feature
+// index d holds the squared norm of the scaled point, larger indices are zero. This is exactly the
+// per-lane operand of one 16x16x4 fp32 MFMA step, for the row side and the column side alike.
+constexpr int kTile = 16;
+constexpr int kPadPoints = 512;  // packed arrays are padded to a multiple of this many points
+inline int ksteps_for(int d) { return (d + 1 + 3) / 4; }
+inline int64_t padded_points(int64_t n) { return (int64_t)round_up((size_t)n, kPadPoints); }
+
+struct Prepared {   // device arrays carved from a workspace by prepare_points()
+  float* Xp;        // [npad/16][KS][64]
+  float* nrm;       // [npad] squared norms of the scaled points (0 for padding)
+  int64_t n, npad;
+  int d, ks, kernel_type;
+  float outputscale, noise;
+};
+
+size_t prepared_bytes(int64_t n, int d);
+// Scale, centre and pack X for kernel `h` into ws (>= prepared_bytes). Asynchronous on stream.
+int prepare_points(const float* X, int64_t n, const egp_hyper_t* h, void* ws, Prepared* out,
+                   hipStream_t stream);
+
+// out = Khat V using prepared points. ws2 >= kmm_core_ws_bytes. V/out are row-major n x t.
+size_t kmm_core_ws_bytes(int64_t n, int t);
+int kmm_core(const Prepared& P, const float* V, int t, float* out, void* ws2, hipStream_t stream);
+
+int validate_hyper(const egp_hyper_t* h);
+int validate_ptr(const void* p, const char* name);
+
+}  // namespace egp

@@ -1,0 +1,493 @@
+// Fused kernel-matrix multiply for gfx950: out = K(X,X) V + noise V with K tiles formed in registers.
+//
+// Paper, Method, "Partitioned kernel MVMs": a row block of the kernel matrix is formed, multiplied by
+// the right-hand side and discarded. Here a "partition" is a 16x16 tile that lives in the accumulator
+// registers of one wavefront between two MFMA instructions and never reaches LDS or HBM.
+//
+// Per 16x16 tile (rows i of a wave's resident row tile, columns j streamed through LDS):
+//   1. r^2[j][i] = |x~_i|^2 + |x~_j|^2 - 2 x~_j . x~_i       KS steps of v_mfma_f32_16x16x4_f32
+//      (the -2 and |x~_j|^2 are folded into the packed column operand / a spare feature slot,
+//       |x~_i|^2 enters as the accumulator's initial value: no VALU work for the distance)
+//   2. k = g(r^2)                                             1 (RBF) or 2 (Matern) transcendentals
+//   3. out[i][:] += k[i][j] V[j][:]                           4 steps of v_mfma_f32_16x16x4_f32
+// Step 1 computes the tile transposed so that its accumulator layout (lane = row i, register r and
+// lane group q = column j = 4q + r) is exactly the A-operand layout of step 3; the contraction over j
+// is reordered accordingly, which a sum permits. V is pre-packed so that the matching B operand of
+// step 3 is one 16-byte LDS read per lane.
+
+#include "egp_internal.h"
+
+namespace egp {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// Scale applied to x/l so that the MFMA result is the argument the transform wants:
+//   RBF:  acc = r^2 log2(e)/2        k = exp2(-acc)
+//   M32:  acc = (sqrt3 r log2 e)^2   a = sqrt(acc), k = (1 + a ln2) exp2(-a)
+//   M52:  acc = (sqrt5 r log2 e)^2   a = sqrt(acc), k = (1 + a ln2 + (a ln2)^2/3) exp2(-a)
+static double point_scale(int kernel_type) {
+  switch (kernel_type) {
+    case EGP_RBF: return sqrt(0.5 * 1.4426950408889634);
+    case EGP_MATERN32: return sqrt(3.0) * 1.4426950408889634;
+    default: return sqrt(5.0) * 1.4426950408889634;
+  }
+}
+
+template <int KIND>
+__device__ __forceinline__ float transform(float acc) {
+  if constexpr (KIND == EGP_RBF) {
+    return __builtin_amdgcn_exp2f(-acc);
+  } else if constexpr (KIND == EGP_MATERN32) {
+    float a = __builtin_amdgcn_sqrtf(__builtin_fabsf(acc));
+    return __builtin_fmaf(a, kLn2, 1.0f) * __builtin_amdgcn_exp2f(-a);
+  } else {
+    float a = __builtin_amdgcn_sqrtf(__builtin_fabsf(acc));
+    float poly = __builtin_fmaf(__builtin_fmaf(a, kLn2 * kLn2 / 3.0f, kLn2), a, 1.0f);
+    return poly * __builtin_amdgcn_exp2f(-a);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Row preparation (HBM-bound, O(n d)): column means, then scaled + centred + packed points.
+// ------------------------------------------------------------------------------------------------
+constexpr int kMeanBlocks = 256;
+
+__global__ __launch_bounds__(256) void col_sum_partial(const float* __restrict__ X, int64_t n, int d,
+                                                       float* __restrict__ partial /*[blocks][64]*/) {
+  // thread t handles feature t % d of points t / d + k * (256/d) ... keep it simple: strided over elements
+  __shared__ float red[256];
+  const int per = 256 / d;                 // points handled per block iteration
+  const int f = threadIdx.x % d, sub = threadIdx.x / d;
+  float acc = 0.f;
+  if (sub < per) {
+    for (int64_t p = (int64_t)blockIdx.x * per + sub; p < n; p += (int64_t)gridDim.x * per)
+      acc += X[p * d + f];
+  }
+  red[threadIdx.x] = (sub < per) ? acc : 0.f;
+  __syncthreads();
+  if (threadIdx.x < d) {
+    float s = 0.f;
+    for (int k = 0; k < per; ++k) s += red[k * d + threadIdx.x];
+    partial[blockIdx.x * 64 + threadIdx.x] = s;
+  }
+}
+
+__global__ __launch_bounds__(64) void col_mean_final(const float* __restrict__ partial, int blocks,
+                                                     int64_t n, int d, float* __restrict__ mean) {
+  if ((int)threadIdx.x < d) {
+    double s = 0.0;
+    for (int b = 0; b < blocks; ++b) s += (double)partial[b * 64 + threadIdx.x];
+    mean[threadIdx.x] = (float)(s / (double)n);
+  }
+}
+
+struct ScaleArg { float inv[EGP_D_MAX + 1]; };
+
+// One thread per (padded) point: x~ = (x - mean) * scale / l, norm = sum x~^2, scattered into the
+// packed MFMA-operand layout. Column-side factor -2 is NOT applied here; the kernel's row operand
+// carries it (see kmm_kernel).
+__global__ __launch_bounds__(256) void pack_points(const float* __restrict__ X, int64_t n, int64_t npad,
+                                                   int d, int ks, const float* __restrict__ mean,
+                                                   ScaleArg sc, float* __restrict__ Xp,
+                                                   float* __restrict__ nrm) {
+  int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (p >= npad) return;
+  const int64_t tile = p >> 4;
+  const int pp = (int)(p & 15);
+  float* base = Xp + tile * ks * 64;
+  float norm = 0.f;
+  const bool real = p < n;
+  for (int f = 0; f < ks * 4; ++f) {
+    float v = 0.f;
+    if (f < d && real) {
+      v = (X[p * d + f] - mean[f]) * sc.inv[f];
+      norm = __builtin_fmaf(v, v, norm);
+    }
+    if (f != d) base[(f >> 2) * 64 + (f & 3) * 16 + pp] = v;
+  }
+  base[(d >> 2) * 64 + (d & 3) * 16 + pp] = norm;
+  nrm[p] = norm;
+}
+
+// V (n x t row-major), columns [c0, c0 + 16*NB) -> Vp[tile][nb][lane][r] = V[16 tile + 4q + r][c0+16nb+p]
+// (zero beyond n or beyond t), and optionally column c0 + 16*NB -> Ep[point].
+__global__ __launch_bounds__(256) void pack_rhs(const float* __restrict__ V, int64_t n, int64_t npad, int t,
+                                                int c0, int nb_count, int extra, f4* __restrict__ Vp,
+                                                float* __restrict__ Ep) {
+  int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;     // (tile, nb, lane)
+  const int64_t total = (npad >> 4) * nb_count * 64;
+  if (g < total) {
+    const int lane = (int)(g & 63);
+    const int64_t tn = g >> 6;
+    const int nb = (int)(tn % nb_count);
+    const int64_t tile = tn / nb_count;
+    const int q = lane >> 4, p = lane & 15;
+    const int c = c0 + nb * 16 + p;
+    f4 v = {0.f, 0.f, 0.f, 0.f};
+    if (c < t) {
+      const int64_t j = tile * 16 + q * 4;
+      if (j + 0 < n) v.x = V[(j + 0) * t + c];
+      if (j + 1 < n) v.y = V[(j + 1) * t + c];
+      if (j + 2 < n) v.z = V[(j + 2) * t + c];
+      if (j + 3 < n) v.w = V[(j + 3) * t + c];
+    }
+    Vp[g] = v;
+  }
+  if (extra && g < npad) {
+    const int c = c0 + nb_count * 16;
+    Ep[g] = (g < n && c < t) ? V[g * t + c] : 0.f;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// The fused kernel.
+//   grid.x = row blocks (4 waves x R row tiles x 16 rows), grid.y = column splits
+//   block  = 256 threads; each wave owns R row tiles for the whole column sweep of its split
+//   LDS    = double-buffered stage of JT column tiles: packed points, packed V, extra column
+//   Part   = [split][npad][TS] raw accumulators (TS = 16 NB + EXTRA); the epilogue kernel reduces
+//            splits in a fixed order, scales by the outputscale and adds noise * V.
+// ------------------------------------------------------------------------------------------------
+template <int KS, int R, int KIND, int NB, int EXTRA, int JT>
+__global__ __launch_bounds__(256, 2) void kmm_kernel(const float* __restrict__ Xp,
+                                                     const float* __restrict__ nrm,
+                                                     const f4* __restrict__ Vp,
+                                                     const float* __restrict__ Ep,
+                                                     float* __restrict__ Part, int64_t npad, int d,
+                                                     int stages_per_split, int stages_total) {
+  constexpr int TS = 16 * NB + EXTRA;
+  constexpr int XF4 = JT * KS * 16;       // f4 elements of packed points per stage
+  constexpr int VF4 = JT * NB * 64;       // f4 elements of packed V per stage
+  constexpr int EF4 = JT * 4;             // f4 elements of the extra column per stage
+  constexpr int NX = (XF4 + 255) / 256;
+  constexpr int NV = (VF4 + 255) / 256;
+
+  __shared__ f4 Xs[2][XF4];
+  __shared__ f4 Vs[2][VF4];
+  __shared__ f4 Es[2][EXTRA ? EF4 : 1];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int q = lane >> 4, p = lane & 15;
+
+  // ---- resident row operands ----
+  const int64_t row_tile0 = ((int64_t)blockIdx.x * 4 + wave) * R;
+  float b[R][KS];
+  f4 cq[R];
+  f4 o[R][NB];
+  float eacc[R];
+  const int ds = d >> 2, dq = d & 3;
+#pragma unroll
+  for (int it = 0; it < R; ++it) {
+    const float* src = Xp + (row_tile0 + it) * KS * 64 + lane;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      float v = -2.0f * src[s * 64];
+      if (s == ds && q == dq) v = 1.0f;     // the slot that multiplies the column point's norm
+      b[it][s] = v;
+    }
+    const float ni = nrm[(row_tile0 + it) * 16 + p];
+    cq[it] = (f4){ni, ni, ni, ni};
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) o[it][nb] = (f4){0.f, 0.f, 0.f, 0.f};
+    eacc[it] = 0.f;
+  }
+
+  const int st_begin = blockIdx.y * stages_per_split;
+  int st_end = st_begin + stages_per_split;
+  if (st_end > stages_total) st_end = stages_total;
+
+  const f4* Xg = reinterpret_cast<const f4*>(Xp);
+  const f4* Eg = reinterpret_cast<const f4*>(Ep);
+  f4 px[NX], pv[NV], pe;
+
+  auto fetch = [&](int st) {
+    const int64_t xoff = (int64_t)st * XF4, voff = (int64_t)st * VF4, eoff = (int64_t)st * EF4;
+#pragma unroll
+    for (int k = 0; k < NX; ++k) {
+      const int idx = tid + k * 256;
+      if (XF4 % 256 == 0 || idx < XF4) px[k] = Xg[xoff + idx];
+    }
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      const int idx = tid + k * 256;
+      if (VF4 % 256 == 0 || idx < VF4) pv[k] = Vp[voff + idx];
+    }
+    if (EXTRA && tid < EF4) pe = Eg[eoff + tid];
+  };
+  auto stash = [&](int buf) {
+#pragma unroll
+    for (int k = 0; k < NX; ++k) {
+      const int idx = tid + k * 256;
+      if (XF4 % 256 == 0 || idx < XF4) Xs[buf][idx] = px[k];
+    }
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      const int idx = tid + k * 256;
+      if (VF4 % 256 == 0 || idx < VF4) Vs[buf][idx] = pv[k];
+    }
+    if (EXTRA && tid < EF4) Es[buf][tid] = pe;
+  };
+
+  if (st_begin < st_end) {
+    fetch(st_begin);
+    stash(0);
+  }
+  __syncthreads();
+
+  for (int st = st_begin; st < st_end; ++st) {
+    const int buf = (st - st_begin) & 1;
+    const bool more = st + 1 < st_end;
+    if (more) fetch(st + 1);
+
+    const float* xs = reinterpret_cast<const float*>(Xs[buf]);
+#pragma unroll 2
+    for (int jt = 0; jt < JT; ++jt) {
+      float a[KS];
+#pragma unroll
+      for (int s = 0; s < KS; ++s) a[s] = xs[(jt * KS + s) * 64 + lane];
+      f4 v[NB];
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) v[nb] = Vs[buf][(jt * NB + nb) * 64 + lane];
+      f4 e = {0.f, 0.f, 0.f, 0.f};
+      if (EXTRA) e = Es[buf][jt * 4 + q];
+#pragma unroll
+      for (int it = 0; it < R; ++it) {
+        f4 acc = cq[it];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s], b[it][s], acc, 0, 0, 0);
+        f4 k;
+        k.x = transform<KIND>(acc.x);
+        k.y = transform<KIND>(acc.y);
+        k.z = transform<KIND>(acc.z);
+        k.w = transform<KIND>(acc.w);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+          o[it][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(k.x, v[nb].x, o[it][nb], 0, 0, 0);
+          o[it][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(k.y, v[nb].y, o[it][nb], 0, 0, 0);
+          o[it][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(k.z, v[nb].z, o[it][nb], 0, 0, 0);
+          o[it][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(k.w, v[nb].w, o[it][nb], 0, 0, 0);
+        }
+        if (EXTRA) {
+          eacc[it] = __builtin_fmaf(k.x, e.x, eacc[it]);
+          eacc[it] = __builtin_fmaf(k.y, e.y, eacc[it]);
+          eacc[it] = __builtin_fmaf(k.z, e.z, eacc[it]);
+          eacc[it] = __builtin_fmaf(k.w, e.w, eacc[it]);
+        }
+      }
+    }
+    if (more) stash(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- write raw accumulators: lane (q,p), register r holds out[row 4q + r][column p] ----
+  float* dst = Part + (int64_t)blockIdx.y * npad * TS;
+#pragma unroll
+  for (int it = 0; it < R; ++it) {
+    const int64_t row0 = (row_tile0 + it) * 16;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      float* r0 = dst + (row0 + q * 4) * TS + nb * 16 + p;
+      r0[0 * TS] = o[it][nb].x;
+      r0[1 * TS] = o[it][nb].y;
+      r0[2 * TS] = o[it][nb].z;
+      r0[3 * TS] = o[it][nb].w;
+    }
+    if (EXTRA) {
+      float s = eacc[it];
+      s += __shfl_xor(s, 16);
+      s += __shfl_xor(s, 32);
+      if (q == 0) dst[(row0 + p) * TS + 16 * NB] = s;
+    }
+  }
+}
+
+// out[row][c0 + c] = s * sum_split Part[split][row][c] + noise * V[row][c0 + c]
+__global__ __launch_bounds__(256) void kmm_epilogue(const float* __restrict__ Part, int splits, int64_t npad,
+                                                    int ts, const float* __restrict__ V, int64_t n, int t,
+                                                    int c0, int tg, float s, float noise,
+                                                    float* __restrict__ out) {
+  int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (g >= n * tg) return;
+  const int64_t row = g / tg;
+  const int c = (int)(g % tg);
+  float acc = 0.f;
+  for (int sp = 0; sp < splits; ++sp) acc += Part[((int64_t)sp * npad + row) * ts + c];
+  const int64_t o = row * t + c0 + c;
+  out[o] = __builtin_fmaf(s, acc, noise * V[o]);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Host side
+// ------------------------------------------------------------------------------------------------
+size_t prepared_bytes(int64_t n, int d) {
+  const int64_t npad = padded_points(n);
+  const int ks = ksteps_for(d);
+  size_t b = 0;
+  b += round_up((size_t)npad * ks * 4 * sizeof(float), 256);   // Xp
+  b += round_up((size_t)npad * sizeof(float), 256);            // nrm
+  b += round_up((size_t)kMeanBlocks * 64 * sizeof(float), 256);  // partial sums
+  b += 256;                                                    // mean
+  return b;
+}
+
+int prepare_points(const float* X, int64_t n, const egp_hyper_t* h, void* ws, Prepared* out,
+                   hipStream_t stream) {
+  const int d = h->d;
+  const int64_t npad = padded_points(n);
+  const int ks = ksteps_for(d);
+  char* w = static_cast<char*>(ws);
+  out->Xp = reinterpret_cast<float*>(w);
+  w += round_up((size_t)npad * ks * 4 * sizeof(float), 256);
+  out->nrm = reinterpret_cast<float*>(w);
+  w += round_up((size_t)npad * sizeof(float), 256);
+  float* partial = reinterpret_cast<float*>(w);
+  w += round_up((size_t)kMeanBlocks * 64 * sizeof(float), 256);
+  float* mean = reinterpret_cast<float*>(w);
+  out->n = n;
+  out->npad = npad;
+  out->d = d;
+  out->ks = ks;
+  out->kernel_type = h->kernel_type;
+  out->outputscale = h->outputscale;
+  out->noise = h->noise;
+
+  ScaleArg sc;
+  const double c = point_scale(h->kernel_type);
+  for (int f = 0; f <= EGP_D_MAX; ++f) sc.inv[f] = f < d ? (float)(c / (double)h->lengthscales[f]) : 0.f;
+
+  hipLaunchKernelGGL(col_sum_partial, dim3(kMeanBlocks), dim3(256), 0, stream, X, n, d, partial);
+  hipLaunchKernelGGL(col_mean_final, dim3(1), dim3(64), 0, stream, partial, kMeanBlocks, n, d, mean);
+  hipLaunchKernelGGL(pack_points, dim3((unsigned)((npad + 255) / 256)), dim3(256), 0, stream, X, n, npad, d,
+                     ks, mean, sc, out->Xp, out->nrm);
+  EGP_HIP(hipGetLastError());
+  return EGP_OK;
+}
+
+namespace {
+
+struct Shape { int R, JT; };
+
+struct Plan {
+  bool big;
+  int splits, stages_per_split, stages_total, row_blocks;
+};
+
+constexpr int kBigR = 8, kBigJT = 16, kSmallR = 2, kSmallJT = 4;
+
+Plan make_plan(int64_t npad) {
+  Plan pl;
+  const int64_t big_rows = 64 * kBigR;
+  pl.big = npad / big_rows >= 64;          // enough row blocks for the wide shape to be worthwhile
+  const int R = pl.big ? kBigR : kSmallR, JT = pl.big ? kBigJT : kSmallJT;
+  pl.row_blocks = (int)(npad / (64 * R));
+  pl.stages_total = (int)(npad / (16 * JT));
+  int want = 1024 / pl.row_blocks;
+  if (want < 1) want = 1;
+  if (want > pl.stages_total) want = pl.stages_total;
+  if (want > 64) want = 64;
+  pl.stages_per_split = (pl.stages_total + want - 1) / want;
+  pl.splits = (pl.stages_total + pl.stages_per_split - 1) / pl.stages_per_split;
+  return pl;
+}
+
+template <int KS, int KIND, int NB, int EXTRA>
+int launch_shape(const Prepared& P, const Plan& pl, const f4* Vp, const float* Ep, float* Part,
+                 hipStream_t stream) {
+  dim3 grid(pl.row_blocks, pl.splits), block(256);
+  if (pl.big) {
+    hipLaunchKernelGGL((kmm_kernel<KS, kBigR, KIND, NB, EXTRA, kBigJT>), grid, block, 0, stream, P.Xp, P.nrm,
+                       Vp, Ep, Part, P.npad, P.d, pl.stages_per_split, pl.stages_total);
+  } else {
+    hipLaunchKernelGGL((kmm_kernel<KS, kSmallR, KIND, NB, EXTRA, kSmallJT>), grid, block, 0, stream, P.Xp,
+                       P.nrm, Vp, Ep, Part, P.npad, P.d, pl.stages_per_split, pl.stages_total);
+  }
+  EGP_HIP(hipGetLastError());
+  return EGP_OK;
+}
+
+template <int KS, int KIND>
+int launch_cols(const Prepared& P, const Plan& pl, int nb, int extra, const f4* Vp, const float* Ep,
+                float* Part, hipStream_t stream) {
+  if (nb == 1 && !extra) return launch_shape<KS, KIND, 1, 0>(P, pl, Vp, Ep, Part, stream);
+  if (nb == 1 && extra) return launch_shape<KS, KIND, 1, 1>(P, pl, Vp, Ep, Part, stream);
+  if (nb == 2 && !extra) return launch_shape<KS, KIND, 2, 0>(P, pl, Vp, Ep, Part, stream);
+  return launch_shape<KS, KIND, 2, 1>(P, pl, Vp, Ep, Part, stream);
+}
+
+template <int KS>
+int launch_kind(const Prepared& P, const Plan& pl, int nb, int extra, const f4* Vp, const float* Ep,
+                float* Part, hipStream_t stream) {
+  switch (P.kernel_type) {
+    case EGP_RBF: return launch_cols<KS, EGP_RBF>(P, pl, nb, extra, Vp, Ep, Part, stream);
+    case EGP_MATERN32: return launch_cols<KS, EGP_MATERN32>(P, pl, nb, extra, Vp, Ep, Part, stream);
+    default: return launch_cols<KS, EGP_MATERN52>(P, pl, nb, extra, Vp, Ep, Part, stream);
+  }
+}
+
+}  // namespace
+
+static int widest_ts(int t) { return t <= 16 ? 16 : (t == 17 ? 17 : (t <= 32 ? 32 : 33)); }
+
+size_t kmm_core_ws_bytes(int64_t n, int t) {
+  const int64_t npad = padded_points(n);
+  const Plan pl = make_plan(npad);
+  const int nb = t > 17 ? 2 : 1;
+  size_t b = 0;
+  b += round_up((size_t)npad * nb * 16 * sizeof(float), 256);                    // Vp
+  b += round_up((size_t)npad * sizeof(float), 256);                              // Ep
+  b += round_up((size_t)pl.splits * npad * widest_ts(t) * sizeof(float), 256);   // Part
+  return b;
+}
+
+int kmm_core(const Prepared& P, const float* V, int t, float* out, void* ws2, hipStream_t stream) {
+  const int64_t npad = P.npad;
+  const Plan pl = make_plan(npad);
+  char* w = static_cast<char*>(ws2);
+  const int tg_max = t > 33 ? 33 : t;
+  const int nb_max = tg_max > 17 ? 2 : 1;
+  f4* Vp = reinterpret_cast<f4*>(w);
+  w += round_up((size_t)npad * nb_max * 16 * sizeof(float), 256);
+  float* Ep = reinterpret_cast<float*>(w);
+  w += round_up((size_t)npad * sizeof(float), 256);
+  float* Part = reinterpret_cast<float*>(w);
+
+  int c0 = 0;
+  while (c0 < t) {
+    const int rem = t - c0;
+    int nb, extra, tg;
+    if (rem <= 16) { nb = 1; extra = 0; tg = rem; }
+    else if (rem == 17) { nb = 1; extra = 1; tg = 17; }
+    else if (rem <= 32) { nb = 2; extra = 0; tg = rem; }
+    else if (rem == 33) { nb = 2; extra = 1; tg = 33; }
+    else { nb = 2; extra = 0; tg = 32; }
+    const int ts = 16 * nb + extra;
+    const int64_t total = (npad >> 4) * nb * 64;
+    const int64_t threads = total > npad ? total : npad;
+    hipLaunchKernelGGL(pack_rhs, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream, V, P.n, npad,
+                       t, c0, nb, extra, Vp, Ep);
+    int rc;
+    switch (P.ks) {
+      case 1: rc = launch_kind<1>(P, pl, nb, extra, Vp, Ep, Part, stream); break;
+      case 2: rc = launch_kind<2>(P, pl, nb, extra, Vp, Ep, Part, stream); break;
+      case 3: rc = launch_kind<3>(P, pl, nb, extra, Vp, Ep, Part, stream); break;
+      case 4: rc = launch_kind<4>(P, pl, nb, extra, Vp, Ep, Part, stream); break;
+      case 5: rc = launch_kind<5>(P, pl, nb, extra, Vp, Ep, Part, stream); break;
+      case 6: rc = launch_kind<6>(P, pl, nb, extra, Vp, Ep, Part, stream); break;
+      case 7: rc = launch_kind<7>(P, pl, nb, extra, Vp, Ep, Part, stream); break;
+      case 8: rc = launch_kind<8>(P, pl, nb, extra, Vp, Ep, Part, stream); break;
+      default: return fail(EGP_ERR_ARG, "d = %d needs %d k-steps; this build supports d <= 31", P.d, P.ks);
+    }
+    if (rc != EGP_OK) return rc;
+    const int64_t outs = P.n * tg;
+    hipLaunchKernelGGL(kmm_epilogue, dim3((unsigned)((outs + 255) / 256)), dim3(256), 0, stream, Part,
+                       pl.splits, npad, ts, V, P.n, t, c0, tg, P.outputscale, P.noise, out);
+    EGP_HIP(hipGetLastError());
+    c0 += tg;
+  }
+  return EGP_OK;
+}
+
+}  // namespace egp

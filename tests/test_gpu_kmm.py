@@ -1,0 +1,111 @@
+"""Parity of the fused HIP kernel-matrix multiply with the dense fp64 oracle (through the C ABI)."""
+import numpy as np
+import pytest
+
+import oracle as orc
+from workloads import make_workload
+
+pytestmark = pytest.mark.gpu
+
+# the benchmark spec: relative Frobenius error of the KMM <= 1e-4 at fp32 (no reduced-precision MFMA is used)
+KMM_TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def egp():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_1903_08114_amd as egp
+    egp.lib()
+    return egp
+
+
+def _run(egp, X, V, ls, s, noise, kind):
+    import torch
+    Xd = torch.from_numpy(np.ascontiguousarray(X)).cuda()
+    Vd = torch.from_numpy(np.ascontiguousarray(V)).cuda()
+    out = egp.kmm(Xd, Vd, ls, s, noise, kind)
+    torch.cuda.synchronize()
+    return out.cpu().numpy().astype(np.float64)
+
+
+def _rel(a, b):
+    return np.linalg.norm(a - b) / np.linalg.norm(b)
+
+
+def test_kmm_c1_full(egp):
+    w = make_workload("C1")
+    got = _run(egp, w.X, w.V, w.lengthscales, w.outputscale, w.noise, w.kernel_type)
+    ref = orc.kmm(w.X, w.V, orc.Hyper(w.kernel_type, w.lengthscales, w.outputscale, w.noise))
+    err = _rel(got, ref)
+    print("C1 KMM rel err", err)
+    assert err <= KMM_TOL
+    # per-column too
+    for c in range(w.t):
+        assert _rel(got[:, c], ref[:, c]) <= KMM_TOL
+
+
+@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52])
+@pytest.mark.parametrize("n,d,t", [(1, 1, 1), (15, 3, 2), (16, 4, 16), (17, 7, 17), (257, 11, 16), (1000, 8, 5),
+                                   (2049, 18, 17), (3001, 25, 16), (777, 31, 33), (1300, 12, 32),
+                                   (600, 2, 40), (513, 5, 70)])
+def test_kmm_shapes(egp, kind, n, d, t):
+    rng = np.random.default_rng(1000 * n + 10 * d + t + kind)
+    X = rng.uniform(-1, 1, (n, d)).astype(np.float32)
+    V = rng.standard_normal((n, t)).astype(np.float32)
+    ls = np.exp(rng.uniform(np.log(0.3), np.log(3.0), d)).astype(np.float32)
+    s, noise = 1.7, 0.3
+    got = _run(egp, X, V, ls, s, noise, kind)
+    ref = orc.kmm(X, V, orc.Hyper(kind, ls, s, noise))
+    assert got.shape == ref.shape
+    assert np.isfinite(got).all()
+    assert _rel(got, ref) <= KMM_TOL
+
+
+def test_kmm_c2_recipe_rows(egp):
+    """Larger case, big-tile launch shape with column splits: sampled rows computed exactly by the oracle."""
+    w = make_workload("C2", n=40000)
+    got = _run(egp, w.X, w.V, w.lengthscales, w.outputscale, w.noise, w.kernel_type)
+    rows = np.random.default_rng(7).choice(w.n, 192, replace=False)
+    rows[:3] = [0, w.n - 1, w.n // 2]
+    ref = orc.kmm_rows(w.X, w.V, orc.Hyper(w.kernel_type, w.lengthscales, w.outputscale, w.noise), rows)
+    assert _rel(got[rows], ref) <= KMM_TOL
+
+
+def test_kmm_special_cases(egp):
+    rng = np.random.default_rng(3)
+    n, d, t = 700, 4, 16
+    X = rng.uniform(0, 1, (n, d)).astype(np.float32)
+    V = rng.standard_normal((n, t)).astype(np.float32)
+    s, noise = 1.3, 0.2
+    # huge lengthscale: K -> s 1 1^T
+    got = _run(egp, X, V, np.full(d, 1e6, np.float32), s, noise, orc.RBF)
+    expect = s * V.astype(np.float64).sum(axis=0, keepdims=True) + noise * V.astype(np.float64)
+    assert _rel(got, expect) <= KMM_TOL
+    # identical points
+    same = np.tile(X[:1], (n, 1))
+    got = _run(egp, same, V, np.full(d, 0.5, np.float32), s, noise, orc.MATERN32)
+    assert _rel(got, expect) <= KMM_TOL
+    # noise = 0 gives K V; determinism: two runs bitwise equal
+    a = _run(egp, X, V, np.full(d, 0.5, np.float32), s, 0.0, orc.MATERN52)
+    b = _run(egp, X, V, np.full(d, 0.5, np.float32), s, 0.0, orc.MATERN52)
+    assert np.array_equal(a, b)
+    ref = orc.kmm(X, V, orc.Hyper(orc.MATERN52, np.full(d, 0.5), s, 0.0))
+    assert _rel(a, ref) <= KMM_TOL
+
+
+def test_kmm_argument_errors(egp):
+    import torch
+    X = torch.zeros(32, 3, device="cuda")
+    V = torch.zeros(32, 2, device="cuda")
+    with pytest.raises(egp.EgpError):
+        egp.kmm(X, V, [1.0, -1.0, 1.0], 1.0, 0.1, 0)
+    with pytest.raises(egp.EgpError):
+        egp.kmm(X, V, [1.0, 1.0, 1.0], 1.0, 0.1, 7)
+    with pytest.raises(egp.EgpError):
+        egp.kmm(X, V, [1.0, 1.0, 1.0], 1.0, -0.1, 0)
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(egp.EgpError) as ei:
+        egp.kmm(X, V, [1.0, 1.0, 1.0], 1.0, 0.1, 0, ws=small)
+    assert ei.value.code == -2
