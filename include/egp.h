@@ -112,7 +112,7 @@ int egp_mbcg(const float* X, int64_t n, const float* B, int32_t t, const egp_hyp
              const egp_precond_t* P, int32_t max_iter, float tol, float* U, double* cg_coef,
              double* gamma0, int32_t* iters_done, float* rel_resid, void* ws, size_t ws_bytes,
              void* stream);
-size_t egp_mbcg_ws_bytes(int64_t n, int32_t d, int32_t t, int32_t rank);
+size_t egp_mbcg_ws_bytes(int64_t n, int32_t d, int32_t t, int32_t rank, int32_t max_iter);
 
 /* Z = P^{-1} R with P = L L^T + noise*I through the Woodbury identity, R and Z device n x t.
  * Exposed so that probe vectors and trace terms can be formed outside the solver. Asynchronous. */

@@ -41,8 +41,23 @@ def lib():
         L = C.CDLL(path)
         L.egp_last_error.restype = C.c_char_p
         L.egp_version.restype = C.c_char_p
-        for name in ("egp_kmm_ws_bytes",):
+        for name in ("egp_kmm_ws_bytes", "egp_piv_chol_precond_ws_bytes", "egp_mbcg_ws_bytes",
+                     "egp_precond_apply_ws_bytes"):
             getattr(L, name).restype = C.c_size_t
+        L.egp_piv_chol_precond_ws_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32]
+        L.egp_mbcg_ws_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+        L.egp_precond_apply_ws_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32]
+        L.egp_piv_chol_precond.restype = C.c_int
+        L.egp_piv_chol_precond.argtypes = [C.c_void_p, C.c_int64, C.POINTER(_Hyper), C.c_float,
+                                           C.POINTER(_Precond), C.c_void_p, C.c_size_t, C.c_void_p]
+        L.egp_precond_apply.restype = C.c_int
+        L.egp_precond_apply.argtypes = [C.POINTER(_Precond), C.c_int64, C.c_float, C.c_void_p, C.c_int32,
+                                        C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.egp_mbcg.restype = C.c_int
+        L.egp_mbcg.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.POINTER(_Hyper),
+                               C.POINTER(_Precond), C.c_int32, C.c_float, C.c_void_p,
+                               C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int32),
+                               C.POINTER(C.c_float), C.c_void_p, C.c_size_t, C.c_void_p]
         L.egp_kmm_ws_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32]
         L.egp_kmm.restype = C.c_int
         L.egp_kmm.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.POINTER(_Hyper), C.c_void_p,
@@ -83,8 +98,43 @@ def _workspace(nbytes, device):
 
 
 class Precond:
-    """Buffers of a rank-k pivoted-Cholesky preconditioner (filled by piv_chol_precond)."""
-    pass
+    """Buffers of a rank-k pivoted-Cholesky preconditioner P = L L^T + noise I (filled by piv_chol_precond).
+
+    L: (rank, n) float32 CUDA tensor (column m of the factor is row m here); pivots: numpy int32;
+    chol_small: (rank, rank) float64 lower factor of noise I + L^T L; logdet: log|P|."""
+
+    def __init__(self, n, capacity, device):
+        import numpy as np
+        import torch
+        self.n, self.capacity, self.rank = int(n), int(capacity), 0
+        self.L_buf = torch.empty((capacity, n), dtype=torch.float32, device=device)
+        self.small_dev = torch.empty((capacity * capacity,), dtype=torch.float32, device=device)
+        self._pivots = np.zeros(capacity, dtype=np.int32)
+        self._small = np.zeros(capacity * capacity + 1, dtype=np.float64)
+        self.noise = None
+
+    def _struct(self, rank):
+        return _Precond(int(rank), C.c_void_p(self.L_buf.data_ptr()),
+                        self._pivots.ctypes.data_as(C.POINTER(C.c_int32)),
+                        self._small.ctypes.data_as(C.POINTER(C.c_double)),
+                        C.c_void_p(self.small_dev.data_ptr()))
+
+    @property
+    def L(self):
+        return self.L_buf[:self.rank]
+
+    @property
+    def pivots(self):
+        return self._pivots[:self.rank].copy()
+
+    @property
+    def chol_small(self):
+        k = self.rank
+        return self._small[:k * k].reshape(k, k).copy()
+
+    @property
+    def logdet(self):
+        return float(self._small[self.capacity * self.capacity])
 
 
 def kmm(X, V, lengthscales, outputscale, noise, kernel_type, out=None, ws=None):
@@ -102,3 +152,66 @@ def kmm(X, V, lengthscales, outputscale, noise, kernel_type, out=None, ws=None):
     _check(L.egp_kmm(_dev(X, "X"), n, _dev(V, "V"), t, C.byref(h), _dev(out, "out"),
                      C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
     return out
+
+
+def piv_chol_precond(X, lengthscales, outputscale, noise, kernel_type, rank, tol_abs=0.0, ws=None):
+    """Rank-`rank` pivoted-Cholesky preconditioner of K(X,X) (egp_piv_chol_precond). Returns a Precond."""
+    L = lib()
+    n, d = X.shape
+    h = _hyper(kernel_type, lengthscales, outputscale, noise)
+    P = Precond(n, rank, X.device)
+    st = P._struct(rank)
+    need = L.egp_piv_chol_precond_ws_bytes(n, d, rank)
+    if ws is None:
+        ws = _workspace(need, X.device)
+    _check(L.egp_piv_chol_precond(_dev(X, "X"), n, C.byref(h), float(tol_abs), C.byref(st),
+                                  C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
+    P.rank = int(st.rank)
+    P.noise = float(noise)
+    return P
+
+
+def precond_apply(P, R, noise=None, out=None, ws=None):
+    """Z = P^{-1} R (egp_precond_apply)."""
+    import torch
+    L = lib()
+    n, t = R.shape
+    if out is None:
+        out = torch.empty_like(R)
+    need = L.egp_precond_apply_ws_bytes(n, t, max(P.rank, 1))
+    if ws is None:
+        ws = _workspace(need, R.device)
+    st = P._struct(P.rank)
+    _check(L.egp_precond_apply(C.byref(st), n, float(P.noise if noise is None else noise), _dev(R, "R"), t,
+                               _dev(out, "Z"), C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
+    return out
+
+
+def mbcg(X, B, lengthscales, outputscale, noise, kernel_type, precond=None, max_iter=100, tol=1e-2, ws=None):
+    """Batched PCG solve of (K + noise I) U = B (egp_mbcg).
+
+    Returns dict: U (n,t) tensor, iters, rel_resid (t,), alphas/betas (iters,t) float64, gamma0 (t,)."""
+    import numpy as np
+    import torch
+    L = lib()
+    n, d = X.shape
+    t = B.shape[1]
+    h = _hyper(kernel_type, lengthscales, outputscale, noise)
+    U = torch.empty_like(B)
+    rank = precond.rank if precond is not None else 0
+    need = L.egp_mbcg_ws_bytes(n, d, t, rank, max_iter)
+    if ws is None:
+        ws = _workspace(need, X.device)
+    coef = np.zeros((max(max_iter, 1), 2, t), dtype=np.float64)
+    gamma0 = np.zeros(t, dtype=np.float64)
+    iters = C.c_int32(0)
+    rel = np.zeros(t, dtype=np.float32)
+    st = precond._struct(precond.rank) if precond is not None else None
+    _check(L.egp_mbcg(_dev(X, "X"), n, _dev(B, "B"), t, C.byref(h), C.byref(st) if st is not None else None,
+                      int(max_iter), float(tol), _dev(U, "U"), coef.ctypes.data_as(C.POINTER(C.c_double)),
+                      gamma0.ctypes.data_as(C.POINTER(C.c_double)), C.byref(iters),
+                      rel.ctypes.data_as(C.POINTER(C.c_float)), C.c_void_p(ws.data_ptr()), ws.numel(),
+                      _stream()))
+    m = int(iters.value)
+    return {"U": U, "iters": m, "rel_resid": rel, "alphas": coef[:m, 0, :].copy(),
+            "betas": coef[:m, 1, :].copy(), "gamma0": gamma0}

@@ -75,4 +75,94 @@ int egp_kmm(const float* X, int64_t n, const float* V, int32_t t, const egp_hype
   return kmm_core(P, V, t, out, static_cast<char*>(ws) + prepared_bytes(n, h->d), s);
 }
 
+static int check_n(int64_t n) {
+  if (n < 1 || n > ((int64_t)1 << 31) - 1) return fail(EGP_ERR_ARG, "n = %lld outside 1..2^31-1", (long long)n);
+  return EGP_OK;
+}
+
+static int check_precond(const egp_precond_t* P, int64_t n, bool filled) {
+  if (P == nullptr) return fail(EGP_ERR_ARG, "preconditioner struct is NULL");
+  if (P->rank < (filled ? 0 : 1) || P->rank > EGP_RANK_MAX || P->rank > n)
+    return fail(EGP_ERR_ARG, "preconditioner rank %d outside 1..min(n, %d)", P->rank, EGP_RANK_MAX);
+  int rc;
+  if ((rc = validate_ptr(P->L, "P->L")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(P->small_dev, "P->small_dev")) != EGP_OK) return rc;
+  if (!filled && (P->pivots == nullptr || P->small == nullptr))
+    return fail(EGP_ERR_ARG, "P->pivots / P->small is NULL");
+  return EGP_OK;
+}
+
+size_t egp_piv_chol_precond_ws_bytes(int64_t n, int32_t d, int32_t rank) {
+  if (n < 1 || d < 1 || d > EGP_D_MAX || rank < 1 || rank > EGP_RANK_MAX) return 0;
+  return pivchol_ws_bytes(n, d, rank);
+}
+
+int egp_piv_chol_precond(const float* X, int64_t n, const egp_hyper_t* h, float tol_abs, egp_precond_t* P,
+                         void* ws, size_t ws_bytes, void* stream) {
+  int rc;
+  if ((rc = validate_hyper(h)) != EGP_OK) return rc;
+  if ((rc = check_n(n)) != EGP_OK) return rc;
+  if (!(h->noise > 0.f)) return fail(EGP_ERR_ARG, "the preconditioner P = L L^T + noise I needs noise > 0");
+  if (!(tol_abs >= 0.f)) return fail(EGP_ERR_ARG, "tol_abs must be >= 0");
+  if ((rc = validate_ptr(X, "X")) != EGP_OK) return rc;
+  if ((rc = check_precond(P, n, false)) != EGP_OK) return rc;
+  if ((rc = validate_ptr(ws, "ws")) != EGP_OK) return rc;
+  const size_t need = egp_piv_chol_precond_ws_bytes(n, h->d, P->rank);
+  if (ws_bytes < need) return fail(EGP_ERR_WS, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, need);
+  return pivchol_core(X, n, h, tol_abs, P, ws, static_cast<hipStream_t>(stream));
+}
+
+size_t egp_precond_apply_ws_bytes(int64_t n, int32_t t, int32_t rank) {
+  if (n < 1 || t < 1 || t > 33 || rank < 1 || rank > EGP_RANK_MAX) return 0;
+  return precond_apply_ws(n, t, rank);
+}
+
+int egp_precond_apply(const egp_precond_t* P, int64_t n, float noise, const float* R, int32_t t, float* Z,
+                      void* ws, size_t ws_bytes, void* stream) {
+  int rc;
+  if ((rc = check_n(n)) != EGP_OK) return rc;
+  if ((rc = check_precond(P, n, true)) != EGP_OK) return rc;
+  if (P->rank < 1) return fail(EGP_ERR_ARG, "preconditioner has rank 0");
+  if (!(noise > 0.f)) return fail(EGP_ERR_ARG, "noise must be > 0");
+  if (t < 1 || t > 33) return fail(EGP_ERR_ARG, "t = %d outside 1..33", t);
+  if ((rc = validate_ptr(R, "R")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(Z, "Z")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(ws, "ws")) != EGP_OK) return rc;
+  const size_t need = precond_apply_ws(n, t, P->rank);
+  if (ws_bytes < need) return fail(EGP_ERR_WS, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, need);
+  return precond_apply_core(P->L, P->rank, P->small_dev, n, noise, R, t, Z, nullptr, ws,
+                            static_cast<hipStream_t>(stream));
+}
+
+size_t egp_mbcg_ws_bytes(int64_t n, int32_t d, int32_t t, int32_t rank, int32_t max_iter) {
+  if (n < 1 || d < 1 || d > EGP_D_MAX || t < 1 || t > 33 || rank < 0 || rank > EGP_RANK_MAX || max_iter < 0)
+    return 0;
+  return mbcg_ws_bytes_core(n, d, t, rank, max_iter);
+}
+
+int egp_mbcg(const float* X, int64_t n, const float* B, int32_t t, const egp_hyper_t* h, const egp_precond_t* P,
+             int32_t max_iter, float tol, float* U, double* cg_coef, double* gamma0, int32_t* iters_done,
+             float* rel_resid, void* ws, size_t ws_bytes, void* stream) {
+  int rc;
+  if ((rc = validate_hyper(h)) != EGP_OK) return rc;
+  if ((rc = check_n(n)) != EGP_OK) return rc;
+  if (t < 1 || t > 33) return fail(EGP_ERR_ARG, "t = %d outside 1..33", t);
+  if (max_iter < 0 || max_iter > 100000) return fail(EGP_ERR_ARG, "max_iter = %d outside 0..100000", max_iter);
+  if (!(tol >= 0.f)) return fail(EGP_ERR_ARG, "tol must be >= 0");
+  if ((rc = validate_ptr(X, "X")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(B, "B")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(U, "U")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(ws, "ws")) != EGP_OK) return rc;
+  if (U == B) return fail(EGP_ERR_ARG, "U must not alias B");
+  if (P != nullptr) {
+    if ((rc = check_precond(P, n, true)) != EGP_OK) return rc;
+    if (!(h->noise > 0.f)) return fail(EGP_ERR_ARG, "a preconditioned solve needs noise > 0");
+    if (P->rank == 0) P = nullptr;
+  }
+  const size_t need = mbcg_ws_bytes_core(n, h->d, t, P ? P->rank : 0, max_iter);
+  if (ws_bytes < need) return fail(EGP_ERR_WS, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, need);
+  return mbcg_core(X, n, B, t, h, P, max_iter, tol, U, cg_coef, gamma0, iters_done, rel_resid, ws,
+                   static_cast<hipStream_t>(stream));
+}
+
 }  // extern "C"

@@ -47,6 +47,17 @@ int prepare_points(const float* X, int64_t n, const egp_hyper_t* h, void* ws, Pr
 size_t kmm_core_ws_bytes(int64_t n, int t);
 int kmm_core(const Prepared& P, const float* V, int t, float* out, void* ws2, hipStream_t stream);
 
+size_t pivchol_ws_bytes(int64_t n, int d, int rank);
+int pivchol_core(const float* X, int64_t n, const egp_hyper_t* h, float tol_abs, egp_precond_t* P, void* ws,
+                 hipStream_t stream);
+size_t precond_apply_ws(int64_t n, int t, int rank);
+int precond_apply_core(const float* L, int rank, const float* Minv_dev, int64_t n, float noise, const float* R,
+                       int t, float* Z, float* rz_partial, void* ws, hipStream_t stream);
+size_t mbcg_ws_bytes_core(int64_t n, int d, int t, int rank, int max_iter);
+int mbcg_core(const float* X, int64_t n, const float* B, int t, const egp_hyper_t* h, const egp_precond_t* P,
+              int max_iter, float tol, float* U, double* cg_coef, double* gamma0, int32_t* iters_done,
+              float* rel_resid, void* ws, hipStream_t stream);
+
 int validate_hyper(const egp_hyper_t* h);
 int validate_ptr(const void* p, const char* name);
 
