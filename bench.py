@@ -1,0 +1,194 @@
+"""Benchmark of the exact-GP hot path on one MI355X.
+
+Workload: configuration C4 of the benchmark spec (n = 2^20 points, d = 11, clustered mixture, RBF-ARD), the one
+the headline metric is quoted on. A timed "step" is one full egp_kmm call on the 16 probe columns: row
+preparation, fused kernel-tile + contraction kernel, epilogue. The preconditioner build (rank 100) and
+mBCG iterations at t = 17 are timed after it and reported in the same JSON line.
+
+Prints ONE JSON line on stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+FP32_PEAK_TFLOPS = 157.3          # MI355X fp32 MFMA (= fp32 vector) peak
+HBM_PEAK_GBS = 8000.0
+
+
+def flops_per_entry(d, t, kernel_type):
+    """Algorithmic flops per kernel entry: 2d (cross term) + 2 (norm adds) + 1 (clamp) + c_g + 2t."""
+    cg = {0: 1, 1: 4, 2: 6}[kernel_type]
+    return 2 * d + 3 + cg + 2 * t
+
+
+def read_traffic(path):
+    """HBM bytes per launch of the fused kernel from the committed rocprofv3 --pmc summary (or None)."""
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch="):
+                    return float(line.split("=", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def prof_read(lib, group):
+    ms = C.c_double(0.0)
+    cnt = C.c_int64(0)
+    lib.egp_profile_read(C.c_int32(group), C.byref(ms), C.byref(cnt))
+    return ms.value, cnt.value
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--n", type=int, default=None, help="override the point count (same recipe)")
+    ap.add_argument("--mbcg-iters", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kmm-only", action="store_true", help="skip preconditioner and mBCG timing")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (the whole n x n product on one MI355X); "
+                 "--gpus must be 1")
+
+    import numpy as np
+    import torch
+    import paper_1903_08114_amd as egp
+    from workloads import make_workload
+
+    lib = egp.lib()
+    lib.egp_profile_enable.argtypes = [C.c_int]
+    lib.egp_profile_read.argtypes = [C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    w = make_workload("C4", n=args.n)
+    n, d = w.n, w.d
+    X = torch.from_numpy(w.X).to(dev)
+    V16 = torch.from_numpy(np.ascontiguousarray(w.V[:, 1:17])).to(dev)     # the 16 probe columns
+    B17 = torch.from_numpy(w.V).to(dev)                                    # [y | 16 probes]
+    out = torch.empty_like(V16)
+    ws = torch.empty(lib.egp_kmm_ws_bytes(n, d, 16), dtype=torch.uint8, device=dev)
+
+    def step():
+        egp.kmm(X, V16, w.lengthscales, w.outputscale, w.noise, w.kernel_type, out=out, ws=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    lib.egp_profile_enable(1)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kmm_ms, kmm_launches = prof_read(lib, 0)
+    pack_ms, _ = prof_read(lib, 1)
+    lib.egp_profile_enable(0)
+    ms_per_step = wall * 1e3 / args.steps
+    entries_per_s = n * n / (wall / args.steps)
+    kern_ms = kmm_ms / max(kmm_launches, 1)
+    fpe = flops_per_entry(d, 16, w.kernel_type)
+    achieved_tflops = fpe * n * n / (kern_ms * 1e-3) / 1e12
+
+    result = {
+        "metric": "kernel entries/s in fused K·V (n=1M,d=11,t=16); s per mBCG iteration",
+        "value": entries_per_s,
+        "unit": "kernel entries/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"C4: n={n}, d={d}, t=16 probe columns, RBF-ARD, 32-component clustered "
+                               "mixture in [0,1]^11, one full egp_kmm call per step"},
+        "roofline": {"bound": "mfma", "achieved": achieved_tflops, "peak": FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved_tflops / FP32_PEAK_TFLOPS,
+                     "traffic": read_traffic(os.path.join(ROOT, "profiles", "kmm_kernel_c4_t16_pmc.txt")),
+                     "kernel": "kmm_kernel", "kernel_ms": kern_ms, "launches": kmm_launches,
+                     "flops_per_entry": fpe, "pack_epilogue_ms_per_step": pack_ms / args.steps},
+    }
+
+    if not args.kmm_only:
+        # ---- preconditioner build (rank 100) and mBCG iterations at t = 17 ----
+        lib.egp_profile_enable(1)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        P = egp.piv_chol_precond(X, w.lengthscales, w.outputscale, w.noise, w.kernel_type, w.rank)
+        torch.cuda.synchronize()
+        pc_s = time.perf_counter() - t0
+        pc_ms, _ = prof_read(lib, 4)
+        lib.egp_profile_enable(1)
+        iters = args.mbcg_iters
+        t0 = time.perf_counter()
+        res = egp.mbcg(X, B17, w.lengthscales, w.outputscale, w.noise, w.kernel_type, precond=P,
+                       max_iter=iters, tol=0.0)
+        torch.cuda.synchronize()
+        cg_s = time.perf_counter() - t0
+        vec_ms, vec_n = prof_read(lib, 2)
+        pre_ms, pre_n = prof_read(lib, 3)
+        k17_ms, k17_n = prof_read(lib, 0)
+        lib.egp_profile_enable(0)
+        t = 17
+        k = P.rank
+        vec_bytes = 11 * n * t * 4          # dot: 2nt; update: 4nt read + 2nt write; direction: 2nt read + nt write
+        pre_bytes = (2 * n * k + 3 * n * t) * 4   # L twice, R twice, Z once
+        pc_bytes = sum(n * (4 * 3 + m + 1 + 2) * 4 for m in range(k))   # packed points, L[:m], new column, diag r/w
+        result["mbcg"] = {
+            "s_per_iter": cg_s / iters, "iters_timed": iters, "t": t, "rank": k,
+            "kmm_kernel_ms_per_iter": k17_ms / max(k17_n, 1),
+            "cg_vector_ms_per_iter": 2 * vec_ms / max(vec_n, 1),
+            "cg_vector_gbs": vec_bytes / (2 * vec_ms / max(vec_n, 1) * 1e-3) / 1e9,
+            "precond_apply_ms": pre_ms / max(pre_n, 1),
+            "precond_apply_gbs": pre_bytes / (pre_ms / max(pre_n, 1) * 1e-3) / 1e9,
+            "hbm_peak_gbs": HBM_PEAK_GBS,
+            "rel_resid_max_after": float(res["rel_resid"].max()),
+        }
+        result["piv_chol"] = {"s": pc_s, "steps_ms": pc_ms, "rank": k,
+                              "gbs": pc_bytes / (pc_ms * 1e-3) / 1e9 if pc_ms > 0 else None}
+        # full solve at the paper's training tolerance (Experiment details: tolerance 1, rank-100 preconditioner)
+        t0 = time.perf_counter()
+        full = egp.mbcg(X, B17, w.lengthscales, w.outputscale, w.noise, w.kernel_type, precond=P,
+                        max_iter=w.max_iter, tol=w.tol)
+        torch.cuda.synchronize()
+        result["mbcg"]["full_solve_tol1"] = {"s": time.perf_counter() - t0, "iters": full["iters"],
+                                             "rel_resid_max": float(full["rel_resid"].max())}
+
+    if not args.no_cpu_baseline:
+        import oracle as orc
+        try:
+            from threadpoolctl import threadpool_info
+            blas_threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            blas_threads = os.cpu_count()
+        m = 96
+        rows = np.random.default_rng(0).choice(n, m, replace=False)
+        h = orc.Hyper(w.kernel_type, w.lengthscales, w.outputscale, w.noise)
+        Vh = w.V[:, 1:17]
+        c0, t0 = time.process_time(), time.perf_counter()
+        ref = orc.kmm_rows(w.X, Vh, h, rows)
+        cpu_wall = time.perf_counter() - t0
+        cpu_used = time.process_time() - c0
+        got = out.cpu().numpy()[rows].astype(np.float64)
+        result["cpu_baseline"] = {
+            "value": m * n / cpu_wall, "unit": "kernel entries/s", "cores": blas_threads, "kind": "oracle",
+            "sample": f"{m} random output rows of the same C4 product (all n columns, fp64 dense rows), "
+                      f"{cpu_wall:.1f} s wall, {cpu_used / cpu_wall:.1f} cores busy on average",
+            "host_cpus": os.cpu_count(),
+        }
+        result["parity_sampled_rows_rel_err"] = float(np.linalg.norm(got - ref) / np.linalg.norm(ref))
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -80,7 +80,7 @@ size_t egp_kmm_ws_bytes(int64_t n, int32_t d, int32_t t);
 
 /* dout[k] = (dK/dl_k) V for k = 0..d-1, dout laid out [d][n][t]: the products the marginal-likelihood
  * gradient needs (paper, Eq. 2). dK/dl_k [i,j] = s h(r_ij) (x_ik-x_jk)^2 / l_k^3 with h = g for RBF,
- * 3 exp(-sqrt3 r) for MATERN32, (5/3)(1+sqrt5 r) exp(-sqrt5 r) for MATERN52. t in 1..16.
+ * 3 exp(-sqrt3 r) for MATERN32, (5/3)(1+sqrt5 r) exp(-sqrt5 r) for MATERN52. t in 1..EGP_T_MAX.
  * Asynchronous on `stream`. */
 int egp_kmm_grad(const float* X, int64_t n, const float* V, int32_t t, const egp_hyper_t* h,
                  float* dout /*device d x n x t*/, void* ws, size_t ws_bytes, void* stream);
@@ -107,11 +107,12 @@ size_t egp_piv_chol_precond_ws_bytes(int64_t n, int32_t d, int32_t rank);
  *   gamma0     host, t doubles: b_c^T P^{-1} b_c (quadrature weights). May be NULL.
  *   iters_done host, one int32
  *   rel_resid  host, t floats, relative residuals after the last iteration
+ *   resid_hist host, [max_iter][t] floats: relative residuals after every iteration. May be NULL.
  * t in 1..33. Synchronises on `stream`. */
 int egp_mbcg(const float* X, int64_t n, const float* B, int32_t t, const egp_hyper_t* h,
              const egp_precond_t* P, int32_t max_iter, float tol, float* U, double* cg_coef,
-             double* gamma0, int32_t* iters_done, float* rel_resid, void* ws, size_t ws_bytes,
-             void* stream);
+             double* gamma0, int32_t* iters_done, float* rel_resid, float* resid_hist, void* ws,
+             size_t ws_bytes, void* stream);
 size_t egp_mbcg_ws_bytes(int64_t n, int32_t d, int32_t t, int32_t rank, int32_t max_iter);
 
 /* Z = P^{-1} R with P = L L^T + noise*I through the Woodbury identity, R and Z device n x t.
@@ -119,6 +120,21 @@ size_t egp_mbcg_ws_bytes(int64_t n, int32_t d, int32_t t, int32_t rank, int32_t 
 int egp_precond_apply(const egp_precond_t* P, int64_t n, float noise, const float* R, int32_t t,
                       float* Z, void* ws, size_t ws_bytes, void* stream);
 size_t egp_precond_apply_ws_bytes(int64_t n, int32_t t, int32_t rank);
+
+/* In-stream timing of kernel groups with HIP events, for roofline reporting. While enabled, each launch
+ * of a group is bracketed by an event pair on the stream it runs on. egp_profile_enable(1) clears the
+ * counters; egp_profile_read waits for the recorded events, and returns the summed duration and the
+ * number of brackets of one group. Groups: */
+typedef enum {
+  EGP_PROF_KMM = 0,      /* the fused kernel-matrix-multiply kernel alone */
+  EGP_PROF_PACK = 1,     /* row preparation, right-hand-side packing, split reduction / epilogue */
+  EGP_PROF_CG_VEC = 2,   /* CG vector kernels (dot, update, direction) of one iteration */
+  EGP_PROF_PRECOND = 3,  /* one application of P^{-1} */
+  EGP_PROF_PIVCHOL = 4,  /* all steps of one pivoted-Cholesky build */
+  EGP_PROF_GRAD = 5      /* the fused derivative kernel alone */
+} egp_prof_group_t;
+int egp_profile_enable(int on);
+int egp_profile_read(int32_t group, double* total_ms /*host*/, int64_t* launches /*host*/);
 
 /* Message of the last failing call on this thread ("" if none). */
 const char* egp_last_error(void);

@@ -57,8 +57,13 @@ def lib():
         L.egp_mbcg.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.POINTER(_Hyper),
                                C.POINTER(_Precond), C.c_int32, C.c_float, C.c_void_p,
                                C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int32),
-                               C.POINTER(C.c_float), C.c_void_p, C.c_size_t, C.c_void_p]
+                               C.POINTER(C.c_float), C.POINTER(C.c_float), C.c_void_p, C.c_size_t, C.c_void_p]
         L.egp_kmm_ws_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32]
+        L.egp_kmm_grad_ws_bytes.restype = C.c_size_t
+        L.egp_kmm_grad_ws_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32]
+        L.egp_kmm_grad.restype = C.c_int
+        L.egp_kmm_grad.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.POINTER(_Hyper), C.c_void_p,
+                                   C.c_void_p, C.c_size_t, C.c_void_p]
         L.egp_kmm.restype = C.c_int
         L.egp_kmm.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.POINTER(_Hyper), C.c_void_p,
                               C.c_void_p, C.c_size_t, C.c_void_p]
@@ -154,6 +159,23 @@ def kmm(X, V, lengthscales, outputscale, noise, kernel_type, out=None, ws=None):
     return out
 
 
+def kmm_grad(X, V, lengthscales, outputscale, noise, kernel_type, out=None, ws=None):
+    """out[k] = (dK/dl_k) V for every lengthscale (egp_kmm_grad). Returns a (d, n, t) tensor."""
+    import torch
+    L = lib()
+    n, d = X.shape
+    t = V.shape[1]
+    h = _hyper(kernel_type, lengthscales, outputscale, noise)
+    if out is None:
+        out = torch.empty((d, n, t), dtype=torch.float32, device=X.device)
+    need = L.egp_kmm_grad_ws_bytes(n, d, t)
+    if ws is None:
+        ws = _workspace(need, X.device)
+    _check(L.egp_kmm_grad(_dev(X, "X"), n, _dev(V, "V"), t, C.byref(h), _dev(out, "dout"),
+                          C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
+    return out
+
+
 def piv_chol_precond(X, lengthscales, outputscale, noise, kernel_type, rank, tol_abs=0.0, ws=None):
     """Rank-`rank` pivoted-Cholesky preconditioner of K(X,X) (egp_piv_chol_precond). Returns a Precond."""
     L = lib()
@@ -206,12 +228,14 @@ def mbcg(X, B, lengthscales, outputscale, noise, kernel_type, precond=None, max_
     gamma0 = np.zeros(t, dtype=np.float64)
     iters = C.c_int32(0)
     rel = np.zeros(t, dtype=np.float32)
+    hist = np.zeros((max(max_iter, 1), t), dtype=np.float32)
     st = precond._struct(precond.rank) if precond is not None else None
     _check(L.egp_mbcg(_dev(X, "X"), n, _dev(B, "B"), t, C.byref(h), C.byref(st) if st is not None else None,
                       int(max_iter), float(tol), _dev(U, "U"), coef.ctypes.data_as(C.POINTER(C.c_double)),
                       gamma0.ctypes.data_as(C.POINTER(C.c_double)), C.byref(iters),
-                      rel.ctypes.data_as(C.POINTER(C.c_float)), C.c_void_p(ws.data_ptr()), ws.numel(),
+                      rel.ctypes.data_as(C.POINTER(C.c_float)), hist.ctypes.data_as(C.POINTER(C.c_float)),
+                      C.c_void_p(ws.data_ptr()), ws.numel(),
                       _stream()))
     m = int(iters.value)
     return {"U": U, "iters": m, "rel_resid": rel, "alphas": coef[:m, 0, :].copy(),
-            "betas": coef[:m, 1, :].copy(), "gamma0": gamma0}
+            "betas": coef[:m, 1, :].copy(), "gamma0": gamma0, "resid_hist": hist[:m].copy()}

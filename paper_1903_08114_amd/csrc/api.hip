@@ -4,6 +4,8 @@
 #include <string.h>
 
 #include <cmath>
+#include <mutex>
+#include <vector>
 
 #include "egp_internal.h"
 
@@ -42,6 +44,50 @@ int validate_hyper(const egp_hyper_t* h) {
   return EGP_OK;
 }
 
+// ---- profiling: event pairs kept until egp_profile_read drains them ----
+struct ProfSlot { hipEvent_t a, b; };
+static std::mutex g_prof_mu;
+static bool g_prof_on = false;
+static std::vector<ProfSlot> g_prof[kProfTags];
+static double g_prof_ms[kProfTags];
+static long g_prof_n[kProfTags];
+
+ProfScope::ProfScope(int tag, hipStream_t stream) : tag_(tag), stream_(stream), slot_(nullptr) {
+  if (!g_prof_on) return;
+  ProfSlot* s = new ProfSlot;
+  if (hipEventCreate(&s->a) != hipSuccess || hipEventCreate(&s->b) != hipSuccess) {
+    delete s;
+    return;
+  }
+  (void)hipEventRecord(s->a, stream);
+  slot_ = s;
+}
+
+ProfScope::~ProfScope() {
+  if (slot_ == nullptr) return;
+  ProfSlot* s = static_cast<ProfSlot*>(slot_);
+  (void)hipEventRecord(s->b, stream_);
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  g_prof[tag_].push_back(*s);
+  delete s;
+}
+
+static void prof_drain() {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  for (int t = 0; t < kProfTags; ++t) {
+    for (ProfSlot& s : g_prof[t]) {
+      float ms = 0.f;
+      if (hipEventSynchronize(s.b) == hipSuccess && hipEventElapsedTime(&ms, s.a, s.b) == hipSuccess) {
+        g_prof_ms[t] += ms;
+        g_prof_n[t] += 1;
+      }
+      (void)hipEventDestroy(s.a);
+      (void)hipEventDestroy(s.b);
+    }
+    g_prof[t].clear();
+  }
+}
+
 }  // namespace egp
 
 using namespace egp;
@@ -50,6 +96,26 @@ extern "C" {
 
 const char* egp_last_error(void) { return g_err; }
 const char* egp_version(void) { return "0.1"; }
+
+int egp_profile_enable(int on) {
+  prof_drain();
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  g_prof_on = on != 0;
+  for (int t = 0; t < kProfTags; ++t) {
+    g_prof_ms[t] = 0.0;
+    g_prof_n[t] = 0;
+  }
+  return EGP_OK;
+}
+
+int egp_profile_read(int32_t group, double* total_ms, int64_t* launches) {
+  if (group < 0 || group >= kProfTags) return fail(EGP_ERR_ARG, "profile group %d outside 0..%d", group, kProfTags - 1);
+  prof_drain();
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  if (total_ms) *total_ms = g_prof_ms[group];
+  if (launches) *launches = g_prof_n[group];
+  return EGP_OK;
+}
 
 size_t egp_kmm_ws_bytes(int64_t n, int32_t d, int32_t t) {
   if (n < 1 || d < 1 || d > EGP_D_MAX || t < 1 || t > EGP_T_MAX) return 0;
@@ -73,6 +139,29 @@ int egp_kmm(const float* X, int64_t n, const float* V, int32_t t, const egp_hype
   Prepared P;
   if ((rc = prepare_points(X, n, h, ws, &P, s)) != EGP_OK) return rc;
   return kmm_core(P, V, t, out, static_cast<char*>(ws) + prepared_bytes(n, h->d), s);
+}
+
+size_t egp_kmm_grad_ws_bytes(int64_t n, int32_t d, int32_t t) {
+  if (n < 1 || d < 1 || d > EGP_D_MAX || t < 1 || t > EGP_T_MAX) return 0;
+  return prepared_bytes(n, d) + kmm_grad_core_ws_bytes(n, d, t);
+}
+
+int egp_kmm_grad(const float* X, int64_t n, const float* V, int32_t t, const egp_hyper_t* h, float* dout, void* ws,
+                 size_t ws_bytes, void* stream) {
+  int rc;
+  if ((rc = validate_hyper(h)) != EGP_OK) return rc;
+  if (n < 1 || n > ((int64_t)1 << 31) - 1) return fail(EGP_ERR_ARG, "n = %lld outside 1..2^31-1", (long long)n);
+  if (t < 1 || t > EGP_T_MAX) return fail(EGP_ERR_ARG, "t = %d outside 1..%d", t, EGP_T_MAX);
+  if ((rc = validate_ptr(X, "X")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(V, "V")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(dout, "dout")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(ws, "ws")) != EGP_OK) return rc;
+  const size_t need = egp_kmm_grad_ws_bytes(n, h->d, t);
+  if (ws_bytes < need) return fail(EGP_ERR_WS, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, need);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  Prepared P;
+  if ((rc = prepare_points(X, n, h, ws, &P, s)) != EGP_OK) return rc;
+  return kmm_grad_core(P, h, V, t, dout, static_cast<char*>(ws) + prepared_bytes(n, h->d), s);
 }
 
 static int check_n(int64_t n) {
@@ -142,7 +231,7 @@ size_t egp_mbcg_ws_bytes(int64_t n, int32_t d, int32_t t, int32_t rank, int32_t 
 
 int egp_mbcg(const float* X, int64_t n, const float* B, int32_t t, const egp_hyper_t* h, const egp_precond_t* P,
              int32_t max_iter, float tol, float* U, double* cg_coef, double* gamma0, int32_t* iters_done,
-             float* rel_resid, void* ws, size_t ws_bytes, void* stream) {
+             float* rel_resid, float* resid_hist, void* ws, size_t ws_bytes, void* stream) {
   int rc;
   if ((rc = validate_hyper(h)) != EGP_OK) return rc;
   if ((rc = check_n(n)) != EGP_OK) return rc;
@@ -161,7 +250,7 @@ int egp_mbcg(const float* X, int64_t n, const float* B, int32_t t, const egp_hyp
   }
   const size_t need = mbcg_ws_bytes_core(n, h->d, t, P ? P->rank : 0, max_iter);
   if (ws_bytes < need) return fail(EGP_ERR_WS, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, need);
-  return mbcg_core(X, n, B, t, h, P, max_iter, tol, U, cg_coef, gamma0, iters_done, rel_resid, ws,
+  return mbcg_core(X, n, B, t, h, P, max_iter, tol, U, cg_coef, gamma0, iters_done, rel_resid, resid_hist, ws,
                    static_cast<hipStream_t>(stream));
 }
 

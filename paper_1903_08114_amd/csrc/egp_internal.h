@@ -47,6 +47,11 @@ int prepare_points(const float* X, int64_t n, const egp_hyper_t* h, void* ws, Pr
 size_t kmm_core_ws_bytes(int64_t n, int t);
 int kmm_core(const Prepared& P, const float* V, int t, float* out, void* ws2, hipStream_t stream);
 
+void launch_pack_rhs(const float* V, int64_t n, int64_t npad, int t, int c0, int nb_count, int extra, void* Vp,
+                     float* Ep, hipStream_t stream);
+size_t kmm_grad_core_ws_bytes(int64_t n, int d, int t);
+int kmm_grad_core(const Prepared& P, const egp_hyper_t* h, const float* V, int t, float* dout, void* ws2,
+                  hipStream_t stream);
 size_t pivchol_ws_bytes(int64_t n, int d, int rank);
 int pivchol_core(const float* X, int64_t n, const egp_hyper_t* h, float tol_abs, egp_precond_t* P, void* ws,
                  hipStream_t stream);
@@ -56,7 +61,18 @@ int precond_apply_core(const float* L, int rank, const float* Minv_dev, int64_t 
 size_t mbcg_ws_bytes_core(int64_t n, int d, int t, int rank, int max_iter);
 int mbcg_core(const float* X, int64_t n, const float* B, int t, const egp_hyper_t* h, const egp_precond_t* P,
               int max_iter, float tol, float* U, double* cg_coef, double* gamma0, int32_t* iters_done,
-              float* rel_resid, void* ws, hipStream_t stream);
+              float* rel_resid, float* resid_hist, void* ws, hipStream_t stream);
+
+// ---- optional in-stream timing of kernel groups with HIP events (egp_profile_*) ----
+enum ProfTag { kProfKmm = 0, kProfPack = 1, kProfCgVec = 2, kProfPrecond = 3, kProfPivChol = 4, kProfGrad = 5,
+               kProfTags = 6 };
+struct ProfScope {   // records an event pair around the launches made during its lifetime
+  ProfScope(int tag, hipStream_t stream);
+  ~ProfScope();
+  int tag_;
+  hipStream_t stream_;
+  void* slot_;
+};
 
 int validate_hyper(const egp_hyper_t* h);
 int validate_ptr(const void* p, const char* name);

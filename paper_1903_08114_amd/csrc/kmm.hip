@@ -142,6 +142,14 @@ __global__ __launch_bounds__(256) void pack_rhs(const float* __restrict__ V, int
   }
 }
 
+void launch_pack_rhs(const float* V, int64_t n, int64_t npad, int t, int c0, int nb_count, int extra, void* Vp,
+                     float* Ep, hipStream_t stream) {
+  const int64_t total = (npad >> 4) * nb_count * 64;
+  const int64_t threads = total > npad ? total : npad;
+  hipLaunchKernelGGL(pack_rhs, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream, V, n, npad, t, c0,
+                     nb_count, extra, static_cast<f4*>(Vp), Ep);
+}
+
 // ------------------------------------------------------------------------------------------------
 // The fused kernel.
 //   grid.x = row blocks (4 waves x R row tiles x 16 rows), grid.y = column splits
@@ -358,6 +366,7 @@ int prepare_points(const float* X, int64_t n, const egp_hyper_t* h, void* ws, Pr
   const double c = point_scale(h->kernel_type);
   for (int f = 0; f <= EGP_D_MAX; ++f) sc.inv[f] = f < d ? (float)(c / (double)h->lengthscales[f]) : 0.f;
 
+  ProfScope prof(kProfPack, stream);
   hipLaunchKernelGGL(col_sum_partial, dim3(kMeanBlocks), dim3(256), 0, stream, X, n, d, partial);
   hipLaunchKernelGGL(col_mean_final, dim3(1), dim3(64), 0, stream, partial, kMeanBlocks, n, d, mean);
   hipLaunchKernelGGL(pack_points, dim3((unsigned)((npad + 255) / 256)), dim3(256), 0, stream, X, n, npad, d,
@@ -464,11 +473,12 @@ int kmm_core(const Prepared& P, const float* V, int t, float* out, void* ws2, hi
     else if (rem == 33) { nb = 2; extra = 1; tg = 33; }
     else { nb = 2; extra = 0; tg = 32; }
     const int ts = 16 * nb + extra;
-    const int64_t total = (npad >> 4) * nb * 64;
-    const int64_t threads = total > npad ? total : npad;
-    hipLaunchKernelGGL(pack_rhs, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream, V, P.n, npad,
-                       t, c0, nb, extra, Vp, Ep);
+    {
+      ProfScope prof(kProfPack, stream);
+      launch_pack_rhs(V, P.n, npad, t, c0, nb, extra, Vp, Ep, stream);
+    }
     int rc;
+    ProfScope* kprof = new ProfScope(kProfKmm, stream);
     switch (P.ks) {
       case 1: rc = launch_kind<1>(P, pl, nb, extra, Vp, Ep, Part, stream); break;
       case 2: rc = launch_kind<2>(P, pl, nb, extra, Vp, Ep, Part, stream); break;
@@ -478,10 +488,12 @@ int kmm_core(const Prepared& P, const float* V, int t, float* out, void* ws2, hi
       case 6: rc = launch_kind<6>(P, pl, nb, extra, Vp, Ep, Part, stream); break;
       case 7: rc = launch_kind<7>(P, pl, nb, extra, Vp, Ep, Part, stream); break;
       case 8: rc = launch_kind<8>(P, pl, nb, extra, Vp, Ep, Part, stream); break;
-      default: return fail(EGP_ERR_ARG, "d = %d needs %d k-steps; this build supports d <= 31", P.d, P.ks);
+      default: rc = fail(EGP_ERR_ARG, "d = %d needs %d k-steps; this build supports d <= 31", P.d, P.ks);
     }
+    delete kprof;
     if (rc != EGP_OK) return rc;
     const int64_t outs = P.n * tg;
+    ProfScope eprof(kProfPack, stream);
     hipLaunchKernelGGL(kmm_epilogue, dim3((unsigned)((outs + 255) / 256)), dim3(256), 0, stream, Part,
                        pl.splits, npad, ts, V, P.n, t, c0, tg, P.outputscale, P.noise, out);
     EGP_HIP(hipGetLastError());

@@ -200,7 +200,7 @@ size_t mbcg_ws_bytes_core(int64_t n, int d, int t, int rank, int max_iter) {
 
 int mbcg_core(const float* X, int64_t n, const float* B, int t, const egp_hyper_t* h, const egp_precond_t* P,
               int max_iter, float tol, float* U, double* cg_coef, double* gamma0, int32_t* iters_done,
-              float* rel_resid, void* ws, hipStream_t stream) {
+              float* rel_resid, float* resid_hist, void* ws, hipStream_t stream) {
   const int rank = P ? P->rank : 0;
   const MbcgWs lay = mbcg_layout(n, h->d, t, rank, max_iter);
   char* w = static_cast<char*>(ws);
@@ -266,9 +266,11 @@ int mbcg_core(const float* X, int64_t n, const float* B, int t, const egp_hyper_
   for (; it < max_iter;) {
     rc = kmm_core(prep, D, t, W, kmm_ws, stream);
     if (rc != EGP_OK) return rc;
+    ProfScope* vprof = new ProfScope(kProfCgVec, stream);
     hipLaunchKernelGGL(cg_dot, dim3(blocks), dim3(256), 0, stream, D, W, n, t, ly.tp, delta_part);
     hipLaunchKernelGGL(cg_update, dim3(blocks), dim3(256), 0, stream, D, W, n, t, ly.tp, gam_part[cur],
                        gparts[cur], delta_part, blocks, U, R, rr_part, it, log);
+    delete vprof;
     const int nxt = cur ^ 1;
     const float* Zsrc;
     if (P) {
@@ -281,8 +283,11 @@ int mbcg_core(const float* X, int64_t n, const float* B, int t, const egp_hyper_
       gparts[nxt] = blocks;
       Zsrc = R;
     }
-    hipLaunchKernelGGL(cg_direction, dim3(blocks), dim3(256), 0, stream, Zsrc, n, t, ly.tp, gam_part[nxt],
-                       gparts[nxt], gam_part[cur], gparts[cur], rr_part, blocks, bb_part, blocks, D, it, log);
+    {
+      ProfScope dprof(kProfCgVec, stream);
+      hipLaunchKernelGGL(cg_direction, dim3(blocks), dim3(256), 0, stream, Zsrc, n, t, ly.tp, gam_part[nxt],
+                         gparts[nxt], gam_part[cur], gparts[cur], rr_part, blocks, bb_part, blocks, D, it, log);
+    }
     EGP_HIP(hipGetLastError());
     EGP_HIP(hipMemcpyAsync(rel.data(), log.rel, sizeof(float) * t, hipMemcpyDeviceToHost, stream));
     EGP_HIP(hipStreamSynchronize(stream));
@@ -290,6 +295,8 @@ int mbcg_core(const float* X, int64_t n, const float* B, int t, const egp_hyper_
     ++it;
     float worst = 0.f;
     bool finite = true;
+    if (resid_hist)
+      for (int c = 0; c < t; ++c) resid_hist[(size_t)(it - 1) * t + c] = rel[c];
     for (int c = 0; c < t; ++c) {
       if (!std::isfinite(rel[c])) finite = false;
       if (rel[c] > worst) worst = rel[c];

@@ -321,6 +321,7 @@ size_t precond_apply_ws(int64_t n, int t, int rank) {
 int precond_apply_core(const float* L, int rank, const float* Minv_dev, int64_t n, float noise, const float* R,
                        int t, float* Z, float* rz_partial, void* ws, hipStream_t stream) {
   if (t > 33) return fail(EGP_ERR_ARG, "preconditioner application supports t <= 33 (got %d)", t);
+  ProfScope prof(kProfPrecond, stream);
   int64_t chunk;
   const int chunks = chunks_for(n, &chunk);
   char* w = static_cast<char*>(ws);
@@ -431,10 +432,13 @@ int pivchol_core(const float* X, int64_t n, const egp_hyper_t* h, float tol_abs,
 
   int64_t nb = (n + 255) / 256;
   const int blocks = (int)(nb > kPcBlocks ? kPcBlocks : nb);
-  hipLaunchKernelGGL(pc_init, dim3((unsigned)nb), dim3(256), 0, stream, diag, n, h->outputscale, st, cap);
-  for (int m = 0; m < cap; ++m)
-    hipLaunchKernelGGL(pc_step, dim3(blocks), dim3(256), 0, stream, prep.Xp, prep.ks, prep.d, h->kernel_type,
-                       h->outputscale, n, P->L, diag, m, tol_abs, st);
+  {
+    ProfScope prof(kProfPivChol, stream);
+    hipLaunchKernelGGL(pc_init, dim3((unsigned)nb), dim3(256), 0, stream, diag, n, h->outputscale, st, cap);
+    for (int m = 0; m < cap; ++m)
+      hipLaunchKernelGGL(pc_step, dim3(blocks), dim3(256), 0, stream, prep.Xp, prep.ks, prep.d, h->kernel_type,
+                         h->outputscale, n, P->L, diag, m, tol_abs, st);
+  }
   EGP_HIP(hipGetLastError());
   int rank = 0;
   EGP_HIP(hipMemcpyAsync(&rank, st.rank_out, sizeof(int), hipMemcpyDeviceToHost, stream));

@@ -1,0 +1,103 @@
+"""The C-ABI library loads and exports every symbol include/egp.h declares; host-side argument checks.
+No compute call is made here (no GPU needed)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "egp.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_1903_08114_amd as egp
+    if not os.path.exists(egp.lib_path()):
+        from paper_1903_08114_amd import build
+        build.build(verbose=False)
+    return egp.lib()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(egp_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_three_entry_points():
+    names = declared_functions()
+    for required in ("egp_kmm", "egp_mbcg", "egp_piv_chol_precond", "egp_kmm_grad"):
+        assert required in names
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert len(names) >= 12
+    for name in names:
+        assert hasattr(lib, name), f"{name} declared in egp.h but not exported"
+
+
+def test_version_and_error_string(lib):
+    assert lib.egp_version().decode().count(".") == 1
+    assert isinstance(lib.egp_last_error(), bytes)
+
+
+def test_workspace_queries_are_host_only(lib):
+    n, d, t = 1 << 20, 11, 17
+    kmm = lib.egp_kmm_ws_bytes(n, d, t)
+    # O(n (d + t)) bytes, never O(n^2): packed points + packed V + one partial buffer
+    assert 0 < kmm < n * (4 * (d + 5) + 4 * 3 * 33) + (1 << 22)
+    mb = lib.egp_mbcg_ws_bytes(n, d, t, 100, 100)
+    assert kmm < mb < 6 * n * t * 4 + kmm + (1 << 28)
+    assert lib.egp_piv_chol_precond_ws_bytes(n, d, 100) > 0
+    assert lib.egp_kmm_ws_bytes(0, d, t) == 0
+    assert lib.egp_kmm_ws_bytes(n, 0, t) == 0
+    assert lib.egp_kmm_ws_bytes(n, 64, t) == 0
+    assert lib.egp_kmm_ws_bytes(n, d, 0) == 0
+    assert lib.egp_mbcg_ws_bytes(n, d, 34, 0, 10) == 0
+
+
+def test_argument_validation_without_device_work(lib):
+    """Bad arguments are rejected before any HIP call is made."""
+    from paper_1903_08114_amd.binding import _hyper
+    h = _hyper(0, [1.0, 1.0], 1.0, 0.1)
+    fake = C.c_void_p(0x1000)      # aligned, never dereferenced: validation fails first
+    # NULL X
+    assert lib.egp_kmm(None, 10, fake, 2, C.byref(h), fake, fake, 1 << 30, None) == -1
+    assert b"X is NULL" in lib.egp_last_error()
+    # misaligned V
+    assert lib.egp_kmm(fake, 10, C.c_void_p(0x1004), 2, C.byref(h), fake, fake, 1 << 30, None) == -1
+    # n < 1, t out of range
+    assert lib.egp_kmm(fake, 0, fake, 2, C.byref(h), fake, fake, 1 << 30, None) == -1
+    assert lib.egp_kmm(fake, 10, fake, 0, C.byref(h), fake, fake, 1 << 30, None) == -1
+    assert lib.egp_kmm(fake, 10, fake, 5000, C.byref(h), fake, fake, 1 << 30, None) == -1
+    # aliasing
+    assert lib.egp_kmm(fake, 10, fake, 2, C.byref(h), fake, C.c_void_p(0x2000), 1 << 30, None) == -1
+    # workspace too small
+    assert lib.egp_kmm(fake, 10, fake, 2, C.byref(h), C.c_void_p(0x3000), C.c_void_p(0x2000), 16, None) == -2
+    # bad hyper-parameters
+    for bad in (_hyper(5, [1.0], 1.0, 0.1), _hyper(0, [0.0], 1.0, 0.1), _hyper(0, [1.0], 0.0, 0.1),
+                _hyper(0, [1.0], 1.0, -1.0), _hyper(0, [float("nan")], 1.0, 0.1)):
+        assert lib.egp_kmm(fake, 10, fake, 2, C.byref(bad), C.c_void_p(0x3000), C.c_void_p(0x2000), 1 << 30,
+                           None) == -1
+    assert lib.egp_kmm(fake, 10, fake, 2, None, C.c_void_p(0x3000), C.c_void_p(0x2000), 1 << 30, None) == -1
+    # mbcg: t > 33, negative max_iter
+    assert lib.egp_mbcg(fake, 10, fake, 34, C.byref(h), None, 5, 0.1, C.c_void_p(0x3000), None, None, None, None,
+                        None, C.c_void_p(0x2000), 1 << 30, None) == -1
+    assert lib.egp_mbcg(fake, 10, fake, 2, C.byref(h), None, -1, 0.1, C.c_void_p(0x3000), None, None, None, None,
+                        None, C.c_void_p(0x2000), 1 << 30, None) == -1
+
+
+def test_product_path_never_imports_the_oracle():
+    pkg = os.path.join(ROOT, "paper_1903_08114_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text, f
+    for dirpath, _, files in os.walk(os.path.join(ROOT, "oracle")):
+        for f in files:
+            if f.endswith(".py"):
+                assert "paper_1903_08114_amd" not in open(os.path.join(dirpath, f)).read().replace(
+                    "The product path (paper_1903_08114_amd)", "")
