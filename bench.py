@@ -57,6 +57,8 @@ def main():
     ap.add_argument("--mbcg-iters", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kmm-only", action="store_true", help="skip preconditioner and mBCG timing")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain 1 GiB copy kernel (calibrates HBM counters under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (the whole n x n product on one MI355X); "
@@ -73,13 +75,22 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
-    w = make_workload("C4", n=args.n)
+    w = make_workload("C4", n=args.n, with_targets=not args.kmm_only)
     n, d = w.n, w.d
     X = torch.from_numpy(w.X).to(dev)
     V16 = torch.from_numpy(np.ascontiguousarray(w.V[:, 1:17])).to(dev)     # the 16 probe columns
     B17 = torch.from_numpy(w.V).to(dev)                                    # [y | 16 probes]
     out = torch.empty_like(V16)
     ws = torch.empty(lib.egp_kmm_ws_bytes(n, d, 16), dtype=torch.uint8, device=dev)
+
+    if args.calib_copy:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        lib.egp_calib_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        lib.egp_calib_copy(C.c_void_p(src.data_ptr()), C.c_void_p(dst.data_ptr()), src.numel(),
+                           C.c_void_p(torch.cuda.current_stream().cuda_stream))
+        torch.cuda.synchronize()
+        del src, dst
 
     def step():
         egp.kmm(X, V16, w.lengthscales, w.outputscale, w.noise, w.kernel_type, out=out, ws=ws)

@@ -136,6 +136,10 @@ typedef enum {
 int egp_profile_enable(int on);
 int egp_profile_read(int32_t group, double* total_ms /*host*/, int64_t* launches /*host*/);
 
+/* Measurement aid: dst[0..count) = src[0..count) with one plain copy kernel (count a multiple of 4).
+ * Reads and writes exactly 4*count bytes each; used to calibrate hardware HBM-traffic counters. */
+int egp_calib_copy(const float* src /*device*/, float* dst /*device*/, int64_t count, void* stream);
+
 /* Message of the last failing call on this thread ("" if none). */
 const char* egp_last_error(void);
 

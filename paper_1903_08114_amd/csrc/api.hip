@@ -88,6 +88,12 @@ static void prof_drain() {
   }
 }
 
+__global__ __launch_bounds__(256) void calib_copy_kernel(const float4* __restrict__ src, float4* __restrict__ dst,
+                                                        int64_t count4) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count4; i += (int64_t)gridDim.x * 256)
+    dst[i] = src[i];
+}
+
 }  // namespace egp
 
 using namespace egp;
@@ -96,6 +102,17 @@ extern "C" {
 
 const char* egp_last_error(void) { return g_err; }
 const char* egp_version(void) { return "0.1"; }
+
+int egp_calib_copy(const float* src, float* dst, int64_t count, void* stream) {
+  int rc;
+  if ((rc = validate_ptr(src, "src")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(dst, "dst")) != EGP_OK) return rc;
+  if (count < 4 || (count & 3) != 0) return fail(EGP_ERR_ARG, "count must be a positive multiple of 4");
+  hipLaunchKernelGGL(calib_copy_kernel, dim3(4096), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     reinterpret_cast<const float4*>(src), reinterpret_cast<float4*>(dst), count / 4);
+  EGP_HIP(hipGetLastError());
+  return EGP_OK;
+}
 
 int egp_profile_enable(int on) {
   prof_drain();
