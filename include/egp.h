@@ -115,6 +115,33 @@ int egp_mbcg(const float* X, int64_t n, const float* B, int32_t t, const egp_hyp
              size_t ws_bytes, void* stream);
 size_t egp_mbcg_ws_bytes(int64_t n, int32_t d, int32_t t, int32_t rank, int32_t max_iter);
 
+/* One evaluation of the log marginal likelihood and its gradient (paper, Eq. 1 and Eq. 2) by the
+ * modified-PCG route the paper builds on: rank-`rank` pivoted-Cholesky preconditioner, one batched solve
+ * on [y | tp probe vectors], stochastic Lanczos quadrature for log|Khat|, probe estimates of the trace
+ * terms, derivative products through egp_kmm_grad's kernel. Zero prior mean.
+ *   y    device, n floats
+ *   W1   device, rank x tp Rademacher (+-1) draws (row-major); ignored when rank = 0
+ *   W2   device, n x tp Rademacher draws; probe c is z_c = L W1[:,c] + sqrt(noise) W2[:,c] (covariance P);
+ *        with rank = 0 the probes are W2 itself
+ *   out  host: value, log-determinant estimate, y^T Khat^{-1} y, gradient w.r.t.
+ *        (l_1..l_d, outputscale, noise) in grad[0..d+1], iterations used, rank used, worst residual
+ * tp in 1..32, rank in 0..EGP_RANK_MAX (noise > 0 needed when rank > 0). Synchronises on `stream`. */
+typedef struct {
+  double mll, logdet, quad;
+  double grad[EGP_D_MAX + 2];
+  int32_t iters, precond_rank;
+  float rel_resid_max;
+} egp_mll_result_t;
+int egp_mll(const float* X, int64_t n, const float* y, const float* W1, const float* W2, int32_t tp,
+            const egp_hyper_t* h, int32_t rank, int32_t max_iter, float tol, egp_mll_result_t* out,
+            void* ws, size_t ws_bytes, void* stream);
+size_t egp_mll_ws_bytes(int64_t n, int32_t d, int32_t tp, int32_t rank, int32_t max_iter);
+
+/* Host-only helper of egp_mll, exported for testing: e1^T log(T) e1 of the symmetric positive definite
+ * tridiagonal T with diagonal diag[0..m) and off-diagonal off[0..m-1). Returns 0, or EGP_ERR_BREAKDOWN
+ * when T is not positive definite. */
+int egp_tridiag_logquad(const double* diag, const double* off, int32_t m, double* out);
+
 /* Z = P^{-1} R with P = L L^T + noise*I through the Woodbury identity, R and Z device n x t.
  * Exposed so that probe vectors and trace terms can be formed outside the solver. Asynchronous. */
 int egp_precond_apply(const egp_precond_t* P, int64_t n, float noise, const float* R, int32_t t,

@@ -21,6 +21,11 @@ class _Hyper(C.Structure):
                 ("outputscale", C.c_float), ("noise", C.c_float)]
 
 
+class _MllResult(C.Structure):
+    _fields_ = [("mll", C.c_double), ("logdet", C.c_double), ("quad", C.c_double), ("grad", C.c_double * 65),
+                ("iters", C.c_int32), ("precond_rank", C.c_int32), ("rel_resid_max", C.c_float)]
+
+
 class _Precond(C.Structure):
     _fields_ = [("rank", C.c_int32), ("L", C.c_void_p), ("pivots", C.POINTER(C.c_int32)),
                 ("small", C.POINTER(C.c_double)), ("small_dev", C.c_void_p)]
@@ -59,6 +64,15 @@ def lib():
                                C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int32),
                                C.POINTER(C.c_float), C.POINTER(C.c_float), C.c_void_p, C.c_size_t, C.c_void_p]
         L.egp_kmm_ws_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32]
+        L.egp_mll_ws_bytes.restype = C.c_size_t
+        L.egp_mll_ws_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+        L.egp_mll.restype = C.c_int
+        L.egp_mll.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                              C.POINTER(_Hyper), C.c_int32, C.c_int32, C.c_float, C.POINTER(_MllResult),
+                              C.c_void_p, C.c_size_t, C.c_void_p]
+        L.egp_tridiag_logquad.restype = C.c_int
+        L.egp_tridiag_logquad.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_int32,
+                                          C.POINTER(C.c_double)]
         L.egp_kmm_grad_ws_bytes.restype = C.c_size_t
         L.egp_kmm_grad_ws_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32]
         L.egp_kmm_grad.restype = C.c_int
@@ -239,3 +253,36 @@ def mbcg(X, B, lengthscales, outputscale, noise, kernel_type, precond=None, max_
     m = int(iters.value)
     return {"U": U, "iters": m, "rel_resid": rel, "alphas": coef[:m, 0, :].copy(),
             "betas": coef[:m, 1, :].copy(), "gamma0": gamma0, "resid_hist": hist[:m].copy()}
+
+
+def mll(X, y, W1, W2, lengthscales, outputscale, noise, kernel_type, rank=100, max_iter=100, tol=1.0, ws=None):
+    """Log marginal likelihood and gradient w.r.t. (lengthscales, outputscale, noise) (egp_mll).
+
+    y: (n,), W1: (rank, tp) and W2: (n, tp) Rademacher draws, all float32 CUDA tensors. Returns a dict."""
+    import numpy as np
+    L = lib()
+    n, d = X.shape
+    tp = W2.shape[1]
+    h = _hyper(kernel_type, lengthscales, outputscale, noise)
+    need = L.egp_mll_ws_bytes(n, d, tp, rank, max_iter)
+    if ws is None:
+        ws = _workspace(need, X.device)
+    res = _MllResult()
+    _check(L.egp_mll(_dev(X, "X"), n, _dev(y, "y"), _dev(W1, "W1") if rank > 0 else None, _dev(W2, "W2"), tp,
+                     C.byref(h), int(rank), int(max_iter), float(tol), C.byref(res),
+                     C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
+    return {"mll": res.mll, "logdet": res.logdet, "quad": res.quad,
+            "grad": np.array(res.grad[:d + 2], dtype=np.float64), "iters": res.iters,
+            "rank": res.precond_rank, "rel_resid_max": res.rel_resid_max}
+
+
+def tridiag_logquad(diag, off):
+    """e1^T log(T) e1 for a symmetric positive definite tridiagonal T (host-only helper, egp_tridiag_logquad)."""
+    import numpy as np
+    diag = np.ascontiguousarray(diag, dtype=np.float64)
+    off = np.ascontiguousarray(off, dtype=np.float64)
+    out = C.c_double(0.0)
+    _check(lib().egp_tridiag_logquad(diag.ctypes.data_as(C.POINTER(C.c_double)),
+                                     off.ctypes.data_as(C.POINTER(C.c_double)) if len(off) else None,
+                                     len(diag), C.byref(out)))
+    return out.value

@@ -181,6 +181,45 @@ int egp_kmm_grad(const float* X, int64_t n, const float* V, int32_t t, const egp
   return kmm_grad_core(P, h, V, t, dout, static_cast<char*>(ws) + prepared_bytes(n, h->d), s);
 }
 
+static int check_n(int64_t n);
+
+size_t egp_mll_ws_bytes(int64_t n, int32_t d, int32_t tp, int32_t rank, int32_t max_iter) {
+  if (n < 1 || d < 1 || d > EGP_D_MAX || tp < 1 || tp > 32 || rank < 0 || rank > EGP_RANK_MAX || max_iter < 1)
+    return 0;
+  return mll_ws_bytes_core(n, d, tp, rank, max_iter);
+}
+
+int egp_mll(const float* X, int64_t n, const float* y, const float* W1, const float* W2, int32_t tp,
+            const egp_hyper_t* h, int32_t rank, int32_t max_iter, float tol, egp_mll_result_t* out, void* ws,
+            size_t ws_bytes, void* stream) {
+  int rc;
+  if ((rc = validate_hyper(h)) != EGP_OK) return rc;
+  if ((rc = check_n(n)) != EGP_OK) return rc;
+  if (tp < 1 || tp > 32) return fail(EGP_ERR_ARG, "tp = %d outside 1..32", tp);
+  if (rank < 0 || rank > EGP_RANK_MAX || rank > n) return fail(EGP_ERR_ARG, "rank = %d outside 0..min(n, %d)", rank, EGP_RANK_MAX);
+  if (rank > 0 && !(h->noise > 0.f)) return fail(EGP_ERR_ARG, "a preconditioned evaluation needs noise > 0");
+  if (max_iter < 1 || max_iter > 100000) return fail(EGP_ERR_ARG, "max_iter = %d outside 1..100000", max_iter);
+  if (!(tol >= 0.f)) return fail(EGP_ERR_ARG, "tol must be >= 0");
+  if (out == nullptr) return fail(EGP_ERR_ARG, "out is NULL");
+  if ((rc = validate_ptr(X, "X")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(y, "y")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(W2, "W2")) != EGP_OK) return rc;
+  if (rank > 0 && (rc = validate_ptr(W1, "W1")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(ws, "ws")) != EGP_OK) return rc;
+  const size_t need = mll_ws_bytes_core(n, h->d, tp, rank, max_iter);
+  if (ws_bytes < need) return fail(EGP_ERR_WS, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, need);
+  return mll_core(X, n, y, W1, W2, tp, h, rank, max_iter, tol, out, ws, static_cast<hipStream_t>(stream));
+}
+
+int egp_tridiag_logquad(const double* diag, const double* off, int32_t m, double* out) {
+  if (diag == nullptr || out == nullptr || m < 1 || (m > 1 && off == nullptr))
+    return fail(EGP_ERR_ARG, "bad tridiagonal arguments");
+  std::vector<double> a(diag, diag + m), b;
+  if (m > 1) b.assign(off, off + m - 1);
+  if (!tridiag_log_quadrature(a, b, out)) return fail(EGP_ERR_BREAKDOWN, "tridiagonal matrix is not positive definite");
+  return EGP_OK;
+}
+
 static int check_n(int64_t n) {
   if (n < 1 || n > ((int64_t)1 << 31) - 1) return fail(EGP_ERR_ARG, "n = %lld outside 1..2^31-1", (long long)n);
   return EGP_OK;

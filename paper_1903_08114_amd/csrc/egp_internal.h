@@ -63,6 +63,15 @@ int mbcg_core(const float* X, int64_t n, const float* B, int t, const egp_hyper_
               int max_iter, float tol, float* U, double* cg_coef, double* gamma0, int32_t* iters_done,
               float* rel_resid, float* resid_hist, void* ws, hipStream_t stream);
 
+size_t mll_ws_bytes_core(int64_t n, int d, int tp, int rank, int max_iter);
+int mll_core(const float* X, int64_t n, const float* y, const float* W1, const float* W2, int tp,
+             const egp_hyper_t* h, int rank_req, int max_iter, float tol, egp_mll_result_t* res, void* ws,
+             hipStream_t stream);
+}  // namespace egp
+#include <vector>
+namespace egp {
+bool tridiag_log_quadrature(std::vector<double> a, std::vector<double> b, double* result);
+
 // ---- optional in-stream timing of kernel groups with HIP events (egp_profile_*) ----
 enum ProfTag { kProfKmm = 0, kProfPack = 1, kProfCgVec = 2, kProfPrecond = 3, kProfPivChol = 4, kProfGrad = 5,
                kProfTags = 6 };

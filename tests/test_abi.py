@@ -101,3 +101,30 @@ def test_product_path_never_imports_the_oracle():
             if f.endswith(".py"):
                 assert "paper_1903_08114_amd" not in open(os.path.join(dirpath, f)).read().replace(
                     "The product path (paper_1903_08114_amd)", "")
+
+
+def test_tridiag_log_quadrature_host_helper(lib):
+    """The library's own tridiagonal eigen-solver (used for the Lanczos quadrature) against numpy's eigh."""
+    import numpy as np
+    import paper_1903_08114_amd as egp
+    rng = np.random.default_rng(0)
+    for m in (1, 2, 3, 7, 40, 200):
+        # a positive definite tridiagonal: Lanczos-like, from a Cholesky-style bidiagonal product
+        dg = rng.uniform(0.5, 2.0, m)
+        lo = rng.uniform(-1.0, 1.0, max(m - 1, 0))
+        Bm = np.diag(dg) + (np.diag(lo, -1) if m > 1 else 0)
+        T = Bm @ Bm.T
+        lam, Q = np.linalg.eigh(T)
+        want = float(np.sum(Q[0] ** 2 * np.log(lam)))
+        got = egp.tridiag_logquad(np.diag(T).copy(), np.diag(T, 1).copy() if m > 1 else np.zeros(0))
+        assert abs(got - want) <= 1e-10 * max(1.0, abs(want)), m
+    # graded spectrum (what CG on an ill-conditioned system produces)
+    m = 60
+    dg = np.geomspace(1e-3, 1e3, m)
+    lo = 0.3 * np.sqrt(dg[:-1] * dg[1:])
+    T = np.diag(dg) + np.diag(lo, 1) + np.diag(lo, -1)
+    lam, Q = np.linalg.eigh(T)
+    assert abs(egp.tridiag_logquad(dg, lo) - np.sum(Q[0] ** 2 * np.log(lam))) < 1e-9
+    # not positive definite -> error
+    with pytest.raises(egp.EgpError):
+        egp.tridiag_logquad(np.array([1.0, -2.0]), np.array([0.1]))
