@@ -48,6 +48,14 @@ def build(verbose: bool = True) -> str:
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("link failed:\n" + res.stderr)
+    # instruction-mix microbenchmark (stand-alone executable, not linked into the library)
+    mb = os.path.join(HERE, "microbench")
+    res = subprocess.run(["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature",
+                          "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
+                          os.path.join(mb, "issue_mix.hip"), "-o", os.path.join(mb, "issue_mix")],
+                         capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("microbenchmark build failed:\n" + res.stderr)
     if verbose:
         print(f"built {LIB} from {len(srcs)} sources")
     return LIB
