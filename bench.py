@@ -57,6 +57,11 @@ def main():
     ap.add_argument("--mbcg-iters", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kmm-only", action="store_true", help="skip preconditioner and mBCG timing")
+    ap.add_argument("--full-solve", action="store_true",
+                    help="also run the C4 solve to the paper's training tolerance (tol 1, rank 100; minutes)")
+    ap.add_argument("--mll", type=int, default=0, metavar="ITERS",
+                    help="also time one C5 marginal-likelihood step (n=2^21, Matern-3/2) capped at ITERS CG iterations")
+    ap.add_argument("--grad", action="store_true", help="also time the C3 KMM and derivative products (n=2^18, d=25)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB copy kernel (calibrates HBM counters under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -166,13 +171,63 @@ def main():
         }
         result["piv_chol"] = {"s": pc_s, "steps_ms": pc_ms, "rank": k,
                               "gbs": pc_bytes / (pc_ms * 1e-3) / 1e9 if pc_ms > 0 else None}
-        # full solve at the paper's training tolerance (Experiment details: tolerance 1, rank-100 preconditioner)
-        t0 = time.perf_counter()
-        full = egp.mbcg(X, B17, w.lengthscales, w.outputscale, w.noise, w.kernel_type, precond=P,
-                        max_iter=w.max_iter, tol=w.tol)
+        if args.full_solve:
+            # solve at the paper's training tolerance (Experiment details: tolerance 1, rank-100 preconditioner)
+            t0 = time.perf_counter()
+            full = egp.mbcg(X, B17, w.lengthscales, w.outputscale, w.noise, w.kernel_type, precond=P,
+                            max_iter=1000, tol=w.tol)
+            torch.cuda.synchronize()
+            result["mbcg"]["full_solve_tol1"] = {"s": time.perf_counter() - t0, "iters": full["iters"],
+                                                 "rel_resid_max": float(full["rel_resid"].max()),
+                                                 "resid_hist_max": [float(v) for v in full["resid_hist"].max(axis=1)]}
+        del P
+
+    if args.grad:
+        w3 = make_workload("C3")
+        X3 = torch.from_numpy(w3.X).to(dev)
+        V3 = torch.from_numpy(w3.V).to(dev)
+        g3 = torch.empty((w3.d, w3.n, w3.t), dtype=torch.float32, device=dev)
+        o3 = torch.empty_like(V3)
+        wsg = torch.empty(lib.egp_kmm_grad_ws_bytes(w3.n, w3.d, w3.t), dtype=torch.uint8, device=dev)
+        wsk = torch.empty(lib.egp_kmm_ws_bytes(w3.n, w3.d, w3.t), dtype=torch.uint8, device=dev)
+        leg = {}
+        for name, fn in (("kmm", lambda: egp.kmm(X3, V3, w3.lengthscales, w3.outputscale, w3.noise, w3.kernel_type,
+                                                 out=o3, ws=wsk)),
+                         ("kmm_grad", lambda: egp.kmm_grad(X3, V3, w3.lengthscales, w3.outputscale, w3.noise,
+                                                           w3.kernel_type, out=g3, ws=wsg))):
+            fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            leg[name + "_s"] = (time.perf_counter() - t0) / 3
+        fk = flops_per_entry(w3.d, w3.t, w3.kernel_type)
+        fg = fk - 2 * w3.t + w3.d * (2 * w3.t + 3)
+        leg["kmm_frac_fp32_peak"] = fk * w3.n ** 2 / leg["kmm_s"] / 1e12 / FP32_PEAK_TFLOPS
+        leg["kmm_grad_frac_fp32_peak"] = fg * w3.n ** 2 / leg["kmm_grad_s"] / 1e12 / FP32_PEAK_TFLOPS
+        leg["workload"] = f"C3: n={w3.n}, d={w3.d}, t={w3.t}, RBF-ARD, all {w3.d} lengthscale derivatives"
+        result["c3"] = leg
+        del X3, V3, g3, o3, wsg, wsk
+
+    if args.mll > 0:
+        w5 = make_workload("C5")
+        rng = np.random.default_rng(5)
+        X5 = torch.from_numpy(w5.X).to(dev)
+        y5 = torch.from_numpy(w5.y).to(dev)
+        W1 = torch.from_numpy((2.0 * rng.integers(0, 2, size=(w5.rank, 16)) - 1.0).astype(np.float32)).to(dev)
+        W2 = torch.from_numpy(np.ascontiguousarray(w5.V[:, 1:17])).to(dev)
+        ws5 = torch.empty(lib.egp_mll_ws_bytes(w5.n, w5.d, 16, w5.rank, args.mll), dtype=torch.uint8, device=dev)
         torch.cuda.synchronize()
-        result["mbcg"]["full_solve_tol1"] = {"s": time.perf_counter() - t0, "iters": full["iters"],
-                                             "rel_resid_max": float(full["rel_resid"].max())}
+        t0 = time.perf_counter()
+        r5 = egp.mll(X5, y5, W1, W2, w5.lengthscales, w5.outputscale, w5.noise, w5.kernel_type, rank=w5.rank,
+                     max_iter=args.mll, tol=w5.tol, ws=ws5)
+        torch.cuda.synchronize()
+        result["c5_mll_step"] = {"s": time.perf_counter() - t0, "cg_iters": r5["iters"],
+                                 "rel_resid_max": r5["rel_resid_max"], "mll": r5["mll"],
+                                 "workload": f"C5: n={w5.n}, d={w5.d}, Matern-3/2 ARD, 16 probes, rank {w5.rank}, "
+                                             f"CG capped at {args.mll} iterations"}
+        del X5, y5, W1, W2, ws5
 
     if not args.no_cpu_baseline:
         import oracle as orc
