@@ -58,6 +58,12 @@ int pivchol_core(const float* X, int64_t n, const egp_hyper_t* h, float tol_abs,
 size_t precond_apply_ws(int64_t n, int t, int rank);
 int precond_apply_core(const float* L, int rank, const float* Minv_dev, int64_t n, float noise, const float* R,
                        int t, float* Z, float* rz_partial, void* ws, hipStream_t stream);
+int precond_apply_blocks(int64_t n);
+int precond_apply_cm(const float* L, int rank, const float* Minv_dev, int64_t n, float noise, const float* R,
+                     int64_t ld, int t, float* Z, float* rz_part, int part_ld, void* ws, hipStream_t stream);
+int kmm_cm_dot_blocks(int64_t npad);
+int kmm_core_cm(const Prepared& P, const float* V, int t, float* out, void* ws2, float* dot_part, int dot_ld,
+                hipStream_t stream);
 size_t mbcg_ws_bytes_core(int64_t n, int d, int t, int rank, int max_iter);
 int mbcg_core(const float* X, int64_t n, const float* B, int t, const egp_hyper_t* h, const egp_precond_t* P,
               int max_iter, float tol, float* U, double* cg_coef, double* gamma0, int32_t* iters_done,

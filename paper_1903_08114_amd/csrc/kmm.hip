@@ -164,7 +164,7 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel(const float* __restrict__ X
                                                      const f4* __restrict__ Vp,
                                                      const float* __restrict__ Ep,
                                                      float* __restrict__ Part, int64_t npad, int d,
-                                                     int stages_per_split, int stages_total) {
+                                                     int stages_per_split, int stages_total, int cm) {
   constexpr int TS = 16 * NB + EXTRA;
   constexpr int XF4 = JT * KS * 16;       // f4 elements of packed points per stage
   constexpr int VF4 = JT * NB * 64;       // f4 elements of packed V per stage
@@ -292,6 +292,23 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel(const float* __restrict__ X
 
   // ---- write raw accumulators: lane (q,p), register r holds out[row 4q + r][column p] ----
   float* dst = Part + (int64_t)blockIdx.y * npad * TS;
+  if (cm) {
+    // column-major partials [TS][npad]: the four rows of a lane are one 16-byte store
+#pragma unroll
+    for (int it = 0; it < R; ++it) {
+      const int64_t row0 = (row_tile0 + it) * 16;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+        *reinterpret_cast<f4*>(dst + (int64_t)(nb * 16 + p) * npad + row0 + q * 4) = o[it][nb];
+      if (EXTRA) {
+        float s = eacc[it];
+        s += __shfl_xor(s, 16);
+        s += __shfl_xor(s, 32);
+        if (q == 0) dst[(int64_t)(16 * NB) * npad + row0 + p] = s;
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int it = 0; it < R; ++it) {
     const int64_t row0 = (row_tile0 + it) * 16;
@@ -325,6 +342,70 @@ __global__ __launch_bounds__(256) void kmm_epilogue(const float* __restrict__ Pa
   for (int sp = 0; sp < splits; ++sp) acc += Part[((int64_t)sp * npad + row) * ts + c];
   const int64_t o = row * t + c0 + c;
   out[o] = __builtin_fmaf(s, acc, noise * V[o]);
+}
+
+// Column-major variants used by the solver (state arrays are [t][ld], column c contiguous, ld = npad,
+// entries beyond n are zero).
+// Vp[tile][nb][lane=(q,p)] = V[c0 + 16 nb + p][16 tile + 4q .. +3]: one 16-byte load per lane.
+__global__ __launch_bounds__(256) void pack_rhs_cm(const float* __restrict__ V, int64_t ld, int64_t npad, int t,
+                                                   int nb_count, f4* __restrict__ Vp) {
+  int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t total = (npad >> 4) * nb_count * 64;
+  if (g >= total) return;
+  const int lane = (int)(g & 63);
+  const int64_t tn = g >> 6;
+  const int nb = (int)(tn % nb_count);
+  const int64_t tile = tn / nb_count;
+  const int q = lane >> 4, p = lane & 15;
+  const int c = nb * 16 + p;
+  f4 v = {0.f, 0.f, 0.f, 0.f};
+  if (c < t) v = *reinterpret_cast<const f4*>(V + (int64_t)c * ld + tile * 16 + q * 4);
+  Vp[g] = v;
+}
+
+// out[c][row] = s * sum_split Part[split][c][row] + noise * V[c][row]; also per-block partial sums of
+// V[c][row] * out[c][row] (the d^T Khat d of CG) into dot_part[c][blockIdx.x]. grid = (blocks, t).
+__global__ __launch_bounds__(256) void kmm_epilogue_cm(const float* __restrict__ Part, int splits, int64_t npad,
+                                                       int ts, const float* __restrict__ V, int64_t ld, int64_t n,
+                                                       float s, float noise, float* __restrict__ out,
+                                                       float* __restrict__ dot_part, int dot_ld) {
+  __shared__ float red[4];
+  const int c = blockIdx.y;
+  const float4* v4 = reinterpret_cast<const float4*>(V + (int64_t)c * ld);
+  float4* o4 = reinterpret_cast<float4*>(out + (int64_t)c * ld);
+  float acc = 0.f;
+  for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < (npad >> 2); g += (int64_t)gridDim.x * 256) {
+    float4 sum = {0.f, 0.f, 0.f, 0.f};
+    for (int sp = 0; sp < splits; ++sp) {
+      const float4 pv = reinterpret_cast<const float4*>(Part + ((int64_t)sp * ts + c) * npad)[g];
+      sum.x += pv.x; sum.y += pv.y; sum.z += pv.z; sum.w += pv.w;
+    }
+    const float4 v = v4[g];
+    float4 r;
+    r.x = __builtin_fmaf(s, sum.x, noise * v.x);
+    r.y = __builtin_fmaf(s, sum.y, noise * v.y);
+    r.z = __builtin_fmaf(s, sum.z, noise * v.z);
+    r.w = __builtin_fmaf(s, sum.w, noise * v.w);
+    const int64_t row = g * 4;                 // rows beyond n are padding and must stay zero
+    if (row + 3 >= n) {
+      if (row + 0 >= n) r.x = 0.f;
+      if (row + 1 >= n) r.y = 0.f;
+      if (row + 2 >= n) r.z = 0.f;
+      r.w = 0.f;
+    }
+    o4[g] = r;
+    acc = __builtin_fmaf(v.x, r.x, acc);
+    acc = __builtin_fmaf(v.y, r.y, acc);
+    acc = __builtin_fmaf(v.z, r.z, acc);
+    acc = __builtin_fmaf(v.w, r.w, acc);
+  }
+  if (dot_part != nullptr) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) dot_part[(int64_t)c * dot_ld + blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -403,15 +484,15 @@ Plan make_plan(int64_t npad) {
 }
 
 template <int KS, int KIND, int NB, int EXTRA>
-int launch_shape(const Prepared& P, const Plan& pl, const f4* Vp, const float* Ep, float* Part,
+int launch_shape(const Prepared& P, const Plan& pl, const f4* Vp, const float* Ep, float* Part, int cm,
                  hipStream_t stream) {
   dim3 grid(pl.row_blocks, pl.splits), block(256);
   if (pl.big) {
     hipLaunchKernelGGL((kmm_kernel<KS, kBigR, KIND, NB, EXTRA, kBigJT>), grid, block, 0, stream, P.Xp, P.nrm,
-                       Vp, Ep, Part, P.npad, P.d, pl.stages_per_split, pl.stages_total);
+                       Vp, Ep, Part, P.npad, P.d, pl.stages_per_split, pl.stages_total, cm);
   } else {
     hipLaunchKernelGGL((kmm_kernel<KS, kSmallR, KIND, NB, EXTRA, kSmallJT>), grid, block, 0, stream, P.Xp,
-                       P.nrm, Vp, Ep, Part, P.npad, P.d, pl.stages_per_split, pl.stages_total);
+                       P.nrm, Vp, Ep, Part, P.npad, P.d, pl.stages_per_split, pl.stages_total, cm);
   }
   EGP_HIP(hipGetLastError());
   return EGP_OK;
@@ -419,20 +500,36 @@ int launch_shape(const Prepared& P, const Plan& pl, const f4* Vp, const float* E
 
 template <int KS, int KIND>
 int launch_cols(const Prepared& P, const Plan& pl, int nb, int extra, const f4* Vp, const float* Ep,
-                float* Part, hipStream_t stream) {
-  if (nb == 1 && !extra) return launch_shape<KS, KIND, 1, 0>(P, pl, Vp, Ep, Part, stream);
-  if (nb == 1 && extra) return launch_shape<KS, KIND, 1, 1>(P, pl, Vp, Ep, Part, stream);
-  if (nb == 2 && !extra) return launch_shape<KS, KIND, 2, 0>(P, pl, Vp, Ep, Part, stream);
-  return launch_shape<KS, KIND, 2, 1>(P, pl, Vp, Ep, Part, stream);
+                float* Part, int cm, hipStream_t stream) {
+  if (nb == 1 && !extra) return launch_shape<KS, KIND, 1, 0>(P, pl, Vp, Ep, Part, cm, stream);
+  if (nb == 1 && extra) return launch_shape<KS, KIND, 1, 1>(P, pl, Vp, Ep, Part, cm, stream);
+  if (nb == 2 && !extra) return launch_shape<KS, KIND, 2, 0>(P, pl, Vp, Ep, Part, cm, stream);
+  return launch_shape<KS, KIND, 2, 1>(P, pl, Vp, Ep, Part, cm, stream);
 }
 
 template <int KS>
 int launch_kind(const Prepared& P, const Plan& pl, int nb, int extra, const f4* Vp, const float* Ep,
-                float* Part, hipStream_t stream) {
+                float* Part, int cm, hipStream_t stream) {
   switch (P.kernel_type) {
-    case EGP_RBF: return launch_cols<KS, EGP_RBF>(P, pl, nb, extra, Vp, Ep, Part, stream);
-    case EGP_MATERN32: return launch_cols<KS, EGP_MATERN32>(P, pl, nb, extra, Vp, Ep, Part, stream);
-    default: return launch_cols<KS, EGP_MATERN52>(P, pl, nb, extra, Vp, Ep, Part, stream);
+    case EGP_RBF: return launch_cols<KS, EGP_RBF>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case EGP_MATERN32: return launch_cols<KS, EGP_MATERN32>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    default: return launch_cols<KS, EGP_MATERN52>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
+  }
+}
+
+int launch_ks(const Prepared& P, const Plan& pl, int nb, int extra, const f4* Vp, const float* Ep, float* Part,
+              int cm, hipStream_t stream) {
+  ProfScope prof(kProfKmm, stream);
+  switch (P.ks) {
+    case 1: return launch_kind<1>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 2: return launch_kind<2>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 3: return launch_kind<3>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 4: return launch_kind<4>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 5: return launch_kind<5>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 6: return launch_kind<6>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 7: return launch_kind<7>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 8: return launch_kind<8>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    default: return fail(EGP_ERR_ARG, "d = %d needs %d k-steps; this build supports d <= 31", P.d, P.ks);
   }
 }
 
@@ -477,20 +574,7 @@ int kmm_core(const Prepared& P, const float* V, int t, float* out, void* ws2, hi
       ProfScope prof(kProfPack, stream);
       launch_pack_rhs(V, P.n, npad, t, c0, nb, extra, Vp, Ep, stream);
     }
-    int rc;
-    ProfScope* kprof = new ProfScope(kProfKmm, stream);
-    switch (P.ks) {
-      case 1: rc = launch_kind<1>(P, pl, nb, extra, Vp, Ep, Part, stream); break;
-      case 2: rc = launch_kind<2>(P, pl, nb, extra, Vp, Ep, Part, stream); break;
-      case 3: rc = launch_kind<3>(P, pl, nb, extra, Vp, Ep, Part, stream); break;
-      case 4: rc = launch_kind<4>(P, pl, nb, extra, Vp, Ep, Part, stream); break;
-      case 5: rc = launch_kind<5>(P, pl, nb, extra, Vp, Ep, Part, stream); break;
-      case 6: rc = launch_kind<6>(P, pl, nb, extra, Vp, Ep, Part, stream); break;
-      case 7: rc = launch_kind<7>(P, pl, nb, extra, Vp, Ep, Part, stream); break;
-      case 8: rc = launch_kind<8>(P, pl, nb, extra, Vp, Ep, Part, stream); break;
-      default: rc = fail(EGP_ERR_ARG, "d = %d needs %d k-steps; this build supports d <= 31", P.d, P.ks);
-    }
-    delete kprof;
+    const int rc = launch_ks(P, pl, nb, extra, Vp, Ep, Part, 0, stream);
     if (rc != EGP_OK) return rc;
     const int64_t outs = P.n * tg;
     ProfScope eprof(kProfPack, stream);
@@ -499,6 +583,43 @@ int kmm_core(const Prepared& P, const float* V, int t, float* out, void* ws2, hi
     EGP_HIP(hipGetLastError());
     c0 += tg;
   }
+  return EGP_OK;
+}
+
+// Column-major variant for the solver: V and out are [t][ld] with ld = P.npad (zero beyond n), t <= 33.
+// dot_part (optional) receives kmm_cm_dot_blocks() partial sums of V[c].out[c] per column, leading
+// dimension dot_ld.
+int kmm_cm_dot_blocks(int64_t npad) {
+  int64_t b = (npad / 4 + 255) / 256;
+  return (int)(b > 64 ? 64 : b);
+}
+
+int kmm_core_cm(const Prepared& P, const float* V, int t, float* out, void* ws2, float* dot_part, int dot_ld,
+                hipStream_t stream) {
+  const int64_t npad = P.npad;
+  const Plan pl = make_plan(npad);
+  char* w = static_cast<char*>(ws2);
+  const int nb = t > 17 ? 2 : 1;
+  const int extra = (t == 17 || t == 33) ? 1 : 0;
+  const int ts = 16 * nb + extra;
+  f4* Vp = reinterpret_cast<f4*>(w);
+  w += round_up((size_t)npad * nb * 16 * sizeof(float), 256);
+  w += round_up((size_t)npad * sizeof(float), 256);      // the row-major path's extra-column buffer (unused here)
+  float* Part = reinterpret_cast<float*>(w);
+  {
+    ProfScope prof(kProfPack, stream);
+    const int64_t total = (npad >> 4) * nb * 64;
+    hipLaunchKernelGGL(pack_rhs_cm, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, V, npad, npad,
+                       extra ? t - 1 : t, nb, Vp);
+  }
+  // the 17th / 33rd column is consumed straight from the state array
+  const float* Ep = extra ? V + (int64_t)(t - 1) * npad : nullptr;
+  const int rc = launch_ks(P, pl, nb, extra, Vp, Ep, Part, 1, stream);
+  if (rc != EGP_OK) return rc;
+  ProfScope eprof(kProfPack, stream);
+  hipLaunchKernelGGL(kmm_epilogue_cm, dim3(kmm_cm_dot_blocks(npad), t), dim3(256), 0, stream, Part, pl.splits, npad,
+                     ts, V, npad, P.n, P.outputscale, P.noise, out, dot_part, dot_ld);
+  EGP_HIP(hipGetLastError());
   return EGP_OK;
 }
 

@@ -6,9 +6,12 @@
 // The modified PCG the paper cites additionally records the CG coefficients alpha_j, beta_j of every
 // column, from which the caller builds Lanczos tridiagonals for the log-determinant estimate.
 //
-// The vector kernels below are HBM-bound. Per-column scalars never travel to the host inside an
-// iteration: every block re-reduces the per-block partial sums in the same fixed order, so all blocks
-// agree on alpha and beta bit for bit. The host reads back only the t relative residuals per iteration.
+// State is held column-major ([t][ld], one right-hand side contiguous, ld = n rounded up to 512 with
+// zero padding), so every vector kernel is a 16-byte-per-lane stream over one column (grid.y = column)
+// and every per-column scalar is block-uniform. The vector kernels are HBM-bound. Scalars never travel
+// to the host inside an iteration: every block re-reduces the per-block partial sums of its column in the
+// same fixed order, so all blocks agree on alpha and beta bit for bit. The host reads back only the t
+// relative residuals per iteration. d^T Khat d comes for free from the multiply's epilogue.
 
 #include <math.h>
 
@@ -18,88 +21,56 @@
 
 namespace egp {
 
-int precond_apply_blocks(int64_t n);
-size_t precond_apply_ws(int64_t n, int t, int rank);
-int precond_apply_core(const float* L, int rank, const float* Minv_dev, int64_t n, float noise, const float* R,
-                       int t, float* Z, float* rz_partial, void* ws, hipStream_t stream);
-
 namespace {
 
-constexpr int kVecBlocks = 1024;
-constexpr int kTMax = 33;
+constexpr int kColBlocks = 64;     // blocks per column in the vector kernels
+constexpr int kPartLd = 1024;      // leading dimension of every per-column partial-sum array
 
-// Thread layout of the vector kernels: TP = power of two >= t columns, 256/TP rows per pass.
-struct Lay { int tp, rows; };
-Lay layout_for(int t) {
-  int tp = 1;
-  while (tp < t) tp *= 2;
-  if (tp < 16) tp = 16;
-  return {tp, 256 / tp};
+__device__ __forceinline__ float block_sum(float v, float* red /*[4]*/) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return (red[0] + red[1]) + (red[2] + red[3]);
 }
 
-// Sum `parts` per-block partials of column c in a fixed order (identical in every block).
-__device__ float reduce_partials(const float* __restrict__ part, int parts, int t, int c, int rl, int rows,
-                                 float* sh /*[256]*/) {
+// Sum of `count` partials (fixed order: thread-strided, then the block tree) in double.
+__device__ double reduce_partials(const float* __restrict__ part, int count, double* red /*[4]*/) {
   double s = 0.0;
-  if (c < t)
-    for (int b = rl; b < parts; b += rows) s += (double)part[(int64_t)b * t + c];
+  for (int b = threadIdx.x; b < count; b += 256) s += (double)part[b];
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
   __syncthreads();
-  sh[threadIdx.x] = (float)s;
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
   __syncthreads();
-  double tot = 0.0;
-  const int tp = 256 / rows;
-  if (c < t)
-    for (int r = 0; r < rows; ++r) tot += (double)sh[r * tp + c];
-  return (float)tot;
+  return (red[0] + red[1]) + (red[2] + red[3]);
 }
 
-// Per-block column sums of `val` (thread (rl, c)) -> out[blockIdx][c].
-__device__ void write_partial(float val, int t, int c, int rl, int rows, float* sh, float* __restrict__ out) {
-  __syncthreads();
-  sh[threadIdx.x] = val;
-  __syncthreads();
-  if (rl == 0 && c < t) {
-    const int tp = 256 / rows;
-    float s = 0.f;
-    for (int r = 0; r < rows; ++r) s += sh[r * tp + c];
-    out[(int64_t)blockIdx.x * t + c] = s;
-  }
-}
-
-// R = B, U = 0, (Z = R when there is no preconditioner), partial sums of B.B
-__global__ __launch_bounds__(256) void cg_init(const float* __restrict__ B, int64_t n, int t, int tp,
+// B (row-major n x t) -> R (column-major), U = 0, optional Z = R; partial sums of b.b per column.
+// grid = (kColBlocks, t)
+__global__ __launch_bounds__(256) void cg_init(const float* __restrict__ B, int64_t n, int t, int64_t ld,
                                                float* __restrict__ U, float* __restrict__ R,
                                                float* __restrict__ Zopt, float* __restrict__ bb_part) {
-  __shared__ float sh[256];
-  const int rows = 256 / tp, c = threadIdx.x % tp, rl = threadIdx.x / tp;
+  __shared__ float red[4];
+  const int c = blockIdx.y;
   float acc = 0.f;
-  if (c < t)
-    for (int64_t i = (int64_t)blockIdx.x * rows + rl; i < n; i += (int64_t)gridDim.x * rows) {
-      const float b = B[i * t + c];
-      U[i * t + c] = 0.f;
-      R[i * t + c] = b;
-      if (Zopt) Zopt[i * t + c] = b;
-      acc = __builtin_fmaf(b, b, acc);
-    }
-  write_partial(acc, t, c, rl, rows, sh, bb_part);
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < ld; i += (int64_t)gridDim.x * 256) {
+    const float b = i < n ? B[i * t + c] : 0.f;
+    const int64_t o = (int64_t)c * ld + i;
+    U[o] = 0.f;
+    R[o] = b;
+    if (Zopt) Zopt[o] = b;
+    acc = __builtin_fmaf(b, b, acc);
+  }
+  const float s = block_sum(acc, red);
+  if (threadIdx.x == 0) bb_part[c * kPartLd + blockIdx.x] = s;
 }
 
-__global__ __launch_bounds__(256) void cg_copy(const float* __restrict__ src, int64_t count,
-                                               float* __restrict__ dst) {
-  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < count; e += (int64_t)gridDim.x * 256)
+__global__ __launch_bounds__(256) void cg_copy(const float4* __restrict__ src, int64_t count4,
+                                               float4* __restrict__ dst) {
+  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < count4; e += (int64_t)gridDim.x * 256)
     dst[e] = src[e];
-}
-
-// partial sums of D.W per column
-__global__ __launch_bounds__(256) void cg_dot(const float* __restrict__ D, const float* __restrict__ W, int64_t n,
-                                              int t, int tp, float* __restrict__ part) {
-  __shared__ float sh[256];
-  const int rows = 256 / tp, c = threadIdx.x % tp, rl = threadIdx.x / tp;
-  float acc = 0.f;
-  if (c < t)
-    for (int64_t i = (int64_t)blockIdx.x * rows + rl; i < n; i += (int64_t)gridDim.x * rows)
-      acc = __builtin_fmaf(D[i * t + c], W[i * t + c], acc);
-  write_partial(acc, t, c, rl, rows, sh, part);
 }
 
 struct CgLog {
@@ -109,74 +80,86 @@ struct CgLog {
   int* breakdown;    // device flag
 };
 
-// alpha = gamma / delta; U += alpha D; R -= alpha W; partial sums of R.R
+// alpha = gamma / delta; U += alpha D; R -= alpha W; partial sums of r.r.   grid = (kColBlocks, t)
 __global__ __launch_bounds__(256) void cg_update(const float* __restrict__ D, const float* __restrict__ W,
-                                                 int64_t n, int t, int tp, const float* __restrict__ gamma_part,
-                                                 int gparts, const float* __restrict__ delta_part, int dparts,
+                                                 int64_t ld, int t, const float* __restrict__ gamma_part, int gparts,
+                                                 const float* __restrict__ delta_part, int dparts,
                                                  float* __restrict__ U, float* __restrict__ R,
                                                  float* __restrict__ rr_part, int iter, CgLog log) {
-  __shared__ float sh[256];
-  const int rows = 256 / tp, c = threadIdx.x % tp, rl = threadIdx.x / tp;
-  const float gamma = reduce_partials(gamma_part, gparts, t, c, rl, rows, sh);
-  const float delta = reduce_partials(delta_part, dparts, t, c, rl, rows, sh);
-  float alpha = 0.f;
-  if (c < t) {
-    if (delta > 0.f && gamma > 0.f) alpha = gamma / delta;
-    if (blockIdx.x == 0 && rl == 0) {
-      log.alpha[(int64_t)iter * t + c] = (delta > 0.f && gamma > 0.f) ? (double)gamma / (double)delta : 0.0;
-      if (gamma > 0.f && !(delta > 0.f)) *log.breakdown = 1;
-    }
+  __shared__ double redd[4];
+  __shared__ float red[4];
+  const int c = blockIdx.y;
+  const double gamma = reduce_partials(gamma_part + c * kPartLd, gparts, redd);
+  const double delta = reduce_partials(delta_part + c * kPartLd, dparts, redd);
+  const bool ok = delta > 0.0 && gamma > 0.0;
+  const float alpha = ok ? (float)(gamma / delta) : 0.f;
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    log.alpha[(int64_t)iter * t + c] = ok ? gamma / delta : 0.0;
+    if (gamma > 0.0 && !(delta > 0.0)) *log.breakdown = 1;
   }
+  const float4* d4 = reinterpret_cast<const float4*>(D + (int64_t)c * ld);
+  const float4* w4 = reinterpret_cast<const float4*>(W + (int64_t)c * ld);
+  float4* u4 = reinterpret_cast<float4*>(U + (int64_t)c * ld);
+  float4* r4 = reinterpret_cast<float4*>(R + (int64_t)c * ld);
   float acc = 0.f;
-  if (c < t)
-    for (int64_t i = (int64_t)blockIdx.x * rows + rl; i < n; i += (int64_t)gridDim.x * rows) {
-      const int64_t o = i * t + c;
-      U[o] = __builtin_fmaf(alpha, D[o], U[o]);
-      const float r = __builtin_fmaf(-alpha, W[o], R[o]);
-      R[o] = r;
-      acc = __builtin_fmaf(r, r, acc);
-    }
-  write_partial(acc, t, c, rl, rows, sh, rr_part);
+  for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < (ld >> 2); g += (int64_t)gridDim.x * 256) {
+    const float4 d = d4[g], w = w4[g];
+    float4 u = u4[g], r = r4[g];
+    u.x = __builtin_fmaf(alpha, d.x, u.x); u.y = __builtin_fmaf(alpha, d.y, u.y);
+    u.z = __builtin_fmaf(alpha, d.z, u.z); u.w = __builtin_fmaf(alpha, d.w, u.w);
+    r.x = __builtin_fmaf(-alpha, w.x, r.x); r.y = __builtin_fmaf(-alpha, w.y, r.y);
+    r.z = __builtin_fmaf(-alpha, w.z, r.z); r.w = __builtin_fmaf(-alpha, w.w, r.w);
+    u4[g] = u;
+    r4[g] = r;
+    acc = __builtin_fmaf(r.x, r.x, acc); acc = __builtin_fmaf(r.y, r.y, acc);
+    acc = __builtin_fmaf(r.z, r.z, acc); acc = __builtin_fmaf(r.w, r.w, acc);
+  }
+  const float s = block_sum(acc, red);
+  if (threadIdx.x == 0) rr_part[c * kPartLd + blockIdx.x] = s;
 }
 
-// beta = gamma_new / gamma_old; D = Z + beta D; block 0 also logs beta and the relative residuals.
-__global__ __launch_bounds__(256) void cg_direction(const float* __restrict__ Z, int64_t n, int t, int tp,
+// beta = gamma_new / gamma_old; D = Z + beta D; block 0 of each column logs beta and the relative residual.
+__global__ __launch_bounds__(256) void cg_direction(const float* __restrict__ Z, int64_t ld, int t,
                                                     const float* __restrict__ gnew_part, int gnparts,
                                                     const float* __restrict__ gold_part, int goparts,
                                                     const float* __restrict__ rr_part, int rrparts,
                                                     const float* __restrict__ bb_part, int bbparts,
                                                     float* __restrict__ D, int iter, CgLog log) {
-  __shared__ float sh[256];
-  const int rows = 256 / tp, c = threadIdx.x % tp, rl = threadIdx.x / tp;
-  const float gnew = reduce_partials(gnew_part, gnparts, t, c, rl, rows, sh);
-  const float gold = reduce_partials(gold_part, goparts, t, c, rl, rows, sh);
-  float beta = 0.f;
-  if (c < t && gold > 0.f && gnew > 0.f) beta = gnew / gold;
+  __shared__ double redd[4];
+  const int c = blockIdx.y;
+  const double gnew = reduce_partials(gnew_part + c * kPartLd, gnparts, redd);
+  const double gold = reduce_partials(gold_part + c * kPartLd, goparts, redd);
+  const bool ok = gold > 0.0 && gnew > 0.0;
+  const float beta = ok ? (float)(gnew / gold) : 0.f;
   if (blockIdx.x == 0) {
-    const float rr = reduce_partials(rr_part, rrparts, t, c, rl, rows, sh);
-    const float bb = reduce_partials(bb_part, bbparts, t, c, rl, rows, sh);
-    if (c < t && rl == 0) {
-      log.beta[(int64_t)iter * t + c] = (gold > 0.f && gnew > 0.f) ? (double)gnew / (double)gold : 0.0;
-      log.rel[c] = bb > 0.f ? sqrtf(rr / bb) : 0.f;
+    const double rr = reduce_partials(rr_part + c * kPartLd, rrparts, redd);
+    const double bb = reduce_partials(bb_part + c * kPartLd, bbparts, redd);
+    if (threadIdx.x == 0) {
+      log.beta[(int64_t)iter * t + c] = ok ? gnew / gold : 0.0;
+      log.rel[c] = bb > 0.0 ? (float)sqrt(rr / bb) : 0.f;
     }
   }
-  if (c < t)
-    for (int64_t i = (int64_t)blockIdx.x * rows + rl; i < n; i += (int64_t)gridDim.x * rows) {
-      const int64_t o = i * t + c;
-      D[o] = __builtin_fmaf(beta, D[o], Z[o]);
-    }
+  const float4* z4 = reinterpret_cast<const float4*>(Z + (int64_t)c * ld);
+  float4* d4 = reinterpret_cast<float4*>(D + (int64_t)c * ld);
+  for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < (ld >> 2); g += (int64_t)gridDim.x * 256) {
+    const float4 z = z4[g];
+    float4 d = d4[g];
+    d.x = __builtin_fmaf(beta, d.x, z.x); d.y = __builtin_fmaf(beta, d.y, z.y);
+    d.z = __builtin_fmaf(beta, d.z, z.z); d.w = __builtin_fmaf(beta, d.w, z.w);
+    d4[g] = d;
+  }
 }
 
-// gamma0[c] = total of gamma partials (one block)
-__global__ __launch_bounds__(256) void cg_gamma0(const float* __restrict__ part, int parts, int t, int tp,
-                                                 double* __restrict__ out) {
-  __shared__ float sh[256];
-  const int rows = 256 / tp, c = threadIdx.x % tp, rl = threadIdx.x / tp;
-  const float g = reduce_partials(part, parts, t, c, rl, rows, sh);
-  if (c < t && rl == 0) out[c] = (double)g;
+// gamma0[c] = total of the gamma partials of column c.  grid = (1, t)
+__global__ __launch_bounds__(256) void cg_gamma0(const float* __restrict__ part, int parts, double* __restrict__ out) {
+  __shared__ double redd[4];
+  const double g = reduce_partials(part + blockIdx.y * kPartLd, parts, redd);
+  if (threadIdx.x == 0) out[blockIdx.y] = g;
 }
 
 }  // namespace
+
+void launch_to_rowmajor(const float* src, int64_t n, int t, int64_t ld, float* dst, hipStream_t stream);
 
 struct MbcgWs {
   size_t prep, kmm, state, part, log, pre, total;
@@ -184,11 +167,12 @@ struct MbcgWs {
 
 static MbcgWs mbcg_layout(int64_t n, int d, int t, int rank, int max_iter) {
   MbcgWs w;
+  const int64_t ld = padded_points(n);
   w.prep = prepared_bytes(n, d);
   w.kmm = kmm_core_ws_bytes(n, t);
-  w.state = 4 * round_up((size_t)n * t * sizeof(float), 256);               // R, D, Z, W
-  w.part = 5 * round_up((size_t)kVecBlocks * kTMax * sizeof(float), 256);   // bb, rr, delta, gamma x2
-  w.log = round_up((size_t)2 * (max_iter > 0 ? max_iter : 1) * t * sizeof(double), 256) + 512;
+  w.state = 5 * round_up((size_t)ld * t * sizeof(float), 256);              // U, R, D, Z, W (column-major)
+  w.part = 5 * round_up((size_t)33 * kPartLd * sizeof(float), 256);         // bb, rr, delta, gamma x2
+  w.log = round_up((size_t)2 * (max_iter > 0 ? max_iter : 1) * t * sizeof(double), 256) + 1024;
   w.pre = rank > 0 ? precond_apply_ws(n, t, rank) : 0;
   w.total = w.prep + w.kmm + w.state + w.part + w.log + w.pre;
   return w;
@@ -203,6 +187,7 @@ int mbcg_core(const float* X, int64_t n, const float* B, int t, const egp_hyper_
               float* rel_resid, float* resid_hist, void* ws, hipStream_t stream) {
   const int rank = P ? P->rank : 0;
   const MbcgWs lay = mbcg_layout(n, h->d, t, rank, max_iter);
+  const int64_t ld = padded_points(n);
   char* w = static_cast<char*>(ws);
   Prepared prep;
   int rc = prepare_points(X, n, h, w, &prep, stream);
@@ -210,13 +195,14 @@ int mbcg_core(const float* X, int64_t n, const float* B, int t, const egp_hyper_
   w += lay.prep;
   void* kmm_ws = w;
   w += lay.kmm;
-  const size_t vec = round_up((size_t)n * t * sizeof(float), 256);
-  float* R = reinterpret_cast<float*>(w);
-  float* D = reinterpret_cast<float*>(w + vec);
-  float* Z = reinterpret_cast<float*>(w + 2 * vec);
-  float* W = reinterpret_cast<float*>(w + 3 * vec);
+  const size_t vec = round_up((size_t)ld * t * sizeof(float), 256);
+  float* Uc = reinterpret_cast<float*>(w);
+  float* R = reinterpret_cast<float*>(w + vec);
+  float* D = reinterpret_cast<float*>(w + 2 * vec);
+  float* Z = reinterpret_cast<float*>(w + 3 * vec);
+  float* W = reinterpret_cast<float*>(w + 4 * vec);
   w += lay.state;
-  const size_t pb = round_up((size_t)kVecBlocks * kTMax * sizeof(float), 256);
+  const size_t pb = round_up((size_t)33 * kPartLd * sizeof(float), 256);
   float* bb_part = reinterpret_cast<float*>(w);
   float* rr_part = reinterpret_cast<float*>(w + pb);
   float* delta_part = reinterpret_cast<float*>(w + 2 * pb);
@@ -229,34 +215,32 @@ int mbcg_core(const float* X, int64_t n, const float* B, int t, const egp_hyper_
   char* tail = w + round_up((size_t)2 * mi * t * sizeof(double), 256);
   log.rel = reinterpret_cast<float*>(tail);
   log.breakdown = reinterpret_cast<int*>(tail + 256);
+  double* g0_dev = reinterpret_cast<double*>(tail + 512);     // 33 doubles fit in the remaining 512 bytes
   w += lay.log;
   void* pre_ws = w;
 
-  const Lay ly = layout_for(t);
-  int64_t want = (n + ly.rows - 1) / ly.rows;
-  const int blocks = (int)(want > kVecBlocks ? kVecBlocks : want);
+  const dim3 vgrid(kColBlocks, t);
   const int pblocks = precond_apply_blocks(n);
-  // with a preconditioner gamma partials come from the Woodbury kernel (pblocks of them), else they
-  // are the r.r partials of the update kernel (blocks of them)
+  const int dot_blocks = kmm_cm_dot_blocks(ld);
   int gparts[2];
 
   EGP_HIP(hipMemsetAsync(log.breakdown, 0, sizeof(int), stream));
-  hipLaunchKernelGGL(cg_init, dim3(blocks), dim3(256), 0, stream, B, n, t, ly.tp, U, R, P ? nullptr : Z, bb_part);
+  hipLaunchKernelGGL(cg_init, vgrid, dim3(256), 0, stream, B, n, t, ld, Uc, R, Z, bb_part);   // Z = R also zeroes Z's padding
   if (P) {
-    rc = precond_apply_core(P->L, rank, P->small_dev, n, h->noise, R, t, Z, gam_part[0], pre_ws, stream);
+    rc = precond_apply_cm(P->L, rank, P->small_dev, n, h->noise, R, ld, t, Z, gam_part[0], kPartLd, pre_ws, stream);
     if (rc != EGP_OK) return rc;
     gparts[0] = pblocks;
   } else {
-    hipLaunchKernelGGL(cg_copy, dim3(blocks), dim3(256), 0, stream, bb_part, (int64_t)blocks * t, gam_part[0]);
-    gparts[0] = blocks;
+    hipLaunchKernelGGL(cg_copy, dim3(64), dim3(256), 0, stream, reinterpret_cast<const float4*>(bb_part),
+                       (int64_t)t * kPartLd / 4, reinterpret_cast<float4*>(gam_part[0]));
+    gparts[0] = kColBlocks;
   }
-  hipLaunchKernelGGL(cg_copy, dim3(1024), dim3(256), 0, stream, Z, n * t, D);
+  hipLaunchKernelGGL(cg_copy, dim3(1024), dim3(256), 0, stream, reinterpret_cast<const float4*>(Z), ld * t / 4,
+                     reinterpret_cast<float4*>(D));
   EGP_HIP(hipGetLastError());
   if (gamma0 != nullptr) {
-    // reuse the start of delta_part as a staging area for t doubles
-    double* g0 = reinterpret_cast<double*>(delta_part);
-    hipLaunchKernelGGL(cg_gamma0, dim3(1), dim3(256), 0, stream, gam_part[0], gparts[0], t, ly.tp, g0);
-    EGP_HIP(hipMemcpyAsync(gamma0, g0, sizeof(double) * t, hipMemcpyDeviceToHost, stream));
+    hipLaunchKernelGGL(cg_gamma0, dim3(1, t), dim3(256), 0, stream, gam_part[0], gparts[0], g0_dev);
+    EGP_HIP(hipMemcpyAsync(gamma0, g0_dev, sizeof(double) * t, hipMemcpyDeviceToHost, stream));
     EGP_HIP(hipStreamSynchronize(stream));
   }
 
@@ -264,29 +248,31 @@ int mbcg_core(const float* X, int64_t n, const float* B, int t, const egp_hyper_
   int it = 0;
   int cur = 0;
   for (; it < max_iter;) {
-    rc = kmm_core(prep, D, t, W, kmm_ws, stream);
+    rc = kmm_core_cm(prep, D, t, W, kmm_ws, delta_part, kPartLd, stream);
     if (rc != EGP_OK) return rc;
-    ProfScope* vprof = new ProfScope(kProfCgVec, stream);
-    hipLaunchKernelGGL(cg_dot, dim3(blocks), dim3(256), 0, stream, D, W, n, t, ly.tp, delta_part);
-    hipLaunchKernelGGL(cg_update, dim3(blocks), dim3(256), 0, stream, D, W, n, t, ly.tp, gam_part[cur],
-                       gparts[cur], delta_part, blocks, U, R, rr_part, it, log);
-    delete vprof;
+    {
+      ProfScope vprof(kProfCgVec, stream);
+      hipLaunchKernelGGL(cg_update, vgrid, dim3(256), 0, stream, D, W, ld, t, gam_part[cur], gparts[cur], delta_part,
+                         dot_blocks, Uc, R, rr_part, it, log);
+    }
     const int nxt = cur ^ 1;
     const float* Zsrc;
     if (P) {
-      rc = precond_apply_core(P->L, rank, P->small_dev, n, h->noise, R, t, Z, gam_part[nxt], pre_ws, stream);
+      rc = precond_apply_cm(P->L, rank, P->small_dev, n, h->noise, R, ld, t, Z, gam_part[nxt], kPartLd, pre_ws,
+                            stream);
       if (rc != EGP_OK) return rc;
       gparts[nxt] = pblocks;
       Zsrc = Z;
     } else {
-      hipLaunchKernelGGL(cg_copy, dim3(blocks), dim3(256), 0, stream, rr_part, (int64_t)blocks * t, gam_part[nxt]);
-      gparts[nxt] = blocks;
+      hipLaunchKernelGGL(cg_copy, dim3(64), dim3(256), 0, stream, reinterpret_cast<const float4*>(rr_part),
+                         (int64_t)t * kPartLd / 4, reinterpret_cast<float4*>(gam_part[nxt]));
+      gparts[nxt] = kColBlocks;
       Zsrc = R;
     }
     {
       ProfScope dprof(kProfCgVec, stream);
-      hipLaunchKernelGGL(cg_direction, dim3(blocks), dim3(256), 0, stream, Zsrc, n, t, ly.tp, gam_part[nxt],
-                         gparts[nxt], gam_part[cur], gparts[cur], rr_part, blocks, bb_part, blocks, D, it, log);
+      hipLaunchKernelGGL(cg_direction, vgrid, dim3(256), 0, stream, Zsrc, ld, t, gam_part[nxt], gparts[nxt],
+                         gam_part[cur], gparts[cur], rr_part, kColBlocks, bb_part, kColBlocks, D, it, log);
     }
     EGP_HIP(hipGetLastError());
     EGP_HIP(hipMemcpyAsync(rel.data(), log.rel, sizeof(float) * t, hipMemcpyDeviceToHost, stream));
@@ -307,6 +293,8 @@ int mbcg_core(const float* X, int64_t n, const float* B, int t, const egp_hyper_
     }
     if (worst <= tol) break;
   }
+  launch_to_rowmajor(Uc, n, t, ld, U, stream);
+  EGP_HIP(hipGetLastError());
   if (iters_done) *iters_done = it;
   if (rel_resid)
     for (int c = 0; c < t; ++c) rel_resid[c] = rel[c];

@@ -157,69 +157,84 @@ __global__ __launch_bounds__(256) void pc_step(const float* __restrict__ Xp, int
   }
 }
 
-// ---- C[a][b] (+)= sum_i A[a][i] * B(b,i) over a chunk of i: generic 64x64 tile, 4x4 per thread ----
-// A is [ra][n] (rows contiguous in i). B is either [rb][n] (BT = false) or [n][rb] row-major (BT = true).
-// Partial results go to Cp[chunk][ra][rb]; a second kernel sums chunks in order.
-template <bool BT>
-__global__ __launch_bounds__(256) void nt_gemm_partial(const float* __restrict__ A, int ra,
-                                                       const float* __restrict__ B, int rb, int64_t n,
-                                                       int64_t chunk, float* __restrict__ Cp) {
-  __shared__ float As[16][64 + 1];
-  __shared__ float Bs[16][64 + 1];
-  const int ta = blockIdx.y * 64, tb = blockIdx.z * 64;
+// ---- C[a][b] = sum_i A[a][i] * B[b][i] over a chunk of i (both operands contiguous in i) ----
+// Block tile 128 (a) x 32 (b), 256 threads each 8 x 2 outputs, 32 points per LDS step. Partial results go to
+// Cp[chunk][ra][rb]; reduce_chunks sums chunks in a fixed order.
+__global__ __launch_bounds__(256) void gram_partial(const float* __restrict__ A, int ra, int64_t lda,
+                                                    const float* __restrict__ B, int rb, int64_t ldb, int64_t n,
+                                                    int64_t chunk, float* __restrict__ Cp, int vecA, int vecB) {
+  __shared__ float As[32][128 + 4];
+  __shared__ float Bs[32][32 + 4];
+  const int ta = blockIdx.y * 128, tb = blockIdx.z * 32;
   const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
   const int64_t i_begin = (int64_t)blockIdx.x * chunk;
   int64_t i_end = i_begin + chunk;
   if (i_end > n) i_end = n;
-  float acc[4][4] = {};
-  for (int64_t i0 = i_begin; i0 < i_end; i0 += 16) {
-    // load 64 rows x 16 points of A (coalesced over i within a row)
-    for (int e = threadIdx.x; e < 64 * 16; e += 256) {
-      const int r = e >> 4, ii = e & 15;
-      const int64_t i = i0 + ii;
-      As[ii][r] = (ta + r < ra && i < i_end) ? A[(int64_t)(ta + r) * n + i] : 0.f;
+  float acc[8][2] = {};
+  for (int64_t i0 = i_begin; i0 < i_end; i0 += 32) {
+    // 128 rows x 32 points of A: 1024 float4, 4 per thread; row a = e / 8, points 4 (e % 8) .. +3
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int e = threadIdx.x + k * 256;
+      const int a = e >> 3, i4 = (e & 7) * 4;
+      float4 v = {0.f, 0.f, 0.f, 0.f};
+      const int64_t i = i0 + i4;
+      if (ta + a < ra) {
+        const float* src = A + (int64_t)(ta + a) * lda + i;
+        if (vecA && i + 3 < i_end) v = *reinterpret_cast<const float4*>(src);
+        else {
+          if (i + 0 < i_end) v.x = src[0];
+          if (i + 1 < i_end) v.y = src[1];
+          if (i + 2 < i_end) v.z = src[2];
+          if (i + 3 < i_end) v.w = src[3];
+        }
+      }
+      As[i4 + 0][a] = v.x; As[i4 + 1][a] = v.y; As[i4 + 2][a] = v.z; As[i4 + 3][a] = v.w;
     }
-    if (!BT) {
-      for (int e = threadIdx.x; e < 64 * 16; e += 256) {
-        const int r = e >> 4, ii = e & 15;
-        const int64_t i = i0 + ii;
-        Bs[ii][r] = (tb + r < rb && i < i_end) ? B[(int64_t)(tb + r) * n + i] : 0.f;
+    {
+      const int e = threadIdx.x;            // 32 rows x 32 points of B: 256 float4
+      const int bb = e >> 3, i4 = (e & 7) * 4;
+      float4 v = {0.f, 0.f, 0.f, 0.f};
+      const int64_t i = i0 + i4;
+      if (tb + bb < rb) {
+        const float* src = B + (int64_t)(tb + bb) * ldb + i;
+        if (vecB && i + 3 < i_end) v = *reinterpret_cast<const float4*>(src);
+        else {
+          if (i + 0 < i_end) v.x = src[0];
+          if (i + 1 < i_end) v.y = src[1];
+          if (i + 2 < i_end) v.z = src[2];
+          if (i + 3 < i_end) v.w = src[3];
+        }
       }
-    } else {
-      for (int e = threadIdx.x; e < 64 * 16; e += 256) {
-        const int ii = e >> 6, r = e & 63;
-        const int64_t i = i0 + ii;
-        Bs[ii][r] = (tb + r < rb && i < i_end) ? B[i * rb + tb + r] : 0.f;
-      }
+      Bs[i4 + 0][bb] = v.x; Bs[i4 + 1][bb] = v.y; Bs[i4 + 2][bb] = v.z; Bs[i4 + 3][bb] = v.w;
     }
     __syncthreads();
+#pragma unroll 8
+    for (int ii = 0; ii < 32; ++ii) {
+      const float4 a0 = *reinterpret_cast<const float4*>(&As[ii][ty * 8]);
+      const float4 a1 = *reinterpret_cast<const float4*>(&As[ii][ty * 8 + 4]);
+      const float2 bv = *reinterpret_cast<const float2*>(&Bs[ii][tx * 2]);
+      const float av[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
 #pragma unroll
-    for (int ii = 0; ii < 16; ++ii) {
-      float av[4], bv[4];
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        av[u] = As[ii][ty * 4 + u];
-        bv[u] = Bs[ii][tx * 4 + u];
+      for (int u = 0; u < 8; ++u) {
+        acc[u][0] = __builtin_fmaf(av[u], bv.x, acc[u][0]);
+        acc[u][1] = __builtin_fmaf(av[u], bv.y, acc[u][1]);
       }
-#pragma unroll
-      for (int u = 0; u < 4; ++u)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) acc[u][v] = __builtin_fmaf(av[u], bv[v], acc[u][v]);
     }
     __syncthreads();
   }
   float* dst = Cp + (int64_t)blockIdx.x * ra * rb;
 #pragma unroll
-  for (int u = 0; u < 4; ++u)
+  for (int u = 0; u < 8; ++u)
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      const int a = ta + ty * 4 + u, b = tb + tx * 4 + v;
+    for (int v = 0; v < 2; ++v) {
+      const int a = ta + ty * 8 + u, b = tb + tx * 2 + v;
       if (a < ra && b < rb) dst[a * rb + b] = acc[u][v];
     }
 }
 
-__global__ __launch_bounds__(256) void sum_chunks(const float* __restrict__ Cp, int chunks, int count,
-                                                  float* __restrict__ C) {
+__global__ __launch_bounds__(256) void reduce_chunks(const float* __restrict__ Cp, int chunks, int count,
+                                                     float* __restrict__ C) {
   const int e = blockIdx.x * 256 + threadIdx.x;
   if (e >= count) return;
   double s = 0.0;
@@ -227,31 +242,24 @@ __global__ __launch_bounds__(256) void sum_chunks(const float* __restrict__ Cp, 
   C[e] = (float)s;
 }
 
-// Y[c][tc] = sum_c' Minv[c][c'] * W[c'][tc] with W = sum over chunks of Wp (one block).
-__global__ __launch_bounds__(256) void small_solve(const float* __restrict__ Wp, int chunks, int k, int t,
-                                                   const float* __restrict__ Minv, float* __restrict__ Y) {
-  extern __shared__ float Wsum[];   // k * t
-  for (int e = threadIdx.x; e < k * t; e += 256) {
-    double s = 0.0;
-    for (int c = 0; c < chunks; ++c) s += (double)Wp[(int64_t)c * k * t + e];
-    Wsum[e] = (float)s;
-  }
-  __syncthreads();
-  for (int e = threadIdx.x; e < k * t; e += 256) {
-    const int c = e / t, tc = e % t;
-    float acc = 0.f;
-    for (int c2 = 0; c2 < k; ++c2) acc = __builtin_fmaf(Minv[c * k + c2], Wsum[c2 * t + tc], acc);
-    Y[e] = acc;
-  }
+// Y[m][c] = sum_m2 Minv[m][m2] * W[m2][c]   (k x k times k x t, one thread per output)
+__global__ __launch_bounds__(256) void small_matmul(const float* __restrict__ Minv, const float* __restrict__ W,
+                                                    int k, int t, float* __restrict__ Y) {
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= k * t) return;
+  const int m = e / t, c = e % t;
+  float acc = 0.f;
+  for (int m2 = 0; m2 < k; ++m2) acc = __builtin_fmaf(Minv[m * k + m2], W[m2 * t + c], acc);
+  Y[e] = acc;
 }
 
-// Z[i][:] = (R[i][:] - sum_c L[c][i] Y[c][:]) / noise; optional per-block partial of sum_i R[i][c] Z[i][c].
-// One thread per point; TT = compile-time bound on t so the outputs stay in registers.
+// Column-major Woodbury finish: Z[c][i] = (R[c][i] - sum_m L[m][i] Y[m][c]) / noise for i < n; optional
+// per-block partial sums of R[c][i] Z[c][i] into rz_part[c][blockIdx]. One thread per point.
 template <int TT>
-__global__ __launch_bounds__(256) void woodbury_finish(const float* __restrict__ L, int k, int64_t n,
-                                                       const float* __restrict__ Y, const float* __restrict__ R,
-                                                       int t, float inv_noise, float* __restrict__ Z,
-                                                       float* __restrict__ rz_partial /*[grid][t] or null*/) {
+__global__ __launch_bounds__(256) void woodbury_finish_cm(const float* __restrict__ L, int k, int64_t n, int64_t ldl,
+                                                          const float* __restrict__ Y, const float* __restrict__ R,
+                                                          int64_t ld, int t, float inv_noise, float* __restrict__ Z,
+                                                          float* __restrict__ rz_part, int part_ld) {
   extern __shared__ float sh[];      // Y: k * t, then reduction scratch 4 * t
   float* Ys = sh;
   float* red = sh + k * t;
@@ -264,9 +272,9 @@ __global__ __launch_bounds__(256) void woodbury_finish(const float* __restrict__
     float acc[TT];
 #pragma unroll
     for (int c = 0; c < TT; ++c) acc[c] = 0.f;
-    for (int c2 = 0; c2 < k; ++c2) {
-      const float l = L[(int64_t)c2 * n + i];
-      const float* y = Ys + c2 * t;
+    for (int m = 0; m < k; ++m) {
+      const float l = L[(int64_t)m * ldl + i];
+      const float* y = Ys + m * t;
 #pragma unroll
       for (int c = 0; c < TT; ++c)
         if (c < t) acc[c] = __builtin_fmaf(l, y[c], acc[c]);
@@ -274,13 +282,13 @@ __global__ __launch_bounds__(256) void woodbury_finish(const float* __restrict__
 #pragma unroll
     for (int c = 0; c < TT; ++c)
       if (c < t) {
-        const float r = R[i * t + c];
+        const float r = R[(int64_t)c * ld + i];
         const float z = (r - acc[c]) * inv_noise;
-        Z[i * t + c] = z;
+        Z[(int64_t)c * ld + i] = z;
         dot[c] = __builtin_fmaf(r, z, dot[c]);
       }
   }
-  if (rz_partial != nullptr) {
+  if (rz_part != nullptr) {
 #pragma unroll
     for (int c = 0; c < TT; ++c) {
       if (c < t) {
@@ -292,19 +300,45 @@ __global__ __launch_bounds__(256) void woodbury_finish(const float* __restrict__
     }
     __syncthreads();
     if ((int)threadIdx.x < t)
-      rz_partial[(int64_t)blockIdx.x * t + threadIdx.x] =
+      rz_part[(int64_t)threadIdx.x * part_ld + blockIdx.x] =
           (red[threadIdx.x] + red[t + threadIdx.x]) + (red[2 * t + threadIdx.x] + red[3 * t + threadIdx.x]);
   }
 }
 
+// row-major n x t  <->  column-major [t][ld] (entries beyond n are written as zero on the way in)
+__global__ __launch_bounds__(256) void to_colmajor(const float* __restrict__ src, int64_t n, int t, int64_t ld,
+                                                   float* __restrict__ dst) {
+  for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < ld * t; g += (int64_t)gridDim.x * 256) {
+    const int c = (int)(g / ld);
+    const int64_t i = g % ld;
+    dst[g] = i < n ? src[i * t + c] : 0.f;
+  }
+}
+
+__global__ __launch_bounds__(256) void to_rowmajor(const float* __restrict__ src, int64_t n, int t, int64_t ld,
+                                                   float* __restrict__ dst) {
+  for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < n * t; g += (int64_t)gridDim.x * 256) {
+    const int64_t i = g / t;
+    const int c = (int)(g % t);
+    dst[g] = src[(int64_t)c * ld + i];
+  }
+}
+
 int chunks_for(int64_t n, int64_t* chunk_out) {
-  int64_t chunk = 4096;
+  int64_t chunk = 2048;
   while ((n + chunk - 1) / chunk > 512) chunk *= 2;
   *chunk_out = chunk;
   return (int)((n + chunk - 1) / chunk);
 }
 
 }  // namespace
+
+void launch_to_colmajor(const float* src, int64_t n, int t, int64_t ld, float* dst, hipStream_t stream) {
+  hipLaunchKernelGGL(to_colmajor, dim3(1024), dim3(256), 0, stream, src, n, t, ld, dst);
+}
+void launch_to_rowmajor(const float* src, int64_t n, int t, int64_t ld, float* dst, hipStream_t stream) {
+  hipLaunchKernelGGL(to_rowmajor, dim3(1024), dim3(256), 0, stream, src, n, t, ld, dst);
+}
 
 int precond_apply_blocks(int64_t n) {
   int64_t b = (n + 255) / 256;
@@ -314,12 +348,15 @@ int precond_apply_blocks(int64_t n) {
 size_t precond_apply_ws(int64_t n, int t, int rank) {
   int64_t chunk;
   const int chunks = chunks_for(n, &chunk);
-  return round_up((size_t)chunks * rank * t * sizeof(float), 256) + round_up((size_t)rank * t * sizeof(float), 256);
+  const int64_t ld = padded_points(n);
+  return round_up((size_t)chunks * rank * t * sizeof(float), 256) + 2 * round_up((size_t)rank * t * sizeof(float), 256) +
+         2 * round_up((size_t)ld * t * sizeof(float), 256);   // the last two: transposes for the row-major entry point
 }
 
-// Z = P^{-1} R; rz_partial (optional) receives precond_apply_blocks(n) x t partial sums of R.Z per column.
-int precond_apply_core(const float* L, int rank, const float* Minv_dev, int64_t n, float noise, const float* R,
-                       int t, float* Z, float* rz_partial, void* ws, hipStream_t stream) {
+// Column-major core: R, Z are [t][ld]; rz_part (optional) is [t][part_ld] with precond_apply_blocks(n) entries
+// per column.
+int precond_apply_cm(const float* L, int rank, const float* Minv_dev, int64_t n, float noise, const float* R,
+                     int64_t ld, int t, float* Z, float* rz_part, int part_ld, void* ws, hipStream_t stream) {
   if (t > 33) return fail(EGP_ERR_ARG, "preconditioner application supports t <= 33 (got %d)", t);
   ProfScope prof(kProfPrecond, stream);
   int64_t chunk;
@@ -327,23 +364,45 @@ int precond_apply_core(const float* L, int rank, const float* Minv_dev, int64_t 
   char* w = static_cast<char*>(ws);
   float* Wp = reinterpret_cast<float*>(w);
   w += round_up((size_t)chunks * rank * t * sizeof(float), 256);
+  float* Wd = reinterpret_cast<float*>(w);
+  w += round_up((size_t)rank * t * sizeof(float), 256);
   float* Y = reinterpret_cast<float*>(w);
-  dim3 grid(chunks, (rank + 63) / 64, (t + 63) / 64);
-  hipLaunchKernelGGL(nt_gemm_partial<true>, grid, dim3(256), 0, stream, L, rank, R, t, n, chunk, Wp);
-  hipLaunchKernelGGL(small_solve, dim3(1), dim3(256), (size_t)rank * t * sizeof(float), stream, Wp, chunks, rank,
-                     t, Minv_dev, Y);
+  dim3 grid(chunks, (rank + 127) / 128, (t + 31) / 32);
+  hipLaunchKernelGGL(gram_partial, grid, dim3(256), 0, stream, L, rank, n, R, t, ld, n, chunk, Wp,
+                     (int)((n & 3) == 0 && (reinterpret_cast<uintptr_t>(L) & 15) == 0), (int)((ld & 3) == 0));
+  hipLaunchKernelGGL(reduce_chunks, dim3((rank * t + 255) / 256), dim3(256), 0, stream, Wp, chunks, rank * t, Wd);
+  hipLaunchKernelGGL(small_matmul, dim3((rank * t + 255) / 256), dim3(256), 0, stream, Minv_dev, Wd, rank, t, Y);
   const int blocks = precond_apply_blocks(n);
   const size_t shb = ((size_t)rank * t + 4 * t) * sizeof(float);
   const float inv_noise = 1.0f / noise;
   if (t <= 16)
-    hipLaunchKernelGGL(woodbury_finish<16>, dim3(blocks), dim3(256), shb, stream, L, rank, n, Y, R, t, inv_noise,
-                       Z, rz_partial);
+    hipLaunchKernelGGL(woodbury_finish_cm<16>, dim3(blocks), dim3(256), shb, stream, L, rank, n, n, Y, R, ld, t,
+                       inv_noise, Z, rz_part, part_ld);
   else if (t <= 17)
-    hipLaunchKernelGGL(woodbury_finish<17>, dim3(blocks), dim3(256), shb, stream, L, rank, n, Y, R, t, inv_noise,
-                       Z, rz_partial);
+    hipLaunchKernelGGL(woodbury_finish_cm<17>, dim3(blocks), dim3(256), shb, stream, L, rank, n, n, Y, R, ld, t,
+                       inv_noise, Z, rz_part, part_ld);
   else
-    hipLaunchKernelGGL(woodbury_finish<33>, dim3(blocks), dim3(256), shb, stream, L, rank, n, Y, R, t, inv_noise,
-                       Z, rz_partial);
+    hipLaunchKernelGGL(woodbury_finish_cm<33>, dim3(blocks), dim3(256), shb, stream, L, rank, n, n, Y, R, ld, t,
+                       inv_noise, Z, rz_part, part_ld);
+  EGP_HIP(hipGetLastError());
+  return EGP_OK;
+}
+
+// Row-major entry (egp_precond_apply, egp_mll): transpose in, apply, transpose out.
+int precond_apply_core(const float* L, int rank, const float* Minv_dev, int64_t n, float noise, const float* R,
+                       int t, float* Z, float* rz_partial, void* ws, hipStream_t stream) {
+  (void)rz_partial;
+  int64_t chunk;
+  const int chunks = chunks_for(n, &chunk);
+  const int64_t ld = padded_points(n);
+  char* w = static_cast<char*>(ws);
+  w += round_up((size_t)chunks * rank * t * sizeof(float), 256) + 2 * round_up((size_t)rank * t * sizeof(float), 256);
+  float* Rc = reinterpret_cast<float*>(w);
+  float* Zc = reinterpret_cast<float*>(w + round_up((size_t)ld * t * sizeof(float), 256));
+  launch_to_colmajor(R, n, t, ld, Rc, stream);
+  const int rc = precond_apply_cm(L, rank, Minv_dev, n, noise, Rc, ld, t, Zc, nullptr, 0, ws, stream);
+  if (rc != EGP_OK) return rc;
+  launch_to_rowmajor(Zc, n, t, ld, Z, stream);
   EGP_HIP(hipGetLastError());
   return EGP_OK;
 }
@@ -452,9 +511,10 @@ int pivchol_core(const float* X, int64_t n, const egp_hyper_t* h, float tol_abs,
   }
   EGP_HIP(hipMemcpyAsync(P->pivots, st.pivots, sizeof(int) * rank, hipMemcpyDeviceToHost, stream));
   // Gram matrix of the factor's columns
-  dim3 grid(chunks, (rank + 63) / 64, (rank + 63) / 64);
-  hipLaunchKernelGGL(nt_gemm_partial<false>, grid, dim3(256), 0, stream, P->L, rank, P->L, rank, n, chunk, Gp);
-  hipLaunchKernelGGL(sum_chunks, dim3((rank * rank + 255) / 256), dim3(256), 0, stream, Gp, chunks, rank * rank,
+  dim3 grid(chunks, (rank + 127) / 128, (rank + 31) / 32);
+  const int vec = (int)((n & 3) == 0);
+  hipLaunchKernelGGL(gram_partial, grid, dim3(256), 0, stream, P->L, rank, n, P->L, rank, n, n, chunk, Gp, vec, vec);
+  hipLaunchKernelGGL(reduce_chunks, dim3((rank * rank + 255) / 256), dim3(256), 0, stream, Gp, chunks, rank * rank,
                      Gd);
   EGP_HIP(hipGetLastError());
   std::vector<float> Gh((size_t)rank * rank);
