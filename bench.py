@@ -156,7 +156,7 @@ def main():
         lib.egp_profile_enable(0)
         t = 17
         k = P.rank
-        vec_bytes = 11 * n * t * 4          # dot: 2nt; update: 4nt read + 2nt write; direction: 2nt read + nt write
+        vec_bytes = 9 * n * t * 4           # update: 4nt read + 2nt write; direction: 2nt read + nt write (d.Kd is fused into the multiply's epilogue)
         pre_bytes = (2 * n * k + 3 * n * t) * 4   # L twice, R twice, Z once
         pc_bytes = sum(n * (4 * 3 + m + 1 + 2) * 4 for m in range(k))   # packed points, L[:m], new column, diag r/w
         result["mbcg"] = {

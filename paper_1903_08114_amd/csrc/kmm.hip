@@ -75,12 +75,16 @@ __global__ __launch_bounds__(256) void col_sum_partial(const float* __restrict__
   }
 }
 
-__global__ __launch_bounds__(64) void col_mean_final(const float* __restrict__ partial, int blocks,
-                                                     int64_t n, int d, float* __restrict__ mean) {
-  if ((int)threadIdx.x < d) {
+// mean[f] = (sum of the per-block partial sums) / n: one wave per feature, lanes stride the blocks.
+__global__ __launch_bounds__(256) void col_mean_final(const float* __restrict__ partial, int blocks,
+                                                      int64_t n, int d, float* __restrict__ mean) {
+  const int lane = threadIdx.x & 63;
+  for (int f = threadIdx.x >> 6; f < d; f += 4) {
     double s = 0.0;
-    for (int b = 0; b < blocks; ++b) s += (double)partial[b * 64 + threadIdx.x];
-    mean[threadIdx.x] = (float)(s / (double)n);
+    for (int b = lane; b < blocks; b += 64) s += (double)partial[b * 64 + f];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
+    if (lane == 0) mean[f] = (float)(s / (double)n);
   }
 }
 
@@ -449,7 +453,7 @@ int prepare_points(const float* X, int64_t n, const egp_hyper_t* h, void* ws, Pr
 
   ProfScope prof(kProfPack, stream);
   hipLaunchKernelGGL(col_sum_partial, dim3(kMeanBlocks), dim3(256), 0, stream, X, n, d, partial);
-  hipLaunchKernelGGL(col_mean_final, dim3(1), dim3(64), 0, stream, partial, kMeanBlocks, n, d, mean);
+  hipLaunchKernelGGL(col_mean_final, dim3(1), dim3(256), 0, stream, partial, kMeanBlocks, n, d, mean);
   hipLaunchKernelGGL(pack_points, dim3((unsigned)((npad + 255) / 256)), dim3(256), 0, stream, X, n, npad, d,
                      ks, mean, sc, out->Xp, out->nrm);
   EGP_HIP(hipGetLastError());

@@ -157,114 +157,118 @@ __global__ __launch_bounds__(256) void pc_step(const float* __restrict__ Xp, int
   }
 }
 
-// ---- C[a][b] = sum_i A[a][i] * B[b][i] over a chunk of i (both operands contiguous in i) ----
-// Block tile 128 (a) x 32 (b), 256 threads each 8 x 2 outputs, 32 points per LDS step. Partial results go to
-// Cp[chunk][ra][rb]; reduce_chunks sums chunks in a fixed order.
-__global__ __launch_bounds__(256) void gram_partial(const float* __restrict__ A, int ra, int64_t lda,
-                                                    const float* __restrict__ B, int rb, int64_t ldb, int64_t n,
-                                                    int64_t chunk, float* __restrict__ Cp, int vecA, int vecB) {
-  __shared__ float As[32][128 + 4];
-  __shared__ float Bs[32][32 + 4];
-  const int ta = blockIdx.y * 128, tb = blockIdx.z * 32;
-  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
-  const int64_t i_begin = (int64_t)blockIdx.x * chunk;
-  int64_t i_end = i_begin + chunk;
-  if (i_end > n) i_end = n;
-  float acc[8][2] = {};
-  for (int64_t i0 = i_begin; i0 < i_end; i0 += 32) {
-    // 128 rows x 32 points of A: 1024 float4, 4 per thread; row a = e / 8, points 4 (e % 8) .. +3
+// ---- C[a][b] = sum_i A[a][i] * B[b][i] (both operands contiguous in i) on the fp32 MFMA ----
+// grid = (blocks, ceil(ra/128), ceil(rb/32)), 4 waves per block; a wave owns 8 x 2 output tiles of 16 x 16
+// and walks groups of 16 points: lane (q,p) loads points 16 g + 4 q .. + 3 of row p of each operand tile
+// (one 16-byte load) and feeds component s to MFMA step s. Both operands use the same point-to-step map, so
+// the pairing is consistent; the order of a sum is free. Every wave writes its own partial result
+// Cp[4 * block + wave][ra][rb]; reduce_chunks sums them in a fixed order.
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ f4 load4_guarded(const float* __restrict__ row, int64_t i, int64_t n, int vec) {
+  f4 v = {0.f, 0.f, 0.f, 0.f};
+  if (vec && i + 3 < n) return *reinterpret_cast<const f4*>(row + i);
+  if (i + 0 < n) v.x = row[i + 0];
+  if (i + 1 < n) v.y = row[i + 1];
+  if (i + 2 < n) v.z = row[i + 2];
+  if (i + 3 < n) v.w = row[i + 3];
+  return v;
+}
+
+__global__ __launch_bounds__(256) void gram_mfma(const float* __restrict__ A, int ra, int64_t lda,
+                                                 const float* __restrict__ B, int rb, int64_t ldb, int64_t n,
+                                                 float* __restrict__ Cp, int vecA, int vecB) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int q = lane >> 4, p = lane & 15;
+  const int a_base = blockIdx.y * 128, b_base = blockIdx.z * 32;
+  int nta = (ra - a_base + 15) / 16;
+  if (nta > 8) nta = 8;
+  int ntb = (rb - b_base + 15) / 16;
+  if (ntb > 2) ntb = 2;
+  f4 acc[8][2];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const int e = threadIdx.x + k * 256;
-      const int a = e >> 3, i4 = (e & 7) * 4;
-      float4 v = {0.f, 0.f, 0.f, 0.f};
-      const int64_t i = i0 + i4;
-      if (ta + a < ra) {
-        const float* src = A + (int64_t)(ta + a) * lda + i;
-        if (vecA && i + 3 < i_end) v = *reinterpret_cast<const float4*>(src);
-        else {
-          if (i + 0 < i_end) v.x = src[0];
-          if (i + 1 < i_end) v.y = src[1];
-          if (i + 2 < i_end) v.z = src[2];
-          if (i + 3 < i_end) v.w = src[3];
+  for (int ta = 0; ta < 8; ++ta)
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) acc[ta][tb] = (f4){0.f, 0.f, 0.f, 0.f};
+  const int64_t groups = (n + 15) / 16;
+  for (int64_t g = (int64_t)blockIdx.x * 4 + wave; g < groups; g += (int64_t)gridDim.x * 4) {
+    const int64_t i = g * 16 + q * 4;
+    f4 av[8], bv[2];
+#pragma unroll
+    for (int ta = 0; ta < 8; ++ta) {
+      const int row = a_base + ta * 16 + p;
+      av[ta] = (ta < nta && row < ra) ? load4_guarded(A + (int64_t)row * lda, i, n, vecA) : (f4){0.f, 0.f, 0.f, 0.f};
+    }
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+      const int row = b_base + tb * 16 + p;
+      bv[tb] = (tb < ntb && row < rb) ? load4_guarded(B + (int64_t)row * ldb, i, n, vecB) : (f4){0.f, 0.f, 0.f, 0.f};
+    }
+#pragma unroll
+    for (int ta = 0; ta < 8; ++ta) {
+      if (ta < nta) {
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) {
+          if (tb < ntb) {
+            acc[ta][tb] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[ta].x, bv[tb].x, acc[ta][tb], 0, 0, 0);
+            acc[ta][tb] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[ta].y, bv[tb].y, acc[ta][tb], 0, 0, 0);
+            acc[ta][tb] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[ta].z, bv[tb].z, acc[ta][tb], 0, 0, 0);
+            acc[ta][tb] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[ta].w, bv[tb].w, acc[ta][tb], 0, 0, 0);
+          }
         }
       }
-      As[i4 + 0][a] = v.x; As[i4 + 1][a] = v.y; As[i4 + 2][a] = v.z; As[i4 + 3][a] = v.w;
     }
-    {
-      const int e = threadIdx.x;            // 32 rows x 32 points of B: 256 float4
-      const int bb = e >> 3, i4 = (e & 7) * 4;
-      float4 v = {0.f, 0.f, 0.f, 0.f};
-      const int64_t i = i0 + i4;
-      if (tb + bb < rb) {
-        const float* src = B + (int64_t)(tb + bb) * ldb + i;
-        if (vecB && i + 3 < i_end) v = *reinterpret_cast<const float4*>(src);
-        else {
-          if (i + 0 < i_end) v.x = src[0];
-          if (i + 1 < i_end) v.y = src[1];
-          if (i + 2 < i_end) v.z = src[2];
-          if (i + 3 < i_end) v.w = src[3];
-        }
-      }
-      Bs[i4 + 0][bb] = v.x; Bs[i4 + 1][bb] = v.y; Bs[i4 + 2][bb] = v.z; Bs[i4 + 3][bb] = v.w;
-    }
-    __syncthreads();
-#pragma unroll 8
-    for (int ii = 0; ii < 32; ++ii) {
-      const float4 a0 = *reinterpret_cast<const float4*>(&As[ii][ty * 8]);
-      const float4 a1 = *reinterpret_cast<const float4*>(&As[ii][ty * 8 + 4]);
-      const float2 bv = *reinterpret_cast<const float2*>(&Bs[ii][tx * 2]);
-      const float av[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        acc[u][0] = __builtin_fmaf(av[u], bv.x, acc[u][0]);
-        acc[u][1] = __builtin_fmaf(av[u], bv.y, acc[u][1]);
-      }
-    }
-    __syncthreads();
   }
-  float* dst = Cp + (int64_t)blockIdx.x * ra * rb;
+  // accumulator layout: register r of lane (q,p) is C[16 ta + 4 q + r][16 tb + p]
+  float* dst = Cp + ((int64_t)blockIdx.x * 4 + wave) * ra * rb;
 #pragma unroll
-  for (int u = 0; u < 8; ++u)
+  for (int ta = 0; ta < 8; ++ta)
 #pragma unroll
-    for (int v = 0; v < 2; ++v) {
-      const int a = ta + ty * 8 + u, b = tb + tx * 2 + v;
-      if (a < ra && b < rb) dst[a * rb + b] = acc[u][v];
+    for (int tb = 0; tb < 2; ++tb) {
+      const float vals[4] = {acc[ta][tb].x, acc[ta][tb].y, acc[ta][tb].z, acc[ta][tb].w};
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int a = a_base + ta * 16 + q * 4 + r, bcol = b_base + tb * 16 + p;
+        if (ta < nta && tb < ntb && a < ra && bcol < rb) dst[a * rb + bcol] = vals[r];
+      }
     }
 }
 
+// C[e] = sum over chunks of Cp[chunk][e], fp64, fixed order: 64 lanes stride the chunks, then a shuffle tree.
+// Block = 4 outputs x 64 lanes.
 __global__ __launch_bounds__(256) void reduce_chunks(const float* __restrict__ Cp, int chunks, int count,
                                                      float* __restrict__ C) {
-  const int e = blockIdx.x * 256 + threadIdx.x;
-  if (e >= count) return;
+  const int e = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
   double s = 0.0;
-  for (int c = 0; c < chunks; ++c) s += (double)Cp[(int64_t)c * count + e];
-  C[e] = (float)s;
+  if (e < count)
+    for (int c = lane; c < chunks; c += 64) s += (double)Cp[(int64_t)c * count + e];
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
+  if (e < count && lane == 0) C[e] = (float)s;
 }
 
-// Y[m][c] = sum_m2 Minv[m][m2] * W[m2][c]   (k x k times k x t, one thread per output)
+// Y[m][c] = sum_m2 Minv[m][m2] * W[m2][c] for c < t, zero for t <= c < ldy (one thread per output)
 __global__ __launch_bounds__(256) void small_matmul(const float* __restrict__ Minv, const float* __restrict__ W,
-                                                    int k, int t, float* __restrict__ Y) {
+                                                    int k, int t, int ldy, float* __restrict__ Y) {
   const int e = blockIdx.x * 256 + threadIdx.x;
-  if (e >= k * t) return;
-  const int m = e / t, c = e % t;
+  if (e >= k * ldy) return;
+  const int m = e / ldy, c = e % ldy;
   float acc = 0.f;
-  for (int m2 = 0; m2 < k; ++m2) acc = __builtin_fmaf(Minv[m * k + m2], W[m2 * t + c], acc);
+  if (c < t)
+    for (int m2 = 0; m2 < k; ++m2) acc = __builtin_fmaf(Minv[m * k + m2], W[m2 * t + c], acc);
   Y[e] = acc;
 }
 
 // Column-major Woodbury finish: Z[c][i] = (R[c][i] - sum_m L[m][i] Y[m][c]) / noise for i < n; optional
-// per-block partial sums of R[c][i] Z[c][i] into rz_part[c][blockIdx]. One thread per point.
+// per-block partial sums of R[c][i] Z[c][i] into rz_part[c][blockIdx]. One thread per point; Y (k x TT,
+// zero-padded columns) is indexed uniformly across the wave, so its entries arrive as scalar operands.
 template <int TT>
 __global__ __launch_bounds__(256) void woodbury_finish_cm(const float* __restrict__ L, int k, int64_t n, int64_t ldl,
                                                           const float* __restrict__ Y, const float* __restrict__ R,
                                                           int64_t ld, int t, float inv_noise, float* __restrict__ Z,
                                                           float* __restrict__ rz_part, int part_ld) {
-  extern __shared__ float sh[];      // Y: k * t, then reduction scratch 4 * t
-  float* Ys = sh;
-  float* red = sh + k * t;
-  for (int e = threadIdx.x; e < k * t; e += 256) Ys[e] = Y[e];
-  __syncthreads();
+  __shared__ float red[4 * TT];
   float dot[TT];
 #pragma unroll
   for (int c = 0; c < TT; ++c) dot[c] = 0.f;
@@ -272,12 +276,25 @@ __global__ __launch_bounds__(256) void woodbury_finish_cm(const float* __restric
     float acc[TT];
 #pragma unroll
     for (int c = 0; c < TT; ++c) acc[c] = 0.f;
-    for (int m = 0; m < k; ++m) {
-      const float l = L[(int64_t)m * ldl + i];
-      const float* y = Ys + m * t;
+    const float* Li = L + i;
+    int m = 0;
+    for (; m + 4 <= k; m += 4) {
+      const float l0 = Li[(int64_t)(m + 0) * ldl], l1 = Li[(int64_t)(m + 1) * ldl];
+      const float l2 = Li[(int64_t)(m + 2) * ldl], l3 = Li[(int64_t)(m + 3) * ldl];
+      const float* y = Y + m * TT;
 #pragma unroll
-      for (int c = 0; c < TT; ++c)
-        if (c < t) acc[c] = __builtin_fmaf(l, y[c], acc[c]);
+      for (int c = 0; c < TT; ++c) {
+        acc[c] = __builtin_fmaf(l0, y[c], acc[c]);
+        acc[c] = __builtin_fmaf(l1, y[TT + c], acc[c]);
+        acc[c] = __builtin_fmaf(l2, y[2 * TT + c], acc[c]);
+        acc[c] = __builtin_fmaf(l3, y[3 * TT + c], acc[c]);
+      }
+    }
+    for (; m < k; ++m) {
+      const float l = Li[(int64_t)m * ldl];
+      const float* y = Y + m * TT;
+#pragma unroll
+      for (int c = 0; c < TT; ++c) acc[c] = __builtin_fmaf(l, y[c], acc[c]);
     }
 #pragma unroll
     for (int c = 0; c < TT; ++c)
@@ -291,17 +308,15 @@ __global__ __launch_bounds__(256) void woodbury_finish_cm(const float* __restric
   if (rz_part != nullptr) {
 #pragma unroll
     for (int c = 0; c < TT; ++c) {
-      if (c < t) {
-        float v = dot[c];
+      float v = dot[c];
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
-        if ((threadIdx.x & 63) == 0) red[(threadIdx.x >> 6) * t + c] = v;
-      }
+      for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+      if ((threadIdx.x & 63) == 0) red[(threadIdx.x >> 6) * TT + c] = v;
     }
     __syncthreads();
     if ((int)threadIdx.x < t)
       rz_part[(int64_t)threadIdx.x * part_ld + blockIdx.x] =
-          (red[threadIdx.x] + red[t + threadIdx.x]) + (red[2 * t + threadIdx.x] + red[3 * t + threadIdx.x]);
+          (red[threadIdx.x] + red[TT + threadIdx.x]) + (red[2 * TT + threadIdx.x] + red[3 * TT + threadIdx.x]);
   }
 }
 
@@ -324,11 +339,16 @@ __global__ __launch_bounds__(256) void to_rowmajor(const float* __restrict__ src
   }
 }
 
+// number of partial results the Gram kernel leaves: 4 waves per block, blocks sized to the point count
+int gram_blocks(int64_t n) {
+  int64_t b = (n / 16 + 4 * 16 - 1) / (4 * 16);     // at least 16 point groups per wave
+  if (b < 1) b = 1;
+  if (b > 1024) b = 1024;
+  return (int)b;
+}
 int chunks_for(int64_t n, int64_t* chunk_out) {
-  int64_t chunk = 2048;
-  while ((n + chunk - 1) / chunk > 512) chunk *= 2;
-  *chunk_out = chunk;
-  return (int)((n + chunk - 1) / chunk);
+  *chunk_out = 0;
+  return 4 * gram_blocks(n);
 }
 
 }  // namespace
@@ -349,7 +369,7 @@ size_t precond_apply_ws(int64_t n, int t, int rank) {
   int64_t chunk;
   const int chunks = chunks_for(n, &chunk);
   const int64_t ld = padded_points(n);
-  return round_up((size_t)chunks * rank * t * sizeof(float), 256) + 2 * round_up((size_t)rank * t * sizeof(float), 256) +
+  return round_up((size_t)chunks * rank * t * sizeof(float), 256) + 2 * round_up((size_t)rank * 33 * sizeof(float), 256) +
          2 * round_up((size_t)ld * t * sizeof(float), 256);   // the last two: transposes for the row-major entry point
 }
 
@@ -365,15 +385,17 @@ int precond_apply_cm(const float* L, int rank, const float* Minv_dev, int64_t n,
   float* Wp = reinterpret_cast<float*>(w);
   w += round_up((size_t)chunks * rank * t * sizeof(float), 256);
   float* Wd = reinterpret_cast<float*>(w);
-  w += round_up((size_t)rank * t * sizeof(float), 256);
+  w += round_up((size_t)rank * 33 * sizeof(float), 256);
   float* Y = reinterpret_cast<float*>(w);
-  dim3 grid(chunks, (rank + 127) / 128, (t + 31) / 32);
-  hipLaunchKernelGGL(gram_partial, grid, dim3(256), 0, stream, L, rank, n, R, t, ld, n, chunk, Wp,
+  dim3 grid(chunks / 4, (rank + 127) / 128, (t + 31) / 32);
+  hipLaunchKernelGGL(gram_mfma, grid, dim3(256), 0, stream, L, rank, n, R, t, ld, n, Wp,
                      (int)((n & 3) == 0 && (reinterpret_cast<uintptr_t>(L) & 15) == 0), (int)((ld & 3) == 0));
-  hipLaunchKernelGGL(reduce_chunks, dim3((rank * t + 255) / 256), dim3(256), 0, stream, Wp, chunks, rank * t, Wd);
-  hipLaunchKernelGGL(small_matmul, dim3((rank * t + 255) / 256), dim3(256), 0, stream, Minv_dev, Wd, rank, t, Y);
+  hipLaunchKernelGGL(reduce_chunks, dim3((rank * t + 3) / 4), dim3(256), 0, stream, Wp, chunks, rank * t, Wd);
+  const int ldy = t <= 16 ? 16 : (t <= 17 ? 17 : 33);
+  hipLaunchKernelGGL(small_matmul, dim3((rank * ldy + 255) / 256), dim3(256), 0, stream, Minv_dev, Wd, rank, t, ldy,
+                     Y);
   const int blocks = precond_apply_blocks(n);
-  const size_t shb = ((size_t)rank * t + 4 * t) * sizeof(float);
+  const size_t shb = 0;
   const float inv_noise = 1.0f / noise;
   if (t <= 16)
     hipLaunchKernelGGL(woodbury_finish_cm<16>, dim3(blocks), dim3(256), shb, stream, L, rank, n, n, Y, R, ld, t,
@@ -396,7 +418,7 @@ int precond_apply_core(const float* L, int rank, const float* Minv_dev, int64_t 
   const int chunks = chunks_for(n, &chunk);
   const int64_t ld = padded_points(n);
   char* w = static_cast<char*>(ws);
-  w += round_up((size_t)chunks * rank * t * sizeof(float), 256) + 2 * round_up((size_t)rank * t * sizeof(float), 256);
+  w += round_up((size_t)chunks * rank * t * sizeof(float), 256) + 2 * round_up((size_t)rank * 33 * sizeof(float), 256);
   float* Rc = reinterpret_cast<float*>(w);
   float* Zc = reinterpret_cast<float*>(w + round_up((size_t)ld * t * sizeof(float), 256));
   launch_to_colmajor(R, n, t, ld, Rc, stream);
@@ -511,11 +533,10 @@ int pivchol_core(const float* X, int64_t n, const egp_hyper_t* h, float tol_abs,
   }
   EGP_HIP(hipMemcpyAsync(P->pivots, st.pivots, sizeof(int) * rank, hipMemcpyDeviceToHost, stream));
   // Gram matrix of the factor's columns
-  dim3 grid(chunks, (rank + 127) / 128, (rank + 31) / 32);
-  const int vec = (int)((n & 3) == 0);
-  hipLaunchKernelGGL(gram_partial, grid, dim3(256), 0, stream, P->L, rank, n, P->L, rank, n, n, chunk, Gp, vec, vec);
-  hipLaunchKernelGGL(reduce_chunks, dim3((rank * rank + 255) / 256), dim3(256), 0, stream, Gp, chunks, rank * rank,
-                     Gd);
+  dim3 grid(chunks / 4, (rank + 127) / 128, (rank + 31) / 32);
+  const int vec = (int)((n & 3) == 0 && (reinterpret_cast<uintptr_t>(P->L) & 15) == 0);
+  hipLaunchKernelGGL(gram_mfma, grid, dim3(256), 0, stream, P->L, rank, n, P->L, rank, n, n, Gp, vec, vec);
+  hipLaunchKernelGGL(reduce_chunks, dim3((rank * rank + 3) / 4), dim3(256), 0, stream, Gp, chunks, rank * rank, Gd);
   EGP_HIP(hipGetLastError());
   std::vector<float> Gh((size_t)rank * rank);
   EGP_HIP(hipMemcpyAsync(Gh.data(), Gd, sizeof(float) * rank * rank, hipMemcpyDeviceToHost, stream));
