@@ -86,6 +86,17 @@ int egp_kmm_grad(const float* X, int64_t n, const float* V, int32_t t, const egp
                  float* dout /*device d x n x t*/, void* ws, size_t ws_bytes, void* stream);
 size_t egp_kmm_grad_ws_bytes(int64_t n, int32_t d, int32_t t);
 
+/* Bilinear forms with the kernel derivatives, without the d x n x t intermediate of egp_kmm_grad:
+ *   out[k] = sum_c w[c] A[:,c]^T (dK/dl_k) B[:,c]   for k = 0..d-1,
+ *   out[d] = sum_c w[c] A[:,c]^T K B[:,c] / outputscale         (the outputscale derivative of K),
+ * which is what every term of the marginal-likelihood gradient is (paper, Eq. 2: A = B = Khat^{-1} y for the
+ * data term; A = Khat^{-1} z_c, B = P^{-1} z_c for the probe estimate of the trace).
+ *   A, B  device n x t row-major, t in 1..36;  w host, t weights (NULL = all ones);  out host, d + 1 doubles.
+ * Synchronises on `stream`. */
+int egp_kmm_grad_bilinear(const float* X, int64_t n, const float* A, const float* B, int32_t t, const float* w,
+                          const egp_hyper_t* h, double* out, void* ws, size_t ws_bytes, void* stream);
+size_t egp_kmm_grad_bilinear_ws_bytes(int64_t n, int32_t d, int32_t t);
+
 /* Partial pivoted Cholesky of the noise-free K from `rank` kernel rows computed on the fly (paper,
  * Method, "Preconditioning": a rank-k preconditioner needs only k kernel rows and is built once
  * before CG). Greedy diagonal pivoting, ties to the lowest index; stops early when the largest

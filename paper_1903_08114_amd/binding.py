@@ -64,6 +64,12 @@ def lib():
                                C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int32),
                                C.POINTER(C.c_float), C.POINTER(C.c_float), C.c_void_p, C.c_size_t, C.c_void_p]
         L.egp_kmm_ws_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32]
+        L.egp_kmm_grad_bilinear_ws_bytes.restype = C.c_size_t
+        L.egp_kmm_grad_bilinear_ws_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32]
+        L.egp_kmm_grad_bilinear.restype = C.c_int
+        L.egp_kmm_grad_bilinear.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int32,
+                                            C.POINTER(C.c_float), C.POINTER(_Hyper), C.POINTER(C.c_double),
+                                            C.c_void_p, C.c_size_t, C.c_void_p]
         L.egp_mll_ws_bytes.restype = C.c_size_t
         L.egp_mll_ws_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
         L.egp_mll.restype = C.c_int
@@ -187,6 +193,28 @@ def kmm_grad(X, V, lengthscales, outputscale, noise, kernel_type, out=None, ws=N
         ws = _workspace(need, X.device)
     _check(L.egp_kmm_grad(_dev(X, "X"), n, _dev(V, "V"), t, C.byref(h), _dev(out, "dout"),
                           C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
+    return out
+
+
+def kmm_grad_bilinear(X, A, B, lengthscales, outputscale, noise, kernel_type, weights=None, ws=None):
+    """sum_c w_c A[:,c]^T (dK/dl_k) B[:,c] for every lengthscale, then sum_c w_c A[:,c]^T K B[:,c] / outputscale
+    (egp_kmm_grad_bilinear). Returns a float64 array of d + 1 values."""
+    import numpy as np
+    L = lib()
+    n, d = X.shape
+    t = A.shape[1]
+    h = _hyper(kernel_type, lengthscales, outputscale, noise)
+    need = L.egp_kmm_grad_bilinear_ws_bytes(n, d, t)
+    if ws is None:
+        ws = _workspace(need, X.device)
+    out = np.zeros(d + 1, dtype=np.float64)
+    wp = None
+    if weights is not None:
+        warr = (C.c_float * t)(*[float(v) for v in weights])
+        wp = C.cast(warr, C.POINTER(C.c_float))
+    _check(L.egp_kmm_grad_bilinear(_dev(X, "X"), n, _dev(A, "A"), _dev(B, "B"), t, wp, C.byref(h),
+                                   out.ctypes.data_as(C.POINTER(C.c_double)), C.c_void_p(ws.data_ptr()),
+                                   ws.numel(), _stream()))
     return out
 
 

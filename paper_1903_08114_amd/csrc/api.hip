@@ -183,6 +183,30 @@ int egp_kmm_grad(const float* X, int64_t n, const float* V, int32_t t, const egp
 
 static int check_n(int64_t n);
 
+size_t egp_kmm_grad_bilinear_ws_bytes(int64_t n, int32_t d, int32_t t) {
+  if (n < 1 || d < 1 || d > EGP_D_MAX || t < 1 || t > 36) return 0;
+  return prepared_bytes(n, d) + bilinear_core_ws_bytes(n, d, t);
+}
+
+int egp_kmm_grad_bilinear(const float* X, int64_t n, const float* A, const float* B, int32_t t, const float* w,
+                          const egp_hyper_t* h, double* out, void* ws, size_t ws_bytes, void* stream) {
+  int rc;
+  if ((rc = validate_hyper(h)) != EGP_OK) return rc;
+  if ((rc = check_n(n)) != EGP_OK) return rc;
+  if (t < 1 || t > 36) return fail(EGP_ERR_ARG, "t = %d outside 1..36", t);
+  if (out == nullptr) return fail(EGP_ERR_ARG, "out is NULL");
+  if ((rc = validate_ptr(X, "X")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(A, "A")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(B, "B")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(ws, "ws")) != EGP_OK) return rc;
+  const size_t need = egp_kmm_grad_bilinear_ws_bytes(n, h->d, t);
+  if (ws_bytes < need) return fail(EGP_ERR_WS, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, need);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  Prepared P;
+  if ((rc = prepare_points(X, n, h, ws, &P, s)) != EGP_OK) return rc;
+  return bilinear_core(P, h, A, B, t, w, out, static_cast<char*>(ws) + prepared_bytes(n, h->d), s);
+}
+
 size_t egp_mll_ws_bytes(int64_t n, int32_t d, int32_t tp, int32_t rank, int32_t max_iter) {
   if (n < 1 || d < 1 || d > EGP_D_MAX || tp < 1 || tp > 32 || rank < 0 || rank > EGP_RANK_MAX || max_iter < 1)
     return 0;

@@ -52,6 +52,9 @@ void launch_pack_rhs(const float* V, int64_t n, int64_t npad, int t, int c0, int
 size_t kmm_grad_core_ws_bytes(int64_t n, int d, int t);
 int kmm_grad_core(const Prepared& P, const egp_hyper_t* h, const float* V, int t, float* dout, void* ws2,
                   hipStream_t stream);
+size_t bilinear_core_ws_bytes(int64_t n, int d, int t);
+int bilinear_core(const Prepared& P, const egp_hyper_t* h, const float* A, const float* B, int t, const float* wcol,
+                  double* out, void* ws2, hipStream_t stream);
 size_t pivchol_ws_bytes(int64_t n, int d, int rank);
 int pivchol_core(const float* X, int64_t n, const egp_hyper_t* h, float tol_abs, egp_precond_t* P, void* ws,
                  hipStream_t stream);

@@ -154,7 +154,7 @@ bool tridiag_log_quadrature(std::vector<double> a, std::vector<double> b, double
 namespace {
 
 struct MllWs {
-  size_t prep, Lbuf, small_dev, B, U, Vp, Zp, dout, KV, part, sub, total;
+  size_t prep, Lbuf, small_dev, B, U, Vp, Zp, part, sub, total;
 };
 
 MllWs mll_layout(int64_t n, int d, int tp, int rank, int max_iter) {
@@ -168,20 +168,18 @@ MllWs mll_layout(int64_t n, int d, int tp, int rank, int max_iter) {
   w.U = vec;
   w.Vp = vec;
   w.Zp = vec;
-  w.dout = round_up((size_t)d * n * t * sizeof(float), 256);
-  w.KV = vec;
   w.part = round_up((size_t)kDotBlocks * 64 * sizeof(float), 256);
   size_t sub = mbcg_ws_bytes_core(n, d, t, rank, max_iter);
   const size_t pc = rank > 0 ? pivchol_ws_bytes(n, d, rank) : 0;
-  const size_t kg = prepared_bytes(n, d) + kmm_grad_core_ws_bytes(n, d, t);
-  const size_t km = prepared_bytes(n, d) + kmm_core_ws_bytes(n, t);
+  const size_t kg = bilinear_core_ws_bytes(n, d, t);
+  const size_t km = 0;
   const size_t pa = rank > 0 ? precond_apply_ws(n, t, rank) : 0;
   if (pc > sub) sub = pc;
   if (kg > sub) sub = kg;
   if (km > sub) sub = km;
   if (pa > sub) sub = pa;
   w.sub = round_up(sub, 256);
-  w.total = w.prep + w.Lbuf + w.small_dev + w.B + w.U + w.Vp + w.Zp + w.dout + w.KV + w.part + w.sub;
+  w.total = w.prep + w.Lbuf + w.small_dev + w.B + w.U + w.Vp + w.Zp + w.part + w.sub;
   return w;
 }
 
@@ -204,8 +202,6 @@ int mll_core(const float* X, int64_t n, const float* y, const float* W1, const f
   float* U = (float*)w;         w += lay.U;
   float* Vp = (float*)w;        w += lay.Vp;
   float* Zp = (float*)w;        w += lay.Zp;
-  float* dout = (float*)w;      w += lay.dout;
-  float* KV = (float*)w;        w += lay.KV;
   float* part = (float*)w;      w += lay.part;
   void* sub = w;
 
@@ -299,37 +295,23 @@ int mll_core(const float* X, int64_t n, const float* y, const float* W1, const f
   res->quad = dots[0];
   res->mll = -0.5 * res->quad - 0.5 * res->logdet - 0.5 * (double)n * log(2.0 * M_PI);
 
-  auto combine = [&](const std::vector<double>& g) {
-    double tr = 0.0;
-    for (int c = 1; c < t; ++c) tr += g[c];
-    tr = tp > 0 ? tr / tp : 0.0;
-    return 0.5 * g[0] - 0.5 * tr;
-  };
-
-  // ---- lengthscales: (dK/dl_k) V' ----
+  // ---- gradient: every term is a bilinear form with weights +1/2 (data term) and -1/(2 tp) (probes) ----
+  std::vector<float> wcol(t);
+  wcol[0] = 0.5f;
+  for (int c = 1; c < t; ++c) wcol[c] = -0.5f / (float)tp;
   Prepared prep;
   rc = prepare_points(X, n, h, prep_ws, &prep, stream);
   if (rc != EGP_OK) return rc;
-  rc = kmm_grad_core(prep, h, Vp, t, dout, sub, stream);
+  std::vector<double> forms(d + 1, 0.0);
+  rc = bilinear_core(prep, h, U, Vp, t, wcol.data(), forms.data(), sub, stream);
   if (rc != EGP_OK) return rc;
-  for (int k = 0; k < d; ++k) {
-    rc = column_dots(U, dout + (size_t)k * n * t, n, t, part, &dots, stream);
-    if (rc != EGP_OK) return rc;
-    res->grad[k] = combine(dots);
-  }
-  // ---- outputscale: dKhat/ds = K / s ----
-  Prepared noiseless = prep;
-  noiseless.noise = 0.f;
-  rc = kmm_core(noiseless, Vp, t, KV, sub, stream);
-  if (rc != EGP_OK) return rc;
-  rc = column_dots(U, KV, n, t, part, &dots, stream);
-  if (rc != EGP_OK) return rc;
-  for (int c = 0; c < t; ++c) dots[c] /= (double)h->outputscale;
-  res->grad[d] = combine(dots);
+  for (int k = 0; k <= d; ++k) res->grad[k] = forms[k];      // lengthscales, then outputscale (dKhat/ds = K / s)
   // ---- noise: dKhat/dnoise = I ----
   rc = column_dots(U, Vp, n, t, part, &dots, stream);
   if (rc != EGP_OK) return rc;
-  res->grad[d + 1] = combine(dots);
+  double gn = 0.0;
+  for (int c = 0; c < t; ++c) gn += (double)wcol[c] * dots[c];
+  res->grad[d + 1] = gn;
   for (int k = d + 2; k < EGP_D_MAX + 2; ++k) res->grad[k] = 0.0;
   return EGP_OK;
 }
