@@ -45,7 +45,7 @@ typedef enum {
  *   MATERN52  g = (1 + sqrt5 r + 5 r^2/3) exp(-sqrt5 r)                                             */
 typedef enum { EGP_RBF = 0, EGP_MATERN32 = 1, EGP_MATERN52 = 2 } egp_kernel_t;
 
-#define EGP_D_MAX 63     /* largest input dimension */
+#define EGP_D_MAX 31     /* largest input dimension (d + 1 feature slots fill at most 8 MFMA k-steps) */
 #define EGP_T_MAX 1024   /* largest number of right-hand-side columns */
 #define EGP_RANK_MAX 256 /* largest preconditioner rank */
 

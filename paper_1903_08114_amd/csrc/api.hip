@@ -39,8 +39,6 @@ int validate_hyper(const egp_hyper_t* h) {
   if (!(h->outputscale > 0.f) || !std::isfinite(h->outputscale))
     return fail(EGP_ERR_ARG, "outputscale must be positive and finite");
   if (!(h->noise >= 0.f) || !std::isfinite(h->noise)) return fail(EGP_ERR_ARG, "noise must be >= 0 and finite");
-  if (ksteps_for(h->d) > 8)
-    return fail(EGP_ERR_ARG, "d = %d: this build's fused kernel supports d <= 31", h->d);
   return EGP_OK;
 }
 

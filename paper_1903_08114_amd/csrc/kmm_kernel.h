@@ -1,0 +1,272 @@
+// The fused kernel-matrix-multiply kernel template and its launch plumbing, shared by the translation
+// units that instantiate it (kmm.hip: d <= 31, kmm_wide.hip: 32 <= d <= 63).
+#pragma once
+
+#include "egp_internal.h"
+
+namespace egp {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+template <int KIND>
+__device__ __forceinline__ float transform(float acc) {
+  if constexpr (KIND == EGP_RBF) {
+    return __builtin_amdgcn_exp2f(-acc);
+  } else if constexpr (KIND == EGP_MATERN32) {
+    float a = __builtin_amdgcn_sqrtf(__builtin_fabsf(acc));
+    return __builtin_fmaf(a, kLn2, 1.0f) * __builtin_amdgcn_exp2f(-a);
+  } else {
+    float a = __builtin_amdgcn_sqrtf(__builtin_fabsf(acc));
+    float poly = __builtin_fmaf(__builtin_fmaf(a, kLn2 * kLn2 / 3.0f, kLn2), a, 1.0f);
+    return poly * __builtin_amdgcn_exp2f(-a);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// The fused kernel.
+//   grid.x = row blocks (4 waves x R row tiles x 16 rows), grid.y = column splits
+//   block  = 256 threads; each wave owns R row tiles for the whole column sweep of its split
+//   LDS    = double-buffered stage of JT column tiles: packed points, packed V, extra column
+//   Part   = [split][npad][TS] raw accumulators (TS = 16 NB + EXTRA); the epilogue kernel reduces
+//            splits in a fixed order, scales by the outputscale and adds noise * V.
+// ------------------------------------------------------------------------------------------------
+template <int KS, int R, int KIND, int NB, int EXTRA, int JT>
+__global__ __launch_bounds__(256, 2) void kmm_kernel(const float* __restrict__ Xp,
+                                                     const float* __restrict__ nrm,
+                                                     const f4* __restrict__ Vp,
+                                                     const float* __restrict__ Ep,
+                                                     float* __restrict__ Part, int64_t npad, int d,
+                                                     int stages_per_split, int stages_total, int cm) {
+  constexpr int TS = 16 * NB + EXTRA;
+  constexpr int XF4 = JT * KS * 16;       // f4 elements of packed points per stage
+  constexpr int VF4 = JT * NB * 64;       // f4 elements of packed V per stage
+  constexpr int EF4 = JT * 4;             // f4 elements of the extra column per stage
+  constexpr int NX = (XF4 + 255) / 256;
+  constexpr int NV = (VF4 + 255) / 256;
+
+  __shared__ f4 Xs[2][XF4];
+  __shared__ f4 Vs[2][VF4];
+  __shared__ f4 Es[2][EXTRA ? EF4 : 1];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int q = lane >> 4, p = lane & 15;
+
+  // ---- resident row operands ----
+  const int64_t row_tile0 = ((int64_t)blockIdx.x * 4 + wave) * R;
+  float b[R][KS];
+  f4 cq[R];
+  f4 o[R][NB];
+  float eacc[R];
+  const int ds = d >> 2, dq = d & 3;
+#pragma unroll
+  for (int it = 0; it < R; ++it) {
+    const float* src = Xp + (row_tile0 + it) * KS * 64 + lane;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      float v = -2.0f * src[s * 64];
+      if (s == ds && q == dq) v = 1.0f;     // the slot that multiplies the column point's norm
+      b[it][s] = v;
+    }
+    const float ni = nrm[(row_tile0 + it) * 16 + p];
+    cq[it] = (f4){ni, ni, ni, ni};
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) o[it][nb] = (f4){0.f, 0.f, 0.f, 0.f};
+    eacc[it] = 0.f;
+  }
+
+  const int st_begin = blockIdx.y * stages_per_split;
+  int st_end = st_begin + stages_per_split;
+  if (st_end > stages_total) st_end = stages_total;
+
+  const f4* Xg = reinterpret_cast<const f4*>(Xp);
+  const f4* Eg = reinterpret_cast<const f4*>(Ep);
+  f4 px[NX], pv[NV], pe;
+
+  auto fetch = [&](int st) {
+    const int64_t xoff = (int64_t)st * XF4, voff = (int64_t)st * VF4, eoff = (int64_t)st * EF4;
+#pragma unroll
+    for (int k = 0; k < NX; ++k) {
+      const int idx = tid + k * 256;
+      if (XF4 % 256 == 0 || idx < XF4) px[k] = Xg[xoff + idx];
+    }
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      const int idx = tid + k * 256;
+      if (VF4 % 256 == 0 || idx < VF4) pv[k] = Vp[voff + idx];
+    }
+    if (EXTRA && tid < EF4) pe = Eg[eoff + tid];
+  };
+  auto stash = [&](int buf) {
+#pragma unroll
+    for (int k = 0; k < NX; ++k) {
+      const int idx = tid + k * 256;
+      if (XF4 % 256 == 0 || idx < XF4) Xs[buf][idx] = px[k];
+    }
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      const int idx = tid + k * 256;
+      if (VF4 % 256 == 0 || idx < VF4) Vs[buf][idx] = pv[k];
+    }
+    if (EXTRA && tid < EF4) Es[buf][tid] = pe;
+  };
+
+  if (st_begin < st_end) {
+    fetch(st_begin);
+    stash(0);
+  }
+  __syncthreads();
+
+  for (int st = st_begin; st < st_end; ++st) {
+    const int buf = (st - st_begin) & 1;
+    const bool more = st + 1 < st_end;
+    if (more) fetch(st + 1);
+
+    const float* xs = reinterpret_cast<const float*>(Xs[buf]);
+#pragma unroll 2
+    for (int jt = 0; jt < JT; ++jt) {
+      float a[KS];
+#pragma unroll
+      for (int s = 0; s < KS; ++s) a[s] = xs[(jt * KS + s) * 64 + lane];
+      f4 v[NB];
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) v[nb] = Vs[buf][(jt * NB + nb) * 64 + lane];
+      f4 e = {0.f, 0.f, 0.f, 0.f};
+      if (EXTRA) e = Es[buf][jt * 4 + q];
+#pragma unroll
+      for (int it = 0; it < R; ++it) {
+        f4 acc = cq[it];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s], b[it][s], acc, 0, 0, 0);
+        f4 k;
+        k.x = transform<KIND>(acc.x);
+        k.y = transform<KIND>(acc.y);
+        k.z = transform<KIND>(acc.z);
+        k.w = transform<KIND>(acc.w);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+          o[it][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(k.x, v[nb].x, o[it][nb], 0, 0, 0);
+          o[it][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(k.y, v[nb].y, o[it][nb], 0, 0, 0);
+          o[it][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(k.z, v[nb].z, o[it][nb], 0, 0, 0);
+          o[it][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(k.w, v[nb].w, o[it][nb], 0, 0, 0);
+        }
+        if (EXTRA) {
+          eacc[it] = __builtin_fmaf(k.x, e.x, eacc[it]);
+          eacc[it] = __builtin_fmaf(k.y, e.y, eacc[it]);
+          eacc[it] = __builtin_fmaf(k.z, e.z, eacc[it]);
+          eacc[it] = __builtin_fmaf(k.w, e.w, eacc[it]);
+        }
+      }
+    }
+    if (more) stash(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- write raw accumulators: lane (q,p), register r holds out[row 4q + r][column p] ----
+  float* dst = Part + (int64_t)blockIdx.y * npad * TS;
+  if (cm) {
+    // column-major partials [TS][npad]: the four rows of a lane are one 16-byte store
+#pragma unroll
+    for (int it = 0; it < R; ++it) {
+      const int64_t row0 = (row_tile0 + it) * 16;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+        *reinterpret_cast<f4*>(dst + (int64_t)(nb * 16 + p) * npad + row0 + q * 4) = o[it][nb];
+      if (EXTRA) {
+        float s = eacc[it];
+        s += __shfl_xor(s, 16);
+        s += __shfl_xor(s, 32);
+        if (q == 0) dst[(int64_t)(16 * NB) * npad + row0 + p] = s;
+      }
+    }
+    return;
+  }
+#pragma unroll
+  for (int it = 0; it < R; ++it) {
+    const int64_t row0 = (row_tile0 + it) * 16;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      float* r0 = dst + (row0 + q * 4) * TS + nb * 16 + p;
+      r0[0 * TS] = o[it][nb].x;
+      r0[1 * TS] = o[it][nb].y;
+      r0[2 * TS] = o[it][nb].z;
+      r0[3 * TS] = o[it][nb].w;
+    }
+    if (EXTRA) {
+      float s = eacc[it];
+      s += __shfl_xor(s, 16);
+      s += __shfl_xor(s, 32);
+      if (q == 0) dst[(row0 + p) * TS + 16 * NB] = s;
+    }
+  }
+}
+
+namespace kmm_detail {
+
+struct Plan {
+  bool big;
+  int splits, stages_per_split, stages_total, row_blocks;
+};
+
+// Launch shapes (row tiles per wave, column tiles per LDS stage). Up to 8 k-steps (d <= 31) the wide shape
+// keeps 8 row tiles per wave; beyond that the row operands (R * KS registers) allow 4.
+constexpr int kSmallR = 2, kSmallJT = 4;
+constexpr int big_r(int ks) { return ks <= 8 ? 8 : 4; }
+constexpr int big_jt(int ks) { return ks <= 8 ? 16 : 4; }
+
+inline Plan make_plan(int64_t npad, int ks) {
+  Plan pl;
+  const int64_t big_rows = 64 * big_r(ks);
+  pl.big = npad / big_rows >= 64;          // enough row blocks for the wide shape to be worthwhile
+  const int R = pl.big ? big_r(ks) : kSmallR, JT = pl.big ? big_jt(ks) : kSmallJT;
+  pl.row_blocks = (int)(npad / (64 * R));
+  pl.stages_total = (int)(npad / (16 * JT));
+  int want = 1024 / pl.row_blocks;
+  if (want < 1) want = 1;
+  if (want > pl.stages_total) want = pl.stages_total;
+  if (want > 64) want = 64;
+  pl.stages_per_split = (pl.stages_total + want - 1) / want;
+  pl.splits = (pl.stages_total + pl.stages_per_split - 1) / pl.stages_per_split;
+  return pl;
+}
+
+template <int KS, int KIND, int NB, int EXTRA>
+int launch_shape(const Prepared& P, const Plan& pl, const f4* Vp, const float* Ep, float* Part, int cm,
+                 hipStream_t stream) {
+  dim3 grid(pl.row_blocks, pl.splits), block(256);
+  if (pl.big) {
+    hipLaunchKernelGGL((kmm_kernel<KS, big_r(KS), KIND, NB, EXTRA, big_jt(KS)>), grid, block, 0, stream, P.Xp, P.nrm,
+                       Vp, Ep, Part, P.npad, P.d, pl.stages_per_split, pl.stages_total, cm);
+  } else {
+    hipLaunchKernelGGL((kmm_kernel<KS, kSmallR, KIND, NB, EXTRA, kSmallJT>), grid, block, 0, stream, P.Xp,
+                       P.nrm, Vp, Ep, Part, P.npad, P.d, pl.stages_per_split, pl.stages_total, cm);
+  }
+  EGP_HIP(hipGetLastError());
+  return EGP_OK;
+}
+
+template <int KS, int KIND>
+int launch_cols(const Prepared& P, const Plan& pl, int nb, int extra, const f4* Vp, const float* Ep,
+                float* Part, int cm, hipStream_t stream) {
+  if (nb == 1 && !extra) return launch_shape<KS, KIND, 1, 0>(P, pl, Vp, Ep, Part, cm, stream);
+  if (nb == 1 && extra) return launch_shape<KS, KIND, 1, 1>(P, pl, Vp, Ep, Part, cm, stream);
+  if (nb == 2 && !extra) return launch_shape<KS, KIND, 2, 0>(P, pl, Vp, Ep, Part, cm, stream);
+  return launch_shape<KS, KIND, 2, 1>(P, pl, Vp, Ep, Part, cm, stream);
+}
+
+template <int KS>
+int launch_kind(const Prepared& P, const Plan& pl, int nb, int extra, const f4* Vp, const float* Ep,
+                float* Part, int cm, hipStream_t stream) {
+  switch (P.kernel_type) {
+    case EGP_RBF: return launch_cols<KS, EGP_RBF>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case EGP_MATERN32: return launch_cols<KS, EGP_MATERN32>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    default: return launch_cols<KS, EGP_MATERN52>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
+  }
+}
+
+}  // namespace kmm_detail
+
+}  // namespace egp
