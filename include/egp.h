@@ -153,6 +153,32 @@ size_t egp_mll_ws_bytes(int64_t n, int32_t d, int32_t tp, int32_t rank, int32_t 
  * when T is not positive definite. */
 int egp_tridiag_logquad(const double* diag, const double* off, int32_t m, double* out);
 
+/* Prediction path (paper, Method "Predictions"; predictive mean and variance equations).
+ *
+ * egp_kmm_cross: out (nq x t) = K(Xq, X) V, the rectangular product between nq query points and the n
+ * training points (no noise term). V is n x t row-major. Asynchronous.
+ *
+ * egp_lanczos: training-data-dependent variance cache. r Lanczos steps on Khat with full
+ * re-orthogonalisation from the start vector b (e.g. y): Q (device, [r][n], orthonormal rows) and the
+ * tridiagonal T = Q Khat Q^T as alpha[r] (diagonal) and beta[r-1] (off-diagonal) on the host. *steps <= r is
+ * the number of vectors produced (fewer when the Krylov space is exhausted). r in 1..EGP_RANK_MAX.
+ * Synchronises.
+ *
+ * egp_predict: mean (device, nq) = K(Xq, X) a with the cached solve a = Khat^{-1} y (device, n); when var is
+ * not NULL, var (device, nq) = outputscale - g^T T^{-1} g with g = Q K(X, xq): the variance of the latent
+ * function from the rank-r cache, O(n r) per query point and no solve. It is never below the exact variance
+ * and reaches it as r grows. Synchronises. */
+int egp_kmm_cross(const float* Xq, int64_t nq, const float* X, int64_t n, const float* V, int32_t t,
+                  const egp_hyper_t* h, float* out, void* ws, size_t ws_bytes, void* stream);
+size_t egp_kmm_cross_ws_bytes(int64_t nq, int64_t n, int32_t d, int32_t t);
+int egp_lanczos(const float* X, int64_t n, const egp_hyper_t* h, const float* b, int32_t r, float* Q,
+                double* alpha, double* beta, int32_t* steps, void* ws, size_t ws_bytes, void* stream);
+size_t egp_lanczos_ws_bytes(int64_t n, int32_t d, int32_t r);
+int egp_predict(const float* Xq, int64_t nq, const float* X, int64_t n, const egp_hyper_t* h, const float* a,
+                const float* Q, int32_t r, const double* alpha, const double* beta, float* mean, float* var,
+                void* ws, size_t ws_bytes, void* stream);
+size_t egp_predict_ws_bytes(int64_t nq, int64_t n, int32_t d, int32_t r);
+
 /* Z = P^{-1} R with P = L L^T + noise*I through the Woodbury identity, R and Z device n x t.
  * Exposed so that probe vectors and trace terms can be formed outside the solver. Asynchronous. */
 int egp_precond_apply(const egp_precond_t* P, int64_t n, float noise, const float* R, int32_t t,

@@ -38,7 +38,7 @@ __all__ = [
     "kmm_rows", "dkernel_dlengthscale", "kmm_grad", "kmm_grad_rows", "chol_solve", "logdet",
     "mll", "mll_grad", "pivoted_cholesky", "precond_matrix", "precond_solve", "precond_logdet",
     "pcg", "tridiag_from_cg", "slq_quadrature", "slq_logdet", "probes_with_cov_P",
-    "mll_stochastic_terms",
+    "mll_stochastic_terms", "predict_exact", "lanczos", "predict_var_lanczos",
 ]
 
 
@@ -343,3 +343,51 @@ def mll_stochastic_terms(X, y, hyper: Hyper, Z, L=None, max_iter=None):
     value = -0.5 * y @ u - 0.5 * ld - 0.5 * n * np.log(2.0 * np.pi)
     grad = 0.5 * quad - 0.5 * traces
     return {"u": u, "logdet": ld, "mll": value, "grad": grad, "trace": traces, "quad": quad}
+
+
+def predict_exact(X, y, Xq, hyper: Hyper):
+    """Predictive moments of the latent function at the rows of Xq with zero prior mean (predictive mean and
+    variance equations of the Background section), by dense Cholesky:
+    mean = K(Xq,X) Khat^{-1} y,  var = k(xq,xq) - k_q^T Khat^{-1} k_q."""
+    X = np.asarray(X, np.float64)
+    Xq = np.asarray(Xq, np.float64)
+    Kh = khat(X, hyper)
+    Kq = kernel_matrix(Xq, X, hyper)
+    mean = Kq @ chol_solve(Kh, np.asarray(y, np.float64))
+    var = hyper.outputscale - np.sum(Kq * chol_solve(Kh, Kq.T).T, axis=1)
+    return mean, var
+
+
+def lanczos(Khat, b, r):
+    """Textbook Lanczos process on the symmetric matrix Khat from start vector b, with full
+    re-orthogonalisation (two Gram-Schmidt passes per step). Returns Q (steps x n, orthonormal rows),
+    alpha (steps), beta (steps-1): T = Q Khat Q^T is tridiagonal with these entries."""
+    Khat = np.asarray(Khat, np.float64)
+    b = np.asarray(b, np.float64)
+    n = len(b)
+    Q = np.zeros((r, n))
+    alpha, beta = [], []
+    Q[0] = b / np.linalg.norm(b)
+    for j in range(r):
+        w = Khat @ Q[j]
+        alpha.append(Q[j] @ w)
+        if j + 1 == r:
+            break
+        for _ in range(2):
+            w = w - Q[:j + 1].T @ (Q[:j + 1] @ w)
+        bj = np.linalg.norm(w)
+        if not bj > 1e-12 * (abs(alpha[0]) + (beta[0] if beta else bj)):
+            break
+        beta.append(bj)
+        Q[j + 1] = w / bj
+    m = len(alpha)
+    return Q[:m], np.array(alpha), np.array(beta[:m - 1])
+
+
+def predict_var_lanczos(Kq, Q, alpha, beta, outputscale):
+    """Cached predictive variance: s - g^T T^{-1} g with g = Q k_q, T = tridiag(alpha, beta): the Galerkin
+    approximation Q^T T^{-1} Q of Khat^{-1} on the Krylov space spanned by the rows of Q. Kq is K(Xq, X)."""
+    m = len(alpha)
+    T = np.diag(alpha) + (np.diag(beta, 1) + np.diag(beta, -1) if m > 1 else 0.0)
+    G = np.asarray(Kq, np.float64) @ np.asarray(Q, np.float64).T
+    return outputscale - np.sum(G * np.linalg.solve(T, G.T).T, axis=1)

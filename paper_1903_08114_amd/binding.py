@@ -70,6 +70,23 @@ def lib():
         L.egp_kmm_grad_bilinear.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int32,
                                             C.POINTER(C.c_float), C.POINTER(_Hyper), C.POINTER(C.c_double),
                                             C.c_void_p, C.c_size_t, C.c_void_p]
+        L.egp_kmm_cross_ws_bytes.restype = C.c_size_t
+        L.egp_kmm_cross_ws_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int32, C.c_int32]
+        L.egp_kmm_cross.restype = C.c_int
+        L.egp_kmm_cross.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32,
+                                    C.POINTER(_Hyper), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.egp_lanczos_ws_bytes.restype = C.c_size_t
+        L.egp_lanczos_ws_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32]
+        L.egp_lanczos.restype = C.c_int
+        L.egp_lanczos.argtypes = [C.c_void_p, C.c_int64, C.POINTER(_Hyper), C.c_void_p, C.c_int32, C.c_void_p,
+                                  C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int32), C.c_void_p,
+                                  C.c_size_t, C.c_void_p]
+        L.egp_predict_ws_bytes.restype = C.c_size_t
+        L.egp_predict_ws_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int32, C.c_int32]
+        L.egp_predict.restype = C.c_int
+        L.egp_predict.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.POINTER(_Hyper), C.c_void_p,
+                                  C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p,
+                                  C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.egp_mll_ws_bytes.restype = C.c_size_t
         L.egp_mll_ws_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
         L.egp_mll.restype = C.c_int
@@ -314,3 +331,74 @@ def tridiag_logquad(diag, off):
                                      off.ctypes.data_as(C.POINTER(C.c_double)) if len(off) else None,
                                      len(diag), C.byref(out)))
     return out.value
+
+
+def kmm_cross(Xq, X, V, lengthscales, outputscale, kernel_type, out=None, ws=None):
+    """out (nq x t) = K(Xq, X) V, no noise term (egp_kmm_cross)."""
+    import torch
+    L = lib()
+    nq, d = Xq.shape
+    n = X.shape[0]
+    t = V.shape[1]
+    h = _hyper(kernel_type, lengthscales, outputscale, 0.0)
+    if out is None:
+        out = torch.empty((nq, t), dtype=torch.float32, device=X.device)
+    if ws is None:
+        ws = _workspace(L.egp_kmm_cross_ws_bytes(nq, n, d, t), X.device)
+    _check(L.egp_kmm_cross(_dev(Xq, "Xq"), nq, _dev(X, "X"), n, _dev(V, "V"), t, C.byref(h), _dev(out, "out"),
+                           C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
+    return out
+
+
+class LanczosCache:
+    """Q (steps, n) float32 CUDA tensor with orthonormal rows and the tridiagonal T = Q Khat Q^T (alpha, beta)."""
+
+    def __init__(self, Q, alpha, beta, steps):
+        self.Q, self.alpha, self.beta, self.steps = Q, alpha, beta, steps
+
+
+def lanczos(X, b, lengthscales, outputscale, noise, kernel_type, r, ws=None):
+    """r Lanczos steps on K + noise I from the start vector b (egp_lanczos). Returns a LanczosCache."""
+    import numpy as np
+    import torch
+    L = lib()
+    n, d = X.shape
+    h = _hyper(kernel_type, lengthscales, outputscale, noise)
+    Q = torch.zeros((r, n), dtype=torch.float32, device=X.device)
+    alpha = np.zeros(r, dtype=np.float64)
+    beta = np.zeros(max(r - 1, 1), dtype=np.float64)
+    steps = C.c_int32(0)
+    if ws is None:
+        ws = _workspace(L.egp_lanczos_ws_bytes(n, d, r), X.device)
+    _check(L.egp_lanczos(_dev(X, "X"), n, C.byref(h), _dev(b, "b"), int(r), _dev(Q, "Q"),
+                         alpha.ctypes.data_as(C.POINTER(C.c_double)), beta.ctypes.data_as(C.POINTER(C.c_double)),
+                         C.byref(steps), C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
+    m = int(steps.value)
+    return LanczosCache(Q[:m], alpha[:m].copy(), beta[:max(m - 1, 0)].copy(), m)
+
+
+def predict(Xq, X, a, lengthscales, outputscale, noise, kernel_type, cache=None, ws=None):
+    """Predictive mean K(Xq,X) a and, with a LanczosCache, the cached predictive variance (egp_predict).
+    Returns (mean, var) float32 CUDA tensors of length nq (var is None without a cache)."""
+    import numpy as np
+    import torch
+    L = lib()
+    nq, d = Xq.shape
+    n = X.shape[0]
+    h = _hyper(kernel_type, lengthscales, outputscale, noise)
+    mean = torch.empty(nq, dtype=torch.float32, device=X.device)
+    r = cache.steps if cache is not None else 0
+    var = torch.empty(nq, dtype=torch.float32, device=X.device) if cache is not None else None
+    if ws is None:
+        ws = _workspace(L.egp_predict_ws_bytes(nq, n, d, r), X.device)
+    if cache is not None:
+        Q = cache.Q.contiguous()
+        al = np.ascontiguousarray(cache.alpha, dtype=np.float64)
+        be = np.ascontiguousarray(cache.beta if r > 1 else np.zeros(1), dtype=np.float64)
+        _check(L.egp_predict(_dev(Xq, "Xq"), nq, _dev(X, "X"), n, C.byref(h), _dev(a, "a"), _dev(Q, "Q"), r,
+                             al.ctypes.data_as(C.POINTER(C.c_double)), be.ctypes.data_as(C.POINTER(C.c_double)),
+                             _dev(mean, "mean"), _dev(var, "var"), C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
+    else:
+        _check(L.egp_predict(_dev(Xq, "Xq"), nq, _dev(X, "X"), n, C.byref(h), _dev(a, "a"), None, 0, None, None,
+                             _dev(mean, "mean"), None, C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
+    return mean, var

@@ -242,6 +242,78 @@ int egp_tridiag_logquad(const double* diag, const double* off, int32_t m, double
   return EGP_OK;
 }
 
+size_t egp_kmm_cross_ws_bytes(int64_t nq, int64_t n, int32_t d, int32_t t) {
+  if (nq < 1 || n < 1 || d < 1 || d > EGP_D_MAX || t < 1 || t > EGP_T_MAX) return 0;
+  return cross_ws_bytes_core(nq, n, d, t);
+}
+
+int egp_kmm_cross(const float* Xq, int64_t nq, const float* X, int64_t n, const float* V, int32_t t,
+                  const egp_hyper_t* h, float* out, void* ws, size_t ws_bytes, void* stream) {
+  int rc;
+  if ((rc = validate_hyper(h)) != EGP_OK) return rc;
+  if ((rc = check_n(n)) != EGP_OK) return rc;
+  if ((rc = check_n(nq)) != EGP_OK) return rc;
+  if (t < 1 || t > EGP_T_MAX) return fail(EGP_ERR_ARG, "t = %d outside 1..%d", t, EGP_T_MAX);
+  if ((rc = validate_ptr(Xq, "Xq")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(X, "X")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(V, "V")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(out, "out")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(ws, "ws")) != EGP_OK) return rc;
+  const size_t need = cross_ws_bytes_core(nq, n, h->d, t);
+  if (ws_bytes < need) return fail(EGP_ERR_WS, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, need);
+  return cross_core(Xq, nq, X, n, V, t, h, out, ws, static_cast<hipStream_t>(stream), 0);
+}
+
+size_t egp_lanczos_ws_bytes(int64_t n, int32_t d, int32_t r) {
+  if (n < 1 || d < 1 || d > EGP_D_MAX || r < 1 || r > EGP_RANK_MAX) return 0;
+  return lanczos_ws_bytes_core(n, d, r);
+}
+
+int egp_lanczos(const float* X, int64_t n, const egp_hyper_t* h, const float* b, int32_t r, float* Q, double* alpha,
+                double* beta, int32_t* steps, void* ws, size_t ws_bytes, void* stream) {
+  int rc;
+  if ((rc = validate_hyper(h)) != EGP_OK) return rc;
+  if ((rc = check_n(n)) != EGP_OK) return rc;
+  if (r < 1 || r > EGP_RANK_MAX || r > n) return fail(EGP_ERR_ARG, "r = %d outside 1..min(n, %d)", r, EGP_RANK_MAX);
+  if (alpha == nullptr || steps == nullptr || (r > 1 && beta == nullptr))
+    return fail(EGP_ERR_ARG, "alpha / beta / steps is NULL");
+  if ((rc = validate_ptr(X, "X")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(b, "b")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(Q, "Q")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(ws, "ws")) != EGP_OK) return rc;
+  const size_t need = lanczos_ws_bytes_core(n, h->d, r);
+  if (ws_bytes < need) return fail(EGP_ERR_WS, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, need);
+  return lanczos_core(X, n, h, b, r, Q, alpha, beta, steps, ws, static_cast<hipStream_t>(stream));
+}
+
+size_t egp_predict_ws_bytes(int64_t nq, int64_t n, int32_t d, int32_t r) {
+  if (nq < 1 || n < 1 || d < 1 || d > EGP_D_MAX || r < 0 || r > EGP_RANK_MAX) return 0;
+  return predict_ws_bytes_core(nq, n, d, r);
+}
+
+int egp_predict(const float* Xq, int64_t nq, const float* X, int64_t n, const egp_hyper_t* h, const float* a,
+                const float* Q, int32_t r, const double* alpha, const double* beta, float* mean, float* var, void* ws,
+                size_t ws_bytes, void* stream) {
+  int rc;
+  if ((rc = validate_hyper(h)) != EGP_OK) return rc;
+  if ((rc = check_n(n)) != EGP_OK) return rc;
+  if ((rc = check_n(nq)) != EGP_OK) return rc;
+  if (r < 0 || r > EGP_RANK_MAX) return fail(EGP_ERR_ARG, "r = %d outside 0..%d", r, EGP_RANK_MAX);
+  if ((rc = validate_ptr(Xq, "Xq")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(X, "X")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(a, "a")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(mean, "mean")) != EGP_OK) return rc;
+  if (var != nullptr) {
+    if ((rc = validate_ptr(var, "var")) != EGP_OK) return rc;
+    if (r < 1 || alpha == nullptr || (r > 1 && beta == nullptr)) return fail(EGP_ERR_ARG, "a variance needs r >= 1, alpha and beta");
+    if ((rc = validate_ptr(Q, "Q")) != EGP_OK) return rc;
+  }
+  if ((rc = validate_ptr(ws, "ws")) != EGP_OK) return rc;
+  const size_t need = predict_ws_bytes_core(nq, n, h->d, var ? r : 0);
+  if (ws_bytes < need) return fail(EGP_ERR_WS, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, need);
+  return predict_core(Xq, nq, X, n, h, a, Q, r, alpha, beta, mean, var, ws, static_cast<hipStream_t>(stream));
+}
+
 static int check_n(int64_t n) {
   if (n < 1 || n > ((int64_t)1 << 31) - 1) return fail(EGP_ERR_ARG, "n = %lld outside 1..2^31-1", (long long)n);
   return EGP_OK;

@@ -33,6 +33,7 @@ inline int64_t padded_points(int64_t n) { return (int64_t)round_up((size_t)n, kP
 struct Prepared {   // device arrays carved from a workspace by prepare_points()
   float* Xp;        // [npad/16][KS][64]
   float* nrm;       // [npad] squared norms of the scaled points (0 for padding)
+  float* mean;      // [d] centre subtracted before scaling
   int64_t n, npad;
   int d, ks, kernel_type;
   float outputscale, noise;
@@ -40,12 +41,16 @@ struct Prepared {   // device arrays carved from a workspace by prepare_points()
 
 size_t prepared_bytes(int64_t n, int d);
 // Scale, centre and pack X for kernel `h` into ws (>= prepared_bytes). Asynchronous on stream.
+// mean_from: device pointer to the centre of another prepared set (for a second point set), or NULL.
 int prepare_points(const float* X, int64_t n, const egp_hyper_t* h, void* ws, Prepared* out,
-                   hipStream_t stream);
+                   hipStream_t stream, const float* mean_from = nullptr);
 
 // out = Khat V using prepared points. ws2 >= kmm_core_ws_bytes. V/out are row-major n x t.
 size_t kmm_core_ws_bytes(int64_t n, int t);
 int kmm_core(const Prepared& P, const float* V, int t, float* out, void* ws2, hipStream_t stream);
+size_t kmm_cross_ws_bytes(int64_t n_rows, int64_t n_cols, int t);
+int kmm_cross(const Prepared& P, const Prepared& Q, const float* V, int t, float* out, void* ws2,
+              hipStream_t stream, int64_t v_ld = 0);
 
 void launch_pack_rhs(const float* V, int64_t n, int64_t npad, int t, int c0, int nb_count, int extra, void* Vp,
                      float* Ep, hipStream_t stream);
@@ -55,6 +60,16 @@ int kmm_grad_core(const Prepared& P, const egp_hyper_t* h, const float* V, int t
 size_t bilinear_core_ws_bytes(int64_t n, int d, int t);
 int bilinear_core(const Prepared& P, const egp_hyper_t* h, const float* A, const float* B, int t, const float* wcol,
                   double* out, void* ws2, hipStream_t stream);
+size_t lanczos_ws_bytes_core(int64_t n, int d, int r);
+int lanczos_core(const float* X, int64_t n, const egp_hyper_t* h, const float* b, int r, float* Q, double* alpha,
+                 double* beta, int32_t* steps, void* ws, hipStream_t stream);
+size_t cross_ws_bytes_core(int64_t nq, int64_t n, int d, int t);
+int cross_core(const float* Xq, int64_t nq, const float* X, int64_t n, const float* V, int t, const egp_hyper_t* h,
+               float* out, void* ws, hipStream_t stream, int64_t v_ld);
+size_t predict_ws_bytes_core(int64_t nq, int64_t n, int d, int r);
+int predict_core(const float* Xq, int64_t nq, const float* X, int64_t n, const egp_hyper_t* h, const float* a,
+                 const float* Q, int r, const double* alpha, const double* beta, float* mean, float* var, void* ws,
+                 hipStream_t stream);
 size_t pivchol_ws_bytes(int64_t n, int d, int rank);
 int pivchol_core(const float* X, int64_t n, const egp_hyper_t* h, float tol_abs, egp_precond_t* P, void* ws,
                  hipStream_t stream);

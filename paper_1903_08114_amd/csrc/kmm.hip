@@ -149,14 +149,16 @@ __global__ __launch_bounds__(256) void kmm_epilogue(const float* __restrict__ Pa
   float acc = 0.f;
   for (int sp = 0; sp < splits; ++sp) acc += Part[((int64_t)sp * npad + row) * ts + c];
   const int64_t o = row * t + c0 + c;
-  out[o] = __builtin_fmaf(s, acc, noise * V[o]);
+  out[o] = V ? __builtin_fmaf(s, acc, noise * V[o]) : s * acc;
 }
 
 // Column-major variants used by the solver (state arrays are [t][ld], column c contiguous, ld = npad,
 // entries beyond n are zero).
 // Vp[tile][nb][lane=(q,p)] = V[c0 + 16 nb + p][16 tile + 4q .. +3]: one 16-byte load per lane.
+// n_valid < 0: columns are zero-padded to npad and 16-byte aligned (solver state); otherwise entries at
+// or beyond n_valid are read as zero with scalar loads (arbitrary ld).
 __global__ __launch_bounds__(256) void pack_rhs_cm(const float* __restrict__ V, int64_t ld, int64_t npad, int t,
-                                                   int nb_count, f4* __restrict__ Vp) {
+                                                   int nb_count, f4* __restrict__ Vp, int64_t n_valid) {
   int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t total = (npad >> 4) * nb_count * 64;
   if (g >= total) return;
@@ -167,7 +169,18 @@ __global__ __launch_bounds__(256) void pack_rhs_cm(const float* __restrict__ V, 
   const int q = lane >> 4, p = lane & 15;
   const int c = nb * 16 + p;
   f4 v = {0.f, 0.f, 0.f, 0.f};
-  if (c < t) v = *reinterpret_cast<const f4*>(V + (int64_t)c * ld + tile * 16 + q * 4);
+  if (c < t) {
+    const int64_t j = tile * 16 + q * 4;
+    const float* src = V + (int64_t)c * ld + j;
+    if (n_valid < 0) {
+      v = *reinterpret_cast<const f4*>(src);
+    } else {
+      if (j + 0 < n_valid) v.x = src[0];
+      if (j + 1 < n_valid) v.y = src[1];
+      if (j + 2 < n_valid) v.z = src[2];
+      if (j + 3 < n_valid) v.w = src[3];
+    }
+  }
   Vp[g] = v;
 }
 
@@ -231,7 +244,7 @@ size_t prepared_bytes(int64_t n, int d) {
 }
 
 int prepare_points(const float* X, int64_t n, const egp_hyper_t* h, void* ws, Prepared* out,
-                   hipStream_t stream) {
+                   hipStream_t stream, const float* mean_from) {
   const int d = h->d;
   const int64_t npad = padded_points(n);
   const int ks = ksteps_for(d);
@@ -243,6 +256,7 @@ int prepare_points(const float* X, int64_t n, const egp_hyper_t* h, void* ws, Pr
   float* partial = reinterpret_cast<float*>(w);
   w += round_up((size_t)kMeanBlocks * 64 * sizeof(float), 256);
   float* mean = reinterpret_cast<float*>(w);
+  out->mean = mean;
   out->n = n;
   out->npad = npad;
   out->d = d;
@@ -256,8 +270,13 @@ int prepare_points(const float* X, int64_t n, const egp_hyper_t* h, void* ws, Pr
   for (int f = 0; f <= EGP_D_MAX; ++f) sc.inv[f] = f < d ? (float)(c / (double)h->lengthscales[f]) : 0.f;
 
   ProfScope prof(kProfPack, stream);
-  hipLaunchKernelGGL(col_sum_partial, dim3(kMeanBlocks), dim3(256), 0, stream, X, n, d, partial);
-  hipLaunchKernelGGL(col_mean_final, dim3(1), dim3(256), 0, stream, partial, kMeanBlocks, n, d, mean);
+  if (mean_from != nullptr) {
+    // a second point set measured against the first one's centre (distances are invariant to the common shift)
+    EGP_HIP(hipMemcpyAsync(mean, mean_from, sizeof(float) * d, hipMemcpyDeviceToDevice, stream));
+  } else {
+    hipLaunchKernelGGL(col_sum_partial, dim3(kMeanBlocks), dim3(256), 0, stream, X, n, d, partial);
+    hipLaunchKernelGGL(col_mean_final, dim3(1), dim3(256), 0, stream, partial, kMeanBlocks, n, d, mean);
+  }
   hipLaunchKernelGGL(pack_points, dim3((unsigned)((npad + 255) / 256)), dim3(256), 0, stream, X, n, npad, d,
                      ks, mean, sc, out->Xp, out->nrm);
   EGP_HIP(hipGetLastError());
@@ -266,18 +285,18 @@ int prepare_points(const float* X, int64_t n, const egp_hyper_t* h, void* ws, Pr
 
 namespace {
 
-int launch_ks(const Prepared& P, const Plan& pl, int nb, int extra, const f4* Vp, const float* Ep, float* Part,
-              int cm, hipStream_t stream) {
+int launch_ks(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, int extra, const f4* Vp,
+              const float* Ep, float* Part, int cm, hipStream_t stream) {
   ProfScope prof(kProfKmm, stream);
   switch (P.ks) {
-    case 1: return launch_kind<1>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
-    case 2: return launch_kind<2>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
-    case 3: return launch_kind<3>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
-    case 4: return launch_kind<4>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
-    case 5: return launch_kind<5>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
-    case 6: return launch_kind<6>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
-    case 7: return launch_kind<7>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
-    case 8: return launch_kind<8>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 1: return launch_kind<1>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 2: return launch_kind<2>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 3: return launch_kind<3>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 4: return launch_kind<4>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 5: return launch_kind<5>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 6: return launch_kind<6>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 7: return launch_kind<7>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 8: return launch_kind<8>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
     default: return fail(EGP_ERR_ARG, "d = %d needs %d k-steps; this build supports d <= 31", P.d, P.ks);
   }
 }
@@ -286,20 +305,30 @@ int launch_ks(const Prepared& P, const Plan& pl, int nb, int extra, const f4* Vp
 
 static int widest_ts(int t) { return t <= 16 ? 16 : (t == 17 ? 17 : (t <= 32 ? 32 : 33)); }
 
-size_t kmm_core_ws_bytes(int64_t n, int t) {
-  const int64_t npad = padded_points(n);
-  const Plan pl = make_plan(npad, 1);     // the split count depends on the shape class only (all KS <= 8 alike)
+size_t kmm_cross_ws_bytes(int64_t n_rows, int64_t n_cols, int t) {
+  const int64_t prow = padded_points(n_rows), pcol = padded_points(n_cols);
+  const Plan pl = make_plan(prow, pcol, 1);   // the split count depends on the shape class only (all KS <= 8 alike)
   const int nb = t > 17 ? 2 : 1;
   size_t b = 0;
-  b += round_up((size_t)npad * nb * 16 * sizeof(float), 256);                    // Vp
-  b += round_up((size_t)npad * sizeof(float), 256);                              // Ep
-  b += round_up((size_t)pl.splits * npad * widest_ts(t) * sizeof(float), 256);   // Part
+  b += round_up((size_t)pcol * nb * 16 * sizeof(float), 256);                    // Vp
+  b += round_up((size_t)pcol * sizeof(float), 256);                              // Ep
+  b += round_up((size_t)pl.splits * prow * widest_ts(t) * sizeof(float), 256);   // Part
   return b;
 }
 
+size_t kmm_core_ws_bytes(int64_t n, int t) { return kmm_cross_ws_bytes(n, n, t); }
+
 int kmm_core(const Prepared& P, const float* V, int t, float* out, void* ws2, hipStream_t stream) {
+  return kmm_cross(P, P, V, t, out, ws2, stream, 0);
+}
+
+// out (Q.n x t, row-major) = K(Q points, P points) V; the noise term is added only when Q and P are the same
+// set. V is P.n x t row-major, or, when v_ld > 0, stored by columns: column c at V + c * v_ld (P.n entries).
+int kmm_cross(const Prepared& P, const Prepared& Q, const float* V, int t, float* out, void* ws2,
+              hipStream_t stream, int64_t v_ld) {
   const int64_t npad = P.npad;
-  const Plan pl = make_plan(npad, P.ks);
+  const bool square = Q.Xp == P.Xp;
+  const Plan pl = make_plan(Q.npad, npad, P.ks);
   char* w = static_cast<char*>(ws2);
   const int tg_max = t > 33 ? 33 : t;
   const int nb_max = tg_max > 17 ? 2 : 1;
@@ -319,16 +348,28 @@ int kmm_core(const Prepared& P, const float* V, int t, float* out, void* ws2, hi
     else if (rem == 33) { nb = 2; extra = 1; tg = 33; }
     else { nb = 2; extra = 0; tg = 32; }
     const int ts = 16 * nb + extra;
-    {
+    if (v_ld > 0) {
+      // columns stored one after the other (e.g. Lanczos vectors): 16 columns per block, the odd one as Ep
+      ProfScope prof(kProfPack, stream);
+      const int64_t total = (npad >> 4) * nb * 64;
+      hipLaunchKernelGGL(pack_rhs_cm, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, V + c0 * v_ld, v_ld,
+                         npad, tg - extra, nb, Vp, P.n);
+      if (extra) {
+        EGP_HIP(hipMemsetAsync(Ep, 0, npad * sizeof(float), stream));
+        EGP_HIP(hipMemcpyAsync(Ep, V + (int64_t)(c0 + tg - 1) * v_ld, P.n * sizeof(float), hipMemcpyDeviceToDevice,
+                               stream));
+      }
+    } else {
       ProfScope prof(kProfPack, stream);
       launch_pack_rhs(V, P.n, npad, t, c0, nb, extra, Vp, Ep, stream);
     }
-    const int rc = launch_ks(P, pl, nb, extra, Vp, Ep, Part, 0, stream);
+    const int rc = launch_ks(P, Q, pl, nb, extra, Vp, Ep, Part, 0, stream);
     if (rc != EGP_OK) return rc;
-    const int64_t outs = P.n * tg;
+    const int64_t outs = Q.n * tg;
     ProfScope eprof(kProfPack, stream);
     hipLaunchKernelGGL(kmm_epilogue, dim3((unsigned)((outs + 255) / 256)), dim3(256), 0, stream, Part,
-                       pl.splits, npad, ts, V, P.n, t, c0, tg, P.outputscale, P.noise, out);
+                       pl.splits, Q.npad, ts, square ? V : nullptr, Q.n, t, c0, tg, P.outputscale,
+                       square ? P.noise : 0.f, out);
     EGP_HIP(hipGetLastError());
     c0 += tg;
   }
@@ -346,7 +387,7 @@ int kmm_cm_dot_blocks(int64_t npad) {
 int kmm_core_cm(const Prepared& P, const float* V, int t, float* out, void* ws2, float* dot_part, int dot_ld,
                 hipStream_t stream) {
   const int64_t npad = P.npad;
-  const Plan pl = make_plan(npad, P.ks);
+  const Plan pl = make_plan(npad, npad, P.ks);
   char* w = static_cast<char*>(ws2);
   const int nb = t > 17 ? 2 : 1;
   const int extra = (t == 17 || t == 33) ? 1 : 0;
@@ -359,11 +400,11 @@ int kmm_core_cm(const Prepared& P, const float* V, int t, float* out, void* ws2,
     ProfScope prof(kProfPack, stream);
     const int64_t total = (npad >> 4) * nb * 64;
     hipLaunchKernelGGL(pack_rhs_cm, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, V, npad, npad,
-                       extra ? t - 1 : t, nb, Vp);
+                       extra ? t - 1 : t, nb, Vp, (int64_t)-1);
   }
   // the 17th / 33rd column is consumed straight from the state array
   const float* Ep = extra ? V + (int64_t)(t - 1) * npad : nullptr;
-  const int rc = launch_ks(P, pl, nb, extra, Vp, Ep, Part, 1, stream);
+  const int rc = launch_ks(P, P, pl, nb, extra, Vp, Ep, Part, 1, stream);
   if (rc != EGP_OK) return rc;
   ProfScope eprof(kProfPack, stream);
   hipLaunchKernelGGL(kmm_epilogue_cm, dim3(kmm_cm_dot_blocks(npad), t), dim3(256), 0, stream, Part, pl.splits, npad,

@@ -34,8 +34,9 @@ __device__ __forceinline__ float transform(float acc) {
 //            splits in a fixed order, scales by the outputscale and adds noise * V.
 // ------------------------------------------------------------------------------------------------
 template <int KS, int R, int KIND, int NB, int EXTRA, int JT>
-__global__ __launch_bounds__(256, 2) void kmm_kernel(const float* __restrict__ Xp,
+__global__ __launch_bounds__(256, 2) void kmm_kernel(const float* __restrict__ XpRow,
                                                      const float* __restrict__ nrm,
+                                                     const float* __restrict__ Xp,
                                                      const f4* __restrict__ Vp,
                                                      const float* __restrict__ Ep,
                                                      float* __restrict__ Part, int64_t npad, int d,
@@ -64,7 +65,7 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel(const float* __restrict__ X
   const int ds = d >> 2, dq = d & 3;
 #pragma unroll
   for (int it = 0; it < R; ++it) {
-    const float* src = Xp + (row_tile0 + it) * KS * 64 + lane;
+    const float* src = XpRow + (row_tile0 + it) * KS * 64 + lane;
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
       float v = -2.0f * src[s * 64];
@@ -217,13 +218,13 @@ constexpr int kSmallR = 2, kSmallJT = 4;
 constexpr int big_r(int ks) { return ks <= 8 ? 8 : 4; }
 constexpr int big_jt(int ks) { return ks <= 8 ? 16 : 4; }
 
-inline Plan make_plan(int64_t npad, int ks) {
+inline Plan make_plan(int64_t npad_rows, int64_t npad_cols, int ks) {
   Plan pl;
   const int64_t big_rows = 64 * big_r(ks);
-  pl.big = npad / big_rows >= 64;          // enough row blocks for the wide shape to be worthwhile
+  pl.big = npad_rows / big_rows >= 64;     // enough row blocks for the wide shape to be worthwhile
   const int R = pl.big ? big_r(ks) : kSmallR, JT = pl.big ? big_jt(ks) : kSmallJT;
-  pl.row_blocks = (int)(npad / (64 * R));
-  pl.stages_total = (int)(npad / (16 * JT));
+  pl.row_blocks = (int)(npad_rows / (64 * R));
+  pl.stages_total = (int)(npad_cols / (16 * JT));
   int want = 1024 / pl.row_blocks;
   if (want < 1) want = 1;
   if (want > pl.stages_total) want = pl.stages_total;
@@ -234,36 +235,36 @@ inline Plan make_plan(int64_t npad, int ks) {
 }
 
 template <int KS, int KIND, int NB, int EXTRA>
-int launch_shape(const Prepared& P, const Plan& pl, const f4* Vp, const float* Ep, float* Part, int cm,
-                 hipStream_t stream) {
+int launch_shape(const Prepared& P, const Prepared& Q, const Plan& pl, const f4* Vp, const float* Ep, float* Part,
+                 int cm, hipStream_t stream) {   // P: column points, Q: row points
   dim3 grid(pl.row_blocks, pl.splits), block(256);
   if (pl.big) {
-    hipLaunchKernelGGL((kmm_kernel<KS, big_r(KS), KIND, NB, EXTRA, big_jt(KS)>), grid, block, 0, stream, P.Xp, P.nrm,
-                       Vp, Ep, Part, P.npad, P.d, pl.stages_per_split, pl.stages_total, cm);
+    hipLaunchKernelGGL((kmm_kernel<KS, big_r(KS), KIND, NB, EXTRA, big_jt(KS)>), grid, block, 0, stream, Q.Xp, Q.nrm,
+                       P.Xp, Vp, Ep, Part, Q.npad, P.d, pl.stages_per_split, pl.stages_total, cm);
   } else {
-    hipLaunchKernelGGL((kmm_kernel<KS, kSmallR, KIND, NB, EXTRA, kSmallJT>), grid, block, 0, stream, P.Xp,
-                       P.nrm, Vp, Ep, Part, P.npad, P.d, pl.stages_per_split, pl.stages_total, cm);
+    hipLaunchKernelGGL((kmm_kernel<KS, kSmallR, KIND, NB, EXTRA, kSmallJT>), grid, block, 0, stream, Q.Xp,
+                       Q.nrm, P.Xp, Vp, Ep, Part, Q.npad, P.d, pl.stages_per_split, pl.stages_total, cm);
   }
   EGP_HIP(hipGetLastError());
   return EGP_OK;
 }
 
 template <int KS, int KIND>
-int launch_cols(const Prepared& P, const Plan& pl, int nb, int extra, const f4* Vp, const float* Ep,
-                float* Part, int cm, hipStream_t stream) {
-  if (nb == 1 && !extra) return launch_shape<KS, KIND, 1, 0>(P, pl, Vp, Ep, Part, cm, stream);
-  if (nb == 1 && extra) return launch_shape<KS, KIND, 1, 1>(P, pl, Vp, Ep, Part, cm, stream);
-  if (nb == 2 && !extra) return launch_shape<KS, KIND, 2, 0>(P, pl, Vp, Ep, Part, cm, stream);
-  return launch_shape<KS, KIND, 2, 1>(P, pl, Vp, Ep, Part, cm, stream);
+int launch_cols(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, int extra, const f4* Vp,
+                const float* Ep, float* Part, int cm, hipStream_t stream) {
+  if (nb == 1 && !extra) return launch_shape<KS, KIND, 1, 0>(P, Q, pl, Vp, Ep, Part, cm, stream);
+  if (nb == 1 && extra) return launch_shape<KS, KIND, 1, 1>(P, Q, pl, Vp, Ep, Part, cm, stream);
+  if (nb == 2 && !extra) return launch_shape<KS, KIND, 2, 0>(P, Q, pl, Vp, Ep, Part, cm, stream);
+  return launch_shape<KS, KIND, 2, 1>(P, Q, pl, Vp, Ep, Part, cm, stream);
 }
 
 template <int KS>
-int launch_kind(const Prepared& P, const Plan& pl, int nb, int extra, const f4* Vp, const float* Ep,
-                float* Part, int cm, hipStream_t stream) {
+int launch_kind(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, int extra, const f4* Vp,
+                const float* Ep, float* Part, int cm, hipStream_t stream) {
   switch (P.kernel_type) {
-    case EGP_RBF: return launch_cols<KS, EGP_RBF>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
-    case EGP_MATERN32: return launch_cols<KS, EGP_MATERN32>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
-    default: return launch_cols<KS, EGP_MATERN52>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case EGP_RBF: return launch_cols<KS, EGP_RBF>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case EGP_MATERN32: return launch_cols<KS, EGP_MATERN32>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    default: return launch_cols<KS, EGP_MATERN52>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
   }
 }
 

@@ -255,8 +255,11 @@ __global__ __launch_bounds__(256) void small_matmul(const float* __restrict__ Mi
   if (e >= k * ldy) return;
   const int m = e / ldy, c = e % ldy;
   float acc = 0.f;
-  if (c < t)
-    for (int m2 = 0; m2 < k; ++m2) acc = __builtin_fmaf(Minv[m * k + m2], W[m2 * t + c], acc);
+  if (c < t) {
+    if (Minv == nullptr) acc = W[m * t + c];      // identity: plain projection coefficients
+    else
+      for (int m2 = 0; m2 < k; ++m2) acc = __builtin_fmaf(Minv[m * k + m2], W[m2 * t + c], acc);
+  }
   Y[e] = acc;
 }
 

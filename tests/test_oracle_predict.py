@@ -1,0 +1,56 @@
+"""Pins for the oracle's prediction functions (CPU only)."""
+import numpy as np
+
+import oracle as orc
+from workloads import well_separated_points
+
+
+def _problem(n=80, nq=15, kind=orc.MATERN32, seed=3):
+    rng = np.random.default_rng(seed)
+    X = well_separated_points(seed, n, 2)
+    Xq = rng.uniform(0, 1, (nq, 2)).astype(np.float32)
+    y = np.sin(6 * X[:, 0]) * np.cos(4 * X[:, 1]) + 0.1 * rng.standard_normal(n)
+    h = orc.Hyper(kind, [0.3, 0.5], 1.4, 0.05)
+    return X, Xq, y, h
+
+
+def test_predict_exact_against_joint_gaussian_conditioning():
+    """Mean and variance must equal the conditional of the joint Gaussian over (f(xq), y)."""
+    X, Xq, y, h = _problem()
+    mean, var = orc.predict_exact(X, y, Xq, h)
+    for j in range(len(Xq)):
+        Z = np.vstack([Xq[j:j + 1].astype(np.float64), X.astype(np.float64)])
+        J = orc.kernel_matrix(Z, Z, h)
+        J[1:, 1:] += h.noise * np.eye(len(X))         # noise on the observations only
+        # Schur complement of the (y,y) block
+        w = np.linalg.solve(J[1:, 1:], J[1:, 0])
+        assert abs(mean[j] - w @ y) < 1e-9
+        assert abs(var[j] - (J[0, 0] - J[0, 1:] @ w)) < 1e-9
+    assert np.all(var > 0) and np.all(var <= h.outputscale + 1e-12)
+    # at a training point with tiny noise the mean interpolates and the variance collapses
+    h0 = orc.Hyper(h.kernel_type, h.lengthscales, h.outputscale, 1e-8)
+    m0, v0 = orc.predict_exact(X, y, X[:5], h0)
+    assert np.allclose(m0, y[:5], atol=1e-4) and np.all(np.abs(v0) < 1e-5)
+
+
+def test_lanczos_invariants_and_cached_variance():
+    X, Xq, y, h = _problem(n=60)
+    Kh = orc.khat(X, h)
+    Kq = orc.kernel_matrix(Xq, X, h)
+    _, exact = orc.predict_exact(X, y, Xq, h)
+    prev = None
+    for r in (5, 20, 60):
+        Q, al, be = orc.lanczos(Kh, y, r)
+        m = len(al)
+        assert np.allclose(Q @ Q.T, np.eye(m), atol=1e-10)
+        T = Q @ Kh @ Q.T
+        assert np.allclose(np.diag(T), al, atol=1e-9) and np.allclose(np.diag(T, 1), be, atol=1e-9)
+        assert np.abs(np.triu(T, 2)).max() < 1e-8
+        v = orc.predict_var_lanczos(Kq, Q, al, be, h.outputscale)
+        assert np.all(v >= exact - 1e-9)              # Galerkin: Q^T T^-1 Q <= Khat^-1
+        if prev is not None:
+            assert np.all(v <= prev + 1e-9)           # monotone in the rank
+        prev = v
+    assert np.allclose(prev, exact, atol=1e-8)        # full Krylov space: exact
+    # first Lanczos vector is the normalised start vector
+    assert np.allclose(Q[0], y / np.linalg.norm(y))
