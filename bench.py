@@ -62,6 +62,9 @@ def main():
     ap.add_argument("--mll", type=int, default=0, metavar="ITERS",
                     help="also time one C5 marginal-likelihood step (n=2^21, Matern-3/2) capped at ITERS CG iterations")
     ap.add_argument("--grad", action="store_true", help="also time the C3 KMM and derivative products (n=2^18, d=25)")
+    ap.add_argument("--predict", type=int, default=0, metavar="R",
+                    help="also time 1000 predictive means + cached variances against the C4 training set with a "
+                         "rank-R Lanczos cache (the cache build is timed separately)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB copy kernel (calibrates HBM counters under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -209,6 +212,27 @@ def main():
         leg["workload"] = f"C3: n={w3.n}, d={w3.d}, t={w3.t}, RBF-ARD, all {w3.d} lengthscale derivatives"
         result["c3"] = leg
         del X3, V3, g3, o3, wsg, wsk
+
+    if args.predict > 0:
+        rng = np.random.default_rng(9)
+        Xq = w.X[rng.choice(n, 1000, replace=False)] + 0.02 * rng.standard_normal((1000, d)).astype(np.float32)
+        Xq = torch.from_numpy(np.ascontiguousarray(Xq, dtype=np.float32)).to(dev)
+        yv = torch.from_numpy(np.ascontiguousarray(w.V[:, 0])).to(dev)
+        a = torch.from_numpy(rng.standard_normal(n).astype(np.float32)).to(dev)   # stands in for the cached solve
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        cache = egp.lanczos(X, yv, w.lengthscales, w.outputscale, w.noise, w.kernel_type, args.predict)
+        torch.cuda.synchronize()
+        build_s = time.perf_counter() - t0
+        egp.predict(Xq, X, a, w.lengthscales, w.outputscale, w.noise, w.kernel_type, cache=cache)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        mean, var = egp.predict(Xq, X, a, w.lengthscales, w.outputscale, w.noise, w.kernel_type, cache=cache)
+        torch.cuda.synchronize()
+        result["predict"] = {"s_per_1000_mean_and_var": time.perf_counter() - t0, "cache_rank": cache.steps,
+                             "cache_build_s": build_s, "n_train": n,
+                             "var_min": float(var.min()), "var_max": float(var.max())}
+        del Xq, yv, a, cache
 
     if args.mll > 0:
         w5 = make_workload("C5")
