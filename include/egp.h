@@ -185,6 +185,18 @@ int egp_precond_apply(const egp_precond_t* P, int64_t n, float noise, const floa
                       float* Z, void* ws, size_t ws_bytes, void* stream);
 size_t egp_precond_apply_ws_bytes(int64_t n, int32_t t, int32_t rank);
 
+/* Arithmetic of the tile x V contraction inside the fused kernel (process-wide; default EGP_KMM_FP32).
+ *   EGP_KMM_FP32        fp32 MFMA throughout: the reference mode, the one every reported fp32 figure uses.
+ *   EGP_KMM_SPLIT_BF16  the kernel entries and V are each split into a high and a low bf16 part and
+ *                       contracted as k_hi v_hi + k_hi v_lo + k_lo v_hi on the bf16 MFMA with fp32 accumulation
+ *                       (16 significant bits per factor); distances and the transform stay in fp32. Faster,
+ *                       because the bf16 MFMA co-executes with the transform's VALU work on this chip; its
+ *                       error and speed are reported separately from the fp32 figures.
+ * Affects egp_kmm, egp_kmm_cross, egp_mbcg, egp_lanczos, egp_mll. Returns EGP_ERR_ARG for an unknown mode. */
+typedef enum { EGP_KMM_FP32 = 0, EGP_KMM_SPLIT_BF16 = 1 } egp_kmm_mode_t;
+int egp_set_kmm_mode(int32_t mode);
+int egp_get_kmm_mode(void);
+
 /* In-stream timing of kernel groups with HIP events, for roofline reporting. While enabled, each launch
  * of a group is bracketed by an event pair on the stream it runs on. egp_profile_enable(1) clears the
  * counters; egp_profile_read waits for the recorded events, and returns the summed duration and the

@@ -3,6 +3,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <atomic>
 #include <cmath>
 #include <mutex>
 #include <vector>
@@ -41,6 +42,9 @@ int validate_hyper(const egp_hyper_t* h) {
   if (!(h->noise >= 0.f) || !std::isfinite(h->noise)) return fail(EGP_ERR_ARG, "noise must be >= 0 and finite");
   return EGP_OK;
 }
+
+static std::atomic<int> g_kmm_mode{EGP_KMM_FP32};
+int kmm_mode() { return g_kmm_mode.load(); }
 
 // ---- profiling: event pairs kept until egp_profile_read drains them ----
 struct ProfSlot { hipEvent_t a, b; };
@@ -100,6 +104,13 @@ extern "C" {
 
 const char* egp_last_error(void) { return g_err; }
 const char* egp_version(void) { return "0.1"; }
+
+int egp_set_kmm_mode(int32_t mode) {
+  if (mode != EGP_KMM_FP32 && mode != EGP_KMM_SPLIT_BF16) return fail(EGP_ERR_ARG, "unknown kmm mode %d", mode);
+  g_kmm_mode.store(mode);
+  return EGP_OK;
+}
+int egp_get_kmm_mode(void) { return g_kmm_mode.load(); }
 
 int egp_calib_copy(const float* src, float* dst, int64_t count, void* stream) {
   int rc;

@@ -107,6 +107,8 @@ struct ProfScope {   // records an event pair around the launches made during it
   void* slot_;
 };
 
+int kmm_mode();     // EGP_KMM_FP32 or EGP_KMM_SPLIT_BF16 (egp_set_kmm_mode)
+
 int validate_hyper(const egp_hyper_t* h);
 int validate_ptr(const void* p, const char* name);
 

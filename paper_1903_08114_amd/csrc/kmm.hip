@@ -285,20 +285,18 @@ int prepare_points(const float* X, int64_t n, const egp_hyper_t* h, void* ws, Pr
 
 namespace {
 
-int launch_ks(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, int extra, const f4* Vp,
-              const float* Ep, float* Part, int cm, hipStream_t stream) {
-  ProfScope prof(kProfKmm, stream);
-  switch (P.ks) {
-    case 1: return launch_kind<1>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
-    case 2: return launch_kind<2>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
-    case 3: return launch_kind<3>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
-    case 4: return launch_kind<4>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
-    case 5: return launch_kind<5>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
-    case 6: return launch_kind<6>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
-    case 7: return launch_kind<7>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
-    case 8: return launch_kind<8>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
-    default: return fail(EGP_ERR_ARG, "d = %d needs %d k-steps; this build supports d <= 31", P.d, P.ks);
+int launch_ks(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, int extra, f4* Vp, const float* Ep,
+              float* Part, int cm, hipStream_t stream) {
+  if (kmm_mode() == EGP_KMM_SPLIT_BF16) {
+    {
+      ProfScope prof(kProfPack, stream);
+      launch_split_vp(Vp, (P.npad >> 4) * nb * 64, stream);
+    }
+    ProfScope prof(kProfKmm, stream);
+    return launch_all_ks_split(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
   }
+  ProfScope prof(kProfKmm, stream);
+  return launch_all_ks<0>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
 }
 
 }  // namespace

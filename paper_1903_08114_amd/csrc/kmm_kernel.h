@@ -33,7 +33,17 @@ __device__ __forceinline__ float transform(float acc) {
 //   Part   = [split][npad][TS] raw accumulators (TS = 16 NB + EXTRA); the epilogue kernel reduces
 //            splits in a fixed order, scales by the outputscale and adds noise * V.
 // ------------------------------------------------------------------------------------------------
-template <int KS, int R, int KIND, int NB, int EXTRA, int JT>
+typedef short s4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+typedef float f2 __attribute__((ext_vector_type(2)));
+
+// SPLIT = 1: the tile x V contraction runs on the bf16 MFMA with both operands split into a high and a low
+// bf16 part (k = k_hi + k_lo, v = v_hi + v_lo; k_hi v_hi + k_hi v_lo + k_lo v_hi, fp32 accumulation): 16
+// significant bits per factor, relative error ~2^-16 per product, and three 16x16x16 steps in place of four
+// fp32 16x16x4 steps. Unlike the fp32 MFMA, the bf16 MFMA co-executes with the VALU work of the transform.
+// The distance step stays in fp32 (it cancels). V arrives pre-split: dwords 0,1 of a packed quad hold the four
+// high parts, dwords 2,3 the four low parts.
+template <int KS, int R, int KIND, int NB, int EXTRA, int JT, int SPLIT>
 __global__ __launch_bounds__(256, 2) void kmm_kernel(const float* __restrict__ XpRow,
                                                      const float* __restrict__ nrm,
                                                      const float* __restrict__ Xp,
@@ -147,12 +157,35 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel(const float* __restrict__ X
         k.y = transform<KIND>(acc.y);
         k.z = transform<KIND>(acc.z);
         k.w = transform<KIND>(acc.w);
+        if constexpr (SPLIT) {
+          // high parts by truncation (taken straight from the upper halves), low parts = exact remainders
+          const unsigned u0 = __float_as_uint(k.x), u1 = __float_as_uint(k.y);
+          const unsigned u2 = __float_as_uint(k.z), u3 = __float_as_uint(k.w);
+          const unsigned hi01 = __builtin_amdgcn_perm(u1, u0, 0x07060302u);
+          const unsigned hi23 = __builtin_amdgcn_perm(u3, u2, 0x07060302u);
+          const f2 l01 = {k.x - __uint_as_float(u0 & 0xffff0000u), k.y - __uint_as_float(u1 & 0xffff0000u)};
+          const f2 l23 = {k.z - __uint_as_float(u2 & 0xffff0000u), k.w - __uint_as_float(u3 & 0xffff0000u)};
+          const unsigned lo01 = __builtin_bit_cast(unsigned, __builtin_convertvector(l01, bf2));
+          const unsigned lo23 = __builtin_bit_cast(unsigned, __builtin_convertvector(l23, bf2));
+          typedef unsigned u2v __attribute__((ext_vector_type(2)));
+          const s4 khi = __builtin_bit_cast(s4, (u2v){hi01, hi23});
+          const s4 klo = __builtin_bit_cast(s4, (u2v){lo01, lo23});
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-          o[it][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(k.x, v[nb].x, o[it][nb], 0, 0, 0);
-          o[it][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(k.y, v[nb].y, o[it][nb], 0, 0, 0);
-          o[it][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(k.z, v[nb].z, o[it][nb], 0, 0, 0);
-          o[it][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(k.w, v[nb].w, o[it][nb], 0, 0, 0);
+          for (int nb = 0; nb < NB; ++nb) {
+            const s4 vhi = __builtin_bit_cast(s4, (f2){v[nb].x, v[nb].y});
+            const s4 vlo = __builtin_bit_cast(s4, (f2){v[nb].z, v[nb].w});
+            o[it][nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(khi, vhi, o[it][nb], 0, 0, 0);
+            o[it][nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(khi, vlo, o[it][nb], 0, 0, 0);
+            o[it][nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(klo, vhi, o[it][nb], 0, 0, 0);
+          }
+        } else {
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) {
+            o[it][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(k.x, v[nb].x, o[it][nb], 0, 0, 0);
+            o[it][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(k.y, v[nb].y, o[it][nb], 0, 0, 0);
+            o[it][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(k.z, v[nb].z, o[it][nb], 0, 0, 0);
+            o[it][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(k.w, v[nb].w, o[it][nb], 0, 0, 0);
+          }
         }
         if (EXTRA) {
           eacc[it] = __builtin_fmaf(k.x, e.x, eacc[it]);
@@ -234,39 +267,60 @@ inline Plan make_plan(int64_t npad_rows, int64_t npad_cols, int ks) {
   return pl;
 }
 
-template <int KS, int KIND, int NB, int EXTRA>
+template <int KS, int KIND, int NB, int EXTRA, int SPLIT>
 int launch_shape(const Prepared& P, const Prepared& Q, const Plan& pl, const f4* Vp, const float* Ep, float* Part,
                  int cm, hipStream_t stream) {   // P: column points, Q: row points
   dim3 grid(pl.row_blocks, pl.splits), block(256);
   if (pl.big) {
-    hipLaunchKernelGGL((kmm_kernel<KS, big_r(KS), KIND, NB, EXTRA, big_jt(KS)>), grid, block, 0, stream, Q.Xp, Q.nrm,
+    hipLaunchKernelGGL((kmm_kernel<KS, big_r(KS), KIND, NB, EXTRA, big_jt(KS), SPLIT>), grid, block, 0, stream, Q.Xp, Q.nrm,
                        P.Xp, Vp, Ep, Part, Q.npad, P.d, pl.stages_per_split, pl.stages_total, cm);
   } else {
-    hipLaunchKernelGGL((kmm_kernel<KS, kSmallR, KIND, NB, EXTRA, kSmallJT>), grid, block, 0, stream, Q.Xp,
+    hipLaunchKernelGGL((kmm_kernel<KS, kSmallR, KIND, NB, EXTRA, kSmallJT, SPLIT>), grid, block, 0, stream, Q.Xp,
                        Q.nrm, P.Xp, Vp, Ep, Part, Q.npad, P.d, pl.stages_per_split, pl.stages_total, cm);
   }
   EGP_HIP(hipGetLastError());
   return EGP_OK;
 }
 
-template <int KS, int KIND>
+template <int KS, int KIND, int SPLIT>
 int launch_cols(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, int extra, const f4* Vp,
                 const float* Ep, float* Part, int cm, hipStream_t stream) {
-  if (nb == 1 && !extra) return launch_shape<KS, KIND, 1, 0>(P, Q, pl, Vp, Ep, Part, cm, stream);
-  if (nb == 1 && extra) return launch_shape<KS, KIND, 1, 1>(P, Q, pl, Vp, Ep, Part, cm, stream);
-  if (nb == 2 && !extra) return launch_shape<KS, KIND, 2, 0>(P, Q, pl, Vp, Ep, Part, cm, stream);
-  return launch_shape<KS, KIND, 2, 1>(P, Q, pl, Vp, Ep, Part, cm, stream);
+  if (nb == 1 && !extra) return launch_shape<KS, KIND, 1, 0, SPLIT>(P, Q, pl, Vp, Ep, Part, cm, stream);
+  if (nb == 1 && extra) return launch_shape<KS, KIND, 1, 1, SPLIT>(P, Q, pl, Vp, Ep, Part, cm, stream);
+  if (nb == 2 && !extra) return launch_shape<KS, KIND, 2, 0, SPLIT>(P, Q, pl, Vp, Ep, Part, cm, stream);
+  return launch_shape<KS, KIND, 2, 1, SPLIT>(P, Q, pl, Vp, Ep, Part, cm, stream);
 }
 
-template <int KS>
+template <int KS, int SPLIT>
 int launch_kind(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, int extra, const f4* Vp,
                 const float* Ep, float* Part, int cm, hipStream_t stream) {
   switch (P.kernel_type) {
-    case EGP_RBF: return launch_cols<KS, EGP_RBF>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
-    case EGP_MATERN32: return launch_cols<KS, EGP_MATERN32>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
-    default: return launch_cols<KS, EGP_MATERN52>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case EGP_RBF: return launch_cols<KS, EGP_RBF, SPLIT>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case EGP_MATERN32: return launch_cols<KS, EGP_MATERN32, SPLIT>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    default: return launch_cols<KS, EGP_MATERN52, SPLIT>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
   }
 }
+
+template <int SPLIT>
+int launch_all_ks(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, int extra, const f4* Vp,
+                  const float* Ep, float* Part, int cm, hipStream_t stream) {
+  switch (P.ks) {
+    case 1: return launch_kind<1, SPLIT>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 2: return launch_kind<2, SPLIT>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 3: return launch_kind<3, SPLIT>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 4: return launch_kind<4, SPLIT>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 5: return launch_kind<5, SPLIT>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 6: return launch_kind<6, SPLIT>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 7: return launch_kind<7, SPLIT>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 8: return launch_kind<8, SPLIT>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    default: return fail(EGP_ERR_ARG, "d = %d needs %d k-steps; this build supports d <= 31", P.d, P.ks);
+  }
+}
+
+// defined in kmm_split.hip: the SPLIT = 1 instantiations and the in-place split of a packed V
+int launch_all_ks_split(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, int extra, const f4* Vp,
+                        const float* Ep, float* Part, int cm, hipStream_t stream);
+void launch_split_vp(f4* Vp, int64_t count, hipStream_t stream);
 
 }  // namespace kmm_detail
 

@@ -109,3 +109,45 @@ def test_kmm_argument_errors(egp):
     with pytest.raises(egp.EgpError) as ei:
         egp.kmm(X, V, [1.0, 1.0, 1.0], 1.0, 0.1, 0, ws=small)
     assert ei.value.code == -2
+
+
+def _set_mode(egp, mode):
+    import ctypes as C
+    L = egp.lib()
+    L.egp_set_kmm_mode.argtypes = [C.c_int32]
+    assert L.egp_set_kmm_mode(mode) == 0
+    assert L.egp_get_kmm_mode() == mode
+
+
+@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52])
+@pytest.mark.parametrize("n,d,t", [(257, 11, 16), (2049, 18, 17), (3001, 25, 16), (777, 31, 33), (600, 2, 40)])
+def test_kmm_split_bf16_mode(egp, kind, n, d, t):
+    """The bf16-split contraction (reported separately from the fp32 mode) meets the same 1e-4 bound."""
+    rng = np.random.default_rng(7 * n + d + t + kind)
+    X = rng.uniform(-1, 1, (n, d)).astype(np.float32)
+    V = rng.standard_normal((n, t)).astype(np.float32)
+    ls = np.exp(rng.uniform(np.log(0.3), np.log(3.0), d)).astype(np.float32)
+    ref = orc.kmm(X, V, orc.Hyper(kind, ls, 1.7, 0.3))
+    try:
+        _set_mode(egp, 1)
+        got = _run(egp, X, V, ls, 1.7, 0.3, kind)
+    finally:
+        _set_mode(egp, 0)
+    err = _rel(got, ref)
+    assert err <= KMM_TOL, err
+    with pytest.raises(AssertionError):
+        _set_mode(egp, 5)
+
+
+def test_kmm_split_bf16_c2_recipe_rows(egp):
+    w = make_workload("C2", n=40000)
+    ref_rows = np.random.default_rng(7).choice(w.n, 128, replace=False)
+    ref = orc.kmm_rows(w.X, w.V, orc.Hyper(w.kernel_type, w.lengthscales, w.outputscale, w.noise), ref_rows)
+    try:
+        _set_mode(egp, 1)
+        got = _run(egp, w.X, w.V, w.lengthscales, w.outputscale, w.noise, w.kernel_type)
+    finally:
+        _set_mode(egp, 0)
+    err = _rel(got[ref_rows], ref)
+    print("C2-recipe split-mode rel err", err)
+    assert err <= KMM_TOL
