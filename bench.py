@@ -137,27 +137,31 @@ def main():
                      "flops_per_entry": fpe, "pack_epilogue_ms_per_step": pack_ms / args.steps},
     }
 
-    # ---- the same product with the bf16-split contraction (egp_set_kmm_mode), reported separately ----
+    # ---- the same product in the two bf16-split modes (egp_set_kmm_mode), reported separately ----
     lib.egp_set_kmm_mode.argtypes = [C.c_int32]
-    lib.egp_set_kmm_mode(1)
-    step()
-    torch.cuda.synchronize()
-    lib.egp_profile_enable(1)
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
+    split_out = {}
+    for mode, key, what in ((1, "split_bf16_mode", "f32 distances and transform; tile x V contraction as a 3-term "
+                             "bf16 hi/lo split on the bf16 MFMA with fp32 accumulation"),
+                            (2, "split_bf16_all_mode", "as split_bf16_mode, and the distance step as a 6-term split "
+                             "of three exact bf16 parts per coordinate, fp32 accumulation")):
+        lib.egp_set_kmm_mode(mode)
         step()
-    torch.cuda.synchronize()
-    swall = time.perf_counter() - t0
-    sk_ms, sk_n = prof_read(lib, 0)
-    lib.egp_profile_enable(0)
+        torch.cuda.synchronize()
+        lib.egp_profile_enable(1)
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        swall = time.perf_counter() - t0
+        sk_ms, sk_n = prof_read(lib, 0)
+        lib.egp_profile_enable(0)
+        split_out[key] = out.clone()
+        result[key] = {
+            "value": n * n / (swall / args.steps), "unit": "kernel entries/s", "ms_per_step": swall * 1e3 / args.steps,
+            "kernel_ms": sk_ms / max(sk_n, 1), "dtype": what,
+            "algorithmic_tflops": fpe * n * n / (sk_ms / max(sk_n, 1) * 1e-3) / 1e12,
+        }
     lib.egp_set_kmm_mode(0)
-    split_out = out.clone()
-    result["split_bf16_mode"] = {
-        "value": n * n / (swall / args.steps), "unit": "kernel entries/s", "ms_per_step": swall * 1e3 / args.steps,
-        "kernel_ms": sk_ms / max(sk_n, 1), "dtype": "f32 distances and transform; tile x V contraction as a 3-term "
-        "bf16 hi/lo split on the bf16 MFMA with fp32 accumulation",
-        "algorithmic_tflops": fpe * n * n / (sk_ms / max(sk_n, 1) * 1e-3) / 1e12,
-    }
     step()                      # leave `out` holding the fp32-mode product for the parity sample below
     torch.cuda.synchronize()
 
@@ -300,9 +304,9 @@ def main():
             "host_cpus": os.cpu_count(),
         }
         result["parity_sampled_rows_rel_err"] = float(np.linalg.norm(got - ref) / np.linalg.norm(ref))
-        got_s = split_out.cpu().numpy()[rows].astype(np.float64)
-        result["split_bf16_mode"]["parity_sampled_rows_rel_err"] = float(np.linalg.norm(got_s - ref) /
-                                                                         np.linalg.norm(ref))
+        for key, so in split_out.items():
+            got_s = so.cpu().numpy()[rows].astype(np.float64)
+            result[key]["parity_sampled_rows_rel_err"] = float(np.linalg.norm(got_s - ref) / np.linalg.norm(ref))
 
     print(json.dumps(result))
 

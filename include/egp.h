@@ -192,8 +192,11 @@ size_t egp_precond_apply_ws_bytes(int64_t n, int32_t t, int32_t rank);
  *                       (16 significant bits per factor); distances and the transform stay in fp32. Faster,
  *                       because the bf16 MFMA co-executes with the transform's VALU work on this chip; its
  *                       error and speed are reported separately from the fp32 figures.
+ *   EGP_KMM_SPLIT_BF16_ALL  additionally the distance step: scaled points are carried as three bf16 parts
+ *                       (24 significant bits, exact) and the six products above the fp32 rounding level are
+ *                       accumulated in fp32 on the bf16 MFMA. Faster again; also reported separately.
  * Affects egp_kmm, egp_kmm_cross, egp_mbcg, egp_lanczos, egp_mll. Returns EGP_ERR_ARG for an unknown mode. */
-typedef enum { EGP_KMM_FP32 = 0, EGP_KMM_SPLIT_BF16 = 1 } egp_kmm_mode_t;
+typedef enum { EGP_KMM_FP32 = 0, EGP_KMM_SPLIT_BF16 = 1, EGP_KMM_SPLIT_BF16_ALL = 2 } egp_kmm_mode_t;
 int egp_set_kmm_mode(int32_t mode);
 int egp_get_kmm_mode(void);
 

@@ -34,6 +34,8 @@ struct Prepared {   // device arrays carved from a workspace by prepare_points()
   float* Xp;        // [npad/16][KS][64]
   float* nrm;       // [npad] squared norms of the scaled points (0 for padding)
   float* mean;      // [d] centre subtracted before scaling
+  void* XbC;        // bf16-split column operands (filled in mode EGP_KMM_SPLIT_BF16_ALL only)
+  void* XbR;        // bf16-split row operands
   int64_t n, npad;
   int d, ks, kernel_type;
   float outputscale, noise;

@@ -240,6 +240,9 @@ size_t prepared_bytes(int64_t n, int d) {
   b += round_up((size_t)npad * sizeof(float), 256);            // nrm
   b += round_up((size_t)kMeanBlocks * 64 * sizeof(float), 256);  // partial sums
   b += 256;                                                    // mean
+  const int ks16 = (d + 1 + 15) / 16;
+  b += round_up((size_t)(npad / 16) * ks16 * 3 * 1024, 256);   // XbC
+  b += round_up((size_t)(npad / 16) * ks16 * 2 * 1024, 256);   // XbR
   return b;
 }
 
@@ -256,6 +259,11 @@ int prepare_points(const float* X, int64_t n, const egp_hyper_t* h, void* ws, Pr
   float* partial = reinterpret_cast<float*>(w);
   w += round_up((size_t)kMeanBlocks * 64 * sizeof(float), 256);
   float* mean = reinterpret_cast<float*>(w);
+  w += 256;
+  const int ks16 = (d + 1 + 15) / 16;
+  out->XbC = w;
+  w += round_up((size_t)(npad / 16) * ks16 * 3 * 1024, 256);
+  out->XbR = w;
   out->mean = mean;
   out->n = n;
   out->npad = npad;
@@ -279,14 +287,27 @@ int prepare_points(const float* X, int64_t n, const egp_hyper_t* h, void* ws, Pr
   }
   hipLaunchKernelGGL(pack_points, dim3((unsigned)((npad + 255) / 256)), dim3(256), 0, stream, X, n, npad, d,
                      ks, mean, sc, out->Xp, out->nrm);
+  if (kmm_mode() == EGP_KMM_SPLIT_BF16_ALL) launch_pack_points_bf(*out, stream);
   EGP_HIP(hipGetLastError());
   return EGP_OK;
 }
 
 namespace {
 
+Plan plan_for_mode(int64_t npad_rows, int64_t npad_cols, int ks, int d, int nb, int extra) {
+  return kmm_mode() == EGP_KMM_SPLIT_BF16_ALL ? make_plan_bf(npad_rows, npad_cols, d, nb, extra)
+                                              : make_plan(npad_rows, npad_cols, ks);
+}
+int max_splits(int64_t npad_rows, int64_t npad_cols) {     // over every launch shape of every mode
+  const int a = make_plan(npad_rows, npad_cols, 1).splits;
+  const int b = make_plan_bf(npad_rows, npad_cols, 1, 1, 0).splits;
+  const int c = make_plan_bf(npad_rows, npad_cols, 1, 2, 1).splits;
+  return a > b ? (a > c ? a : c) : (b > c ? b : c);
+}
+
 int launch_ks(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, int extra, f4* Vp, const float* Ep,
-              float* Part, int cm, hipStream_t stream) {
+              float* Part, int cm, hipStream_t stream, void* Vb) {
+  if (kmm_mode() == EGP_KMM_SPLIT_BF16_ALL) return launch_all_bf(P, Q, pl, nb, extra, Vp, Vb, Ep, Part, cm, stream);
   if (kmm_mode() == EGP_KMM_SPLIT_BF16) {
     {
       ProfScope prof(kProfPack, stream);
@@ -305,12 +326,14 @@ static int widest_ts(int t) { return t <= 16 ? 16 : (t == 17 ? 17 : (t <= 32 ? 3
 
 size_t kmm_cross_ws_bytes(int64_t n_rows, int64_t n_cols, int t) {
   const int64_t prow = padded_points(n_rows), pcol = padded_points(n_cols);
-  const Plan pl = make_plan(prow, pcol, 1);   // the split count depends on the shape class only (all KS <= 8 alike)
+  // the split count depends on the shape class only; take the larger of the fp32 and the all-bf16 plans
+  const int splits = max_splits(prow, pcol);
   const int nb = t > 17 ? 2 : 1;
   size_t b = 0;
   b += round_up((size_t)pcol * nb * 16 * sizeof(float), 256);                    // Vp
   b += round_up((size_t)pcol * sizeof(float), 256);                              // Ep
-  b += round_up((size_t)pl.splits * prow * widest_ts(t) * sizeof(float), 256);   // Part
+  b += round_up((size_t)splits * prow * widest_ts(t) * sizeof(float), 256);      // Part
+  b += round_up((size_t)pcol * nb * 32 * sizeof(float), 256);                    // split V of the all-bf16 mode
   return b;
 }
 
@@ -326,7 +349,7 @@ int kmm_cross(const Prepared& P, const Prepared& Q, const float* V, int t, float
               hipStream_t stream, int64_t v_ld) {
   const int64_t npad = P.npad;
   const bool square = Q.Xp == P.Xp;
-  const Plan pl = make_plan(Q.npad, npad, P.ks);
+  const int splits_max = max_splits(Q.npad, npad);
   char* w = static_cast<char*>(ws2);
   const int tg_max = t > 33 ? 33 : t;
   const int nb_max = tg_max > 17 ? 2 : 1;
@@ -335,6 +358,8 @@ int kmm_cross(const Prepared& P, const Prepared& Q, const float* V, int t, float
   float* Ep = reinterpret_cast<float*>(w);
   w += round_up((size_t)npad * sizeof(float), 256);
   float* Part = reinterpret_cast<float*>(w);
+  w += round_up((size_t)splits_max * Q.npad * widest_ts(t) * sizeof(float), 256);
+  void* Vb = w;
 
   int c0 = 0;
   while (c0 < t) {
@@ -346,6 +371,7 @@ int kmm_cross(const Prepared& P, const Prepared& Q, const float* V, int t, float
     else if (rem == 33) { nb = 2; extra = 1; tg = 33; }
     else { nb = 2; extra = 0; tg = 32; }
     const int ts = 16 * nb + extra;
+    const Plan pl = plan_for_mode(Q.npad, npad, P.ks, P.d, nb, extra);
     if (v_ld > 0) {
       // columns stored one after the other (e.g. Lanczos vectors): 16 columns per block, the odd one as Ep
       ProfScope prof(kProfPack, stream);
@@ -361,7 +387,7 @@ int kmm_cross(const Prepared& P, const Prepared& Q, const float* V, int t, float
       ProfScope prof(kProfPack, stream);
       launch_pack_rhs(V, P.n, npad, t, c0, nb, extra, Vp, Ep, stream);
     }
-    const int rc = launch_ks(P, Q, pl, nb, extra, Vp, Ep, Part, 0, stream);
+    const int rc = launch_ks(P, Q, pl, nb, extra, Vp, Ep, Part, 0, stream, Vb);
     if (rc != EGP_OK) return rc;
     const int64_t outs = Q.n * tg;
     ProfScope eprof(kProfPack, stream);
@@ -385,15 +411,18 @@ int kmm_cm_dot_blocks(int64_t npad) {
 int kmm_core_cm(const Prepared& P, const float* V, int t, float* out, void* ws2, float* dot_part, int dot_ld,
                 hipStream_t stream) {
   const int64_t npad = P.npad;
-  const Plan pl = make_plan(npad, npad, P.ks);
+  const int splits_max = max_splits(npad, npad);
   char* w = static_cast<char*>(ws2);
   const int nb = t > 17 ? 2 : 1;
   const int extra = (t == 17 || t == 33) ? 1 : 0;
+  const Plan pl = plan_for_mode(npad, npad, P.ks, P.d, nb, extra);
   const int ts = 16 * nb + extra;
   f4* Vp = reinterpret_cast<f4*>(w);
   w += round_up((size_t)npad * nb * 16 * sizeof(float), 256);
   w += round_up((size_t)npad * sizeof(float), 256);      // the row-major path's extra-column buffer (unused here)
   float* Part = reinterpret_cast<float*>(w);
+  w += round_up((size_t)splits_max * npad * widest_ts(t) * sizeof(float), 256);
+  void* Vb = w;
   {
     ProfScope prof(kProfPack, stream);
     const int64_t total = (npad >> 4) * nb * 64;
@@ -402,7 +431,7 @@ int kmm_core_cm(const Prepared& P, const float* V, int t, float* out, void* ws2,
   }
   // the 17th / 33rd column is consumed straight from the state array
   const float* Ep = extra ? V + (int64_t)(t - 1) * npad : nullptr;
-  const int rc = launch_ks(P, P, pl, nb, extra, Vp, Ep, Part, 1, stream);
+  const int rc = launch_ks(P, P, pl, nb, extra, Vp, Ep, Part, 1, stream, Vb);
   if (rc != EGP_OK) return rc;
   ProfScope eprof(kProfPack, stream);
   hipLaunchKernelGGL(kmm_epilogue_cm, dim3(kmm_cm_dot_blocks(npad), t), dim3(256), 0, stream, Part, pl.splits, npad,

@@ -95,46 +95,34 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel(const float* __restrict__ X
 
   const f4* Xg = reinterpret_cast<const f4*>(Xp);
   const f4* Eg = reinterpret_cast<const f4*>(Ep);
-  f4 px[NX], pv[NV], pe;
-
-  auto fetch = [&](int st) {
+  // Stage copy global -> LDS without passing through registers: the 64 lanes of a wave deposit 16 bytes each
+  // at consecutive LDS addresses from a wave-uniform base (the packed arrays are already in operand order, so
+  // a stage is a straight copy).
+  auto issue = [&](int st, int buf) {
     const int64_t xoff = (int64_t)st * XF4, voff = (int64_t)st * VF4, eoff = (int64_t)st * EF4;
 #pragma unroll
-    for (int k = 0; k < NX; ++k) {
-      const int idx = tid + k * 256;
-      if (XF4 % 256 == 0 || idx < XF4) px[k] = Xg[xoff + idx];
-    }
+    for (int k = 0; k < NX; ++k)
+      if (XF4 % 256 == 0 || k * 256 + wave * 64 < XF4)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Xg + xoff + tid + k * 256),
+                                         (__attribute__((address_space(3))) void*)(&Xs[buf][k * 256 + wave * 64]), 16, 0, 0);
 #pragma unroll
-    for (int k = 0; k < NV; ++k) {
-      const int idx = tid + k * 256;
-      if (VF4 % 256 == 0 || idx < VF4) pv[k] = Vp[voff + idx];
-    }
-    if (EXTRA && tid < EF4) pe = Eg[eoff + tid];
-  };
-  auto stash = [&](int buf) {
-#pragma unroll
-    for (int k = 0; k < NX; ++k) {
-      const int idx = tid + k * 256;
-      if (XF4 % 256 == 0 || idx < XF4) Xs[buf][idx] = px[k];
-    }
-#pragma unroll
-    for (int k = 0; k < NV; ++k) {
-      const int idx = tid + k * 256;
-      if (VF4 % 256 == 0 || idx < VF4) Vs[buf][idx] = pv[k];
-    }
-    if (EXTRA && tid < EF4) Es[buf][tid] = pe;
+    for (int k = 0; k < NV; ++k)
+      if (VF4 % 256 == 0 || k * 256 + wave * 64 < VF4)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Vp + voff + tid + k * 256),
+                                         (__attribute__((address_space(3))) void*)(&Vs[buf][k * 256 + wave * 64]), 16, 0, 0);
+    if (EXTRA && tid < EF4)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Eg + eoff + tid),
+                                       (__attribute__((address_space(3))) void*)(&Es[buf][0]), 16, 0, 0);
   };
 
-  if (st_begin < st_end) {
-    fetch(st_begin);
-    stash(0);
-  }
+  if (st_begin < st_end) issue(st_begin, 0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 
   for (int st = st_begin; st < st_end; ++st) {
     const int buf = (st - st_begin) & 1;
     const bool more = st + 1 < st_end;
-    if (more) fetch(st + 1);
+    if (more) issue(st + 1, buf ^ 1);
 
     const float* xs = reinterpret_cast<const float*>(Xs[buf]);
 #pragma unroll 2
@@ -195,7 +183,7 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel(const float* __restrict__ X
         }
       }
     }
-    if (more) stash(buf ^ 1);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
   }
 
@@ -321,6 +309,11 @@ int launch_all_ks(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, 
 int launch_all_ks_split(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, int extra, const f4* Vp,
                         const float* Ep, float* Part, int cm, hipStream_t stream);
 void launch_split_vp(f4* Vp, int64_t count, hipStream_t stream);
+// defined in kmm_bf.hip: every contraction on the bf16 MFMA
+Plan make_plan_bf(int64_t npad_rows, int64_t npad_cols, int d, int nb, int extra);
+void launch_pack_points_bf(const Prepared& P, hipStream_t stream);
+int launch_all_bf(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, int extra, const f4* Vp, void* Vb,
+                  const float* Ep, float* Part, int cm, hipStream_t stream);
 
 }  // namespace kmm_detail
 

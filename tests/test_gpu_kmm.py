@@ -119,17 +119,19 @@ def _set_mode(egp, mode):
     assert L.egp_get_kmm_mode() == mode
 
 
+@pytest.mark.parametrize("mode", [1, 2])
 @pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52])
-@pytest.mark.parametrize("n,d,t", [(257, 11, 16), (2049, 18, 17), (3001, 25, 16), (777, 31, 33), (600, 2, 40)])
-def test_kmm_split_bf16_mode(egp, kind, n, d, t):
-    """The bf16-split contraction (reported separately from the fp32 mode) meets the same 1e-4 bound."""
+@pytest.mark.parametrize("n,d,t", [(257, 11, 16), (2049, 18, 17), (3001, 25, 16), (777, 31, 33), (600, 2, 40),
+                                   (1, 1, 1), (1000, 15, 5), (513, 16, 17)])
+def test_kmm_split_bf16_mode(egp, mode, kind, n, d, t):
+    """The bf16-split modes (reported separately from the fp32 mode) meet the same 1e-4 bound."""
     rng = np.random.default_rng(7 * n + d + t + kind)
     X = rng.uniform(-1, 1, (n, d)).astype(np.float32)
     V = rng.standard_normal((n, t)).astype(np.float32)
     ls = np.exp(rng.uniform(np.log(0.3), np.log(3.0), d)).astype(np.float32)
     ref = orc.kmm(X, V, orc.Hyper(kind, ls, 1.7, 0.3))
     try:
-        _set_mode(egp, 1)
+        _set_mode(egp, mode)
         got = _run(egp, X, V, ls, 1.7, 0.3, kind)
     finally:
         _set_mode(egp, 0)
@@ -139,12 +141,13 @@ def test_kmm_split_bf16_mode(egp, kind, n, d, t):
         _set_mode(egp, 5)
 
 
-def test_kmm_split_bf16_c2_recipe_rows(egp):
+@pytest.mark.parametrize("mode", [1, 2])
+def test_kmm_split_bf16_c2_recipe_rows(egp, mode):
     w = make_workload("C2", n=40000)
     ref_rows = np.random.default_rng(7).choice(w.n, 128, replace=False)
     ref = orc.kmm_rows(w.X, w.V, orc.Hyper(w.kernel_type, w.lengthscales, w.outputscale, w.noise), ref_rows)
     try:
-        _set_mode(egp, 1)
+        _set_mode(egp, mode)
         got = _run(egp, w.X, w.V, w.lengthscales, w.outputscale, w.noise, w.kernel_type)
     finally:
         _set_mode(egp, 0)
