@@ -148,6 +148,27 @@ int egp_mll(const float* X, int64_t n, const float* y, const float* W1, const fl
             void* ws, size_t ws_bytes, void* stream);
 size_t egp_mll_ws_bytes(int64_t n, int32_t d, int32_t tp, int32_t rank, int32_t max_iter);
 
+/* Hyper-parameter fitting: `steps` Adam ascent steps on the log marginal likelihood (paper, Experiment details:
+ * Adam with step size 0.1, a few steps on the full data after pre-training on a subset — pre-training is this
+ * same call on a subset; learned noise kept above a floor). Each step is one egp_mll evaluation with the given
+ * probe draws (the same draws at every step). Parameters move in log-space: l_k, outputscale, and
+ * noise - noise_floor stay positive. The objective is L / n.
+ *   lengthscales  host, d floats: start values in, fitted values out
+ *   outputscale, noise  host scalars: start values in, fitted values out
+ *   last          host, optional: the evaluation at the final parameters
+ *   mll_history   host, optional, steps + 1 doubles: L before each step and at the end
+ * Workspace: egp_mll_ws_bytes. Synchronises on `stream`. */
+typedef struct {
+  int32_t steps;      /* >= 0 */
+  float lr;           /* Adam step size (0.1 in the paper) */
+  float beta1, beta2, eps;   /* 0.9, 0.999, 1e-8 */
+  float noise_floor;  /* >= 0 (0.1 in the paper's largest runs) */
+} egp_adam_t;
+int egp_train_adam(const float* X, int64_t n, const float* y, const float* W1, const float* W2, int32_t tp,
+                   int32_t kernel_type, int32_t d, float* lengthscales, float* outputscale, float* noise,
+                   int32_t rank, int32_t max_iter, float tol, const egp_adam_t* opt, egp_mll_result_t* last,
+                   double* mll_history, void* ws, size_t ws_bytes, void* stream);
+
 /* Host-only helper of egp_mll, exported for testing: e1^T log(T) e1 of the symmetric positive definite
  * tridiagonal T with diagonal diag[0..m) and off-diagonal off[0..m-1). Returns 0, or EGP_ERR_BREAKDOWN
  * when T is not positive definite. */

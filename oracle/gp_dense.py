@@ -38,7 +38,7 @@ __all__ = [
     "kmm_rows", "dkernel_dlengthscale", "kmm_grad", "kmm_grad_rows", "chol_solve", "logdet",
     "mll", "mll_grad", "pivoted_cholesky", "precond_matrix", "precond_solve", "precond_logdet",
     "pcg", "tridiag_from_cg", "slq_quadrature", "slq_logdet", "probes_with_cov_P",
-    "mll_stochastic_terms", "predict_exact", "lanczos", "predict_var_lanczos",
+    "mll_stochastic_terms", "predict_exact", "lanczos", "predict_var_lanczos", "train_adam",
 ]
 
 
@@ -391,3 +391,48 @@ def predict_var_lanczos(Kq, Q, alpha, beta, outputscale):
     T = np.diag(alpha) + (np.diag(beta, 1) + np.diag(beta, -1) if m > 1 else 0.0)
     G = np.asarray(Kq, np.float64) @ np.asarray(Q, np.float64).T
     return outputscale - np.sum(G * np.linalg.solve(T, G.T).T, axis=1)
+
+
+def train_adam(X, y, hyper: Hyper, steps, lr=0.1, noise_floor=0.0, rank=0, W1=None, W2=None,
+               beta1=0.9, beta2=0.999, eps=1e-8):
+    """Adam ascent on L / n in log-parameters phi = (log l_k, log s, log(noise - floor)) (Experiment details:
+    Adam, step size 0.1, noise kept above a floor). With W2 given, value and gradient are the stochastic
+    estimates of mll_stochastic_terms with probes of covariance P built from the Rademacher draws W1, W2 and a
+    rank-`rank` pivoted Cholesky recomputed at every step; with W2 = None they are the exact dense ones.
+    Returns (final Hyper, list of L before each step and at the end)."""
+    X = np.asarray(X, np.float64)
+    y = np.asarray(y, np.float64)
+    d = len(hyper.lengthscales)
+    n = len(y)
+    phi = np.concatenate([np.log(hyper.lengthscales), [np.log(hyper.outputscale)],
+                          [np.log(max(hyper.noise - noise_floor, 1e-4 * (noise_floor if noise_floor > 0 else 1.0)))]])
+    m = np.zeros(d + 2)
+    v = np.zeros(d + 2)
+    history = []
+
+    def current():
+        return Hyper(hyper.kernel_type, np.exp(phi[:d]), np.exp(phi[d]), noise_floor + np.exp(phi[d + 1]))
+
+    def evaluate(h):
+        if W2 is None:
+            return mll(X, y, h), mll_grad(X, y, h)
+        if rank > 0:
+            L, _ = pivoted_cholesky(kernel_matrix(X, X, h), rank)
+            Z = probes_with_cov_P(L, h.noise, W1, W2)
+        else:
+            L, Z = None, np.asarray(W2, np.float64)
+        out = mll_stochastic_terms(X, y, h, Z, L)
+        return out["mll"], out["grad"]
+
+    for step in range(steps + 1):
+        h = current()
+        value, grad = evaluate(h)
+        history.append(value)
+        if step == steps:
+            break
+        theta = np.concatenate([h.lengthscales, [h.outputscale], [np.exp(phi[d + 1])]])
+        g = theta * grad / n
+        m = beta1 * m + (1 - beta1) * g
+        v = beta2 * v + (1 - beta2) * g * g
+        phi = phi + lr * (m / (1 - beta1 ** (step + 1))) / (np.sqrt(v / (1 - beta2 ** (step + 1))) + eps)
+    return current(), history

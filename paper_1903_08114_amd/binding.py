@@ -26,6 +26,11 @@ class _MllResult(C.Structure):
                 ("iters", C.c_int32), ("precond_rank", C.c_int32), ("rel_resid_max", C.c_float)]
 
 
+class _Adam(C.Structure):
+    _fields_ = [("steps", C.c_int32), ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
+                ("eps", C.c_float), ("noise_floor", C.c_float)]
+
+
 class _Precond(C.Structure):
     _fields_ = [("rank", C.c_int32), ("L", C.c_void_p), ("pivots", C.POINTER(C.c_int32)),
                 ("small", C.POINTER(C.c_double)), ("small_dev", C.c_void_p)]
@@ -93,6 +98,12 @@ def lib():
         L.egp_mll.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                               C.POINTER(_Hyper), C.c_int32, C.c_int32, C.c_float, C.POINTER(_MllResult),
                               C.c_void_p, C.c_size_t, C.c_void_p]
+        L.egp_train_adam.restype = C.c_int
+        L.egp_train_adam.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                     C.c_int32, C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_float),
+                                     C.POINTER(C.c_float), C.c_int32, C.c_int32, C.c_float, C.POINTER(_Adam),
+                                     C.POINTER(_MllResult), C.POINTER(C.c_double), C.c_void_p, C.c_size_t,
+                                     C.c_void_p]
         L.egp_tridiag_logquad.restype = C.c_int
         L.egp_tridiag_logquad.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_int32,
                                           C.POINTER(C.c_double)]
@@ -402,3 +413,27 @@ def predict(Xq, X, a, lengthscales, outputscale, noise, kernel_type, cache=None,
         _check(L.egp_predict(_dev(Xq, "Xq"), nq, _dev(X, "X"), n, C.byref(h), _dev(a, "a"), None, 0, None, None,
                              _dev(mean, "mean"), None, C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
     return mean, var
+
+
+def train_adam(X, y, W1, W2, lengthscales, outputscale, noise, kernel_type, rank=100, max_iter=100, tol=1.0,
+               steps=3, lr=0.1, noise_floor=0.0, beta1=0.9, beta2=0.999, eps=1e-8, ws=None):
+    """`steps` Adam ascent steps on the log marginal likelihood (egp_train_adam).
+    Returns dict: lengthscales, outputscale, noise (fitted), mll_history (steps + 1), last (final evaluation)."""
+    import numpy as np
+    L = lib()
+    n, d = X.shape
+    tp = W2.shape[1]
+    ls = (C.c_float * d)(*[float(v) for v in lengthscales])
+    s_io, n_io = C.c_float(float(outputscale)), C.c_float(float(noise))
+    opt = _Adam(int(steps), float(lr), float(beta1), float(beta2), float(eps), float(noise_floor))
+    res = _MllResult()
+    hist = np.zeros(steps + 1, dtype=np.float64)
+    if ws is None:
+        ws = _workspace(L.egp_mll_ws_bytes(n, d, tp, rank, max_iter), X.device)
+    _check(L.egp_train_adam(_dev(X, "X"), n, _dev(y, "y"), _dev(W1, "W1") if rank > 0 else None, _dev(W2, "W2"), tp,
+                            int(kernel_type), d, ls, C.byref(s_io), C.byref(n_io), int(rank), int(max_iter),
+                            float(tol), C.byref(opt), C.byref(res), hist.ctypes.data_as(C.POINTER(C.c_double)),
+                            C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
+    return {"lengthscales": np.array(list(ls), dtype=np.float64), "outputscale": float(s_io.value),
+            "noise": float(n_io.value), "mll_history": hist,
+            "last": {"mll": res.mll, "grad": np.array(res.grad[:d + 2]), "iters": res.iters}}

@@ -244,6 +244,37 @@ int egp_mll(const float* X, int64_t n, const float* y, const float* W1, const fl
   return mll_core(X, n, y, W1, W2, tp, h, rank, max_iter, tol, out, ws, static_cast<hipStream_t>(stream));
 }
 
+int egp_train_adam(const float* X, int64_t n, const float* y, const float* W1, const float* W2, int32_t tp,
+                   int32_t kernel_type, int32_t d, float* lengthscales, float* outputscale, float* noise,
+                   int32_t rank, int32_t max_iter, float tol, const egp_adam_t* opt, egp_mll_result_t* last,
+                   double* mll_history, void* ws, size_t ws_bytes, void* stream) {
+  if (lengthscales == nullptr || outputscale == nullptr || noise == nullptr || opt == nullptr)
+    return fail(EGP_ERR_ARG, "lengthscales / outputscale / noise / opt is NULL");
+  if (opt->steps < 0 || opt->steps > 100000 || !(opt->lr > 0.f) || !(opt->beta1 >= 0.f && opt->beta1 < 1.f) ||
+      !(opt->beta2 >= 0.f && opt->beta2 < 1.f) || !(opt->eps > 0.f) || !(opt->noise_floor >= 0.f))
+    return fail(EGP_ERR_ARG, "bad Adam settings");
+  egp_hyper_t h = {kernel_type, d, lengthscales, *outputscale, *noise};
+  int rc;
+  if ((rc = validate_hyper(&h)) != EGP_OK) return rc;
+  if ((rc = check_n(n)) != EGP_OK) return rc;
+  if (tp < 1 || tp > 32) return fail(EGP_ERR_ARG, "tp = %d outside 1..32", tp);
+  if (rank < 0 || rank > EGP_RANK_MAX || rank > n) return fail(EGP_ERR_ARG, "rank = %d outside 0..min(n, %d)", rank, EGP_RANK_MAX);
+  if (max_iter < 1 || max_iter > 100000) return fail(EGP_ERR_ARG, "max_iter = %d outside 1..100000", max_iter);
+  if (!(tol >= 0.f)) return fail(EGP_ERR_ARG, "tol must be >= 0");
+  if ((rc = validate_ptr(X, "X")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(y, "y")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(W2, "W2")) != EGP_OK) return rc;
+  if (rank > 0 && (rc = validate_ptr(W1, "W1")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(ws, "ws")) != EGP_OK) return rc;
+  const size_t need = mll_ws_bytes_core(n, d, tp, rank, max_iter);
+  if (ws_bytes < need) return fail(EGP_ERR_WS, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, need);
+  rc = train_adam_core(X, n, y, W1, W2, tp, &h, lengthscales, rank, max_iter, tol, opt, last, mll_history, ws,
+                       static_cast<hipStream_t>(stream));
+  *outputscale = h.outputscale;
+  *noise = h.noise;
+  return rc;
+}
+
 int egp_tridiag_logquad(const double* diag, const double* off, int32_t m, double* out) {
   if (diag == nullptr || out == nullptr || m < 1 || (m > 1 && off == nullptr))
     return fail(EGP_ERR_ARG, "bad tridiagonal arguments");

@@ -93,6 +93,10 @@ size_t mll_ws_bytes_core(int64_t n, int d, int tp, int rank, int max_iter);
 int mll_core(const float* X, int64_t n, const float* y, const float* W1, const float* W2, int tp,
              const egp_hyper_t* h, int rank_req, int max_iter, float tol, egp_mll_result_t* res, void* ws,
              hipStream_t stream);
+int train_adam_core(const float* X, int64_t n, const float* y, const float* W1, const float* W2, int tp,
+                    egp_hyper_t* h, float* lengthscales_io, int rank, int max_iter, float tol,
+                    const egp_adam_t* opt, egp_mll_result_t* last, double* mll_history, void* ws,
+                    hipStream_t stream);
 }  // namespace egp
 #include <vector>
 namespace egp {

@@ -316,4 +316,46 @@ int mll_core(const float* X, int64_t n, const float* y, const float* W1, const f
   return EGP_OK;
 }
 
+// Adam ascent on the log marginal likelihood in log-parameters (paper, Experiment details: hyper-parameters are
+// fitted with Adam, step size 0.1, a few steps on the full data after pre-training on a subset; the learned
+// noise is kept above a floor). Parameters: phi = (log l_1..log l_d, log s, log(noise - floor)); the gradient
+// with respect to phi is theta dL/dtheta by the chain rule. The objective is scaled by 1/n as is usual, which
+// Adam's normalisation makes immaterial. The same probe draws are used at every step.
+int train_adam_core(const float* X, int64_t n, const float* y, const float* W1, const float* W2, int tp,
+                    egp_hyper_t* h, float* lengthscales_io, int rank, int max_iter, float tol,
+                    const egp_adam_t* opt, egp_mll_result_t* last, double* mll_history, void* ws,
+                    hipStream_t stream) {
+  const int d = h->d, np = d + 2;
+  const double floor_ = opt->noise_floor > 0.f ? (double)opt->noise_floor : 0.0;
+  std::vector<double> phi(np), m(np, 0.0), v(np, 0.0);
+  for (int k = 0; k < d; ++k) phi[k] = log((double)lengthscales_io[k]);
+  phi[d] = log((double)h->outputscale);
+  double excess = (double)h->noise - floor_;
+  if (!(excess > 0.0)) excess = 1e-4 * (floor_ > 0.0 ? floor_ : 1.0);
+  phi[d + 1] = log(excess);
+  const double b1 = opt->beta1, b2 = opt->beta2, eps = opt->eps, lr = opt->lr;
+  egp_mll_result_t res;
+  for (int step = 0; step <= opt->steps; ++step) {
+    for (int k = 0; k < d; ++k) lengthscales_io[k] = (float)exp(phi[k]);
+    h->lengthscales = lengthscales_io;
+    h->outputscale = (float)exp(phi[d]);
+    h->noise = (float)(floor_ + exp(phi[d + 1]));
+    if (step == opt->steps && last == nullptr && mll_history == nullptr) break;
+    const int rc = mll_core(X, n, y, W1, W2, tp, h, rank, max_iter, tol, &res, ws, stream);
+    if (rc != EGP_OK) return rc;
+    if (mll_history) mll_history[step] = res.mll;
+    if (step == opt->steps) break;        // the last evaluation only reports the objective at the final parameters
+    for (int k = 0; k < np; ++k) {
+      const double theta = k < d ? exp(phi[k]) : (k == d ? exp(phi[d]) : exp(phi[d + 1]));
+      const double g = theta * res.grad[k] / (double)n;        // ascent direction on L / n in log-parameters
+      m[k] = b1 * m[k] + (1.0 - b1) * g;
+      v[k] = b2 * v[k] + (1.0 - b2) * g * g;
+      const double mh = m[k] / (1.0 - pow(b1, step + 1)), vh = v[k] / (1.0 - pow(b2, step + 1));
+      phi[k] += lr * mh / (sqrt(vh) + eps);
+    }
+  }
+  if (last) *last = res;
+  return EGP_OK;
+}
+
 }  // namespace egp

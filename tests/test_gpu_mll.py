@@ -58,3 +58,25 @@ def test_mll_matches_oracle_with_same_probes(egp, kind, rank):
     assert abs(got["mll"] - exact) <= 0.02 * abs(exact) + 2.0
     gexact = orc.mll_grad(X, y, h)
     assert np.all(np.abs(got["grad"] - gexact) <= 0.25 * np.abs(gexact) + 0.1 * np.abs(gexact).max())
+
+
+def test_train_adam_tracks_the_oracle_loop(egp):
+    """Three Adam steps with the same probe draws on both sides: parameter trajectories and objective values
+    agree up to fp32 effects; the noise floor holds."""
+    rng = np.random.default_rng(77)
+    n, d, tp, rank = 900, 2, 16, 10
+    X = well_separated_points(13, n, d)
+    y = (np.sin(5 * X[:, 0]) + np.cos(3 * X[:, 1]) + 0.2 * rng.standard_normal(n)).astype(np.float32)
+    ls0, s0, noise0, floor = np.array([0.9, 1.3], np.float32), 0.8, 0.4, 0.1
+    kind = orc.RBF
+    w1 = rademacher(rng, (rank, tp))
+    w2 = rademacher(rng, (n, tp))
+    got = egp.train_adam(_cuda(X), _cuda(y), _cuda(w1), _cuda(w2), ls0, s0, noise0, kind, rank=rank, max_iter=400,
+                         tol=1e-5, steps=3, lr=0.1, noise_floor=floor)
+    href, hist = orc.train_adam(X, y, orc.Hyper(kind, ls0, s0, noise0), steps=3, lr=0.1, noise_floor=floor,
+                                rank=rank, W1=w1, W2=w2)
+    assert np.allclose(got["lengthscales"], href.lengthscales, rtol=2e-2)
+    assert abs(got["outputscale"] - href.outputscale) <= 2e-2 * href.outputscale
+    assert abs(got["noise"] - href.noise) <= 2e-2 * href.noise and got["noise"] > floor
+    assert np.allclose(got["mll_history"], hist, rtol=3e-3, atol=0.5)
+    assert got["mll_history"][-1] > got["mll_history"][0]

@@ -171,3 +171,26 @@ def test_stochastic_mll_terms_within_monte_carlo_error():
     assert abs(out["mll"] - orc.mll(X, y, h)) < 0.5
     g = orc.mll_grad(X, y, h)
     assert np.all(np.abs(out["grad"] - g) <= 0.15 * np.abs(g) + 0.5)
+
+
+def test_adam_loop_pins():
+    """Oracle training loop: no-op at zero steps; the first Adam step moves every log-parameter by exactly
+    +-lr in the direction of its gradient sign; the exact objective rises with exact gradients."""
+    rng = np.random.default_rng(10)
+    n, d = 60, 2
+    X = well_separated_points(41, n, d)
+    y = np.sin(5 * X[:, 0]) + 0.3 * rng.standard_normal(n)
+    h0 = orc.Hyper(orc.RBF, [0.8, 0.8], 0.7, 0.6)
+    h_same, hist = orc.train_adam(X, y, h0, steps=0)
+    assert np.allclose(h_same.lengthscales, h0.lengthscales) and len(hist) == 1
+    assert abs(hist[0] - orc.mll(X, y, h0)) < 1e-12
+    floor = 0.05
+    h1, _ = orc.train_adam(X, y, h0, steps=1, lr=0.1, noise_floor=floor)
+    g = orc.mll_grad(X, y, orc.Hyper(orc.RBF, h0.lengthscales, h0.outputscale, h0.noise))
+    moved = np.log(np.concatenate([h1.lengthscales / h0.lengthscales, [h1.outputscale / h0.outputscale],
+                                   [(h1.noise - floor) / (h0.noise - floor)]]))
+    assert np.allclose(moved, 0.1 * np.sign(g), atol=1e-6)
+    _, hist = orc.train_adam(X, y, h0, steps=15, lr=0.05)
+    assert hist[-1] > hist[0] + 1.0 and all(b > a - 0.05 for a, b in zip(hist, hist[1:]))
+    hf, _ = orc.train_adam(X, y, h0, steps=3, lr=0.5, noise_floor=0.3)
+    assert hf.noise > 0.3
