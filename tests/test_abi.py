@@ -46,8 +46,9 @@ def test_version_and_error_string(lib):
 def test_workspace_queries_are_host_only(lib):
     n, d, t = 1 << 20, 11, 17
     kmm = lib.egp_kmm_ws_bytes(n, d, t)
-    # O(n (d + t)) bytes, never O(n^2): packed points + packed V + one partial buffer
-    assert 0 < kmm < n * (4 * (d + 5) + 4 * 3 * 33) + (1 << 22)
+    # O(n (d + t)) bytes, never O(n^2): packed points (fp32 and the bf16-split operands), packed V (fp32 and
+    # split), one partial buffer
+    assert 0 < kmm < n * (4 * (d + 5) + 320 + 4 * 6 * 33) + (1 << 22)
     mb = lib.egp_mbcg_ws_bytes(n, d, t, 100, 100)
     assert kmm < mb < 6 * n * t * 4 + kmm + (1 << 28)
     assert lib.egp_piv_chol_precond_ws_bytes(n, d, 100) > 0
