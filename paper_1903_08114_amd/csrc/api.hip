@@ -28,11 +28,11 @@ int validate_ptr(const void* p, const char* name) {
   return EGP_OK;
 }
 
-int validate_hyper(const egp_hyper_t* h) {
+int validate_hyper(const egp_hyper_t* h, int d_max) {
   if (h == nullptr) return fail(EGP_ERR_ARG, "hyper-parameter struct is NULL");
   if (h->kernel_type < EGP_RBF || h->kernel_type > EGP_MATERN52)
     return fail(EGP_ERR_ARG, "unknown kernel_type %d", h->kernel_type);
-  if (h->d < 1 || h->d > EGP_D_MAX) return fail(EGP_ERR_ARG, "d = %d outside 1..%d", h->d, EGP_D_MAX);
+  if (h->d < 1 || h->d > d_max) return fail(EGP_ERR_ARG, "d = %d outside 1..%d for this entry point", h->d, d_max);
   if (h->lengthscales == nullptr) return fail(EGP_ERR_ARG, "lengthscales is NULL");
   for (int k = 0; k < h->d; ++k)
     if (!(h->lengthscales[k] > 0.f) || !std::isfinite(h->lengthscales[k]))
@@ -144,7 +144,7 @@ int egp_profile_read(int32_t group, double* total_ms, int64_t* launches) {
 }
 
 size_t egp_kmm_ws_bytes(int64_t n, int32_t d, int32_t t) {
-  if (n < 1 || d < 1 || d > EGP_D_MAX || t < 1 || t > EGP_T_MAX) return 0;
+  if (n < 1 || d < 1 || d > EGP_D_WIDE_MAX || t < 1 || t > EGP_T_MAX) return 0;
   return prepared_bytes(n, d) + kmm_core_ws_bytes(n, t);
 }
 
@@ -175,7 +175,7 @@ size_t egp_kmm_grad_ws_bytes(int64_t n, int32_t d, int32_t t) {
 int egp_kmm_grad(const float* X, int64_t n, const float* V, int32_t t, const egp_hyper_t* h, float* dout, void* ws,
                  size_t ws_bytes, void* stream) {
   int rc;
-  if ((rc = validate_hyper(h)) != EGP_OK) return rc;
+  if ((rc = validate_hyper(h, EGP_D_MAX)) != EGP_OK) return rc;
   if (n < 1 || n > ((int64_t)1 << 31) - 1) return fail(EGP_ERR_ARG, "n = %lld outside 1..2^31-1", (long long)n);
   if (t < 1 || t > EGP_T_MAX) return fail(EGP_ERR_ARG, "t = %d outside 1..%d", t, EGP_T_MAX);
   if ((rc = validate_ptr(X, "X")) != EGP_OK) return rc;
@@ -200,7 +200,7 @@ size_t egp_kmm_grad_bilinear_ws_bytes(int64_t n, int32_t d, int32_t t) {
 int egp_kmm_grad_bilinear(const float* X, int64_t n, const float* A, const float* B, int32_t t, const float* w,
                           const egp_hyper_t* h, double* out, void* ws, size_t ws_bytes, void* stream) {
   int rc;
-  if ((rc = validate_hyper(h)) != EGP_OK) return rc;
+  if ((rc = validate_hyper(h, EGP_D_MAX)) != EGP_OK) return rc;
   if ((rc = check_n(n)) != EGP_OK) return rc;
   if (t < 1 || t > 36) return fail(EGP_ERR_ARG, "t = %d outside 1..36", t);
   if (out == nullptr) return fail(EGP_ERR_ARG, "out is NULL");
@@ -226,7 +226,7 @@ int egp_mll(const float* X, int64_t n, const float* y, const float* W1, const fl
             const egp_hyper_t* h, int32_t rank, int32_t max_iter, float tol, egp_mll_result_t* out, void* ws,
             size_t ws_bytes, void* stream) {
   int rc;
-  if ((rc = validate_hyper(h)) != EGP_OK) return rc;
+  if ((rc = validate_hyper(h, EGP_D_MAX)) != EGP_OK) return rc;
   if ((rc = check_n(n)) != EGP_OK) return rc;
   if (tp < 1 || tp > 32) return fail(EGP_ERR_ARG, "tp = %d outside 1..32", tp);
   if (rank < 0 || rank > EGP_RANK_MAX || rank > n) return fail(EGP_ERR_ARG, "rank = %d outside 0..min(n, %d)", rank, EGP_RANK_MAX);
@@ -255,7 +255,7 @@ int egp_train_adam(const float* X, int64_t n, const float* y, const float* W1, c
     return fail(EGP_ERR_ARG, "bad Adam settings");
   egp_hyper_t h = {kernel_type, d, lengthscales, *outputscale, *noise};
   int rc;
-  if ((rc = validate_hyper(&h)) != EGP_OK) return rc;
+  if ((rc = validate_hyper(&h, EGP_D_MAX)) != EGP_OK) return rc;
   if ((rc = check_n(n)) != EGP_OK) return rc;
   if (tp < 1 || tp > 32) return fail(EGP_ERR_ARG, "tp = %d outside 1..32", tp);
   if (rank < 0 || rank > EGP_RANK_MAX || rank > n) return fail(EGP_ERR_ARG, "rank = %d outside 0..min(n, %d)", rank, EGP_RANK_MAX);
@@ -285,7 +285,7 @@ int egp_tridiag_logquad(const double* diag, const double* off, int32_t m, double
 }
 
 size_t egp_kmm_cross_ws_bytes(int64_t nq, int64_t n, int32_t d, int32_t t) {
-  if (nq < 1 || n < 1 || d < 1 || d > EGP_D_MAX || t < 1 || t > EGP_T_MAX) return 0;
+  if (nq < 1 || n < 1 || d < 1 || d > EGP_D_WIDE_MAX || t < 1 || t > EGP_T_MAX) return 0;
   return cross_ws_bytes_core(nq, n, d, t);
 }
 
@@ -307,7 +307,7 @@ int egp_kmm_cross(const float* Xq, int64_t nq, const float* X, int64_t n, const 
 }
 
 size_t egp_lanczos_ws_bytes(int64_t n, int32_t d, int32_t r) {
-  if (n < 1 || d < 1 || d > EGP_D_MAX || r < 1 || r > EGP_RANK_MAX) return 0;
+  if (n < 1 || d < 1 || d > EGP_D_WIDE_MAX || r < 1 || r > EGP_RANK_MAX) return 0;
   return lanczos_ws_bytes_core(n, d, r);
 }
 
@@ -329,7 +329,7 @@ int egp_lanczos(const float* X, int64_t n, const egp_hyper_t* h, const float* b,
 }
 
 size_t egp_predict_ws_bytes(int64_t nq, int64_t n, int32_t d, int32_t r) {
-  if (nq < 1 || n < 1 || d < 1 || d > EGP_D_MAX || r < 0 || r > EGP_RANK_MAX) return 0;
+  if (nq < 1 || n < 1 || d < 1 || d > EGP_D_WIDE_MAX || r < 0 || r > EGP_RANK_MAX) return 0;
   return predict_ws_bytes_core(nq, n, d, r);
 }
 
@@ -374,7 +374,7 @@ static int check_precond(const egp_precond_t* P, int64_t n, bool filled) {
 }
 
 size_t egp_piv_chol_precond_ws_bytes(int64_t n, int32_t d, int32_t rank) {
-  if (n < 1 || d < 1 || d > EGP_D_MAX || rank < 1 || rank > EGP_RANK_MAX) return 0;
+  if (n < 1 || d < 1 || d > EGP_D_WIDE_MAX || rank < 1 || rank > EGP_RANK_MAX) return 0;
   return pivchol_ws_bytes(n, d, rank);
 }
 
@@ -416,7 +416,7 @@ int egp_precond_apply(const egp_precond_t* P, int64_t n, float noise, const floa
 }
 
 size_t egp_mbcg_ws_bytes(int64_t n, int32_t d, int32_t t, int32_t rank, int32_t max_iter) {
-  if (n < 1 || d < 1 || d > EGP_D_MAX || t < 1 || t > 33 || rank < 0 || rank > EGP_RANK_MAX || max_iter < 0)
+  if (n < 1 || d < 1 || d > EGP_D_WIDE_MAX || t < 1 || t > 33 || rank < 0 || rank > EGP_RANK_MAX || max_iter < 0)
     return 0;
   return mbcg_ws_bytes_core(n, d, t, rank, max_iter);
 }

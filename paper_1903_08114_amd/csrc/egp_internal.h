@@ -115,7 +115,7 @@ struct ProfScope {   // records an event pair around the launches made during it
 
 int kmm_mode();     // EGP_KMM_FP32 or EGP_KMM_SPLIT_BF16 (egp_set_kmm_mode)
 
-int validate_hyper(const egp_hyper_t* h);
+int validate_hyper(const egp_hyper_t* h, int d_max = EGP_D_WIDE_MAX);
 int validate_ptr(const void* p, const char* name);
 
 }  // namespace egp

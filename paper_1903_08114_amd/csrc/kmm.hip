@@ -38,23 +38,32 @@ static double point_scale(int kernel_type) {
 // ------------------------------------------------------------------------------------------------
 constexpr int kMeanBlocks = 256;
 
+constexpr int kMeanLd = EGP_D_WIDE_MAX + 1;    // leading dimension of the per-block partial sums
+
 __global__ __launch_bounds__(256) void col_sum_partial(const float* __restrict__ X, int64_t n, int d,
-                                                       float* __restrict__ partial /*[blocks][64]*/) {
-  // thread t handles feature t % d of points t / d + k * (256/d) ... keep it simple: strided over elements
+                                                       float* __restrict__ partial /*[blocks][kMeanLd]*/) {
   __shared__ float red[256];
-  const int per = 256 / d;                 // points handled per block iteration
-  const int f = threadIdx.x % d, sub = threadIdx.x / d;
-  float acc = 0.f;
-  if (sub < per) {
-    for (int64_t p = (int64_t)blockIdx.x * per + sub; p < n; p += (int64_t)gridDim.x * per)
-      acc += X[p * d + f];
-  }
-  red[threadIdx.x] = (sub < per) ? acc : 0.f;
-  __syncthreads();
-  if (threadIdx.x < d) {
-    float s = 0.f;
-    for (int k = 0; k < per; ++k) s += red[k * d + threadIdx.x];
-    partial[blockIdx.x * 64 + threadIdx.x] = s;
+  if (d <= 128) {
+    // thread = (point slot, feature): 256 / d points per pass
+    const int per = 256 / d;
+    const int f = threadIdx.x % d, sub = threadIdx.x / d;
+    float acc = 0.f;
+    if (sub < per)
+      for (int64_t p = (int64_t)blockIdx.x * per + sub; p < n; p += (int64_t)gridDim.x * per) acc += X[p * d + f];
+    red[threadIdx.x] = (sub < per) ? acc : 0.f;
+    __syncthreads();
+    if ((int)threadIdx.x < d) {
+      float s = 0.f;
+      for (int k = 0; k < per; ++k) s += red[k * d + threadIdx.x];
+      partial[blockIdx.x * kMeanLd + threadIdx.x] = s;
+    }
+  } else {
+    // one point per pass, threads stride the features
+    for (int f = threadIdx.x; f < d; f += 256) {
+      float acc = 0.f;
+      for (int64_t p = blockIdx.x; p < n; p += gridDim.x) acc += X[p * d + f];
+      partial[blockIdx.x * kMeanLd + f] = acc;
+    }
   }
 }
 
@@ -64,14 +73,14 @@ __global__ __launch_bounds__(256) void col_mean_final(const float* __restrict__ 
   const int lane = threadIdx.x & 63;
   for (int f = threadIdx.x >> 6; f < d; f += 4) {
     double s = 0.0;
-    for (int b = lane; b < blocks; b += 64) s += (double)partial[b * 64 + f];
+    for (int b = lane; b < blocks; b += 64) s += (double)partial[b * kMeanLd + f];
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
     if (lane == 0) mean[f] = (float)(s / (double)n);
   }
 }
 
-struct ScaleArg { float inv[EGP_D_MAX + 1]; };
+struct ScaleArg { float inv[EGP_D_WIDE_MAX + 1]; };
 
 // One thread per (padded) point: x~ = (x - mean) * scale / l, norm = sum x~^2, scattered into the
 // packed MFMA-operand layout. Column-side factor -2 is NOT applied here; the kernel's row operand
@@ -238,11 +247,13 @@ size_t prepared_bytes(int64_t n, int d) {
   size_t b = 0;
   b += round_up((size_t)npad * ks * 4 * sizeof(float), 256);   // Xp
   b += round_up((size_t)npad * sizeof(float), 256);            // nrm
-  b += round_up((size_t)kMeanBlocks * 64 * sizeof(float), 256);  // partial sums
-  b += 256;                                                    // mean
-  const int ks16 = (d + 1 + 15) / 16;
-  b += round_up((size_t)(npad / 16) * ks16 * 3 * 1024, 256);   // XbC
-  b += round_up((size_t)(npad / 16) * ks16 * 2 * 1024, 256);   // XbR
+  b += round_up((size_t)kMeanBlocks * kMeanLd * sizeof(float), 256);  // partial sums
+  b += round_up((size_t)kMeanLd * sizeof(float), 256);         // mean
+  if (d <= EGP_D_MAX) {                                        // bf16-split operands exist for d <= 31 only
+    const int ks16 = (d + 1 + 15) / 16;
+    b += round_up((size_t)(npad / 16) * ks16 * 3 * 1024, 256);   // XbC
+    b += round_up((size_t)(npad / 16) * ks16 * 2 * 1024, 256);   // XbR
+  }
   return b;
 }
 
@@ -257,9 +268,9 @@ int prepare_points(const float* X, int64_t n, const egp_hyper_t* h, void* ws, Pr
   out->nrm = reinterpret_cast<float*>(w);
   w += round_up((size_t)npad * sizeof(float), 256);
   float* partial = reinterpret_cast<float*>(w);
-  w += round_up((size_t)kMeanBlocks * 64 * sizeof(float), 256);
+  w += round_up((size_t)kMeanBlocks * kMeanLd * sizeof(float), 256);
   float* mean = reinterpret_cast<float*>(w);
-  w += 256;
+  w += round_up((size_t)kMeanLd * sizeof(float), 256);
   const int ks16 = (d + 1 + 15) / 16;
   out->XbC = w;
   w += round_up((size_t)(npad / 16) * ks16 * 3 * 1024, 256);
@@ -275,7 +286,7 @@ int prepare_points(const float* X, int64_t n, const egp_hyper_t* h, void* ws, Pr
 
   ScaleArg sc;
   const double c = point_scale(h->kernel_type);
-  for (int f = 0; f <= EGP_D_MAX; ++f) sc.inv[f] = f < d ? (float)(c / (double)h->lengthscales[f]) : 0.f;
+  for (int f = 0; f <= EGP_D_WIDE_MAX; ++f) sc.inv[f] = f < d ? (float)(c / (double)h->lengthscales[f]) : 0.f;
 
   ProfScope prof(kProfPack, stream);
   if (mean_from != nullptr) {
@@ -287,7 +298,7 @@ int prepare_points(const float* X, int64_t n, const egp_hyper_t* h, void* ws, Pr
   }
   hipLaunchKernelGGL(pack_points, dim3((unsigned)((npad + 255) / 256)), dim3(256), 0, stream, X, n, npad, d,
                      ks, mean, sc, out->Xp, out->nrm);
-  if (kmm_mode() == EGP_KMM_SPLIT_BF16_ALL) launch_pack_points_bf(*out, stream);
+  if (kmm_mode() == EGP_KMM_SPLIT_BF16_ALL && d <= EGP_D_MAX) launch_pack_points_bf(*out, stream);
   EGP_HIP(hipGetLastError());
   return EGP_OK;
 }
@@ -295,11 +306,19 @@ int prepare_points(const float* X, int64_t n, const egp_hyper_t* h, void* ws, Pr
 namespace {
 
 Plan plan_for_mode(int64_t npad_rows, int64_t npad_cols, int ks, int d, int nb, int extra) {
+  if (ks > 8) return make_plan_wide(npad_rows, npad_cols, ks, nb, extra);     // d > 31: fp32 wide kernel in every mode
   return kmm_mode() == EGP_KMM_SPLIT_BF16_ALL ? make_plan_bf(npad_rows, npad_cols, d, nb, extra)
                                               : make_plan(npad_rows, npad_cols, ks);
 }
 int max_splits(int64_t npad_rows, int64_t npad_cols) {     // over every launch shape of every mode
-  const int a = make_plan(npad_rows, npad_cols, 1).splits;
+  int wmax = 0;
+  for (int ks = 9; ks <= (EGP_D_WIDE_MAX + 4) / 4; ks += 8)
+    for (int nb = 1; nb <= 2; ++nb) {
+      const int s = make_plan_wide(npad_rows, npad_cols, ks, nb, 1).splits;
+      if (s > wmax) wmax = s;
+    }
+  const int a0 = make_plan(npad_rows, npad_cols, 1).splits;
+  const int a = a0 > wmax ? a0 : wmax;
   const int b = make_plan_bf(npad_rows, npad_cols, 1, 1, 0).splits;
   const int c = make_plan_bf(npad_rows, npad_cols, 1, 2, 1).splits;
   return a > b ? (a > c ? a : c) : (b > c ? b : c);
@@ -307,6 +326,7 @@ int max_splits(int64_t npad_rows, int64_t npad_cols) {     // over every launch 
 
 int launch_ks(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, int extra, f4* Vp, const float* Ep,
               float* Part, int cm, hipStream_t stream, void* Vb) {
+  if (P.ks > 8) return launch_wide(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
   if (kmm_mode() == EGP_KMM_SPLIT_BF16_ALL) return launch_all_bf(P, Q, pl, nb, extra, Vp, Vb, Ep, Part, cm, stream);
   if (kmm_mode() == EGP_KMM_SPLIT_BF16) {
     {

@@ -309,6 +309,10 @@ int launch_all_ks(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, 
 int launch_all_ks_split(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, int extra, const f4* Vp,
                         const float* Ep, float* Part, int cm, hipStream_t stream);
 void launch_split_vp(f4* Vp, int64_t count, hipStream_t stream);
+// defined in kmm_wide.hip: more than 8 distance k-steps (d > 31), operands from LDS
+Plan make_plan_wide(int64_t npad_rows, int64_t npad_cols, int ks, int nb, int extra);
+int launch_wide(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, int extra, const f4* Vp, const float* Ep,
+                float* Part, int cm, hipStream_t stream);
 // defined in kmm_bf.hip: every contraction on the bf16 MFMA
 Plan make_plan_bf(int64_t npad_rows, int64_t npad_cols, int d, int nb, int extra);
 void launch_pack_points_bf(const Prepared& P, hipStream_t stream);

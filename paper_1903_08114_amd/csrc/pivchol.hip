@@ -80,7 +80,7 @@ __global__ __launch_bounds__(256) void pc_step(const float* __restrict__ Xp, int
                                                int64_t n, float* __restrict__ L, float* __restrict__ diag, int m,
                                                float tol_abs, PcState st) {
   __shared__ Cand sh[4];
-  __shared__ float xpiv[EGP_D_MAX + 1];
+  __shared__ float xpiv[EGP_D_WIDE_MAX + 1];
   __shared__ float lrow[EGP_RANK_MAX];
   if (*st.stop) return;
 

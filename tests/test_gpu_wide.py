@@ -1,0 +1,124 @@
+"""Inputs of more than 31 dimensions (the paper's UCI sets reach d = 385, Table 1 / dataset list): the fused
+multiply, the rectangular multiply, the preconditioner, the solver and prediction against the fp64 oracle."""
+import numpy as np
+import pytest
+
+import oracle as orc
+from workloads import rademacher
+
+pytestmark = pytest.mark.gpu
+
+KMM_TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def egp():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_1903_08114_amd as egp
+    egp.lib()
+    return egp
+
+
+def _cuda(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _rel(a, b):
+    return np.linalg.norm(a - b) / np.linalg.norm(b)
+
+
+def _inputs(seed, n, d, t):
+    rng = np.random.default_rng(seed)
+    X = rng.uniform(-1, 1, (n, d)).astype(np.float32)
+    V = rng.standard_normal((n, t)).astype(np.float32)
+    # lengthscales of the order sqrt(d): kernel values stay away from 0 and 1
+    ls = (np.sqrt(d) * np.exp(rng.uniform(np.log(0.4), np.log(1.5), d))).astype(np.float32)
+    return X, V, ls
+
+
+@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52])
+@pytest.mark.parametrize("n,d,t", [(300, 32, 16), (1000, 77, 17), (2049, 90, 16), (700, 160, 33), (1200, 385, 16),
+                                   (513, 399, 5), (40, 35, 1), (3000, 164, 32)])
+def test_kmm_wide_shapes(egp, kind, n, d, t):
+    X, V, ls = _inputs(7000 * kind + 10 * d + t, n, d, t)
+    s, noise = 1.3, 0.2
+    import torch
+    out = egp.kmm(_cuda(X), _cuda(V), ls, s, noise, kind)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    ref = orc.kmm(X, V, orc.Hyper(kind, ls, s, noise))
+    assert np.isfinite(got).all()
+    err = _rel(got, ref)
+    print(f"wide kmm n={n} d={d} t={t} kind={kind}: rel err {err:.2e}")
+    assert err <= KMM_TOL
+
+
+def test_kmm_wide_every_mode_runs_fp32(egp):
+    """Modes 1 and 2 cover d <= 31; beyond that every mode takes the fp32 path and gives identical bits."""
+    X, V, ls = _inputs(5, 900, 64, 16)
+    base = egp.kmm(_cuda(X), _cuda(V), ls, 1.0, 0.1, orc.RBF).cpu().numpy()
+    L = egp.lib()
+    try:
+        for mode in (1, 2):
+            L.egp_set_kmm_mode(mode)
+            got = egp.kmm(_cuda(X), _cuda(V), ls, 1.0, 0.1, orc.RBF).cpu().numpy()
+            assert np.array_equal(got, base)
+    finally:
+        L.egp_set_kmm_mode(0)
+
+
+@pytest.mark.parametrize("nq,n,d,t", [(100, 1500, 90, 1), (700, 900, 385, 20)])
+def test_kmm_cross_wide(egp, nq, n, d, t):
+    X, V, ls = _inputs(11 + d, n, d, t)
+    Xq = np.random.default_rng(d).uniform(-1, 1, (nq, d)).astype(np.float32)
+    got = egp.kmm_cross(_cuda(Xq), _cuda(X), _cuda(V), ls, 0.9, orc.MATERN52).cpu().numpy().astype(np.float64)
+    ref = orc.kernel_matrix(Xq, X, orc.Hyper(orc.MATERN52, ls, 0.9, 0.0)) @ V.astype(np.float64)
+    assert _rel(got, ref) <= KMM_TOL
+
+
+def test_gradient_entry_points_reject_wide(egp):
+    X, V, ls = _inputs(1, 100, 40, 2)
+    with pytest.raises(egp.EgpError):
+        egp.kmm_grad(_cuda(X), _cuda(V), ls, 1.0, 0.1, orc.RBF)
+
+
+@pytest.mark.parametrize("d", [77, 385])
+def test_solver_and_prediction_wide(egp, d):
+    """Preconditioned solve to convergence against a dense Cholesky solve; predictive mean and cached variance."""
+    n, t, rank = 1200, 5, 20
+    X, _, ls = _inputs(300 + d, n, d, t)
+    rng = np.random.default_rng(d)
+    y = np.sin(X[:, :4].sum(axis=1)) + 0.1 * rng.standard_normal(n)
+    B = np.concatenate([y[:, None], rademacher(rng, (n, t - 1))], axis=1).astype(np.float32)
+    s, noise, kind = 1.0, 0.05, orc.RBF
+    h = orc.Hyper(kind, ls, s, noise)
+    Khat = orc.khat(X, h)
+    Lref, pref = orc.pivoted_cholesky(orc.kernel_matrix(X, X, h), rank)
+    P = egp.piv_chol_precond(_cuda(X), ls, s, noise, kind, rank)
+    # compare what is unique: the approximation L L^T (pivot ties between near-equal diagonals may differ)
+    Lg = P.L.cpu().numpy().astype(np.float64).T
+    if P.pivots.tolist() == pref.tolist():
+        assert np.abs(Lg - Lref).max() <= 5e-4
+    res_g = np.trace(Khat - noise * np.eye(n) - Lg @ Lg.T)
+    res_o = np.trace(Khat - noise * np.eye(n) - Lref @ Lref.T)
+    assert abs(res_g - res_o) <= 1e-3 * abs(res_o)
+    sol = egp.mbcg(_cuda(X), _cuda(B), ls, s, noise, kind, precond=P, max_iter=300, tol=1e-5)
+    U = sol["U"].cpu().numpy().astype(np.float64)
+    Uref = orc.chol_solve(Khat, B.astype(np.float64))
+    assert _rel(U, Uref) <= 2e-3
+    # prediction
+    nq = 64
+    Xq = rng.uniform(-1, 1, (nq, d)).astype(np.float32)
+    a = Uref[:, 0].astype(np.float32)
+    cache = egp.lanczos(_cuda(X), _cuda(y.astype(np.float32)), ls, s, noise, kind, 24)
+    mean, var = egp.predict(_cuda(Xq), _cuda(X), _cuda(a), ls, s, noise, kind, cache=cache)
+    mref, vref = orc.predict_exact(X, y, Xq, h)
+    assert np.abs(mean.cpu().numpy() - mref).max() <= 2e-3 * max(1.0, np.abs(mref).max())
+    Qo, ao, bo = orc.lanczos(Khat, y.astype(np.float64), 24)
+    vlan = orc.predict_var_lanczos(orc.kernel_matrix(Xq, X, h), Qo, ao, bo, s)
+    vg = var.cpu().numpy().astype(np.float64)
+    assert np.abs(vg - vlan).max() <= 2e-3
+    assert (vg >= vref - 2e-3).all()
