@@ -19,6 +19,9 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + INCLUDE, "-I" + CSRC,
     # packed fp32 VALU forms are kept off for every device function of this library
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # MFMA accumulators in ordinary VGPRs: every kernel here fits the unified register file at its occupancy, and
+    # the AGPR form costs copies between the two halves that an fp32 MFMA cannot hide
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
     "-Wno-unused-command-line-argument", "-Wno-pass-failed",
 ]
 

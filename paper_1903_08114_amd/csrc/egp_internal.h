@@ -30,8 +30,18 @@ constexpr int kPadPoints = 512;  // packed arrays are padded to a multiple of th
 inline int ksteps_for(int d) { return (d + 1 + 3) / 4; }
 inline int64_t padded_points(int64_t n) { return (int64_t)round_up((size_t)n, kPadPoints); }
 
+// Float offset, inside one 16-point tile of the packed point array, of feature slot f of point pp (0..15).
+// Up to 8 k-steps (d <= 31) a tile is [ks][64]: step f/4, lane (f%4)*16 + pp. Beyond that the steps are grouped
+// by four, [ks/4][64][4], so that one 128-bit LDS read serves four MFMA steps; the ks%4 left-over steps keep the
+// [step][64] form behind the groups.
+__host__ __device__ inline int xp_offset(int ks, int f, int pp) {
+  const int s = f >> 2, lane = (f & 3) * 16 + pp;
+  if (ks <= 8 || s >= (ks & ~3)) return s * 64 + lane;
+  return (s >> 2) * 256 + lane * 4 + (s & 3);
+}
+
 struct Prepared {   // device arrays carved from a workspace by prepare_points()
-  float* Xp;        // [npad/16][KS][64]
+  float* Xp;        // [npad/16] tiles of KS*64 floats, element order given by xp_offset()
   float* nrm;       // [npad] squared norms of the scaled points (0 for padding)
   float* mean;      // [d] centre subtracted before scaling
   void* XbC;        // bf16-split column operands (filled in mode EGP_KMM_SPLIT_BF16_ALL only)

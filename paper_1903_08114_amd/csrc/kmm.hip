@@ -102,9 +102,9 @@ __global__ __launch_bounds__(256) void pack_points(const float* __restrict__ X, 
       v = (X[p * d + f] - mean[f]) * sc.inv[f];
       norm = __builtin_fmaf(v, v, norm);
     }
-    if (f != d) base[(f >> 2) * 64 + (f & 3) * 16 + pp] = v;
+    if (f != d) base[xp_offset(ks, f, pp)] = v;
   }
-  base[(d >> 2) * 64 + (d & 3) * 16 + pp] = norm;
+  base[xp_offset(ks, d, pp)] = norm;
   nrm[p] = norm;
 }
 

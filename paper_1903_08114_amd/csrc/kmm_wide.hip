@@ -32,13 +32,23 @@ __global__ __launch_bounds__(256) void kmm_kernel_wide(const float* __restrict__
   const int64_t row_tile0 = ((int64_t)blockIdx.x * 4 + wave) * RW;
   const int ds = d >> 2, dq = d & 3;
 
-  // rows of this wave: -2 x~ with the norm slot set to 1
-  for (int it = 0; it < RW; ++it)
-    for (int s = 0; s < ks; ++s) {
-      float v = -2.0f * XpRow[((row_tile0 + it) * ks + s) * 64 + lane];
-      if (s == ds && q == dq) v = 1.0f;
-      Rs[((wave * RW + it) * ks + s) * 64 + lane] = v;
+  // rows of this wave: -2 x~ with the norm slot set to 1, same element order as the packed tiles
+  const int ks4 = ks >> 2, kt = ks & 3;      // groups of four k-steps, left-over steps
+  for (int it = 0; it < RW; ++it) {
+    const float* src = XpRow + (row_tile0 + it) * ks * 64;
+    float* dstr = Rs + (wave * RW + it) * ks * 64;
+    for (int e = lane; e < ks * 64; e += 64) {
+      int s_, l_;
+      if (e < ks4 * 256) {
+        s_ = (e >> 8) * 4 + (e & 3);
+        l_ = (e >> 2) & 63;
+      } else {
+        s_ = e >> 6;
+        l_ = e & 63;
+      }
+      dstr[e] = (s_ == ds && (l_ >> 4) == dq) ? 1.0f : -2.0f * src[e];
     }
+  }
   f4 cq[RW], o[RW][NB];
   float eacc[RW];
 #pragma unroll
@@ -80,17 +90,57 @@ __global__ __launch_bounds__(256) void kmm_kernel_wide(const float* __restrict__
     if (more) issue(st + 1, buf ^ 1);
     const float* xs = Xs + buf * jt_stage * ks * 64;
     for (int jt = 0; jt < jt_stage; ++jt) {
-      const float* xt = xs + jt * ks * 64 + lane;
+      const float* xt = xs + jt * ks * 64;
+      const f4* xg = reinterpret_cast<const f4*>(xt) + lane;
       f4 acc[RW];
+      const f4* rg[RW];
 #pragma unroll
-      for (int it = 0; it < RW; ++it) acc[it] = cq[it];
-#pragma unroll 4
-      for (int s = 0; s < ks; ++s) {
-        const float a = xt[s * 64];
-#pragma unroll
-        for (int it = 0; it < RW; ++it)
-          acc[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, Rs[((wave * RW + it) * ks + s) * 64 + lane], acc[it], 0, 0, 0);
+      for (int it = 0; it < RW; ++it) {
+        acc[it] = cq[it];
+        rg[it] = reinterpret_cast<const f4*>(Rs + (wave * RW + it) * ks * 64) + lane;
       }
+      // left-over steps first (index clamped, so the loads need no branch): in flight while the groups run
+      float ta[3], tr[RW][3];
+#pragma unroll
+      for (int k = 0; k < 3; ++k) {
+        const int sk = ks4 * 4 + k < ks ? ks4 * 4 + k : ks - 1;
+        ta[k] = xt[sk * 64 + lane];
+#pragma unroll
+        for (int it = 0; it < RW; ++it) tr[it][k] = Rs[((wave * RW + it) * ks + sk) * 64 + lane];
+      }
+      // groups of four steps, two groups per trip with the operands of the next group loaded ahead (ping-pong)
+      auto four = [&](const f4& a, const f4 (&r)[RW]) {
+#pragma unroll
+        for (int it = 0; it < RW; ++it) acc[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, r[it].x, acc[it], 0, 0, 0);
+#pragma unroll
+        for (int it = 0; it < RW; ++it) acc[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, r[it].y, acc[it], 0, 0, 0);
+#pragma unroll
+        for (int it = 0; it < RW; ++it) acc[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, r[it].z, acc[it], 0, 0, 0);
+#pragma unroll
+        for (int it = 0; it < RW; ++it) acc[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, r[it].w, acc[it], 0, 0, 0);
+      };
+      f4 a0 = xg[0], a1, r0[RW], r1[RW];
+#pragma unroll
+      for (int it = 0; it < RW; ++it) r0[it] = rg[it][0];
+      int g = 0;
+      for (; g + 2 <= ks4; g += 2) {
+        a1 = xg[(g + 1) * 64];
+#pragma unroll
+        for (int it = 0; it < RW; ++it) r1[it] = rg[it][(g + 1) * 64];
+        four(a0, r0);
+        const int gn = g + 2 < ks4 ? g + 2 : ks4 - 1;
+        a0 = xg[gn * 64];
+#pragma unroll
+        for (int it = 0; it < RW; ++it) r0[it] = rg[it][gn * 64];
+        four(a1, r1);
+      }
+      if (g < ks4) four(a0, r0);
+#pragma unroll
+      for (int k = 0; k < 3; ++k)
+        if (k < kt) {
+#pragma unroll
+          for (int it = 0; it < RW; ++it) acc[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(ta[k], tr[it][k], acc[it], 0, 0, 0);
+        }
       f4 v[NB];
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) v[nb] = Vs[buf * vf4 + (jt * NB + nb) * 64 + lane];

@@ -106,8 +106,8 @@ __global__ __launch_bounds__(256) void pc_step(const float* __restrict__ Xp, int
   const int64_t piv = w.i;
   if (blockIdx.x == 0 && threadIdx.x == 0) st.pivots[m] = w.i;
 
-  const float* pbase = Xp + (piv >> 4) * ks * 64 + (piv & 15);
-  for (int f = threadIdx.x; f < d; f += 256) xpiv[f] = pbase[(f >> 2) * 64 + (f & 3) * 16];
+  const float* pbase = Xp + (piv >> 4) * ks * 64;
+  for (int f = threadIdx.x; f < d; f += 256) xpiv[f] = pbase[xp_offset(ks, f, (int)(piv & 15))];
   for (int c = threadIdx.x; c < m; c += 256) lrow[c] = L[(int64_t)c * n + piv];
   __syncthreads();
   const float root = sqrtf(w.v);
@@ -125,10 +125,11 @@ __global__ __launch_bounds__(256) void pc_step(const float* __restrict__ Xp, int
       col = 0.f;
       newd = -INFINITY;
     } else {
-      const float* xb = Xp + (i >> 4) * ks * 64 + (i & 15);
+      const float* xb = Xp + (i >> 4) * ks * 64;
+      const int pp = (int)(i & 15);
       float r2 = 0.f;
       for (int f = 0; f < d; ++f) {
-        const float df = xpiv[f] - xb[(f >> 2) * 64 + (f & 3) * 16];
+        const float df = xpiv[f] - xb[xp_offset(ks, f, pp)];
         r2 = __builtin_fmaf(df, df, r2);
       }
       float acc = s * transform_rt(kind, r2);
