@@ -268,10 +268,10 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_bf(const u4* __restrict__ X
   }
 }
 
-// 8 row tiles per wave for the plain 16-column case; 4 when a 17th column or a second column block adds
-// registers (the compiler otherwise parks values in accumulator registers and pays for the moves)
+// 8 row tiles per wave; 4 when two 16-feature groups (d >= 16) meet a 17th column or a second column block,
+// where 8 tiles' operands and accumulators no longer fit 256 registers without spilling
 constexpr int kBfSmallR = 2;
-constexpr int bf_big_r(int nb, int extra) { return 8; }
+constexpr int bf_big_r(int ks16, int nb, int extra) { return (ks16 >= 2 && (nb == 2 || extra)) ? 4 : 8; }
 constexpr int bf_big_jt(int ks16, int nb = 1) { return 8 / ks16 / nb; }   // keeps a stage near 36 KB
 constexpr int bf_small_jt(int ks16) { return 4 / ks16; }
 
@@ -282,7 +282,7 @@ int launch_bf_shape(const Prepared& P, const Prepared& Q, const kmm_detail::Plan
   const u4* xr = reinterpret_cast<const u4*>(Q.XbR);
   const u4* xc = reinterpret_cast<const u4*>(P.XbC);
   if (pl.big)
-    hipLaunchKernelGGL((kmm_kernel_bf<KS16, bf_big_r(NB, EXTRA), KIND, NB, EXTRA, bf_big_jt(KS16, NB)>), grid, block, 0, stream, xr, Q.nrm, xc,
+    hipLaunchKernelGGL((kmm_kernel_bf<KS16, bf_big_r(KS16, NB, EXTRA), KIND, NB, EXTRA, bf_big_jt(KS16, NB)>), grid, block, 0, stream, xr, Q.nrm, xc,
                        VbA, VbB, Ep, Part, Q.npad, pl.stages_per_split, pl.stages_total, cm);
   else
     hipLaunchKernelGGL((kmm_kernel_bf<KS16, kBfSmallR, KIND, NB, EXTRA, bf_small_jt(KS16)>), grid, block, 0, stream, xr, Q.nrm,
@@ -318,7 +318,7 @@ Plan make_plan_bf(int64_t npad_rows, int64_t npad_cols, int d, int nb, int extra
   Plan pl;
   const int ks16 = (d + 1 + 15) / 16;
   pl.big = npad_rows / (64 * 8) >= 64;
-  const int R = pl.big ? bf_big_r(nb, extra) : kBfSmallR, JT = pl.big ? bf_big_jt(ks16, nb) : bf_small_jt(ks16);
+  const int R = pl.big ? bf_big_r(ks16, nb, extra) : kBfSmallR, JT = pl.big ? bf_big_jt(ks16, nb) : bf_small_jt(ks16);
   pl.row_blocks = (int)(npad_rows / (64 * R));
   pl.stages_total = (int)(npad_cols / (16 * JT));
   int want = 1024 / pl.row_blocks;
