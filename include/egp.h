@@ -45,16 +45,16 @@ typedef enum {
  *   MATERN52  g = (1 + sqrt5 r + 5 r^2/3) exp(-sqrt5 r)                                             */
 typedef enum { EGP_RBF = 0, EGP_MATERN32 = 1, EGP_MATERN52 = 2 } egp_kernel_t;
 
-#define EGP_D_MAX 31        /* largest input dimension of the gradient entry points (egp_kmm_grad,
-                               egp_kmm_grad_bilinear, egp_mll, egp_train_adam) and of the bf16-split modes */
-#define EGP_D_WIDE_MAX 399  /* largest input dimension of egp_kmm, egp_kmm_cross, egp_piv_chol_precond, egp_mbcg,
-                               egp_lanczos, egp_predict (d > 31 runs a variant that keeps row operands in LDS) */
+#define EGP_D_MAX 31        /* largest input dimension of egp_kmm_grad (the materialised derivative product) and of
+                               the bf16-split modes */
+#define EGP_D_WIDE_MAX 399  /* largest input dimension of every other entry point (d > 31 runs variants that keep
+                               the row operands in LDS) */
 #define EGP_T_MAX 1024   /* largest number of right-hand-side columns */
 #define EGP_RANK_MAX 256 /* largest preconditioner rank */
 
 typedef struct {
   int32_t kernel_type;        /* egp_kernel_t */
-  int32_t d;                  /* 1..EGP_D_WIDE_MAX (1..EGP_D_MAX for the gradient entry points) */
+  int32_t d;                  /* 1..EGP_D_WIDE_MAX (1..EGP_D_MAX for egp_kmm_grad) */
   const float* lengthscales;  /* host, d values > 0 (a shared lengthscale is d equal values) */
   float outputscale;          /* s > 0 */
   float noise;                /* sigma^2 >= 0, the value added to the diagonal: Khat = K + noise*I
@@ -142,7 +142,7 @@ size_t egp_mbcg_ws_bytes(int64_t n, int32_t d, int32_t t, int32_t rank, int32_t 
  * tp in 1..32, rank in 0..EGP_RANK_MAX (noise > 0 needed when rank > 0). Synchronises on `stream`. */
 typedef struct {
   double mll, logdet, quad;
-  double grad[EGP_D_MAX + 2];
+  double grad[EGP_D_WIDE_MAX + 2];
   int32_t iters, precond_rank;
   float rel_resid_max;
 } egp_mll_result_t;

@@ -22,7 +22,7 @@ class _Hyper(C.Structure):
 
 
 class _MllResult(C.Structure):
-    _fields_ = [("mll", C.c_double), ("logdet", C.c_double), ("quad", C.c_double), ("grad", C.c_double * 33),
+    _fields_ = [("mll", C.c_double), ("logdet", C.c_double), ("quad", C.c_double), ("grad", C.c_double * 401),
                 ("iters", C.c_int32), ("precond_rank", C.c_int32), ("rel_resid_max", C.c_float)]
 
 

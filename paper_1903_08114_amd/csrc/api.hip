@@ -193,14 +193,14 @@ int egp_kmm_grad(const float* X, int64_t n, const float* V, int32_t t, const egp
 static int check_n(int64_t n);
 
 size_t egp_kmm_grad_bilinear_ws_bytes(int64_t n, int32_t d, int32_t t) {
-  if (n < 1 || d < 1 || d > EGP_D_MAX || t < 1 || t > 36) return 0;
+  if (n < 1 || d < 1 || d > EGP_D_WIDE_MAX || t < 1 || t > 36) return 0;
   return prepared_bytes(n, d) + bilinear_core_ws_bytes(n, d, t);
 }
 
 int egp_kmm_grad_bilinear(const float* X, int64_t n, const float* A, const float* B, int32_t t, const float* w,
                           const egp_hyper_t* h, double* out, void* ws, size_t ws_bytes, void* stream) {
   int rc;
-  if ((rc = validate_hyper(h, EGP_D_MAX)) != EGP_OK) return rc;
+  if ((rc = validate_hyper(h)) != EGP_OK) return rc;
   if ((rc = check_n(n)) != EGP_OK) return rc;
   if (t < 1 || t > 36) return fail(EGP_ERR_ARG, "t = %d outside 1..36", t);
   if (out == nullptr) return fail(EGP_ERR_ARG, "out is NULL");
@@ -217,7 +217,7 @@ int egp_kmm_grad_bilinear(const float* X, int64_t n, const float* A, const float
 }
 
 size_t egp_mll_ws_bytes(int64_t n, int32_t d, int32_t tp, int32_t rank, int32_t max_iter) {
-  if (n < 1 || d < 1 || d > EGP_D_MAX || tp < 1 || tp > 32 || rank < 0 || rank > EGP_RANK_MAX || max_iter < 1)
+  if (n < 1 || d < 1 || d > EGP_D_WIDE_MAX || tp < 1 || tp > 32 || rank < 0 || rank > EGP_RANK_MAX || max_iter < 1)
     return 0;
   return mll_ws_bytes_core(n, d, tp, rank, max_iter);
 }
@@ -226,7 +226,7 @@ int egp_mll(const float* X, int64_t n, const float* y, const float* W1, const fl
             const egp_hyper_t* h, int32_t rank, int32_t max_iter, float tol, egp_mll_result_t* out, void* ws,
             size_t ws_bytes, void* stream) {
   int rc;
-  if ((rc = validate_hyper(h, EGP_D_MAX)) != EGP_OK) return rc;
+  if ((rc = validate_hyper(h)) != EGP_OK) return rc;
   if ((rc = check_n(n)) != EGP_OK) return rc;
   if (tp < 1 || tp > 32) return fail(EGP_ERR_ARG, "tp = %d outside 1..32", tp);
   if (rank < 0 || rank > EGP_RANK_MAX || rank > n) return fail(EGP_ERR_ARG, "rank = %d outside 0..min(n, %d)", rank, EGP_RANK_MAX);
@@ -255,7 +255,7 @@ int egp_train_adam(const float* X, int64_t n, const float* y, const float* W1, c
     return fail(EGP_ERR_ARG, "bad Adam settings");
   egp_hyper_t h = {kernel_type, d, lengthscales, *outputscale, *noise};
   int rc;
-  if ((rc = validate_hyper(&h, EGP_D_MAX)) != EGP_OK) return rc;
+  if ((rc = validate_hyper(&h)) != EGP_OK) return rc;
   if ((rc = check_n(n)) != EGP_OK) return rc;
   if (tp < 1 || tp > 32) return fail(EGP_ERR_ARG, "tp = %d outside 1..32", tp);
   if (rank < 0 || rank > EGP_RANK_MAX || rank > n) return fail(EGP_ERR_ARG, "rank = %d outside 0..min(n, %d)", rank, EGP_RANK_MAX);

@@ -17,39 +17,19 @@
 #include <vector>
 
 #include "egp_internal.h"
+#include "bilinear_detail.h"
 
 namespace egp {
 
-typedef float f4 __attribute__((ext_vector_type(4)));
-
 namespace {
 
-constexpr float kLn2 = 0.6931471805599453f;
+using bilinear_detail::f4;
+using bilinear_detail::hg;
+
 // row tiles per wave: fewer when the per-tile feature registers (4 KS of them) grow
 constexpr int br_for(int ks) { return ks <= 3 ? 4 : (ks <= 5 ? 2 : 1); }
 constexpr int BJT = 8;     // column tiles per LDS stage
-constexpr int kDMaxB = 31; // lengthscales handled (the fused kernels support d <= 31)
-
-// h(r) and g(r) up to the constant factors the host applies (see kmm_grad.hip): returns h', sets g'
-template <int KIND>
-__device__ __forceinline__ float hg(float acc, float* g) {
-  if constexpr (KIND == EGP_RBF) {
-    const float e = __builtin_amdgcn_exp2f(-acc);
-    *g = e;
-    return e;
-  } else if constexpr (KIND == EGP_MATERN32) {
-    const float a = __builtin_amdgcn_sqrtf(__builtin_fabsf(acc));
-    const float e = __builtin_amdgcn_exp2f(-a);
-    *g = __builtin_fmaf(a, kLn2, 1.0f) * e;
-    return e;
-  } else {
-    const float a = __builtin_amdgcn_sqrtf(__builtin_fabsf(acc));
-    const float e = __builtin_amdgcn_exp2f(-a);
-    const float lin = __builtin_fmaf(a, kLn2, 1.0f);
-    *g = __builtin_fmaf(a * a, kLn2 * kLn2 / 3.0f, lin) * e;
-    return lin * e;
-  }
-}
+constexpr int kDMaxB = 31; // lengthscales handled by this kernel (d > 31: kmm_bilinear_wide.hip)
 
 // M (n x t row-major) -> packed [tile][ts][64]: lane (q,p) of step s holds w[4s+q] * M[16 tile + p][4s + q]
 __global__ __launch_bounds__(256) void pack_cols(const float* __restrict__ M, int64_t n, int64_t npad, int t, int ts,
@@ -278,6 +258,7 @@ int launch_ts(const Prepared& P, const BPlan& pl, int ts, const float* Ap, const
 }  // namespace
 
 size_t bilinear_core_ws_bytes(int64_t n, int d, int t) {
+  if (ksteps_for(d) > 8) return bilinear_detail::bilinear_wide_ws_bytes(n, d, t);
   const int64_t npad = padded_points(n);
   const int ts = (t + 3) / 4;
   const BPlan pl = bilinear_plan(npad, ksteps_for(d));
@@ -291,6 +272,7 @@ size_t bilinear_core_ws_bytes(int64_t n, int d, int t) {
 // A, B: device n x t row-major; wcol: host t weights or NULL. Synchronises on the stream.
 int bilinear_core(const Prepared& P, const egp_hyper_t* h, const float* A, const float* B, int t, const float* wcol,
                   double* out, void* ws2, hipStream_t stream) {
+  if (P.ks > 8) return bilinear_detail::bilinear_wide_core(P, h, A, B, t, wcol, out, ws2, stream);
   const int64_t npad = P.npad;
   const int ts = (t + 3) / 4;
   if (ts > 9) return fail(EGP_ERR_ARG, "bilinear forms support t <= 36 (got %d)", t);

@@ -312,7 +312,7 @@ int mll_core(const float* X, int64_t n, const float* y, const float* W1, const f
   double gn = 0.0;
   for (int c = 0; c < t; ++c) gn += (double)wcol[c] * dots[c];
   res->grad[d + 1] = gn;
-  for (int k = d + 2; k < EGP_D_MAX + 2; ++k) res->grad[k] = 0.0;
+  for (int k = d + 2; k < EGP_D_WIDE_MAX + 2; ++k) res->grad[k] = 0.0;
   return EGP_OK;
 }
 

@@ -56,8 +56,10 @@ def test_workspace_queries_are_host_only(lib):
     assert lib.egp_kmm_ws_bytes(n, 0, t) == 0
     assert lib.egp_kmm_ws_bytes(n, 400, t) == 0
     assert lib.egp_kmm_ws_bytes(4096, 399, t) > 4096 * 400 * 4
-    assert lib.egp_kmm_grad_ws_bytes(n, 32, t) == 0          # gradient entry points stay at d <= 31
-    assert lib.egp_mll_ws_bytes(n, 32, 8, 10, 10) == 0
+    assert lib.egp_kmm_grad_ws_bytes(n, 32, t) == 0          # the materialised derivative product stays at d <= 31
+    assert lib.egp_mll_ws_bytes(4096, 90, 8, 10, 10) > 0
+    assert lib.egp_kmm_grad_bilinear_ws_bytes(4096, 399, 17) > 0
+    assert lib.egp_mll_ws_bytes(4096, 400, 8, 10, 10) == 0
     assert lib.egp_kmm_ws_bytes(n, d, 0) == 0
     assert lib.egp_mbcg_ws_bytes(n, d, 34, 0, 10) == 0
 

@@ -79,10 +79,69 @@ def test_kmm_cross_wide(egp, nq, n, d, t):
     assert _rel(got, ref) <= KMM_TOL
 
 
-def test_gradient_entry_points_reject_wide(egp):
+def test_materialised_gradient_rejects_wide(egp):
     X, V, ls = _inputs(1, 100, 40, 2)
     with pytest.raises(egp.EgpError):
         egp.kmm_grad(_cuda(X), _cuda(V), ls, 1.0, 0.1, orc.RBF)
+
+
+GRAD_TOL = 1e-4
+
+
+@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52])
+@pytest.mark.parametrize("n,d,t", [(600, 32, 17), (1000, 77, 17), (900, 90, 5), (500, 164, 16), (400, 200, 33),
+                                   (300, 385, 17), (200, 399, 3), (40, 47, 1)])
+def test_bilinear_forms_wide(egp, kind, n, d, t):
+    """sum_c w_c a_c^T (dK/dl_k) b_c for every lengthscale and the outputscale form, d > 31 (expanded squared
+    difference contracted on the MFMA), against the dense oracle; same Cauchy-Schwarz bound as for d <= 31."""
+    X, _, ls = _inputs(900 * kind + d + t, n, d, t)
+    rng = np.random.default_rng(n + d)
+    A = rng.standard_normal((n, t)).astype(np.float32)
+    B = rng.standard_normal((n, t)).astype(np.float32)
+    wts = rng.uniform(-1, 1, t).astype(np.float32)
+    s, noise = 1.3, 0.1
+    h = orc.Hyper(kind, ls, s, noise)
+    got = egp.kmm_grad_bilinear(_cuda(X), _cuda(A), _cuda(B), ls, s, noise, kind, weights=wts)
+    Aw = A.astype(np.float64) * wts.astype(np.float64)
+    worst = 0.0
+    # every lengthscale up to d = 64; beyond that the first, the last and a seeded sample (oracle time)
+    ks = range(d) if d <= 64 else sorted({0, d - 1, *rng.choice(d, 14, replace=False).tolist()})
+    for k in ks:
+        dKB = orc.dkernel_dlengthscale(X, X, h, k) @ B.astype(np.float64)
+        ref = np.sum(Aw * dKB)
+        bound = GRAD_TOL * np.linalg.norm(Aw) * np.linalg.norm(dKB)
+        worst = max(worst, abs(got[k] - ref) / bound)
+        assert abs(got[k] - ref) <= bound + 1e-12, (k, got[k], ref, bound)
+    KB = orc.kernel_matrix(X, X, h) @ B.astype(np.float64) / s
+    ref = np.sum(Aw * KB)
+    assert abs(got[d] - ref) <= GRAD_TOL * np.linalg.norm(Aw) * np.linalg.norm(KB) + 1e-12
+    print(f"wide bilinear n={n} d={d} t={t} kind={kind}: worst error / bound = {worst:.3f}")
+
+
+@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN52])
+@pytest.mark.parametrize("rank", [0, 10])
+def test_mll_wide_matches_oracle_with_same_probes(egp, kind, rank):
+    """Marginal likelihood and gradient at d = 40: same probe draws on both sides."""
+    rng = np.random.default_rng(140 + kind + rank)
+    n, d, tp = 900, 40, 16
+    X, _, ls = _inputs(55, n, d, 1)
+    y = (np.sin(X[:, :5].sum(axis=1)) + 0.2 * rng.standard_normal(n)).astype(np.float32)
+    s, noise = 1.2, 0.15
+    h = orc.Hyper(kind, ls, s, noise)
+    w1 = rademacher(rng, (max(rank, 1), tp))
+    w2 = rademacher(rng, (n, tp))
+    got = egp.mll(_cuda(X), _cuda(y), _cuda(w1), _cuda(w2), ls, s, noise, kind, rank=rank, max_iter=400, tol=1e-5)
+    assert got["rel_resid_max"] <= 1e-5 and got["rank"] == rank
+    if rank:
+        L, piv = orc.pivoted_cholesky(orc.kernel_matrix(X, X, h), rank)
+        assert egp.piv_chol_precond(_cuda(X), ls, s, noise, kind, rank).pivots.tolist() == piv.tolist()
+        Z = orc.probes_with_cov_P(L, noise, w1, w2)
+    else:
+        L, Z = None, w2.astype(np.float64)
+    ref = orc.mll_stochastic_terms(X, y, h, Z, L)
+    assert abs(got["mll"] - ref["mll"]) <= 2e-3 * abs(ref["mll"]) + 0.05
+    scale = np.abs(ref["grad"]) + 0.02 * np.abs(ref["grad"]).max()
+    assert np.all(np.abs(got["grad"] - ref["grad"]) <= 2e-2 * scale), (got["grad"], ref["grad"])
 
 
 @pytest.mark.parametrize("d", [77, 385])
