@@ -41,6 +41,11 @@ def read_traffic(path):
     return None
 
 
+def progress(msg):
+    """One line per finished leg on stderr (stdout carries the single JSON line)."""
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
 def prof_read(lib, group):
     ms = C.c_double(0.0)
     cnt = C.c_int64(0)
@@ -84,6 +89,7 @@ def main():
     torch.cuda.set_device(dev)
 
     w = make_workload("C4", n=args.n, with_targets=not args.kmm_only)
+    progress("C4 inputs generated")
     n, d = w.n, w.d
     X = torch.from_numpy(w.X).to(dev)
     V16 = torch.from_numpy(np.ascontiguousarray(w.V[:, 1:17])).to(dev)     # the 16 probe columns
@@ -165,6 +171,7 @@ def main():
     step()                      # leave `out` holding the fp32-mode product for the parity sample below
     torch.cuda.synchronize()
 
+    progress("fused multiply timed in every mode")
     if not args.kmm_only:
         # ---- preconditioner build (rank 100) and mBCG iterations at t = 17 ----
         lib.egp_profile_enable(1)
@@ -200,21 +207,64 @@ def main():
             "hbm_peak_gbs": HBM_PEAK_GBS,
             "rel_resid_max_after": float(res["rel_resid"].max()),
         }
+        # the same iterations with every contraction on the bf16 MFMA (opt-in mode, reported separately)
+        lib.egp_set_kmm_mode(2)
+        egp.mbcg(X, B17, w.lengthscales, w.outputscale, w.noise, w.kernel_type, precond=P, max_iter=1, tol=0.0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        egp.mbcg(X, B17, w.lengthscales, w.outputscale, w.noise, w.kernel_type, precond=P, max_iter=iters, tol=0.0)
+        torch.cuda.synchronize()
+        result["mbcg"]["s_per_iter_split_bf16_all_mode"] = (time.perf_counter() - t0) / iters
+        lib.egp_set_kmm_mode(0)
         result["piv_chol"] = {"s": pc_s, "steps_ms": pc_ms, "rank": k,
                               "gbs": pc_bytes / (pc_ms * 1e-3) / 1e9 if pc_ms > 0 else None}
+        progress("preconditioner and mBCG iterations timed")
         if args.full_solve:
             # solve at the paper's training tolerance (Experiment details: tolerance 1, rank-100 preconditioner)
             t0 = time.perf_counter()
             full = egp.mbcg(X, B17, w.lengthscales, w.outputscale, w.noise, w.kernel_type, precond=P,
-                            max_iter=1000, tol=w.tol)
+                            max_iter=w.max_iter, tol=w.tol)
             torch.cuda.synchronize()
             result["mbcg"]["full_solve_tol1"] = {"s": time.perf_counter() - t0, "iters": full["iters"],
                                                  "rel_resid_max": float(full["rel_resid"].max()),
                                                  "resid_hist_max": [float(v) for v in full["resid_hist"].max(axis=1)]}
         del P
+        progress("C4 solver legs done")
+
+    if not args.kmm_only:
+        # ---- the small configurations: one multiply and the configured solve each ----
+        for name in ("C1", "C2"):
+            ws_ = make_workload(name)
+            Xs = torch.from_numpy(ws_.X).to(dev)
+            Bs = torch.from_numpy(ws_.V).to(dev)
+            hyp = (ws_.lengthscales, ws_.outputscale, ws_.noise, ws_.kernel_type)
+            os_ = egp.kmm(Xs, Bs, *hyp)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(20):
+                egp.kmm(Xs, Bs, *hyp, out=os_)
+            torch.cuda.synchronize()
+            kmm_s = (time.perf_counter() - t0) / 20
+            Ps = egp.piv_chol_precond(Xs, *hyp, ws_.rank)
+            egp.mbcg(Xs, Bs, *hyp, precond=Ps, max_iter=2, tol=0.0)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            rs = egp.mbcg(Xs, Bs, *hyp, precond=Ps, max_iter=ws_.max_iter, tol=ws_.tol)
+            torch.cuda.synchronize()
+            solve_s = time.perf_counter() - t0
+            fk = flops_per_entry(ws_.d, ws_.t, ws_.kernel_type)
+            result[name.lower()] = {
+                "workload": f"{name}: n={ws_.n}, d={ws_.d}, t={ws_.t}, rank {ws_.rank}, tol {ws_.tol}",
+                "kmm_s": kmm_s, "kmm_entries_per_s": ws_.n ** 2 / kmm_s,
+                "kmm_frac_fp32_peak": fk * ws_.n ** 2 / kmm_s / 1e12 / FP32_PEAK_TFLOPS,
+                "solve_s": solve_s, "solve_iters": rs["iters"], "rel_resid_max": float(rs["rel_resid"].max()),
+            }
+            del Xs, Bs, os_, Ps
+            progress(f"{name} multiply and solve timed")
 
     if args.grad:
         w3 = make_workload("C3")
+        progress("C3 inputs generated")
         X3 = torch.from_numpy(w3.X).to(dev)
         V3 = torch.from_numpy(w3.V).to(dev)
         g3 = torch.empty((w3.d, w3.n, w3.t), dtype=torch.float32, device=dev)
@@ -240,6 +290,7 @@ def main():
         leg["workload"] = f"C3: n={w3.n}, d={w3.d}, t={w3.t}, RBF-ARD, all {w3.d} lengthscale derivatives"
         result["c3"] = leg
         del X3, V3, g3, o3, wsg, wsk
+        progress("C3 multiply and derivative product timed")
 
     if args.predict > 0:
         rng = np.random.default_rng(9)
@@ -261,9 +312,11 @@ def main():
                              "cache_build_s": build_s, "n_train": n,
                              "var_min": float(var.min()), "var_max": float(var.max())}
         del Xq, yv, a, cache
+        progress("prediction leg timed")
 
     if args.mll > 0:
         w5 = make_workload("C5")
+        progress("C5 inputs generated")
         rng = np.random.default_rng(5)
         X5 = torch.from_numpy(w5.X).to(dev)
         y5 = torch.from_numpy(w5.y).to(dev)
@@ -280,6 +333,7 @@ def main():
                                  "workload": f"C5: n={w5.n}, d={w5.d}, Matern-3/2 ARD, 16 probes, rank {w5.rank}, "
                                              f"CG capped at {args.mll} iterations"}
         del X5, y5, W1, W2, ws5
+        progress("C5 marginal-likelihood step timed")
 
     if not args.no_cpu_baseline:
         import oracle as orc

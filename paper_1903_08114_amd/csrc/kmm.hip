@@ -308,7 +308,7 @@ namespace {
 Plan plan_for_mode(int64_t npad_rows, int64_t npad_cols, int ks, int d, int nb, int extra) {
   if (ks > 8) return make_plan_wide(npad_rows, npad_cols, ks, nb, extra);     // d > 31: fp32 wide kernel in every mode
   return kmm_mode() == EGP_KMM_SPLIT_BF16_ALL ? make_plan_bf(npad_rows, npad_cols, d, nb, extra)
-                                              : make_plan(npad_rows, npad_cols, ks);
+                                              : make_plan(npad_rows, npad_cols, ks, nb, extra);
 }
 int max_splits(int64_t npad_rows, int64_t npad_cols) {     // over every launch shape of every mode
   int wmax = 0;
@@ -317,7 +317,8 @@ int max_splits(int64_t npad_rows, int64_t npad_cols) {     // over every launch 
       const int s = make_plan_wide(npad_rows, npad_cols, ks, nb, 1).splits;
       if (s > wmax) wmax = s;
     }
-  const int a0 = make_plan(npad_rows, npad_cols, 1).splits;
+  const int a1 = make_plan(npad_rows, npad_cols, 1).splits, a2 = make_plan(npad_rows, npad_cols, 1, 2, 1).splits;
+  const int a0 = a1 > a2 ? a1 : a2;
   const int a = a0 > wmax ? a0 : wmax;
   const int b = make_plan_bf(npad_rows, npad_cols, 1, 1, 0).splits;
   const int c = make_plan_bf(npad_rows, npad_cols, 1, 2, 1).splits;

@@ -72,6 +72,13 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel(const float* __restrict__ X
   f4 cq[R];
   f4 o[R][NB];
   float eacc[R];
+  // Two-level accumulation: `o` sums a block of kFlushCols column points and is then folded into `o2`. A single
+  // fp32 accumulator over n = 10^6 terms carries a rounding error of ~2^-24 sqrt(n) relative to the sum of
+  // magnitudes (2e-5 of the result for random-sign right-hand sides at n = 2^20); with blocks of 4096 column
+  // points the two levels carry ~3e-6 together.
+  f4 o2[R][NB];
+  float eacc2[R];
+  constexpr int kFlushStages = 4096 / (16 * JT);     // blocks of 4096 column points
   const int ds = d >> 2, dq = d & 3;
 #pragma unroll
   for (int it = 0; it < R; ++it) {
@@ -85,9 +92,27 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel(const float* __restrict__ X
     const float ni = nrm[(row_tile0 + it) * 16 + p];
     cq[it] = (f4){ni, ni, ni, ni};
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) o[it][nb] = (f4){0.f, 0.f, 0.f, 0.f};
+    for (int nb = 0; nb < NB; ++nb) {
+      o[it][nb] = (f4){0.f, 0.f, 0.f, 0.f};
+      o2[it][nb] = (f4){0.f, 0.f, 0.f, 0.f};
+    }
     eacc[it] = 0.f;
+    eacc2[it] = 0.f;
   }
+  auto fold = [&]() {
+#pragma unroll
+    for (int it = 0; it < R; ++it) {
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        o2[it][nb] += o[it][nb];
+        o[it][nb] = (f4){0.f, 0.f, 0.f, 0.f};
+      }
+      if (EXTRA) {
+        eacc2[it] += eacc[it];
+        eacc[it] = 0.f;
+      }
+    }
+  };
 
   const int st_begin = blockIdx.y * stages_per_split;
   int st_end = st_begin + stages_per_split;
@@ -183,9 +208,11 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel(const float* __restrict__ X
         }
       }
     }
+    if ((st - st_begin) % kFlushStages == kFlushStages - 1) fold();
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
   }
+  fold();
 
   // ---- write raw accumulators: lane (q,p), register r holds out[row 4q + r][column p] ----
   float* dst = Part + (int64_t)blockIdx.y * npad * TS;
@@ -196,9 +223,9 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel(const float* __restrict__ X
       const int64_t row0 = (row_tile0 + it) * 16;
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb)
-        *reinterpret_cast<f4*>(dst + (int64_t)(nb * 16 + p) * npad + row0 + q * 4) = o[it][nb];
+        *reinterpret_cast<f4*>(dst + (int64_t)(nb * 16 + p) * npad + row0 + q * 4) = o2[it][nb];
       if (EXTRA) {
-        float s = eacc[it];
+        float s = eacc2[it];
         s += __shfl_xor(s, 16);
         s += __shfl_xor(s, 32);
         if (q == 0) dst[(int64_t)(16 * NB) * npad + row0 + p] = s;
@@ -212,13 +239,13 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel(const float* __restrict__ X
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       float* r0 = dst + (row0 + q * 4) * TS + nb * 16 + p;
-      r0[0 * TS] = o[it][nb].x;
-      r0[1 * TS] = o[it][nb].y;
-      r0[2 * TS] = o[it][nb].z;
-      r0[3 * TS] = o[it][nb].w;
+      r0[0 * TS] = o2[it][nb].x;
+      r0[1 * TS] = o2[it][nb].y;
+      r0[2 * TS] = o2[it][nb].z;
+      r0[3 * TS] = o2[it][nb].w;
     }
     if (EXTRA) {
-      float s = eacc[it];
+      float s = eacc2[it];
       s += __shfl_xor(s, 16);
       s += __shfl_xor(s, 32);
       if (q == 0) dst[(row0 + p) * TS + 16 * NB] = s;
@@ -236,14 +263,15 @@ struct Plan {
 // Launch shapes (row tiles per wave, column tiles per LDS stage). Up to 8 k-steps (d <= 31) the wide shape
 // keeps 8 row tiles per wave; beyond that the row operands (R * KS registers) allow 4.
 constexpr int kSmallR = 2, kSmallJT = 4;
-constexpr int big_r(int ks) { return ks <= 8 ? 8 : 4; }
+// (with two column blocks AND a 33rd column the two accumulator levels of 8 tiles exceed 256 registers: 4 tiles)
+constexpr int big_r(int ks, int nb = 1, int extra = 0) { return (ks <= 8 && !(nb == 2 && extra)) ? 8 : 4; }
 constexpr int big_jt(int ks) { return ks <= 8 ? 16 : 4; }
 
-inline Plan make_plan(int64_t npad_rows, int64_t npad_cols, int ks) {
+inline Plan make_plan(int64_t npad_rows, int64_t npad_cols, int ks, int nb = 1, int extra = 0) {
   Plan pl;
-  const int64_t big_rows = 64 * big_r(ks);
+  const int64_t big_rows = 64 * 8;
   pl.big = npad_rows / big_rows >= 64;     // enough row blocks for the wide shape to be worthwhile
-  const int R = pl.big ? big_r(ks) : kSmallR, JT = pl.big ? big_jt(ks) : kSmallJT;
+  const int R = pl.big ? big_r(ks, nb, extra) : kSmallR, JT = pl.big ? big_jt(ks) : kSmallJT;
   pl.row_blocks = (int)(npad_rows / (64 * R));
   pl.stages_total = (int)(npad_cols / (16 * JT));
   int want = 1024 / pl.row_blocks;
@@ -260,7 +288,7 @@ int launch_shape(const Prepared& P, const Prepared& Q, const Plan& pl, const f4*
                  int cm, hipStream_t stream) {   // P: column points, Q: row points
   dim3 grid(pl.row_blocks, pl.splits), block(256);
   if (pl.big) {
-    hipLaunchKernelGGL((kmm_kernel<KS, big_r(KS), KIND, NB, EXTRA, big_jt(KS), SPLIT>), grid, block, 0, stream, Q.Xp, Q.nrm,
+    hipLaunchKernelGGL((kmm_kernel<KS, big_r(KS, NB, EXTRA), KIND, NB, EXTRA, big_jt(KS), SPLIT>), grid, block, 0, stream, Q.Xp, Q.nrm,
                        P.Xp, Vp, Ep, Part, Q.npad, P.d, pl.stages_per_split, pl.stages_total, cm);
   } else {
     hipLaunchKernelGGL((kmm_kernel<KS, kSmallR, KIND, NB, EXTRA, kSmallJT, SPLIT>), grid, block, 0, stream, Q.Xp,

@@ -49,16 +49,35 @@ __global__ __launch_bounds__(256) void kmm_kernel_wide(const float* __restrict__
       dstr[e] = (s_ == ds && (l_ >> 4) == dq) ? 1.0f : -2.0f * src[e];
     }
   }
-  f4 cq[RW], o[RW][NB];
-  float eacc[RW];
+  f4 cq[RW], o[RW][NB], o2[RW][NB];      // o: current block of 4096 column points, o2: sum of the blocks
+  float eacc[RW], eacc2[RW];
 #pragma unroll
   for (int it = 0; it < RW; ++it) {
     const float ni = nrm[(row_tile0 + it) * 16 + p];
     cq[it] = (f4){ni, ni, ni, ni};
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) o[it][nb] = (f4){0.f, 0.f, 0.f, 0.f};
+    for (int nb = 0; nb < NB; ++nb) {
+      o[it][nb] = (f4){0.f, 0.f, 0.f, 0.f};
+      o2[it][nb] = (f4){0.f, 0.f, 0.f, 0.f};
+    }
     eacc[it] = 0.f;
+    eacc2[it] = 0.f;
   }
+  auto fold = [&]() {      // two-level accumulation, see kmm_kernel.h
+#pragma unroll
+    for (int it = 0; it < RW; ++it) {
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        o2[it][nb] += o[it][nb];
+        o[it][nb] = (f4){0.f, 0.f, 0.f, 0.f};
+      }
+      if (EXTRA) {
+        eacc2[it] += eacc[it];
+        eacc[it] = 0.f;
+      }
+    }
+  };
+  const int flush_stages = 256 / jt_stage;
 
   const int st_begin = blockIdx.y * stages_per_split;
   int st_end = st_begin + stages_per_split;
@@ -168,9 +187,11 @@ __global__ __launch_bounds__(256) void kmm_kernel_wide(const float* __restrict__
         }
       }
     }
+    if ((st - st_begin) % flush_stages == flush_stages - 1) fold();
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
   }
+  fold();
 
   float* dst = Part + (int64_t)blockIdx.y * npad * TS;
 #pragma unroll
@@ -179,19 +200,19 @@ __global__ __launch_bounds__(256) void kmm_kernel_wide(const float* __restrict__
     if (cm) {
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb)
-        *reinterpret_cast<f4*>(dst + (int64_t)(nb * 16 + p) * npad + row0 + q * 4) = o[it][nb];
+        *reinterpret_cast<f4*>(dst + (int64_t)(nb * 16 + p) * npad + row0 + q * 4) = o2[it][nb];
     } else {
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
         float* r0 = dst + (row0 + q * 4) * TS + nb * 16 + p;
-        r0[0 * TS] = o[it][nb].x;
-        r0[1 * TS] = o[it][nb].y;
-        r0[2 * TS] = o[it][nb].z;
-        r0[3 * TS] = o[it][nb].w;
+        r0[0 * TS] = o2[it][nb].x;
+        r0[1 * TS] = o2[it][nb].y;
+        r0[2 * TS] = o2[it][nb].z;
+        r0[3 * TS] = o2[it][nb].w;
       }
     }
     if (EXTRA) {
-      float s = eacc[it];
+      float s = eacc2[it];
       s += __shfl_xor(s, 16);
       s += __shfl_xor(s, 32);
       if (q == 0) {

@@ -136,6 +136,35 @@ def test_mbcg_converges_to_cholesky(egp, use_precond, t):
         assert res["iters"] < plain["iters"]
 
 
+@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32])
+def test_mbcg_in_bf16_split_modes(egp, mode, kind):
+    """The opt-in contraction modes keep the multiply's relative error near 1e-5, so the solver converges to the
+    same solution; the attainable true residual is that error times ||Khat|| ||u|| / ||b|| (here ~1e-3)."""
+    n, d, t = 3000, 11, 17
+    rng = np.random.default_rng(300 + mode + kind)
+    X = rng.uniform(0, 1, (n, d)).astype(np.float32)
+    B = rademacher(rng, (n, t))
+    B[:, 0] = np.sin(4 * X[:, 0]) + 0.1 * rng.standard_normal(n)
+    ls = np.exp(rng.uniform(np.log(0.3), np.log(1.5), d)).astype(np.float32)
+    s, noise = 1.0, 0.05
+    Xd, Bd = _cuda(X), _cuda(B)
+    L = egp.lib()
+    try:
+        L.egp_set_kmm_mode(mode)
+        P = egp.piv_chol_precond(Xd, ls, s, noise, kind, 30)
+        res = egp.mbcg(Xd, Bd, ls, s, noise, kind, precond=P, max_iter=400, tol=1e-3)
+    finally:
+        L.egp_set_kmm_mode(0)
+    assert res["rel_resid"].max() <= 1e-3
+    Kh = orc.khat(X, orc.Hyper(kind, ls, s, noise))
+    ref = orc.chol_solve(Kh, B)
+    U = res["U"].cpu().numpy().astype(np.float64)
+    assert np.linalg.norm(U - ref) / np.linalg.norm(ref) <= 5e-3
+    true_res = np.linalg.norm(Kh @ U - B, axis=0) / np.linalg.norm(B, axis=0)
+    assert true_res.max() <= 3e-3
+
+
 def test_mbcg_batched_equals_single_and_duplicates(egp):
     n, d = 900, 3
     rng = np.random.default_rng(2)
