@@ -163,7 +163,8 @@ __global__ __launch_bounds__(256) void pc_step(const float* __restrict__ Xp, int
 // and walks groups of 16 points: lane (q,p) loads points 16 g + 4 q .. + 3 of row p of each operand tile
 // (one 16-byte load) and feeds component s to MFMA step s. Both operands use the same point-to-step map, so
 // the pairing is consistent; the order of a sum is free. Every wave writes its own partial result
-// Cp[4 * block + wave][ra][rb]; reduce_chunks sums them in a fixed order.
+// Cp[ra][rb][4 * block + wave] (the chunk index contiguous, so that reduce_chunks reads coalesced); reduce_chunks
+// sums them in a fixed order.
 typedef float f4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ f4 load4_guarded(const float* __restrict__ row, int64_t i, int64_t n, int vec) {
@@ -221,7 +222,7 @@ __global__ __launch_bounds__(256) void gram_mfma(const float* __restrict__ A, in
     }
   }
   // accumulator layout: register r of lane (q,p) is C[16 ta + 4 q + r][16 tb + p]
-  float* dst = Cp + ((int64_t)blockIdx.x * 4 + wave) * ra * rb;
+  const int64_t chunks = (int64_t)gridDim.x * 4, chunk_id = (int64_t)blockIdx.x * 4 + wave;
 #pragma unroll
   for (int ta = 0; ta < 8; ++ta)
 #pragma unroll
@@ -230,12 +231,12 @@ __global__ __launch_bounds__(256) void gram_mfma(const float* __restrict__ A, in
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int a = a_base + ta * 16 + q * 4 + r, bcol = b_base + tb * 16 + p;
-        if (ta < nta && tb < ntb && a < ra && bcol < rb) dst[a * rb + bcol] = vals[r];
+        if (ta < nta && tb < ntb && a < ra && bcol < rb) Cp[(int64_t)(a * rb + bcol) * chunks + chunk_id] = vals[r];
       }
     }
 }
 
-// C[e] = sum over chunks of Cp[chunk][e], fp64, fixed order: 64 lanes stride the chunks, then a shuffle tree.
+// C[e] = sum over chunks of Cp[e][chunk], fp64, fixed order: 64 lanes stride the chunks, then a shuffle tree.
 // Block = 4 outputs x 64 lanes.
 __global__ __launch_bounds__(256) void reduce_chunks(const float* __restrict__ Cp, int chunks, int count,
                                                      float* __restrict__ C) {
@@ -243,25 +244,31 @@ __global__ __launch_bounds__(256) void reduce_chunks(const float* __restrict__ C
   const int lane = threadIdx.x & 63;
   double s = 0.0;
   if (e < count)
-    for (int c = lane; c < chunks; c += 64) s += (double)Cp[(int64_t)c * count + e];
+    for (int c = lane; c < chunks; c += 64) s += (double)Cp[(int64_t)e * chunks + c];
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
   if (e < count && lane == 0) C[e] = (float)s;
 }
 
-// Y[m][c] = sum_m2 Minv[m][m2] * W[m2][c] for c < t, zero for t <= c < ldy (one thread per output)
+// Y[m][c] = sum_m2 Minv[m][m2] * W[m2][c] for c < t, zero for t <= c < ldy. One wave per output: the lanes stride
+// m2, then a shuffle tree (fixed order).
 __global__ __launch_bounds__(256) void small_matmul(const float* __restrict__ Minv, const float* __restrict__ W,
                                                     int k, int t, int ldy, float* __restrict__ Y) {
-  const int e = blockIdx.x * 256 + threadIdx.x;
+  const int e = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
   if (e >= k * ldy) return;
   const int m = e / ldy, c = e % ldy;
   float acc = 0.f;
   if (c < t) {
-    if (Minv == nullptr) acc = W[m * t + c];      // identity: plain projection coefficients
-    else
-      for (int m2 = 0; m2 < k; ++m2) acc = __builtin_fmaf(Minv[m * k + m2], W[m2 * t + c], acc);
+    if (Minv == nullptr) {
+      acc = lane == 0 ? W[m * t + c] : 0.f;      // identity: plain projection coefficients
+    } else {
+      for (int m2 = lane; m2 < k; m2 += 64) acc = __builtin_fmaf(Minv[m * k + m2], W[m2 * t + c], acc);
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
   }
-  Y[e] = acc;
+  if (lane == 0) Y[e] = acc;
 }
 
 // Column-major Woodbury finish: Z[c][i] = (R[c][i] - sum_m L[m][i] Y[m][c]) / noise for i < n; optional
@@ -396,7 +403,7 @@ int precond_apply_cm(const float* L, int rank, const float* Minv_dev, int64_t n,
                      (int)((n & 3) == 0 && (reinterpret_cast<uintptr_t>(L) & 15) == 0), (int)((ld & 3) == 0));
   hipLaunchKernelGGL(reduce_chunks, dim3((rank * t + 3) / 4), dim3(256), 0, stream, Wp, chunks, rank * t, Wd);
   const int ldy = t <= 16 ? 16 : (t <= 17 ? 17 : 33);
-  hipLaunchKernelGGL(small_matmul, dim3((rank * ldy + 255) / 256), dim3(256), 0, stream, Minv_dev, Wd, rank, t, ldy,
+  hipLaunchKernelGGL(small_matmul, dim3((rank * ldy + 3) / 4), dim3(256), 0, stream, Minv_dev, Wd, rank, t, ldy,
                      Y);
   const int blocks = precond_apply_blocks(n);
   const size_t shb = 0;
