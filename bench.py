@@ -62,8 +62,8 @@ def main():
     ap.add_argument("--mbcg-iters", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kmm-only", action="store_true", help="skip preconditioner and mBCG timing")
-    ap.add_argument("--full-solve", action="store_true",
-                    help="also run the C4 solve to the paper's training tolerance (tol 1, rank 100; minutes)")
+    ap.add_argument("--no-full-solve", dest="full_solve", action="store_false",
+                    help="skip the C4 solve to the paper's training tolerance (tol 1, rank 100, at most 100 iterations; ~20 s)")
     ap.add_argument("--mll", type=int, default=0, metavar="ITERS",
                     help="also time one C5 marginal-likelihood step (n=2^21, Matern-3/2) capped at ITERS CG iterations")
     ap.add_argument("--grad", action="store_true", help="also time the C3 KMM and derivative products (n=2^18, d=25)")

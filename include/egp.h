@@ -69,8 +69,9 @@ typedef struct {
   int32_t* pivots;   /* host, capacity entries: original row indices in selection order */
   double* small;     /* host, capacity*capacity + 1 doubles: lower Cholesky factor (row-major rank x rank)
                         of noise*I + L^T L, followed at index capacity*capacity by log|P| */
-  float* small_dev;  /* device, capacity*capacity floats: inverse of noise*I + L^T L (row-major
-                        rank x rank), used by the solver to apply P^{-1} */
+  double* small_dev; /* device, capacity*capacity doubles: inverse of noise*I + L^T L (row-major
+                        rank x rank), used by the solver to apply P^{-1}. fp64 because P^{-1} r subtracts
+                        nearly equal vectors: the k x k algebra and its n-term sums run in fp64 */
 } egp_precond_t;
 
 /* out = Khat V = K(X,X) V + noise V, K never materialised (paper, Method, "Partitioned kernel MVMs":

@@ -161,7 +161,7 @@ class Precond:
         import torch
         self.n, self.capacity, self.rank = int(n), int(capacity), 0
         self.L_buf = torch.empty((capacity, n), dtype=torch.float32, device=device)
-        self.small_dev = torch.empty((capacity * capacity,), dtype=torch.float32, device=device)
+        self.small_dev = torch.empty((capacity * capacity,), dtype=torch.float64, device=device)
         self._pivots = np.zeros(capacity, dtype=np.int32)
         self._small = np.zeros(capacity * capacity + 1, dtype=np.float64)
         self.noise = None

@@ -86,10 +86,10 @@ size_t pivchol_ws_bytes(int64_t n, int d, int rank);
 int pivchol_core(const float* X, int64_t n, const egp_hyper_t* h, float tol_abs, egp_precond_t* P, void* ws,
                  hipStream_t stream);
 size_t precond_apply_ws(int64_t n, int t, int rank);
-int precond_apply_core(const float* L, int rank, const float* Minv_dev, int64_t n, float noise, const float* R,
+int precond_apply_core(const float* L, int rank, const double* Minv_dev, int64_t n, float noise, const float* R,
                        int t, float* Z, float* rz_partial, void* ws, hipStream_t stream);
 int precond_apply_blocks(int64_t n);
-int precond_apply_cm(const float* L, int rank, const float* Minv_dev, int64_t n, float noise, const float* R,
+int precond_apply_cm(const float* L, int rank, const double* Minv_dev, int64_t n, float noise, const float* R,
                      int64_t ld, int t, float* Z, float* rz_part, int part_ld, void* ws, hipStream_t stream);
 int kmm_cm_dot_blocks(int64_t npad);
 int kmm_core_cm(const Prepared& P, const float* V, int t, float* out, void* ws2, float* dot_part, int dot_ld,

@@ -163,7 +163,7 @@ MllWs mll_layout(int64_t n, int d, int tp, int rank, int max_iter) {
   const size_t vec = round_up((size_t)n * t * sizeof(float), 256);
   w.prep = prepared_bytes(n, d);
   w.Lbuf = round_up((size_t)(rank > 0 ? rank : 1) * n * sizeof(float), 256);
-  w.small_dev = round_up((size_t)(rank > 0 ? rank * rank : 1) * sizeof(float), 256);
+  w.small_dev = round_up((size_t)(rank > 0 ? rank * rank : 1) * sizeof(double), 256);
   w.B = vec;
   w.U = vec;
   w.Vp = vec;
@@ -197,7 +197,7 @@ int mll_core(const float* X, int64_t n, const float* y, const float* W1, const f
   char* w = static_cast<char*>(ws);
   char* prep_ws = w;            w += lay.prep;
   float* Lbuf = (float*)w;      w += lay.Lbuf;
-  float* small_dev = (float*)w; w += lay.small_dev;
+  double* small_dev = (double*)w; w += lay.small_dev;
   float* B = (float*)w;         w += lay.B;
   float* U = (float*)w;         w += lay.U;
   float* Vp = (float*)w;        w += lay.Vp;

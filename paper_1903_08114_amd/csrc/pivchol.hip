@@ -158,14 +158,20 @@ __global__ __launch_bounds__(256) void pc_step(const float* __restrict__ Xp, int
   }
 }
 
-// ---- C[a][b] = sum_i A[a][i] * B[b][i] (both operands contiguous in i) on the fp32 MFMA ----
-// grid = (blocks, ceil(ra/128), ceil(rb/32)), 4 waves per block; a wave owns 8 x 2 output tiles of 16 x 16
+// ---- C[a][b] = sum_i A[a][i] * B[b][i] (both operands contiguous in i) on the fp64 MFMA ----
+// Why fp64: P^{-1} r = (r - L M L^T r) / noise subtracts two vectors that agree to a relative noise / lambda in the
+// directions L captures (lambda up to ~n s, i.e. 10^-6 at n = 2^20); with L^T r, L^T L or the final combination
+// accumulated in fp32 the difference is rounding noise, r^T P^{-1} r can turn negative and CG breaks down. The
+// inputs are fp32 values; their products and sums are carried in fp64 (v_mfma_f64_16x16x4_f64, 78.6 TFLOP/s: the
+// kernel stays HBM-bound).
+// grid = (blocks, ceil(ra/64), ceil(rb/32)), 4 waves per block; a wave owns 4 x 2 output tiles of 16 x 16
 // and walks groups of 16 points: lane (q,p) loads points 16 g + 4 q .. + 3 of row p of each operand tile
 // (one 16-byte load) and feeds component s to MFMA step s. Both operands use the same point-to-step map, so
 // the pairing is consistent; the order of a sum is free. Every wave writes its own partial result
 // Cp[ra][rb][4 * block + wave] (the chunk index contiguous, so that reduce_chunks reads coalesced); reduce_chunks
 // sums them in a fixed order.
 typedef float f4 __attribute__((ext_vector_type(4)));
+typedef double d4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ f4 load4_guarded(const float* __restrict__ row, int64_t i, int64_t n, int vec) {
   f4 v = {0.f, 0.f, 0.f, 0.f};
@@ -177,27 +183,29 @@ __device__ __forceinline__ f4 load4_guarded(const float* __restrict__ row, int64
   return v;
 }
 
+constexpr int kGramTa = 4;      // 16-row tiles of A per wave
+
 __global__ __launch_bounds__(256) void gram_mfma(const float* __restrict__ A, int ra, int64_t lda,
                                                  const float* __restrict__ B, int rb, int64_t ldb, int64_t n,
-                                                 float* __restrict__ Cp, int vecA, int vecB) {
+                                                 double* __restrict__ Cp, int vecA, int vecB) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int q = lane >> 4, p = lane & 15;
-  const int a_base = blockIdx.y * 128, b_base = blockIdx.z * 32;
+  const int a_base = blockIdx.y * (16 * kGramTa), b_base = blockIdx.z * 32;
   int nta = (ra - a_base + 15) / 16;
-  if (nta > 8) nta = 8;
+  if (nta > kGramTa) nta = kGramTa;
   int ntb = (rb - b_base + 15) / 16;
   if (ntb > 2) ntb = 2;
-  f4 acc[8][2];
+  d4 acc[kGramTa][2];
 #pragma unroll
-  for (int ta = 0; ta < 8; ++ta)
+  for (int ta = 0; ta < kGramTa; ++ta)
 #pragma unroll
-    for (int tb = 0; tb < 2; ++tb) acc[ta][tb] = (f4){0.f, 0.f, 0.f, 0.f};
+    for (int tb = 0; tb < 2; ++tb) acc[ta][tb] = (d4){0.0, 0.0, 0.0, 0.0};
   const int64_t groups = (n + 15) / 16;
   for (int64_t g = (int64_t)blockIdx.x * 4 + wave; g < groups; g += (int64_t)gridDim.x * 4) {
     const int64_t i = g * 16 + q * 4;
-    f4 av[8], bv[2];
+    f4 av[kGramTa], bv[2];
 #pragma unroll
-    for (int ta = 0; ta < 8; ++ta) {
+    for (int ta = 0; ta < kGramTa; ++ta) {
       const int row = a_base + ta * 16 + p;
       av[ta] = (ta < nta && row < ra) ? load4_guarded(A + (int64_t)row * lda, i, n, vecA) : (f4){0.f, 0.f, 0.f, 0.f};
     }
@@ -207,30 +215,30 @@ __global__ __launch_bounds__(256) void gram_mfma(const float* __restrict__ A, in
       bv[tb] = (tb < ntb && row < rb) ? load4_guarded(B + (int64_t)row * ldb, i, n, vecB) : (f4){0.f, 0.f, 0.f, 0.f};
     }
 #pragma unroll
-    for (int ta = 0; ta < 8; ++ta) {
+    for (int ta = 0; ta < kGramTa; ++ta) {
       if (ta < nta) {
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb) {
           if (tb < ntb) {
-            acc[ta][tb] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[ta].x, bv[tb].x, acc[ta][tb], 0, 0, 0);
-            acc[ta][tb] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[ta].y, bv[tb].y, acc[ta][tb], 0, 0, 0);
-            acc[ta][tb] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[ta].z, bv[tb].z, acc[ta][tb], 0, 0, 0);
-            acc[ta][tb] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[ta].w, bv[tb].w, acc[ta][tb], 0, 0, 0);
+            acc[ta][tb] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)av[ta].x, (double)bv[tb].x, acc[ta][tb], 0, 0, 0);
+            acc[ta][tb] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)av[ta].y, (double)bv[tb].y, acc[ta][tb], 0, 0, 0);
+            acc[ta][tb] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)av[ta].z, (double)bv[tb].z, acc[ta][tb], 0, 0, 0);
+            acc[ta][tb] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)av[ta].w, (double)bv[tb].w, acc[ta][tb], 0, 0, 0);
           }
         }
       }
     }
   }
-  // accumulator layout: register r of lane (q,p) is C[16 ta + 4 q + r][16 tb + p]
+  // fp64 accumulator layout (differs from the fp32 one): register r of lane (q,p) is C[16 ta + 4 r + q][16 tb + p]
   const int64_t chunks = (int64_t)gridDim.x * 4, chunk_id = (int64_t)blockIdx.x * 4 + wave;
 #pragma unroll
-  for (int ta = 0; ta < 8; ++ta)
+  for (int ta = 0; ta < kGramTa; ++ta)
 #pragma unroll
     for (int tb = 0; tb < 2; ++tb) {
-      const float vals[4] = {acc[ta][tb].x, acc[ta][tb].y, acc[ta][tb].z, acc[ta][tb].w};
+      const double vals[4] = {acc[ta][tb].x, acc[ta][tb].y, acc[ta][tb].z, acc[ta][tb].w};
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const int a = a_base + ta * 16 + q * 4 + r, bcol = b_base + tb * 16 + p;
+        const int a = a_base + ta * 16 + r * 4 + q, bcol = b_base + tb * 16 + p;
         if (ta < nta && tb < ntb && a < ra && bcol < rb) Cp[(int64_t)(a * rb + bcol) * chunks + chunk_id] = vals[r];
       }
     }
@@ -238,32 +246,32 @@ __global__ __launch_bounds__(256) void gram_mfma(const float* __restrict__ A, in
 
 // C[e] = sum over chunks of Cp[e][chunk], fp64, fixed order: 64 lanes stride the chunks, then a shuffle tree.
 // Block = 4 outputs x 64 lanes.
-__global__ __launch_bounds__(256) void reduce_chunks(const float* __restrict__ Cp, int chunks, int count,
-                                                     float* __restrict__ C) {
+__global__ __launch_bounds__(256) void reduce_chunks(const double* __restrict__ Cp, int chunks, int count,
+                                                     double* __restrict__ C) {
   const int e = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   double s = 0.0;
   if (e < count)
-    for (int c = lane; c < chunks; c += 64) s += (double)Cp[(int64_t)e * chunks + c];
+    for (int c = lane; c < chunks; c += 64) s += Cp[(int64_t)e * chunks + c];
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
-  if (e < count && lane == 0) C[e] = (float)s;
+  if (e < count && lane == 0) C[e] = s;
 }
 
-// Y[m][c] = sum_m2 Minv[m][m2] * W[m2][c] for c < t, zero for t <= c < ldy. One wave per output: the lanes stride
-// m2, then a shuffle tree (fixed order).
-__global__ __launch_bounds__(256) void small_matmul(const float* __restrict__ Minv, const float* __restrict__ W,
-                                                    int k, int t, int ldy, float* __restrict__ Y) {
+// Y[m][c] = sum_m2 Minv[m][m2] * W[m2][c] for c < t, zero for t <= c < ldy (fp64). One wave per output: the
+// lanes stride m2, then a shuffle tree (fixed order).
+__global__ __launch_bounds__(256) void small_matmul(const double* __restrict__ Minv, const double* __restrict__ W,
+                                                    int k, int t, int ldy, double* __restrict__ Y) {
   const int e = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if (e >= k * ldy) return;
   const int m = e / ldy, c = e % ldy;
-  float acc = 0.f;
+  double acc = 0.0;
   if (c < t) {
     if (Minv == nullptr) {
-      acc = lane == 0 ? W[m * t + c] : 0.f;      // identity: plain projection coefficients
+      acc = lane == 0 ? W[m * t + c] : 0.0;      // identity: plain projection coefficients
     } else {
-      for (int m2 = lane; m2 < k; m2 += 64) acc = __builtin_fmaf(Minv[m * k + m2], W[m2 * t + c], acc);
+      for (int m2 = lane; m2 < k; m2 += 64) acc = fma(Minv[m * k + m2], W[m2 * t + c], acc);
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
@@ -271,47 +279,45 @@ __global__ __launch_bounds__(256) void small_matmul(const float* __restrict__ Mi
   if (lane == 0) Y[e] = acc;
 }
 
-// Column-major Woodbury finish: Z[c][i] = (R[c][i] - sum_m L[m][i] Y[m][c]) / noise for i < n; optional
-// per-block partial sums of R[c][i] Z[c][i] into rz_part[c][blockIdx]. One thread per point; Y (k x TT,
-// zero-padded columns) is indexed uniformly across the wave, so its entries arrive as scalar operands.
+// Column-major Woodbury finish: Z[c][i] = (R[c][i] - sum_m L[m][i] Y[m][c]) / noise for i < n, the sum and the
+// difference in fp64 (see gram_mfma), the result rounded to fp32; optional per-block partial sums of
+// R[c][i] Z[c][i] into rz_part[c][blockIdx]. One thread per point; Y (k x TT, zero-padded columns) is indexed
+// uniformly across the wave, so its entries arrive as scalar operands.
 template <int TT>
 __global__ __launch_bounds__(256) void woodbury_finish_cm(const float* __restrict__ L, int k, int64_t n, int64_t ldl,
-                                                          const float* __restrict__ Y, const float* __restrict__ R,
-                                                          int64_t ld, int t, float inv_noise, float* __restrict__ Z,
+                                                          const double* __restrict__ Y, const float* __restrict__ R,
+                                                          int64_t ld, int t, double inv_noise, float* __restrict__ Z,
                                                           float* __restrict__ rz_part, int part_ld) {
   __shared__ float red[4 * TT];
   float dot[TT];
 #pragma unroll
   for (int c = 0; c < TT; ++c) dot[c] = 0.f;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
-    float acc[TT];
+    double acc[TT];
 #pragma unroll
-    for (int c = 0; c < TT; ++c) acc[c] = 0.f;
+    for (int c = 0; c < TT; ++c) acc[c] = 0.0;
     const float* Li = L + i;
     int m = 0;
-    for (; m + 4 <= k; m += 4) {
-      const float l0 = Li[(int64_t)(m + 0) * ldl], l1 = Li[(int64_t)(m + 1) * ldl];
-      const float l2 = Li[(int64_t)(m + 2) * ldl], l3 = Li[(int64_t)(m + 3) * ldl];
-      const float* y = Y + m * TT;
+    for (; m + 2 <= k; m += 2) {
+      const double l0 = (double)Li[(int64_t)(m + 0) * ldl], l1 = (double)Li[(int64_t)(m + 1) * ldl];
+      const double* y = Y + m * TT;
 #pragma unroll
       for (int c = 0; c < TT; ++c) {
-        acc[c] = __builtin_fmaf(l0, y[c], acc[c]);
-        acc[c] = __builtin_fmaf(l1, y[TT + c], acc[c]);
-        acc[c] = __builtin_fmaf(l2, y[2 * TT + c], acc[c]);
-        acc[c] = __builtin_fmaf(l3, y[3 * TT + c], acc[c]);
+        acc[c] = fma(l0, y[c], acc[c]);
+        acc[c] = fma(l1, y[TT + c], acc[c]);
       }
     }
     for (; m < k; ++m) {
-      const float l = Li[(int64_t)m * ldl];
-      const float* y = Y + m * TT;
+      const double l = (double)Li[(int64_t)m * ldl];
+      const double* y = Y + m * TT;
 #pragma unroll
-      for (int c = 0; c < TT; ++c) acc[c] = __builtin_fmaf(l, y[c], acc[c]);
+      for (int c = 0; c < TT; ++c) acc[c] = fma(l, y[c], acc[c]);
     }
 #pragma unroll
     for (int c = 0; c < TT; ++c)
       if (c < t) {
         const float r = R[(int64_t)c * ld + i];
-        const float z = (r - acc[c]) * inv_noise;
+        const float z = (float)(((double)r - acc[c]) * inv_noise);
         Z[(int64_t)c * ld + i] = z;
         dot[c] = __builtin_fmaf(r, z, dot[c]);
       }
@@ -380,25 +386,25 @@ size_t precond_apply_ws(int64_t n, int t, int rank) {
   int64_t chunk;
   const int chunks = chunks_for(n, &chunk);
   const int64_t ld = padded_points(n);
-  return round_up((size_t)chunks * rank * t * sizeof(float), 256) + 2 * round_up((size_t)rank * 33 * sizeof(float), 256) +
+  return round_up((size_t)chunks * rank * t * sizeof(double), 256) + 2 * round_up((size_t)rank * 33 * sizeof(double), 256) +
          2 * round_up((size_t)ld * t * sizeof(float), 256);   // the last two: transposes for the row-major entry point
 }
 
 // Column-major core: R, Z are [t][ld]; rz_part (optional) is [t][part_ld] with precond_apply_blocks(n) entries
 // per column.
-int precond_apply_cm(const float* L, int rank, const float* Minv_dev, int64_t n, float noise, const float* R,
+int precond_apply_cm(const float* L, int rank, const double* Minv_dev, int64_t n, float noise, const float* R,
                      int64_t ld, int t, float* Z, float* rz_part, int part_ld, void* ws, hipStream_t stream) {
   if (t > 33) return fail(EGP_ERR_ARG, "preconditioner application supports t <= 33 (got %d)", t);
   ProfScope prof(kProfPrecond, stream);
   int64_t chunk;
   const int chunks = chunks_for(n, &chunk);
   char* w = static_cast<char*>(ws);
-  float* Wp = reinterpret_cast<float*>(w);
-  w += round_up((size_t)chunks * rank * t * sizeof(float), 256);
-  float* Wd = reinterpret_cast<float*>(w);
-  w += round_up((size_t)rank * 33 * sizeof(float), 256);
-  float* Y = reinterpret_cast<float*>(w);
-  dim3 grid(chunks / 4, (rank + 127) / 128, (t + 31) / 32);
+  double* Wp = reinterpret_cast<double*>(w);
+  w += round_up((size_t)chunks * rank * t * sizeof(double), 256);
+  double* Wd = reinterpret_cast<double*>(w);
+  w += round_up((size_t)rank * 33 * sizeof(double), 256);
+  double* Y = reinterpret_cast<double*>(w);
+  dim3 grid(chunks / 4, (rank + 16 * kGramTa - 1) / (16 * kGramTa), (t + 31) / 32);
   hipLaunchKernelGGL(gram_mfma, grid, dim3(256), 0, stream, L, rank, n, R, t, ld, n, Wp,
                      (int)((n & 3) == 0 && (reinterpret_cast<uintptr_t>(L) & 15) == 0), (int)((ld & 3) == 0));
   hipLaunchKernelGGL(reduce_chunks, dim3((rank * t + 3) / 4), dim3(256), 0, stream, Wp, chunks, rank * t, Wd);
@@ -407,7 +413,7 @@ int precond_apply_cm(const float* L, int rank, const float* Minv_dev, int64_t n,
                      Y);
   const int blocks = precond_apply_blocks(n);
   const size_t shb = 0;
-  const float inv_noise = 1.0f / noise;
+  const double inv_noise = 1.0 / (double)noise;
   if (t <= 16)
     hipLaunchKernelGGL(woodbury_finish_cm<16>, dim3(blocks), dim3(256), shb, stream, L, rank, n, n, Y, R, ld, t,
                        inv_noise, Z, rz_part, part_ld);
@@ -422,14 +428,14 @@ int precond_apply_cm(const float* L, int rank, const float* Minv_dev, int64_t n,
 }
 
 // Row-major entry (egp_precond_apply, egp_mll): transpose in, apply, transpose out.
-int precond_apply_core(const float* L, int rank, const float* Minv_dev, int64_t n, float noise, const float* R,
+int precond_apply_core(const float* L, int rank, const double* Minv_dev, int64_t n, float noise, const float* R,
                        int t, float* Z, float* rz_partial, void* ws, hipStream_t stream) {
   (void)rz_partial;
   int64_t chunk;
   const int chunks = chunks_for(n, &chunk);
   const int64_t ld = padded_points(n);
   char* w = static_cast<char*>(ws);
-  w += round_up((size_t)chunks * rank * t * sizeof(float), 256) + 2 * round_up((size_t)rank * 33 * sizeof(float), 256);
+  w += round_up((size_t)chunks * rank * t * sizeof(double), 256) + 2 * round_up((size_t)rank * 33 * sizeof(double), 256);
   float* Rc = reinterpret_cast<float*>(w);
   float* Zc = reinterpret_cast<float*>(w + round_up((size_t)ld * t * sizeof(float), 256));
   launch_to_colmajor(R, n, t, ld, Rc, stream);
@@ -448,14 +454,14 @@ size_t pivchol_ws_bytes(int64_t n, int d, int rank) {
   b += round_up((size_t)rank * sizeof(int), 256);                         // pivots
   b += 256;                                                               // rank, stop
   b += round_up((size_t)2 * kPcBlocks * sizeof(float), 256) * 2;          // candidates
-  b += round_up((size_t)chunks * rank * rank * sizeof(float), 256);       // Gram partials
-  b += round_up((size_t)rank * rank * sizeof(float), 256);                // Gram
+  b += round_up((size_t)chunks * rank * rank * sizeof(double), 256);      // Gram partials
+  b += round_up((size_t)rank * rank * sizeof(double), 256);               // Gram
   return b;
 }
 
 // Factor noise*I + G (fp64, host), write the lower factor + log|P| to `small`, its inverse to `inv`.
 static int small_factor(const std::vector<double>& G, int k, int cap, double noise, int64_t n, double* small,
-                        std::vector<float>* inv) {
+                        std::vector<double>* inv) {
   std::vector<double> A((size_t)k * k), Lc((size_t)k * k, 0.0);
   for (int a = 0; a < k; ++a)
     for (int b = 0; b < k; ++b) A[a * k + b] = 0.5 * (G[a * k + b] + G[b * k + a]) + (a == b ? noise : 0.0);
@@ -479,7 +485,7 @@ static int small_factor(const std::vector<double>& G, int k, int cap, double noi
     for (int b = 0; b < k; ++b) small[a * k + b] = Lc[a * k + b];
   small[(size_t)cap * cap] = logdet;
   // inverse: solve (Lc Lc^T) Xcol = e_col
-  inv->assign((size_t)k * k, 0.f);
+  inv->assign((size_t)k * k, 0.0);
   std::vector<double> y(k), x(k);
   for (int col = 0; col < k; ++col) {
     for (int i = 0; i < k; ++i) {
@@ -492,7 +498,7 @@ static int small_factor(const std::vector<double>& G, int k, int cap, double noi
       for (int c = i + 1; c < k; ++c) v -= Lc[c * k + i] * x[c];
       x[i] = v / Lc[i * k + i];
     }
-    for (int i = 0; i < k; ++i) (*inv)[(size_t)i * k + col] = (float)x[i];
+    for (int i = 0; i < k; ++i) (*inv)[(size_t)i * k + col] = x[i];
   }
   return EGP_OK;
 }
@@ -518,9 +524,9 @@ int pivchol_core(const float* X, int64_t n, const egp_hyper_t* h, float tol_abs,
   w += round_up((size_t)2 * kPcBlocks * sizeof(float), 256);
   st.cand_i = reinterpret_cast<int*>(w);
   w += round_up((size_t)2 * kPcBlocks * sizeof(float), 256);
-  float* Gp = reinterpret_cast<float*>(w);
-  w += round_up((size_t)chunks * cap * cap * sizeof(float), 256);
-  float* Gd = reinterpret_cast<float*>(w);
+  double* Gp = reinterpret_cast<double*>(w);
+  w += round_up((size_t)chunks * cap * cap * sizeof(double), 256);
+  double* Gd = reinterpret_cast<double*>(w);
 
   int64_t nb = (n + 255) / 256;
   const int blocks = (int)(nb > kPcBlocks ? kPcBlocks : nb);
@@ -544,19 +550,18 @@ int pivchol_core(const float* X, int64_t n, const egp_hyper_t* h, float tol_abs,
   }
   EGP_HIP(hipMemcpyAsync(P->pivots, st.pivots, sizeof(int) * rank, hipMemcpyDeviceToHost, stream));
   // Gram matrix of the factor's columns
-  dim3 grid(chunks / 4, (rank + 127) / 128, (rank + 31) / 32);
+  dim3 grid(chunks / 4, (rank + 16 * kGramTa - 1) / (16 * kGramTa), (rank + 31) / 32);
   const int vec = (int)((n & 3) == 0 && (reinterpret_cast<uintptr_t>(P->L) & 15) == 0);
   hipLaunchKernelGGL(gram_mfma, grid, dim3(256), 0, stream, P->L, rank, n, P->L, rank, n, n, Gp, vec, vec);
   hipLaunchKernelGGL(reduce_chunks, dim3((rank * rank + 3) / 4), dim3(256), 0, stream, Gp, chunks, rank * rank, Gd);
   EGP_HIP(hipGetLastError());
-  std::vector<float> Gh((size_t)rank * rank);
-  EGP_HIP(hipMemcpyAsync(Gh.data(), Gd, sizeof(float) * rank * rank, hipMemcpyDeviceToHost, stream));
+  std::vector<double> G((size_t)rank * rank);
+  EGP_HIP(hipMemcpyAsync(G.data(), Gd, sizeof(double) * rank * rank, hipMemcpyDeviceToHost, stream));
   EGP_HIP(hipStreamSynchronize(stream));
-  std::vector<double> G(Gh.begin(), Gh.end());
-  std::vector<float> inv;
+  std::vector<double> inv;
   rc = small_factor(G, rank, cap, (double)h->noise, n, P->small, &inv);
   if (rc != EGP_OK) return rc;
-  EGP_HIP(hipMemcpyAsync(P->small_dev, inv.data(), sizeof(float) * rank * rank, hipMemcpyHostToDevice, stream));
+  EGP_HIP(hipMemcpyAsync(P->small_dev, inv.data(), sizeof(double) * rank * rank, hipMemcpyHostToDevice, stream));
   EGP_HIP(hipStreamSynchronize(stream));
   return EGP_OK;
 }
