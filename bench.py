@@ -228,6 +228,15 @@ def main():
             result["mbcg"]["full_solve_tol1"] = {"s": time.perf_counter() - t0, "iters": full["iters"],
                                                  "rel_resid_max": float(full["rel_resid"].max()),
                                                  "resid_hist_max": [float(v) for v in full["resid_hist"].max(axis=1)]}
+            lib.egp_set_kmm_mode(2)
+            t0 = time.perf_counter()
+            full2 = egp.mbcg(X, B17, w.lengthscales, w.outputscale, w.noise, w.kernel_type, precond=P,
+                             max_iter=w.max_iter, tol=w.tol)
+            torch.cuda.synchronize()
+            lib.egp_set_kmm_mode(0)
+            result["mbcg"]["full_solve_tol1_split_bf16_all_mode"] = {
+                "s": time.perf_counter() - t0, "iters": full2["iters"],
+                "rel_resid_max": float(full2["rel_resid"].max())}
         del P
         progress("C4 solver legs done")
 
