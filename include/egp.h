@@ -50,7 +50,7 @@ typedef enum { EGP_RBF = 0, EGP_MATERN32 = 1, EGP_MATERN52 = 2 } egp_kernel_t;
 #define EGP_D_WIDE_MAX 399  /* largest input dimension of every other entry point (d > 31 runs variants that keep
                                the row operands in LDS) */
 #define EGP_T_MAX 1024   /* largest number of right-hand-side columns */
-#define EGP_RANK_MAX 256 /* largest preconditioner rank */
+#define EGP_RANK_MAX 1024 /* largest preconditioner rank and Lanczos cache rank */
 
 typedef struct {
   int32_t kernel_type;        /* egp_kernel_t */

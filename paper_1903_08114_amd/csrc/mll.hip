@@ -27,17 +27,14 @@ __global__ __launch_bounds__(256) void make_probes(const float* __restrict__ L, 
                                                    const float* __restrict__ W1, const float* __restrict__ W2,
                                                    int tp, float sigma, const float* __restrict__ y,
                                                    float* __restrict__ B /*n x (tp+1)*/) {
-  extern __shared__ float w1s[];   // rank * tp
-  for (int e = threadIdx.x; e < rank * tp; e += 256) w1s[e] = W1[e];
-  __syncthreads();
-  const int t = tp + 1;
+  const int t = tp + 1;      // W1 is indexed uniformly across the wave: its entries arrive as scalar operands
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
     float acc[TT];
 #pragma unroll
     for (int c = 0; c < TT; ++c) acc[c] = 0.f;
     for (int m = 0; m < rank; ++m) {
       const float l = L[(int64_t)m * n + i];
-      const float* w = w1s + m * tp;
+      const float* w = W1 + m * tp;
 #pragma unroll
       for (int c = 0; c < TT; ++c)
         if (c < tp) acc[c] = __builtin_fmaf(l, w[c], acc[c]);
@@ -229,7 +226,7 @@ int mll_core(const float* X, int64_t n, const float* y, const float* W1, const f
     const float sigma = rank > 0 ? sqrtf(h->noise) : 1.0f;
     int64_t nb = (n + 255) / 256;
     const int blocks = (int)(nb > 2048 ? 2048 : nb);
-    const size_t shb = (size_t)(rank > 0 ? rank : 1) * tp * sizeof(float);
+    const size_t shb = 0;
     if (tp <= 16)
       hipLaunchKernelGGL(make_probes<16>, dim3(blocks), dim3(256), shb, stream, Lbuf, rank, n, W1, W2, tp, sigma, y, B);
     else

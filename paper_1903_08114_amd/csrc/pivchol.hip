@@ -363,9 +363,16 @@ int gram_blocks(int64_t n) {
   if (b > 1024) b = 1024;
   return (int)b;
 }
-int chunks_for(int64_t n, int64_t* chunk_out) {
-  *chunk_out = 0;
-  return 4 * gram_blocks(n);
+// Partial results of a Gram product with ra x rb outputs: the grid's y and z dimensions already spread the output
+// tiles, so the point range is cut into only as many chunks as keep ~4096 waves in flight (a multiple of 4: one
+// chunk per wave of a block). Keeps the partial buffer small at high rank.
+int chunks_for(int64_t n, int ra, int rb) {
+  const int tiles = ((ra + 16 * kGramTa - 1) / (16 * kGramTa)) * ((rb + 31) / 32);
+  int c = 4096 / (tiles > 0 ? tiles : 1);
+  c &= ~3;
+  if (c < 4) c = 4;
+  const int cap = 4 * gram_blocks(n);
+  return c < cap ? c : cap;
 }
 
 }  // namespace
@@ -382,11 +389,24 @@ int precond_apply_blocks(int64_t n) {
   return (int)(b > 1024 ? 1024 : b);
 }
 
+// Upper bound, in doubles, of chunks_for(n, r, r) * r * r over every r <= cap (the factorisation may stop early)
+static size_t gram_partial_doubles(int64_t n, int cap) {
+  const size_t a = (size_t)4 * gram_blocks(n) * cap * cap;
+  const size_t b = (size_t)4096 * 2048 + (size_t)4 * cap * cap;
+  return a < b ? a : b;
+}
+
+// Upper bound, in doubles, of chunks_for(n, r, t) * r * t over every r <= rank (the Lanczos process applies
+// projections of growing rank through the same workspace)
+static size_t apply_partial_doubles(int64_t n, int rank, int t) {
+  const size_t a = (size_t)4 * gram_blocks(n) * rank * t;
+  const size_t b = (size_t)4096 * 64 * t + (size_t)4 * rank * t;
+  return a < b ? a : b;
+}
+
 size_t precond_apply_ws(int64_t n, int t, int rank) {
-  int64_t chunk;
-  const int chunks = chunks_for(n, &chunk);
   const int64_t ld = padded_points(n);
-  return round_up((size_t)chunks * rank * t * sizeof(double), 256) + 2 * round_up((size_t)rank * 33 * sizeof(double), 256) +
+  return round_up(apply_partial_doubles(n, rank, t) * sizeof(double), 256) + 2 * round_up((size_t)rank * 33 * sizeof(double), 256) +
          2 * round_up((size_t)ld * t * sizeof(float), 256);   // the last two: transposes for the row-major entry point
 }
 
@@ -396,11 +416,10 @@ int precond_apply_cm(const float* L, int rank, const double* Minv_dev, int64_t n
                      int64_t ld, int t, float* Z, float* rz_part, int part_ld, void* ws, hipStream_t stream) {
   if (t > 33) return fail(EGP_ERR_ARG, "preconditioner application supports t <= 33 (got %d)", t);
   ProfScope prof(kProfPrecond, stream);
-  int64_t chunk;
-  const int chunks = chunks_for(n, &chunk);
+  const int chunks = chunks_for(n, rank, t);
   char* w = static_cast<char*>(ws);
   double* Wp = reinterpret_cast<double*>(w);
-  w += round_up((size_t)chunks * rank * t * sizeof(double), 256);
+  w += round_up((size_t)chunks * rank * t * sizeof(double), 256);      // within the bound precond_apply_ws reserves
   double* Wd = reinterpret_cast<double*>(w);
   w += round_up((size_t)rank * 33 * sizeof(double), 256);
   double* Y = reinterpret_cast<double*>(w);
@@ -431,8 +450,7 @@ int precond_apply_cm(const float* L, int rank, const double* Minv_dev, int64_t n
 int precond_apply_core(const float* L, int rank, const double* Minv_dev, int64_t n, float noise, const float* R,
                        int t, float* Z, float* rz_partial, void* ws, hipStream_t stream) {
   (void)rz_partial;
-  int64_t chunk;
-  const int chunks = chunks_for(n, &chunk);
+  const int chunks = chunks_for(n, rank, t);
   const int64_t ld = padded_points(n);
   char* w = static_cast<char*>(ws);
   w += round_up((size_t)chunks * rank * t * sizeof(double), 256) + 2 * round_up((size_t)rank * 33 * sizeof(double), 256);
@@ -447,14 +465,12 @@ int precond_apply_core(const float* L, int rank, const double* Minv_dev, int64_t
 }
 
 size_t pivchol_ws_bytes(int64_t n, int d, int rank) {
-  int64_t chunk;
-  const int chunks = chunks_for(n, &chunk);
   size_t b = prepared_bytes(n, d);
   b += round_up((size_t)n * sizeof(float), 256);                          // diag
   b += round_up((size_t)rank * sizeof(int), 256);                         // pivots
   b += 256;                                                               // rank, stop
   b += round_up((size_t)2 * kPcBlocks * sizeof(float), 256) * 2;          // candidates
-  b += round_up((size_t)chunks * rank * rank * sizeof(double), 256);      // Gram partials
+  b += round_up(gram_partial_doubles(n, rank) * sizeof(double), 256);      // Gram partials
   b += round_up((size_t)rank * rank * sizeof(double), 256);               // Gram
   return b;
 }
@@ -486,17 +502,22 @@ static int small_factor(const std::vector<double>& G, int k, int cap, double noi
   small[(size_t)cap * cap] = logdet;
   // inverse: solve (Lc Lc^T) Xcol = e_col
   inv->assign((size_t)k * k, 0.0);
-  std::vector<double> y(k), x(k);
+  std::vector<double> y(k), x(k), Lt((size_t)k * k);
+  for (int a = 0; a < k; ++a)
+    for (int b = 0; b < k; ++b) Lt[(size_t)b * k + a] = Lc[(size_t)a * k + b];      // contiguous rows for the back substitution
   for (int col = 0; col < k; ++col) {
-    for (int i = 0; i < k; ++i) {
+    for (int i = 0; i < col; ++i) y[i] = 0.0;                                       // e_col starts with zeros
+    for (int i = col; i < k; ++i) {
       double v = (i == col) ? 1.0 : 0.0;
-      for (int c = 0; c < i; ++c) v -= Lc[i * k + c] * y[c];
-      y[i] = v / Lc[i * k + i];
+      const double* li = &Lc[(size_t)i * k];
+      for (int c = col; c < i; ++c) v -= li[c] * y[c];
+      y[i] = v / li[i];
     }
     for (int i = k - 1; i >= 0; --i) {
       double v = y[i];
-      for (int c = i + 1; c < k; ++c) v -= Lc[c * k + i] * x[c];
-      x[i] = v / Lc[i * k + i];
+      const double* lt = &Lt[(size_t)i * k];
+      for (int c = i + 1; c < k; ++c) v -= lt[c] * x[c];
+      x[i] = v / lt[i];
     }
     for (int i = 0; i < k; ++i) (*inv)[(size_t)i * k + col] = x[i];
   }
@@ -509,8 +530,6 @@ int pivchol_core(const float* X, int64_t n, const egp_hyper_t* h, float tol_abs,
   Prepared prep;
   int rc = prepare_points(X, n, h, ws, &prep, stream);
   if (rc != EGP_OK) return rc;
-  int64_t chunk;
-  const int chunks = chunks_for(n, &chunk);
   char* w = static_cast<char*>(ws) + prepared_bytes(n, h->d);
   float* diag = reinterpret_cast<float*>(w);
   w += round_up((size_t)n * sizeof(float), 256);
@@ -525,7 +544,7 @@ int pivchol_core(const float* X, int64_t n, const egp_hyper_t* h, float tol_abs,
   st.cand_i = reinterpret_cast<int*>(w);
   w += round_up((size_t)2 * kPcBlocks * sizeof(float), 256);
   double* Gp = reinterpret_cast<double*>(w);
-  w += round_up((size_t)chunks * cap * cap * sizeof(double), 256);
+  w += round_up(gram_partial_doubles(n, cap) * sizeof(double), 256);
   double* Gd = reinterpret_cast<double*>(w);
 
   int64_t nb = (n + 255) / 256;
@@ -550,6 +569,7 @@ int pivchol_core(const float* X, int64_t n, const egp_hyper_t* h, float tol_abs,
   }
   EGP_HIP(hipMemcpyAsync(P->pivots, st.pivots, sizeof(int) * rank, hipMemcpyDeviceToHost, stream));
   // Gram matrix of the factor's columns
+  const int chunks = chunks_for(n, rank, rank);
   dim3 grid(chunks / 4, (rank + 16 * kGramTa - 1) / (16 * kGramTa), (rank + 31) / 32);
   const int vec = (int)((n & 3) == 0 && (reinterpret_cast<uintptr_t>(P->L) & 15) == 0);
   hipLaunchKernelGGL(gram_mfma, grid, dim3(256), 0, stream, P->L, rank, n, P->L, rank, n, n, Gp, vec, vec);

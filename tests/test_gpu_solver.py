@@ -69,6 +69,38 @@ def test_precond_apply_matches_dense_solve(egp, t):
     assert np.linalg.norm(Z - ref) / np.linalg.norm(ref) <= 1e-4
 
 
+@pytest.mark.parametrize("rank", [300, 1024])
+def test_high_rank_preconditioner_small_noise(egp, rank):
+    """Rank up to EGP_RANK_MAX with lambda_max / noise ~ 10^6: P^{-1} R loses everything to cancellation unless the
+    k x k algebra and its n-term sums are carried in fp64. Checked against the dense fp64 solve with the GPU's own L
+    (P is defined by the stored factor), on a smooth right-hand side that lives in the range of L."""
+    n, d = 3000, 2
+    rng = np.random.default_rng(rank)
+    X = rng.uniform(0, 1, (n, d)).astype(np.float32)
+    ls = np.full(d, 0.3, np.float32)
+    s, noise, kind = 2.0, 1e-3, orc.MATERN32      # slowly decaying spectrum: every requested step is taken
+    P = egp.piv_chol_precond(_cuda(X), ls, s, noise, kind, rank)
+    assert P.rank == rank
+    Lg = P.L.cpu().numpy().astype(np.float64).T
+    R = np.stack([np.sin(3 * X[:, 0]) + X[:, 1], np.cos(2 * X[:, 1]), rng.standard_normal(n)], axis=1).astype(np.float32)
+    Z = egp.precond_apply(P, _cuda(R)).cpu().numpy().astype(np.float64)
+    ref = orc.precond_solve(Lg, noise, R)
+    for c in range(3):
+        assert np.linalg.norm(Z[:, c] - ref[:, c]) / np.linalg.norm(ref[:, c]) <= 1e-4, c
+    # r^T P^{-1} r stays positive and accurate for the smooth columns (where the fp32 version produced noise)
+    for c in range(2):
+        assert abs(R[:, c].astype(np.float64) @ Z[:, c] - R[:, c].astype(np.float64) @ ref[:, c]) <= \
+            1e-4 * abs(R[:, c].astype(np.float64) @ ref[:, c])
+    assert abs(P.logdet - orc.precond_logdet(Lg, noise)) <= 1e-6 * abs(orc.precond_logdet(Lg, noise)) + 1e-3
+    # the solver uses it: convergence to the dense solution
+    B = R[:, :2].copy()
+    res = egp.mbcg(_cuda(X), _cuda(B), ls, s, noise, kind, precond=P, max_iter=300, tol=1e-4)
+    assert res["rel_resid"].max() <= 1e-4
+    Kh = orc.khat(X, orc.Hyper(kind, ls, s, noise))
+    true_res = np.linalg.norm(Kh @ res["U"].cpu().numpy().astype(np.float64) - B, axis=0) / np.linalg.norm(B, axis=0)
+    assert true_res.max() <= 5e-3
+
+
 def test_mbcg_c1(egp):
     """C1: 20 iterations, rank-5 preconditioner; compared with the oracle's column-by-column PCG run with
     the same preconditioner, and with the Cholesky solution."""
