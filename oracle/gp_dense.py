@@ -38,7 +38,8 @@ __all__ = [
     "kmm_rows", "dkernel_dlengthscale", "kmm_grad", "kmm_grad_rows", "chol_solve", "logdet",
     "mll", "mll_grad", "pivoted_cholesky", "precond_matrix", "precond_solve", "precond_logdet",
     "pcg", "tridiag_from_cg", "slq_quadrature", "slq_logdet", "probes_with_cov_P",
-    "mll_stochastic_terms", "predict_exact", "lanczos", "predict_var_lanczos", "train_adam",
+    "mll_stochastic_terms", "predict_exact", "lanczos", "predict_var_lanczos", "block_lanczos",
+    "predict_var_galerkin", "train_adam",
 ]
 
 
@@ -391,6 +392,43 @@ def predict_var_lanczos(Kq, Q, alpha, beta, outputscale):
     T = np.diag(alpha) + (np.diag(beta, 1) + np.diag(beta, -1) if m > 1 else 0.0)
     G = np.asarray(Kq, np.float64) @ np.asarray(Q, np.float64).T
     return outputscale - np.sum(G * np.linalg.solve(T, G.T).T, axis=1)
+
+
+def block_lanczos(Khat, B0, m):
+    """Orthonormal basis of the block Krylov space span{B0, Khat B0, .., Khat^(m-1) B0} and the projected matrix.
+
+    The variance cache only needs an orthonormal Q and T = Q Khat Q^T (the Galerkin approximation Q^T T^{-1} Q of
+    Khat^{-1}, never above Khat^{-1}); a block of b start vectors makes every multiply with Khat carry b columns.
+    Plain block Gram-Schmidt: W = Khat Q_j, two projection passes against all earlier vectors, thin QR of the
+    remainder gives Q_{j+1}. Stops when a remainder loses rank. Returns Q (r x n, orthonormal rows) and T (r x r),
+    which is block tridiagonal up to rounding (it is formed as Q Khat Q^T, not assumed)."""
+    Khat = np.asarray(Khat, np.float64)
+    B0 = np.asarray(B0, np.float64)
+    if B0.ndim == 1:
+        B0 = B0[:, None]
+    Qb, R0 = np.linalg.qr(B0)
+    if np.min(np.abs(np.diag(R0))) <= 1e-12 * np.max(np.abs(np.diag(R0))):
+        raise ValueError("start block is rank deficient")
+    blocks = [Qb]
+    for _ in range(m - 1):
+        W = Khat @ blocks[-1]
+        Qall = np.concatenate(blocks, axis=1)
+        for _ in range(2):
+            W = W - Qall @ (Qall.T @ W)
+        Qn, Rn = np.linalg.qr(W)
+        dr = np.abs(np.diag(Rn))
+        if np.min(dr) <= 1e-10 * np.linalg.norm(Khat @ blocks[-1]):
+            break
+        blocks.append(Qn)
+    Q = np.concatenate(blocks, axis=1).T
+    T = Q @ Khat @ Q.T
+    return Q, 0.5 * (T + T.T)
+
+
+def predict_var_galerkin(Kq, Q, T, outputscale):
+    """Cached predictive variance s - g^T T^{-1} g, g = Q k_q, for any orthonormal Q with T = Q Khat Q^T."""
+    G = np.asarray(Kq, np.float64) @ np.asarray(Q, np.float64).T
+    return outputscale - np.sum(G * np.linalg.solve(np.asarray(T, np.float64), G.T).T, axis=1)
 
 
 def train_adam(X, y, hyper: Hyper, steps, lr=0.1, noise_floor=0.0, rank=0, W1=None, W2=None,

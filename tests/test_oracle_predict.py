@@ -54,3 +54,43 @@ def test_lanczos_invariants_and_cached_variance():
     assert np.allclose(prev, exact, atol=1e-8)        # full Krylov space: exact
     # first Lanczos vector is the normalised start vector
     assert np.allclose(Q[0], y / np.linalg.norm(y))
+
+
+def test_block_lanczos_pins():
+    """Block Krylov basis: reduces to the single-vector process for one start vector, spans the block Krylov space,
+    gives a block-tridiagonal projection, and its Galerkin variance is an upper bound that decreases with the
+    number of blocks and is exact once the space is the whole of R^n."""
+    X, Xq, y, h = _problem(n=60)
+    rng = np.random.default_rng(8)
+    Kh = orc.khat(X, h)
+    Kq = orc.kernel_matrix(Xq, X, h)
+    _, exact = orc.predict_exact(X, y, Xq, h)
+    # (1) one start vector: same subspace, same tridiagonal (up to the sign of each basis vector), same variance
+    Q1, T1 = orc.block_lanczos(Kh, y, 12)
+    Ql, al, be = orc.lanczos(Kh, y, 12)
+    sign = np.sign(np.sum(Q1 * Ql, axis=1))
+    assert np.allclose(Q1 * sign[:, None], Ql, atol=1e-8)
+    assert np.allclose(np.diag(T1), al, atol=1e-9) and np.allclose(np.abs(np.diag(T1, 1)), be, atol=1e-9)
+    assert np.allclose(orc.predict_var_galerkin(Kq, Q1, T1, h.outputscale),
+                       orc.predict_var_lanczos(Kq, Ql, al, be, h.outputscale), atol=1e-10)
+    # (2) a block of 4: orthonormal, T = Q Khat Q^T block tridiagonal, spans [B, Khat B, Khat^2 B]
+    B0 = np.concatenate([y[:, None], rng.choice([-1.0, 1.0], size=(60, 3))], axis=1)
+    Q, T = orc.block_lanczos(Kh, B0, 3)
+    assert Q.shape == (12, 60) and np.allclose(Q @ Q.T, np.eye(12), atol=1e-10)
+    assert np.allclose(T, Q @ Kh @ Q.T, atol=1e-9)
+    assert np.abs(T[:4, 8:]).max() < 1e-8               # blocks (0, 2) vanish
+    Kry = np.concatenate([B0, Kh @ B0, Kh @ Kh @ B0], axis=1)
+    resid = Kry - Q.T @ (Q @ Kry)
+    assert np.abs(resid).max() <= 1e-8 * np.abs(Kry).max()
+    # (3) Galerkin bound, monotone in the number of blocks, exact at full dimension
+    prev = None
+    for m in (1, 3, 8, 15):
+        Qm, Tm = orc.block_lanczos(Kh, B0, m)
+        v = orc.predict_var_galerkin(Kq, Qm, Tm, h.outputscale)
+        assert np.all(v >= exact - 1e-9)
+        if prev is not None:
+            assert np.all(v <= prev + 1e-9)
+        prev = v
+    assert Qm.shape[0] == 60 and np.allclose(prev, exact, atol=1e-8)
+    # (4) planted mistake check: T without the projection (plain Khat block) must fail the identity
+    assert not np.allclose(T, Kh[:12, :12], atol=1e-3)
