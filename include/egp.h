@@ -192,7 +192,16 @@ int egp_tridiag_logquad(const double* diag, const double* off, int32_t m, double
  * egp_predict: mean (device, nq) = K(Xq, X) a with the cached solve a = Khat^{-1} y (device, n); when var is
  * not NULL, var (device, nq) = outputscale - g^T T^{-1} g with g = Q K(X, xq): the variance of the latent
  * function from the rank-r cache, O(n r) per query point and no solve. It is never below the exact variance
- * and reaches it as r grows. Synchronises. */
+ * and reaches it as r grows. Synchronises.
+ *
+ * egp_block_lanczos: the same cache from a block of b start vectors (B0: device, n x b row-major, b in 1..32; e.g.
+ * [y | random signs]). Builds an orthonormal basis Q (device, [b*blocks][n]) of span{B0, Khat B0, ..,
+ * Khat^(blocks-1) B0} and the projected matrix T = Q Khat Q^T (host, (b*blocks)^2 doubles, row-major with leading
+ * dimension b*blocks; rows and columns beyond *rows are zero). One fused multiply serves b basis vectors, which
+ * makes the cache b times cheaper per vector than egp_lanczos. *rows = b * (blocks completed), fewer than
+ * b*blocks when the Krylov space is exhausted. b*blocks in 1..EGP_RANK_MAX. Synchronises.
+ *
+ * egp_predict_dense: egp_predict with such a dense T (leading dimension ldt) in place of (alpha, beta). */
 int egp_kmm_cross(const float* Xq, int64_t nq, const float* X, int64_t n, const float* V, int32_t t,
                   const egp_hyper_t* h, float* out, void* ws, size_t ws_bytes, void* stream);
 size_t egp_kmm_cross_ws_bytes(int64_t nq, int64_t n, int32_t d, int32_t t);
@@ -203,6 +212,12 @@ int egp_predict(const float* Xq, int64_t nq, const float* X, int64_t n, const eg
                 const float* Q, int32_t r, const double* alpha, const double* beta, float* mean, float* var,
                 void* ws, size_t ws_bytes, void* stream);
 size_t egp_predict_ws_bytes(int64_t nq, int64_t n, int32_t d, int32_t r);
+int egp_block_lanczos(const float* X, int64_t n, const egp_hyper_t* h, const float* B0, int32_t b, int32_t blocks,
+                      float* Q, double* T, int32_t* rows, void* ws, size_t ws_bytes, void* stream);
+size_t egp_block_lanczos_ws_bytes(int64_t n, int32_t d, int32_t b, int32_t blocks);
+int egp_predict_dense(const float* Xq, int64_t nq, const float* X, int64_t n, const egp_hyper_t* h, const float* a,
+                      const float* Q, int32_t r, const double* T, int32_t ldt, float* mean, float* var, void* ws,
+                      size_t ws_bytes, void* stream);
 
 /* Z = P^{-1} R with P = L L^T + noise*I through the Woodbury identity, R and Z device n x t.
  * Exposed so that probe vectors and trace terms can be formed outside the solver. Asynchronous. */

@@ -104,6 +104,16 @@ def lib():
                                      C.POINTER(C.c_float), C.c_int32, C.c_int32, C.c_float, C.POINTER(_Adam),
                                      C.POINTER(_MllResult), C.POINTER(C.c_double), C.c_void_p, C.c_size_t,
                                      C.c_void_p]
+        L.egp_block_lanczos.restype = C.c_int
+        L.egp_block_lanczos.argtypes = [C.c_void_p, C.c_int64, C.POINTER(_Hyper), C.c_void_p, C.c_int32, C.c_int32,
+                                        C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int32), C.c_void_p,
+                                        C.c_size_t, C.c_void_p]
+        L.egp_block_lanczos_ws_bytes.restype = C.c_size_t
+        L.egp_block_lanczos_ws_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.c_int32]
+        L.egp_predict_dense.restype = C.c_int
+        L.egp_predict_dense.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.POINTER(_Hyper), C.c_void_p,
+                                        C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.c_int32, C.c_void_p,
+                                        C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.egp_tridiag_logquad.restype = C.c_int
         L.egp_tridiag_logquad.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_int32,
                                           C.POINTER(C.c_double)]
@@ -388,6 +398,35 @@ def lanczos(X, b, lengthscales, outputscale, noise, kernel_type, r, ws=None):
     return LanczosCache(Q[:m], alpha[:m].copy(), beta[:max(m - 1, 0)].copy(), m)
 
 
+class BlockCache:
+    """Q (rows, n) float32 CUDA tensor with orthonormal rows and the dense projected matrix T = Q Khat Q^T."""
+
+    def __init__(self, Q, T, steps):
+        self.Q, self.T, self.steps = Q, T, steps
+
+
+def block_lanczos(X, B0, lengthscales, outputscale, noise, kernel_type, blocks, ws=None):
+    """Variance cache from a block of start vectors B0 (n, b), b <= 32 (egp_block_lanczos). Returns a BlockCache with
+    up to b * blocks basis vectors; one fused multiply per block."""
+    import numpy as np
+    import torch
+    L = lib()
+    n, d = X.shape
+    b = B0.shape[1]
+    rcap = b * int(blocks)
+    h = _hyper(kernel_type, lengthscales, outputscale, noise)
+    Q = torch.zeros((rcap, n), dtype=torch.float32, device=X.device)
+    T = np.zeros((rcap, rcap), dtype=np.float64)
+    rows = C.c_int32(0)
+    if ws is None:
+        ws = _workspace(L.egp_block_lanczos_ws_bytes(n, d, b, int(blocks)), X.device)
+    _check(L.egp_block_lanczos(_dev(X, "X"), n, C.byref(h), _dev(B0, "B0"), b, int(blocks), _dev(Q, "Q"),
+                               T.ctypes.data_as(C.POINTER(C.c_double)), C.byref(rows),
+                               C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
+    m = int(rows.value)
+    return BlockCache(Q[:m], np.ascontiguousarray(T[:m, :m]), m)
+
+
 def predict(Xq, X, a, lengthscales, outputscale, noise, kernel_type, cache=None, ws=None):
     """Predictive mean K(Xq,X) a and, with a LanczosCache, the cached predictive variance (egp_predict).
     Returns (mean, var) float32 CUDA tensors of length nq (var is None without a cache)."""
@@ -402,7 +441,13 @@ def predict(Xq, X, a, lengthscales, outputscale, noise, kernel_type, cache=None,
     var = torch.empty(nq, dtype=torch.float32, device=X.device) if cache is not None else None
     if ws is None:
         ws = _workspace(L.egp_predict_ws_bytes(nq, n, d, r), X.device)
-    if cache is not None:
+    if isinstance(cache, BlockCache):
+        Q = cache.Q.contiguous()
+        T = np.ascontiguousarray(cache.T, dtype=np.float64)
+        _check(L.egp_predict_dense(_dev(Xq, "Xq"), nq, _dev(X, "X"), n, C.byref(h), _dev(a, "a"), _dev(Q, "Q"), r,
+                                   T.ctypes.data_as(C.POINTER(C.c_double)), r, _dev(mean, "mean"), _dev(var, "var"),
+                                   C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
+    elif cache is not None:
         Q = cache.Q.contiguous()
         al = np.ascontiguousarray(cache.alpha, dtype=np.float64)
         be = np.ascontiguousarray(cache.beta if r > 1 else np.zeros(1), dtype=np.float64)

@@ -328,6 +328,50 @@ int egp_lanczos(const float* X, int64_t n, const egp_hyper_t* h, const float* b,
   return lanczos_core(X, n, h, b, r, Q, alpha, beta, steps, ws, static_cast<hipStream_t>(stream));
 }
 
+size_t egp_block_lanczos_ws_bytes(int64_t n, int32_t d, int32_t b, int32_t blocks) {
+  if (n < 1 || d < 1 || d > EGP_D_WIDE_MAX || b < 1 || b > 32 || blocks < 1 || (int64_t)b * blocks > EGP_RANK_MAX) return 0;
+  return block_lanczos_ws_bytes_core(n, d, b, blocks);
+}
+
+int egp_block_lanczos(const float* X, int64_t n, const egp_hyper_t* h, const float* B0, int32_t b, int32_t blocks,
+                      float* Q, double* T, int32_t* rows, void* ws, size_t ws_bytes, void* stream) {
+  int rc;
+  if ((rc = validate_hyper(h)) != EGP_OK) return rc;
+  if ((rc = check_n(n)) != EGP_OK) return rc;
+  if (b < 1 || b > 32) return fail(EGP_ERR_ARG, "b = %d outside 1..32", b);
+  if (blocks < 1 || (int64_t)b * blocks > EGP_RANK_MAX || (int64_t)b * blocks > n)
+    return fail(EGP_ERR_ARG, "b * blocks = %lld outside 1..min(n, %d)", (long long)b * blocks, EGP_RANK_MAX);
+  if (T == nullptr || rows == nullptr) return fail(EGP_ERR_ARG, "T / rows is NULL");
+  if ((rc = validate_ptr(X, "X")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(B0, "B0")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(Q, "Q")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(ws, "ws")) != EGP_OK) return rc;
+  const size_t need = block_lanczos_ws_bytes_core(n, h->d, b, blocks);
+  if (ws_bytes < need) return fail(EGP_ERR_WS, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, need);
+  return block_lanczos_core(X, n, h, B0, b, blocks, Q, T, rows, ws, static_cast<hipStream_t>(stream));
+}
+
+int egp_predict_dense(const float* Xq, int64_t nq, const float* X, int64_t n, const egp_hyper_t* h, const float* a,
+                      const float* Q, int32_t r, const double* T, int32_t ldt, float* mean, float* var, void* ws,
+                      size_t ws_bytes, void* stream) {
+  int rc;
+  if ((rc = validate_hyper(h)) != EGP_OK) return rc;
+  if ((rc = check_n(n)) != EGP_OK) return rc;
+  if ((rc = check_n(nq)) != EGP_OK) return rc;
+  if (r < 1 || r > EGP_RANK_MAX || ldt < r) return fail(EGP_ERR_ARG, "r = %d outside 1..%d or ldt < r", r, EGP_RANK_MAX);
+  if (T == nullptr) return fail(EGP_ERR_ARG, "T is NULL");
+  if ((rc = validate_ptr(Xq, "Xq")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(X, "X")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(a, "a")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(mean, "mean")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(var, "var")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(Q, "Q")) != EGP_OK) return rc;
+  if ((rc = validate_ptr(ws, "ws")) != EGP_OK) return rc;
+  const size_t need = predict_ws_bytes_core(nq, n, h->d, r);
+  if (ws_bytes < need) return fail(EGP_ERR_WS, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, need);
+  return predict_core(Xq, nq, X, n, h, a, Q, r, nullptr, nullptr, mean, var, ws, static_cast<hipStream_t>(stream), T, ldt);
+}
+
 size_t egp_predict_ws_bytes(int64_t nq, int64_t n, int32_t d, int32_t r) {
   if (nq < 1 || n < 1 || d < 1 || d > EGP_D_WIDE_MAX || r < 0 || r > EGP_RANK_MAX) return 0;
   return predict_ws_bytes_core(nq, n, d, r);

@@ -81,7 +81,11 @@ int cross_core(const float* Xq, int64_t nq, const float* X, int64_t n, const flo
 size_t predict_ws_bytes_core(int64_t nq, int64_t n, int d, int r);
 int predict_core(const float* Xq, int64_t nq, const float* X, int64_t n, const egp_hyper_t* h, const float* a,
                  const float* Q, int r, const double* alpha, const double* beta, float* mean, float* var, void* ws,
-                 hipStream_t stream);
+                 hipStream_t stream,
+                 const double* Tdense = nullptr, int ldt = 0);
+size_t block_lanczos_ws_bytes_core(int64_t n, int d, int b, int blocks);
+int block_lanczos_core(const float* X, int64_t n, const egp_hyper_t* h, const float* B0, int b, int blocks, float* Q,
+                       double* T, int32_t* rows_out, void* ws, hipStream_t stream);
 size_t pivchol_ws_bytes(int64_t n, int d, int rank);
 int pivchol_core(const float* X, int64_t n, const egp_hyper_t* h, float tol_abs, egp_precond_t* P, void* ws,
                  hipStream_t stream);
@@ -89,8 +93,18 @@ size_t precond_apply_ws(int64_t n, int t, int rank);
 int precond_apply_core(const float* L, int rank, const double* Minv_dev, int64_t n, float noise, const float* R,
                        int t, float* Z, float* rz_partial, void* ws, hipStream_t stream);
 int precond_apply_blocks(int64_t n);
+// coef_dev / coef_ld (optional): where the k x t coefficients Y of the call live in the workspace afterwards
 int precond_apply_cm(const float* L, int rank, const double* Minv_dev, int64_t n, float noise, const float* R,
-                     int64_t ld, int t, float* Z, float* rz_part, int part_ld, void* ws, hipStream_t stream);
+                     int64_t ld, int t, float* Z, float* rz_part, int part_ld, void* ws, hipStream_t stream,
+                     const double** coef_dev = nullptr, int* coef_ld = nullptr);
+// G (device, ra x rb doubles) = A B^T over n points; A, B have one row per vector (leading dimensions lda, ldb)
+size_t gram_cm_ws_bytes(int64_t n, int ra, int rb);
+int gram_cm(const float* A, int ra, int64_t lda, const float* B, int rb, int64_t ldb, int64_t n, double* G_dev,
+            void* ws, hipStream_t stream);
+// Out[c][i] = sum_m In[m][i] Cf[m][c] for i < n (fp64 sums), zero for n <= i < ld_out; k rows in, t <= 32 rows out
+int combine_cm(const float* In, int k, int64_t ld_in, const double* Cf_dev, int t, int64_t n, float* Out,
+               int64_t ld_out, hipStream_t stream);
+void launch_to_colmajor(const float* src, int64_t n, int t, int64_t ld, float* dst, hipStream_t stream);
 int kmm_cm_dot_blocks(int64_t npad);
 int kmm_core_cm(const Prepared& P, const float* V, int t, float* out, void* ws2, float* dot_part, int dot_ld,
                 hipStream_t stream);

@@ -413,7 +413,8 @@ size_t precond_apply_ws(int64_t n, int t, int rank) {
 // Column-major core: R, Z are [t][ld]; rz_part (optional) is [t][part_ld] with precond_apply_blocks(n) entries
 // per column.
 int precond_apply_cm(const float* L, int rank, const double* Minv_dev, int64_t n, float noise, const float* R,
-                     int64_t ld, int t, float* Z, float* rz_part, int part_ld, void* ws, hipStream_t stream) {
+                     int64_t ld, int t, float* Z, float* rz_part, int part_ld, void* ws, hipStream_t stream,
+                     const double** coef_dev, int* coef_ld) {
   if (t > 33) return fail(EGP_ERR_ARG, "preconditioner application supports t <= 33 (got %d)", t);
   ProfScope prof(kProfPrecond, stream);
   const int chunks = chunks_for(n, rank, t);
@@ -428,6 +429,8 @@ int precond_apply_cm(const float* L, int rank, const double* Minv_dev, int64_t n
                      (int)((n & 3) == 0 && (reinterpret_cast<uintptr_t>(L) & 15) == 0), (int)((ld & 3) == 0));
   hipLaunchKernelGGL(reduce_chunks, dim3((rank * t + 3) / 4), dim3(256), 0, stream, Wp, chunks, rank * t, Wd);
   const int ldy = t <= 16 ? 16 : (t <= 17 ? 17 : 33);
+  if (coef_dev) *coef_dev = Y;
+  if (coef_ld) *coef_ld = ldy;
   hipLaunchKernelGGL(small_matmul, dim3((rank * ldy + 3) / 4), dim3(256), 0, stream, Minv_dev, Wd, rank, t, ldy,
                      Y);
   const int blocks = precond_apply_blocks(n);
@@ -442,6 +445,57 @@ int precond_apply_cm(const float* L, int rank, const double* Minv_dev, int64_t n
   else
     hipLaunchKernelGGL(woodbury_finish_cm<33>, dim3(blocks), dim3(256), shb, stream, L, rank, n, n, Y, R, ld, t,
                        inv_noise, Z, rz_part, part_ld);
+  EGP_HIP(hipGetLastError());
+  return EGP_OK;
+}
+
+size_t gram_cm_ws_bytes(int64_t n, int ra, int rb) {
+  return round_up((size_t)chunks_for(n, ra, rb) * ra * rb * sizeof(double), 256);
+}
+
+int gram_cm(const float* A, int ra, int64_t lda, const float* B, int rb, int64_t ldb, int64_t n, double* G_dev,
+            void* ws, hipStream_t stream) {
+  const int chunks = chunks_for(n, ra, rb);
+  double* Gp = static_cast<double*>(ws);
+  dim3 grid(chunks / 4, (ra + 16 * kGramTa - 1) / (16 * kGramTa), (rb + 31) / 32);
+  const int va = (int)((lda & 3) == 0 && (reinterpret_cast<uintptr_t>(A) & 15) == 0);
+  const int vb = (int)((ldb & 3) == 0 && (reinterpret_cast<uintptr_t>(B) & 15) == 0);
+  hipLaunchKernelGGL(gram_mfma, grid, dim3(256), 0, stream, A, ra, lda, B, rb, ldb, n, Gp, va, vb);
+  hipLaunchKernelGGL(reduce_chunks, dim3((ra * rb + 3) / 4), dim3(256), 0, stream, Gp, chunks, ra * rb, G_dev);
+  EGP_HIP(hipGetLastError());
+  return EGP_OK;
+}
+
+namespace {
+// one thread per point; the coefficients are indexed uniformly across the wave (scalar operands)
+__global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ In, int k, int64_t ld_in,
+                                                      const double* __restrict__ Cf, int t, int64_t n,
+                                                      float* __restrict__ Out, int64_t ld_out) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < ld_out; i += (int64_t)gridDim.x * 256) {
+    double acc[32];
+#pragma unroll
+    for (int c = 0; c < 32; ++c) acc[c] = 0.0;
+    if (i < n)
+      for (int m = 0; m < k; ++m) {
+        const double v = (double)In[(int64_t)m * ld_in + i];
+        const double* cf = Cf + m * t;
+#pragma unroll
+        for (int c = 0; c < 32; ++c)
+          if (c < t) acc[c] = fma(v, cf[c], acc[c]);
+      }
+#pragma unroll
+    for (int c = 0; c < 32; ++c)
+      if (c < t) Out[(int64_t)c * ld_out + i] = (float)acc[c];
+  }
+}
+}  // namespace
+
+int combine_cm(const float* In, int k, int64_t ld_in, const double* Cf_dev, int t, int64_t n, float* Out,
+               int64_t ld_out, hipStream_t stream) {
+  if (t > 32) return fail(EGP_ERR_ARG, "combine_cm supports t <= 32 (got %d)", t);
+  int64_t nb = (ld_out + 255) / 256;
+  hipLaunchKernelGGL(combine_kernel, dim3((unsigned)(nb > 2048 ? 2048 : nb)), dim3(256), 0, stream, In, k, ld_in,
+                     Cf_dev, t, n, Out, ld_out);
   EGP_HIP(hipGetLastError());
   return EGP_OK;
 }

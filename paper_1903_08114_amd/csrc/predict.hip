@@ -133,6 +133,153 @@ int lanczos_core(const float* X, int64_t n, const egp_hyper_t* h, const float* b
   return EGP_OK;
 }
 
+// ------------------------------------------------------------------------------------------------
+// Block variant: orthonormal basis of span{B0, Khat B0, .., Khat^(blocks-1) B0} and T = Q Khat Q^T (dense).
+// The variance cache only needs an orthonormal Q and the projected matrix (Galerkin: Q^T T^{-1} Q <= Khat^{-1}), and
+// a fused multiply costs the same for 1 and for 16 columns, so b start vectors make the cache b times cheaper per
+// basis vector. Per block: one multiply, two projection passes against every earlier vector (their coefficients
+// are the entries of T), Cholesky-QR applied twice to the remainder.
+// ------------------------------------------------------------------------------------------------
+namespace {
+
+struct BlockWs { size_t prep, kmm, vec, small, gram, pre, total; };
+BlockWs block_layout(int64_t n, int d, int b, int rcap) {
+  BlockWs w;
+  const int64_t ld = padded_points(n);
+  w.prep = prepared_bytes(n, d);
+  w.kmm = kmm_core_ws_bytes(n, b);
+  w.vec = 3 * round_up((size_t)ld * b * sizeof(float), 256);
+  w.small = 2 * round_up((size_t)32 * 32 * sizeof(double), 256);
+  w.gram = gram_cm_ws_bytes(n, b, b);
+  w.pre = precond_apply_ws(n, b, rcap);
+  w.total = w.prep + w.kmm + w.vec + w.small + w.gram + w.pre;
+  return w;
+}
+
+}  // namespace
+
+size_t block_lanczos_ws_bytes_core(int64_t n, int d, int b, int blocks) { return block_layout(n, d, b, b * blocks).total; }
+
+int block_lanczos_core(const float* X, int64_t n, const egp_hyper_t* h, const float* B0, int b, int blocks, float* Q,
+                       double* T, int32_t* rows_out, void* ws, hipStream_t stream) {
+  const int rcap = b * blocks;
+  const BlockWs lay = block_layout(n, h->d, b, rcap);
+  const int64_t ld = padded_points(n);
+  char* w = static_cast<char*>(ws);
+  Prepared prep;
+  int rc = prepare_points(X, n, h, w, &prep, stream);
+  if (rc != EGP_OK) return rc;
+  w += lay.prep;
+  void* kmm_ws = w;
+  w += lay.kmm;
+  const size_t vb = round_up((size_t)ld * b * sizeof(float), 256);
+  float* V = reinterpret_cast<float*>(w);
+  float* W = reinterpret_cast<float*>(w + vb);
+  float* W2 = reinterpret_cast<float*>(w + 2 * vb);
+  w += lay.vec;
+  double* Gdev = reinterpret_cast<double*>(w);
+  double* Cfdev = reinterpret_cast<double*>(w + round_up((size_t)32 * 32 * sizeof(double), 256));
+  w += lay.small;
+  void* gram_ws = w;
+  w += lay.gram;
+  void* pre_ws = w;
+
+  EGP_HIP(hipMemsetAsync(V, 0, 3 * vb, stream));      // the padding beyond n stays zero throughout
+  launch_to_colmajor(B0, n, b, ld, W, stream);
+
+  std::vector<double> G((size_t)b * b), R((size_t)b * b), Rinv((size_t)b * b);
+  // dst = src R^{-1} with src^T src = R^T R (upper R). Returns 1 when the block has lost rank.
+  auto cholqr = [&](const float* src, float* dst, int* deficient) -> int {
+    *deficient = 0;
+    int rc2 = gram_cm(src, b, ld, src, b, ld, n, Gdev, gram_ws, stream);
+    if (rc2 != EGP_OK) return rc2;
+    EGP_HIP(hipMemcpyAsync(G.data(), Gdev, sizeof(double) * b * b, hipMemcpyDeviceToHost, stream));
+    EGP_HIP(hipStreamSynchronize(stream));
+    double gmax = 0.0;
+    for (int i = 0; i < b; ++i) gmax = fmax(gmax, G[(size_t)i * b + i]);
+    std::fill(R.begin(), R.end(), 0.0);
+    for (int j = 0; j < b; ++j) {            // R^T R = G, R upper: row j of R
+      double s = G[(size_t)j * b + j];
+      for (int c = 0; c < j; ++c) s -= R[(size_t)c * b + j] * R[(size_t)c * b + j];
+      if (!(s > 1e-10 * gmax)) {
+        *deficient = 1;
+        return EGP_OK;
+      }
+      const double dj = sqrt(s);
+      R[(size_t)j * b + j] = dj;
+      for (int i = j + 1; i < b; ++i) {
+        double v = 0.5 * (G[(size_t)j * b + i] + G[(size_t)i * b + j]);
+        for (int c = 0; c < j; ++c) v -= R[(size_t)c * b + j] * R[(size_t)c * b + i];
+        R[(size_t)j * b + i] = v / dj;
+      }
+    }
+    std::fill(Rinv.begin(), Rinv.end(), 0.0);      // upper-triangular inverse by back substitution per column
+    for (int c = 0; c < b; ++c) {
+      Rinv[(size_t)c * b + c] = 1.0 / R[(size_t)c * b + c];
+      for (int i = c - 1; i >= 0; --i) {
+        double v = 0.0;
+        for (int k = i + 1; k <= c; ++k) v -= R[(size_t)i * b + k] * Rinv[(size_t)k * b + c];
+        Rinv[(size_t)i * b + c] = v / R[(size_t)i * b + i];
+      }
+    }
+    EGP_HIP(hipMemcpyAsync(Cfdev, Rinv.data(), sizeof(double) * b * b, hipMemcpyHostToDevice, stream));
+    rc2 = combine_cm(src, b, ld, Cfdev, b, n, dst, ld, stream);
+    if (rc2 != EGP_OK) return rc2;
+    EGP_HIP(hipStreamSynchronize(stream));         // Rinv (host) is reused by the next call
+    return EGP_OK;
+  };
+
+  int deficient = 0;
+  rc = cholqr(W, W2, &deficient);
+  if (rc != EGP_OK) return rc;
+  if (!deficient) rc = cholqr(W2, V, &deficient);
+  if (rc != EGP_OK) return rc;
+  if (deficient) return fail(EGP_ERR_ARG, "the start block of the block Lanczos process is rank deficient");
+  EGP_HIP(hipMemcpy2DAsync(Q, sizeof(float) * n, V, sizeof(float) * ld, sizeof(float) * n, b,
+                           hipMemcpyDeviceToDevice, stream));
+  int rtot = b;
+  std::vector<double> U((size_t)rcap * rcap, 0.0), C1, C2;
+  for (int j = 0; j < blocks; ++j) {
+    rc = kmm_core_cm(prep, V, b, W, kmm_ws, nullptr, 0, stream);      // W = Khat V_j
+    if (rc != EGP_OK) return rc;
+    const double* coef = nullptr;
+    int ldy = 0;
+    rc = precond_apply_cm(Q, rtot, nullptr, n, 1.0f, W, ld, b, W2, nullptr, 0, pre_ws, stream, &coef, &ldy);
+    if (rc != EGP_OK) return rc;
+    C1.resize((size_t)rtot * ldy);
+    EGP_HIP(hipMemcpyAsync(C1.data(), coef, sizeof(double) * rtot * ldy, hipMemcpyDeviceToHost, stream));
+    EGP_HIP(hipStreamSynchronize(stream));
+    rc = precond_apply_cm(Q, rtot, nullptr, n, 1.0f, W2, ld, b, W, nullptr, 0, pre_ws, stream, &coef, &ldy);
+    if (rc != EGP_OK) return rc;
+    C2.resize((size_t)rtot * ldy);
+    EGP_HIP(hipMemcpyAsync(C2.data(), coef, sizeof(double) * rtot * ldy, hipMemcpyDeviceToHost, stream));
+    EGP_HIP(hipStreamSynchronize(stream));
+    for (int i = 0; i < rtot; ++i)
+      for (int c = 0; c < b; ++c) U[(size_t)i * rcap + j * b + c] = C1[(size_t)i * ldy + c] + C2[(size_t)i * ldy + c];
+    if (j + 1 == blocks) break;
+    rc = cholqr(W, W2, &deficient);
+    if (rc != EGP_OK) return rc;
+    if (!deficient) rc = cholqr(W2, V, &deficient);
+    if (rc != EGP_OK) return rc;
+    if (deficient) break;                            // invariant subspace reached
+    EGP_HIP(hipMemcpy2DAsync(Q + (int64_t)rtot * n, sizeof(float) * n, V, sizeof(float) * ld, sizeof(float) * n, b,
+                             hipMemcpyDeviceToDevice, stream));
+    rtot += b;
+  }
+  // T: entries were measured as Q_all^T (Khat V_j); take the upper block triangle, symmetrise the diagonal blocks
+  for (size_t e = 0; e < (size_t)rcap * rcap; ++e) T[e] = 0.0;
+  for (int i = 0; i < rtot; ++i)
+    for (int k = i; k < rtot; ++k) {
+      double v = U[(size_t)i * rcap + k];
+      if (i / b == k / b) v = 0.5 * (v + U[(size_t)k * rcap + i]);
+      T[(size_t)i * rcap + k] = v;
+      T[(size_t)k * rcap + i] = v;
+    }
+  *rows_out = rtot;
+  EGP_HIP(hipStreamSynchronize(stream));
+  return EGP_OK;
+}
+
 size_t cross_ws_bytes_core(int64_t nq, int64_t n, int d, int t) {
   return prepared_bytes(n, d) + prepared_bytes(nq, d) + kmm_cross_ws_bytes(nq, n, t);
 }
@@ -159,7 +306,7 @@ size_t predict_ws_bytes_core(int64_t nq, int64_t n, int d, int r) {
 // mean = K(Xq, X) a; var = s - g^T T^{-1} g with g = Q K(X, xq) (var may be NULL). Synchronises.
 int predict_core(const float* Xq, int64_t nq, const float* X, int64_t n, const egp_hyper_t* h, const float* a,
                  const float* Q, int r, const double* alpha, const double* beta, float* mean, float* var, void* ws,
-                 hipStream_t stream) {
+                 hipStream_t stream, const double* Tdense, int ldt) {
   int rc = cross_core(Xq, nq, X, n, a, 1, h, mean, ws, stream, 0);
   if (rc != EGP_OK) return rc;
   if (var == nullptr) {
@@ -167,13 +314,31 @@ int predict_core(const float* Xq, int64_t nq, const float* X, int64_t n, const e
     return EGP_OK;
   }
   if (Q == nullptr || r < 1) return fail(EGP_ERR_ARG, "a variance needs the Lanczos cache (Q, alpha, beta)");
-  // Cholesky of T (host, fp64): T = Lt Lt^T with Lt lower bidiagonal (diagonal dd, sub-diagonal ee)
-  std::vector<double> dd(r), ee(r > 1 ? r - 1 : 0);
-  for (int j = 0; j < r; ++j) {
-    double s = alpha[j] - (j > 0 ? ee[j - 1] * ee[j - 1] : 0.0);
-    if (!(s > 0.0)) return fail(EGP_ERR_BREAKDOWN, "the Lanczos tridiagonal is not positive definite at step %d", j);
-    dd[j] = sqrt(s);
-    if (j + 1 < r) ee[j] = beta[j] / dd[j];
+  // Cholesky of T (host, fp64): T = Lt Lt^T with Lt lower bidiagonal (diagonal dd, sub-diagonal ee) for the
+  // tridiagonal cache, dense lower Ld for the block cache
+  std::vector<double> dd(Tdense ? 0 : r), ee(!Tdense && r > 1 ? r - 1 : 0), Ld(Tdense ? (size_t)r * r : 0, 0.0);
+  if (Tdense) {
+    for (int j = 0; j < r; ++j) {
+      double s = Tdense[(size_t)j * ldt + j];
+      for (int c = 0; c < j; ++c) s -= Ld[(size_t)j * r + c] * Ld[(size_t)j * r + c];
+      if (!(s > 0.0)) return fail(EGP_ERR_BREAKDOWN, "the projected matrix T is not positive definite at row %d", j);
+      const double dj = sqrt(s);
+      Ld[(size_t)j * r + j] = dj;
+      for (int i = j + 1; i < r; ++i) {
+        double v = Tdense[(size_t)i * ldt + j];
+        const double* li = &Ld[(size_t)i * r];
+        const double* lj = &Ld[(size_t)j * r];
+        for (int c = 0; c < j; ++c) v -= li[c] * lj[c];
+        Ld[(size_t)i * r + j] = v / dj;
+      }
+    }
+  } else {
+    for (int j = 0; j < r; ++j) {
+      double s = alpha[j] - (j > 0 ? ee[j - 1] * ee[j - 1] : 0.0);
+      if (!(s > 0.0)) return fail(EGP_ERR_BREAKDOWN, "the Lanczos tridiagonal is not positive definite at step %d", j);
+      dd[j] = sqrt(s);
+      if (j + 1 < r) ee[j] = beta[j] / dd[j];
+    }
   }
   char* w = static_cast<char*>(ws);
   const size_t sub = cross_ws_bytes_core(nq, n, h->d, predict_cross_t(r));
@@ -187,13 +352,24 @@ int predict_core(const float* Xq, int64_t nq, const float* X, int64_t n, const e
   for (int64_t qi = 0; qi < nq; ++qi) {
     // forward substitution Lt y = g, then g^T T^{-1} g = |y|^2
     double acc = 0.0;
-    for (int j = 0; j < r; ++j) {
-      double v = (double)Gh[(size_t)qi * r + j];
-      if (j > 0) v -= ee[j - 1] * y[j - 1];
-      y[j] = v / dd[j];
-      acc += y[j] * y[j];
+    if (Tdense) {
+      for (int j = 0; j < r; ++j) {
+        double v = (double)Gh[(size_t)qi * r + j];
+        const double* lj = &Ld[(size_t)j * r];
+        for (int c = 0; c < j; ++c) v -= lj[c] * y[c];
+        y[j] = v / lj[j];
+        acc += y[j] * y[j];
+      }
+    } else {
+      for (int j = 0; j < r; ++j) {
+        double v = (double)Gh[(size_t)qi * r + j];
+        if (j > 0) v -= ee[j - 1] * y[j - 1];
+        y[j] = v / dd[j];
+        acc += y[j] * y[j];
+      }
     }
-    vh[qi] = (float)((double)h->outputscale - acc);
+    const double v = (double)h->outputscale - acc;
+    vh[qi] = (float)(v > 0.0 ? v : 0.0);      // rounding can leave a tiny negative value where the cache is exact
   }
   EGP_HIP(hipMemcpyAsync(var, vh.data(), sizeof(float) * nq, hipMemcpyHostToDevice, stream));
   EGP_HIP(hipStreamSynchronize(stream));

@@ -80,7 +80,9 @@ def fit_and_predict(X, y, Xq, kernel_type=0, rank=100, probes=16, subset=10000, 
     times["solve_s"] = time.perf_counter() - t0
     say(f"solve: {sol['iters']} iterations, relative residual {float(sol['rel_resid'].max()):.3g}")
     t0 = time.perf_counter()
-    cache = egp.lanczos(Xd, yd, ls, s, noise, kernel_type, cache_rank)
+    # variance cache: block Krylov space of [y | 15 random sign vectors] (one fused multiply per 16 basis vectors)
+    B0 = np.concatenate([y[:, None], rademacher(rng, (n, 15))], axis=1)
+    cache = egp.block_lanczos(Xd, cuda(B0), ls, s, noise, kernel_type, max(1, min(cache_rank, n) // 16))
     times["cache_s"] = time.perf_counter() - t0
     # ---- predictions ----
     Xqd = cuda(Xq)

@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 
 import oracle as orc
-from workloads import make_workload, well_separated_points
+from workloads import make_workload, rademacher, well_separated_points
 
 pytestmark = pytest.mark.gpu
 KMM_TOL = 1e-4
@@ -113,3 +113,62 @@ def test_predict_c4_recipe_timing_shape(egp):
     h = orc.Hyper(w.kernel_type, w.lengthscales, w.outputscale, 0.0)
     ref = orc.kernel_matrix(Xq[:64], w.X, h) @ a.astype(np.float64)
     assert _rel(mean.cpu().numpy()[:64].astype(np.float64), ref) <= KMM_TOL
+
+
+@pytest.mark.parametrize("kind,b,blocks", [(orc.RBF, 16, 6), (orc.MATERN32, 4, 20), (orc.MATERN52, 32, 3), (orc.RBF, 1, 25)])
+def test_block_lanczos_cache(egp, kind, b, blocks):
+    """Block Krylov variance cache against the oracle's block process from the same start block: orthonormal Q,
+    T = Q Khat Q^T, and the subspace-invariant quantity — the cached variance — equal to the oracle's; never below
+    the exact variance; with b = 1 it coincides with the single-vector cache."""
+    n, nq, d = 900, 200, 2
+    rng = np.random.default_rng(31 + kind + b)
+    X = well_separated_points(6, n, d)
+    Xq = rng.uniform(0, 1, (nq, d)).astype(np.float32)
+    y = (np.sin(6 * X[:, 0]) * np.cos(4 * X[:, 1]) + 0.1 * rng.standard_normal(n)).astype(np.float32)
+    ls = np.array([0.25, 0.35], np.float32)
+    s, noise = 1.2, 0.05
+    h = orc.Hyper(kind, ls, s, noise)
+    B0 = np.concatenate([y[:, None], rademacher(rng, (n, b - 1))], axis=1) if b > 1 else y[:, None].copy()
+    Xd = _cuda(X)
+    cache = egp.block_lanczos(Xd, _cuda(B0), ls, s, noise, kind, blocks)
+    assert cache.steps == b * blocks
+    Kh = orc.khat(X, h)
+    Kq = orc.kernel_matrix(Xq, X, h)
+    Q = cache.Q.cpu().numpy().astype(np.float64)
+    assert np.abs(Q @ Q.T - np.eye(cache.steps)).max() <= 5e-5
+    Tq = Q @ Kh @ Q.T
+    assert np.abs(cache.T - Tq).max() <= 2e-4 * np.abs(Tq).max()
+    assert np.allclose(cache.T, cache.T.T)
+    Qo, To = orc.block_lanczos(Kh, B0.astype(np.float64), blocks)
+    assert Qo.shape[0] == cache.steps
+    # the first two blocks span the same space on both sides; later Krylov blocks are ill-conditioned functions of
+    # the start block (fp32 storage on one side, fp64 on the other), so from there on only what the subspaces are
+    # used for is compared: the variances
+    k2 = min(2 * b, cache.steps)
+    assert np.abs(Qo[:k2] - (Qo[:k2] @ Q[:k2].T) @ Q[:k2]).max() <= 2e-3
+    a = _cuda(orc.chol_solve(Kh, y.astype(np.float64)).astype(np.float32))
+    _, var = egp.predict(_cuda(Xq), Xd, a, ls, s, noise, kind, cache=cache)
+    var = var.cpu().numpy().astype(np.float64)
+    vo = orc.predict_var_galerkin(Kq, Qo, To, s)
+    _, exact = orc.predict_exact(X, y, Xq, h)
+    assert np.abs(var - vo).max() <= 5e-3 * s
+    assert np.all(var >= exact - 5e-3 * s)
+    if b == 1:
+        single = egp.lanczos(Xd, _cuda(y), ls, s, noise, kind, blocks)
+        _, v1 = egp.predict(_cuda(Xq), Xd, a, ls, s, noise, kind, cache=single)
+        assert np.abs(var - v1.cpu().numpy()).max() <= 2e-3 * s
+
+
+def test_block_lanczos_stops_at_an_invariant_subspace_and_rejects_bad_blocks(egp):
+    n, d = 64, 1
+    X = np.linspace(0, 1, n, dtype=np.float32)[:, None]
+    rng = np.random.default_rng(2)
+    B0 = rademacher(rng, (n, 16))
+    cache = egp.block_lanczos(_cuda(X), _cuda(B0), [0.3], 1.0, 0.1, orc.MATERN32, 4)      # 4 * 16 = n
+    assert cache.steps == 64
+    bad = B0.copy()
+    bad[:, 3] = bad[:, 1]                                                                 # rank-deficient start block
+    with pytest.raises(egp.EgpError):
+        egp.block_lanczos(_cuda(X), _cuda(bad), [0.3], 1.0, 0.1, orc.MATERN32, 2)
+    with pytest.raises(egp.EgpError):
+        egp.block_lanczos(_cuda(X), _cuda(B0), [0.3], 1.0, 0.1, orc.MATERN32, 5)          # b * blocks > n
