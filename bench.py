@@ -67,6 +67,8 @@ def main():
     ap.add_argument("--mll", type=int, default=0, metavar="ITERS",
                     help="also time one C5 marginal-likelihood step (n=2^21, Matern-3/2) capped at ITERS CG iterations")
     ap.add_argument("--grad", action="store_true", help="also time the C3 KMM and derivative products (n=2^18, d=25)")
+    ap.add_argument("--mll-rank", type=int, default=0, metavar="K",
+                    help="preconditioner rank of the C5 step (default: the configuration's 100)")
     ap.add_argument("--predict", type=int, default=0, metavar="R",
                     help="also time 1000 predictive means + cached variances against the C4 training set with a "
                          "rank-R Lanczos cache (the cache build is timed separately)")
@@ -349,17 +351,18 @@ def main():
         rng = np.random.default_rng(5)
         X5 = torch.from_numpy(w5.X).to(dev)
         y5 = torch.from_numpy(w5.y).to(dev)
-        W1 = torch.from_numpy((2.0 * rng.integers(0, 2, size=(w5.rank, 16)) - 1.0).astype(np.float32)).to(dev)
+        rank5 = args.mll_rank if args.mll_rank > 0 else w5.rank
+        W1 = torch.from_numpy((2.0 * rng.integers(0, 2, size=(rank5, 16)) - 1.0).astype(np.float32)).to(dev)
         W2 = torch.from_numpy(np.ascontiguousarray(w5.V[:, 1:17])).to(dev)
-        ws5 = torch.empty(lib.egp_mll_ws_bytes(w5.n, w5.d, 16, w5.rank, args.mll), dtype=torch.uint8, device=dev)
+        ws5 = torch.empty(lib.egp_mll_ws_bytes(w5.n, w5.d, 16, rank5, args.mll), dtype=torch.uint8, device=dev)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        r5 = egp.mll(X5, y5, W1, W2, w5.lengthscales, w5.outputscale, w5.noise, w5.kernel_type, rank=w5.rank,
+        r5 = egp.mll(X5, y5, W1, W2, w5.lengthscales, w5.outputscale, w5.noise, w5.kernel_type, rank=rank5,
                      max_iter=args.mll, tol=w5.tol, ws=ws5)
         torch.cuda.synchronize()
         result["c5_mll_step"] = {"s": time.perf_counter() - t0, "cg_iters": r5["iters"],
                                  "rel_resid_max": r5["rel_resid_max"], "mll": r5["mll"],
-                                 "workload": f"C5: n={w5.n}, d={w5.d}, Matern-3/2 ARD, 16 probes, rank {w5.rank}, "
+                                 "workload": f"C5: n={w5.n}, d={w5.d}, Matern-3/2 ARD, 16 probes, rank {rank5}, "
                                              f"CG capped at {args.mll} iterations"}
         del X5, y5, W1, W2, ws5
         progress("C5 marginal-likelihood step timed")
