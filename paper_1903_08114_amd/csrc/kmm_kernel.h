@@ -265,13 +265,17 @@ struct Plan {
 constexpr int kSmallR = 2, kSmallJT = 4;
 // (with two column blocks AND a 33rd column the two accumulator levels of 8 tiles exceed 256 registers: 4 tiles)
 constexpr int big_r(int ks, int nb = 1, int extra = 0) { return (ks <= 8 && !(nb == 2 && extra)) ? 8 : 4; }
-constexpr int big_jt(int ks) { return ks <= 8 ? 16 : 4; }
+// column tiles per stage: the largest of 16, 8, 4 whose double-buffered stage stays within 80 KB of LDS, so that
+// two workgroups share a CU (a 90 KB stage at KS = 7 or at 32 columns left one wave per SIMD)
+constexpr int big_jt(int ks, int nb = 1) {
+  return 2 * 16 * (ks * 256 + nb * 1024 + 16) <= 80 * 1024 ? 16 : (2 * 8 * (ks * 256 + nb * 1024 + 16) <= 80 * 1024 ? 8 : 4);
+}
 
 inline Plan make_plan(int64_t npad_rows, int64_t npad_cols, int ks, int nb = 1, int extra = 0) {
   Plan pl;
   const int64_t big_rows = 64 * 8;
   pl.big = npad_rows / big_rows >= 64;     // enough row blocks for the wide shape to be worthwhile
-  const int R = pl.big ? big_r(ks, nb, extra) : kSmallR, JT = pl.big ? big_jt(ks) : kSmallJT;
+  const int R = pl.big ? big_r(ks, nb, extra) : kSmallR, JT = pl.big ? big_jt(ks, nb) : kSmallJT;
   pl.row_blocks = (int)(npad_rows / (64 * R));
   pl.stages_total = (int)(npad_cols / (16 * JT));
   int want = 1024 / pl.row_blocks;
@@ -288,7 +292,7 @@ int launch_shape(const Prepared& P, const Prepared& Q, const Plan& pl, const f4*
                  int cm, hipStream_t stream) {   // P: column points, Q: row points
   dim3 grid(pl.row_blocks, pl.splits), block(256);
   if (pl.big) {
-    hipLaunchKernelGGL((kmm_kernel<KS, big_r(KS, NB, EXTRA), KIND, NB, EXTRA, big_jt(KS), SPLIT>), grid, block, 0, stream, Q.Xp, Q.nrm,
+    hipLaunchKernelGGL((kmm_kernel<KS, big_r(KS, NB, EXTRA), KIND, NB, EXTRA, big_jt(KS, NB), SPLIT>), grid, block, 0, stream, Q.Xp, Q.nrm,
                        P.Xp, Vp, Ep, Part, Q.npad, P.d, pl.stages_per_split, pl.stages_total, cm);
   } else {
     hipLaunchKernelGGL((kmm_kernel<KS, kSmallR, KIND, NB, EXTRA, kSmallJT, SPLIT>), grid, block, 0, stream, Q.Xp,
