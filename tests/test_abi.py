@@ -134,3 +134,37 @@ def test_tridiag_log_quadrature_host_helper(lib):
     # not positive definite -> error
     with pytest.raises(egp.EgpError):
         egp.tridiag_logquad(np.array([1.0, -2.0]), np.array([0.1]))
+
+
+@pytest.mark.parametrize("n", [1, 17, 4096, 100000, 1 << 21])
+@pytest.mark.parametrize("d", [1, 11, 31, 32, 90, 399])
+def test_workspace_queries_cover_every_shape(lib, n, d):
+    """Every in-range shape has a workspace size, sizes grow with the problem, out-of-range shapes report 0."""
+    prev = 0
+    for t in (1, 16, 17, 33, 64, 1024):
+        b = lib.egp_kmm_ws_bytes(n, d, t)
+        assert b > 0 and b >= prev
+        prev = b
+        assert lib.egp_kmm_cross_ws_bytes(7, n, d, t) > 0
+    assert lib.egp_kmm_ws_bytes(n, d, 1025) == 0
+    for rank in (1, 100, 1024):
+        if rank > n:
+            continue
+        pc = lib.egp_piv_chol_precond_ws_bytes(n, d, rank)
+        assert pc > 0
+        mb = lib.egp_mbcg_ws_bytes(n, d, 17, rank, 50)
+        assert mb > lib.egp_kmm_ws_bytes(n, d, 17)
+        assert lib.egp_mll_ws_bytes(n, d, 16, rank, 50) > mb
+        assert lib.egp_precond_apply_ws_bytes(n, 17, rank) > 0
+        assert lib.egp_lanczos_ws_bytes(n, d, rank) > 0
+        assert lib.egp_predict_ws_bytes(100, n, d, rank) > 0
+    assert lib.egp_piv_chol_precond_ws_bytes(n, d, 1025) == 0
+    assert lib.egp_mbcg_ws_bytes(n, d, 34, 0, 10) == 0
+    assert lib.egp_block_lanczos_ws_bytes(n, d, 16, 4) > 0
+    assert lib.egp_block_lanczos_ws_bytes(n, d, 33, 1) == 0
+    assert lib.egp_block_lanczos_ws_bytes(n, d, 32, 33) == 0          # 32 * 33 > EGP_RANK_MAX
+    assert lib.egp_kmm_grad_bilinear_ws_bytes(n, d, 36) > 0
+    assert lib.egp_kmm_grad_bilinear_ws_bytes(n, d, 37) == 0
+    assert (lib.egp_kmm_grad_ws_bytes(n, d, 16) > 0) == (d <= 31)
+    # nothing is quadratic in n: a 2^21-point problem at rank 1024 stays far below the 288 GB of one MI355X
+    assert lib.egp_mll_ws_bytes(1 << 21, d, 16, 1024, 100) < 40 * (1 << 30)
