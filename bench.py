@@ -67,6 +67,9 @@ def main():
     ap.add_argument("--mll", type=int, default=0, metavar="ITERS",
                     help="also time one C5 marginal-likelihood step (n=2^21, Matern-3/2) capped at ITERS CG iterations")
     ap.add_argument("--grad", action="store_true", help="also time the C3 KMM and derivative products (n=2^18, d=25)")
+    ap.add_argument("--wide", action="store_true",
+                    help="also time the d > 31 kernels: multiply and gradient forms at n=2^18, d=90 (the shape of the "
+                         "paper's d=90 set), uniform points, RBF")
     ap.add_argument("--mll-rank", type=int, default=0, metavar="K",
                     help="preconditioner rank of the C5 step (default: the configuration's 100)")
     ap.add_argument("--predict", type=int, default=0, metavar="R",
@@ -317,6 +320,37 @@ def main():
         result["c3"] = leg
         del X3, V3, g3, o3, wsg, wsk
         progress("C3 multiply and derivative product timed")
+
+    if args.wide:
+        nw_, dw_, tw_ = 262144, 90, 17
+        g = torch.Generator(device=dev).manual_seed(90)
+        Xw = torch.rand((nw_, dw_), device=dev, generator=g) * 2 - 1
+        Aw = torch.randn((nw_, tw_), device=dev, generator=g)
+        Bw = torch.randn((nw_, tw_), device=dev, generator=g)
+        lsw = np.full(dw_, np.sqrt(dw_), np.float32)
+        V16 = Aw[:, :16].contiguous()
+        ow = egp.kmm(Xw, V16, lsw, 1.0, 0.1, 0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(3):
+            egp.kmm(Xw, V16, lsw, 1.0, 0.1, 0, out=ow)
+        torch.cuda.synchronize()
+        kmm_s = (time.perf_counter() - t0) / 3
+        egp.kmm_grad_bilinear(Xw, Aw, Bw, lsw, 1.0, 0.1, 0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        egp.kmm_grad_bilinear(Xw, Aw, Bw, lsw, 1.0, 0.1, 0)
+        torch.cuda.synchronize()
+        bil_s = time.perf_counter() - t0
+        fk = flops_per_entry(dw_, 16, 0)
+        result["wide_d90"] = {
+            "workload": f"n={nw_}, d={dw_}, uniform points, RBF-ARD; multiply at t=16, gradient forms at t={tw_}",
+            "kmm_s": kmm_s, "kmm_entries_per_s": nw_ ** 2 / kmm_s,
+            "kmm_frac_fp32_peak": fk * nw_ ** 2 / kmm_s / 1e12 / FP32_PEAK_TFLOPS,
+            "grad_bilinear_s": bil_s,
+        }
+        del Xw, Aw, Bw, V16, ow
+        progress("d=90 multiply and gradient forms timed")
 
     if args.predict > 0:
         rng = np.random.default_rng(9)
