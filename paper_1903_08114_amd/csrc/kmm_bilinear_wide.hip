@@ -152,6 +152,10 @@ __global__ __launch_bounds__(256) void bilinear_wide_kernel(const float* __restr
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 
+  f4 rfirst[RW];      // row operands of the first group of four k-steps: resident in registers
+#pragma unroll
+  for (int it = 0; it < RW; ++it) rfirst[it] = reinterpret_cast<const f4*>(Rs + (wave * RW + it) * rowf)[lane];
+
   for (int ct = ct_begin; ct < ct_end; ++ct) {
     const int buf = nbuf == 2 ? ((ct - ct_begin) & 1) : 0;
     const bool more = ct + 1 < ct_end;
@@ -165,7 +169,6 @@ __global__ __launch_bounds__(256) void bilinear_wide_kernel(const float* __restr
     f4 acc[RW], sv[RW];
 #pragma unroll
     for (int it = 0; it < RW; ++it) {
-      acc[it] = cq[it];
       sv[it] = (f4){0.f, 0.f, 0.f, 0.f};
       rg[it] = reinterpret_cast<const f4*>(Rs + (wave * RW + it) * rowf) + lane;
       ag[it] = reinterpret_cast<const f4*>(Rs + (wave * RW + it) * rowf + ks * 64) + lane;
@@ -190,22 +193,31 @@ __global__ __launch_bounds__(256) void bilinear_wide_kernel(const float* __restr
       for (int it = 0; it < RW; ++it) dstacc[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, r[it].w, dstacc[it], 0, 0, 0);
     };
     {
-      f4 a0 = xg[0], a1, r0[RW], r1[RW];
+      // group 0 peeled: resident row operands, the row norms enter as the first MFMA's accumulator input
+      f4 a0 = xg[0], a1 = xg[64], r1[RW], r0[RW];
 #pragma unroll
-      for (int it = 0; it < RW; ++it) r0[it] = rg[it][0];
-      int g = 0;
+      for (int it = 0; it < RW; ++it) r1[it] = rg[it][64];
+#pragma unroll
+      for (int it = 0; it < RW; ++it) acc[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0.x, rfirst[it].x, cq[it], 0, 0, 0);
+#pragma unroll
+      for (int it = 0; it < RW; ++it) acc[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0.y, rfirst[it].y, acc[it], 0, 0, 0);
+#pragma unroll
+      for (int it = 0; it < RW; ++it) acc[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0.z, rfirst[it].z, acc[it], 0, 0, 0);
+#pragma unroll
+      for (int it = 0; it < RW; ++it) acc[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0.w, rfirst[it].w, acc[it], 0, 0, 0);
+      int g = 1;
       for (; g + 2 <= ks4; g += 2) {
-        a1 = xg[(g + 1) * 64];
+        a0 = xg[(g + 1) * 64];
 #pragma unroll
-        for (int it = 0; it < RW; ++it) r1[it] = rg[it][(g + 1) * 64];
-        four(acc, a0, r0);
-        const int gn = g + 2 < ks4 ? g + 2 : ks4 - 1;
-        a0 = xg[gn * 64];
-#pragma unroll
-        for (int it = 0; it < RW; ++it) r0[it] = rg[it][gn * 64];
+        for (int it = 0; it < RW; ++it) r0[it] = rg[it][(g + 1) * 64];
         four(acc, a1, r1);
+        const int gn = g + 2 < ks4 ? g + 2 : ks4 - 1;
+        a1 = xg[gn * 64];
+#pragma unroll
+        for (int it = 0; it < RW; ++it) r1[it] = rg[it][gn * 64];
+        four(acc, a0, r0);
       }
-      if (g < ks4) four(acc, a0, r0);
+      if (g < ks4) four(acc, a1, r1);
 #pragma unroll
       for (int k = 0; k < 3; ++k)
         if (k < kt) {

@@ -103,6 +103,10 @@ __global__ __launch_bounds__(256) void kmm_kernel_wide(const float* __restrict__
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 
+  f4 rfirst[RW];      // row operands of the first group of four k-steps: resident in registers
+#pragma unroll
+  for (int it = 0; it < RW; ++it) rfirst[it] = reinterpret_cast<const f4*>(Rs + (wave * RW + it) * ks * 64)[lane];
+
   for (int st = st_begin; st < st_end; ++st) {
     const int buf = (st - st_begin) & 1;
     const bool more = st + 1 < st_end;
@@ -114,10 +118,7 @@ __global__ __launch_bounds__(256) void kmm_kernel_wide(const float* __restrict__
       f4 acc[RW];
       const f4* rg[RW];
 #pragma unroll
-      for (int it = 0; it < RW; ++it) {
-        acc[it] = cq[it];
-        rg[it] = reinterpret_cast<const f4*>(Rs + (wave * RW + it) * ks * 64) + lane;
-      }
+      for (int it = 0; it < RW; ++it) rg[it] = reinterpret_cast<const f4*>(Rs + (wave * RW + it) * ks * 64) + lane;
       // left-over steps first (index clamped, so the loads need no branch): in flight while the groups run
       float ta[3], tr[RW][3];
 #pragma unroll
@@ -138,22 +139,33 @@ __global__ __launch_bounds__(256) void kmm_kernel_wide(const float* __restrict__
 #pragma unroll
         for (int it = 0; it < RW; ++it) acc[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, r[it].w, acc[it], 0, 0, 0);
       };
-      f4 a0 = xg[0], a1, r0[RW], r1[RW];
+      // Group 0 is peeled: its row operands never change (rfirst, loaded once per kernel) and its first MFMA takes
+      // the row norms as the accumulator input, so a tile starts without any register copy. There are at least
+      // two groups (KS >= 9).
+      f4 a0 = xg[0], a1 = xg[64], r1[RW], r0[RW];
 #pragma unroll
-      for (int it = 0; it < RW; ++it) r0[it] = rg[it][0];
-      int g = 0;
+      for (int it = 0; it < RW; ++it) r1[it] = rg[it][64];
+#pragma unroll
+      for (int it = 0; it < RW; ++it) acc[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0.x, rfirst[it].x, cq[it], 0, 0, 0);
+#pragma unroll
+      for (int it = 0; it < RW; ++it) acc[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0.y, rfirst[it].y, acc[it], 0, 0, 0);
+#pragma unroll
+      for (int it = 0; it < RW; ++it) acc[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0.z, rfirst[it].z, acc[it], 0, 0, 0);
+#pragma unroll
+      for (int it = 0; it < RW; ++it) acc[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0.w, rfirst[it].w, acc[it], 0, 0, 0);
+      int g = 1;
       for (; g + 2 <= ks4; g += 2) {
-        a1 = xg[(g + 1) * 64];
+        a0 = xg[(g + 1) * 64];
 #pragma unroll
-        for (int it = 0; it < RW; ++it) r1[it] = rg[it][(g + 1) * 64];
-        four(a0, r0);
-        const int gn = g + 2 < ks4 ? g + 2 : ks4 - 1;
-        a0 = xg[gn * 64];
-#pragma unroll
-        for (int it = 0; it < RW; ++it) r0[it] = rg[it][gn * 64];
+        for (int it = 0; it < RW; ++it) r0[it] = rg[it][(g + 1) * 64];
         four(a1, r1);
+        const int gn = g + 2 < ks4 ? g + 2 : ks4 - 1;
+        a1 = xg[gn * 64];
+#pragma unroll
+        for (int it = 0; it < RW; ++it) r1[it] = rg[it][gn * 64];
+        four(a0, r0);
       }
-      if (g < ks4) four(a0, r0);
+      if (g < ks4) four(a1, r1);
 #pragma unroll
       for (int k = 0; k < 3; ++k)
         if (k < kt) {
