@@ -307,6 +307,7 @@ namespace {
 
 Plan plan_for_mode(int64_t npad_rows, int64_t npad_cols, int ks, int d, int nb, int extra) {
   if (ks > 8) return make_plan_wide(npad_rows, npad_cols, ks, nb, extra);     // d > 31: fp32 wide kernel in every mode
+  if (nb == 0) return make_plan(npad_rows, npad_cols, ks, nb, extra);         // single column: fp32 kernel in every mode
   return kmm_mode() == EGP_KMM_SPLIT_BF16_ALL ? make_plan_bf(npad_rows, npad_cols, d, nb, extra)
                                               : make_plan(npad_rows, npad_cols, ks, nb, extra);
 }
@@ -328,6 +329,10 @@ int max_splits(int64_t npad_rows, int64_t npad_cols) {     // over every launch 
 int launch_ks(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, int extra, f4* Vp, const float* Ep,
               float* Part, int cm, hipStream_t stream, void* Vb) {
   if (P.ks > 8) return launch_wide(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
+  if (nb == 0) {      // a single column has no MFMA contraction to move to bf16: the fp32 kernel serves every mode
+    ProfScope prof(kProfKmm, stream);
+    return launch_all_ks<0>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
+  }
   if (kmm_mode() == EGP_KMM_SPLIT_BF16_ALL) return launch_all_bf(P, Q, pl, nb, extra, Vp, Vb, Ep, Part, cm, stream);
   if (kmm_mode() == EGP_KMM_SPLIT_BF16) {
     {
@@ -386,7 +391,8 @@ int kmm_cross(const Prepared& P, const Prepared& Q, const float* V, int t, float
   while (c0 < t) {
     const int rem = t - c0;
     int nb, extra, tg;
-    if (rem <= 16) { nb = 1; extra = 0; tg = rem; }
+    if (rem == 1 && P.ks <= 8) { nb = 0; extra = 1; tg = 1; }      // a single column: VALU contraction, no MFMA block
+    else if (rem <= 16) { nb = 1; extra = 0; tg = rem; }
     else if (rem == 17) { nb = 1; extra = 1; tg = 17; }
     else if (rem <= 32) { nb = 2; extra = 0; tg = rem; }
     else if (rem == 33) { nb = 2; extra = 1; tg = 33; }
@@ -397,8 +403,9 @@ int kmm_cross(const Prepared& P, const Prepared& Q, const float* V, int t, float
       // columns stored one after the other (e.g. Lanczos vectors): 16 columns per block, the odd one as Ep
       ProfScope prof(kProfPack, stream);
       const int64_t total = (npad >> 4) * nb * 64;
-      hipLaunchKernelGGL(pack_rhs_cm, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, V + c0 * v_ld, v_ld,
-                         npad, tg - extra, nb, Vp, P.n);
+      if (nb > 0)
+        hipLaunchKernelGGL(pack_rhs_cm, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, V + c0 * v_ld, v_ld,
+                           npad, tg - extra, nb, Vp, P.n);
       if (extra) {
         EGP_HIP(hipMemsetAsync(Ep, 0, npad * sizeof(float), stream));
         EGP_HIP(hipMemcpyAsync(Ep, V + (int64_t)(c0 + tg - 1) * v_ld, P.n * sizeof(float), hipMemcpyDeviceToDevice,
@@ -434,17 +441,18 @@ int kmm_core_cm(const Prepared& P, const float* V, int t, float* out, void* ws2,
   const int64_t npad = P.npad;
   const int splits_max = max_splits(npad, npad);
   char* w = static_cast<char*>(ws2);
-  const int nb = t > 17 ? 2 : 1;
-  const int extra = (t == 17 || t == 33) ? 1 : 0;
+  const bool single = t == 1 && P.ks <= 8;      // one column: consumed straight from the state array on the VALU
+  const int nb = single ? 0 : (t > 17 ? 2 : 1);
+  const int extra = (single || t == 17 || t == 33) ? 1 : 0;
   const Plan pl = plan_for_mode(npad, npad, P.ks, P.d, nb, extra);
   const int ts = 16 * nb + extra;
   f4* Vp = reinterpret_cast<f4*>(w);
-  w += round_up((size_t)npad * nb * 16 * sizeof(float), 256);
+  w += round_up((size_t)npad * (nb > 0 ? nb : 1) * 16 * sizeof(float), 256);
   w += round_up((size_t)npad * sizeof(float), 256);      // the row-major path's extra-column buffer (unused here)
   float* Part = reinterpret_cast<float*>(w);
   w += round_up((size_t)splits_max * npad * widest_ts(t) * sizeof(float), 256);
   void* Vb = w;
-  {
+  if (nb > 0) {
     ProfScope prof(kProfPack, stream);
     const int64_t total = (npad >> 4) * nb * 64;
     hipLaunchKernelGGL(pack_rhs_cm, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, V, npad, npad,

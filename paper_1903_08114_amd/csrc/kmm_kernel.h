@@ -52,6 +52,8 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel(const float* __restrict__ X
                                                      float* __restrict__ Part, int64_t npad, int d,
                                                      int stages_per_split, int stages_total, int cm) {
   constexpr int TS = 16 * NB + EXTRA;
+  constexpr int NBA = NB > 0 ? NB : 1;    // array extents when there is no 16-column block (single column: NB = 0, EXTRA = 1)
+  static_assert(NB > 0 || EXTRA, "a launch carries at least one column");
   constexpr int XF4 = JT * KS * 16;       // f4 elements of packed points per stage
   constexpr int VF4 = JT * NB * 64;       // f4 elements of packed V per stage
   constexpr int EF4 = JT * 4;             // f4 elements of the extra column per stage
@@ -59,7 +61,7 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel(const float* __restrict__ X
   constexpr int NV = (VF4 + 255) / 256;
 
   __shared__ f4 Xs[2][XF4];
-  __shared__ f4 Vs[2][VF4];
+  __shared__ f4 Vs[2][VF4 > 0 ? VF4 : 1];
   __shared__ f4 Es[2][EXTRA ? EF4 : 1];
 
   const int tid = threadIdx.x;
@@ -70,13 +72,13 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel(const float* __restrict__ X
   const int64_t row_tile0 = ((int64_t)blockIdx.x * 4 + wave) * R;
   float b[R][KS];
   f4 cq[R];
-  f4 o[R][NB];
+  f4 o[R][NBA];
   float eacc[R];
   // Two-level accumulation: `o` sums a block of kFlushCols column points and is then folded into `o2`. A single
   // fp32 accumulator over n = 10^6 terms carries a rounding error of ~2^-24 sqrt(n) relative to the sum of
   // magnitudes (2e-5 of the result for random-sign right-hand sides at n = 2^20); with blocks of 4096 column
   // points the two levels carry ~3e-6 together.
-  f4 o2[R][NB];
+  f4 o2[R][NBA];
   float eacc2[R];
   constexpr int kFlushStages = 4096 / (16 * JT);     // blocks of 4096 column points
   const int ds = d >> 2, dq = d & 3;
@@ -155,7 +157,7 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel(const float* __restrict__ X
       float a[KS];
 #pragma unroll
       for (int s = 0; s < KS; ++s) a[s] = xs[(jt * KS + s) * 64 + lane];
-      f4 v[NB];
+      f4 v[NBA];
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) v[nb] = Vs[buf][(jt * NB + nb) * 64 + lane];
       f4 e = {0.f, 0.f, 0.f, 0.f};
@@ -305,6 +307,7 @@ int launch_shape(const Prepared& P, const Prepared& Q, const Plan& pl, const f4*
 template <int KS, int KIND, int SPLIT>
 int launch_cols(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, int extra, const f4* Vp,
                 const float* Ep, float* Part, int cm, hipStream_t stream) {
+  if (nb == 0) return launch_shape<KS, KIND, 0, 1, SPLIT>(P, Q, pl, Vp, Ep, Part, cm, stream);      // one column, on the VALU
   if (nb == 1 && !extra) return launch_shape<KS, KIND, 1, 0, SPLIT>(P, Q, pl, Vp, Ep, Part, cm, stream);
   if (nb == 1 && extra) return launch_shape<KS, KIND, 1, 1, SPLIT>(P, Q, pl, Vp, Ep, Part, cm, stream);
   if (nb == 2 && !extra) return launch_shape<KS, KIND, 2, 0, SPLIT>(P, Q, pl, Vp, Ep, Part, cm, stream);
