@@ -240,6 +240,14 @@ typedef enum { EGP_KMM_FP32 = 0, EGP_KMM_SPLIT_BF16 = 1, EGP_KMM_SPLIT_BF16_ALL 
 int egp_set_kmm_mode(int32_t mode);
 int egp_get_kmm_mode(void);
 
+/* Host-only self-check of the launch planning, for tests; touches no GPU. The fused kernel cuts the column points
+ * into splits whose partial sums sit in the workspace before a deterministic reduction. For a product with
+ * n_rows x n_cols kernel entries and t right-hand sides in the current mode, used[0] (host) receives the largest
+ * split count any of its launches takes and sized[0] (host) the count the workspace of egp_kmm_ws_bytes /
+ * egp_kmm_cross_ws_bytes holds; used <= sized always (a launch that would break this returns EGP_ERR_WS instead of
+ * running). Returns 0, or EGP_ERR_ARG for sizes outside the library's limits or null outputs. */
+int egp_kmm_plan_splits(int64_t n_rows, int64_t n_cols, int32_t d, int32_t t, int32_t* used, int32_t* sized);
+
 /* In-stream timing of kernel groups with HIP events, for roofline reporting. While enabled, each launch
  * of a group is bracketed by an event pair on the stream it runs on. egp_profile_enable(1) clears the
  * counters; egp_profile_read waits for the recorded events, and returns the summed duration and the

@@ -77,6 +77,8 @@ def lib():
                                             C.c_void_p, C.c_size_t, C.c_void_p]
         L.egp_kmm_cross_ws_bytes.restype = C.c_size_t
         L.egp_kmm_cross_ws_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int32, C.c_int32]
+        L.egp_kmm_plan_splits.argtypes = [C.c_int64, C.c_int64, C.c_int32, C.c_int32, C.POINTER(C.c_int32),
+                                          C.POINTER(C.c_int32)]
         L.egp_kmm_cross.restype = C.c_int
         L.egp_kmm_cross.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32,
                                     C.POINTER(_Hyper), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]

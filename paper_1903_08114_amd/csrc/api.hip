@@ -112,6 +112,16 @@ int egp_set_kmm_mode(int32_t mode) {
 }
 int egp_get_kmm_mode(void) { return g_kmm_mode.load(); }
 
+int egp_kmm_plan_splits(int64_t n_rows, int64_t n_cols, int32_t d, int32_t t, int32_t* used, int32_t* sized) {
+  if (n_rows < 1 || n_cols < 1 || d < 1 || d > EGP_D_WIDE_MAX || t < 1 || t > EGP_T_MAX || !used || !sized)
+    return fail(EGP_ERR_ARG, "egp_kmm_plan_splits: size out of range or null output");
+  int u = 0, s = 0;
+  kmm_plan_splits(n_rows, n_cols, d, t, &u, &s);
+  *used = u;
+  *sized = s;
+  return EGP_OK;
+}
+
 int egp_calib_copy(const float* src, float* dst, int64_t count, void* stream) {
   int rc;
   if ((rc = validate_ptr(src, "src")) != EGP_OK) return rc;

@@ -59,6 +59,7 @@ int prepare_points(const float* X, int64_t n, const egp_hyper_t* h, void* ws, Pr
 
 // out = Khat V using prepared points. ws2 >= kmm_core_ws_bytes. V/out are row-major n x t.
 size_t kmm_core_ws_bytes(int64_t n, int t);
+void kmm_plan_splits(int64_t n_rows, int64_t n_cols, int d, int t, int* used, int* sized);   // host-only planning check
 int kmm_core(const Prepared& P, const float* V, int t, float* out, void* ws2, hipStream_t stream);
 size_t kmm_cross_ws_bytes(int64_t n_rows, int64_t n_cols, int t);
 int kmm_cross(const Prepared& P, const Prepared& Q, const float* V, int t, float* out, void* ws2,

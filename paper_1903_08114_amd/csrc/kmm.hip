@@ -307,29 +307,36 @@ namespace {
 
 Plan plan_for_mode(int64_t npad_rows, int64_t npad_cols, int ks, int d, int nb, int extra) {
   if (ks > 8) return make_plan_wide(npad_rows, npad_cols, ks, nb, extra);     // d > 31: fp32 wide kernel in every mode
-  if (nb == 0) return make_plan(npad_rows, npad_cols, ks, nb, extra);         // single column: fp32 kernel in every mode
+  if (nb == 0 && kmm_mode() != EGP_KMM_SPLIT_BF16_ALL)
+    return make_plan(npad_rows, npad_cols, ks, nb, extra);     // a single column has no contraction to split
   return kmm_mode() == EGP_KMM_SPLIT_BF16_ALL ? make_plan_bf(npad_rows, npad_cols, d, nb, extra)
                                               : make_plan(npad_rows, npad_cols, ks, nb, extra);
 }
-int max_splits(int64_t npad_rows, int64_t npad_cols) {     // over every launch shape of every mode
-  int wmax = 0;
-  for (int ks = 9; ks <= (EGP_D_WIDE_MAX + 4) / 4; ks += 8)
-    for (int nb = 1; nb <= 2; ++nb) {
-      const int s = make_plan_wide(npad_rows, npad_cols, ks, nb, 1).splits;
-      if (s > wmax) wmax = s;
-    }
-  const int a1 = make_plan(npad_rows, npad_cols, 1).splits, a2 = make_plan(npad_rows, npad_cols, 1, 2, 1).splits;
-  const int a0 = a1 > a2 ? a1 : a2;
-  const int a = a0 > wmax ? a0 : wmax;
-  const int b = make_plan_bf(npad_rows, npad_cols, 1, 1, 0).splits;
-  const int c = make_plan_bf(npad_rows, npad_cols, 1, 2, 1).splits;
-  return a > b ? (a > c ? a : c) : (b > c ? b : c);
+// Upper bound of the column-split count over every launch shape of every mode. Each plan takes
+// splits <= min(64, max(1, 1024 / row_blocks), stages_total); a workgroup covers at most 64 * 8 rows and a stage at
+// least 16 column points, so row_blocks >= npad_rows / 512 and stages_total <= npad_cols / 16. The partial-sum
+// buffer is sized from this bound, not from a list of shapes.
+int max_splits(int64_t npad_rows, int64_t npad_cols) {
+  const int64_t rb_min = npad_rows / (64 * 8) > 0 ? npad_rows / (64 * 8) : 1;
+  int64_t w = 1024 / rb_min;
+  if (w < 1) w = 1;
+  if (w > 64) w = 64;
+  const int64_t s = npad_cols / 16;
+  return (int)(w < s ? w : s);
+}
+
+// A launch whose plan asks for more splits than the partial-sum buffer holds is refused on the host.
+int check_splits(const Plan& pl, int splits_max) {
+  if (pl.splits > splits_max)
+    return fail(EGP_ERR_WS, "internal: launch plan wants %d column splits, workspace holds %d", pl.splits, splits_max);
+  return EGP_OK;
 }
 
 int launch_ks(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, int extra, f4* Vp, const float* Ep,
               float* Part, int cm, hipStream_t stream, void* Vb) {
   if (P.ks > 8) return launch_wide(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
-  if (nb == 0) {      // a single column has no MFMA contraction to move to bf16: the fp32 kernel serves every mode
+  if (nb == 0 && kmm_mode() != EGP_KMM_SPLIT_BF16_ALL) {
+    // a single column has no MFMA contraction to move to bf16: the fp32 kernel serves the contraction-only split mode
     ProfScope prof(kProfKmm, stream);
     return launch_all_ks<0>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
   }
@@ -347,6 +354,41 @@ int launch_ks(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, int 
 }
 
 }  // namespace
+
+// The next group of right-hand-side columns: nb blocks of 16 through the MFMA contraction, extra = 1 for a 17th /
+// 33rd (or, up to d = 31, a lone) column on the VALU.
+static void next_group(int rem, int ks, int* nb, int* extra, int* tg) {
+  if (rem == 1 && ks <= 8) { *nb = 0; *extra = 1; *tg = 1; }      // a single column: VALU contraction, no MFMA block
+  else if (rem <= 16) { *nb = 1; *extra = 0; *tg = rem; }
+  else if (rem == 17) { *nb = 1; *extra = 1; *tg = 17; }
+  else if (rem <= 32) { *nb = 2; *extra = 0; *tg = rem; }
+  else if (rem == 33) { *nb = 2; *extra = 1; *tg = 33; }
+  else { *nb = 2; *extra = 0; *tg = 32; }
+}
+
+// Host-only check of the launch planning (no GPU work): the largest column-split count that a product of these
+// sizes launches with in the current mode, row-major and (t <= 33, square) column-major entry alike, and the count
+// its workspace holds.
+void kmm_plan_splits(int64_t n_rows, int64_t n_cols, int d, int t, int* used, int* sized) {
+  const int64_t prow = padded_points(n_rows), pcol = padded_points(n_cols);
+  const int ks = ksteps_for(d);
+  int worst = 0;
+  for (int c0 = 0; c0 < t;) {
+    int nb, extra, tg;
+    next_group(t - c0, ks, &nb, &extra, &tg);
+    const int s = plan_for_mode(prow, pcol, ks, d, nb, extra).splits;
+    if (s > worst) worst = s;
+    c0 += tg;
+  }
+  if (t <= 33 && prow == pcol) {
+    const bool single = t == 1 && ks <= 8;
+    const int nb = single ? 0 : (t > 17 ? 2 : 1), extra = (single || t == 17 || t == 33) ? 1 : 0;
+    const int s = plan_for_mode(prow, pcol, ks, d, nb, extra).splits;
+    if (s > worst) worst = s;
+  }
+  *used = worst;
+  *sized = max_splits(prow, pcol);
+}
 
 static int widest_ts(int t) { return t <= 16 ? 16 : (t == 17 ? 17 : (t <= 32 ? 32 : 33)); }
 
@@ -391,14 +433,10 @@ int kmm_cross(const Prepared& P, const Prepared& Q, const float* V, int t, float
   while (c0 < t) {
     const int rem = t - c0;
     int nb, extra, tg;
-    if (rem == 1 && P.ks <= 8) { nb = 0; extra = 1; tg = 1; }      // a single column: VALU contraction, no MFMA block
-    else if (rem <= 16) { nb = 1; extra = 0; tg = rem; }
-    else if (rem == 17) { nb = 1; extra = 1; tg = 17; }
-    else if (rem <= 32) { nb = 2; extra = 0; tg = rem; }
-    else if (rem == 33) { nb = 2; extra = 1; tg = 33; }
-    else { nb = 2; extra = 0; tg = 32; }
+    next_group(rem, P.ks, &nb, &extra, &tg);
     const int ts = 16 * nb + extra;
     const Plan pl = plan_for_mode(Q.npad, npad, P.ks, P.d, nb, extra);
+    if (int rc = check_splits(pl, splits_max)) return rc;
     if (v_ld > 0) {
       // columns stored one after the other (e.g. Lanczos vectors): 16 columns per block, the odd one as Ep
       ProfScope prof(kProfPack, stream);
@@ -445,6 +483,7 @@ int kmm_core_cm(const Prepared& P, const float* V, int t, float* out, void* ws2,
   const int nb = single ? 0 : (t > 17 ? 2 : 1);
   const int extra = (single || t == 17 || t == 33) ? 1 : 0;
   const Plan pl = plan_for_mode(npad, npad, P.ks, P.d, nb, extra);
+  if (int rc = check_splits(pl, splits_max)) return rc;
   const int ts = 16 * nb + extra;
   f4* Vp = reinterpret_cast<f4*>(w);
   w += round_up((size_t)npad * (nb > 0 ? nb : 1) * 16 * sizeof(float), 256);

@@ -103,6 +103,8 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_bf(const u4* __restrict__ X
                                                         float* __restrict__ Part, int64_t npad,
                                                         int stages_per_split, int stages_total, int cm) {
   constexpr int TS = 16 * NB + EXTRA;
+  constexpr int NBA = NB > 0 ? NB : 1;       // array extents of the single-column shape (NB = 0, EXTRA = 1)
+  static_assert(NB > 0 || EXTRA, "a launch carries at least one column");
   constexpr int XU4 = JT * KS16 * 3 * 64;    // u4 elements of column operands per stage
   constexpr int AU4 = JT * NB * 64;          // u4 elements of [v_hi|v_hi] (and of [v_lo|0]) per stage
   constexpr int EF4 = JT * 4;
@@ -110,8 +112,8 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_bf(const u4* __restrict__ X
   static_assert(XU4 % 256 == 0, "stage size");
 
   __shared__ u4 Xs[2][XU4];
-  __shared__ u4 As[2][AU4];
-  __shared__ u2 Bs[2][AU4];
+  __shared__ u4 As[2][AU4 > 0 ? AU4 : 1];
+  __shared__ u2 Bs[2][AU4 > 0 ? AU4 : 1];
   __shared__ f4 Es[2][EXTRA ? EF4 : 1];
 
   const int tid = threadIdx.x;
@@ -121,7 +123,7 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_bf(const u4* __restrict__ X
 
   b8 br[R][KS16][2];
   f4 cq[R];
-  f4 o[R][NB];
+  f4 o[R][NBA];
   float eacc[R];
 #pragma unroll
   for (int it = 0; it < R; ++it) {
@@ -188,7 +190,7 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_bf(const u4* __restrict__ X
       for (int g = 0; g < KS16; ++g)
 #pragma unroll
         for (int op = 0; op < 3; ++op) ac[g][op] = __builtin_bit_cast(b8, Xs[buf][((jt * KS16 + g) * 3 + op) * 64 + lane]);
-      b8 va[NB], vl[NB];
+      b8 va[NBA], vl[NBA];
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
         va[nb] = __builtin_bit_cast(b8, As[buf][(jt * NB + nb) * 64 + lane]);
@@ -272,7 +274,7 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_bf(const u4* __restrict__ X
 // where 8 tiles' operands and accumulators no longer fit 256 registers without spilling
 constexpr int kBfSmallR = 2;
 constexpr int bf_big_r(int ks16, int nb, int extra) { return (ks16 >= 2 && (nb == 2 || extra)) ? 4 : 8; }
-constexpr int bf_big_jt(int ks16, int nb = 1) { return 8 / ks16 / nb; }   // keeps a stage near 36 KB
+constexpr int bf_big_jt(int ks16, int nb = 1) { return 8 / ks16 / (nb > 0 ? nb : 1); }   // keeps a stage near 36 KB
 constexpr int bf_small_jt(int ks16) { return 4 / ks16; }
 
 template <int KS16, int KIND, int NB, int EXTRA>
@@ -294,6 +296,7 @@ int launch_bf_shape(const Prepared& P, const Prepared& Q, const kmm_detail::Plan
 template <int KS16, int KIND>
 int launch_bf_cols(const Prepared& P, const Prepared& Q, const kmm_detail::Plan& pl, int nb, int extra, const u4* VbA,
                    const u2* VbB, const float* Ep, float* Part, int cm, hipStream_t stream) {
+  if (nb == 0) return launch_bf_shape<KS16, KIND, 0, 1>(P, Q, pl, VbA, VbB, Ep, Part, cm, stream);      // one column, on the VALU
   if (nb == 1 && !extra) return launch_bf_shape<KS16, KIND, 1, 0>(P, Q, pl, VbA, VbB, Ep, Part, cm, stream);
   if (nb == 1 && extra) return launch_bf_shape<KS16, KIND, 1, 1>(P, Q, pl, VbA, VbB, Ep, Part, cm, stream);
   if (nb == 2 && !extra) return launch_bf_shape<KS16, KIND, 2, 0>(P, Q, pl, VbA, VbB, Ep, Part, cm, stream);
@@ -343,7 +346,7 @@ int launch_all_bf(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, 
   const int64_t count = (P.npad >> 4) * nb * 64;
   u4* VbA = static_cast<u4*>(Vb);
   u2* VbB = reinterpret_cast<u2*>(VbA + count);
-  {
+  if (count > 0) {
     ProfScope prof(kProfPack, stream);
     hipLaunchKernelGGL(split_v_bf, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, stream, Vp, count, VbA, VbB);
   }

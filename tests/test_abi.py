@@ -168,3 +168,37 @@ def test_workspace_queries_cover_every_shape(lib, n, d):
     assert (lib.egp_kmm_grad_ws_bytes(n, d, 16) > 0) == (d <= 31)
     # nothing is quadratic in n: a 2^21-point problem at rank 1024 stays far below the 288 GB of one MI355X
     assert lib.egp_mll_ws_bytes(1 << 21, d, 16, 1024, 100) < 40 * (1 << 30)
+
+
+def _plan_splits(lib, rows, cols, d, t):
+    used, sized = C.c_int32(-1), C.c_int32(-1)
+    assert lib.egp_kmm_plan_splits(rows, cols, d, t, C.byref(used), C.byref(sized)) == 0
+    return used.value, sized.value
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_partial_sum_buffer_holds_every_launch_plan(lib, mode):
+    """No launch shape of any mode cuts the column points into more splits than the workspace holds partial
+    sums for (host-side planning only). Sizes cover every padding class up to 2^15 rows and a few large ones,
+    square and cross; d covers every k-step count and both sides of each launch-shape boundary."""
+    ds = sorted(set(list(range(1, 36)) + list(range(36, 400, 4)) + [131, 132, 135, 136, 159, 160, 161, 399]))
+    points = [1, 512, 513, 1025, 1537, 2047, 2500, 4096, 5000, 8192, 12345, 16384, 32767, 32768, 40000, 65536,
+              100000, 1 << 18, 1 << 20, 1 << 21]
+    assert lib.egp_set_kmm_mode(mode) == 0
+    try:
+        for rows in points:
+            for cols in (rows, 1, 513, 2047, 40000, 1 << 20):
+                for d in ds:
+                    for t in (1, 2, 16, 17, 18, 32, 33, 34, 49, 50, 100):
+                        used, sized = _plan_splits(lib, rows, cols, d, t)
+                        assert 1 <= used <= sized <= 64, (rows, cols, d, t, mode, used, sized)
+    finally:
+        assert lib.egp_set_kmm_mode(0) == 0
+
+
+def test_plan_check_pins_a_shape_with_two_row_tiles_and_short_stages(lib):
+    """2047 points at d = 159 (40 k-steps: two row tiles per wave, two column tiles per stage) take 64 splits; the
+    workspace must hold them. This launch-shape class lies between the shapes a sampled bound would look at."""
+    used, sized = _plan_splits(lib, 2047, 2047, 159, 18)
+    assert used == 64 and sized >= 64
+    assert lib.egp_kmm_plan_splits(0, 5, 3, 1, None, None) != 0

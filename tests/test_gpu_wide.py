@@ -41,7 +41,8 @@ def _inputs(seed, n, d, t):
 
 @pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52])
 @pytest.mark.parametrize("n,d,t", [(300, 32, 16), (1000, 77, 17), (2049, 90, 16), (700, 160, 33), (1200, 385, 16),
-                                   (513, 399, 5), (40, 35, 1), (3000, 164, 32)])
+                                   (513, 399, 5), (40, 35, 1), (3000, 164, 32),
+                                   (2047, 159, 18), (1500, 135, 33), (1025, 140, 16)])
 def test_kmm_wide_shapes(egp, kind, n, d, t):
     X, V, ls = _inputs(7000 * kind + 10 * d + t, n, d, t)
     s, noise = 1.3, 0.2
