@@ -4,8 +4,9 @@ Thin ctypes binding over libegp.so (argument marshalling only; every step runs i
 """
 from .binding import (EGP_RBF, EGP_MATERN32, EGP_MATERN52, EgpError, Precond, kmm, kmm_grad, kmm_grad_bilinear, piv_chol_precond,
                       precond_apply, mbcg, mll, tridiag_logquad, kmm_cross, lanczos, predict,
-                      LanczosCache, BlockCache, block_lanczos, train_adam, lib, lib_path)
+                      LanczosCache, BlockCache, block_lanczos, train_adam, lib, lib_path, set_workspace_guard)
 
 __all__ = ["EGP_RBF", "EGP_MATERN32", "EGP_MATERN52", "EgpError", "Precond", "kmm", "kmm_grad", "kmm_grad_bilinear", "piv_chol_precond",
            "precond_apply", "mbcg", "mll", "tridiag_logquad", "kmm_cross", "lanczos",
-           "predict", "LanczosCache", "BlockCache", "block_lanczos", "train_adam", "lib", "lib_path"]
+           "predict", "LanczosCache", "BlockCache", "block_lanczos", "train_adam", "lib", "lib_path",
+           "set_workspace_guard"]

@@ -131,7 +131,34 @@ def lib():
     return _lib
 
 
+# Debug aid for tests: with a guard of G bytes set, every workspace this module allocates is followed by G bytes
+# of a fill pattern, verified after the library call that used it. A kernel writing past its workspace then
+# raises here instead of corrupting a neighbouring tensor.
+_GUARD_FILL = 0x5A
+_guard_bytes = int(os.environ.get("EGP_WS_GUARD_BYTES", "0"))
+_guards = []
+
+
+def set_workspace_guard(nbytes):
+    """Set the number of guard bytes behind each workspace allocated by this module (0 switches the check off)."""
+    global _guard_bytes
+    _guard_bytes = max(int(nbytes), 0)
+    _guards.clear()
+
+
+def _verify_guards():
+    import torch
+    pending, _guards[:] = list(_guards), []
+    for buf, used in pending:
+        torch.cuda.synchronize(buf.device)
+        if not bool((buf[used:] == _GUARD_FILL).all()):
+            bad = int((buf[used:] != _GUARD_FILL).nonzero()[0])
+            raise EgpError(-2, f"workspace overrun: byte {bad} behind a workspace of {used} bytes was overwritten")
+
+
 def _check(rc):
+    if _guards:
+        _verify_guards()
     if rc != 0:
         raise EgpError(rc, lib().egp_last_error().decode())
 
@@ -159,7 +186,14 @@ def _stream():
 
 def _workspace(nbytes, device):
     import torch
-    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+    nbytes = max(int(nbytes), 256)
+    if _guard_bytes == 0:
+        return torch.empty(nbytes, dtype=torch.uint8, device=device)
+    used = (nbytes + 255) // 256 * 256
+    buf = torch.empty(used + _guard_bytes, dtype=torch.uint8, device=device)
+    buf[used:].fill_(_GUARD_FILL)
+    _guards.append((buf, used))
+    return buf[:nbytes]
 
 
 class Precond:
