@@ -235,8 +235,15 @@ size_t egp_precond_apply_ws_bytes(int64_t n, int32_t t, int32_t rank);
  *   EGP_KMM_SPLIT_BF16_ALL  additionally the distance step: scaled points are carried as three bf16 parts
  *                       (24 significant bits, exact) and the six products above the fp32 rounding level are
  *                       accumulated in fp32 on the bf16 MFMA. Faster again; also reported separately.
+ *   EGP_KMM_FP32_SYM    fp32 arithmetic as in EGP_KMM_FP32, and the symmetry of the kernel matrix exploited: in a
+ *                       square product every tile off the block diagonal is formed once and used for both the
+ *                       row-side and the column-side output (paper, Background: K is a covariance matrix). The
+ *                       column-side sums leave the kernel as float atomic adds, so results agree with
+ *                       EGP_KMM_FP32 up to summation order and their last bits are not reproducible from run to
+ *                       run. Applies to d <= 14, n >= 32257 and groups of 16 columns; other shapes run the
+ *                       EGP_KMM_FP32 kernels.
  * Affects egp_kmm, egp_kmm_cross, egp_mbcg, egp_lanczos, egp_mll. Returns EGP_ERR_ARG for an unknown mode. */
-typedef enum { EGP_KMM_FP32 = 0, EGP_KMM_SPLIT_BF16 = 1, EGP_KMM_SPLIT_BF16_ALL = 2 } egp_kmm_mode_t;
+typedef enum { EGP_KMM_FP32 = 0, EGP_KMM_SPLIT_BF16 = 1, EGP_KMM_SPLIT_BF16_ALL = 2, EGP_KMM_FP32_SYM = 3 } egp_kmm_mode_t;
 int egp_set_kmm_mode(int32_t mode);
 int egp_get_kmm_mode(void);
 

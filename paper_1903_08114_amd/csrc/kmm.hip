@@ -305,8 +305,12 @@ int prepare_points(const float* X, int64_t n, const egp_hyper_t* h, void* ws, Pr
 
 namespace {
 
-Plan plan_for_mode(int64_t npad_rows, int64_t npad_cols, int ks, int d, int nb, int extra) {
+Plan plan_for_mode(int64_t npad_rows, int64_t npad_cols, int ks, int d, int nb, int extra, bool square = false) {
   if (ks > 8) return make_plan_wide(npad_rows, npad_cols, ks, nb, extra);     // d > 31: fp32 wide kernel in every mode
+  if (kmm_mode() == EGP_KMM_FP32_SYM) {     // fp32 arithmetic; shapes the symmetric kernel does not cover run the plain one
+    if (square && sym_applies(npad_rows, npad_cols, ks, nb, extra)) return make_plan_sym(npad_rows);
+    return make_plan(npad_rows, npad_cols, ks, nb, extra);
+  }
   if (nb == 0 && kmm_mode() != EGP_KMM_SPLIT_BF16_ALL)
     return make_plan(npad_rows, npad_cols, ks, nb, extra);     // a single column has no contraction to split
   return kmm_mode() == EGP_KMM_SPLIT_BF16_ALL ? make_plan_bf(npad_rows, npad_cols, d, nb, extra)
@@ -335,6 +339,7 @@ int check_splits(const Plan& pl, int splits_max) {
 int launch_ks(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, int extra, f4* Vp, const float* Ep,
               float* Part, int cm, hipStream_t stream, void* Vb) {
   if (P.ks > 8) return launch_wide(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
+  if (pl.sym) return launch_sym(P, pl, Vp, Ep, Part, cm, stream);
   if (nb == 0 && kmm_mode() != EGP_KMM_SPLIT_BF16_ALL) {
     // a single column has no MFMA contraction to move to bf16: the fp32 kernel serves the contraction-only split mode
     ProfScope prof(kProfKmm, stream);
@@ -376,14 +381,14 @@ void kmm_plan_splits(int64_t n_rows, int64_t n_cols, int d, int t, int* used, in
   for (int c0 = 0; c0 < t;) {
     int nb, extra, tg;
     next_group(t - c0, ks, &nb, &extra, &tg);
-    const int s = plan_for_mode(prow, pcol, ks, d, nb, extra).splits;
+    const int s = plan_for_mode(prow, pcol, ks, d, nb, extra, prow == pcol).splits;
     if (s > worst) worst = s;
     c0 += tg;
   }
   if (t <= 33 && prow == pcol) {
     const bool single = t == 1 && ks <= 8;
     const int nb = single ? 0 : (t > 17 ? 2 : 1), extra = (single || t == 17 || t == 33) ? 1 : 0;
-    const int s = plan_for_mode(prow, pcol, ks, d, nb, extra).splits;
+    const int s = plan_for_mode(prow, pcol, ks, d, nb, extra, true).splits;
     if (s > worst) worst = s;
   }
   *used = worst;
@@ -400,7 +405,7 @@ size_t kmm_cross_ws_bytes(int64_t n_rows, int64_t n_cols, int t) {
   size_t b = 0;
   b += round_up((size_t)pcol * nb * 16 * sizeof(float), 256);                    // Vp
   b += round_up((size_t)pcol * sizeof(float), 256);                              // Ep
-  b += round_up((size_t)splits * prow * widest_ts(t) * sizeof(float), 256);      // Part
+  b += round_up((size_t)(splits + 1) * prow * widest_ts(t) * sizeof(float), 256);      // Part (+1: column-side slab of the symmetric kernel)
   b += round_up((size_t)pcol * nb * 32 * sizeof(float), 256);                    // split V of the all-bf16 mode
   return b;
 }
@@ -426,7 +431,7 @@ int kmm_cross(const Prepared& P, const Prepared& Q, const float* V, int t, float
   float* Ep = reinterpret_cast<float*>(w);
   w += round_up((size_t)npad * sizeof(float), 256);
   float* Part = reinterpret_cast<float*>(w);
-  w += round_up((size_t)splits_max * Q.npad * widest_ts(t) * sizeof(float), 256);
+  w += round_up((size_t)(splits_max + 1) * Q.npad * widest_ts(t) * sizeof(float), 256);
   void* Vb = w;
 
   int c0 = 0;
@@ -435,7 +440,7 @@ int kmm_cross(const Prepared& P, const Prepared& Q, const float* V, int t, float
     int nb, extra, tg;
     next_group(rem, P.ks, &nb, &extra, &tg);
     const int ts = 16 * nb + extra;
-    const Plan pl = plan_for_mode(Q.npad, npad, P.ks, P.d, nb, extra);
+    const Plan pl = plan_for_mode(Q.npad, npad, P.ks, P.d, nb, extra, square);
     if (int rc = check_splits(pl, splits_max)) return rc;
     if (v_ld > 0) {
       // columns stored one after the other (e.g. Lanczos vectors): 16 columns per block, the odd one as Ep
@@ -458,7 +463,7 @@ int kmm_cross(const Prepared& P, const Prepared& Q, const float* V, int t, float
     const int64_t outs = Q.n * tg;
     ProfScope eprof(kProfPack, stream);
     hipLaunchKernelGGL(kmm_epilogue, dim3((unsigned)((outs + 255) / 256)), dim3(256), 0, stream, Part,
-                       pl.splits, Q.npad, ts, square ? V : nullptr, Q.n, t, c0, tg, P.outputscale,
+                       pl.splits + pl.extra_slabs, Q.npad, ts, square ? V : nullptr, Q.n, t, c0, tg, P.outputscale,
                        square ? P.noise : 0.f, out);
     EGP_HIP(hipGetLastError());
     c0 += tg;
@@ -482,14 +487,14 @@ int kmm_core_cm(const Prepared& P, const float* V, int t, float* out, void* ws2,
   const bool single = t == 1 && P.ks <= 8;      // one column: consumed straight from the state array on the VALU
   const int nb = single ? 0 : (t > 17 ? 2 : 1);
   const int extra = (single || t == 17 || t == 33) ? 1 : 0;
-  const Plan pl = plan_for_mode(npad, npad, P.ks, P.d, nb, extra);
+  const Plan pl = plan_for_mode(npad, npad, P.ks, P.d, nb, extra, true);
   if (int rc = check_splits(pl, splits_max)) return rc;
   const int ts = 16 * nb + extra;
   f4* Vp = reinterpret_cast<f4*>(w);
   w += round_up((size_t)npad * (nb > 0 ? nb : 1) * 16 * sizeof(float), 256);
   w += round_up((size_t)npad * sizeof(float), 256);      // the row-major path's extra-column buffer (unused here)
   float* Part = reinterpret_cast<float*>(w);
-  w += round_up((size_t)splits_max * npad * widest_ts(t) * sizeof(float), 256);
+  w += round_up((size_t)(splits_max + 1) * npad * widest_ts(t) * sizeof(float), 256);
   void* Vb = w;
   if (nb > 0) {
     ProfScope prof(kProfPack, stream);
@@ -502,7 +507,7 @@ int kmm_core_cm(const Prepared& P, const float* V, int t, float* out, void* ws2,
   const int rc = launch_ks(P, P, pl, nb, extra, Vp, Ep, Part, 1, stream, Vb);
   if (rc != EGP_OK) return rc;
   ProfScope eprof(kProfPack, stream);
-  hipLaunchKernelGGL(kmm_epilogue_cm, dim3(kmm_cm_dot_blocks(npad), t), dim3(256), 0, stream, Part, pl.splits, npad,
+  hipLaunchKernelGGL(kmm_epilogue_cm, dim3(kmm_cm_dot_blocks(npad), t), dim3(256), 0, stream, Part, pl.splits + pl.extra_slabs, npad,
                      ts, V, npad, P.n, P.outputscale, P.noise, out, dot_part, dot_ld);
   EGP_HIP(hipGetLastError());
   return EGP_OK;

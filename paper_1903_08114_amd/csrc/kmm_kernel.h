@@ -260,6 +260,8 @@ namespace kmm_detail {
 struct Plan {
   bool big;
   int splits, stages_per_split, stages_total, row_blocks;
+  int extra_slabs = 0;      // slabs of the partial-sum buffer behind the per-split ones (symmetric kernel: 1)
+  bool sym = false;         // launch the symmetric kernel
 };
 
 // Launch shapes (row tiles per wave, column tiles per LDS stage). Up to 8 k-steps (d <= 31) the wide shape
@@ -348,6 +350,10 @@ void launch_split_vp(f4* Vp, int64_t count, hipStream_t stream);
 Plan make_plan_wide(int64_t npad_rows, int64_t npad_cols, int ks, int nb, int extra);
 int launch_wide(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, int extra, const f4* Vp, const float* Ep,
                 float* Part, int cm, hipStream_t stream);
+// defined in kmm_sym.hip: square products that use every off-diagonal tile twice
+bool sym_applies(int64_t npad_rows, int64_t npad_cols, int ks, int nb, int extra);
+Plan make_plan_sym(int64_t npad);
+int launch_sym(const Prepared& P, const Plan& pl, const f4* Vp, const float* Ep, float* Part, int cm, hipStream_t stream);
 // defined in kmm_bf.hip: every contraction on the bf16 MFMA
 Plan make_plan_bf(int64_t npad_rows, int64_t npad_cols, int d, int nb, int extra);
 void launch_pack_points_bf(const Prepared& P, hipStream_t stream);

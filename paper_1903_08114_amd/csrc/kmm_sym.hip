@@ -1,0 +1,322 @@
+// Symmetric variant of the fused kernel-matrix multiply (square products, d <= 14, groups of 16 right-hand sides).
+//
+// The kernel matrix is symmetric (paper, Background: k(x, x') is a covariance), so the tile K[I,J] that serves
+// out[I] += K[I,J] V[J] also serves out[J] += K[I,J]^T V[I]. A workgroup owns 64 R rows (row block b) and sweeps
+// the column blocks b, b+1, ..., b + floor(nblk/2) (cyclically). On the blocks strictly between the diagonal one
+// and the half-way one every tile is used twice, so the distance steps and the transform of half of all tiles are
+// never computed:
+//   row side     as in kmm_kernel: the tile feeds the contraction with V[J] straight from the accumulator layout;
+//   column side  needs the tile transposed relative to that layout. Each wave passes the tile through a private
+//                LDS patch (one 16-byte write, four 4-byte reads per lane, both free of bank conflicts), and
+//                contracts it with the packed V of its own row tiles (resident in registers). The column-side sums
+//                of a wave's R row tiles go to LDS; at the end of a stage the four waves' sums are added up and
+//                leave the workgroup as float atomic adds into one extra slab of the partial-sum buffer.
+//                (LDS float atomics were measured far too slow for the first step: plain stores, one patch per wave.)
+// The diagonal block and (for an even block count) the half-way block are computed one-sided, as in kmm_kernel.
+// Results differ from kmm_kernel's only in summation order; the order of the atomic adds is not fixed, so the last
+// bits are not reproducible from run to run.
+#include "kmm_kernel.h"
+
+namespace egp {
+namespace kmm_detail {
+
+namespace {
+
+constexpr int kSymR = 8, kSymJT = 8;
+constexpr int kPatch = 304;      // floats of one transposition patch: 76 slots of 16 bytes
+
+template <int KS, int KIND, int EXTRA>
+__global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict__ Xp, const float* __restrict__ nrm,
+                                                         const f4* __restrict__ Vp, const float* __restrict__ Ep,
+                                                         float* __restrict__ Part, int64_t npad, int d, int nblk,
+                                                         int stages_per_split, int cm) {
+  constexpr int R = kSymR, JT = kSymJT;
+  constexpr int TS = 16 + EXTRA;
+  constexpr int SB = 64 * R / (16 * JT);      // stages per block of 64 R points
+  constexpr int XF4 = JT * KS * 16, VF4 = JT * 64, EF4 = JT * 4;
+  constexpr int NX = (XF4 + 255) / 256, NV = (VF4 + 255) / 256;
+  static_assert(EXTRA == 0, "the 17th column is not built yet");
+
+  __shared__ f4 Xs[2][XF4];
+  __shared__ f4 Vs[2][VF4];
+  __shared__ __attribute__((aligned(16))) float Ts[4][2][kPatch];      // per wave: two transposition patches
+  __shared__ f4 CJ[4][JT][64];      // column-side sums of one stage, per wave: [wave][tile][lane], register r = component
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int q = lane >> 4, p = lane & 15;
+  const int bi = blockIdx.x;
+  const int half = nblk >> 1;
+  const int stages_all = (half + 1) * SB;      // this workgroup's whole sweep, in stages
+  const int s_total = nblk * SB;
+
+  const int64_t row_tile0 = ((int64_t)bi * 4 + wave) * R;
+  float b[R][KS];
+  f4 cq[R], o[R], o2[R], vrow[R];
+  constexpr int kFlushStages = 4096 / (16 * JT);
+  const int ds = d >> 2, dq = d & 3;
+#pragma unroll
+  for (int it = 0; it < R; ++it) {
+    const float* src = Xp + (row_tile0 + it) * KS * 64 + lane;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      float v = -2.0f * src[s * 64];
+      if (s == ds && q == dq) v = 1.0f;
+      b[it][s] = v;
+    }
+    const float ni = nrm[(row_tile0 + it) * 16 + p];
+    cq[it] = (f4){ni, ni, ni, ni};
+    o[it] = (f4){0.f, 0.f, 0.f, 0.f};
+    o2[it] = (f4){0.f, 0.f, 0.f, 0.f};
+    vrow[it] = Vp[(row_tile0 + it) * 64 + lane];
+  }
+  auto fold = [&]() {
+#pragma unroll
+    for (int it = 0; it < R; ++it) {
+      o2[it] += o[it];
+      o[it] = (f4){0.f, 0.f, 0.f, 0.f};
+    }
+  };
+  // transposition patch: lane (q,p) holds M[4q + r][p] in register r and wants M[p][4q + r]
+  float* patch = &Ts[wave][0][0];
+  const int woff = 4 * (20 * q + 4 * (p & 3) + (p >> 2));      // 16-byte slot of this lane's four values
+  const int roff = 80 * (p >> 2) + 4 * q + (p & 3);            // + 16 r: the value for step r
+
+  const int k_begin = blockIdx.y * stages_per_split;
+  int k_end = k_begin + stages_per_split;
+  if (k_end > stages_all) k_end = stages_all;
+
+  const f4* Xg = reinterpret_cast<const f4*>(Xp);
+  auto abs_stage = [&](int k) {
+    int st = bi * SB + k;
+    return st >= s_total ? st - s_total : st;
+  };
+  auto is_dual = [&](int k) {
+    const int delta = k / SB;
+    return delta != 0 && !(delta == half && (nblk & 1) == 0);
+  };
+  auto issue = [&](int st, int buf) {
+    const int64_t xoff = (int64_t)st * XF4, voff = (int64_t)st * VF4;
+#pragma unroll
+    for (int k = 0; k < NX; ++k)
+      if (XF4 % 256 == 0 || k * 256 + wave * 64 < XF4)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Xg + xoff + tid + k * 256),
+                                         (__attribute__((address_space(3))) void*)(&Xs[buf][k * 256 + wave * 64]), 16, 0, 0);
+#pragma unroll
+    for (int k = 0; k < NV; ++k)
+      if (VF4 % 256 == 0 || k * 256 + wave * 64 < VF4)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Vp + voff + tid + k * 256),
+                                         (__attribute__((address_space(3))) void*)(&Vs[buf][k * 256 + wave * 64]), 16, 0, 0);
+  };
+  // the column-side sums of stage st (absolute), one partial per wave in CJ, leave as atomic adds into the extra slab
+  float* slab = Part + (int64_t)gridDim.y * npad * TS;
+  auto flush = [&](int st) {
+#pragma unroll
+    for (int h = 0; h < JT / 4; ++h) {
+      const int jt = wave + 4 * h;      // thread (wave, lane) adds up the four waves' sums of tiles wave, wave + 4, ...
+      f4 v = CJ[0][jt][lane];
+      v += CJ[1][jt][lane];
+      v += CJ[2][jt][lane];
+      v += CJ[3][jt][lane];
+      const int64_t j = ((int64_t)st * JT + jt) * 16 + 4 * q;
+      if (cm) {
+        float* dst = slab + (int64_t)p * npad + j;
+        unsafeAtomicAdd(dst + 0, v.x);
+        unsafeAtomicAdd(dst + 1, v.y);
+        unsafeAtomicAdd(dst + 2, v.z);
+        unsafeAtomicAdd(dst + 3, v.w);
+      } else {
+        float* dst = slab + j * TS + p;
+        unsafeAtomicAdd(dst + 0 * TS, v.x);
+        unsafeAtomicAdd(dst + 1 * TS, v.y);
+        unsafeAtomicAdd(dst + 2 * TS, v.z);
+        unsafeAtomicAdd(dst + 3 * TS, v.w);
+      }
+    }
+  };
+
+  if (k_begin < k_end) issue(abs_stage(k_begin), 0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+
+  for (int k = k_begin; k < k_end; ++k) {
+    const int buf = (k - k_begin) & 1;
+    const int st = abs_stage(k);
+    if (k + 1 < k_end) issue(abs_stage(k + 1), buf ^ 1);
+    const bool dual = is_dual(k);
+    const float* xs = reinterpret_cast<const float*>(Xs[buf]);
+    if (!dual) {
+#pragma unroll 2
+      for (int jt = 0; jt < JT; ++jt) {
+        float a[KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) a[s] = xs[(jt * KS + s) * 64 + lane];
+        const f4 v = Vs[buf][jt * 64 + lane];
+#pragma unroll
+        for (int it = 0; it < R; ++it) {
+          f4 acc = cq[it];
+#pragma unroll
+          for (int s = 0; s < KS; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s], b[it][s], acc, 0, 0, 0);
+          f4 kk;
+          kk.x = transform<KIND>(acc.x);
+          kk.y = transform<KIND>(acc.y);
+          kk.z = transform<KIND>(acc.z);
+          kk.w = transform<KIND>(acc.w);
+          o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.x, v.x, o[it], 0, 0, 0);
+          o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.y, v.y, o[it], 0, 0, 0);
+          o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.z, v.z, o[it], 0, 0, 0);
+          o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.w, v.w, o[it], 0, 0, 0);
+        }
+      }
+    } else {
+      // Operands of the next column tile are fetched while the current one is worked on; the order of the LDS
+      // traffic and the MFMA groups inside a row-tile step is pinned (sched_barrier), because the compiler would
+      // otherwise sink the reads of the transposed tile next to their use and expose their latency.
+      float a[KS];
+#pragma unroll
+      for (int s = 0; s < KS; ++s) a[s] = xs[s * 64 + lane];
+      f4 v = Vs[buf][lane];
+      for (int jt = 0; jt < JT; ++jt) {
+        const int jn = jt + 1 < JT ? jt + 1 : JT - 1;
+        float an[KS];
+        f4 vn = v;
+        f4 oj = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int it = 0; it <= R; ++it) {
+          f4 kt = {0.f, 0.f, 0.f, 0.f};
+          if (it > 0) {      // transposed tile of the previous step: in flight during this step's distance MFMAs
+            const float* rp = patch + ((it - 1) & 1) * kPatch + roff;
+            kt.x = rp[0];
+            kt.y = rp[16];
+            kt.z = rp[32];
+            kt.w = rp[48];
+          }
+          if (it == R / 2) {
+#pragma unroll
+            for (int s = 0; s < KS; ++s) an[s] = xs[(jn * KS + s) * 64 + lane];
+            vn = Vs[buf][jn * 64 + lane];
+          }
+          __builtin_amdgcn_sched_barrier(0);
+          f4 acc = {0.f, 0.f, 0.f, 0.f};
+          if (it < R) {
+            acc = cq[it];
+#pragma unroll
+            for (int s = 0; s < KS; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s], b[it][s], acc, 0, 0, 0);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+          if (it > 0) {      // column side of the previous step; also covers the latency of the distance result
+            oj = __builtin_amdgcn_mfma_f32_16x16x4f32(kt.x, vrow[it - 1].x, oj, 0, 0, 0);
+            oj = __builtin_amdgcn_mfma_f32_16x16x4f32(kt.y, vrow[it - 1].y, oj, 0, 0, 0);
+            oj = __builtin_amdgcn_mfma_f32_16x16x4f32(kt.z, vrow[it - 1].z, oj, 0, 0, 0);
+            oj = __builtin_amdgcn_mfma_f32_16x16x4f32(kt.w, vrow[it - 1].w, oj, 0, 0, 0);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+          if (it < R) {
+            f4 kk;
+            kk.x = transform<KIND>(acc.x);
+            kk.y = transform<KIND>(acc.y);
+            kk.z = transform<KIND>(acc.z);
+            kk.w = transform<KIND>(acc.w);
+            o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.x, v.x, o[it], 0, 0, 0);
+            o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.y, v.y, o[it], 0, 0, 0);
+            o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.z, v.z, o[it], 0, 0, 0);
+            o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.w, v.w, o[it], 0, 0, 0);
+            *reinterpret_cast<f4*>(patch + (it & 1) * kPatch + woff) = kk;
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        CJ[wave][jt][lane] = oj;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) a[s] = an[s];
+        v = vn;
+      }
+    }
+    if ((k - k_begin) % kFlushStages == kFlushStages - 1) fold();
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (dual) {      // uniform over the workgroup
+      flush(st);
+      __syncthreads();             // the per-wave sums are free again
+    }
+  }
+  fold();
+
+  // row side: raw accumulators of this split, as in kmm_kernel
+  float* dst = Part + (int64_t)blockIdx.y * npad * TS;
+#pragma unroll
+  for (int it = 0; it < R; ++it) {
+    const int64_t row0 = (row_tile0 + it) * 16;
+    if (cm) {
+      *reinterpret_cast<f4*>(dst + (int64_t)p * npad + row0 + q * 4) = o2[it];
+    } else {
+      float* r0 = dst + (row0 + q * 4) * TS + p;
+      r0[0 * TS] = o2[it].x;
+      r0[1 * TS] = o2[it].y;
+      r0[2 * TS] = o2[it].z;
+      r0[3 * TS] = o2[it].w;
+    }
+  }
+}
+
+template <int KS, int KIND>
+int launch_sym_one(const Prepared& P, const Plan& pl, const f4* Vp, const float* Ep, float* Part, int cm,
+                   hipStream_t stream) {
+  const int nblk = (int)(P.npad / (64 * kSymR));
+  hipLaunchKernelGGL((kmm_kernel_sym<KS, KIND, 0>), dim3(nblk, pl.splits), dim3(256), 0, stream, P.Xp, P.nrm, Vp, Ep,
+                     Part, P.npad, P.d, nblk, pl.stages_per_split, cm);
+  EGP_HIP(hipGetLastError());
+  return EGP_OK;
+}
+
+template <int KS>
+int launch_sym_kind(const Prepared& P, const Plan& pl, const f4* Vp, const float* Ep, float* Part, int cm,
+                    hipStream_t stream) {
+  switch (P.kernel_type) {
+    case EGP_RBF: return launch_sym_one<KS, EGP_RBF>(P, pl, Vp, Ep, Part, cm, stream);
+    case EGP_MATERN32: return launch_sym_one<KS, EGP_MATERN32>(P, pl, Vp, Ep, Part, cm, stream);
+    default: return launch_sym_one<KS, EGP_MATERN52>(P, pl, Vp, Ep, Part, cm, stream);
+  }
+}
+
+}  // namespace
+
+bool sym_applies(int64_t npad_rows, int64_t npad_cols, int ks, int nb, int extra) {
+  // up to 4 distance k-steps (d <= 14) the resident operands of 8 row tiles fit the register file at two waves per SIMD
+  return npad_rows == npad_cols && ks <= 4 && nb == 1 && extra == 0 && npad_rows / (64 * 8) >= 64;
+}
+
+// stages_total holds the length of one workgroup's sweep; row_blocks the block count
+Plan make_plan_sym(int64_t npad) {
+  Plan pl;
+  pl.big = true;
+  pl.sym = true;
+  pl.extra_slabs = 1;
+  const int nblk = (int)(npad / (64 * kSymR));
+  constexpr int SB = 64 * kSymR / (16 * kSymJT);
+  pl.row_blocks = nblk;
+  pl.stages_total = (nblk / 2 + 1) * SB;
+  int want = 1024 / nblk;
+  if (want < 1) want = 1;
+  if (want > pl.stages_total) want = pl.stages_total;
+  if (want > 64) want = 64;
+  pl.stages_per_split = (pl.stages_total + want - 1) / want;
+  pl.splits = (pl.stages_total + pl.stages_per_split - 1) / pl.stages_per_split;
+  return pl;
+}
+
+// Part must hold pl.splits + 1 slabs of npad x 16 floats; the last one receives the column-side sums and is
+// cleared here.
+int launch_sym(const Prepared& P, const Plan& pl, const f4* Vp, const float* Ep, float* Part, int cm, hipStream_t stream) {
+  ProfScope prof(kProfKmm, stream);
+  EGP_HIP(hipMemsetAsync(Part + (int64_t)pl.splits * P.npad * 16, 0, (size_t)P.npad * 16 * sizeof(float), stream));
+  switch (P.ks) {
+    case 1: return launch_sym_kind<1>(P, pl, Vp, Ep, Part, cm, stream);
+    case 2: return launch_sym_kind<2>(P, pl, Vp, Ep, Part, cm, stream);
+    case 3: return launch_sym_kind<3>(P, pl, Vp, Ep, Part, cm, stream);
+    case 4: return launch_sym_kind<4>(P, pl, Vp, Ep, Part, cm, stream);
+    default: return fail(EGP_ERR_ARG, "the symmetric kernel supports d <= 14");
+  }
+}
+
+}  // namespace kmm_detail
+}  // namespace egp

@@ -176,7 +176,7 @@ def _plan_splits(lib, rows, cols, d, t):
     return used.value, sized.value
 
 
-@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("mode", [0, 1, 2, 3])
 def test_partial_sum_buffer_holds_every_launch_plan(lib, mode):
     """No launch shape of any mode cuts the column points into more splits than the workspace holds partial
     sums for (host-side planning only). Sizes cover every padding class up to 2^15 rows and a few large ones,

@@ -154,3 +154,47 @@ def test_kmm_split_bf16_c2_recipe_rows(egp, mode):
     err = _rel(got[ref_rows], ref)
     print("C2-recipe split-mode rel err", err)
     assert err <= KMM_TOL
+
+
+@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52])
+@pytest.mark.parametrize("n,d,t", [(32768, 11, 16), (33000, 3, 16), (40000, 14, 48), (65536, 8, 16), (33281, 11, 17)])
+def test_kmm_symmetric_mode_rows(egp, kind, n, d, t):
+    """The symmetric fp32 mode (every off-diagonal tile used for the row-side and the column-side output) against
+    rows computed exactly by the oracle: even and odd block counts, rows at the block edges and around the half-way
+    block, several column groups; t = 17 takes the one-sided kernel for its 17th column."""
+    rng = np.random.default_rng(11 * n + d + t + kind)
+    X = rng.uniform(-1, 1, (n, d)).astype(np.float32)
+    V = rng.standard_normal((n, t)).astype(np.float32)
+    ls = np.exp(rng.uniform(np.log(0.3), np.log(3.0), d)).astype(np.float32)
+    rows = rng.choice(n, 160, replace=False)
+    edges = [0, 1, 15, 16, 511, 512, 513, n // 2 - 1, n // 2, n // 2 + 511, n // 2 + 512, n - 513, n - 512, n - 2, n - 1]
+    rows[:len(edges)] = edges
+    rows = np.unique(rows)
+    ref = orc.kmm_rows(X, V, orc.Hyper(kind, ls, 1.3, 0.2), rows)
+    base = _run(egp, X, V, ls, 1.3, 0.2, kind)
+    try:
+        _set_mode(egp, 3)
+        got = _run(egp, X, V, ls, 1.3, 0.2, kind)
+    finally:
+        _set_mode(egp, 0)
+    assert np.isfinite(got).all()
+    err = _rel(got[rows], ref)
+    print(f"symmetric mode n={n} d={d} t={t} kind={kind}: rel err {err:.2e}; vs one-sided kernel {_rel(got, base):.2e}")
+    assert err <= KMM_TOL
+    assert _rel(got, base) <= 2e-5      # every row: same arithmetic, different summation order
+
+
+def test_kmm_symmetric_mode_falls_back_on_other_shapes(egp):
+    """Shapes the symmetric kernel does not cover (small n, d > 14) give the one-sided kernel's bits."""
+    for n, d in ((3000, 11), (33000, 18)):
+        rng = np.random.default_rng(n + d)
+        X = rng.uniform(-1, 1, (n, d)).astype(np.float32)
+        V = rng.standard_normal((n, 16)).astype(np.float32)
+        ls = np.full(d, 0.8, np.float32)
+        base = _run(egp, X, V, ls, 1.0, 0.1, orc.RBF)
+        try:
+            _set_mode(egp, 3)
+            got = _run(egp, X, V, ls, 1.0, 0.1, orc.RBF)
+        finally:
+            _set_mode(egp, 0)
+        assert np.array_equal(got, base)

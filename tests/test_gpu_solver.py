@@ -241,3 +241,35 @@ def test_mbcg_slq_logdet_from_gpu_coefficients(egp):
     est = P.logdet + terms.mean()
     exact = orc.logdet(orc.khat(X, h))
     assert abs(est - exact) <= 4 * terms.std(ddof=1) / np.sqrt(tp) + 1e-3 * abs(exact)
+
+
+@pytest.mark.parametrize("t", [16, 17])
+def test_mbcg_in_symmetric_mode(egp, t):
+    """The symmetric fp32 mode inside the solver (column-major state, t = 16 takes the two-sided kernel): same
+    iterates as the one-sided kernel up to summation order, and a true residual (rows computed exactly by the
+    oracle) at the level the recurrence reports."""
+    n, d = 33000, 11
+    rng = np.random.default_rng(77 + t)
+    X = rng.uniform(0, 1, (n, d)).astype(np.float32)
+    B = rademacher(rng, (n, t))
+    B[:, 0] = np.sin(4 * X[:, 0]) + 0.1 * rng.standard_normal(n)
+    ls = np.exp(rng.uniform(np.log(0.3), np.log(1.5), d)).astype(np.float32)
+    s, noise, kind = 1.0, 0.5, orc.RBF
+    Xd, Bd = _cuda(X), _cuda(B)
+    P = egp.piv_chol_precond(Xd, ls, s, noise, kind, 50)
+    base = egp.mbcg(Xd, Bd, ls, s, noise, kind, precond=P, max_iter=200, tol=1e-3)
+    L = egp.lib()
+    try:
+        L.egp_set_kmm_mode(3)
+        res = egp.mbcg(Xd, Bd, ls, s, noise, kind, precond=P, max_iter=200, tol=1e-3)
+    finally:
+        L.egp_set_kmm_mode(0)
+    assert res["rel_resid"].max() <= 1e-3
+    assert abs(res["iters"] - base["iters"]) <= 2
+    U = res["U"].cpu().numpy().astype(np.float64)
+    Ub = base["U"].cpu().numpy().astype(np.float64)
+    assert np.linalg.norm(U - Ub) / np.linalg.norm(Ub) <= 5e-3
+    rows = rng.choice(n, 96, replace=False)
+    KU = orc.kmm_rows(X, U, orc.Hyper(kind, ls, s, noise), rows)
+    true_res = np.linalg.norm(KU - B[rows], axis=0) / np.linalg.norm(B[rows], axis=0)
+    assert true_res.max() <= 5e-3
