@@ -308,7 +308,8 @@ namespace {
 Plan plan_for_mode(int64_t npad_rows, int64_t npad_cols, int ks, int d, int nb, int extra, bool square = false) {
   if (ks > 8) return make_plan_wide(npad_rows, npad_cols, ks, nb, extra);     // d > 31: fp32 wide kernel in every mode
   if (kmm_mode() == EGP_KMM_FP32_SYM) {     // fp32 arithmetic; shapes the symmetric kernel does not cover run the plain one
-    if (square && sym_applies(npad_rows, npad_cols, ks, nb, extra)) return make_plan_sym(npad_rows);
+    const int r = square ? sym_row_tiles(npad_rows, npad_cols, ks, nb, extra) : 0;
+    if (r > 0) return make_plan_sym(npad_rows, r, ks);
     return make_plan(npad_rows, npad_cols, ks, nb, extra);
   }
   if (nb == 0 && kmm_mode() != EGP_KMM_SPLIT_BF16_ALL)
@@ -339,7 +340,7 @@ int check_splits(const Plan& pl, int splits_max) {
 int launch_ks(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, int extra, f4* Vp, const float* Ep,
               float* Part, int cm, hipStream_t stream, void* Vb) {
   if (P.ks > 8) return launch_wide(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
-  if (pl.sym) return launch_sym(P, pl, Vp, Ep, Part, cm, stream);
+  if (pl.sym) return launch_sym(P, pl, extra, Vp, Ep, Part, cm, stream);
   if (nb == 0 && kmm_mode() != EGP_KMM_SPLIT_BF16_ALL) {
     // a single column has no MFMA contraction to move to bf16: the fp32 kernel serves the contraction-only split mode
     ProfScope prof(kProfKmm, stream);

@@ -351,9 +351,10 @@ Plan make_plan_wide(int64_t npad_rows, int64_t npad_cols, int ks, int nb, int ex
 int launch_wide(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, int extra, const f4* Vp, const float* Ep,
                 float* Part, int cm, hipStream_t stream);
 // defined in kmm_sym.hip: square products that use every off-diagonal tile twice
-bool sym_applies(int64_t npad_rows, int64_t npad_cols, int ks, int nb, int extra);
-Plan make_plan_sym(int64_t npad);
-int launch_sym(const Prepared& P, const Plan& pl, const f4* Vp, const float* Ep, float* Part, int cm, hipStream_t stream);
+int sym_row_tiles(int64_t npad_rows, int64_t npad_cols, int ks, int nb, int extra);
+Plan make_plan_sym(int64_t npad, int r, int ks);
+int launch_sym(const Prepared& P, const Plan& pl, int extra, const f4* Vp, const float* Ep, float* Part, int cm,
+               hipStream_t stream);
 // defined in kmm_bf.hip: every contraction on the bf16 MFMA
 Plan make_plan_bf(int64_t npad_rows, int64_t npad_cols, int d, int nb, int extra);
 void launch_pack_points_bf(const Prepared& P, hipStream_t stream);

@@ -1,4 +1,4 @@
-// Symmetric variant of the fused kernel-matrix multiply (square products, d <= 14, groups of 16 right-hand sides).
+// Symmetric variant of the fused kernel-matrix multiply (square products, d <= 31, 16 or 17 right-hand sides).
 //
 // The kernel matrix is symmetric (paper, Background: k(x, x') is a covariance), so the tile K[I,J] that serves
 // out[I] += K[I,J] V[J] also serves out[J] += K[I,J]^T V[I]. A workgroup owns 64 R rows (row block b) and sweeps
@@ -22,25 +22,36 @@ namespace kmm_detail {
 
 namespace {
 
-constexpr int kSymR = 8, kSymJT = 8;
+// column tiles per stage: 8 up to 4 distance k-steps, 4 beyond (keeps the workgroup's LDS under 80 KB: two per CU)
+constexpr int sym_jt(int ks) { return ks <= 4 ? 8 : 4; }
 constexpr int kPatch = 304;      // floats of one transposition patch: 76 slots of 16 bytes
 
-template <int KS, int KIND, int EXTRA>
+// Sum over the 16 lanes of a DPP row (all lanes receive it): two quad permutations, half-row mirror, row mirror.
+__device__ __forceinline__ float row_sum16(float x) {
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xf, 0xf, false));
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xf, 0xf, false));
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xf, 0xf, false));
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x140, 0xf, 0xf, false));
+  return x;
+}
+
+template <int KS, int R, int KIND, int EXTRA>
 __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict__ Xp, const float* __restrict__ nrm,
                                                          const f4* __restrict__ Vp, const float* __restrict__ Ep,
                                                          float* __restrict__ Part, int64_t npad, int d, int nblk,
                                                          int stages_per_split, int cm) {
-  constexpr int R = kSymR, JT = kSymJT;
+  constexpr int JT = sym_jt(KS);
   constexpr int TS = 16 + EXTRA;
   constexpr int SB = 64 * R / (16 * JT);      // stages per block of 64 R points
   constexpr int XF4 = JT * KS * 16, VF4 = JT * 64, EF4 = JT * 4;
   constexpr int NX = (XF4 + 255) / 256, NV = (VF4 + 255) / 256;
-  static_assert(EXTRA == 0, "the 17th column is not built yet");
 
   __shared__ f4 Xs[2][XF4];
   __shared__ f4 Vs[2][VF4];
   __shared__ __attribute__((aligned(16))) float Ts[4][2][kPatch];      // per wave: two transposition patches
+  __shared__ f4 Es[2][EXTRA ? EF4 : 1];
   __shared__ f4 CJ[4][JT][64];      // column-side sums of one stage, per wave: [wave][tile][lane], register r = component
+  __shared__ float CJE[4][JT][16];  // the same for the 17th column: [wave][tile][column point]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -53,6 +64,7 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
   const int64_t row_tile0 = ((int64_t)bi * 4 + wave) * R;
   float b[R][KS];
   f4 cq[R], o[R], o2[R], vrow[R];
+  float eacc[R], eacc2[R], erow[R];
   constexpr int kFlushStages = 4096 / (16 * JT);
   const int ds = d >> 2, dq = d & 3;
 #pragma unroll
@@ -69,12 +81,19 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
     o[it] = (f4){0.f, 0.f, 0.f, 0.f};
     o2[it] = (f4){0.f, 0.f, 0.f, 0.f};
     vrow[it] = Vp[(row_tile0 + it) * 64 + lane];
+    eacc[it] = 0.f;
+    eacc2[it] = 0.f;
+    erow[it] = EXTRA ? Ep[(row_tile0 + it) * 16 + p] : 0.f;
   }
   auto fold = [&]() {
 #pragma unroll
     for (int it = 0; it < R; ++it) {
       o2[it] += o[it];
       o[it] = (f4){0.f, 0.f, 0.f, 0.f};
+      if (EXTRA) {
+        eacc2[it] += eacc[it];
+        eacc[it] = 0.f;
+      }
     }
   };
   // transposition patch: lane (q,p) holds M[4q + r][p] in register r and wants M[p][4q + r]
@@ -87,6 +106,7 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
   if (k_end > stages_all) k_end = stages_all;
 
   const f4* Xg = reinterpret_cast<const f4*>(Xp);
+  const f4* Eg = reinterpret_cast<const f4*>(Ep);
   auto abs_stage = [&](int k) {
     int st = bi * SB + k;
     return st >= s_total ? st - s_total : st;
@@ -107,12 +127,15 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
       if (VF4 % 256 == 0 || k * 256 + wave * 64 < VF4)
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Vp + voff + tid + k * 256),
                                          (__attribute__((address_space(3))) void*)(&Vs[buf][k * 256 + wave * 64]), 16, 0, 0);
+    if (EXTRA && tid < EF4)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Eg + (int64_t)st * EF4 + tid),
+                                       (__attribute__((address_space(3))) void*)(&Es[buf][0]), 16, 0, 0);
   };
   // the column-side sums of stage st (absolute), one partial per wave in CJ, leave as atomic adds into the extra slab
   float* slab = Part + (int64_t)gridDim.y * npad * TS;
   auto flush = [&](int st) {
 #pragma unroll
-    for (int h = 0; h < JT / 4; ++h) {
+    for (int h = 0; h < JT / 4; ++h) {      // JT is a multiple of 4
       const int jt = wave + 4 * h;      // thread (wave, lane) adds up the four waves' sums of tiles wave, wave + 4, ...
       f4 v = CJ[0][jt][lane];
       v += CJ[1][jt][lane];
@@ -133,6 +156,16 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
         unsafeAtomicAdd(dst + 3 * TS, v.w);
       }
     }
+    if (EXTRA) {
+      // every thread takes part (a divergent tail here cost the whole kernel ~60 registers): thread = (pair of
+      // waves, tile, column point), for JT = 4 the upper half repeats with a zero addend
+      const int e = tid & (JT * 16 - 1), hw = (tid / (JT * 16)) & 1;
+      const int jt = e >> 4, jj = e & 15;
+      float v = CJE[2 * hw][jt][jj] + CJE[2 * hw + 1][jt][jj];
+      if (JT * 32 < 256 && tid >= JT * 32) v = 0.f;
+      const int64_t j = ((int64_t)st * JT + jt) * 16 + jj;
+      unsafeAtomicAdd(cm ? slab + (int64_t)16 * npad + j : slab + j * TS + 16, v);
+    }
   };
 
   if (k_begin < k_end) issue(abs_stage(k_begin), 0);
@@ -152,6 +185,8 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
 #pragma unroll
         for (int s = 0; s < KS; ++s) a[s] = xs[(jt * KS + s) * 64 + lane];
         const f4 v = Vs[buf][jt * 64 + lane];
+        f4 e = {0.f, 0.f, 0.f, 0.f};
+        if (EXTRA) e = Es[buf][jt * 4 + q];
 #pragma unroll
         for (int it = 0; it < R; ++it) {
           f4 acc = cq[it];
@@ -166,6 +201,12 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
           o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.y, v.y, o[it], 0, 0, 0);
           o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.z, v.z, o[it], 0, 0, 0);
           o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.w, v.w, o[it], 0, 0, 0);
+          if (EXTRA) {
+            eacc[it] = __builtin_fmaf(kk.x, e.x, eacc[it]);
+            eacc[it] = __builtin_fmaf(kk.y, e.y, eacc[it]);
+            eacc[it] = __builtin_fmaf(kk.z, e.z, eacc[it]);
+            eacc[it] = __builtin_fmaf(kk.w, e.w, eacc[it]);
+          }
         }
       }
     } else {
@@ -176,11 +217,13 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
 #pragma unroll
       for (int s = 0; s < KS; ++s) a[s] = xs[s * 64 + lane];
       f4 v = Vs[buf][lane];
+      f4 e = {0.f, 0.f, 0.f, 0.f};
+      if (EXTRA) e = Es[buf][q];
       for (int jt = 0; jt < JT; ++jt) {
         const int jn = jt + 1 < JT ? jt + 1 : JT - 1;
         float an[KS];
-        f4 vn = v;
-        f4 oj = {0.f, 0.f, 0.f, 0.f};
+        f4 vn = v, en = e;
+        f4 oj = {0.f, 0.f, 0.f, 0.f}, ej = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int it = 0; it <= R; ++it) {
           f4 kt = {0.f, 0.f, 0.f, 0.f};
@@ -195,6 +238,7 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
 #pragma unroll
             for (int s = 0; s < KS; ++s) an[s] = xs[(jn * KS + s) * 64 + lane];
             vn = Vs[buf][jn * 64 + lane];
+            if (EXTRA) en = Es[buf][jn * 4 + q];
           }
           __builtin_amdgcn_sched_barrier(0);
           f4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -222,10 +266,32 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
             o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.z, v.z, o[it], 0, 0, 0);
             o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.w, v.w, o[it], 0, 0, 0);
             *reinterpret_cast<f4*>(patch + (it & 1) * kPatch + woff) = kk;
+            if (EXTRA) {
+              // kk.r = k(column point 4q + r, row point p): row side sums over the column points, column side over
+              // the row points (lanes p; reduced after the row tiles)
+              eacc[it] = __builtin_fmaf(kk.x, e.x, eacc[it]);
+              eacc[it] = __builtin_fmaf(kk.y, e.y, eacc[it]);
+              eacc[it] = __builtin_fmaf(kk.z, e.z, eacc[it]);
+              eacc[it] = __builtin_fmaf(kk.w, e.w, eacc[it]);
+              ej.x = __builtin_fmaf(kk.x, erow[it], ej.x);
+              ej.y = __builtin_fmaf(kk.y, erow[it], ej.y);
+              ej.z = __builtin_fmaf(kk.z, erow[it], ej.z);
+              ej.w = __builtin_fmaf(kk.w, erow[it], ej.w);
+            }
           }
           __builtin_amdgcn_sched_barrier(0);
         }
         CJ[wave][jt][lane] = oj;
+        if (EXTRA) {
+          ej.x = row_sum16(ej.x);
+          ej.y = row_sum16(ej.y);
+          ej.z = row_sum16(ej.z);
+          ej.w = row_sum16(ej.w);
+          // every lane of the row holds the four sums: all sixteen store them (a predicated store in this loop
+          // cost ~60 registers)
+          *reinterpret_cast<f4*>(&CJE[wave][jt][4 * q]) = ej;
+          e = en;
+        }
 #pragma unroll
         for (int s = 0; s < KS; ++s) a[s] = an[s];
         v = vn;
@@ -255,46 +321,65 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
       r0[2 * TS] = o2[it].z;
       r0[3 * TS] = o2[it].w;
     }
+    if (EXTRA) {
+      float s = eacc2[it];
+      s += __shfl_xor(s, 16);
+      s += __shfl_xor(s, 32);
+      if (q == 0) {
+        if (cm) dst[(int64_t)16 * npad + row0 + p] = s;
+        else dst[(row0 + p) * TS + 16] = s;
+      }
+    }
   }
 }
 
-template <int KS, int KIND>
+template <int KS, int R, int KIND, int EXTRA>
 int launch_sym_one(const Prepared& P, const Plan& pl, const f4* Vp, const float* Ep, float* Part, int cm,
                    hipStream_t stream) {
-  const int nblk = (int)(P.npad / (64 * kSymR));
-  hipLaunchKernelGGL((kmm_kernel_sym<KS, KIND, 0>), dim3(nblk, pl.splits), dim3(256), 0, stream, P.Xp, P.nrm, Vp, Ep,
-                     Part, P.npad, P.d, nblk, pl.stages_per_split, cm);
+  const int nblk = (int)(P.npad / (64 * R));
+  hipLaunchKernelGGL((kmm_kernel_sym<KS, R, KIND, EXTRA>), dim3(nblk, pl.splits), dim3(256), 0, stream, P.Xp, P.nrm, Vp,
+                     Ep, Part, P.npad, P.d, nblk, pl.stages_per_split, cm);
   EGP_HIP(hipGetLastError());
   return EGP_OK;
 }
 
+template <int KS, int KIND>
+int launch_sym_shape(const Prepared& P, const Plan& pl, int extra, const f4* Vp, const float* Ep, float* Part, int cm,
+                     hipStream_t stream) {
+  if (extra) return launch_sym_one<KS, 4, KIND, 1>(P, pl, Vp, Ep, Part, cm, stream);
+  if constexpr (KS <= 4) return launch_sym_one<KS, 8, KIND, 0>(P, pl, Vp, Ep, Part, cm, stream);
+  else return launch_sym_one<KS, 4, KIND, 0>(P, pl, Vp, Ep, Part, cm, stream);
+}
+
 template <int KS>
-int launch_sym_kind(const Prepared& P, const Plan& pl, const f4* Vp, const float* Ep, float* Part, int cm,
+int launch_sym_kind(const Prepared& P, const Plan& pl, int extra, const f4* Vp, const float* Ep, float* Part, int cm,
                     hipStream_t stream) {
   switch (P.kernel_type) {
-    case EGP_RBF: return launch_sym_one<KS, EGP_RBF>(P, pl, Vp, Ep, Part, cm, stream);
-    case EGP_MATERN32: return launch_sym_one<KS, EGP_MATERN32>(P, pl, Vp, Ep, Part, cm, stream);
-    default: return launch_sym_one<KS, EGP_MATERN52>(P, pl, Vp, Ep, Part, cm, stream);
+    case EGP_RBF: return launch_sym_shape<KS, EGP_RBF>(P, pl, extra, Vp, Ep, Part, cm, stream);
+    case EGP_MATERN32: return launch_sym_shape<KS, EGP_MATERN32>(P, pl, extra, Vp, Ep, Part, cm, stream);
+    default: return launch_sym_shape<KS, EGP_MATERN52>(P, pl, extra, Vp, Ep, Part, cm, stream);
   }
 }
 
 }  // namespace
 
-bool sym_applies(int64_t npad_rows, int64_t npad_cols, int ks, int nb, int extra) {
-  // up to 4 distance k-steps (d <= 14) the resident operands of 8 row tiles fit the register file at two waves per SIMD
-  return npad_rows == npad_cols && ks <= 4 && nb == 1 && extra == 0 && npad_rows / (64 * 8) >= 64;
+// Row tiles per wave of the symmetric kernel for this shape, or 0 where it does not apply. Eight row tiles fit the
+// register file (two waves per SIMD) up to 4 distance k-steps (d <= 14) without a 17th column; four otherwise.
+int sym_row_tiles(int64_t npad_rows, int64_t npad_cols, int ks, int nb, int extra) {
+  if (npad_rows != npad_cols || ks > 8 || nb != 1 || npad_rows / (64 * 8) < 64) return 0;
+  return (ks <= 4 && !extra) ? 8 : 4;
 }
 
 // stages_total holds the length of one workgroup's sweep; row_blocks the block count
-Plan make_plan_sym(int64_t npad) {
+Plan make_plan_sym(int64_t npad, int r, int ks) {
   Plan pl;
   pl.big = true;
   pl.sym = true;
   pl.extra_slabs = 1;
-  const int nblk = (int)(npad / (64 * kSymR));
-  constexpr int SB = 64 * kSymR / (16 * kSymJT);
+  const int nblk = (int)(npad / (64 * r));
+  const int sb = 64 * r / (16 * sym_jt(ks));
   pl.row_blocks = nblk;
-  pl.stages_total = (nblk / 2 + 1) * SB;
+  pl.stages_total = (nblk / 2 + 1) * sb;
   int want = 1024 / nblk;
   if (want < 1) want = 1;
   if (want > pl.stages_total) want = pl.stages_total;
@@ -304,17 +389,23 @@ Plan make_plan_sym(int64_t npad) {
   return pl;
 }
 
-// Part must hold pl.splits + 1 slabs of npad x 16 floats; the last one receives the column-side sums and is
-// cleared here.
-int launch_sym(const Prepared& P, const Plan& pl, const f4* Vp, const float* Ep, float* Part, int cm, hipStream_t stream) {
+// Part must hold pl.splits + 1 slabs of npad x (16 + extra) floats; the last one receives the column-side sums and
+// is cleared here.
+int launch_sym(const Prepared& P, const Plan& pl, int extra, const f4* Vp, const float* Ep, float* Part, int cm,
+               hipStream_t stream) {
   ProfScope prof(kProfKmm, stream);
-  EGP_HIP(hipMemsetAsync(Part + (int64_t)pl.splits * P.npad * 16, 0, (size_t)P.npad * 16 * sizeof(float), stream));
+  const size_t slab = (size_t)P.npad * (16 + extra);
+  EGP_HIP(hipMemsetAsync(Part + (size_t)pl.splits * slab, 0, slab * sizeof(float), stream));
   switch (P.ks) {
-    case 1: return launch_sym_kind<1>(P, pl, Vp, Ep, Part, cm, stream);
-    case 2: return launch_sym_kind<2>(P, pl, Vp, Ep, Part, cm, stream);
-    case 3: return launch_sym_kind<3>(P, pl, Vp, Ep, Part, cm, stream);
-    case 4: return launch_sym_kind<4>(P, pl, Vp, Ep, Part, cm, stream);
-    default: return fail(EGP_ERR_ARG, "the symmetric kernel supports d <= 14");
+    case 1: return launch_sym_kind<1>(P, pl, extra, Vp, Ep, Part, cm, stream);
+    case 2: return launch_sym_kind<2>(P, pl, extra, Vp, Ep, Part, cm, stream);
+    case 3: return launch_sym_kind<3>(P, pl, extra, Vp, Ep, Part, cm, stream);
+    case 4: return launch_sym_kind<4>(P, pl, extra, Vp, Ep, Part, cm, stream);
+    case 5: return launch_sym_kind<5>(P, pl, extra, Vp, Ep, Part, cm, stream);
+    case 6: return launch_sym_kind<6>(P, pl, extra, Vp, Ep, Part, cm, stream);
+    case 7: return launch_sym_kind<7>(P, pl, extra, Vp, Ep, Part, cm, stream);
+    case 8: return launch_sym_kind<8>(P, pl, extra, Vp, Ep, Part, cm, stream);
+    default: return fail(EGP_ERR_ARG, "the symmetric kernel supports d <= 31");
   }
 }
 
