@@ -114,23 +114,45 @@ def main():
     def step():
         egp.kmm(X, V16, w.lengthscales, w.outputscale, w.noise, w.kernel_type, out=out, ws=ws)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    lib.egp_profile_enable(1)
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    kmm_ms, kmm_launches = prof_read(lib, 0)
-    pack_ms, _ = prof_read(lib, 1)
-    lib.egp_profile_enable(0)
-    ms_per_step = wall * 1e3 / args.steps
-    entries_per_s = n * n / (wall / args.steps)
-    kern_ms = kmm_ms / max(kmm_launches, 1)
+    lib.egp_set_kmm_mode.argtypes = [C.c_int32]
+
+    def timed(mode, warmup):
+        """W untimed and K timed steps in one arithmetic mode; the kernel's own duration from in-stream events."""
+        lib.egp_set_kmm_mode(mode)
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        lib.egp_profile_enable(1)
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        k_ms, k_n = prof_read(lib, 0)
+        p_ms, _ = prof_read(lib, 1)
+        lib.egp_profile_enable(0)
+        lib.egp_set_kmm_mode(0)
+        return {"wall": wall, "kern_ms": k_ms / max(k_n, 1), "launches": k_n, "pack_ms": p_ms / args.steps}
+
     fpe = flops_per_entry(d, 16, w.kernel_type)
-    achieved_tflops = fpe * n * n / (kern_ms * 1e-3) / 1e12
+    one = timed(0, args.warmup)                       # one-sided fp32 kernel: every tile of the n x n matrix formed
+    one_out = out.clone()
+    sym = timed(3, args.warmup)                       # symmetric fp32 mode: the headline
+    # flops the symmetric kernel executes per logical entry: distance + transform once per tile pair, the
+    # contraction once per side; the diagonal block (and for an even block count the half-way block) one-sided
+    npad = (n + 511) // 512 * 512
+    sym_used = npad >= 32768 and d <= 31
+    nblk = npad // 512 if d <= 14 else npad // 256
+    even = nblk % 2 == 0
+    plain_blocks = 1 + (1 if even else 0)
+    dual_blocks = nblk // 2 - (1 if even else 0)
+    fpe_pair_half = (fpe - 2 * 16) / 2 + 2 * 16       # per logical entry of a tile used on both sides
+    fpe_exec = (plain_blocks * fpe + 2 * dual_blocks * fpe_pair_half) / nblk if sym_used else fpe
+    head = sym if sym_used else one
+    ms_per_step = head["wall"] * 1e3 / args.steps
+    entries_per_s = n * n / (head["wall"] / args.steps)
+    kern_ms = head["kern_ms"]
+    achieved_tflops = fpe_exec * n * n / (kern_ms * 1e-3) / 1e12
 
     result = {
         "metric": "kernel entries/s in fused K·V (n=1M,d=11,t=16); s per mBCG iteration",
@@ -140,16 +162,29 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"C4: n={n}, d={d}, t=16 probe columns, RBF-ARD, 32-component clustered "
-                               "mixture in [0,1]^11, one full egp_kmm call per step"},
+                               "mixture in [0,1]^11, one full egp_kmm call per step",
+                   "kmm_mode": "EGP_KMM_FP32_SYM: fp32 arithmetic, logical n^2 entries counted, every off-diagonal "
+                               "tile formed once and used for both output sides" if sym_used else "EGP_KMM_FP32"},
+        # achieved counts the flops the symmetric kernel has to execute (fpe_exec per logical entry); against the
+        # one-sided count of flops_per_entry the same launch reads frac_one_sided_count (it may exceed 1)
         "roofline": {"bound": "mfma", "achieved": achieved_tflops, "peak": FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved_tflops / FP32_PEAK_TFLOPS,
-                     "traffic": read_traffic(os.path.join(ROOT, "profiles", "kmm_kernel_c4_t16_pmc.txt")),
-                     "kernel": "kmm_kernel", "kernel_ms": kern_ms, "launches": kmm_launches,
-                     "flops_per_entry": fpe, "pack_epilogue_ms_per_step": pack_ms / args.steps},
+                     "traffic": read_traffic(os.path.join(ROOT, "profiles", "kmm_kernel_sym_c4_t16_pmc.txt"
+                                                          if sym_used else "kmm_kernel_c4_t16_pmc.txt")),
+                     "kernel": "kmm_kernel_sym" if sym_used else "kmm_kernel", "kernel_ms": kern_ms,
+                     "launches": head["launches"], "flops_per_entry_executed": fpe_exec,
+                     "flops_per_entry": fpe, "frac_one_sided_count": fpe * n * n / (kern_ms * 1e-3) / 1e12 / FP32_PEAK_TFLOPS,
+                     "pack_epilogue_ms_per_step": head["pack_ms"]},
+        "one_sided_fp32_mode": {
+            "value": n * n / (one["wall"] / args.steps), "unit": "kernel entries/s",
+            "ms_per_step": one["wall"] * 1e3 / args.steps, "kernel": "kmm_kernel", "kernel_ms": one["kern_ms"],
+            "roofline_frac": fpe * n * n / (one["kern_ms"] * 1e-3) / 1e12 / FP32_PEAK_TFLOPS,
+            "traffic": read_traffic(os.path.join(ROOT, "profiles", "kmm_kernel_c4_t16_pmc.txt")),
+            "note": "EGP_KMM_FP32, the library's default: every tile formed, summation order fixed (bit-reproducible)"},
     }
+    sym_out = out.clone()
 
     # ---- the same product in the two bf16-split modes (egp_set_kmm_mode), reported separately ----
-    lib.egp_set_kmm_mode.argtypes = [C.c_int32]
     split_out = {}
     for mode, key, what in ((1, "split_bf16_mode", "f32 distances and transform; tile x V contraction as a 3-term "
                              "bf16 hi/lo split on the bf16 MFMA with fp32 accumulation"),
@@ -220,6 +255,15 @@ def main():
         egp.mbcg(X, B17, w.lengthscales, w.outputscale, w.noise, w.kernel_type, precond=P, max_iter=iters, tol=0.0)
         torch.cuda.synchronize()
         result["mbcg"]["s_per_iter_split_bf16_all_mode"] = (time.perf_counter() - t0) / iters
+        # and in the symmetric fp32 mode (t = 17: the 17th column on the VALU on both sides)
+        lib.egp_set_kmm_mode(3)
+        egp.mbcg(X, B17, w.lengthscales, w.outputscale, w.noise, w.kernel_type, precond=P, max_iter=1, tol=0.0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        res3 = egp.mbcg(X, B17, w.lengthscales, w.outputscale, w.noise, w.kernel_type, precond=P, max_iter=iters, tol=0.0)
+        torch.cuda.synchronize()
+        result["mbcg"]["s_per_iter_symmetric_mode"] = (time.perf_counter() - t0) / iters
+        result["mbcg"]["rel_resid_max_after_symmetric_mode"] = float(res3["rel_resid"].max())
         lib.egp_set_kmm_mode(0)
         result["piv_chol"] = {"s": pc_s, "steps_ms": pc_ms, "rank": k,
                               "gbs": pc_bytes / (pc_ms * 1e-3) / 1e9 if pc_ms > 0 else None}
@@ -257,6 +301,14 @@ def main():
             result["mbcg"]["full_solve_tol1_rank512"] = {
                 "precond_build_s": build512, "s": time.perf_counter() - t0, "iters": full3["iters"],
                 "rel_resid_max": float(full3["rel_resid"].max())}
+            lib.egp_set_kmm_mode(3)
+            t0 = time.perf_counter()
+            full4 = egp.mbcg(X, B17, w.lengthscales, w.outputscale, w.noise, w.kernel_type, precond=P,
+                             max_iter=w.max_iter, tol=w.tol)
+            torch.cuda.synchronize()
+            lib.egp_set_kmm_mode(0)
+            result["mbcg"]["full_solve_tol1_rank512_symmetric_mode"] = {
+                "s": time.perf_counter() - t0, "iters": full4["iters"], "rel_resid_max": float(full4["rel_resid"].max())}
         del P
         progress("C4 solver legs done")
 
@@ -416,7 +468,8 @@ def main():
         ref = orc.kmm_rows(w.X, Vh, h, rows)
         cpu_wall = time.perf_counter() - t0
         cpu_used = time.process_time() - c0
-        got = out.cpu().numpy()[rows].astype(np.float64)
+        got = sym_out.cpu().numpy()[rows].astype(np.float64)      # the headline leg's product
+        got_one = one_out.cpu().numpy()[rows].astype(np.float64)
         result["cpu_baseline"] = {
             "value": m * n / cpu_wall, "unit": "kernel entries/s", "cores": max(1, int(round(cpu_used / cpu_wall))),
             "kind": "oracle", "blas_threads_available": blas_threads,
@@ -425,6 +478,7 @@ def main():
             "host_cpus": os.cpu_count(),
         }
         result["parity_sampled_rows_rel_err"] = float(np.linalg.norm(got - ref) / np.linalg.norm(ref))
+        result["one_sided_fp32_mode"]["parity_sampled_rows_rel_err"] = float(np.linalg.norm(got_one - ref) / np.linalg.norm(ref))
         for key, so in split_out.items():
             got_s = so.cpu().numpy()[rows].astype(np.float64)
             result[key]["parity_sampled_rows_rel_err"] = float(np.linalg.norm(got_s - ref) / np.linalg.norm(ref))

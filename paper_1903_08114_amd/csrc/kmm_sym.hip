@@ -134,22 +134,27 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
   // the column-side sums of stage st (absolute), one partial per wave in CJ, leave as atomic adds into the extra slab
   float* slab = Part + (int64_t)gridDim.y * npad * TS;
   auto flush = [&](int st) {
+    if (cm) {
+      // column-major slab [column][row]: a thread takes (column tid / 16, row tid % 16) of every tile, so that the
+      // sixteen rows of a column are one contiguous 64-byte run of atomic adds
+      const int c = tid >> 4, jrow = tid & 15;
+      const float* cf = reinterpret_cast<const float*>(&CJ[0][0][0]);
+      const int off = ((jrow >> 2) * 16 + c) * 4 + (jrow & 3);
 #pragma unroll
-    for (int h = 0; h < JT / 4; ++h) {      // JT is a multiple of 4
-      const int jt = wave + 4 * h;      // thread (wave, lane) adds up the four waves' sums of tiles wave, wave + 4, ...
-      f4 v = CJ[0][jt][lane];
-      v += CJ[1][jt][lane];
-      v += CJ[2][jt][lane];
-      v += CJ[3][jt][lane];
-      const int64_t j = ((int64_t)st * JT + jt) * 16 + 4 * q;
-      if (cm) {
-        float* dst = slab + (int64_t)p * npad + j;
-        unsafeAtomicAdd(dst + 0, v.x);
-        unsafeAtomicAdd(dst + 1, v.y);
-        unsafeAtomicAdd(dst + 2, v.z);
-        unsafeAtomicAdd(dst + 3, v.w);
-      } else {
-        float* dst = slab + j * TS + p;
+      for (int jt = 0; jt < JT; ++jt) {
+        const float v = (cf[(0 * JT + jt) * 256 + off] + cf[(1 * JT + jt) * 256 + off]) +
+                        (cf[(2 * JT + jt) * 256 + off] + cf[(3 * JT + jt) * 256 + off]);
+        unsafeAtomicAdd(slab + (int64_t)c * npad + ((int64_t)st * JT + jt) * 16 + jrow, v);
+      }
+    } else {
+#pragma unroll
+      for (int h = 0; h < JT / 4; ++h) {      // JT is a multiple of 4
+        const int jt = wave + 4 * h;      // thread (wave, lane) adds up the four waves' sums of tiles wave, wave + 4, ...
+        f4 v = CJ[0][jt][lane];
+        v += CJ[1][jt][lane];
+        v += CJ[2][jt][lane];
+        v += CJ[3][jt][lane];
+        float* dst = slab + (((int64_t)st * JT + jt) * 16 + 4 * q) * TS + p;
         unsafeAtomicAdd(dst + 0 * TS, v.x);
         unsafeAtomicAdd(dst + 1 * TS, v.y);
         unsafeAtomicAdd(dst + 2 * TS, v.z);
