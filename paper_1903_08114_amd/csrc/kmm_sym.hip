@@ -24,7 +24,7 @@ namespace {
 
 // column tiles per stage: 8 up to 4 distance k-steps, 4 beyond (keeps the workgroup's LDS under 80 KB: two per CU)
 constexpr int sym_jt(int ks) { return ks <= 4 ? 8 : 4; }
-constexpr int kPatch = 304;      // floats of one transposition patch: 76 slots of 16 bytes
+constexpr int kPatch = 280;      // floats of one transposition patch: 70 slots of 16 bytes
 
 // Sum over the 16 lanes of a DPP row (all lanes receive it): two quad permutations, half-row mirror, row mirror.
 __device__ __forceinline__ float row_sum16(float x) {
@@ -98,8 +98,10 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
   };
   // transposition patch: lane (q,p) holds M[4q + r][p] in register r and wants M[p][4q + r]
   float* patch = &Ts[wave][0][0];
-  const int woff = 4 * (20 * q + 4 * (p & 3) + (p >> 2));      // 16-byte slot of this lane's four values
-  const int roff = 80 * (p >> 2) + 4 * q + (p & 3);            // + 16 r: the value for step r
+  // 16-byte slot of writer (q, p = 4a + b): 18 q + (a & 1) + 8 (a >> 1) + 2 b. Free of bank conflicts for 32 banks
+  // with 8 lanes per write pass / 32 per read pass as well as for 64 banks with 16 / 64 (checked by enumeration).
+  const int woff = 4 * (18 * q + ((p >> 2) & 1) + 8 * (p >> 3) + 2 * (p & 3));
+  const int roff = 72 * (p >> 2) + 4 * (q & 1) + 32 * (q >> 1) + (p & 3);      // + 8 r: the value for step r
 
   const int k_begin = blockIdx.y * stages_per_split;
   int k_end = k_begin + stages_per_split;
@@ -235,9 +237,9 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
           if (it > 0) {      // transposed tile of the previous step: in flight during this step's distance MFMAs
             const float* rp = patch + ((it - 1) & 1) * kPatch + roff;
             kt.x = rp[0];
-            kt.y = rp[16];
-            kt.z = rp[32];
-            kt.w = rp[48];
+            kt.y = rp[8];
+            kt.z = rp[16];
+            kt.w = rp[24];
           }
           if (it == R / 2) {
 #pragma unroll
