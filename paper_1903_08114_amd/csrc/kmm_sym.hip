@@ -56,7 +56,10 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int q = lane >> 4, p = lane & 15;
-  const int bi = blockIdx.x;
+  // Workgroups are dealt to the 8 XCDs round-robin. Row blocks are renumbered so that the workgroups resident on one
+  // XCD own neighbouring row blocks: their sweeps then run a few stages apart over the same column tiles and share
+  // them through that XCD's L2 (with the plain numbering every workgroup of an XCD streamed a range of its own).
+  const int bi = (nblk & 7) == 0 ? (int)(blockIdx.x & 7) * (nblk >> 3) + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
   const int half = nblk >> 1;
   const int stages_all = (half + 1) * SB;      // this workgroup's whole sweep, in stages
   const int s_total = nblk * SB;
