@@ -42,8 +42,10 @@ typedef enum {
  * appendix: independent lengthscales). k(x,x') = outputscale * g(r), r^2 = sum_k ((x_k-x'_k)/l_k)^2,
  *   RBF       g = exp(-r^2/2)
  *   MATERN32  g = (1 + sqrt3 r) exp(-sqrt3 r)
- *   MATERN52  g = (1 + sqrt5 r + 5 r^2/3) exp(-sqrt5 r)                                             */
-typedef enum { EGP_RBF = 0, EGP_MATERN32 = 1, EGP_MATERN52 = 2 } egp_kernel_t;
+ *   MATERN52  g = (1 + sqrt5 r + 5 r^2/3) exp(-sqrt5 r)
+ *   MATERN12  g = exp(-r)   (the Matern family's nu = 1/2 member; its lengthscale derivative keeps a 1/r, taken as
+ *                            0 for a point against itself)                                           */
+typedef enum { EGP_RBF = 0, EGP_MATERN32 = 1, EGP_MATERN52 = 2, EGP_MATERN12 = 3 } egp_kernel_t;
 
 #define EGP_D_MAX 31        /* largest input dimension of egp_kmm_grad (the materialised derivative product) and of
                                the bf16-split modes */

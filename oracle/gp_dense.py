@@ -14,7 +14,7 @@ oracle runs the textbook algorithm step by step on the dense matrix.
 The paper names the kernels (RBF, Matern; Background and Experiment details) and
 cites the modified PCG, pivoted-Cholesky preconditioner and stochastic
 log-determinant without stating them; the forms used here are the standard ones
-(Rasmussen & Williams ch. 4 for the kernels; Golub & Van Loan for PCG and for
+(Rasmussen & Williams ch. 4 for the kernels, Matern-1/2 = exp(-r) included; Golub & Van Loan for PCG and for
 diagonal-pivoted Cholesky; the CG<->Lanczos identity and Gauss quadrature for
 the log-determinant).
 
@@ -31,10 +31,10 @@ from __future__ import annotations
 import numpy as np
 import scipy.linalg as sla
 
-RBF, MATERN32, MATERN52 = 0, 1, 2
+RBF, MATERN32, MATERN52, MATERN12 = 0, 1, 2, 3
 
 __all__ = [
-    "RBF", "MATERN32", "MATERN52", "Hyper", "sq_dist", "kernel_matrix", "khat", "kmm",
+    "RBF", "MATERN32", "MATERN52", "MATERN12", "Hyper", "sq_dist", "kernel_matrix", "khat", "kmm",
     "kmm_rows", "dkernel_dlengthscale", "kmm_grad", "kmm_grad_rows", "chol_solve", "logdet",
     "mll", "mll_grad", "pivoted_cholesky", "precond_matrix", "precond_solve", "precond_logdet",
     "pcg", "tridiag_from_cg", "slq_quadrature", "slq_logdet", "probes_with_cov_P",
@@ -77,11 +77,14 @@ def _g(r2, kernel_type):
     if kernel_type == MATERN52:
         a = np.sqrt(5.0) * r
         return (1.0 + a + a * a / 3.0) * np.exp(-a)
+    if kernel_type == MATERN12:
+        return np.exp(-r)
     raise ValueError("unknown kernel type")
 
 
 def _h(r2, kernel_type):
-    """h(r) with d g / d l_k = h(r) * (x_k - x'_k)^2 / l_k^3 (chain rule; r cancels, so r=0 is regular)."""
+    """h(r) with d g / d l_k = h(r) * (x_k - x'_k)^2 / l_k^3 (chain rule; for RBF and Matern-3/2, 5/2 r cancels, so
+    r=0 is regular; Matern-1/2 keeps a 1/r)."""
     if kernel_type == RBF:
         return np.exp(-0.5 * r2)
     r = np.sqrt(r2)
@@ -90,6 +93,11 @@ def _h(r2, kernel_type):
     if kernel_type == MATERN52:
         a = np.sqrt(5.0) * r
         return (5.0 / 3.0) * (1.0 + a) * np.exp(-a)
+    if kernel_type == MATERN12:
+        # g = exp(-r): d g / d l_k = exp(-r) (x_k - x'_k)^2 / (r l_k^3); at r = 0 the squared difference is 0 too
+        # and the entry (a point against itself) does not depend on the lengthscales: 0
+        safe = np.where(r > 0.0, r, 1.0)
+        return np.where(r > 0.0, np.exp(-r) / safe, 0.0)
     raise ValueError("unknown kernel type")
 
 

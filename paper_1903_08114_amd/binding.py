@@ -5,7 +5,7 @@ import ctypes as C
 import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-EGP_RBF, EGP_MATERN32, EGP_MATERN52 = 0, 1, 2
+EGP_RBF, EGP_MATERN32, EGP_MATERN52, EGP_MATERN12 = 0, 1, 2, 3
 
 _lib = None
 

@@ -30,7 +30,7 @@ int validate_ptr(const void* p, const char* name) {
 
 int validate_hyper(const egp_hyper_t* h, int d_max) {
   if (h == nullptr) return fail(EGP_ERR_ARG, "hyper-parameter struct is NULL");
-  if (h->kernel_type < EGP_RBF || h->kernel_type > EGP_MATERN52)
+  if (h->kernel_type < EGP_RBF || h->kernel_type > EGP_MATERN12)
     return fail(EGP_ERR_ARG, "unknown kernel_type %d", h->kernel_type);
   if (h->d < 1 || h->d > d_max) return fail(EGP_ERR_ARG, "d = %d outside 1..%d for this entry point", h->d, d_max);
   if (h->lengthscales == nullptr) return fail(EGP_ERR_ARG, "lengthscales is NULL");

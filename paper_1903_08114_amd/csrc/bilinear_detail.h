@@ -22,6 +22,13 @@ __device__ __forceinline__ float hg(float acc, float* g) {
     const float e = __builtin_amdgcn_exp2f(-a);
     *g = __builtin_fmaf(a, kLn2, 1.0f) * e;
     return e;
+  } else if constexpr (KIND == EGP_MATERN12) {
+    // g = exp(-r), h = exp(-r) / r: the 1/r does not cancel here. A point against itself (acc = 0) has a zero
+    // squared difference in every feature; its weight is set to 0 so that 0 * inf cannot arise.
+    const float m = __builtin_fabsf(acc);
+    const float e = __builtin_amdgcn_exp2f(-__builtin_amdgcn_sqrtf(m));
+    *g = e;
+    return m > 0.f ? e * __builtin_amdgcn_rsqf(m) : 0.f;
   } else {
     const float a = __builtin_amdgcn_sqrtf(__builtin_fabsf(acc));
     const float e = __builtin_amdgcn_exp2f(-a);

@@ -25,10 +25,12 @@ using namespace kmm_detail;
 //   RBF:  acc = r^2 log2(e)/2        k = exp2(-acc)
 //   M32:  acc = (sqrt3 r log2 e)^2   a = sqrt(acc), k = (1 + a ln2) exp2(-a)
 //   M52:  acc = (sqrt5 r log2 e)^2   a = sqrt(acc), k = (1 + a ln2 + (a ln2)^2/3) exp2(-a)
+//   M12:  acc = (r log2 e)^2         a = sqrt(acc), k = exp2(-a)
 static double point_scale(int kernel_type) {
   switch (kernel_type) {
     case EGP_RBF: return sqrt(0.5 * 1.4426950408889634);
     case EGP_MATERN32: return sqrt(3.0) * 1.4426950408889634;
+    case EGP_MATERN12: return 1.4426950408889634;
     default: return sqrt(5.0) * 1.4426950408889634;
   }
 }

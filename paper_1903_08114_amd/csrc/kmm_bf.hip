@@ -101,7 +101,8 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_bf(const u4* __restrict__ X
                                                         const u4* __restrict__ XbC, const u4* __restrict__ VbA,
                                                         const u2* __restrict__ VbB, const float* __restrict__ Ep,
                                                         float* __restrict__ Part, int64_t npad,
-                                                        int stages_per_split, int stages_total, int cm) {
+                                                        int stages_per_split, int stages_total, int cm,
+                                                        int square) {
   constexpr int TS = 16 * NB + EXTRA;
   constexpr int NBA = NB > 0 ? NB : 1;       // array extents of the single-column shape (NB = 0, EXTRA = 1)
   static_assert(NB > 0 || EXTRA, "a launch carries at least one column");
@@ -214,6 +215,9 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_bf(const u4* __restrict__ X
         k.y = transform<KIND>(acc.y);
         k.z = transform<KIND>(acc.z);
         k.w = transform<KIND>(acc.w);
+        if constexpr (KIND == EGP_MATERN12) {      // exact k(x, x) on the diagonal of a square product (see kmm_kernel.h)
+          if (square && row_tile0 + it == (int64_t)st * JT + jt) set_unit_diagonal(k, q, p);
+        }
         const unsigned u0 = __float_as_uint(k.x), u1 = __float_as_uint(k.y);
         const unsigned u2_ = __float_as_uint(k.z), u3 = __float_as_uint(k.w);
         const unsigned hi01 = __builtin_amdgcn_perm(u1, u0, 0x07060302u);
@@ -285,10 +289,10 @@ int launch_bf_shape(const Prepared& P, const Prepared& Q, const kmm_detail::Plan
   const u4* xc = reinterpret_cast<const u4*>(P.XbC);
   if (pl.big)
     hipLaunchKernelGGL((kmm_kernel_bf<KS16, bf_big_r(KS16, NB, EXTRA), KIND, NB, EXTRA, bf_big_jt(KS16, NB)>), grid, block, 0, stream, xr, Q.nrm, xc,
-                       VbA, VbB, Ep, Part, Q.npad, pl.stages_per_split, pl.stages_total, cm);
+                       VbA, VbB, Ep, Part, Q.npad, pl.stages_per_split, pl.stages_total, cm, (int)(Q.Xp == P.Xp));
   else
     hipLaunchKernelGGL((kmm_kernel_bf<KS16, kBfSmallR, KIND, NB, EXTRA, bf_small_jt(KS16)>), grid, block, 0, stream, xr, Q.nrm,
-                       xc, VbA, VbB, Ep, Part, Q.npad, pl.stages_per_split, pl.stages_total, cm);
+                       xc, VbA, VbB, Ep, Part, Q.npad, pl.stages_per_split, pl.stages_total, cm, (int)(Q.Xp == P.Xp));
   EGP_HIP(hipGetLastError());
   return EGP_OK;
 }
@@ -309,6 +313,7 @@ int launch_bf_kind(const Prepared& P, const Prepared& Q, const kmm_detail::Plan&
   switch (P.kernel_type) {
     case EGP_RBF: return launch_bf_cols<KS16, EGP_RBF>(P, Q, pl, nb, extra, VbA, VbB, Ep, Part, cm, stream);
     case EGP_MATERN32: return launch_bf_cols<KS16, EGP_MATERN32>(P, Q, pl, nb, extra, VbA, VbB, Ep, Part, cm, stream);
+    case EGP_MATERN12: return launch_bf_cols<KS16, EGP_MATERN12>(P, Q, pl, nb, extra, VbA, VbB, Ep, Part, cm, stream);
     default: return launch_bf_cols<KS16, EGP_MATERN52>(P, Q, pl, nb, extra, VbA, VbB, Ep, Part, cm, stream);
   }
 }

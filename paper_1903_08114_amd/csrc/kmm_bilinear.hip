@@ -230,6 +230,10 @@ void launch_b(const Prepared& P, const BPlan& pl, const float* Ap, const float* 
       hipLaunchKernelGGL((bilinear_kernel<KS, TS, EGP_MATERN32>), grid, block, 0, stream, P.Xp, P.nrm, Ap, Bp, part,
                          P.npad, P.d, pl.stages_per_split, pl.stages_total);
       break;
+    case EGP_MATERN12:
+      hipLaunchKernelGGL((bilinear_kernel<KS, TS, EGP_MATERN12>), grid, block, 0, stream, P.Xp, P.nrm, Ap, Bp, part,
+                         P.npad, P.d, pl.stages_per_split, pl.stages_total);
+      break;
     default:
       hipLaunchKernelGGL((bilinear_kernel<KS, TS, EGP_MATERN52>), grid, block, 0, stream, P.Xp, P.nrm, Ap, Bp, part,
                          P.npad, P.d, pl.stages_per_split, pl.stages_total);
@@ -315,8 +319,11 @@ int bilinear_core(const Prepared& P, const egp_hyper_t* h, const float* A, const
   EGP_HIP(hipMemcpyAsync(hp.data(), part, hp.size() * sizeof(float), hipMemcpyDeviceToHost, stream));
   EGP_HIP(hipStreamSynchronize(stream));
   const double c2 = h->kernel_type == EGP_RBF ? 0.5 * 1.4426950408889634
-                    : (h->kernel_type == EGP_MATERN32 ? 3.0 : 5.0) * 1.4426950408889634 * 1.4426950408889634;
-  const double hfac = h->kernel_type == EGP_RBF ? 1.0 : (h->kernel_type == EGP_MATERN32 ? 3.0 : 5.0 / 3.0);
+                    : (h->kernel_type == EGP_MATERN32 ? 3.0 : (h->kernel_type == EGP_MATERN52 ? 5.0 : 1.0)) *
+                          1.4426950408889634 * 1.4426950408889634;
+  // Matern-1/2: h = exp(-r) / r = log2(e) exp2(-a) / a with a = r log2(e)
+  const double hfac = h->kernel_type == EGP_RBF ? 1.0
+                      : (h->kernel_type == EGP_MATERN32 ? 3.0 : (h->kernel_type == EGP_MATERN52 ? 5.0 / 3.0 : 1.4426950408889634));
   for (int k = 0; k <= P.d; ++k) {
     double s = 0.0;
     for (int64_t bidx = 0; bidx < nblk; ++bidx) s += (double)hp[(size_t)bidx * (kDMaxB + 1) + k];

@@ -238,8 +238,19 @@ __global__ __launch_bounds__(256) void bilinear_wide_kernel(const float* __restr
 #pragma unroll
     for (int it = 0; it < RW; ++it) {
       float g0, g1, g2, g3;
-      const float h0 = hg<KIND>(acc[it].x, &g0), h1 = hg<KIND>(acc[it].y, &g1);
-      const float h2 = hg<KIND>(acc[it].z, &g2), h3 = hg<KIND>(acc[it].w, &g3);
+      float h0 = hg<KIND>(acc[it].x, &g0), h1 = hg<KIND>(acc[it].y, &g1);
+      float h2 = hg<KIND>(acc[it].z, &g2), h3 = hg<KIND>(acc[it].w, &g3);
+      if constexpr (KIND == EGP_MATERN12) {
+        // A point against itself: the expanded squared difference is rounding noise, not 0, and h = exp(-r)/r is
+        // huge at a computed r ~ 3e-4; the entry does not depend on the lengthscales, so its weight is 0.
+        if (row_tile0 + it == ct) {
+          const int r = p - 4 * q;
+          if (r == 0) h0 = 0.f;
+          if (r == 1) h1 = 0.f;
+          if (r == 2) h2 = 0.f;
+          if (r == 3) h3 = 0.f;
+        }
+      }
       acc_s = __builtin_fmaf(sv[it].x, g0, acc_s);
       acc_s = __builtin_fmaf(sv[it].y, g1, acc_s);
       acc_s = __builtin_fmaf(sv[it].z, g2, acc_s);
@@ -449,6 +460,7 @@ int bilinear_wide_core(const Prepared& P, const egp_hyper_t* h, const float* A, 
     switch (P.kernel_type) {
       case EGP_RBF: rc = launch_nbf<EGP_RBF>(P, pl, Ap, Bp, Xf, part, stream); break;
       case EGP_MATERN32: rc = launch_nbf<EGP_MATERN32>(P, pl, Ap, Bp, Xf, part, stream); break;
+      case EGP_MATERN12: rc = launch_nbf<EGP_MATERN12>(P, pl, Ap, Bp, Xf, part, stream); break;
       default: rc = launch_nbf<EGP_MATERN52>(P, pl, Ap, Bp, Xf, part, stream);
     }
   }
@@ -458,8 +470,11 @@ int bilinear_wide_core(const Prepared& P, const egp_hyper_t* h, const float* A, 
   EGP_HIP(hipMemcpyAsync(hp.data(), part, hp.size() * sizeof(float), hipMemcpyDeviceToHost, stream));
   EGP_HIP(hipStreamSynchronize(stream));
   const double c2 = h->kernel_type == EGP_RBF ? 0.5 * 1.4426950408889634
-                    : (h->kernel_type == EGP_MATERN32 ? 3.0 : 5.0) * 1.4426950408889634 * 1.4426950408889634;
-  const double hfac = h->kernel_type == EGP_RBF ? 1.0 : (h->kernel_type == EGP_MATERN32 ? 3.0 : 5.0 / 3.0);
+                    : (h->kernel_type == EGP_MATERN32 ? 3.0 : (h->kernel_type == EGP_MATERN52 ? 5.0 : 1.0)) *
+                          1.4426950408889634 * 1.4426950408889634;
+  // Matern-1/2: h = exp(-r) / r = log2(e) exp2(-a) / a with a = r log2(e)
+  const double hfac = h->kernel_type == EGP_RBF ? 1.0
+                      : (h->kernel_type == EGP_MATERN32 ? 3.0 : (h->kernel_type == EGP_MATERN52 ? 5.0 / 3.0 : 1.4426950408889634));
   for (int k = 0; k <= P.d; ++k) {
     double s = 0.0;
     for (int64_t bidx = 0; bidx < nblk; ++bidx) s += (double)hp[(size_t)bidx * kWLd + k];

@@ -23,7 +23,7 @@ constexpr int DK = 13;   // lengthscales per pass
 constexpr int GR = 2;    // row tiles per wave
 constexpr int GJT = 8;   // column tiles per LDS stage
 
-// h(r) up to a constant factor that the output scale carries (1, 3, 5/3)
+// h(r) up to a constant factor that the output scale carries (1, 3, 5/3; log2 e for Matern-1/2)
 template <int KIND>
 __device__ __forceinline__ float htransform(float acc) {
   if constexpr (KIND == EGP_RBF) {
@@ -31,6 +31,9 @@ __device__ __forceinline__ float htransform(float acc) {
   } else if constexpr (KIND == EGP_MATERN32) {
     float a = __builtin_amdgcn_sqrtf(__builtin_fabsf(acc));
     return __builtin_amdgcn_exp2f(-a);
+  } else if constexpr (KIND == EGP_MATERN12) {
+    const float m = __builtin_fabsf(acc);      // exp(-r) / r, 0 for a point against itself
+    return m > 0.f ? __builtin_amdgcn_exp2f(-__builtin_amdgcn_sqrtf(m)) * __builtin_amdgcn_rsqf(m) : 0.f;
   } else {
     float a = __builtin_amdgcn_sqrtf(__builtin_fabsf(acc));
     return __builtin_fmaf(a, kLn2, 1.0f) * __builtin_amdgcn_exp2f(-a);
@@ -225,6 +228,10 @@ int launch_grad(const Prepared& P, const GPlan& pl, const f4* Vp, float* dst, in
       hipLaunchKernelGGL((kmm_grad_kernel<KS, EGP_MATERN32>), grid, block, 0, stream, P.Xp, P.nrm, Vp, dst, P.npad,
                          P.n, P.d, k0, dk, pl.stages_per_split, pl.stages_total, direct, t, c0, tg, sc);
       break;
+    case EGP_MATERN12:
+      hipLaunchKernelGGL((kmm_grad_kernel<KS, EGP_MATERN12>), grid, block, 0, stream, P.Xp, P.nrm, Vp, dst, P.npad,
+                         P.n, P.d, k0, dk, pl.stages_per_split, pl.stages_total, direct, t, c0, tg, sc);
+      break;
     default:
       hipLaunchKernelGGL((kmm_grad_kernel<KS, EGP_MATERN52>), grid, block, 0, stream, P.Xp, P.nrm, Vp, dst, P.npad,
                          P.n, P.d, k0, dk, pl.stages_per_split, pl.stages_total, direct, t, c0, tg, sc);
@@ -254,8 +261,11 @@ int kmm_grad_core(const Prepared& P, const egp_hyper_t* h, const float* V, int t
 
   // x~ = c x / l  =>  (x_ik - x_jk)^2 / l_k^3 = (x~_ik - x~_jk)^2 / (l_k c^2); Matern h carries 3 resp. 5/3
   const double c2 = h->kernel_type == EGP_RBF ? 0.5 * 1.4426950408889634
-                    : (h->kernel_type == EGP_MATERN32 ? 3.0 : 5.0) * 1.4426950408889634 * 1.4426950408889634;
-  const double hfac = h->kernel_type == EGP_RBF ? 1.0 : (h->kernel_type == EGP_MATERN32 ? 3.0 : 5.0 / 3.0);
+                    : (h->kernel_type == EGP_MATERN32 ? 3.0 : (h->kernel_type == EGP_MATERN52 ? 5.0 : 1.0)) *
+                          1.4426950408889634 * 1.4426950408889634;
+  // Matern-1/2: h = exp(-r) / r = log2(e) exp2(-a) / a with a = r log2(e)
+  const double hfac = h->kernel_type == EGP_RBF ? 1.0
+                      : (h->kernel_type == EGP_MATERN32 ? 3.0 : (h->kernel_type == EGP_MATERN52 ? 5.0 / 3.0 : 1.4426950408889634));
   GradScale sc;
   for (int k = 0; k <= EGP_D_MAX; ++k)
     sc.v[k] = k < P.d ? (float)((double)h->outputscale * hfac / ((double)h->lengthscales[k] * c2)) : 0.f;

@@ -18,11 +18,26 @@ __device__ __forceinline__ float transform(float acc) {
   } else if constexpr (KIND == EGP_MATERN32) {
     float a = __builtin_amdgcn_sqrtf(__builtin_fabsf(acc));
     return __builtin_fmaf(a, kLn2, 1.0f) * __builtin_amdgcn_exp2f(-a);
+  } else if constexpr (KIND == EGP_MATERN12) {
+    return __builtin_amdgcn_exp2f(-__builtin_amdgcn_sqrtf(__builtin_fabsf(acc)));
   } else {
     float a = __builtin_amdgcn_sqrtf(__builtin_fabsf(acc));
     float poly = __builtin_fmaf(__builtin_fmaf(a, kLn2 * kLn2 / 3.0f, kLn2), a, 1.0f);
     return poly * __builtin_amdgcn_exp2f(-a);
   }
+}
+
+// Matern-1/2 has a cusp at r = 0: g = exp(-r) has slope -1 there, so the rounding error of the norm expansion
+// (|x~_i|^2 + |x~_j|^2 - 2 x~_i.x~_j ~ 1e-7 instead of 0 for a point against itself) becomes an error of ~3e-4 in
+// k(x, x), on every diagonal entry of a square product. On diagonal tiles of square products those entries are set
+// to their exact value 1 (lane (q, p), register r holds k(column 4q + r, row p)). The other families are flat at 0.
+template <typename V4>
+__device__ __forceinline__ void set_unit_diagonal(V4& k, int q, int p) {
+  const int r = p - 4 * q;
+  if (r == 0) k.x = 1.0f;
+  if (r == 1) k.y = 1.0f;
+  if (r == 2) k.z = 1.0f;
+  if (r == 3) k.w = 1.0f;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -172,6 +187,9 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel(const float* __restrict__ X
         k.y = transform<KIND>(acc.y);
         k.z = transform<KIND>(acc.z);
         k.w = transform<KIND>(acc.w);
+        if constexpr (KIND == EGP_MATERN12) {
+          if (XpRow == Xp && row_tile0 + it == (int64_t)st * JT + jt) set_unit_diagonal(k, q, p);
+        }
         if constexpr (SPLIT) {
           // high parts by truncation (taken straight from the upper halves), low parts = exact remainders
           const unsigned u0 = __float_as_uint(k.x), u1 = __float_as_uint(k.y);
@@ -322,6 +340,7 @@ int launch_kind(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, in
   switch (P.kernel_type) {
     case EGP_RBF: return launch_cols<KS, EGP_RBF, SPLIT>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
     case EGP_MATERN32: return launch_cols<KS, EGP_MATERN32, SPLIT>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case EGP_MATERN12: return launch_cols<KS, EGP_MATERN12, SPLIT>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
     default: return launch_cols<KS, EGP_MATERN52, SPLIT>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
   }
 }

@@ -207,6 +207,9 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
           kk.y = transform<KIND>(acc.y);
           kk.z = transform<KIND>(acc.z);
           kk.w = transform<KIND>(acc.w);
+          if constexpr (KIND == EGP_MATERN12) {      // exact k(x, x) on the diagonal (see kmm_kernel.h)
+            if (row_tile0 + it == (int64_t)st * JT + jt) set_unit_diagonal(kk, q, p);
+          }
           o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.x, v.x, o[it], 0, 0, 0);
           o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.y, v.y, o[it], 0, 0, 0);
           o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.z, v.z, o[it], 0, 0, 0);
@@ -367,6 +370,7 @@ int launch_sym_kind(const Prepared& P, const Plan& pl, int extra, const f4* Vp, 
   switch (P.kernel_type) {
     case EGP_RBF: return launch_sym_shape<KS, EGP_RBF>(P, pl, extra, Vp, Ep, Part, cm, stream);
     case EGP_MATERN32: return launch_sym_shape<KS, EGP_MATERN32>(P, pl, extra, Vp, Ep, Part, cm, stream);
+    case EGP_MATERN12: return launch_sym_shape<KS, EGP_MATERN12>(P, pl, extra, Vp, Ep, Part, cm, stream);
     default: return launch_sym_shape<KS, EGP_MATERN52>(P, pl, extra, Vp, Ep, Part, cm, stream);
   }
 }

@@ -184,6 +184,9 @@ __global__ __launch_bounds__(256) void kmm_kernel_wide(const float* __restrict__
         k.y = transform<KIND>(acc[it].y);
         k.z = transform<KIND>(acc[it].z);
         k.w = transform<KIND>(acc[it].w);
+        if constexpr (KIND == EGP_MATERN12) {      // exact k(x, x) on the diagonal of a square product (see kmm_kernel.h)
+          if (XpRow == Xp && row_tile0 + it == (int64_t)st * jt_stage + jt) set_unit_diagonal(k, q, p);
+        }
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
           o[it][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(k.x, v[nb].x, o[it][nb], 0, 0, 0);
@@ -276,6 +279,7 @@ int launch_wide_kind(const Prepared& P, const Prepared& Q, const kmm_detail::Pla
   switch (P.kernel_type) {
     case EGP_RBF: return launch_wide_cols<RW, EGP_RBF>(P, Q, pl, sh, nb, extra, Vp, Ep, Part, cm, stream);
     case EGP_MATERN32: return launch_wide_cols<RW, EGP_MATERN32>(P, Q, pl, sh, nb, extra, Vp, Ep, Part, cm, stream);
+    case EGP_MATERN12: return launch_wide_cols<RW, EGP_MATERN12>(P, Q, pl, sh, nb, extra, Vp, Ep, Part, cm, stream);
     default: return launch_wide_cols<RW, EGP_MATERN52>(P, Q, pl, sh, nb, extra, Vp, Ep, Part, cm, stream);
   }
 }

@@ -28,6 +28,7 @@ __device__ __forceinline__ float transform_rt(int kind, float acc) {
   const float a = __builtin_amdgcn_sqrtf(__builtin_fabsf(acc));
   const float e = __builtin_amdgcn_exp2f(-a);
   if (kind == EGP_MATERN32) return __builtin_fmaf(a, kLn2, 1.0f) * e;
+  if (kind == EGP_MATERN12) return e;
   return __builtin_fmaf(__builtin_fmaf(a, kLn2 * kLn2 / 3.0f, kLn2), a, 1.0f) * e;
 }
 

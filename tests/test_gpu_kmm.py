@@ -46,7 +46,7 @@ def test_kmm_c1_full(egp):
         assert _rel(got[:, c], ref[:, c]) <= KMM_TOL
 
 
-@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52])
+@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52, orc.MATERN12])
 @pytest.mark.parametrize("n,d,t", [(1, 1, 1), (15, 3, 2), (16, 4, 16), (17, 7, 17), (257, 11, 16), (1000, 8, 5),
                                    (2049, 18, 17), (3001, 25, 16), (777, 31, 33), (1300, 12, 32),
                                    (600, 2, 40), (513, 5, 70)])
@@ -120,7 +120,7 @@ def _set_mode(egp, mode):
 
 
 @pytest.mark.parametrize("mode", [1, 2])
-@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52])
+@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52, orc.MATERN12])
 @pytest.mark.parametrize("n,d,t", [(257, 11, 16), (2049, 18, 17), (3001, 25, 16), (777, 31, 33), (600, 2, 40),
                                    (1, 1, 1), (1000, 15, 5), (513, 16, 17)])
 def test_kmm_split_bf16_mode(egp, mode, kind, n, d, t):
@@ -156,7 +156,7 @@ def test_kmm_split_bf16_c2_recipe_rows(egp, mode):
     assert err <= KMM_TOL
 
 
-@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52])
+@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52, orc.MATERN12])
 @pytest.mark.parametrize("n,d,t", [(32768, 11, 16), (33000, 3, 16), (40000, 14, 48), (65536, 8, 16), (33281, 11, 17),
                                    (33000, 18, 17), (34000, 25, 16), (32768, 31, 17), (40000, 2, 33), (33000, 8, 1)])
 def test_kmm_symmetric_mode_rows(egp, kind, n, d, t):

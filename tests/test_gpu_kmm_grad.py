@@ -28,7 +28,7 @@ def _run(egp, X, V, ls, s, noise, kind):
     return out.cpu().numpy().astype(np.float64)
 
 
-@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52])
+@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52, orc.MATERN12])
 @pytest.mark.parametrize("n,d,t", [(1, 1, 1), (33, 3, 2), (500, 8, 16), (1030, 11, 17), (700, 25, 16),
                                    (300, 14, 5), (257, 27, 33), (2100, 31, 4)])
 def test_kmm_grad_shapes(egp, kind, n, d, t):
@@ -61,7 +61,7 @@ def test_kmm_grad_c3_recipe_rows(egp):
         assert np.linalg.norm(got[k][rows] - ref[k]) / np.linalg.norm(ref[k]) <= GRAD_TOL, k
 
 
-@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52])
+@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52, orc.MATERN12])
 @pytest.mark.parametrize("n,d,t", [(1, 1, 1), (50, 2, 3), (700, 3, 17), (1500, 11, 17), (900, 18, 16), (400, 25, 5),
                                    (300, 31, 33)])
 def test_bilinear_forms_match_oracle(egp, kind, n, d, t):

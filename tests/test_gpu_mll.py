@@ -23,7 +23,7 @@ def _cuda(a):
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
 
 
-@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52])
+@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52, orc.MATERN12])
 @pytest.mark.parametrize("rank", [0, 12])
 def test_mll_matches_oracle_with_same_probes(egp, kind, rank):
     """Same Rademacher draws on both sides: the two stochastic estimates must agree up to fp32 effects,
@@ -54,10 +54,13 @@ def test_mll_matches_oracle_with_same_probes(egp, kind, rank):
     scale = np.abs(ref["grad"]) + 0.02 * np.abs(ref["grad"]).max()
     assert np.all(np.abs(got["grad"] - ref["grad"]) <= 2e-2 * scale), (got["grad"], ref["grad"])
     # and the exact values (dense Cholesky), within a generous Monte-Carlo band
+    # (Matern-1/2 decays slowest in the spectrum, so more eigenvalues sit away from the noise level and the 16-probe
+    # log-determinant estimate scatters about twice as much: band doubled)
     exact = orc.mll(X, y, h)
-    assert abs(got["mll"] - exact) <= 0.02 * abs(exact) + 2.0
+    band = 2.0 if kind == orc.MATERN12 else 1.0
+    assert abs(got["mll"] - exact) <= band * (0.02 * abs(exact) + 2.0)
     gexact = orc.mll_grad(X, y, h)
-    assert np.all(np.abs(got["grad"] - gexact) <= 0.25 * np.abs(gexact) + 0.1 * np.abs(gexact).max())
+    assert np.all(np.abs(got["grad"] - gexact) <= band * (0.25 * np.abs(gexact) + 0.1 * np.abs(gexact).max()))
 
 
 def test_train_adam_tracks_the_oracle_loop(egp):

@@ -28,7 +28,7 @@ def _rel(a, b):
     return np.linalg.norm(a - b) / np.linalg.norm(b)
 
 
-@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52])
+@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52, orc.MATERN12])
 @pytest.mark.parametrize("nq,n,d,t", [(1, 1, 1, 1), (7, 300, 3, 1), (1000, 777, 8, 16), (33, 2500, 11, 17),
                                       (600, 900, 18, 40), (2100, 50, 25, 33)])
 def test_kmm_cross_matches_oracle(egp, kind, nq, n, d, t):

@@ -23,7 +23,7 @@ def _cuda(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52])
+@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52, orc.MATERN12])
 @pytest.mark.parametrize("n,d,rank", [(64, 2, 8), (300, 3, 20), (1000, 2, 12)])
 def test_pivots_bit_exact_and_factor(egp, kind, n, d, rank):
     """Pivot order must equal the oracle's exactly on well-separated tiny inputs (no near-ties)."""

@@ -39,7 +39,7 @@ def _inputs(seed, n, d, t):
     return X, V, ls
 
 
-@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52])
+@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52, orc.MATERN12])
 @pytest.mark.parametrize("n,d,t", [(300, 32, 16), (1000, 77, 17), (2049, 90, 16), (700, 160, 33), (1200, 385, 16),
                                    (513, 399, 5), (40, 35, 1), (3000, 164, 32),
                                    (2047, 159, 18), (1500, 135, 33), (1025, 140, 16)])
@@ -89,7 +89,7 @@ def test_materialised_gradient_rejects_wide(egp):
 GRAD_TOL = 1e-4
 
 
-@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52])
+@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52, orc.MATERN12])
 @pytest.mark.parametrize("n,d,t", [(600, 32, 17), (1000, 77, 17), (900, 90, 5), (500, 164, 16), (400, 200, 33),
                                    (300, 385, 17), (200, 399, 3), (40, 47, 1)])
 def test_bilinear_forms_wide(egp, kind, n, d, t):

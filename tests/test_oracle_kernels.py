@@ -8,7 +8,7 @@ import pytest
 import oracle as orc
 from workloads import make_workload, well_separated_points
 
-KINDS = [orc.RBF, orc.MATERN32, orc.MATERN52]
+KINDS = [orc.RBF, orc.MATERN32, orc.MATERN52, orc.MATERN12]
 
 
 def _scalar_kernel(x, z, ls, s, kind):
@@ -21,6 +21,8 @@ def _scalar_kernel(x, z, ls, s, kind):
         return s * math.exp(-r2 / 2.0)
     if kind == orc.MATERN32:
         return s * (1.0 + math.sqrt(3.0) * r) * math.exp(-math.sqrt(3.0) * r)
+    if kind == orc.MATERN12:
+        return s * math.exp(-r)
     return s * (1.0 + math.sqrt(5.0) * r + 5.0 * r2 / 3.0) * math.exp(-math.sqrt(5.0) * r)
 
 
@@ -155,3 +157,18 @@ def test_mll_gradient_vs_finite_differences():
     h = orc.Hyper(orc.RBF, theta[:d], theta[d], theta[d + 1])
     ref = multivariate_normal(mean=np.zeros(n), cov=orc.khat(X, h)).logpdf(y)
     assert abs(orc.mll(X, y, h) - ref) < 1e-8
+
+
+def test_matern12_is_the_ornstein_uhlenbeck_kernel():
+    """In one dimension exp(-|x - x'| / l) is the covariance of a Markov process: the inverse of the kernel matrix
+    of sorted points is tridiagonal, with the textbook closed form (rho_i = exp(-gap_i / l))."""
+    rng = np.random.default_rng(12)
+    x = np.sort(rng.uniform(0, 5, 12))
+    ell, s = 0.7, 1.9
+    K = orc.kernel_matrix(x[:, None], x[:, None], orc.Hyper(orc.MATERN12, [ell], s, 0.0))
+    Kinv = np.linalg.inv(K)
+    off = np.abs(np.triu(Kinv, 2)).max()
+    assert off <= 1e-9 * np.abs(Kinv).max()
+    rho = np.exp(-np.diff(x) / ell)
+    expect_off = -rho / (1.0 - rho ** 2) / s
+    assert np.allclose(np.diag(Kinv, 1), expect_off, rtol=1e-8)

@@ -21,7 +21,7 @@ def test_pivoted_cholesky_full_rank_reproduces_K():
     assert np.linalg.norm(L @ L.T - K) / np.linalg.norm(K) <= 1e-10
 
 
-@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52])
+@pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52, orc.MATERN12])
 def test_pivoted_cholesky_invariants_and_greedy_pivots(kind):
     X, h, K, _ = _setup(n=80, kind=kind)
     k = 12

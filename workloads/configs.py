@@ -5,7 +5,7 @@ from dataclasses import dataclass, field
 
 import numpy as np
 
-RBF, MATERN32, MATERN52 = 0, 1, 2
+RBF, MATERN32, MATERN52, MATERN12 = 0, 1, 2, 3
 CONFIG_NAMES = ("C1", "C2", "C3", "C4", "C5")
 
 
