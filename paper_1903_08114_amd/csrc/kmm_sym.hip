@@ -22,8 +22,9 @@ namespace kmm_detail {
 
 namespace {
 
-// column tiles per stage: 8 up to 4 distance k-steps, 4 beyond (keeps the workgroup's LDS under 80 KB: two per CU)
-constexpr int sym_jt(int ks) { return ks <= 4 ? 8 : 4; }
+// column tiles per stage: 8 up to 4 distance k-steps without a 17th column, else 4 (keeps the workgroup's LDS under
+// 80 KB: two per CU)
+constexpr int sym_jt(int ks, int extra) { return (ks <= 4 && !extra) ? 8 : 4; }
 constexpr int kPatch = 280;      // floats of one transposition patch: 70 slots of 16 bytes
 
 // Sum over the 16 lanes of a DPP row (all lanes receive it): two quad permutations, half-row mirror, row mirror.
@@ -40,7 +41,7 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
                                                          const f4* __restrict__ Vp, const float* __restrict__ Ep,
                                                          float* __restrict__ Part, int64_t npad, int d, int nblk,
                                                          int stages_per_split, int cm) {
-  constexpr int JT = sym_jt(KS);
+  constexpr int JT = sym_jt(KS, EXTRA);
   constexpr int TS = 16 + EXTRA;
   constexpr int SB = 64 * R / (16 * JT);      // stages per block of 64 R points
   constexpr int XF4 = JT * KS * 16, VF4 = JT * 64, EF4 = JT * 4;
@@ -51,7 +52,9 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
   __shared__ __attribute__((aligned(16))) float Ts[4][2][kPatch];      // per wave: two transposition patches
   __shared__ f4 Es[2][EXTRA ? EF4 : 1];
   __shared__ f4 CJ[4][JT][64];      // column-side sums of one stage, per wave: [wave][tile][lane], register r = component
-  __shared__ float CJE[4][JT][16];  // the same for the 17th column: [wave][tile][column point]
+  // the same for the 17th column: lane (q, p), component r holds the sum over the wave's rows with point index p of
+  // k(column 4q + r, row) e[row]; the sum over p is left to the flush
+  __shared__ f4 CJE[EXTRA ? 4 : 1][EXTRA ? JT : 1][EXTRA ? 64 : 1];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -167,14 +170,26 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
       }
     }
     if (EXTRA) {
-      // every thread takes part (a divergent tail here cost the whole kernel ~60 registers): thread = (pair of
-      // waves, tile, column point), for JT = 4 the upper half repeats with a zero addend
-      const int e = tid & (JT * 16 - 1), hw = (tid / (JT * 16)) & 1;
-      const int jt = e >> 4, jj = e & 15;
-      float v = CJE[2 * hw][jt][jj] + CJE[2 * hw + 1][jt][jj];
-      if (JT * 32 < 256 && tid >= JT * 32) v = 0.f;
-      const int64_t j = ((int64_t)st * JT + jt) * 16 + jj;
-      unsafeAtomicAdd(cm ? slab + (int64_t)16 * npad + j : slab + j * TS + 16, v);
+      // JT = 4: thread (wave, lane) takes tile `wave`; sum over the four waves, then over the 16 lanes of the DPP row
+      // (point index p). Every lane then holds the four sums of its row q; lane p adds component p & 3 (p >= 4: a
+      // zero, elsewhere), so that no thread is masked off (a divergent tail here cost the whole kernel ~60 registers).
+      static_assert(!EXTRA || JT == 4, "one tile per wave in the flush of the 17th column");
+      f4 v = CJE[0][wave][lane];
+      v += CJE[1][wave][lane];
+      v += CJE[2][wave][lane];
+      v += CJE[3][wave][lane];
+      v.x = row_sum16(v.x);
+      v.y = row_sum16(v.y);
+      v.z = row_sum16(v.z);
+      v.w = row_sum16(v.w);
+      const int r = p & 3;
+      float add = r == 0 ? v.x : (r == 1 ? v.y : (r == 2 ? v.z : v.w));
+      if (p >= 4) add = 0.f;
+      // the zero addends go to distinct elements of the same rows (columns 1..3): lanes of one instruction that
+      // hit one address are serialised (measured: 685 ms against 450 ms per launch)
+      const int col = p < 4 ? 16 : (p >> 2);
+      const int64_t j = ((int64_t)st * JT + wave) * 16 + 4 * q + r;
+      unsafeAtomicAdd(cm ? slab + (int64_t)col * npad + j : slab + j * TS + col, add);
     }
   };
 
@@ -296,13 +311,7 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
         }
         CJ[wave][jt][lane] = oj;
         if (EXTRA) {
-          ej.x = row_sum16(ej.x);
-          ej.y = row_sum16(ej.y);
-          ej.z = row_sum16(ej.z);
-          ej.w = row_sum16(ej.w);
-          // every lane of the row holds the four sums: all sixteen store them (a predicated store in this loop
-          // cost ~60 registers)
-          *reinterpret_cast<f4*>(&CJE[wave][jt][4 * q]) = ej;
+          CJE[wave][jt][lane] = ej;
           e = en;
         }
 #pragma unroll
@@ -385,13 +394,13 @@ int sym_row_tiles(int64_t npad_rows, int64_t npad_cols, int ks, int nb, int extr
 }
 
 // stages_total holds the length of one workgroup's sweep; row_blocks the block count
-Plan make_plan_sym(int64_t npad, int r, int ks) {
+Plan make_plan_sym(int64_t npad, int r, int ks, int extra) {
   Plan pl;
   pl.big = true;
   pl.sym = true;
   pl.extra_slabs = 1;
   const int nblk = (int)(npad / (64 * r));
-  const int sb = 64 * r / (16 * sym_jt(ks));
+  const int sb = 64 * r / (16 * sym_jt(ks, extra));
   pl.row_blocks = nblk;
   pl.stages_total = (nblk / 2 + 1) * sb;
   int want = 1024 / nblk;
