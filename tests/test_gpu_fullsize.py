@@ -42,16 +42,22 @@ def test_c4_kmm_full_size_sampled_rows(egp):
     h = orc.Hyper(w.kernel_type, w.lengthscales, w.outputscale, w.noise)
     X = _cuda(w.X)
     rows = _rows(w.n, 48, 1)
+    L = egp.lib()
     for cols in (slice(1, 17), slice(0, 17)):
         V = np.ascontiguousarray(w.V[:, cols])
-        out = egp.kmm(X, _cuda(V), w.lengthscales, w.outputscale, w.noise, w.kernel_type)
-        torch.cuda.synchronize()
-        got = out[torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.float64)
         ref = orc.kmm_rows(w.X, V, h, rows)
-        err = _rel(got, ref)
-        print("C4 t=%d sampled-row rel err %.3e" % (V.shape[1], err))
-        assert err <= KMM_TOL
-        assert torch.isfinite(out).all()
+        for mode in (0, 3):      # the one-sided default and the symmetric mode bench.py's headline leg runs in
+            try:
+                L.egp_set_kmm_mode(mode)
+                out = egp.kmm(X, _cuda(V), w.lengthscales, w.outputscale, w.noise, w.kernel_type)
+                torch.cuda.synchronize()
+            finally:
+                L.egp_set_kmm_mode(0)
+            got = out[torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.float64)
+            err = _rel(got, ref)
+            print("C4 t=%d mode %d sampled-row rel err %.3e" % (V.shape[1], mode, err))
+            assert err <= KMM_TOL
+            assert torch.isfinite(out).all()
 
 
 def test_c5_kmm_full_size_sampled_rows(egp):
@@ -74,8 +80,15 @@ def test_c3_kmm_and_grad_full_size_sampled_rows(egp):
     X, V = _cuda(w.X), _cuda(w.V)
     rows = _rows(w.n, 24, 3)
     idx = torch.from_numpy(rows).cuda()
-    out = egp.kmm(X, V, w.lengthscales, w.outputscale, w.noise, w.kernel_type)
-    assert _rel(out[idx].cpu().numpy().astype(np.float64), orc.kmm_rows(w.X, w.V, h, rows)) <= KMM_TOL
+    ref_rows = orc.kmm_rows(w.X, w.V, h, rows)
+    for mode in (0, 3):
+        try:
+            egp.lib().egp_set_kmm_mode(mode)
+            out = egp.kmm(X, V, w.lengthscales, w.outputscale, w.noise, w.kernel_type)
+            torch.cuda.synchronize()
+        finally:
+            egp.lib().egp_set_kmm_mode(0)
+        assert _rel(out[idx].cpu().numpy().astype(np.float64), ref_rows) <= KMM_TOL
     g = egp.kmm_grad(X, V, w.lengthscales, w.outputscale, w.noise, w.kernel_type)
     torch.cuda.synchronize()
     ref = orc.kmm_grad_rows(w.X, w.V, h, rows)
