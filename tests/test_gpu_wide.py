@@ -182,3 +182,45 @@ def test_solver_and_prediction_wide(egp, d):
     vg = var.cpu().numpy().astype(np.float64)
     assert np.abs(vg - vlan).max() <= 2e-3
     assert (vg >= vref - 2e-3).all()
+
+
+@pytest.mark.parametrize("n,d,t,kind", [(32768, 40, 16, orc.RBF), (33000, 90, 16, orc.MATERN32), (34000, 164, 16, orc.RBF),
+                                         (33000, 300, 32, orc.MATERN52), (33281, 77, 16, orc.MATERN12)])
+def test_kmm_wide_symmetric_mode_rows(egp, n, d, t, kind):
+    """The symmetric fp32 mode beyond d = 31 (16-column groups): rows computed exactly by the oracle, both row-tile
+    shapes, every stage size, even and odd block counts; and every row against the one-sided kernel."""
+    X, V, ls = _inputs(31 * d + t + kind, n, d, t)
+    rng = np.random.default_rng(d)
+    rows = rng.choice(n, 96, replace=False)
+    edges = [0, 15, 16, 63, 64, 127, 128, n // 2 - 1, n // 2, n // 2 + 64, n - 129, n - 128, n - 1]
+    rows[:len(edges)] = edges
+    rows = np.unique(rows)
+    ref = orc.kmm_rows(X, V, orc.Hyper(kind, ls, 1.1, 0.3), rows)
+    Xd, Vd = _cuda(X), _cuda(V)
+    base = egp.kmm(Xd, Vd, ls, 1.1, 0.3, kind).cpu().numpy().astype(np.float64)
+    L = egp.lib()
+    try:
+        L.egp_set_kmm_mode(3)
+        got = egp.kmm(Xd, Vd, ls, 1.1, 0.3, kind).cpu().numpy().astype(np.float64)
+    finally:
+        L.egp_set_kmm_mode(0)
+    assert np.isfinite(got).all()
+    err = _rel(got[rows], ref)
+    print(f"wide symmetric n={n} d={d} t={t} kind={kind}: rel err {err:.2e}; vs one-sided {_rel(got, base):.2e}")
+    assert err <= KMM_TOL
+    assert _rel(got, base) <= 2e-5
+
+
+def test_kmm_wide_symmetric_mode_falls_back(egp):
+    """d = 385 does not fit the symmetric wide kernel's LDS budget; 17 columns are not built for it: one-sided bits."""
+    for d, t in ((385, 16), (90, 17)):
+        X, V, ls = _inputs(d + t, 33000, d, t)
+        Xd, Vd = _cuda(X), _cuda(V)
+        base = egp.kmm(Xd, Vd, ls, 1.0, 0.1, orc.RBF).cpu().numpy()
+        L = egp.lib()
+        try:
+            L.egp_set_kmm_mode(3)
+            got = egp.kmm(Xd, Vd, ls, 1.0, 0.1, orc.RBF).cpu().numpy()
+        finally:
+            L.egp_set_kmm_mode(0)
+        assert np.array_equal(got, base)
