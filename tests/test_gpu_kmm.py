@@ -187,11 +187,11 @@ def test_kmm_symmetric_mode_rows(egp, kind, n, d, t):
 
 
 def test_kmm_symmetric_mode_falls_back_on_other_shapes(egp):
-    """Shapes the symmetric kernel does not cover (small n, d > 31) give the one-sided kernel's bits."""
-    for n, d in ((3000, 11), (33000, 40)):
+    """Shapes the symmetric kernels do not cover (small n, a group of 32 columns) give the one-sided kernel's bits."""
+    for n, d, t in ((3000, 11, 16), (33000, 11, 32)):
         rng = np.random.default_rng(n + d)
         X = rng.uniform(-1, 1, (n, d)).astype(np.float32)
-        V = rng.standard_normal((n, 16)).astype(np.float32)
+        V = rng.standard_normal((n, t)).astype(np.float32)
         ls = np.full(d, 0.8, np.float32)
         base = _run(egp, X, V, ls, 1.0, 0.1, orc.RBF)
         try:

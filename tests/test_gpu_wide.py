@@ -224,3 +224,27 @@ def test_kmm_wide_symmetric_mode_falls_back(egp):
         finally:
             L.egp_set_kmm_mode(0)
         assert np.array_equal(got, base)
+
+
+def test_mbcg_wide_in_symmetric_mode(egp):
+    """Solver at d = 90 with 16 right-hand sides: the symmetric wide kernel with the column-major state arrays gives
+    the one-sided kernel's iterates up to summation order."""
+    n, d, t = 33000, 90, 16
+    X, B, ls = _inputs(901, n, d, t)
+    s, noise, kind = 1.0, 0.5, orc.RBF
+    Xd, Bd = _cuda(X), _cuda(B)
+    base = egp.mbcg(Xd, Bd, ls, s, noise, kind, max_iter=12, tol=0.0)
+    L = egp.lib()
+    try:
+        L.egp_set_kmm_mode(3)
+        res = egp.mbcg(Xd, Bd, ls, s, noise, kind, max_iter=12, tol=0.0)
+    finally:
+        L.egp_set_kmm_mode(0)
+    assert np.allclose(res["alphas"][:3], base["alphas"][:3], rtol=1e-4)
+    U = res["U"].cpu().numpy().astype(np.float64)
+    Ub = base["U"].cpu().numpy().astype(np.float64)
+    assert _rel(U, Ub) <= 1e-3
+    rows = np.random.default_rng(3).choice(n, 64, replace=False)
+    KU = orc.kmm_rows(X, U, orc.Hyper(kind, ls, s, noise), rows)
+    true_res = np.linalg.norm(KU - B[rows], axis=0) / np.linalg.norm(B[rows], axis=0)
+    assert true_res.max() <= max(3.0 * float(res["rel_resid"].max()), 1e-3)
