@@ -364,6 +364,15 @@ def main():
                 fn()
             torch.cuda.synchronize()
             leg[name + "_s"] = (time.perf_counter() - t0) / 3
+        lib.egp_set_kmm_mode(3)
+        egp.kmm(X3, V3, w3.lengthscales, w3.outputscale, w3.noise, w3.kernel_type, out=o3, ws=wsk)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(3):
+            egp.kmm(X3, V3, w3.lengthscales, w3.outputscale, w3.noise, w3.kernel_type, out=o3, ws=wsk)
+        torch.cuda.synchronize()
+        leg["kmm_s_symmetric_mode"] = (time.perf_counter() - t0) / 3
+        lib.egp_set_kmm_mode(0)
         fk = flops_per_entry(w3.d, w3.t, w3.kernel_type)
         fg = fk - 2 * w3.t + w3.d * (2 * w3.t + 3)
         leg["kmm_frac_fp32_peak"] = fk * w3.n ** 2 / leg["kmm_s"] / 1e12 / FP32_PEAK_TFLOPS
@@ -388,6 +397,15 @@ def main():
             egp.kmm(Xw, V16, lsw, 1.0, 0.1, 0, out=ow)
         torch.cuda.synchronize()
         kmm_s = (time.perf_counter() - t0) / 3
+        lib.egp_set_kmm_mode(3)
+        egp.kmm(Xw, V16, lsw, 1.0, 0.1, 0, out=ow)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(3):
+            egp.kmm(Xw, V16, lsw, 1.0, 0.1, 0, out=ow)
+        torch.cuda.synchronize()
+        kmm_sym_s = (time.perf_counter() - t0) / 3
+        lib.egp_set_kmm_mode(0)
         egp.kmm_grad_bilinear(Xw, Aw, Bw, lsw, 1.0, 0.1, 0)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -399,6 +417,7 @@ def main():
             "workload": f"n={nw_}, d={dw_}, uniform points, RBF-ARD; multiply at t=16, gradient forms at t={tw_}",
             "kmm_s": kmm_s, "kmm_entries_per_s": nw_ ** 2 / kmm_s,
             "kmm_frac_fp32_peak": fk * nw_ ** 2 / kmm_s / 1e12 / FP32_PEAK_TFLOPS,
+            "kmm_s_symmetric_mode": kmm_sym_s, "kmm_entries_per_s_symmetric_mode": nw_ ** 2 / kmm_sym_s,
             "grad_bilinear_s": bil_s,
         }
         del Xw, Aw, Bw, V16, ow
