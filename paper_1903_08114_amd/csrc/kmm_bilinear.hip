@@ -11,6 +11,12 @@
 // acc_k += w (x~_ik - x~_jk)^2. The accumulators are per lane (d + 1 registers per wave, not per row tile);
 // they are reduced across the wave, the block and the grid at the end, the last step in fp64.
 // Against materialising (dK/dl_k) V (4 d MFMA steps per tile) this needs TS MFMA steps per tile.
+//
+// dK/dtheta is symmetric, so only S + S^T matters: sum_ij S_ij D_ij = sum over tile pairs {I,J} of
+// (S_IJ + S_JI^T) . D_IJ. A workgroup sweeps the column blocks (256 points) from its own to the half-way one,
+// cyclically, and forms S_IJ + S_JI^T = Aw_I B_J^T + B_I Aw_J^T with 2 TS MFMA steps per tile; the own block and the
+// half-way block (which both partners visit) carry the weight 1/2. Half of all tiles are never formed: the distance
+// steps, the transform and above all the per-lengthscale VALU work are halved.
 
 #include <math.h>
 
@@ -26,9 +32,10 @@ namespace {
 using bilinear_detail::f4;
 using bilinear_detail::hg;
 
-// row tiles per wave: fewer when the per-tile feature registers (4 KS of them) grow
-constexpr int br_for(int ks) { return ks <= 3 ? 4 : (ks <= 5 ? 2 : 1); }
-constexpr int BJT = 8;     // column tiles per LDS stage
+// row tiles per wave: fewer when the per-tile registers (4 KS features, 2 TS operands of S + S^T) grow
+constexpr int br_for(int ks, int ts) { return ks <= 5 ? ((ks == 3 && ts <= 5) ? 4 : 2) : 1; }
+constexpr int BJT = 4;     // column tiles per LDS stage
+constexpr int kBlk = 256;  // points per block of the symmetric sweep (a multiple of every workgroup's row count)
 constexpr int kDMaxB = 31; // lengthscales handled by this kernel (d > 31: kmm_bilinear_wide.hip)
 
 // M (n x t row-major) -> packed [tile][ts][64]: lane (q,p) of step s holds w[4s+q] * M[16 tile + p][4s + q]
@@ -53,14 +60,16 @@ template <int KS, int TS, int KIND>
 __global__ __launch_bounds__(256, 2) void bilinear_kernel(const float* __restrict__ Xp, const float* __restrict__ nrm,
                                                           const float* __restrict__ Ap, const float* __restrict__ Bp,
                                                           float* __restrict__ part, int64_t npad, int d,
-                                                          int stages_per_split, int stages_total) {
-  constexpr int BR = br_for(KS);
+                                                          int stages_per_split) {
+  constexpr int BR = br_for(KS, TS);
+  constexpr int SB = kBlk / (16 * BJT);      // stages per block
   constexpr int XF4 = BJT * KS * 16;
   constexpr int BF4 = BJT * TS * 16;
   constexpr int NX = (XF4 + 255) / 256;
   constexpr int NB = (BF4 + 255) / 256;
   __shared__ f4 Xs[2][XF4];
-  __shared__ f4 Bs[2][BF4];
+  __shared__ f4 Bs[2][BF4];      // B of the column tiles
+  __shared__ f4 As[2][BF4];      // A (weighted) of the column tiles
   __shared__ float red[4][kDMaxB + 1];
 
   const int tid = threadIdx.x;
@@ -68,7 +77,7 @@ __global__ __launch_bounds__(256, 2) void bilinear_kernel(const float* __restric
   const int q = lane >> 4, p = lane & 15;
   const int64_t row_tile0 = ((int64_t)blockIdx.x * 4 + wave) * BR;
 
-  float b[BR][KS], a_op[BR][TS], xi[BR][KS * 4];
+  float b[BR][KS], a_op[BR][TS], b_op[BR][TS], xi[BR][KS * 4];
   f4 cq[BR];
   float acc_k[KS * 4];     // one accumulator per feature slot; slots >= d stay unused
   float acc_s = 0.f;
@@ -85,42 +94,63 @@ __global__ __launch_bounds__(256, 2) void bilinear_kernel(const float* __restric
       b[it][s] = v;
     }
 #pragma unroll
-    for (int s = 0; s < TS; ++s) a_op[it][s] = Ap[((row_tile0 + it) * TS + s) * 64 + lane];
+    for (int s = 0; s < TS; ++s) {
+      a_op[it][s] = Ap[((row_tile0 + it) * TS + s) * 64 + lane];
+      b_op[it][s] = Bp[((row_tile0 + it) * TS + s) * 64 + lane];
+    }
     const float ni = nrm[(row_tile0 + it) * 16 + p];
     cq[it] = (f4){ni, ni, ni, ni};
 #pragma unroll
     for (int k = 0; k < KS * 4; ++k) xi[it][k] = tile[(k >> 2) * 64 + (k & 3) * 16 + p];
   }
 
+  // this workgroup's sweep: blocks own, own + 1, ..., own + half (cyclic), SB stages each
+  const int nblk = (int)(npad / kBlk);      // even: npad is a multiple of 512
+  const int half = nblk >> 1;
+  const int own = (int)(((int64_t)blockIdx.x * 64 * BR) / kBlk);
+  const int stages_all = (half + 1) * SB;
+  const int s_total = nblk * SB;
   const int st_begin = blockIdx.y * stages_per_split;
   int st_end = st_begin + stages_per_split;
-  if (st_end > stages_total) st_end = stages_total;
+  if (st_end > stages_all) st_end = stages_all;
+  auto abs_stage = [&](int k) {
+    int st = own * SB + k;
+    return st >= s_total ? st - s_total : st;
+  };
   const f4* Xg = reinterpret_cast<const f4*>(Xp);
   const f4* Bg = reinterpret_cast<const f4*>(Bp);
-  f4 px[NX], pb[NB];
-  auto fetch = [&](int st) {
+  const f4* Ag = reinterpret_cast<const f4*>(Ap);
+  f4 px[NX], pb[NB], pa[NB];
+  auto fetch = [&](int k) {
+    const int st = abs_stage(k);
     const int64_t xoff = (int64_t)st * XF4, boff = (int64_t)st * BF4;
 #pragma unroll
-    for (int k = 0; k < NX; ++k) {
-      const int idx = tid + k * 256;
-      if (XF4 % 256 == 0 || idx < XF4) px[k] = Xg[xoff + idx];
+    for (int i = 0; i < NX; ++i) {
+      const int idx = tid + i * 256;
+      if (XF4 % 256 == 0 || idx < XF4) px[i] = Xg[xoff + idx];
     }
 #pragma unroll
-    for (int k = 0; k < NB; ++k) {
-      const int idx = tid + k * 256;
-      if (BF4 % 256 == 0 || idx < BF4) pb[k] = Bg[boff + idx];
+    for (int i = 0; i < NB; ++i) {
+      const int idx = tid + i * 256;
+      if (BF4 % 256 == 0 || idx < BF4) {
+        pb[i] = Bg[boff + idx];
+        pa[i] = Ag[boff + idx];
+      }
     }
   };
   auto stash = [&](int buf) {
 #pragma unroll
-    for (int k = 0; k < NX; ++k) {
-      const int idx = tid + k * 256;
-      if (XF4 % 256 == 0 || idx < XF4) Xs[buf][idx] = px[k];
+    for (int i = 0; i < NX; ++i) {
+      const int idx = tid + i * 256;
+      if (XF4 % 256 == 0 || idx < XF4) Xs[buf][idx] = px[i];
     }
 #pragma unroll
-    for (int k = 0; k < NB; ++k) {
-      const int idx = tid + k * 256;
-      if (BF4 % 256 == 0 || idx < BF4) Bs[buf][idx] = pb[k];
+    for (int i = 0; i < NB; ++i) {
+      const int idx = tid + i * 256;
+      if (BF4 % 256 == 0 || idx < BF4) {
+        Bs[buf][idx] = pb[i];
+        As[buf][idx] = pa[i];
+      }
     }
   };
 
@@ -136,14 +166,21 @@ __global__ __launch_bounds__(256, 2) void bilinear_kernel(const float* __restric
     if (more) fetch(st + 1);
     const float* xs = reinterpret_cast<const float*>(Xs[buf]);
     const float* bs = reinterpret_cast<const float*>(Bs[buf]);
+    const float* as = reinterpret_cast<const float*>(As[buf]);
+    const int delta = st / SB;
+    const float wgt = (delta == 0 || delta == half) ? 0.5f : 1.0f;
     for (int jt = 0; jt < BJT; ++jt) {
       const float* xt = xs + jt * KS * 64;
       const float* bt = bs + jt * TS * 64;
-      float a[KS], bo[TS];
+      const float* at = as + jt * TS * 64;
+      float a[KS], bo[TS], ao[TS];
 #pragma unroll
       for (int s = 0; s < KS; ++s) a[s] = xt[s * 64 + lane];
 #pragma unroll
-      for (int s = 0; s < TS; ++s) bo[s] = bt[s * 64 + lane];
+      for (int s = 0; s < TS; ++s) {
+        bo[s] = bt[s * 64 + lane];
+        ao[s] = at[s * 64 + lane];
+      }
       f4 w[BR];
 #pragma unroll
       for (int it = 0; it < BR; ++it) {
@@ -153,6 +190,9 @@ __global__ __launch_bounds__(256, 2) void bilinear_kernel(const float* __restric
         f4 sv = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < TS; ++s) sv = __builtin_amdgcn_mfma_f32_16x16x4f32(bo[s], a_op[it][s], sv, 0, 0, 0);
+#pragma unroll
+        for (int s = 0; s < TS; ++s) sv = __builtin_amdgcn_mfma_f32_16x16x4f32(ao[s], b_op[it][s], sv, 0, 0, 0);
+        sv *= wgt;
         float g0, g1, g2, g3;
         const float h0 = hg<KIND>(acc.x, &g0), h1 = hg<KIND>(acc.y, &g1);
         const float h2 = hg<KIND>(acc.z, &g2), h3 = hg<KIND>(acc.w, &g3);
@@ -205,10 +245,11 @@ __global__ __launch_bounds__(256, 2) void bilinear_kernel(const float* __restric
 }
 
 struct BPlan { int row_blocks, splits, stages_per_split, stages_total; };
-BPlan bilinear_plan(int64_t npad, int ks) {
+BPlan bilinear_plan(int64_t npad, int ks, int ts) {
   BPlan pl;
-  pl.row_blocks = (int)(npad / (64 * br_for(ks)));
-  pl.stages_total = (int)(npad / (16 * BJT));
+  pl.row_blocks = (int)(npad / (64 * br_for(ks, ts)));
+  // one workgroup's sweep: its own block and the following npad / (2 kBlk) blocks, kBlk / (16 BJT) stages each
+  pl.stages_total = (int)(npad / kBlk / 2 + 1) * (kBlk / (16 * BJT));
   int want = 1024 / pl.row_blocks;
   if (want < 1) want = 1;
   if (want > pl.stages_total) want = pl.stages_total;
@@ -224,19 +265,19 @@ void launch_b(const Prepared& P, const BPlan& pl, const float* Ap, const float* 
   switch (P.kernel_type) {
     case EGP_RBF:
       hipLaunchKernelGGL((bilinear_kernel<KS, TS, EGP_RBF>), grid, block, 0, stream, P.Xp, P.nrm, Ap, Bp, part, P.npad,
-                         P.d, pl.stages_per_split, pl.stages_total);
+                         P.d, pl.stages_per_split);
       break;
     case EGP_MATERN32:
       hipLaunchKernelGGL((bilinear_kernel<KS, TS, EGP_MATERN32>), grid, block, 0, stream, P.Xp, P.nrm, Ap, Bp, part,
-                         P.npad, P.d, pl.stages_per_split, pl.stages_total);
+                         P.npad, P.d, pl.stages_per_split);
       break;
     case EGP_MATERN12:
       hipLaunchKernelGGL((bilinear_kernel<KS, TS, EGP_MATERN12>), grid, block, 0, stream, P.Xp, P.nrm, Ap, Bp, part,
-                         P.npad, P.d, pl.stages_per_split, pl.stages_total);
+                         P.npad, P.d, pl.stages_per_split);
       break;
     default:
       hipLaunchKernelGGL((bilinear_kernel<KS, TS, EGP_MATERN52>), grid, block, 0, stream, P.Xp, P.nrm, Ap, Bp, part,
-                         P.npad, P.d, pl.stages_per_split, pl.stages_total);
+                         P.npad, P.d, pl.stages_per_split);
   }
 }
 
@@ -265,7 +306,7 @@ size_t bilinear_core_ws_bytes(int64_t n, int d, int t) {
   if (ksteps_for(d) > 8) return bilinear_detail::bilinear_wide_ws_bytes(n, d, t);
   const int64_t npad = padded_points(n);
   const int ts = (t + 3) / 4;
-  const BPlan pl = bilinear_plan(npad, ksteps_for(d));
+  const BPlan pl = bilinear_plan(npad, ksteps_for(d), ts);
   size_t b = 2 * round_up((size_t)npad * ts * 4 * sizeof(float), 256);                                 // Ap, Bp
   b += round_up((size_t)pl.row_blocks * pl.splits * (kDMaxB + 1) * sizeof(float), 256);                // partials
   b += 256;                                                                                            // column weights
@@ -280,7 +321,7 @@ int bilinear_core(const Prepared& P, const egp_hyper_t* h, const float* A, const
   const int64_t npad = P.npad;
   const int ts = (t + 3) / 4;
   if (ts > 9) return fail(EGP_ERR_ARG, "bilinear forms support t <= 36 (got %d)", t);
-  const BPlan pl = bilinear_plan(npad, P.ks);
+  const BPlan pl = bilinear_plan(npad, P.ks, ts);
   char* w = static_cast<char*>(ws2);
   const size_t pbytes = round_up((size_t)npad * ts * 4 * sizeof(float), 256);
   float* Ap = reinterpret_cast<float*>(w);
