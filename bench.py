@@ -326,6 +326,15 @@ def main():
                 egp.kmm(Xs, Bs, *hyp, out=os_)
             torch.cuda.synchronize()
             kmm_s = (time.perf_counter() - t0) / 20
+            lib.egp_set_kmm_mode(3)      # symmetric mode (applies from n_pad = 32768: C2; C1 runs the one-sided kernel)
+            egp.kmm(Xs, Bs, *hyp, out=os_)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(20):
+                egp.kmm(Xs, Bs, *hyp, out=os_)
+            torch.cuda.synchronize()
+            kmm_sym_s = (time.perf_counter() - t0) / 20
+            lib.egp_set_kmm_mode(0)
             Ps = egp.piv_chol_precond(Xs, *hyp, ws_.rank)
             egp.mbcg(Xs, Bs, *hyp, precond=Ps, max_iter=2, tol=0.0)
             torch.cuda.synchronize()
@@ -338,6 +347,7 @@ def main():
                 "workload": f"{name}: n={ws_.n}, d={ws_.d}, t={ws_.t}, rank {ws_.rank}, tol {ws_.tol}",
                 "kmm_s": kmm_s, "kmm_entries_per_s": ws_.n ** 2 / kmm_s,
                 "kmm_frac_fp32_peak": fk * ws_.n ** 2 / kmm_s / 1e12 / FP32_PEAK_TFLOPS,
+                "kmm_s_symmetric_mode": kmm_sym_s,
                 "solve_s": solve_s, "solve_iters": rs["iters"], "rel_resid_max": float(rs["rel_resid"].max()),
             }
             del Xs, Bs, os_, Ps
