@@ -386,6 +386,19 @@ int launch_sym_kind(const Prepared& P, const Plan& pl, int extra, const f4* Vp, 
 
 }  // namespace
 
+// Clears the column-side slab. A fill kernel rather than hipMemsetAsync: memset nodes recorded into a captured
+// graph have replayed wrongly on this platform, and a caller may capture the stream.
+__global__ __launch_bounds__(256) void zero_slab(f4* __restrict__ p, int64_t count) {
+  for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < count; g += (int64_t)gridDim.x * 256)
+    p[g] = (f4){0.f, 0.f, 0.f, 0.f};
+}
+void launch_zero_slab(float* slab, size_t floats, hipStream_t stream) {      // floats: a multiple of 4
+  const int64_t count = (int64_t)(floats / 4);
+  int64_t blocks = (count + 255) / 256;
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(zero_slab, dim3((unsigned)blocks), dim3(256), 0, stream, reinterpret_cast<f4*>(slab), count);
+}
+
 // Row tiles per wave of the symmetric kernel for this shape, or 0 where it does not apply. Eight row tiles fit the
 // register file (two waves per SIMD) up to 4 distance k-steps (d <= 14) without a 17th column; four otherwise.
 int sym_row_tiles(int64_t npad_rows, int64_t npad_cols, int ks, int nb, int extra) {
@@ -418,7 +431,7 @@ int launch_sym(const Prepared& P, const Plan& pl, int extra, const f4* Vp, const
                hipStream_t stream) {
   ProfScope prof(kProfKmm, stream);
   const size_t slab = (size_t)P.npad * (16 + extra);
-  EGP_HIP(hipMemsetAsync(Part + (size_t)pl.splits * slab, 0, slab * sizeof(float), stream));
+  launch_zero_slab(Part + (size_t)pl.splits * slab, slab, stream);      // npad is a multiple of 512: slab % 4 == 0
   switch (P.ks) {
     case 1: return launch_sym_kind<1>(P, pl, extra, Vp, Ep, Part, cm, stream);
     case 2: return launch_sym_kind<2>(P, pl, extra, Vp, Ep, Part, cm, stream);

@@ -368,7 +368,7 @@ int launch_wide_sym(const Prepared& P, const Plan& pl, const f4* Vp, float* Part
   if (sh.jt < 1) return fail(EGP_ERR_ARG, "the symmetric wide kernel does not fit d = %d", P.d);
   ProfScope prof(kProfKmm, stream);
   const size_t slab = (size_t)P.npad * 16;
-  EGP_HIP(hipMemsetAsync(Part + (size_t)pl.splits * slab, 0, slab * sizeof(float), stream));
+  launch_zero_slab(Part + (size_t)pl.splits * slab, slab, stream);
   if (sh.rw == 2) return launch_wide_sym_kind<2>(P, pl, sh, Vp, Part, cm, stream);
   return launch_wide_sym_kind<1>(P, pl, sh, Vp, Part, cm, stream);
 }
