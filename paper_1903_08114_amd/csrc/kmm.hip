@@ -310,7 +310,7 @@ namespace {
 Plan plan_for_mode(int64_t npad_rows, int64_t npad_cols, int ks, int d, int nb, int extra, bool square = false) {
   if (ks > 8) {      // d > 31: fp32 wide kernels in every mode
     if (kmm_mode() == EGP_KMM_FP32_SYM && square && wide_sym_applies(npad_rows, npad_cols, ks, nb, extra))
-      return make_plan_wide_sym(npad_rows, ks);
+      return make_plan_wide_sym(npad_rows, ks, extra);
     return make_plan_wide(npad_rows, npad_cols, ks, nb, extra);
   }
   if (kmm_mode() == EGP_KMM_FP32_SYM) {     // fp32 arithmetic; shapes the symmetric kernel does not cover run the plain one
@@ -346,7 +346,7 @@ int check_splits(const Plan& pl, int splits_max) {
 int launch_ks(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, int extra, f4* Vp, const float* Ep,
               float* Part, int cm, hipStream_t stream, void* Vb) {
   if (P.ks > 8) {
-    if (pl.sym) return launch_wide_sym(P, pl, Vp, Part, cm, stream);
+    if (pl.sym) return launch_wide_sym(P, pl, extra, Vp, Ep, Part, cm, stream);
     return launch_wide(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
   }
   if (pl.sym) return launch_sym(P, pl, extra, Vp, Ep, Part, cm, stream);

@@ -375,10 +375,11 @@ int sym_row_tiles(int64_t npad_rows, int64_t npad_cols, int ks, int nb, int extr
 Plan make_plan_sym(int64_t npad, int r, int ks, int extra);
 int launch_sym(const Prepared& P, const Plan& pl, int extra, const f4* Vp, const float* Ep, float* Part, int cm,
                hipStream_t stream);
-// defined in kmm_wide_sym.hip: the same for d > 31 (16-column groups)
+// defined in kmm_wide_sym.hip: the same for d > 31 (groups of 16 or 17 columns)
 bool wide_sym_applies(int64_t npad_rows, int64_t npad_cols, int ks, int nb, int extra);
-Plan make_plan_wide_sym(int64_t npad, int ks);
-int launch_wide_sym(const Prepared& P, const Plan& pl, const f4* Vp, float* Part, int cm, hipStream_t stream);
+Plan make_plan_wide_sym(int64_t npad, int ks, int extra);
+int launch_wide_sym(const Prepared& P, const Plan& pl, int extra, const f4* Vp, const float* Ep, float* Part, int cm,
+                    hipStream_t stream);
 // defined in kmm_bf.hip: every contraction on the bf16 MFMA
 Plan make_plan_bf(int64_t npad_rows, int64_t npad_cols, int d, int nb, int extra);
 void launch_pack_points_bf(const Prepared& P, hipStream_t stream);

@@ -1,5 +1,5 @@
-// Symmetric variant of the fused multiply for inputs of more than 31 dimensions (square products, 16 right-hand
-// sides): kmm_wide.hip's tile loop (row operands in LDS, grouped k-steps) with kmm_sym.hip's two-sided use of every
+// Symmetric variant of the fused multiply for inputs of more than 31 dimensions (square products, 16 or 17
+// right-hand sides): kmm_wide.hip's tile loop (row operands in LDS, grouped k-steps) with kmm_sym.hip's two-sided use of every
 // tile off the block diagonal. With KS distance steps per tile against 4 contraction steps per side, forming a tile
 // once instead of twice saves the larger share the larger d is (d = 90: 23 + 8 MFMA per tile pair against 54).
 //
@@ -16,20 +16,32 @@ namespace {
 
 constexpr int kPatchW = 280;      // floats of one transposition patch (layout: kmm_sym.hip)
 
-template <int RW, int KIND>
+// Sum over the 16 lanes of a DPP row (all lanes receive it), as in kmm_sym.hip.
+__device__ __forceinline__ float row_sum16w(float x) {
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xf, 0xf, false));
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xf, 0xf, false));
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xf, 0xf, false));
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x140, 0xf, 0xf, false));
+  return x;
+}
+
+template <int RW, int KIND, int EXTRA>
 __global__ __launch_bounds__(256) void kmm_kernel_wide_sym(const float* __restrict__ Xp, const float* __restrict__ nrm,
-                                                           const f4* __restrict__ Vp, float* __restrict__ Part,
-                                                           int64_t npad, int d, int ks, int jt_stage, int nblk,
-                                                           int stages_per_split, int cm) {
-  constexpr int TS = 16;
+                                                           const f4* __restrict__ Vp, const float* __restrict__ Ep,
+                                                           float* __restrict__ Part, int64_t npad, int d, int ks,
+                                                           int jt_stage, int nblk, int stages_per_split, int cm) {
+  constexpr int TS = 16 + EXTRA;
   extern __shared__ __align__(16) unsigned char smem[];
   // rows [4 RW][ks][64] | 2 x column stage [jt_stage][ks][64] | 2 x V stage [jt_stage][64] f4 |
-  // patches [4 waves][2][RW][kPatchW] | column-side sums [4 waves][jt_stage][64] f4
+  // patches [4 waves][2][RW][kPatchW] | column-side sums [4 waves][jt_stage][64] f4 |
+  // with a 17th column: 2 x its stage [jt_stage][4] f4 | its column-side sums [4 waves][jt_stage][64] f4
   float* Rs = reinterpret_cast<float*>(smem);
   float* Xs = Rs + 4 * RW * ks * 64;
   f4* Vs = reinterpret_cast<f4*>(Xs + 2 * jt_stage * ks * 64);
   float* Ts = reinterpret_cast<float*>(Vs + 2 * jt_stage * 64);
   f4* CJ = reinterpret_cast<f4*>(Ts + 4 * 2 * RW * kPatchW);
+  f4* Es = CJ + 4 * jt_stage * 64;
+  f4* CJE = Es + 2 * jt_stage * 4;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -59,6 +71,7 @@ __global__ __launch_bounds__(256) void kmm_kernel_wide_sym(const float* __restri
     }
   }
   f4 cq[RW], o[RW], o2[RW], vrow[RW];
+  float eacc[RW], eacc2[RW], erow[RW];
 #pragma unroll
   for (int it = 0; it < RW; ++it) {
     const float ni = nrm[(row_tile0 + it) * 16 + p];
@@ -66,12 +79,19 @@ __global__ __launch_bounds__(256) void kmm_kernel_wide_sym(const float* __restri
     o[it] = (f4){0.f, 0.f, 0.f, 0.f};
     o2[it] = (f4){0.f, 0.f, 0.f, 0.f};
     vrow[it] = Vp[(row_tile0 + it) * 64 + lane];
+    eacc[it] = 0.f;
+    eacc2[it] = 0.f;
+    erow[it] = EXTRA ? Ep[(row_tile0 + it) * 16 + p] : 0.f;
   }
   auto fold = [&]() {
 #pragma unroll
     for (int it = 0; it < RW; ++it) {
       o2[it] += o[it];
       o[it] = (f4){0.f, 0.f, 0.f, 0.f};
+      if (EXTRA) {
+        eacc2[it] += eacc[it];
+        eacc[it] = 0.f;
+      }
     }
   };
   const int flush_stages = 256 / jt_stage;
@@ -83,8 +103,9 @@ __global__ __launch_bounds__(256) void kmm_kernel_wide_sym(const float* __restri
   const int k_begin = blockIdx.y * stages_per_split;
   int k_end = k_begin + stages_per_split;
   if (k_end > stages_all) k_end = stages_all;
-  const int xf4 = jt_stage * ks * 16, vf4 = jt_stage * 64;
+  const int xf4 = jt_stage * ks * 16, vf4 = jt_stage * 64, ef4 = jt_stage * 4;
   const f4* Xg = reinterpret_cast<const f4*>(Xp);
+  const f4* Eg = reinterpret_cast<const f4*>(Ep);
   auto abs_stage = [&](int k) {
     int st = bi * sb + k;
     return st >= s_total ? st - s_total : st;
@@ -103,6 +124,9 @@ __global__ __launch_bounds__(256) void kmm_kernel_wide_sym(const float* __restri
     for (int k = wave * 64; k < vf4; k += 256)
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Vp + voff + k + lane),
                                        (__attribute__((address_space(3))) void*)(Vs + buf * vf4 + k), 16, 0, 0);
+    if (EXTRA && tid < ef4)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Eg + (int64_t)st * ef4 + tid),
+                                       (__attribute__((address_space(3))) void*)(Es + buf * ef4), 16, 0, 0);
   };
   float* slab = Part + (int64_t)gridDim.y * npad * TS;
   auto flush = [&](int st) {
@@ -127,6 +151,26 @@ __global__ __launch_bounds__(256) void kmm_kernel_wide_sym(const float* __restri
         unsafeAtomicAdd(dst + 1 * TS, v.y);
         unsafeAtomicAdd(dst + 2 * TS, v.z);
         unsafeAtomicAdd(dst + 3 * TS, v.w);
+      }
+    }
+    if (EXTRA) {
+      // per tile: sum over the four waves, then over the 16 lanes of the DPP row (point index p); lane p adds
+      // component p & 3, lanes p >= 4 a zero to a distinct element (no lane masked off, no address hit twice)
+      for (int jt = wave; jt < jt_stage; jt += 4) {      // wave-uniform
+        f4 v = CJE[(0 * jt_stage + jt) * 64 + lane];
+        v += CJE[(1 * jt_stage + jt) * 64 + lane];
+        v += CJE[(2 * jt_stage + jt) * 64 + lane];
+        v += CJE[(3 * jt_stage + jt) * 64 + lane];
+        v.x = row_sum16w(v.x);
+        v.y = row_sum16w(v.y);
+        v.z = row_sum16w(v.z);
+        v.w = row_sum16w(v.w);
+        const int r = p & 3;
+        float add = r == 0 ? v.x : (r == 1 ? v.y : (r == 2 ? v.z : v.w));
+        if (p >= 4) add = 0.f;
+        const int col = p < 4 ? 16 : (p >> 2);
+        const int64_t j = ((int64_t)st * jt_stage + jt) * 16 + 4 * q + r;
+        unsafeAtomicAdd(cm ? slab + (int64_t)col * npad + j : slab + j * TS + col, add);
       }
     }
   };
@@ -196,7 +240,7 @@ __global__ __launch_bounds__(256) void kmm_kernel_wide_sym(const float* __restri
       }
   };
   // transform and row-side contraction of the RW tiles of one column tile; returns the tiles in kk
-  auto row_side = [&](const f4 (&acc)[RW], const f4& v, bool diag_stage, int64_t col_tile, f4 (&kk)[RW]) {
+  auto row_side = [&](const f4 (&acc)[RW], const f4& v, const f4& e, bool diag_stage, int64_t col_tile, f4 (&kk)[RW]) {
 #pragma unroll
     for (int it = 0; it < RW; ++it) {
       kk[it].x = transform<KIND>(acc[it].x);
@@ -210,6 +254,12 @@ __global__ __launch_bounds__(256) void kmm_kernel_wide_sym(const float* __restri
       o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk[it].y, v.y, o[it], 0, 0, 0);
       o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk[it].z, v.z, o[it], 0, 0, 0);
       o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk[it].w, v.w, o[it], 0, 0, 0);
+      if (EXTRA) {
+        eacc[it] = __builtin_fmaf(kk[it].x, e.x, eacc[it]);
+        eacc[it] = __builtin_fmaf(kk[it].y, e.y, eacc[it]);
+        eacc[it] = __builtin_fmaf(kk[it].z, e.z, eacc[it]);
+        eacc[it] = __builtin_fmaf(kk[it].w, e.w, eacc[it]);
+      }
     }
   };
   // read back the RW tiles of patch set `set`, transposed
@@ -247,7 +297,9 @@ __global__ __launch_bounds__(256) void kmm_kernel_wide_sym(const float* __restri
       for (int jt = 0; jt < jt_stage; ++jt) {
         f4 acc[RW], kk[RW];
         distances(xs + jt * ks * 64, acc);
-        row_side(acc, Vs[buf * vf4 + jt * 64 + lane], diag_stage, (int64_t)st * jt_stage + jt, kk);
+        f4 e = {0.f, 0.f, 0.f, 0.f};
+        if (EXTRA) e = Es[buf * ef4 + jt * 4 + q];
+        row_side(acc, Vs[buf * vf4 + jt * 64 + lane], e, diag_stage, (int64_t)st * jt_stage + jt, kk);
       }
     } else {
       for (int jt = 0; jt < jt_stage; ++jt) {
@@ -258,10 +310,25 @@ __global__ __launch_bounds__(256) void kmm_kernel_wide_sym(const float* __restri
         distances(xs + jt * ks * 64, acc);
         __builtin_amdgcn_sched_barrier(0);
         if (jt > 0) col_side(ktr, jt - 1);
-        row_side(acc, Vs[buf * vf4 + jt * 64 + lane], false, 0, kk);
+        f4 e = {0.f, 0.f, 0.f, 0.f};
+        if (EXTRA) e = Es[buf * ef4 + jt * 4 + q];
+        row_side(acc, Vs[buf * vf4 + jt * 64 + lane], e, false, 0, kk);
 #pragma unroll
         for (int it = 0; it < RW; ++it)
           *reinterpret_cast<f4*>(patch + ((jt & 1) * RW + it) * kPatchW + woff) = kk[it];
+        if (EXTRA) {
+          // column side of the 17th column from the untransposed tiles: kk.r = k(column 4q + r, row p); the sum over
+          // the lanes p is taken in the flush
+          f4 ej = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int it = 0; it < RW; ++it) {
+            ej.x = __builtin_fmaf(kk[it].x, erow[it], ej.x);
+            ej.y = __builtin_fmaf(kk[it].y, erow[it], ej.y);
+            ej.z = __builtin_fmaf(kk[it].z, erow[it], ej.z);
+            ej.w = __builtin_fmaf(kk[it].w, erow[it], ej.w);
+          }
+          CJE[(wave * jt_stage + jt) * 64 + lane] = ej;
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
       {
@@ -293,17 +360,26 @@ __global__ __launch_bounds__(256) void kmm_kernel_wide_sym(const float* __restri
       r0[2 * TS] = o2[it].z;
       r0[3 * TS] = o2[it].w;
     }
+    if (EXTRA) {
+      float sum = eacc2[it];
+      sum += __shfl_xor(sum, 16);
+      sum += __shfl_xor(sum, 32);
+      if (q == 0) {
+        if (cm) dst[(int64_t)16 * npad + row0 + p] = sum;
+        else dst[(row0 + p) * TS + 16] = sum;
+      }
+    }
   }
 }
 
 struct WideSymShape { int rw, jt; size_t lds; };
 // LDS: rows 4 rw ks 256 B | patches 4 x 2 x rw x 1120 B | per column tile of a stage: 2 x (ks 256 + 1024) B of
-// operands and 4 x 1024 B of column-side sums. jt = 0: does not fit.
-WideSymShape wide_sym_shape(int ks) {
+// operands and 4 x 1024 B of column-side sums (a 17th column: 2 x 64 B and 4 x 1024 B more). jt = 0: does not fit.
+WideSymShape wide_sym_shape(int ks, int extra) {
   WideSymShape w;
   w.rw = ks <= 40 ? 2 : 1;
   const size_t fixed = (size_t)4 * w.rw * ks * 256 + (size_t)4 * 2 * w.rw * kPatchW * 4;
-  const size_t per_jt = (size_t)2 * (ks * 256 + 1024) + 4 * 1024;
+  const size_t per_jt = (size_t)2 * (ks * 256 + 1024) + 4 * 1024 + (extra ? 2 * 64 + 4 * 1024 : 0);
   const size_t budget = 150 * 1024;
   int jt = 4;
   while (jt >= 1 && fixed + jt * per_jt > budget) jt /= 2;
@@ -312,39 +388,39 @@ WideSymShape wide_sym_shape(int ks) {
   return w;
 }
 
-template <int RW, int KIND>
-int launch_wide_sym_one(const Prepared& P, const Plan& pl, const WideSymShape& sh, const f4* Vp, float* Part, int cm,
-                        hipStream_t stream) {
-  auto kern = kmm_kernel_wide_sym<RW, KIND>;
+template <int RW, int KIND, int EXTRA>
+int launch_wide_sym_one(const Prepared& P, const Plan& pl, const WideSymShape& sh, const f4* Vp, const float* Ep,
+                        float* Part, int cm, hipStream_t stream) {
+  auto kern = kmm_kernel_wide_sym<RW, KIND, EXTRA>;
   EGP_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                               (int)sh.lds));
   const int nblk = (int)(P.npad / (64 * RW));
-  hipLaunchKernelGGL(kern, dim3(nblk, pl.splits), dim3(256), sh.lds, stream, P.Xp, P.nrm, Vp, Part, P.npad, P.d, P.ks,
-                     sh.jt, nblk, pl.stages_per_split, cm);
+  hipLaunchKernelGGL(kern, dim3(nblk, pl.splits), dim3(256), sh.lds, stream, P.Xp, P.nrm, Vp, Ep, Part, P.npad, P.d,
+                     P.ks, sh.jt, nblk, pl.stages_per_split, cm);
   EGP_HIP(hipGetLastError());
   return EGP_OK;
 }
 
-template <int RW>
-int launch_wide_sym_kind(const Prepared& P, const Plan& pl, const WideSymShape& sh, const f4* Vp, float* Part, int cm,
-                         hipStream_t stream) {
+template <int RW, int EXTRA>
+int launch_wide_sym_kind(const Prepared& P, const Plan& pl, const WideSymShape& sh, const f4* Vp, const float* Ep,
+                         float* Part, int cm, hipStream_t stream) {
   switch (P.kernel_type) {
-    case EGP_RBF: return launch_wide_sym_one<RW, EGP_RBF>(P, pl, sh, Vp, Part, cm, stream);
-    case EGP_MATERN32: return launch_wide_sym_one<RW, EGP_MATERN32>(P, pl, sh, Vp, Part, cm, stream);
-    case EGP_MATERN12: return launch_wide_sym_one<RW, EGP_MATERN12>(P, pl, sh, Vp, Part, cm, stream);
-    default: return launch_wide_sym_one<RW, EGP_MATERN52>(P, pl, sh, Vp, Part, cm, stream);
+    case EGP_RBF: return launch_wide_sym_one<RW, EGP_RBF, EXTRA>(P, pl, sh, Vp, Ep, Part, cm, stream);
+    case EGP_MATERN32: return launch_wide_sym_one<RW, EGP_MATERN32, EXTRA>(P, pl, sh, Vp, Ep, Part, cm, stream);
+    case EGP_MATERN12: return launch_wide_sym_one<RW, EGP_MATERN12, EXTRA>(P, pl, sh, Vp, Ep, Part, cm, stream);
+    default: return launch_wide_sym_one<RW, EGP_MATERN52, EXTRA>(P, pl, sh, Vp, Ep, Part, cm, stream);
   }
 }
 
 }  // namespace
 
 bool wide_sym_applies(int64_t npad_rows, int64_t npad_cols, int ks, int nb, int extra) {
-  return npad_rows == npad_cols && ks > 8 && nb == 1 && extra == 0 && npad_rows / (64 * 8) >= 64 &&
-         wide_sym_shape(ks).jt >= 1;
+  return npad_rows == npad_cols && ks > 8 && nb == 1 && npad_rows / (64 * 8) >= 64 &&
+         wide_sym_shape(ks, extra).jt >= 1;
 }
 
-Plan make_plan_wide_sym(int64_t npad, int ks) {
-  const WideSymShape sh = wide_sym_shape(ks);
+Plan make_plan_wide_sym(int64_t npad, int ks, int extra) {
+  const WideSymShape sh = wide_sym_shape(ks, extra);
   Plan pl;
   pl.big = true;
   pl.sym = true;
@@ -362,15 +438,20 @@ Plan make_plan_wide_sym(int64_t npad, int ks) {
   return pl;
 }
 
-// Part must hold pl.splits + 1 slabs of npad x 16 floats; the last one is cleared here.
-int launch_wide_sym(const Prepared& P, const Plan& pl, const f4* Vp, float* Part, int cm, hipStream_t stream) {
-  const WideSymShape sh = wide_sym_shape(P.ks);
+// Part must hold pl.splits + 1 slabs of npad x (16 + extra) floats; the last one is cleared here.
+int launch_wide_sym(const Prepared& P, const Plan& pl, int extra, const f4* Vp, const float* Ep, float* Part, int cm,
+                    hipStream_t stream) {
+  const WideSymShape sh = wide_sym_shape(P.ks, extra);
   if (sh.jt < 1) return fail(EGP_ERR_ARG, "the symmetric wide kernel does not fit d = %d", P.d);
   ProfScope prof(kProfKmm, stream);
-  const size_t slab = (size_t)P.npad * 16;
+  const size_t slab = (size_t)P.npad * (16 + extra);
   launch_zero_slab(Part + (size_t)pl.splits * slab, slab, stream);
-  if (sh.rw == 2) return launch_wide_sym_kind<2>(P, pl, sh, Vp, Part, cm, stream);
-  return launch_wide_sym_kind<1>(P, pl, sh, Vp, Part, cm, stream);
+  if (sh.rw == 2) {
+    if (extra) return launch_wide_sym_kind<2, 1>(P, pl, sh, Vp, Ep, Part, cm, stream);
+    return launch_wide_sym_kind<2, 0>(P, pl, sh, Vp, Ep, Part, cm, stream);
+  }
+  if (extra) return launch_wide_sym_kind<1, 1>(P, pl, sh, Vp, Ep, Part, cm, stream);
+  return launch_wide_sym_kind<1, 0>(P, pl, sh, Vp, Ep, Part, cm, stream);
 }
 
 }  // namespace kmm_detail

@@ -185,10 +185,12 @@ def test_solver_and_prediction_wide(egp, d):
 
 
 @pytest.mark.parametrize("n,d,t,kind", [(32768, 40, 16, orc.RBF), (33000, 90, 16, orc.MATERN32), (34000, 164, 16, orc.RBF),
-                                         (33000, 300, 32, orc.MATERN52), (33281, 77, 16, orc.MATERN12)])
+                                         (33000, 300, 32, orc.MATERN52), (33281, 77, 16, orc.MATERN12),
+                                         (33000, 90, 17, orc.RBF), (32768, 36, 17, orc.MATERN52), (33000, 200, 33, orc.MATERN32)])
 def test_kmm_wide_symmetric_mode_rows(egp, n, d, t, kind):
-    """The symmetric fp32 mode beyond d = 31 (16-column groups): rows computed exactly by the oracle, both row-tile
-    shapes, every stage size, even and odd block counts; and every row against the one-sided kernel."""
+    """The symmetric fp32 mode beyond d = 31 (groups of 16 or 17 columns; wider groups fall back): rows computed
+    exactly by the oracle, both row-tile shapes, every stage size, even and odd block counts; and every row against
+    the one-sided kernel."""
     X, V, ls = _inputs(31 * d + t + kind, n, d, t)
     rng = np.random.default_rng(d)
     rows = rng.choice(n, 96, replace=False)
@@ -212,8 +214,8 @@ def test_kmm_wide_symmetric_mode_rows(egp, n, d, t, kind):
 
 
 def test_kmm_wide_symmetric_mode_falls_back(egp):
-    """d = 385 does not fit the symmetric wide kernel's LDS budget; 17 columns are not built for it: one-sided bits."""
-    for d, t in ((385, 16), (90, 17)):
+    """d = 385 does not fit the symmetric wide kernel's LDS budget; 32 columns are not built for it: one-sided bits."""
+    for d, t in ((385, 16), (90, 32)):
         X, V, ls = _inputs(d + t, 33000, d, t)
         Xd, Vd = _cuda(X), _cuda(V)
         base = egp.kmm(Xd, Vd, ls, 1.0, 0.1, orc.RBF).cpu().numpy()
@@ -226,10 +228,11 @@ def test_kmm_wide_symmetric_mode_falls_back(egp):
         assert np.array_equal(got, base)
 
 
-def test_mbcg_wide_in_symmetric_mode(egp):
-    """Solver at d = 90 with 16 right-hand sides: the symmetric wide kernel with the column-major state arrays gives
-    the one-sided kernel's iterates up to summation order."""
-    n, d, t = 33000, 90, 16
+@pytest.mark.parametrize("t", [16, 17])
+def test_mbcg_wide_in_symmetric_mode(egp, t):
+    """Solver at d = 90 with 16 / 17 right-hand sides: the symmetric wide kernel with the column-major state arrays
+    gives the one-sided kernel's iterates up to summation order."""
+    n, d = 33000, 90
     X, B, ls = _inputs(901, n, d, t)
     s, noise, kind = 1.0, 0.5, orc.RBF
     Xd, Bd = _cuda(X), _cuda(B)
