@@ -349,7 +349,7 @@ int launch_ks(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, int 
     if (pl.sym) return launch_wide_sym(P, pl, extra, Vp, Ep, Part, cm, stream);
     return launch_wide(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
   }
-  if (pl.sym) return launch_sym(P, pl, extra, Vp, Ep, Part, cm, stream);
+  if (pl.sym) return launch_sym(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
   if (nb == 0 && kmm_mode() != EGP_KMM_SPLIT_BF16_ALL) {
     // a single column has no MFMA contraction to move to bf16: the fp32 kernel serves the contraction-only split mode
     ProfScope prof(kProfKmm, stream);

@@ -36,22 +36,23 @@ __device__ __forceinline__ float row_sum16(float x) {
   return x;
 }
 
-template <int KS, int R, int KIND, int EXTRA>
+template <int KS, int R, int KIND, int NB, int EXTRA>
 __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict__ Xp, const float* __restrict__ nrm,
                                                          const f4* __restrict__ Vp, const float* __restrict__ Ep,
                                                          float* __restrict__ Part, int64_t npad, int d, int nblk,
                                                          int stages_per_split, int cm) {
   constexpr int JT = sym_jt(KS, EXTRA);
-  constexpr int TS = 16 + EXTRA;
+  constexpr int TS = 16 * NB + EXTRA;      // NB = 0, EXTRA = 1: a single column, everything on the VALU
+  static_assert(NB == 1 || (NB == 0 && EXTRA == 1), "16, 17 or 1 columns");
   constexpr int SB = 64 * R / (16 * JT);      // stages per block of 64 R points
   constexpr int XF4 = JT * KS * 16, VF4 = JT * 64, EF4 = JT * 4;
   constexpr int NX = (XF4 + 255) / 256, NV = (VF4 + 255) / 256;
 
   __shared__ f4 Xs[2][XF4];
-  __shared__ f4 Vs[2][VF4];
-  __shared__ __attribute__((aligned(16))) float Ts[4][2][kPatch];      // per wave: two transposition patches
+  __shared__ f4 Vs[2][NB ? VF4 : 1];
+  __shared__ __attribute__((aligned(16))) float Ts[NB ? 4 : 1][2][NB ? kPatch : 4];      // per wave: two transposition patches
   __shared__ f4 Es[2][EXTRA ? EF4 : 1];
-  __shared__ f4 CJ[4][JT][64];      // column-side sums of one stage, per wave: [wave][tile][lane], register r = component
+  __shared__ f4 CJ[NB ? 4 : 1][NB ? JT : 1][NB ? 64 : 1];      // column-side sums of one stage, per wave: [wave][tile][lane], register r = component
   // the same for the 17th column: lane (q, p), component r holds the sum over the wave's rows with point index p of
   // k(column 4q + r, row) e[row]; the sum over p is left to the flush
   __shared__ f4 CJE[EXTRA ? 4 : 1][EXTRA ? JT : 1][EXTRA ? 64 : 1];
@@ -86,7 +87,7 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
     cq[it] = (f4){ni, ni, ni, ni};
     o[it] = (f4){0.f, 0.f, 0.f, 0.f};
     o2[it] = (f4){0.f, 0.f, 0.f, 0.f};
-    vrow[it] = Vp[(row_tile0 + it) * 64 + lane];
+    vrow[it] = NB ? Vp[(row_tile0 + it) * 64 + lane] : (f4){0.f, 0.f, 0.f, 0.f};
     eacc[it] = 0.f;
     eacc2[it] = 0.f;
     erow[it] = EXTRA ? Ep[(row_tile0 + it) * 16 + p] : 0.f;
@@ -103,7 +104,7 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
     }
   };
   // transposition patch: lane (q,p) holds M[4q + r][p] in register r and wants M[p][4q + r]
-  float* patch = &Ts[wave][0][0];
+  float* patch = &Ts[NB ? wave : 0][0][0];
   // 16-byte slot of writer (q, p = 4a + b): 18 q + (a & 1) + 8 (a >> 1) + 2 b. Free of bank conflicts for 32 banks
   // with 8 lanes per write pass / 32 per read pass as well as for 64 banks with 16 / 64 (checked by enumeration).
   const int woff = 4 * (18 * q + ((p >> 2) & 1) + 8 * (p >> 3) + 2 * (p & 3));
@@ -130,11 +131,13 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
       if (XF4 % 256 == 0 || k * 256 + wave * 64 < XF4)
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Xg + xoff + tid + k * 256),
                                          (__attribute__((address_space(3))) void*)(&Xs[buf][k * 256 + wave * 64]), 16, 0, 0);
+    if constexpr (NB > 0) {
 #pragma unroll
-    for (int k = 0; k < NV; ++k)
-      if (VF4 % 256 == 0 || k * 256 + wave * 64 < VF4)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Vp + voff + tid + k * 256),
-                                         (__attribute__((address_space(3))) void*)(&Vs[buf][k * 256 + wave * 64]), 16, 0, 0);
+      for (int k = 0; k < NV; ++k)
+        if (VF4 % 256 == 0 || k * 256 + wave * 64 < VF4)
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Vp + voff + tid + k * 256),
+                                           (__attribute__((address_space(3))) void*)(&Vs[buf][k * 256 + wave * 64]), 16, 0, 0);
+    }
     if (EXTRA && tid < EF4)
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Eg + (int64_t)st * EF4 + tid),
                                        (__attribute__((address_space(3))) void*)(&Es[buf][0]), 16, 0, 0);
@@ -142,7 +145,8 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
   // the column-side sums of stage st (absolute), one partial per wave in CJ, leave as atomic adds into the extra slab
   float* slab = Part + (int64_t)gridDim.y * npad * TS;
   auto flush = [&](int st) {
-    if (cm) {
+    if constexpr (NB == 0) {
+    } else if (cm) {
       // column-major slab [column][row]: a thread takes (column tid / 16, row tid % 16) of every tile, so that the
       // sixteen rows of a column are one contiguous 64-byte run of atomic adds
       const int c = tid >> 4, jrow = tid & 15;
@@ -187,9 +191,15 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
       if (p >= 4) add = 0.f;
       // the zero addends go to distinct elements of the same rows (columns 1..3): lanes of one instruction that
       // hit one address are serialised (measured: 685 ms against 450 ms per launch)
-      const int col = p < 4 ? 16 : (p >> 2);
       const int64_t j = ((int64_t)st * JT + wave) * 16 + 4 * q + r;
-      unsafeAtomicAdd(cm ? slab + (int64_t)col * npad + j : slab + j * TS + col, add);
+      if constexpr (NB > 0) {
+        const int col = p < 4 ? 16 : (p >> 2);
+        unsafeAtomicAdd(cm ? slab + (int64_t)col * npad + j : slab + j * TS + col, add);
+      } else {
+        // a single column: the slab has no other elements to park the zeros on, and this shape has registers to
+        // spare for a masked add (slab is [npad] in both layouts)
+        if (p < 4) unsafeAtomicAdd(slab + j, add);
+      }
     }
   };
 
@@ -209,7 +219,8 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
         float a[KS];
 #pragma unroll
         for (int s = 0; s < KS; ++s) a[s] = xs[(jt * KS + s) * 64 + lane];
-        const f4 v = Vs[buf][jt * 64 + lane];
+        f4 v = {0.f, 0.f, 0.f, 0.f};
+        if (NB) v = Vs[buf][jt * 64 + lane];
         f4 e = {0.f, 0.f, 0.f, 0.f};
         if (EXTRA) e = Es[buf][jt * 4 + q];
 #pragma unroll
@@ -225,10 +236,12 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
           if constexpr (KIND == EGP_MATERN12) {      // exact k(x, x) on the diagonal (see kmm_kernel.h)
             if (row_tile0 + it == (int64_t)st * JT + jt) set_unit_diagonal(kk, q, p);
           }
-          o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.x, v.x, o[it], 0, 0, 0);
-          o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.y, v.y, o[it], 0, 0, 0);
-          o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.z, v.z, o[it], 0, 0, 0);
-          o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.w, v.w, o[it], 0, 0, 0);
+          if constexpr (NB > 0) {
+            o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.x, v.x, o[it], 0, 0, 0);
+            o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.y, v.y, o[it], 0, 0, 0);
+            o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.z, v.z, o[it], 0, 0, 0);
+            o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.w, v.w, o[it], 0, 0, 0);
+          }
           if (EXTRA) {
             eacc[it] = __builtin_fmaf(kk.x, e.x, eacc[it]);
             eacc[it] = __builtin_fmaf(kk.y, e.y, eacc[it]);
@@ -244,7 +257,8 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
       float a[KS];
 #pragma unroll
       for (int s = 0; s < KS; ++s) a[s] = xs[s * 64 + lane];
-      f4 v = Vs[buf][lane];
+      f4 v = {0.f, 0.f, 0.f, 0.f};
+      if (NB) v = Vs[buf][lane];
       f4 e = {0.f, 0.f, 0.f, 0.f};
       if (EXTRA) e = Es[buf][q];
       for (int jt = 0; jt < JT; ++jt) {
@@ -255,7 +269,7 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
 #pragma unroll
         for (int it = 0; it <= R; ++it) {
           f4 kt = {0.f, 0.f, 0.f, 0.f};
-          if (it > 0) {      // transposed tile of the previous step: in flight during this step's distance MFMAs
+          if (NB && it > 0) {      // transposed tile of the previous step: in flight during this step's distance MFMAs
             const float* rp = patch + ((it - 1) & 1) * kPatch + roff;
             kt.x = rp[0];
             kt.y = rp[8];
@@ -265,7 +279,7 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
           if (it == R / 2) {
 #pragma unroll
             for (int s = 0; s < KS; ++s) an[s] = xs[(jn * KS + s) * 64 + lane];
-            vn = Vs[buf][jn * 64 + lane];
+            if (NB) vn = Vs[buf][jn * 64 + lane];
             if (EXTRA) en = Es[buf][jn * 4 + q];
           }
           __builtin_amdgcn_sched_barrier(0);
@@ -276,7 +290,7 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
             for (int s = 0; s < KS; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s], b[it][s], acc, 0, 0, 0);
           }
           __builtin_amdgcn_sched_barrier(0);
-          if (it > 0) {      // column side of the previous step; also covers the latency of the distance result
+          if (NB && it > 0) {      // column side of the previous step; also covers the latency of the distance result
             oj = __builtin_amdgcn_mfma_f32_16x16x4f32(kt.x, vrow[it - 1].x, oj, 0, 0, 0);
             oj = __builtin_amdgcn_mfma_f32_16x16x4f32(kt.y, vrow[it - 1].y, oj, 0, 0, 0);
             oj = __builtin_amdgcn_mfma_f32_16x16x4f32(kt.z, vrow[it - 1].z, oj, 0, 0, 0);
@@ -289,11 +303,13 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
             kk.y = transform<KIND>(acc.y);
             kk.z = transform<KIND>(acc.z);
             kk.w = transform<KIND>(acc.w);
-            o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.x, v.x, o[it], 0, 0, 0);
-            o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.y, v.y, o[it], 0, 0, 0);
-            o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.z, v.z, o[it], 0, 0, 0);
-            o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.w, v.w, o[it], 0, 0, 0);
-            *reinterpret_cast<f4*>(patch + (it & 1) * kPatch + woff) = kk;
+            if constexpr (NB > 0) {
+              o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.x, v.x, o[it], 0, 0, 0);
+              o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.y, v.y, o[it], 0, 0, 0);
+              o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.z, v.z, o[it], 0, 0, 0);
+              o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.w, v.w, o[it], 0, 0, 0);
+              *reinterpret_cast<f4*>(patch + (it & 1) * kPatch + woff) = kk;
+            }
             if (EXTRA) {
               // kk.r = k(column point 4q + r, row point p): row side sums over the column points, column side over
               // the row points (lanes p; reduced after the row tiles)
@@ -309,7 +325,7 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
           }
           __builtin_amdgcn_sched_barrier(0);
         }
-        CJ[wave][jt][lane] = oj;
+        if constexpr (NB > 0) CJ[wave][jt][lane] = oj;
         if (EXTRA) {
           CJE[wave][jt][lane] = ej;
           e = en;
@@ -334,53 +350,56 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
 #pragma unroll
   for (int it = 0; it < R; ++it) {
     const int64_t row0 = (row_tile0 + it) * 16;
-    if (cm) {
-      *reinterpret_cast<f4*>(dst + (int64_t)p * npad + row0 + q * 4) = o2[it];
-    } else {
-      float* r0 = dst + (row0 + q * 4) * TS + p;
-      r0[0 * TS] = o2[it].x;
-      r0[1 * TS] = o2[it].y;
-      r0[2 * TS] = o2[it].z;
-      r0[3 * TS] = o2[it].w;
+    if constexpr (NB > 0) {
+      if (cm) {
+        *reinterpret_cast<f4*>(dst + (int64_t)p * npad + row0 + q * 4) = o2[it];
+      } else {
+        float* r0 = dst + (row0 + q * 4) * TS + p;
+        r0[0 * TS] = o2[it].x;
+        r0[1 * TS] = o2[it].y;
+        r0[2 * TS] = o2[it].z;
+        r0[3 * TS] = o2[it].w;
+      }
     }
     if (EXTRA) {
       float s = eacc2[it];
       s += __shfl_xor(s, 16);
       s += __shfl_xor(s, 32);
       if (q == 0) {
-        if (cm) dst[(int64_t)16 * npad + row0 + p] = s;
-        else dst[(row0 + p) * TS + 16] = s;
+        if (cm) dst[(int64_t)(16 * NB) * npad + row0 + p] = s;
+        else dst[(row0 + p) * TS + 16 * NB] = s;
       }
     }
   }
 }
 
-template <int KS, int R, int KIND, int EXTRA>
+template <int KS, int R, int KIND, int NB, int EXTRA>
 int launch_sym_one(const Prepared& P, const Plan& pl, const f4* Vp, const float* Ep, float* Part, int cm,
                    hipStream_t stream) {
   const int nblk = (int)(P.npad / (64 * R));
-  hipLaunchKernelGGL((kmm_kernel_sym<KS, R, KIND, EXTRA>), dim3(nblk, pl.splits), dim3(256), 0, stream, P.Xp, P.nrm, Vp,
-                     Ep, Part, P.npad, P.d, nblk, pl.stages_per_split, cm);
+  hipLaunchKernelGGL((kmm_kernel_sym<KS, R, KIND, NB, EXTRA>), dim3(nblk, pl.splits), dim3(256), 0, stream, P.Xp, P.nrm,
+                     Vp, Ep, Part, P.npad, P.d, nblk, pl.stages_per_split, cm);
   EGP_HIP(hipGetLastError());
   return EGP_OK;
 }
 
 template <int KS, int KIND>
-int launch_sym_shape(const Prepared& P, const Plan& pl, int extra, const f4* Vp, const float* Ep, float* Part, int cm,
-                     hipStream_t stream) {
-  if (extra) return launch_sym_one<KS, 4, KIND, 1>(P, pl, Vp, Ep, Part, cm, stream);
-  if constexpr (KS <= 4) return launch_sym_one<KS, 8, KIND, 0>(P, pl, Vp, Ep, Part, cm, stream);
-  else return launch_sym_one<KS, 4, KIND, 0>(P, pl, Vp, Ep, Part, cm, stream);
+int launch_sym_shape(const Prepared& P, const Plan& pl, int nb, int extra, const f4* Vp, const float* Ep, float* Part,
+                     int cm, hipStream_t stream) {
+  if (nb == 0) return launch_sym_one<KS, 8, KIND, 0, 1>(P, pl, Vp, Ep, Part, cm, stream);
+  if (extra) return launch_sym_one<KS, 4, KIND, 1, 1>(P, pl, Vp, Ep, Part, cm, stream);
+  if constexpr (KS <= 4) return launch_sym_one<KS, 8, KIND, 1, 0>(P, pl, Vp, Ep, Part, cm, stream);
+  else return launch_sym_one<KS, 4, KIND, 1, 0>(P, pl, Vp, Ep, Part, cm, stream);
 }
 
 template <int KS>
-int launch_sym_kind(const Prepared& P, const Plan& pl, int extra, const f4* Vp, const float* Ep, float* Part, int cm,
-                    hipStream_t stream) {
+int launch_sym_kind(const Prepared& P, const Plan& pl, int nb, int extra, const f4* Vp, const float* Ep, float* Part,
+                    int cm, hipStream_t stream) {
   switch (P.kernel_type) {
-    case EGP_RBF: return launch_sym_shape<KS, EGP_RBF>(P, pl, extra, Vp, Ep, Part, cm, stream);
-    case EGP_MATERN32: return launch_sym_shape<KS, EGP_MATERN32>(P, pl, extra, Vp, Ep, Part, cm, stream);
-    case EGP_MATERN12: return launch_sym_shape<KS, EGP_MATERN12>(P, pl, extra, Vp, Ep, Part, cm, stream);
-    default: return launch_sym_shape<KS, EGP_MATERN52>(P, pl, extra, Vp, Ep, Part, cm, stream);
+    case EGP_RBF: return launch_sym_shape<KS, EGP_RBF>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case EGP_MATERN32: return launch_sym_shape<KS, EGP_MATERN32>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case EGP_MATERN12: return launch_sym_shape<KS, EGP_MATERN12>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    default: return launch_sym_shape<KS, EGP_MATERN52>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
   }
 }
 
@@ -400,9 +419,11 @@ void launch_zero_slab(float* slab, size_t floats, hipStream_t stream) {      // 
 }
 
 // Row tiles per wave of the symmetric kernel for this shape, or 0 where it does not apply. Eight row tiles fit the
-// register file (two waves per SIMD) up to 4 distance k-steps (d <= 14) without a 17th column; four otherwise.
+// register file (two waves per SIMD) up to 4 distance k-steps (d <= 14) without a 17th column, and for a single
+// column; four otherwise.
 int sym_row_tiles(int64_t npad_rows, int64_t npad_cols, int ks, int nb, int extra) {
-  if (npad_rows != npad_cols || ks > 8 || nb != 1 || npad_rows / (64 * 8) < 64) return 0;
+  if (npad_rows != npad_cols || ks > 8 || nb > 1 || npad_rows / (64 * 8) < 64) return 0;
+  if (nb == 0) return 8;      // a single column: no contraction block, few registers
   return (ks <= 4 && !extra) ? 8 : 4;
 }
 
@@ -425,22 +446,22 @@ Plan make_plan_sym(int64_t npad, int r, int ks, int extra) {
   return pl;
 }
 
-// Part must hold pl.splits + 1 slabs of npad x (16 + extra) floats; the last one receives the column-side sums and
+// Part must hold pl.splits + 1 slabs of npad x (16 nb + extra) floats; the last one receives the column-side sums and
 // is cleared here.
-int launch_sym(const Prepared& P, const Plan& pl, int extra, const f4* Vp, const float* Ep, float* Part, int cm,
+int launch_sym(const Prepared& P, const Plan& pl, int nb, int extra, const f4* Vp, const float* Ep, float* Part, int cm,
                hipStream_t stream) {
   ProfScope prof(kProfKmm, stream);
-  const size_t slab = (size_t)P.npad * (16 + extra);
+  const size_t slab = (size_t)P.npad * (16 * nb + extra);
   launch_zero_slab(Part + (size_t)pl.splits * slab, slab, stream);      // npad is a multiple of 512: slab % 4 == 0
   switch (P.ks) {
-    case 1: return launch_sym_kind<1>(P, pl, extra, Vp, Ep, Part, cm, stream);
-    case 2: return launch_sym_kind<2>(P, pl, extra, Vp, Ep, Part, cm, stream);
-    case 3: return launch_sym_kind<3>(P, pl, extra, Vp, Ep, Part, cm, stream);
-    case 4: return launch_sym_kind<4>(P, pl, extra, Vp, Ep, Part, cm, stream);
-    case 5: return launch_sym_kind<5>(P, pl, extra, Vp, Ep, Part, cm, stream);
-    case 6: return launch_sym_kind<6>(P, pl, extra, Vp, Ep, Part, cm, stream);
-    case 7: return launch_sym_kind<7>(P, pl, extra, Vp, Ep, Part, cm, stream);
-    case 8: return launch_sym_kind<8>(P, pl, extra, Vp, Ep, Part, cm, stream);
+    case 1: return launch_sym_kind<1>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 2: return launch_sym_kind<2>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 3: return launch_sym_kind<3>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 4: return launch_sym_kind<4>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 5: return launch_sym_kind<5>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 6: return launch_sym_kind<6>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 7: return launch_sym_kind<7>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
+    case 8: return launch_sym_kind<8>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
     default: return fail(EGP_ERR_ARG, "the symmetric kernel supports d <= 31");
   }
 }

@@ -158,12 +158,13 @@ def test_kmm_split_bf16_c2_recipe_rows(egp, mode):
 
 @pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52, orc.MATERN12])
 @pytest.mark.parametrize("n,d,t", [(32768, 11, 16), (33000, 3, 16), (40000, 14, 48), (65536, 8, 16), (33281, 11, 17),
-                                   (33000, 18, 17), (34000, 25, 16), (32768, 31, 17), (40000, 2, 33), (33000, 8, 1)])
+                                   (33000, 18, 17), (34000, 25, 16), (32768, 31, 17), (40000, 2, 33), (33000, 8, 1), (40000, 25, 1),
+                                   (32768, 11, 18)])
 def test_kmm_symmetric_mode_rows(egp, kind, n, d, t):
     """The symmetric fp32 mode (every off-diagonal tile used for the row-side and the column-side output) against
     rows computed exactly by the oracle: even and odd block counts, rows at the block edges and around the half-way
-    block, several column groups, with and without a 17th column, every stage shape; a 33-column group and a
-    single column take the one-sided kernels."""
+    block, several column groups, with and without a 17th column, a single column, every stage shape; a 33-column
+    group takes the one-sided kernel."""
     rng = np.random.default_rng(11 * n + d + t + kind)
     X = rng.uniform(-1, 1, (n, d)).astype(np.float32)
     V = rng.standard_normal((n, t)).astype(np.float32)
