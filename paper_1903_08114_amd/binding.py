@@ -163,6 +163,21 @@ def _check(rc):
         raise EgpError(rc, lib().egp_last_error().decode())
 
 
+KMM_MODES = {"fp32": 0, "split_bf16": 1, "split_bf16_all": 2, "fp32_sym": 3}
+
+
+def set_kmm_mode(mode):
+    """Select the arithmetic of the fused multiply for every later call in this process (egp_set_kmm_mode):
+    "fp32" (default, bit-reproducible), "fp32_sym" (same arithmetic, every off-diagonal tile of a square product used
+    for both output sides: fastest fp32 path, last bits not reproducible), "split_bf16", "split_bf16_all" (contractions
+    on the bf16 MFMA through exact bf16 splits). Accepts the name or the integer code; returns the previous code."""
+    L = lib()
+    code = KMM_MODES[mode] if isinstance(mode, str) else int(mode)
+    prev = int(L.egp_get_kmm_mode())
+    _check(L.egp_set_kmm_mode(C.c_int32(code)))
+    return prev
+
+
 def _hyper(kernel_type, lengthscales, outputscale, noise):
     ls = [float(v) for v in lengthscales]
     arr = (C.c_float * len(ls))(*ls)

@@ -101,7 +101,10 @@ def main():
     ap.add_argument("--n", type=int, default=65536)
     ap.add_argument("--d", type=int, default=8)
     ap.add_argument("--nq", type=int, default=1000)
-    ap.add_argument("--kernel", type=int, default=0, help="0 RBF, 1 Matern-3/2, 2 Matern-5/2")
+    ap.add_argument("--kernel", type=int, default=0, help="0 RBF, 1 Matern-3/2, 2 Matern-5/2, 3 Matern-1/2")
+    ap.add_argument("--kmm-mode", default="fp32", choices=["fp32", "fp32_sym", "split_bf16", "split_bf16_all"],
+                    help="arithmetic of the fused multiply: fp32 (bit-reproducible), fp32_sym (fastest fp32 path), "
+                         "split_bf16, split_bf16_all")
     ap.add_argument("--rank", type=int, default=512,
                     help="preconditioner rank (the paper uses 100; here an iteration costs far more than applying the "
                          "preconditioner, so a higher rank pays)")
@@ -111,6 +114,8 @@ def main():
     X, y, f, noise_std = synthetic_regression(args.n + args.nq, args.d)
     Xt, yt = X[:args.n], y[:args.n]
     Xq, yq, fq = X[args.n:], y[args.n:], f[args.n:]
+    import paper_1903_08114_amd as egp
+    egp.set_kmm_mode(args.kmm_mode)
     out = fit_and_predict(Xt, yt, Xq, kernel_type=args.kernel, rank=args.rank, noise_floor=args.noise_floor)
     rmse = float(np.sqrt(np.mean((out["mean"] - yq) ** 2)))
     rmse_f = float(np.sqrt(np.mean((out["mean"] - fq) ** 2)))

@@ -202,3 +202,17 @@ def test_plan_check_pins_a_shape_with_two_row_tiles_and_short_stages(lib):
     used, sized = _plan_splits(lib, 2047, 2047, 159, 18)
     assert used == 64 and sized >= 64
     assert lib.egp_kmm_plan_splits(0, 5, 3, 1, None, None) != 0
+
+
+def test_python_mode_switch_by_name(lib):
+    import paper_1903_08114_amd as egp
+    prev = egp.set_kmm_mode("fp32_sym")
+    try:
+        assert lib.egp_get_kmm_mode() == 3
+        assert egp.set_kmm_mode(prev) == 3
+        with pytest.raises(egp.EgpError):
+            egp.set_kmm_mode(9)
+        with pytest.raises(KeyError):
+            egp.set_kmm_mode("fp16")
+    finally:
+        lib.egp_set_kmm_mode(0)
