@@ -48,6 +48,10 @@ def lib():
         if not os.path.exists(path):
             raise ImportError(f"{path} is missing: run `python -m paper_1903_08114_amd.build` first; "
                               "there is no CPU fallback")
+        # torch first: it ships its own HIP runtime, and the device buffers this library works on are torch's. Loaded
+        # the other way round, libegp.so binds the system runtime and then sees no device of torch's process state
+        # ("no ROCm-capable device is detected" from the first launch).
+        import torch  # noqa: F401
         L = C.CDLL(path)
         L.egp_last_error.restype = C.c_char_p
         L.egp_version.restype = C.c_char_p
