@@ -216,3 +216,12 @@ def test_python_mode_switch_by_name(lib):
             egp.set_kmm_mode("fp16")
     finally:
         lib.egp_set_kmm_mode(0)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on exactly one GPU: bench.py --gpus N with N > 1 exits with a message saying so."""
+    import subprocess
+    import sys
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert res.returncode != 0
+    assert "one GPU" in (res.stderr + res.stdout)
