@@ -242,8 +242,8 @@ size_t egp_precond_apply_ws_bytes(int64_t n, int32_t t, int32_t rank);
  *                       row-side and the column-side output (paper, Background: K is a covariance matrix). The
  *                       column-side sums leave the kernel as float atomic adds, so results agree with
  *                       EGP_KMM_FP32 up to summation order and their last bits are not reproducible from run to
- *                       run. Applies to n >= 32257, groups of 1, 16 or 17 columns (1: d <= 31) and d <= 355; other shapes run the
- *                       EGP_KMM_FP32 kernels.
+ *                       run. Applies to n >= 32257 and d <= 355, to groups of 1, 16 or 17 columns (1: d <= 31) and, up to
+ *                       d = 31, of 32 or 33 columns (33: d <= 11); other shapes run the EGP_KMM_FP32 kernels.
  * Affects egp_kmm, egp_kmm_cross, egp_mbcg, egp_lanczos, egp_mll. Returns EGP_ERR_ARG for an unknown mode. */
 typedef enum { EGP_KMM_FP32 = 0, EGP_KMM_SPLIT_BF16 = 1, EGP_KMM_SPLIT_BF16_ALL = 2, EGP_KMM_FP32_SYM = 3 } egp_kmm_mode_t;
 int egp_set_kmm_mode(int32_t mode);

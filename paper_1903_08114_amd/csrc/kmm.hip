@@ -315,7 +315,7 @@ Plan plan_for_mode(int64_t npad_rows, int64_t npad_cols, int ks, int d, int nb, 
   }
   if (kmm_mode() == EGP_KMM_FP32_SYM) {     // fp32 arithmetic; shapes the symmetric kernel does not cover run the plain one
     const int r = square ? sym_row_tiles(npad_rows, npad_cols, ks, nb, extra) : 0;
-    if (r > 0) return make_plan_sym(npad_rows, r, ks, extra);
+    if (r > 0) return make_plan_sym(npad_rows, r, ks, nb, extra);
     return make_plan(npad_rows, npad_cols, ks, nb, extra);
   }
   if (nb == 0 && kmm_mode() != EGP_KMM_SPLIT_BF16_ALL)

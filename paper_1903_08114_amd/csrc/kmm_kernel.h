@@ -372,7 +372,7 @@ int launch_wide(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, in
 // defined in kmm_sym.hip: square products that use every off-diagonal tile twice
 void launch_zero_slab(float* slab, size_t floats, hipStream_t stream);
 int sym_row_tiles(int64_t npad_rows, int64_t npad_cols, int ks, int nb, int extra);
-Plan make_plan_sym(int64_t npad, int r, int ks, int extra);
+Plan make_plan_sym(int64_t npad, int r, int ks, int nb, int extra);
 int launch_sym(const Prepared& P, const Plan& pl, int nb, int extra, const f4* Vp, const float* Ep, float* Part, int cm,
                hipStream_t stream);
 // defined in kmm_wide_sym.hip: the same for d > 31 (groups of 16 or 17 columns)

@@ -1,4 +1,5 @@
-// Symmetric variant of the fused kernel-matrix multiply (square products, d <= 31, 16 or 17 right-hand sides).
+// Symmetric variant of the fused kernel-matrix multiply (square products, d <= 31; 1, 16, 17, 32 or 33 right-hand
+// sides per launch).
 //
 // The kernel matrix is symmetric (paper, Background: k(x, x') is a covariance), so the tile K[I,J] that serves
 // out[I] += K[I,J] V[J] also serves out[J] += K[I,J]^T V[I]. A workgroup owns 64 R rows (row block b) and sweeps
@@ -22,9 +23,9 @@ namespace kmm_detail {
 
 namespace {
 
-// column tiles per stage: 8 up to 4 distance k-steps without a 17th column, else 4 (keeps the workgroup's LDS under
-// 80 KB: two per CU)
-constexpr int sym_jt(int ks, int extra) { return (ks <= 4 && !extra) ? 8 : 4; }
+// column tiles per stage: 8 up to 4 distance k-steps with one 16-column block and no 17th column, else 4 (keeps the
+// workgroup's LDS under 80 KB: two per CU)
+constexpr int sym_jt(int ks, int nb, int extra) { return (ks <= 4 && nb <= 1 && !extra) ? 8 : 4; }
 constexpr int kPatch = 280;      // floats of one transposition patch: 70 slots of 16 bytes
 
 // Sum over the 16 lanes of a DPP row (all lanes receive it): two quad permutations, half-row mirror, row mirror.
@@ -41,18 +42,19 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
                                                          const f4* __restrict__ Vp, const float* __restrict__ Ep,
                                                          float* __restrict__ Part, int64_t npad, int d, int nblk,
                                                          int stages_per_split, int cm) {
-  constexpr int JT = sym_jt(KS, EXTRA);
+  constexpr int JT = sym_jt(KS, NB, EXTRA);
   constexpr int TS = 16 * NB + EXTRA;      // NB = 0, EXTRA = 1: a single column, everything on the VALU
-  static_assert(NB == 1 || (NB == 0 && EXTRA == 1), "16, 17 or 1 columns");
+  static_assert(NB == 1 || NB == 2 || (NB == 0 && EXTRA == 1), "1, 16, 17, 32 or 33 columns");
+  constexpr int NBA = NB > 0 ? NB : 1;      // array extents
   constexpr int SB = 64 * R / (16 * JT);      // stages per block of 64 R points
-  constexpr int XF4 = JT * KS * 16, VF4 = JT * 64, EF4 = JT * 4;
+  constexpr int XF4 = JT * KS * 16, VF4 = JT * NBA * 64, EF4 = JT * 4;
   constexpr int NX = (XF4 + 255) / 256, NV = (VF4 + 255) / 256;
 
   __shared__ f4 Xs[2][XF4];
   __shared__ f4 Vs[2][NB ? VF4 : 1];
   __shared__ __attribute__((aligned(16))) float Ts[NB ? 4 : 1][2][NB ? kPatch : 4];      // per wave: two transposition patches
   __shared__ f4 Es[2][EXTRA ? EF4 : 1];
-  __shared__ f4 CJ[NB ? 4 : 1][NB ? JT : 1][NB ? 64 : 1];      // column-side sums of one stage, per wave: [wave][tile][lane], register r = component
+  __shared__ f4 CJ[NB ? 4 : 1][NB ? JT : 1][NBA][NB ? 64 : 1];      // column-side sums of one stage, per wave: [wave][tile][block][lane], register r = component
   // the same for the 17th column: lane (q, p), component r holds the sum over the wave's rows with point index p of
   // k(column 4q + r, row) e[row]; the sum over p is left to the flush
   __shared__ f4 CJE[EXTRA ? 4 : 1][EXTRA ? JT : 1][EXTRA ? 64 : 1];
@@ -70,7 +72,7 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
 
   const int64_t row_tile0 = ((int64_t)bi * 4 + wave) * R;
   float b[R][KS];
-  f4 cq[R], o[R], o2[R], vrow[R];
+  f4 cq[R], o[R][NBA], o2[R][NBA], vrow[R][NBA];
   float eacc[R], eacc2[R], erow[R];
   constexpr int kFlushStages = 4096 / (16 * JT);
   const int ds = d >> 2, dq = d & 3;
@@ -85,9 +87,12 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
     }
     const float ni = nrm[(row_tile0 + it) * 16 + p];
     cq[it] = (f4){ni, ni, ni, ni};
-    o[it] = (f4){0.f, 0.f, 0.f, 0.f};
-    o2[it] = (f4){0.f, 0.f, 0.f, 0.f};
-    vrow[it] = NB ? Vp[(row_tile0 + it) * 64 + lane] : (f4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int nb = 0; nb < NBA; ++nb) {
+      o[it][nb] = (f4){0.f, 0.f, 0.f, 0.f};
+      o2[it][nb] = (f4){0.f, 0.f, 0.f, 0.f};
+      vrow[it][nb] = NB ? Vp[((row_tile0 + it) * NBA + nb) * 64 + lane] : (f4){0.f, 0.f, 0.f, 0.f};
+    }
     eacc[it] = 0.f;
     eacc2[it] = 0.f;
     erow[it] = EXTRA ? Ep[(row_tile0 + it) * 16 + p] : 0.f;
@@ -95,8 +100,11 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
   auto fold = [&]() {
 #pragma unroll
     for (int it = 0; it < R; ++it) {
-      o2[it] += o[it];
-      o[it] = (f4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int nb = 0; nb < NBA; ++nb) {
+        o2[it][nb] += o[it][nb];
+        o[it][nb] = (f4){0.f, 0.f, 0.f, 0.f};
+      }
       if (EXTRA) {
         eacc2[it] += eacc[it];
         eacc[it] = 0.f;
@@ -150,27 +158,33 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
       // column-major slab [column][row]: a thread takes (column tid / 16, row tid % 16) of every tile, so that the
       // sixteen rows of a column are one contiguous 64-byte run of atomic adds
       const int c = tid >> 4, jrow = tid & 15;
-      const float* cf = reinterpret_cast<const float*>(&CJ[0][0][0]);
+      const float* cf = reinterpret_cast<const float*>(&CJ[0][0][0][0]);
       const int off = ((jrow >> 2) * 16 + c) * 4 + (jrow & 3);
 #pragma unroll
-      for (int jt = 0; jt < JT; ++jt) {
-        const float v = (cf[(0 * JT + jt) * 256 + off] + cf[(1 * JT + jt) * 256 + off]) +
-                        (cf[(2 * JT + jt) * 256 + off] + cf[(3 * JT + jt) * 256 + off]);
-        unsafeAtomicAdd(slab + (int64_t)c * npad + ((int64_t)st * JT + jt) * 16 + jrow, v);
-      }
+      for (int jt = 0; jt < JT; ++jt)
+#pragma unroll
+        for (int nb = 0; nb < NBA; ++nb) {
+          const int t0 = (jt * NBA + nb) * 256 + off;
+          const float v = (cf[0 * JT * NBA * 256 + t0] + cf[1 * JT * NBA * 256 + t0]) +
+                          (cf[2 * JT * NBA * 256 + t0] + cf[3 * JT * NBA * 256 + t0]);
+          unsafeAtomicAdd(slab + (int64_t)(16 * nb + c) * npad + ((int64_t)st * JT + jt) * 16 + jrow, v);
+        }
     } else {
 #pragma unroll
       for (int h = 0; h < JT / 4; ++h) {      // JT is a multiple of 4
         const int jt = wave + 4 * h;      // thread (wave, lane) adds up the four waves' sums of tiles wave, wave + 4, ...
-        f4 v = CJ[0][jt][lane];
-        v += CJ[1][jt][lane];
-        v += CJ[2][jt][lane];
-        v += CJ[3][jt][lane];
-        float* dst = slab + (((int64_t)st * JT + jt) * 16 + 4 * q) * TS + p;
-        unsafeAtomicAdd(dst + 0 * TS, v.x);
-        unsafeAtomicAdd(dst + 1 * TS, v.y);
-        unsafeAtomicAdd(dst + 2 * TS, v.z);
-        unsafeAtomicAdd(dst + 3 * TS, v.w);
+#pragma unroll
+        for (int nb = 0; nb < NBA; ++nb) {
+          f4 v = CJ[0][jt][nb][lane];
+          v += CJ[1][jt][nb][lane];
+          v += CJ[2][jt][nb][lane];
+          v += CJ[3][jt][nb][lane];
+          float* dst = slab + (((int64_t)st * JT + jt) * 16 + 4 * q) * TS + 16 * nb + p;
+          unsafeAtomicAdd(dst + 0 * TS, v.x);
+          unsafeAtomicAdd(dst + 1 * TS, v.y);
+          unsafeAtomicAdd(dst + 2 * TS, v.z);
+          unsafeAtomicAdd(dst + 3 * TS, v.w);
+        }
       }
     }
     if (EXTRA) {
@@ -193,7 +207,7 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
       // hit one address are serialised (measured: 685 ms against 450 ms per launch)
       const int64_t j = ((int64_t)st * JT + wave) * 16 + 4 * q + r;
       if constexpr (NB > 0) {
-        const int col = p < 4 ? 16 : (p >> 2);
+        const int col = p < 4 ? 16 * NB : (p >> 2);
         unsafeAtomicAdd(cm ? slab + (int64_t)col * npad + j : slab + j * TS + col, add);
       } else {
         // a single column: the slab has no other elements to park the zeros on, and this shape has registers to
@@ -219,8 +233,9 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
         float a[KS];
 #pragma unroll
         for (int s = 0; s < KS; ++s) a[s] = xs[(jt * KS + s) * 64 + lane];
-        f4 v = {0.f, 0.f, 0.f, 0.f};
-        if (NB) v = Vs[buf][jt * 64 + lane];
+        f4 v[NBA];
+#pragma unroll
+        for (int nb = 0; nb < NBA; ++nb) v[nb] = NB ? Vs[buf][(jt * NBA + nb) * 64 + lane] : (f4){0.f, 0.f, 0.f, 0.f};
         f4 e = {0.f, 0.f, 0.f, 0.f};
         if (EXTRA) e = Es[buf][jt * 4 + q];
 #pragma unroll
@@ -237,10 +252,13 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
             if (row_tile0 + it == (int64_t)st * JT + jt) set_unit_diagonal(kk, q, p);
           }
           if constexpr (NB > 0) {
-            o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.x, v.x, o[it], 0, 0, 0);
-            o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.y, v.y, o[it], 0, 0, 0);
-            o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.z, v.z, o[it], 0, 0, 0);
-            o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.w, v.w, o[it], 0, 0, 0);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+              o[it][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.x, v[nb].x, o[it][nb], 0, 0, 0);
+              o[it][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.y, v[nb].y, o[it][nb], 0, 0, 0);
+              o[it][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.z, v[nb].z, o[it][nb], 0, 0, 0);
+              o[it][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.w, v[nb].w, o[it][nb], 0, 0, 0);
+            }
           }
           if (EXTRA) {
             eacc[it] = __builtin_fmaf(kk.x, e.x, eacc[it]);
@@ -257,15 +275,21 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
       float a[KS];
 #pragma unroll
       for (int s = 0; s < KS; ++s) a[s] = xs[s * 64 + lane];
-      f4 v = {0.f, 0.f, 0.f, 0.f};
-      if (NB) v = Vs[buf][lane];
+      f4 v[NBA];
+#pragma unroll
+      for (int nb = 0; nb < NBA; ++nb) v[nb] = NB ? Vs[buf][nb * 64 + lane] : (f4){0.f, 0.f, 0.f, 0.f};
       f4 e = {0.f, 0.f, 0.f, 0.f};
       if (EXTRA) e = Es[buf][q];
       for (int jt = 0; jt < JT; ++jt) {
         const int jn = jt + 1 < JT ? jt + 1 : JT - 1;
         float an[KS];
-        f4 vn = v, en = e;
-        f4 oj = {0.f, 0.f, 0.f, 0.f}, ej = {0.f, 0.f, 0.f, 0.f};
+        f4 vn[NBA], oj[NBA];
+#pragma unroll
+        for (int nb = 0; nb < NBA; ++nb) {
+          vn[nb] = v[nb];
+          oj[nb] = (f4){0.f, 0.f, 0.f, 0.f};
+        }
+        f4 en = e, ej = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int it = 0; it <= R; ++it) {
           f4 kt = {0.f, 0.f, 0.f, 0.f};
@@ -279,7 +303,10 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
           if (it == R / 2) {
 #pragma unroll
             for (int s = 0; s < KS; ++s) an[s] = xs[(jn * KS + s) * 64 + lane];
-            if (NB) vn = Vs[buf][jn * 64 + lane];
+            if constexpr (NB > 0) {
+#pragma unroll
+              for (int nb = 0; nb < NB; ++nb) vn[nb] = Vs[buf][(jn * NB + nb) * 64 + lane];
+            }
             if (EXTRA) en = Es[buf][jn * 4 + q];
           }
           __builtin_amdgcn_sched_barrier(0);
@@ -291,10 +318,13 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
           }
           __builtin_amdgcn_sched_barrier(0);
           if (NB && it > 0) {      // column side of the previous step; also covers the latency of the distance result
-            oj = __builtin_amdgcn_mfma_f32_16x16x4f32(kt.x, vrow[it - 1].x, oj, 0, 0, 0);
-            oj = __builtin_amdgcn_mfma_f32_16x16x4f32(kt.y, vrow[it - 1].y, oj, 0, 0, 0);
-            oj = __builtin_amdgcn_mfma_f32_16x16x4f32(kt.z, vrow[it - 1].z, oj, 0, 0, 0);
-            oj = __builtin_amdgcn_mfma_f32_16x16x4f32(kt.w, vrow[it - 1].w, oj, 0, 0, 0);
+#pragma unroll
+            for (int nb = 0; nb < NBA; ++nb) {
+              oj[nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(kt.x, vrow[it - 1][nb].x, oj[nb], 0, 0, 0);
+              oj[nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(kt.y, vrow[it - 1][nb].y, oj[nb], 0, 0, 0);
+              oj[nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(kt.z, vrow[it - 1][nb].z, oj[nb], 0, 0, 0);
+              oj[nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(kt.w, vrow[it - 1][nb].w, oj[nb], 0, 0, 0);
+            }
           }
           __builtin_amdgcn_sched_barrier(0);
           if (it < R) {
@@ -304,10 +334,13 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
             kk.z = transform<KIND>(acc.z);
             kk.w = transform<KIND>(acc.w);
             if constexpr (NB > 0) {
-              o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.x, v.x, o[it], 0, 0, 0);
-              o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.y, v.y, o[it], 0, 0, 0);
-              o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.z, v.z, o[it], 0, 0, 0);
-              o[it] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.w, v.w, o[it], 0, 0, 0);
+#pragma unroll
+              for (int nb = 0; nb < NB; ++nb) {
+                o[it][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.x, v[nb].x, o[it][nb], 0, 0, 0);
+                o[it][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.y, v[nb].y, o[it][nb], 0, 0, 0);
+                o[it][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.z, v[nb].z, o[it][nb], 0, 0, 0);
+                o[it][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(kk.w, v[nb].w, o[it][nb], 0, 0, 0);
+              }
               *reinterpret_cast<f4*>(patch + (it & 1) * kPatch + woff) = kk;
             }
             if (EXTRA) {
@@ -325,14 +358,18 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
           }
           __builtin_amdgcn_sched_barrier(0);
         }
-        if constexpr (NB > 0) CJ[wave][jt][lane] = oj;
+        if constexpr (NB > 0) {
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) CJ[wave][jt][nb][lane] = oj[nb];
+        }
         if (EXTRA) {
           CJE[wave][jt][lane] = ej;
           e = en;
         }
 #pragma unroll
         for (int s = 0; s < KS; ++s) a[s] = an[s];
-        v = vn;
+#pragma unroll
+        for (int nb = 0; nb < NBA; ++nb) v[nb] = vn[nb];
       }
     }
     if ((k - k_begin) % kFlushStages == kFlushStages - 1) fold();
@@ -351,14 +388,17 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
   for (int it = 0; it < R; ++it) {
     const int64_t row0 = (row_tile0 + it) * 16;
     if constexpr (NB > 0) {
-      if (cm) {
-        *reinterpret_cast<f4*>(dst + (int64_t)p * npad + row0 + q * 4) = o2[it];
-      } else {
-        float* r0 = dst + (row0 + q * 4) * TS + p;
-        r0[0 * TS] = o2[it].x;
-        r0[1 * TS] = o2[it].y;
-        r0[2 * TS] = o2[it].z;
-        r0[3 * TS] = o2[it].w;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        if (cm) {
+          *reinterpret_cast<f4*>(dst + (int64_t)(16 * nb + p) * npad + row0 + q * 4) = o2[it][nb];
+        } else {
+          float* r0 = dst + (row0 + q * 4) * TS + 16 * nb + p;
+          r0[0 * TS] = o2[it][nb].x;
+          r0[1 * TS] = o2[it][nb].y;
+          r0[2 * TS] = o2[it][nb].z;
+          r0[3 * TS] = o2[it][nb].w;
+        }
       }
     }
     if (EXTRA) {
@@ -387,6 +427,11 @@ template <int KS, int KIND>
 int launch_sym_shape(const Prepared& P, const Plan& pl, int nb, int extra, const f4* Vp, const float* Ep, float* Part,
                      int cm, hipStream_t stream) {
   if (nb == 0) return launch_sym_one<KS, 8, KIND, 0, 1>(P, pl, Vp, Ep, Part, cm, stream);
+  if (nb == 2) {
+    if (!extra) return launch_sym_one<KS, 4, KIND, 2, 0>(P, pl, Vp, Ep, Part, cm, stream);
+    if constexpr (KS <= 3) return launch_sym_one<KS, 4, KIND, 2, 1>(P, pl, Vp, Ep, Part, cm, stream);
+    else return fail(EGP_ERR_ARG, "internal: no symmetric kernel for 33 columns at this d");
+  }
   if (extra) return launch_sym_one<KS, 4, KIND, 1, 1>(P, pl, Vp, Ep, Part, cm, stream);
   if constexpr (KS <= 4) return launch_sym_one<KS, 8, KIND, 1, 0>(P, pl, Vp, Ep, Part, cm, stream);
   else return launch_sym_one<KS, 4, KIND, 1, 0>(P, pl, Vp, Ep, Part, cm, stream);
@@ -419,22 +464,23 @@ void launch_zero_slab(float* slab, size_t floats, hipStream_t stream) {      // 
 }
 
 // Row tiles per wave of the symmetric kernel for this shape, or 0 where it does not apply. Eight row tiles fit the
-// register file (two waves per SIMD) up to 4 distance k-steps (d <= 14) without a 17th column, and for a single
-// column; four otherwise.
+// register file (two waves per SIMD) up to 4 distance k-steps (d <= 14) with 16 columns, and for a single column;
+// four otherwise.
 int sym_row_tiles(int64_t npad_rows, int64_t npad_cols, int ks, int nb, int extra) {
-  if (npad_rows != npad_cols || ks > 8 || nb > 1 || npad_rows / (64 * 8) < 64) return 0;
+  if (npad_rows != npad_cols || ks > 8 || nb > 2 || npad_rows / (64 * 8) < 64) return 0;
   if (nb == 0) return 8;      // a single column: no contraction block, few registers
+  if (nb == 2) return (extra && ks > 3) ? 0 : 4;      // 33 columns beyond d = 11: the stage would not fit 80 KB of LDS
   return (ks <= 4 && !extra) ? 8 : 4;
 }
 
 // stages_total holds the length of one workgroup's sweep; row_blocks the block count
-Plan make_plan_sym(int64_t npad, int r, int ks, int extra) {
+Plan make_plan_sym(int64_t npad, int r, int ks, int nb, int extra) {
   Plan pl;
   pl.big = true;
   pl.sym = true;
   pl.extra_slabs = 1;
   const int nblk = (int)(npad / (64 * r));
-  const int sb = 64 * r / (16 * sym_jt(ks, extra));
+  const int sb = 64 * r / (16 * sym_jt(ks, nb, extra));
   pl.row_blocks = nblk;
   pl.stages_total = (nblk / 2 + 1) * sb;
   int want = 1024 / nblk;

@@ -159,12 +159,13 @@ def test_kmm_split_bf16_c2_recipe_rows(egp, mode):
 @pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52, orc.MATERN12])
 @pytest.mark.parametrize("n,d,t", [(32768, 11, 16), (33000, 3, 16), (40000, 14, 48), (65536, 8, 16), (33281, 11, 17),
                                    (33000, 18, 17), (34000, 25, 16), (32768, 31, 17), (40000, 2, 33), (33000, 8, 1), (40000, 25, 1),
-                                   (32768, 11, 18)])
+                                   (32768, 11, 18), (33000, 11, 33), (33281, 25, 32), (32768, 31, 32), (34000, 18, 33),
+                                   (33000, 11, 65)])
 def test_kmm_symmetric_mode_rows(egp, kind, n, d, t):
     """The symmetric fp32 mode (every off-diagonal tile used for the row-side and the column-side output) against
     rows computed exactly by the oracle: even and odd block counts, rows at the block edges and around the half-way
-    block, several column groups, with and without a 17th column, a single column, every stage shape; a 33-column
-    group takes the one-sided kernel."""
+    block, several column groups (1, 16, 17, 32, 33 columns, ragged ones), every stage shape; a 33-column group
+    beyond d = 11 takes the one-sided kernel."""
     rng = np.random.default_rng(11 * n + d + t + kind)
     X = rng.uniform(-1, 1, (n, d)).astype(np.float32)
     V = rng.standard_normal((n, t)).astype(np.float32)
@@ -188,8 +189,9 @@ def test_kmm_symmetric_mode_rows(egp, kind, n, d, t):
 
 
 def test_kmm_symmetric_mode_falls_back_on_other_shapes(egp):
-    """Shapes the symmetric kernels do not cover (small n, a group of 32 columns) give the one-sided kernel's bits."""
-    for n, d, t in ((3000, 11, 16), (33000, 11, 32)):
+    """Shapes the symmetric kernels do not cover (small n, a group of 33 columns beyond d = 11) give the one-sided
+    kernel's bits."""
+    for n, d, t in ((3000, 11, 16), (33000, 18, 33)):
         rng = np.random.default_rng(n + d)
         X = rng.uniform(-1, 1, (n, d)).astype(np.float32)
         V = rng.standard_normal((n, t)).astype(np.float32)

@@ -243,7 +243,7 @@ def test_mbcg_slq_logdet_from_gpu_coefficients(egp):
     assert abs(est - exact) <= 4 * terms.std(ddof=1) / np.sqrt(tp) + 1e-3 * abs(exact)
 
 
-@pytest.mark.parametrize("t", [16, 17, 1])
+@pytest.mark.parametrize("t", [16, 17, 1, 32, 33])
 def test_mbcg_in_symmetric_mode(egp, t):
     """The symmetric fp32 mode inside the solver (column-major state, t = 16 takes the two-sided kernel): same
     iterates as the one-sided kernel up to summation order, and a true residual (rows computed exactly by the
