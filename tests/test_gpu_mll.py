@@ -83,3 +83,34 @@ def test_train_adam_tracks_the_oracle_loop(egp):
     assert abs(got["noise"] - href.noise) <= 2e-2 * href.noise and got["noise"] > floor
     assert np.allclose(got["mll_history"], hist, rtol=3e-3, atol=0.5)
     assert got["mll_history"][-1] > got["mll_history"][0]
+
+
+@pytest.mark.parametrize("kind,tp", [(orc.MATERN32, 16), (orc.RBF, 15), (orc.RBF, 32)])
+def test_mll_in_symmetric_mode_matches_default_mode(egp, kind, tp):
+    """At a size where the symmetric kernels run (17, 16 and 33 columns in the solver), the likelihood step gives the
+    default mode's value and gradient up to summation order and the stopping point of the solver: same probes, same
+    preconditioner. The default mode is the one checked against the dense oracle above; n = 33000 is out of reach of
+    a dense factorisation."""
+    n, d, rank = 33000, 11, 30
+    rng = np.random.default_rng(900 + kind + tp)
+    X = rng.uniform(0, 1, (n, d)).astype(np.float32)
+    y = (np.sin(5 * X[:, 0]) + np.cos(3 * X[:, 1]) + 0.2 * rng.standard_normal(n)).astype(np.float32)
+    ls = np.exp(rng.uniform(np.log(0.3), np.log(1.5), d)).astype(np.float32)
+    s, noise = 1.1, 0.5
+    w1, w2 = _cuda(rademacher(rng, (rank, tp))), _cuda(rademacher(rng, (n, tp)))
+    Xd, yd = _cuda(X), _cuda(y)
+    base = egp.mll(Xd, yd, w1, w2, ls, s, noise, kind, rank=rank, max_iter=300, tol=1e-3)
+    try:
+        egp.set_kmm_mode("fp32_sym")
+        got = egp.mll(Xd, yd, w1, w2, ls, s, noise, kind, rank=rank, max_iter=300, tol=1e-3)
+    finally:
+        egp.set_kmm_mode("fp32")
+    print(f"mll at n={n} kind={kind} tp={tp}: default {base['mll']:.3f} ({base['iters']} it), symmetric {got['mll']:.3f} "
+          f"({got['iters']} it)")
+    assert got["rel_resid_max"] <= 1e-3 and base["rel_resid_max"] <= 1e-3
+    assert abs(got["iters"] - base["iters"]) <= 2
+    assert abs(got["quad"] - base["quad"]) <= 2e-3 * abs(base["quad"])
+    assert abs(got["logdet"] - base["logdet"]) <= 1e-3 * abs(base["logdet"]) + 0.5
+    assert abs(got["mll"] - base["mll"]) <= 1e-3 * abs(base["mll"]) + 0.5
+    scale = np.abs(base["grad"]) + 0.02 * np.abs(base["grad"]).max()
+    assert np.all(np.abs(got["grad"] - base["grad"]) <= 2e-2 * scale), (got["grad"], base["grad"])

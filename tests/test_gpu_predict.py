@@ -44,6 +44,28 @@ def test_kmm_cross_matches_oracle(egp, kind, nq, n, d, t):
     assert _rel(got, ref) <= KMM_TOL
 
 
+def test_kmm_cross_equal_sizes_in_symmetric_mode(egp):
+    """Two different point sets of the same (large) size are not a symmetric product: the symmetric mode must leave
+    such a call to the one-sided kernel. Checked against oracle rows and against the default mode's bits."""
+    nq = n = 33000
+    d, t, kind = 11, 16, orc.RBF
+    rng = np.random.default_rng(2024)
+    X = rng.uniform(-1, 1, (n, d)).astype(np.float32)
+    Xq = rng.uniform(-1, 1, (nq, d)).astype(np.float32)
+    V = rng.standard_normal((n, t)).astype(np.float32)
+    ls = np.exp(rng.uniform(np.log(0.4), np.log(2.5), d)).astype(np.float32)
+    base = egp.kmm_cross(_cuda(Xq), _cuda(X), _cuda(V), ls, 1.1, kind).cpu().numpy()
+    try:
+        egp.set_kmm_mode("fp32_sym")
+        got = egp.kmm_cross(_cuda(Xq), _cuda(X), _cuda(V), ls, 1.1, kind).cpu().numpy()
+    finally:
+        egp.set_kmm_mode("fp32")
+    assert np.array_equal(got, base)
+    rows = rng.choice(nq, 64, replace=False)
+    ref = orc.kernel_matrix(Xq[rows], X, orc.Hyper(kind, ls, 1.1, 0.0)) @ V.astype(np.float64)
+    assert _rel(got[rows].astype(np.float64), ref) <= KMM_TOL
+
+
 def test_lanczos_cache_properties_and_parity(egp):
     n, d, r = 700, 3, 40
     rng = np.random.default_rng(8)

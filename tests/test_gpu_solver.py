@@ -273,3 +273,47 @@ def test_mbcg_in_symmetric_mode(egp, t):
     KU = orc.kmm_rows(X, U, orc.Hyper(kind, ls, s, noise), rows)
     true_res = np.linalg.norm(KU - B[rows], axis=0) / np.linalg.norm(B[rows], axis=0)
     assert true_res.max() <= 5e-3
+
+
+@pytest.mark.parametrize("mode", ["fp32", "fp32_sym"])
+def test_lanczos_three_term_recurrence_at_size(egp, mode):
+    """Lanczos (single vector) and block Lanczos at a size where the symmetric kernels run: the basis is orthonormal
+    and Khat q_j = beta_{j-1} q_{j-1} + alpha_j q_j + beta_j q_{j+1} holds on rows of Khat Q^T computed exactly by the
+    oracle; the block variant's projected matrix equals Q Khat Q^T on sampled-row evidence (Khat Q^T rows against
+    (T Q)^T rows for the interior blocks)."""
+    n, d, r = 33000, 3, 10
+    rng = np.random.default_rng(321)
+    X = rng.uniform(0, 1, (n, d)).astype(np.float32)
+    y = (np.sin(6 * X[:, 0]) + X[:, 1] ** 2 + 0.1 * rng.standard_normal(n)).astype(np.float32)
+    ls = np.array([0.3, 0.5, 0.9], np.float32)
+    s, noise, kind = 1.3, 0.1, orc.MATERN52
+    h = orc.Hyper(kind, ls, s, noise)
+    rows = rng.choice(n, 96, replace=False)
+    try:
+        egp.set_kmm_mode(mode)
+        c = egp.lanczos(_cuda(X), _cuda(y), ls, s, noise, kind, r)
+        B0 = np.concatenate([y[:, None], rademacher(rng, (n, 15))], axis=1)
+        bc = egp.block_lanczos(_cuda(X), _cuda(B0), ls, s, noise, kind, 3)
+    finally:
+        egp.set_kmm_mode("fp32")
+    assert c.steps == r
+    Q = c.Q.cpu().numpy().astype(np.float64)
+    assert np.abs(Q @ Q.T - np.eye(r)).max() <= 5e-5
+    KQ = orc.kmm_rows(X, Q.T.astype(np.float32), h, rows)          # (rows, r)
+    scale = np.abs(c.alpha).max()
+    for j in range(r - 1):
+        rhs = c.alpha[j] * Q[j, rows] + c.beta[j] * Q[j + 1, rows]
+        if j > 0:
+            rhs = rhs + c.beta[j - 1] * Q[j - 1, rows]
+        assert np.linalg.norm(KQ[:, j] - rhs) <= 2e-4 * scale * np.linalg.norm(Q[j, rows]) + 1e-7, j
+    # block variant: Khat Q_b^T lies in the span of blocks b-1, b, b+1 with coefficients T
+    m = bc.steps
+    assert m == 48
+    Qb = bc.Q.cpu().numpy().astype(np.float64)
+    assert np.abs(Qb @ Qb.T - np.eye(m)).max() <= 5e-5
+    KQb = orc.kmm_rows(X, Qb.T.astype(np.float32), h, rows)        # (rows, m)
+    T = np.asarray(bc.T, dtype=np.float64)
+    assert np.abs(T - T.T).max() <= 1e-4 * np.abs(T).max()
+    recon = Qb[:, rows].T @ T                                      # (rows, m): sum_i Q[i, row] T[i, j]
+    inner = slice(0, 32)                                           # blocks whose successor is in the basis
+    assert np.linalg.norm(KQb[:, inner] - recon[:, inner]) <= 3e-4 * np.abs(T).max() * np.linalg.norm(Qb[:32, rows])
