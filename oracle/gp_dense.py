@@ -21,8 +21,12 @@ the log-determinant).
 Pins (tests/test_oracle_*.py, CPU only): closed-form kernel values, brute-force
 scalar loops, symmetry/PSD, limits of the lengthscale, finite differences,
 LAPACK dpstrf pivots, greedy Schur-complement pivots, CG vs Cholesky, finite
-termination, exact Gauss quadrature at m=n Lanczos steps, Monte-Carlo error of
-the stochastic log-determinant. No function here is "parity unpinned".
+termination, the CG tridiagonal against explicit Lanczos at truncations, exact
+Gauss quadrature at m=n Lanczos steps, stochastic estimators exact for complete
+(Hadamard) probe sets and within Monte-Carlo error for random ones, Adam's
+second step against the published recurrences. No function here is "parity
+unpinned"; tests/oracle_mutation_sweep.py checks that single-token changes to
+this file are rejected by those pins.
 
 All functions take array-likes, cast to float64, and return float64.
 """

@@ -1,5 +1,6 @@
 """Pins for the oracle's prediction functions (CPU only)."""
 import numpy as np
+import pytest
 
 import oracle as orc
 from workloads import well_separated_points
@@ -54,6 +55,12 @@ def test_lanczos_invariants_and_cached_variance():
     assert np.allclose(prev, exact, atol=1e-8)        # full Krylov space: exact
     # first Lanczos vector is the normalised start vector
     assert np.allclose(Q[0], y / np.linalg.norm(y))
+    # the smallest ranks against the Galerkin formula with the projected matrix formed densely
+    for r in (1, 2, 3):
+        Q, al, be = orc.lanczos(Kh, y, r)
+        G = Kq @ Q.T
+        dense = h.outputscale - np.sum(G * np.linalg.solve(Q @ Kh @ Q.T, G.T).T, axis=1)
+        assert np.allclose(orc.predict_var_lanczos(Kq, Q, al, be, h.outputscale), dense, atol=1e-10)
 
 
 def test_block_lanczos_pins():
@@ -94,3 +101,21 @@ def test_block_lanczos_pins():
     assert Qm.shape[0] == 60 and np.allclose(prev, exact, atol=1e-8)
     # (4) planted mistake check: T without the projection (plain Khat block) must fail the identity
     assert not np.allclose(T, Kh[:12, :12], atol=1e-3)
+
+
+def test_block_lanczos_start_block_conditions():
+    """A start block with a repeated column is refused; columns of very different length are not (only the directions
+    matter); asking for more blocks than the space holds stops at n basis vectors."""
+    X, Xq, y, h = _problem(n=24)
+    Kh = orc.khat(X, h)
+    rng = np.random.default_rng(2)
+    B = rng.standard_normal((24, 4))
+    with pytest.raises(ValueError):
+        orc.block_lanczos(Kh, np.concatenate([B, B[:, :1]], axis=1), 2)
+    Bs = B * np.array([1.0, 1e-3, 1e3, 1e-6])
+    Q1, T1 = orc.block_lanczos(Kh, B, 3)
+    Q2, T2 = orc.block_lanczos(Kh, Bs, 3)
+    assert Q2.shape == Q1.shape == (12, 24)
+    assert np.allclose(Q1.T @ Q1, Q2.T @ Q2, atol=1e-8)          # same subspace: same orthogonal projector
+    Qf, Tf = orc.block_lanczos(Kh, B, 10)
+    assert Qf.shape[0] == 24 and np.allclose(Qf @ Qf.T, np.eye(24), atol=1e-9)
