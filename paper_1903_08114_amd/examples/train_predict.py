@@ -35,8 +35,10 @@ def rademacher(rng, shape):
 
 def fit_and_predict(X, y, Xq, kernel_type=0, rank=512, probes=16, subset=10000, pre_steps=30, full_steps=3, lr=0.1,
                     noise_floor=0.1, train_tol=1.0, train_iters=100, solve_tol=1e-2, solve_iters=1000,
-                    cache_rank=256, seed=0, verbose=True):
-    """Returns dict with the fitted hyper-parameters, predictive mean and variance (numpy) and timings."""
+                    cache_rank=256, exact_var=0, seed=0, verbose=True):
+    """Returns dict with the fitted hyper-parameters, predictive mean and variance (numpy) and timings.
+    exact_var > 0 (at most 32): the first exact_var test points also get their variance from a solve with the
+    columns k(X, x*), returned as "var_exact" (the cached variance is an upper bound of it)."""
     import torch
     import paper_1903_08114_amd as egp
     rng = np.random.default_rng(seed)
@@ -92,8 +94,19 @@ def fit_and_predict(X, y, Xq, kernel_type=0, rank=512, probes=16, subset=10000, 
     mean, var = egp.predict(Xqd, Xd, a, ls, s, noise, kernel_type, cache=cache)
     torch.cuda.synchronize()
     times["predict_s"] = time.perf_counter() - t0
-    return {"lengthscales": ls, "outputscale": s, "noise": noise, "mean": mean.cpu().numpy(),
-            "var": var.cpu().numpy(), "alpha": a, "solve_iters": sol["iters"], "times": times}
+    out = {"lengthscales": ls, "outputscale": s, "noise": noise, "mean": mean.cpu().numpy(),
+           "var": var.cpu().numpy(), "alpha": a, "solve_iters": sol["iters"], "times": times}
+    if exact_var > 0:
+        # s - k*^T Khat^{-1} k* with the solve done for real: the columns k(X, x*) come from a cross product with the
+        # identity, the solve is the same preconditioned batched CG
+        m = min(int(exact_var), 32, Xq.shape[0])
+        t0 = time.perf_counter()
+        Kq = egp.kmm_cross(Xd, Xqd[:m].contiguous(), torch.eye(m, dtype=torch.float32, device=dev), ls, s,
+                           kernel_type)
+        Uq = egp.mbcg(Xd, Kq, ls, s, noise, kernel_type, precond=P, max_iter=solve_iters, tol=solve_tol)["U"]
+        out["var_exact"] = (s - (Kq * Uq).sum(dim=0)).cpu().numpy()
+        times["exact_var_s"] = time.perf_counter() - t0
+    return out
 
 
 def main():
@@ -110,19 +123,30 @@ def main():
                          "preconditioner, so a higher rank pays)")
     ap.add_argument("--noise-floor", type=float, default=0.1,
                     help="lower bound of the learned noise variance (the paper keeps it at 0.1 on its largest sets)")
+    ap.add_argument("--exact-var", type=int, default=32,
+                    help="number of test points (at most 32) whose variance is also computed by a solve, to show how "
+                         "far above it the cached upper bound sits")
     args = ap.parse_args()
     X, y, f, noise_std = synthetic_regression(args.n + args.nq, args.d)
     Xt, yt = X[:args.n], y[:args.n]
     Xq, yq, fq = X[args.n:], y[args.n:], f[args.n:]
     import paper_1903_08114_amd as egp
     egp.set_kmm_mode(args.kmm_mode)
-    out = fit_and_predict(Xt, yt, Xq, kernel_type=args.kernel, rank=args.rank, noise_floor=args.noise_floor)
+    out = fit_and_predict(Xt, yt, Xq, kernel_type=args.kernel, rank=args.rank, noise_floor=args.noise_floor,
+                          exact_var=args.exact_var)
     rmse = float(np.sqrt(np.mean((out["mean"] - yq) ** 2)))
     rmse_f = float(np.sqrt(np.mean((out["mean"] - fq) ** 2)))
     v = np.maximum(out["var"], 0.0) + out["noise"]
     nll = float(np.mean(0.5 * np.log(2 * np.pi * v) + 0.5 * (yq - out["mean"]) ** 2 / v))
     print(f"held-out RMSE {rmse:.4f} (noise level {noise_std:.4f}), RMSE against the noise-free target {rmse_f:.4f}, "
           f"NLL {nll:.4f}")
+    if "var_exact" in out:
+        m = len(out["var_exact"])
+        ve = np.maximum(out["var_exact"], 0.0) + out["noise"]
+        nll_e = float(np.mean(0.5 * np.log(2 * np.pi * ve) + 0.5 * (yq[:m] - out["mean"][:m]) ** 2 / ve))
+        nll_c = float(np.mean(0.5 * np.log(2 * np.pi * v[:m]) + 0.5 * (yq[:m] - out["mean"][:m]) ** 2 / v[:m]))
+        print(f"first {m} test points: mean latent variance {out['var_exact'].mean():.4f} by solve, "
+              f"{out['var'][:m].mean():.4f} from the cache (an upper bound); NLL {nll_e:.4f} against {nll_c:.4f}")
     print("fitted noise", round(out["noise"], 4), "outputscale", round(out["outputscale"], 4))
     print("timings (s):", {k: round(v, 3) for k, v in out["times"].items()})
 

@@ -18,13 +18,16 @@ def test_fit_solve_predict_matches_exact_gp():
     Xt, yt, Xq, yq = X[:n], y[:n], X[n:], y[n:]
     out = fit_and_predict(Xt, yt, Xq, kernel_type=orc.RBF, rank=40, probes=16, subset=1500, pre_steps=40,
                           full_steps=3, train_tol=1e-2, train_iters=200, solve_tol=1e-4, cache_rank=150,
-                          noise_floor=1e-4, verbose=False)
+                          noise_floor=1e-4, exact_var=32, verbose=False)
     h = orc.Hyper(orc.RBF, out["lengthscales"], out["outputscale"], out["noise"])
     mean_ref, var_ref = orc.predict_exact(Xt, yt, Xq, h)
     # same hyper-parameters, exact dense GP: means agree, cached variances sit just above the exact ones
     assert np.abs(out["mean"] - mean_ref).max() <= 5e-3 * max(1.0, np.abs(mean_ref).max())
     assert np.all(out["var"] >= var_ref - 5e-3)
     assert np.mean(out["var"] - var_ref) <= 0.05 * out["outputscale"]
+    # variances from a solve with the columns k(X, x*): the exact ones up to the solve's tolerance
+    assert out["var_exact"].shape == (32,)
+    assert np.abs(out["var_exact"] - var_ref[:32]).max() <= 2e-3 * out["outputscale"]
     # it has learned: held-out error close to the noise level, far below predicting the mean (standardised y: 1.0)
     rmse = float(np.sqrt(np.mean((out["mean"] - yq) ** 2)))
     assert rmse <= 1.5 * noise_std + 0.05, (rmse, noise_std)
