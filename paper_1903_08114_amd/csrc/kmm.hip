@@ -148,17 +148,20 @@ void launch_pack_rhs(const float* V, int64_t n, int64_t npad, int t, int c0, int
                      nb_count, extra, static_cast<f4*>(Vp), Ep);
 }
 
-// out[row][c0 + c] = s * sum_split Part[split][row][c] + noise * V[row][c0 + c]
+// out[row][c0 + c] = s * sum_split Part[split][row][c] + noise * V[row][c0 + c]. After a symmetric kernel the
+// column-side sums (cside: int64 fixed point [row][c], scale from colmax, see colside_exp) are added as well.
 __global__ __launch_bounds__(256) void kmm_epilogue(const float* __restrict__ Part, int splits, int64_t npad,
                                                     int ts, const float* __restrict__ V, int64_t n, int t,
                                                     int c0, int tg, float s, float noise,
-                                                    float* __restrict__ out) {
+                                                    float* __restrict__ out, const long long* __restrict__ cside,
+                                                    const unsigned* __restrict__ colmax) {
   int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (g >= n * tg) return;
   const int64_t row = g / tg;
   const int c = (int)(g % tg);
   float acc = 0.f;
   for (int sp = 0; sp < splits; ++sp) acc += Part[((int64_t)sp * npad + row) * ts + c];
+  if (cside != nullptr) acc += colside_value(cside[row * ts + c], colside_exp(colmax[c], npad));
   const int64_t o = row * t + c0 + c;
   out[o] = V ? __builtin_fmaf(s, acc, noise * V[o]) : s * acc;
 }
@@ -200,9 +203,12 @@ __global__ __launch_bounds__(256) void pack_rhs_cm(const float* __restrict__ V, 
 __global__ __launch_bounds__(256) void kmm_epilogue_cm(const float* __restrict__ Part, int splits, int64_t npad,
                                                        int ts, const float* __restrict__ V, int64_t ld, int64_t n,
                                                        float s, float noise, float* __restrict__ out,
-                                                       float* __restrict__ dot_part, int dot_ld) {
+                                                       float* __restrict__ dot_part, int dot_ld,
+                                                       const long long* __restrict__ cside,
+                                                       const unsigned* __restrict__ colmax) {
   __shared__ float red[4];
   const int c = blockIdx.y;
+  const int ce = cside != nullptr ? colside_exp(colmax[c], npad) : 0;
   const float4* v4 = reinterpret_cast<const float4*>(V + (int64_t)c * ld);
   float4* o4 = reinterpret_cast<float4*>(out + (int64_t)c * ld);
   float acc = 0.f;
@@ -211,6 +217,13 @@ __global__ __launch_bounds__(256) void kmm_epilogue_cm(const float* __restrict__
     for (int sp = 0; sp < splits; ++sp) {
       const float4 pv = reinterpret_cast<const float4*>(Part + ((int64_t)sp * ts + c) * npad)[g];
       sum.x += pv.x; sum.y += pv.y; sum.z += pv.z; sum.w += pv.w;
+    }
+    if (cside != nullptr) {      // column-side sums of a symmetric kernel: int64 fixed point, [c][row]
+      const long long* cs = cside + (int64_t)c * npad + g * 4;
+      sum.x += colside_value(cs[0], ce);
+      sum.y += colside_value(cs[1], ce);
+      sum.z += colside_value(cs[2], ce);
+      sum.w += colside_value(cs[3], ce);
     }
     const float4 v = v4[g];
     float4 r;
@@ -415,7 +428,8 @@ size_t kmm_cross_ws_bytes(int64_t n_rows, int64_t n_cols, int t) {
   size_t b = 0;
   b += round_up((size_t)pcol * nb * 16 * sizeof(float), 256);                    // Vp
   b += round_up((size_t)pcol * sizeof(float), 256);                              // Ep
-  b += round_up((size_t)(splits + 1) * prow * widest_ts(t) * sizeof(float), 256);      // Part (+1: column-side slab of the symmetric kernel)
+  // Part (+2 slabs and the column maxima: column-side region of the symmetric kernels)
+  b += round_up(((size_t)(splits + 2) * prow * widest_ts(t) + kmm_detail::kColmaxFloats) * sizeof(float), 256);
   b += round_up((size_t)pcol * nb * 32 * sizeof(float), 256);                    // split V of the all-bf16 mode
   return b;
 }
@@ -441,7 +455,7 @@ int kmm_cross(const Prepared& P, const Prepared& Q, const float* V, int t, float
   float* Ep = reinterpret_cast<float*>(w);
   w += round_up((size_t)npad * sizeof(float), 256);
   float* Part = reinterpret_cast<float*>(w);
-  w += round_up((size_t)(splits_max + 1) * Q.npad * widest_ts(t) * sizeof(float), 256);
+  w += round_up(((size_t)(splits_max + 2) * Q.npad * widest_ts(t) + kColmaxFloats) * sizeof(float), 256);
   void* Vb = w;
 
   int c0 = 0;
@@ -472,9 +486,11 @@ int kmm_cross(const Prepared& P, const Prepared& Q, const float* V, int t, float
     if (rc != EGP_OK) return rc;
     const int64_t outs = Q.n * tg;
     ProfScope eprof(kProfPack, stream);
-    hipLaunchKernelGGL(kmm_epilogue, dim3((unsigned)((outs + 255) / 256)), dim3(256), 0, stream, Part,
-                       pl.splits + pl.extra_slabs, Q.npad, ts, square ? V : nullptr, Q.n, t, c0, tg, P.outputscale,
-                       square ? P.noise : 0.f, out);
+    const float* cside = Part + (size_t)pl.splits * Q.npad * ts;      // behind the row-side slabs (symmetric kernels)
+    hipLaunchKernelGGL(kmm_epilogue, dim3((unsigned)((outs + 255) / 256)), dim3(256), 0, stream, Part, pl.splits,
+                       Q.npad, ts, square ? V : nullptr, Q.n, t, c0, tg, P.outputscale, square ? P.noise : 0.f, out,
+                       pl.sym ? reinterpret_cast<const long long*>(cside) : nullptr,
+                       reinterpret_cast<const unsigned*>(cside + 2 * (size_t)Q.npad * ts));
     EGP_HIP(hipGetLastError());
     c0 += tg;
   }
@@ -504,7 +520,7 @@ int kmm_core_cm(const Prepared& P, const float* V, int t, float* out, void* ws2,
   w += round_up((size_t)npad * (nb > 0 ? nb : 1) * 16 * sizeof(float), 256);
   w += round_up((size_t)npad * sizeof(float), 256);      // the row-major path's extra-column buffer (unused here)
   float* Part = reinterpret_cast<float*>(w);
-  w += round_up((size_t)(splits_max + 1) * npad * widest_ts(t) * sizeof(float), 256);
+  w += round_up(((size_t)(splits_max + 2) * npad * widest_ts(t) + kColmaxFloats) * sizeof(float), 256);
   void* Vb = w;
   if (nb > 0) {
     ProfScope prof(kProfPack, stream);
@@ -517,8 +533,11 @@ int kmm_core_cm(const Prepared& P, const float* V, int t, float* out, void* ws2,
   const int rc = launch_ks(P, P, pl, nb, extra, Vp, Ep, Part, 1, stream, Vb);
   if (rc != EGP_OK) return rc;
   ProfScope eprof(kProfPack, stream);
-  hipLaunchKernelGGL(kmm_epilogue_cm, dim3(kmm_cm_dot_blocks(npad), t), dim3(256), 0, stream, Part, pl.splits + pl.extra_slabs, npad,
-                     ts, V, npad, P.n, P.outputscale, P.noise, out, dot_part, dot_ld);
+  const float* cside = Part + (size_t)pl.splits * npad * ts;      // behind the row-side slabs (symmetric kernels)
+  hipLaunchKernelGGL(kmm_epilogue_cm, dim3(kmm_cm_dot_blocks(npad), t), dim3(256), 0, stream, Part, pl.splits, npad,
+                     ts, V, npad, P.n, P.outputscale, P.noise, out, dot_part, dot_ld,
+                     pl.sym ? reinterpret_cast<const long long*>(cside) : nullptr,
+                     reinterpret_cast<const unsigned*>(cside + 2 * (size_t)npad * ts));
   EGP_HIP(hipGetLastError());
   return EGP_OK;
 }

@@ -40,6 +40,31 @@ __device__ __forceinline__ void set_unit_diagonal(V4& k, int q, int p) {
   if (r == 3) k.w = 1.0f;
 }
 
+// Column-side sums of the symmetric kernels: 64-bit fixed point, so that the atomic adds from different workgroups
+// commute exactly and the result does not depend on their order (float atomics would make the last bits vary from
+// run to run). Column c of the right-hand sides gets the scale 2^e_c with e_c chosen from max_i |V_ic| (colmax, float
+// bits) such that n_pad * max|V| * 2^e_c <= 2^61: kernel values are at most 1, so no sum of contributions can leave
+// the int64 range, and one unit is 2^-61 of that bound (2^-37 or less of the fp32 rounding level of the result).
+__device__ __forceinline__ int colside_exp(unsigned maxbits, int64_t npad) {
+  int eb = (int)((maxbits >> 23) & 0xffu) - 127;      // max|V| < 2^(eb + 1)
+  if (eb < -126) eb = -126;
+  const int lg = 64 - __builtin_clzll((unsigned long long)(npad - 1));      // npad <= 2^lg
+  const int e = 60 - eb - lg;
+  return e > 120 ? 120 : e;      // never below -99: a float scale exists either way
+}
+__device__ __forceinline__ float colside_scale(int e) { return __uint_as_float((unsigned)(e + 127) << 23); }
+__device__ __forceinline__ float colside_value(long long sum, int e) {      // sum * 2^-e, rounded once to fp32
+  return (float)((double)sum * __builtin_bit_cast(double, (unsigned long long)(1023 - e) << 52));
+}
+__device__ __forceinline__ void colside_add(long long* dst, float v, float scale) {
+  const float a = __builtin_fabsf(v) * scale;                    // exact: a power of two
+  const float ah = __builtin_floorf(a * 0x1p-32f);
+  const float al = __builtin_fmaf(-ah, 0x1p32f, a);              // exact: the low bits of a, in [0, 2^32)
+  unsigned long long m = ((unsigned long long)(unsigned)ah << 32) | (unsigned long long)(unsigned)al;
+  if (v < 0.f) m = 0ull - m;
+  atomicAdd(reinterpret_cast<unsigned long long*>(dst), m);
+}
+
 // ------------------------------------------------------------------------------------------------
 // The fused kernel.
 //   grid.x = row blocks (4 waves x R row tiles x 16 rows), grid.y = column splits
@@ -278,7 +303,7 @@ namespace kmm_detail {
 struct Plan {
   bool big;
   int splits, stages_per_split, stages_total, row_blocks;
-  int extra_slabs = 0;      // slabs of the partial-sum buffer behind the per-split ones (symmetric kernel: 1)
+  int extra_slabs = 0;      // float slabs of room behind the per-split ones (symmetric kernels: 2, one int64 slab)
   bool sym = false;         // launch the symmetric kernel
 };
 
@@ -371,6 +396,11 @@ int launch_wide(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, in
                 float* Part, int cm, hipStream_t stream);
 // defined in kmm_sym.hip: square products that use every off-diagonal tile twice
 void launch_zero_slab(float* slab, size_t floats, hipStream_t stream);
+void launch_col_absmax(const f4* Vp, const float* Ep, int64_t npad, int nb, int extra, unsigned* colmax,
+                       hipStream_t stream);
+// The column-side region of the partial-sum buffer, after the pl.splits row-side slabs: an int64 slab (the room of
+// two float slabs) followed by the per-column maxima (kColmaxFloats floats of room).
+constexpr int kColmaxFloats = 64;
 int sym_row_tiles(int64_t npad_rows, int64_t npad_cols, int ks, int nb, int extra);
 Plan make_plan_sym(int64_t npad, int r, int ks, int nb, int extra);
 int launch_sym(const Prepared& P, const Plan& pl, int nb, int extra, const f4* Vp, const float* Ep, float* Part, int cm,

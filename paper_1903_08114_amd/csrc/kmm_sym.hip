@@ -11,11 +11,12 @@
 //                LDS patch (one 16-byte write, four 4-byte reads per lane, both free of bank conflicts), and
 //                contracts it with the packed V of its own row tiles (resident in registers). The column-side sums
 //                of a wave's R row tiles go to LDS; at the end of a stage the four waves' sums are added up and
-//                leave the workgroup as float atomic adds into one extra slab of the partial-sum buffer.
+//                leave the workgroup as 64-bit fixed-point atomic adds (colside_add, kmm_kernel.h) into an extra slab
+//                of the partial-sum buffer.
 //                (LDS float atomics were measured far too slow for the first step: plain stores, one patch per wave.)
 // The diagonal block and (for an even block count) the half-way block are computed one-sided, as in kmm_kernel.
-// Results differ from kmm_kernel's only in summation order; the order of the atomic adds is not fixed, so the last
-// bits are not reproducible from run to run.
+// Results differ from kmm_kernel's only in summation order. Within a workgroup that order is fixed, and the integer
+// atomic adds between workgroups commute exactly: results are reproducible bit for bit.
 #include "kmm_kernel.h"
 
 namespace egp {
@@ -42,6 +43,7 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
                                                          const f4* __restrict__ Vp, const float* __restrict__ Ep,
                                                          float* __restrict__ Part, int64_t npad, int d, int nblk,
                                                          int stages_per_split, int cm) {
+  // (the int64 column-side slab and the column maxima follow the gridDim.y row-side slabs of Part)
   constexpr int JT = sym_jt(KS, NB, EXTRA);
   constexpr int TS = 16 * NB + EXTRA;      // NB = 0, EXTRA = 1: a single column, everything on the VALU
   static_assert(NB == 1 || NB == 2 || (NB == 0 && EXTRA == 1), "1, 16, 17, 32 or 33 columns");
@@ -58,6 +60,7 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
   // the same for the 17th column: lane (q, p), component r holds the sum over the wave's rows with point index p of
   // k(column 4q + r, row) e[row]; the sum over p is left to the flush
   __shared__ f4 CJE[EXTRA ? 4 : 1][EXTRA ? JT : 1][EXTRA ? 64 : 1];
+  __shared__ float cscale[34];      // fixed-point scale of each right-hand-side column (colside_exp)
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -151,7 +154,10 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
                                        (__attribute__((address_space(3))) void*)(&Es[buf][0]), 16, 0, 0);
   };
   // the column-side sums of stage st (absolute), one partial per wave in CJ, leave as atomic adds into the extra slab
-  float* slab = Part + (int64_t)gridDim.y * npad * TS;
+  long long* slab = reinterpret_cast<long long*>(Part + (int64_t)gridDim.y * npad * TS);
+  if (tid < TS)
+    cscale[tid] = colside_scale(colside_exp(reinterpret_cast<const unsigned*>(slab + npad * TS)[tid], npad));
+  // (visible to every thread after the barrier that follows the first stage's loads)
   auto flush = [&](int st) {
     if constexpr (NB == 0) {
     } else if (cm) {
@@ -159,6 +165,9 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
       // sixteen rows of a column are one contiguous 64-byte run of atomic adds
       const int c = tid >> 4, jrow = tid & 15;
       const float* cf = reinterpret_cast<const float*>(&CJ[0][0][0][0]);
+      float sc[NBA];
+#pragma unroll
+      for (int nb = 0; nb < NBA; ++nb) sc[nb] = cscale[16 * nb + c];
       const int off = ((jrow >> 2) * 16 + c) * 4 + (jrow & 3);
 #pragma unroll
       for (int jt = 0; jt < JT; ++jt)
@@ -167,7 +176,7 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
           const int t0 = (jt * NBA + nb) * 256 + off;
           const float v = (cf[0 * JT * NBA * 256 + t0] + cf[1 * JT * NBA * 256 + t0]) +
                           (cf[2 * JT * NBA * 256 + t0] + cf[3 * JT * NBA * 256 + t0]);
-          unsafeAtomicAdd(slab + (int64_t)(16 * nb + c) * npad + ((int64_t)st * JT + jt) * 16 + jrow, v);
+          colside_add(slab + (int64_t)(16 * nb + c) * npad + ((int64_t)st * JT + jt) * 16 + jrow, v, sc[nb]);
         }
     } else {
 #pragma unroll
@@ -179,11 +188,12 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
           v += CJ[1][jt][nb][lane];
           v += CJ[2][jt][nb][lane];
           v += CJ[3][jt][nb][lane];
-          float* dst = slab + (((int64_t)st * JT + jt) * 16 + 4 * q) * TS + 16 * nb + p;
-          unsafeAtomicAdd(dst + 0 * TS, v.x);
-          unsafeAtomicAdd(dst + 1 * TS, v.y);
-          unsafeAtomicAdd(dst + 2 * TS, v.z);
-          unsafeAtomicAdd(dst + 3 * TS, v.w);
+          long long* dst = slab + (((int64_t)st * JT + jt) * 16 + 4 * q) * TS + 16 * nb + p;
+          const float sc = cscale[16 * nb + p];
+          colside_add(dst + 0 * TS, v.x, sc);
+          colside_add(dst + 1 * TS, v.y, sc);
+          colside_add(dst + 2 * TS, v.z, sc);
+          colside_add(dst + 3 * TS, v.w, sc);
         }
       }
     }
@@ -207,12 +217,12 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
       // hit one address are serialised (measured: 685 ms against 450 ms per launch)
       const int64_t j = ((int64_t)st * JT + wave) * 16 + 4 * q + r;
       if constexpr (NB > 0) {
-        const int col = p < 4 ? 16 * NB : (p >> 2);
-        unsafeAtomicAdd(cm ? slab + (int64_t)col * npad + j : slab + j * TS + col, add);
+        const int col = 16 * NB;
+        if (p < 4) colside_add(cm ? slab + (int64_t)col * npad + j : slab + j * TS + col, add, cscale[16 * NB]);
       } else {
         // a single column: the slab has no other elements to park the zeros on, and this shape has registers to
         // spare for a masked add (slab is [npad] in both layouts)
-        if (p < 4) unsafeAtomicAdd(slab + j, add);
+        if (p < 4) colside_add(slab + j, add, cscale[0]);
       }
     }
   };
@@ -463,6 +473,40 @@ void launch_zero_slab(float* slab, size_t floats, hipStream_t stream) {      // 
   hipLaunchKernelGGL(zero_slab, dim3((unsigned)blocks), dim3(256), 0, stream, reinterpret_cast<f4*>(slab), count);
 }
 
+// colmax[16 nb + p] = max over the points of |V| in column p of block nb, colmax[16 nb_count] the same for the extra
+// column, as float bits (non-negative floats order like unsigned integers, so an integer atomic max is exact and
+// independent of the order). colmax must be zero on entry. Every thread walks elements of one (block, lane) class.
+__global__ __launch_bounds__(256) void col_absmax(const f4* __restrict__ Vp, const float* __restrict__ Ep, int64_t npad,
+                                                  int nb_count, int extra, unsigned* __restrict__ colmax) {
+  const int lane = threadIdx.x & 63;
+  const int64_t stride = (int64_t)gridDim.x * 256;      // a multiple of 128: block and lane of an element stay fixed
+  if (nb_count > 0) {
+    const int64_t total = (npad >> 4) * nb_count * 64;
+    const int64_t g0 = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    float m = 0.f;
+    for (int64_t g = g0; g < total; g += stride) {
+      const f4 v = Vp[g];
+      m = __builtin_fmaxf(m, __builtin_fmaxf(__builtin_fmaxf(__builtin_fabsf(v.x), __builtin_fabsf(v.y)),
+                                             __builtin_fmaxf(__builtin_fabsf(v.z), __builtin_fabsf(v.w))));
+    }
+    m = __builtin_fmaxf(m, __shfl_xor(m, 16));
+    m = __builtin_fmaxf(m, __shfl_xor(m, 32));
+    const int nb = (int)((g0 >> 6) % nb_count);
+    if (lane < 16 && g0 < total) atomicMax(colmax + 16 * nb + lane, __float_as_uint(m));
+  }
+  if (extra) {
+    float m = 0.f;
+    for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < npad; g += stride) m = __builtin_fmaxf(m, __builtin_fabsf(Ep[g]));
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) m = __builtin_fmaxf(m, __shfl_xor(m, off));
+    if (lane == 0) atomicMax(colmax + 16 * nb_count, __float_as_uint(m));
+  }
+}
+void launch_col_absmax(const f4* Vp, const float* Ep, int64_t npad, int nb, int extra, unsigned* colmax,
+                       hipStream_t stream) {
+  hipLaunchKernelGGL(col_absmax, dim3(256), dim3(256), 0, stream, Vp, Ep, npad, nb, extra, colmax);
+}
+
 // Row tiles per wave of the symmetric kernel for this shape, or 0 where it does not apply. Eight row tiles fit the
 // register file (two waves per SIMD) up to 4 distance k-steps (d <= 14) with 16 columns, and for a single column;
 // four otherwise.
@@ -478,7 +522,7 @@ Plan make_plan_sym(int64_t npad, int r, int ks, int nb, int extra) {
   Plan pl;
   pl.big = true;
   pl.sym = true;
-  pl.extra_slabs = 1;
+  pl.extra_slabs = 2;      // the int64 column-side slab
   const int nblk = (int)(npad / (64 * r));
   const int sb = 64 * r / (16 * sym_jt(ks, nb, extra));
   pl.row_blocks = nblk;
@@ -492,13 +536,15 @@ Plan make_plan_sym(int64_t npad, int r, int ks, int nb, int extra) {
   return pl;
 }
 
-// Part must hold pl.splits + 1 slabs of npad x (16 nb + extra) floats; the last one receives the column-side sums and
-// is cleared here.
+// Part must hold pl.splits + 2 slabs of npad x (16 nb + extra) floats and kColmaxFloats more: the room of the last two
+// slabs is the int64 slab of the column-side sums, cleared here, followed by the column maxima, computed here.
 int launch_sym(const Prepared& P, const Plan& pl, int nb, int extra, const f4* Vp, const float* Ep, float* Part, int cm,
                hipStream_t stream) {
   ProfScope prof(kProfKmm, stream);
   const size_t slab = (size_t)P.npad * (16 * nb + extra);
-  launch_zero_slab(Part + (size_t)pl.splits * slab, slab, stream);      // npad is a multiple of 512: slab % 4 == 0
+  float* cside = Part + (size_t)pl.splits * slab;
+  launch_zero_slab(cside, 2 * slab + kColmaxFloats, stream);      // npad is a multiple of 512: a multiple of 4 floats
+  launch_col_absmax(Vp, Ep, P.npad, nb, extra, reinterpret_cast<unsigned*>(cside + 2 * slab), stream);
   switch (P.ks) {
     case 1: return launch_sym_kind<1>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
     case 2: return launch_sym_kind<2>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);

@@ -128,16 +128,21 @@ __global__ __launch_bounds__(256) void kmm_kernel_wide_sym(const float* __restri
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Eg + (int64_t)st * ef4 + tid),
                                        (__attribute__((address_space(3))) void*)(Es + buf * ef4), 16, 0, 0);
   };
-  float* slab = Part + (int64_t)gridDim.y * npad * TS;
+  // column-side sums leave as 64-bit fixed-point atomic adds (colside_add, kmm_kernel.h): order-independent
+  __shared__ float cscale[18];
+  long long* slab = reinterpret_cast<long long*>(Part + (int64_t)gridDim.y * npad * TS);
+  if (tid < TS)
+    cscale[tid] = colside_scale(colside_exp(reinterpret_cast<const unsigned*>(slab + npad * TS)[tid], npad));
   auto flush = [&](int st) {
     if (cm) {
       const int c = tid >> 4, jrow = tid & 15;
       const float* cf = reinterpret_cast<const float*>(CJ);
       const int off = ((jrow >> 2) * 16 + c) * 4 + (jrow & 3);
+      const float sc = cscale[c];
       for (int jt = 0; jt < jt_stage; ++jt) {
         const float v = (cf[(0 * jt_stage + jt) * 256 + off] + cf[(1 * jt_stage + jt) * 256 + off]) +
                         (cf[(2 * jt_stage + jt) * 256 + off] + cf[(3 * jt_stage + jt) * 256 + off]);
-        unsafeAtomicAdd(slab + (int64_t)c * npad + ((int64_t)st * jt_stage + jt) * 16 + jrow, v);
+        colside_add(slab + (int64_t)c * npad + ((int64_t)st * jt_stage + jt) * 16 + jrow, v, sc);
       }
     } else {
       for (int e = tid; e < jt_stage * 64; e += 256) {      // (tile, lane)
@@ -146,11 +151,12 @@ __global__ __launch_bounds__(256) void kmm_kernel_wide_sym(const float* __restri
         v += CJ[(1 * jt_stage + jt) * 64 + l];
         v += CJ[(2 * jt_stage + jt) * 64 + l];
         v += CJ[(3 * jt_stage + jt) * 64 + l];
-        float* dst = slab + (((int64_t)st * jt_stage + jt) * 16 + 4 * (l >> 4)) * TS + (l & 15);
-        unsafeAtomicAdd(dst + 0 * TS, v.x);
-        unsafeAtomicAdd(dst + 1 * TS, v.y);
-        unsafeAtomicAdd(dst + 2 * TS, v.z);
-        unsafeAtomicAdd(dst + 3 * TS, v.w);
+        long long* dst = slab + (((int64_t)st * jt_stage + jt) * 16 + 4 * (l >> 4)) * TS + (l & 15);
+        const float sc = cscale[l & 15];
+        colside_add(dst + 0 * TS, v.x, sc);
+        colside_add(dst + 1 * TS, v.y, sc);
+        colside_add(dst + 2 * TS, v.z, sc);
+        colside_add(dst + 3 * TS, v.w, sc);
       }
     }
     if (EXTRA) {
@@ -168,9 +174,9 @@ __global__ __launch_bounds__(256) void kmm_kernel_wide_sym(const float* __restri
         const int r = p & 3;
         float add = r == 0 ? v.x : (r == 1 ? v.y : (r == 2 ? v.z : v.w));
         if (p >= 4) add = 0.f;
-        const int col = p < 4 ? 16 : (p >> 2);
+        const int col = 16;
         const int64_t j = ((int64_t)st * jt_stage + jt) * 16 + 4 * q + r;
-        unsafeAtomicAdd(cm ? slab + (int64_t)col * npad + j : slab + j * TS + col, add);
+        if (p < 4) colside_add(cm ? slab + (int64_t)col * npad + j : slab + j * TS + col, add, cscale[16]);
       }
     }
   };
@@ -424,7 +430,7 @@ Plan make_plan_wide_sym(int64_t npad, int ks, int extra) {
   Plan pl;
   pl.big = true;
   pl.sym = true;
-  pl.extra_slabs = 1;
+  pl.extra_slabs = 2;      // the int64 column-side slab
   const int nblk = (int)(npad / (64 * sh.rw));
   const int sb = 4 * sh.rw / sh.jt;
   pl.row_blocks = nblk;
@@ -438,14 +444,17 @@ Plan make_plan_wide_sym(int64_t npad, int ks, int extra) {
   return pl;
 }
 
-// Part must hold pl.splits + 1 slabs of npad x (16 + extra) floats; the last one is cleared here.
+// Part must hold pl.splits + 2 slabs of npad x (16 + extra) floats and kColmaxFloats more: the int64 column-side slab,
+// cleared here, and the column maxima, computed here (as in launch_sym).
 int launch_wide_sym(const Prepared& P, const Plan& pl, int extra, const f4* Vp, const float* Ep, float* Part, int cm,
                     hipStream_t stream) {
   const WideSymShape sh = wide_sym_shape(P.ks, extra);
   if (sh.jt < 1) return fail(EGP_ERR_ARG, "the symmetric wide kernel does not fit d = %d", P.d);
   ProfScope prof(kProfKmm, stream);
   const size_t slab = (size_t)P.npad * (16 + extra);
-  launch_zero_slab(Part + (size_t)pl.splits * slab, slab, stream);
+  float* cside = Part + (size_t)pl.splits * slab;
+  launch_zero_slab(cside, 2 * slab + kColmaxFloats, stream);
+  launch_col_absmax(Vp, Ep, P.npad, 1, extra, reinterpret_cast<unsigned*>(cside + 2 * slab), stream);
   if (sh.rw == 2) {
     if (extra) return launch_wide_sym_kind<2, 1>(P, pl, sh, Vp, Ep, Part, cm, stream);
     return launch_wide_sym_kind<2, 0>(P, pl, sh, Vp, Ep, Part, cm, stream);

@@ -188,6 +188,41 @@ def test_kmm_symmetric_mode_rows(egp, kind, n, d, t):
     assert _rel(got, base) <= 2e-5      # every row: same arithmetic, different summation order
 
 
+@pytest.mark.parametrize("n,d,t", [(33000, 11, 17), (40000, 14, 48), (33000, 8, 1), (33000, 40, 17)])
+def test_kmm_symmetric_mode_is_bit_reproducible(egp, n, d, t):
+    """The column-side sums travel between workgroups as 64-bit fixed-point atomic adds, which commute exactly: the
+    same call gives the same bits every time, also with other work in between, and for right-hand sides whose columns
+    differ by many orders of magnitude (each column has its own fixed-point scale)."""
+    rng = np.random.default_rng(n + d + t)
+    X = rng.uniform(-1, 1, (n, d)).astype(np.float32)
+    V = rng.standard_normal((n, t)).astype(np.float32)
+    V *= np.exp(rng.uniform(np.log(1e-12), np.log(1e12), t)).astype(np.float32)      # column scales 1e-12 .. 1e12
+    ls = np.exp(rng.uniform(np.log(0.3), np.log(3.0), d)).astype(np.float32)
+    try:
+        _set_mode(egp, 3)
+        first = _run(egp, X, V, ls, 1.3, 0.2, orc.MATERN32)
+        _run(egp, X, np.flipud(V).copy(), ls, 0.7, 0.1, orc.RBF)
+        for _ in range(3):
+            again = _run(egp, X, V, ls, 1.3, 0.2, orc.MATERN32)
+            assert np.array_equal(first, again)
+        _set_mode(egp, 0)
+        base = _run(egp, X, V, ls, 1.3, 0.2, orc.MATERN32)
+    finally:
+        _set_mode(egp, 0)
+    # column by column (their scales differ by 24 orders of magnitude): the one-sided kernel's result up to summation order
+    for c in range(t):
+        assert _rel(first[:, c], base[:, c]) <= 2e-5, c
+    # a zero column stays exactly zero beside non-zero ones
+    V0 = V.copy()
+    V0[:, 0] = 0.0
+    try:
+        _set_mode(egp, 3)
+        z = _run(egp, X, V0, ls, 1.3, 0.2, orc.MATERN32)
+    finally:
+        _set_mode(egp, 0)
+    assert np.all(z[:, 0] == 0.0) and (t == 1 or np.array_equal(z[:, 1:], first[:, 1:]))
+
+
 def test_kmm_symmetric_mode_falls_back_on_other_shapes(egp):
     """Shapes the symmetric kernels do not cover (small n, a group of 33 columns beyond d = 11) give the one-sided
     kernel's bits."""

@@ -266,6 +266,12 @@ def test_mbcg_in_symmetric_mode(egp, t):
         L.egp_set_kmm_mode(0)
     assert res["rel_resid"].max() <= 1e-3
     assert abs(res["iters"] - base["iters"]) <= 2
+    try:      # the symmetric kernels are order-independent: the whole solve repeats bit for bit
+        L.egp_set_kmm_mode(3)
+        res2 = egp.mbcg(Xd, Bd, ls, s, noise, kind, precond=P, max_iter=200, tol=1e-3)
+    finally:
+        L.egp_set_kmm_mode(0)
+    assert res2["iters"] == res["iters"] and bool((res2["U"] == res["U"]).all())
     U = res["U"].cpu().numpy().astype(np.float64)
     Ub = base["U"].cpu().numpy().astype(np.float64)
     assert np.linalg.norm(U - Ub) / np.linalg.norm(Ub) <= 5e-3
