@@ -21,6 +21,7 @@ sys.path.insert(0, ROOT)
 
 FP32_PEAK_TFLOPS = 157.3          # MI355X fp32 MFMA (= fp32 vector) peak
 HBM_PEAK_GBS = 8000.0
+ONE_SIDED = 3                     # EGP_KMM_FP32_ONE_SIDED: fp32 with every tile formed, for comparison with the default
 
 
 def flops_per_entry(d, t, kernel_type):
@@ -135,9 +136,9 @@ def main():
         return {"wall": wall, "kern_ms": k_ms / max(k_n, 1), "launches": k_n, "pack_ms": p_ms / args.steps}
 
     fpe = flops_per_entry(d, 16, w.kernel_type)
-    one = timed(0, args.warmup)                       # one-sided fp32 kernel: every tile of the n x n matrix formed
+    one = timed(ONE_SIDED, args.warmup)               # fp32 with every tile of the n x n matrix formed (for comparison)
     one_out = out.clone()
-    sym = timed(3, args.warmup)                       # symmetric fp32 mode: the headline
+    sym = timed(0, args.warmup)                       # the default fp32 mode (symmetric kernels at this size): the headline
     # flops the symmetric kernel executes per logical entry: distance + transform once per tile pair, the
     # contraction once per side; the diagonal block (and for an even block count the half-way block) one-sided
     npad = (n + 511) // 512 * 512
@@ -163,8 +164,9 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"C4: n={n}, d={d}, t=16 probe columns, RBF-ARD, 32-component clustered "
                                "mixture in [0,1]^11, one full egp_kmm call per step",
-                   "kmm_mode": "EGP_KMM_FP32_SYM: fp32 arithmetic, logical n^2 entries counted, every off-diagonal "
-                               "tile formed once and used for both output sides" if sym_used else "EGP_KMM_FP32"},
+                   "kmm_mode": "EGP_KMM_FP32 (the default): fp32 arithmetic, logical n^2 entries counted; at this size "
+                               "every off-diagonal tile is formed once and used for both output sides, column-side "
+                               "sums as 64-bit fixed-point atomic adds (bit-reproducible)" if sym_used else "EGP_KMM_FP32"},
         # achieved counts the flops the symmetric kernel has to execute (fpe_exec per logical entry); against the
         # one-sided count of flops_per_entry the same launch reads frac_one_sided_count (it may exceed 1)
         "roofline": {"bound": "mfma", "achieved": achieved_tflops, "peak": FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
@@ -180,7 +182,7 @@ def main():
             "ms_per_step": one["wall"] * 1e3 / args.steps, "kernel": "kmm_kernel", "kernel_ms": one["kern_ms"],
             "roofline_frac": fpe * n * n / (one["kern_ms"] * 1e-3) / 1e12 / FP32_PEAK_TFLOPS,
             "traffic": read_traffic(os.path.join(ROOT, "profiles", "kmm_kernel_c4_t16_pmc.txt")),
-            "note": "EGP_KMM_FP32, the library's default: every tile formed, summation order fixed (bit-reproducible)"},
+            "note": "EGP_KMM_FP32_ONE_SIDED: every tile formed, no use of the symmetry (kept for comparison)"},
     }
     sym_out = out.clone()
 
@@ -255,15 +257,15 @@ def main():
         egp.mbcg(X, B17, w.lengthscales, w.outputscale, w.noise, w.kernel_type, precond=P, max_iter=iters, tol=0.0)
         torch.cuda.synchronize()
         result["mbcg"]["s_per_iter_split_bf16_all_mode"] = (time.perf_counter() - t0) / iters
-        # and in the symmetric fp32 mode (t = 17: the 17th column on the VALU on both sides)
-        lib.egp_set_kmm_mode(3)
+        # and with the symmetry switched off (every tile formed)
+        lib.egp_set_kmm_mode(ONE_SIDED)
         egp.mbcg(X, B17, w.lengthscales, w.outputscale, w.noise, w.kernel_type, precond=P, max_iter=1, tol=0.0)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         res3 = egp.mbcg(X, B17, w.lengthscales, w.outputscale, w.noise, w.kernel_type, precond=P, max_iter=iters, tol=0.0)
         torch.cuda.synchronize()
-        result["mbcg"]["s_per_iter_symmetric_mode"] = (time.perf_counter() - t0) / iters
-        result["mbcg"]["rel_resid_max_after_symmetric_mode"] = float(res3["rel_resid"].max())
+        result["mbcg"]["s_per_iter_one_sided_mode"] = (time.perf_counter() - t0) / iters
+        result["mbcg"]["rel_resid_max_after_one_sided_mode"] = float(res3["rel_resid"].max())
         lib.egp_set_kmm_mode(0)
         result["piv_chol"] = {"s": pc_s, "steps_ms": pc_ms, "rank": k,
                               "gbs": pc_bytes / (pc_ms * 1e-3) / 1e9 if pc_ms > 0 else None}
@@ -301,13 +303,13 @@ def main():
             result["mbcg"]["full_solve_tol1_rank512"] = {
                 "precond_build_s": build512, "s": time.perf_counter() - t0, "iters": full3["iters"],
                 "rel_resid_max": float(full3["rel_resid"].max())}
-            lib.egp_set_kmm_mode(3)
+            lib.egp_set_kmm_mode(ONE_SIDED)
             t0 = time.perf_counter()
             full4 = egp.mbcg(X, B17, w.lengthscales, w.outputscale, w.noise, w.kernel_type, precond=P,
                              max_iter=w.max_iter, tol=w.tol)
             torch.cuda.synchronize()
             lib.egp_set_kmm_mode(0)
-            result["mbcg"]["full_solve_tol1_rank512_symmetric_mode"] = {
+            result["mbcg"]["full_solve_tol1_rank512_one_sided_mode"] = {
                 "s": time.perf_counter() - t0, "iters": full4["iters"], "rel_resid_max": float(full4["rel_resid"].max())}
         del P
         progress("C4 solver legs done")
@@ -326,14 +328,14 @@ def main():
                 egp.kmm(Xs, Bs, *hyp, out=os_)
             torch.cuda.synchronize()
             kmm_s = (time.perf_counter() - t0) / 20
-            lib.egp_set_kmm_mode(3)      # symmetric mode (applies from n_pad = 32768: C2; C1 runs the one-sided kernel)
+            lib.egp_set_kmm_mode(ONE_SIDED)      # (the symmetric kernels apply from n_pad = 32768: C2; C1 runs the one-sided kernel anyway)
             egp.kmm(Xs, Bs, *hyp, out=os_)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             for _ in range(20):
                 egp.kmm(Xs, Bs, *hyp, out=os_)
             torch.cuda.synchronize()
-            kmm_sym_s = (time.perf_counter() - t0) / 20
+            kmm_one_s = (time.perf_counter() - t0) / 20
             lib.egp_set_kmm_mode(0)
             Ps = egp.piv_chol_precond(Xs, *hyp, ws_.rank)
             egp.mbcg(Xs, Bs, *hyp, precond=Ps, max_iter=2, tol=0.0)
@@ -346,8 +348,8 @@ def main():
             result[name.lower()] = {
                 "workload": f"{name}: n={ws_.n}, d={ws_.d}, t={ws_.t}, rank {ws_.rank}, tol {ws_.tol}",
                 "kmm_s": kmm_s, "kmm_entries_per_s": ws_.n ** 2 / kmm_s,
-                "kmm_frac_fp32_peak": fk * ws_.n ** 2 / kmm_s / 1e12 / FP32_PEAK_TFLOPS,
-                "kmm_s_symmetric_mode": kmm_sym_s,
+                "kmm_s_one_sided_mode": kmm_one_s,
+                "kmm_frac_fp32_peak_one_sided_mode": fk * ws_.n ** 2 / kmm_one_s / 1e12 / FP32_PEAK_TFLOPS,
                 "solve_s": solve_s, "solve_iters": rs["iters"], "rel_resid_max": float(rs["rel_resid"].max()),
             }
             del Xs, Bs, os_, Ps
@@ -374,18 +376,18 @@ def main():
                 fn()
             torch.cuda.synchronize()
             leg[name + "_s"] = (time.perf_counter() - t0) / 3
-        lib.egp_set_kmm_mode(3)
+        lib.egp_set_kmm_mode(ONE_SIDED)
         egp.kmm(X3, V3, w3.lengthscales, w3.outputscale, w3.noise, w3.kernel_type, out=o3, ws=wsk)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(3):
             egp.kmm(X3, V3, w3.lengthscales, w3.outputscale, w3.noise, w3.kernel_type, out=o3, ws=wsk)
         torch.cuda.synchronize()
-        leg["kmm_s_symmetric_mode"] = (time.perf_counter() - t0) / 3
+        leg["kmm_s_one_sided_mode"] = (time.perf_counter() - t0) / 3
         lib.egp_set_kmm_mode(0)
         fk = flops_per_entry(w3.d, w3.t, w3.kernel_type)
         fg = fk - 2 * w3.t + w3.d * (2 * w3.t + 3)
-        leg["kmm_frac_fp32_peak"] = fk * w3.n ** 2 / leg["kmm_s"] / 1e12 / FP32_PEAK_TFLOPS
+        leg["kmm_frac_fp32_peak_one_sided_mode"] = fk * w3.n ** 2 / leg["kmm_s_one_sided_mode"] / 1e12 / FP32_PEAK_TFLOPS
         leg["kmm_grad_frac_fp32_peak"] = fg * w3.n ** 2 / leg["kmm_grad_s"] / 1e12 / FP32_PEAK_TFLOPS
         leg["workload"] = f"C3: n={w3.n}, d={w3.d}, t={w3.t}, RBF-ARD, all {w3.d} lengthscale derivatives"
         result["c3"] = leg
@@ -407,14 +409,14 @@ def main():
             egp.kmm(Xw, V16, lsw, 1.0, 0.1, 0, out=ow)
         torch.cuda.synchronize()
         kmm_s = (time.perf_counter() - t0) / 3
-        lib.egp_set_kmm_mode(3)
+        lib.egp_set_kmm_mode(ONE_SIDED)
         egp.kmm(Xw, V16, lsw, 1.0, 0.1, 0, out=ow)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(3):
             egp.kmm(Xw, V16, lsw, 1.0, 0.1, 0, out=ow)
         torch.cuda.synchronize()
-        kmm_sym_s = (time.perf_counter() - t0) / 3
+        kmm_one_s = (time.perf_counter() - t0) / 3
         lib.egp_set_kmm_mode(0)
         egp.kmm_grad_bilinear(Xw, Aw, Bw, lsw, 1.0, 0.1, 0)
         torch.cuda.synchronize()
@@ -426,8 +428,8 @@ def main():
         result["wide_d90"] = {
             "workload": f"n={nw_}, d={dw_}, uniform points, RBF-ARD; multiply at t=16, gradient forms at t={tw_}",
             "kmm_s": kmm_s, "kmm_entries_per_s": nw_ ** 2 / kmm_s,
-            "kmm_frac_fp32_peak": fk * nw_ ** 2 / kmm_s / 1e12 / FP32_PEAK_TFLOPS,
-            "kmm_s_symmetric_mode": kmm_sym_s, "kmm_entries_per_s_symmetric_mode": nw_ ** 2 / kmm_sym_s,
+            "kmm_s_one_sided_mode": kmm_one_s, "kmm_entries_per_s_one_sided_mode": nw_ ** 2 / kmm_one_s,
+            "kmm_frac_fp32_peak_one_sided_mode": fk * nw_ ** 2 / kmm_one_s / 1e12 / FP32_PEAK_TFLOPS,
             "grad_bilinear_s": bil_s,
         }
         del Xw, Aw, Bw, V16, ow

@@ -227,8 +227,15 @@ int egp_precond_apply(const egp_precond_t* P, int64_t n, float noise, const floa
                       float* Z, void* ws, size_t ws_bytes, void* stream);
 size_t egp_precond_apply_ws_bytes(int64_t n, int32_t t, int32_t rank);
 
-/* Arithmetic of the tile x V contraction inside the fused kernel (process-wide; default EGP_KMM_FP32).
- *   EGP_KMM_FP32        fp32 MFMA throughout: the reference mode, the one every reported fp32 figure uses.
+/* Arithmetic of the fused kernel (process-wide; default EGP_KMM_FP32). Every mode gives bit-reproducible results.
+ *   EGP_KMM_FP32        fp32 MFMA throughout: the reference mode, the one every reported fp32 figure uses. In a
+ *                       square product (egp_kmm, the solver, Lanczos, the likelihood) with n >= 32257 the symmetry
+ *                       of the kernel matrix is exploited (paper, Background: K is a covariance matrix): every tile
+ *                       off the block diagonal is formed once and used for both the row-side and the column-side
+ *                       output. The column-side sums travel between workgroups as 64-bit fixed-point atomic adds,
+ *                       which commute exactly, so the order of the adds does not show in the result. This covers
+ *                       d <= 355, groups of 1, 16 or 17 columns (1: d <= 31) and, up to d = 31, of 32 or 33 columns
+ *                       (33: d <= 11); every other shape forms every tile (the kernels of EGP_KMM_FP32_ONE_SIDED).
  *   EGP_KMM_SPLIT_BF16  the kernel entries and V are each split into a high and a low bf16 part and
  *                       contracted as k_hi v_hi + k_hi v_lo + k_lo v_hi on the bf16 MFMA with fp32 accumulation
  *                       (16 significant bits per factor); distances and the transform stay in fp32. Faster,
@@ -237,15 +244,11 @@ size_t egp_precond_apply_ws_bytes(int64_t n, int32_t t, int32_t rank);
  *   EGP_KMM_SPLIT_BF16_ALL  additionally the distance step: scaled points are carried as three bf16 parts
  *                       (24 significant bits, exact) and the six products above the fp32 rounding level are
  *                       accumulated in fp32 on the bf16 MFMA. Faster again; also reported separately.
- *   EGP_KMM_FP32_SYM    fp32 arithmetic as in EGP_KMM_FP32, and the symmetry of the kernel matrix exploited: in a
- *                       square product every tile off the block diagonal is formed once and used for both the
- *                       row-side and the column-side output (paper, Background: K is a covariance matrix). The
- *                       column-side sums leave the kernel as float atomic adds, so results agree with
- *                       EGP_KMM_FP32 up to summation order and their last bits are not reproducible from run to
- *                       run. Applies to n >= 32257 and d <= 355, to groups of 1, 16 or 17 columns (1: d <= 31) and, up to
- *                       d = 31, of 32 or 33 columns (33: d <= 11); other shapes run the EGP_KMM_FP32 kernels.
+ *   EGP_KMM_FP32_ONE_SIDED  fp32 arithmetic with every tile formed in every product (no use of the symmetry): the
+ *                       same results as EGP_KMM_FP32 up to summation order, 1.1x to 1.7x slower on large square
+ *                       products; kept for comparison and measurement.
  * Affects egp_kmm, egp_kmm_cross, egp_mbcg, egp_lanczos, egp_mll. Returns EGP_ERR_ARG for an unknown mode. */
-typedef enum { EGP_KMM_FP32 = 0, EGP_KMM_SPLIT_BF16 = 1, EGP_KMM_SPLIT_BF16_ALL = 2, EGP_KMM_FP32_SYM = 3 } egp_kmm_mode_t;
+typedef enum { EGP_KMM_FP32 = 0, EGP_KMM_SPLIT_BF16 = 1, EGP_KMM_SPLIT_BF16_ALL = 2, EGP_KMM_FP32_ONE_SIDED = 3 } egp_kmm_mode_t;
 int egp_set_kmm_mode(int32_t mode);
 int egp_get_kmm_mode(void);
 

@@ -167,14 +167,15 @@ def _check(rc):
         raise EgpError(rc, lib().egp_last_error().decode())
 
 
-KMM_MODES = {"fp32": 0, "split_bf16": 1, "split_bf16_all": 2, "fp32_sym": 3}
+KMM_MODES = {"fp32": 0, "split_bf16": 1, "split_bf16_all": 2, "fp32_one_sided": 3}
 
 
 def set_kmm_mode(mode):
     """Select the arithmetic of the fused multiply for every later call in this process (egp_set_kmm_mode):
-    "fp32" (default, bit-reproducible), "fp32_sym" (same arithmetic, every off-diagonal tile of a square product used
-    for both output sides: fastest fp32 path, last bits not reproducible), "split_bf16", "split_bf16_all" (contractions
-    on the bf16 MFMA through exact bf16 splits). Accepts the name or the integer code; returns the previous code."""
+    "fp32" (default: fp32 throughout; large square products use every off-diagonal tile for both output sides),
+    "fp32_one_sided" (fp32 with every tile formed: same results up to summation order, slower; for comparison),
+    "split_bf16", "split_bf16_all" (contractions on the bf16 MFMA through exact bf16 splits). All modes are
+    bit-reproducible. Accepts the name or the integer code; returns the previous code."""
     L = lib()
     code = KMM_MODES[mode] if isinstance(mode, str) else int(mode)
     prev = int(L.egp_get_kmm_mode())

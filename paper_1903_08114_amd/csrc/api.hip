@@ -106,7 +106,7 @@ const char* egp_last_error(void) { return g_err; }
 const char* egp_version(void) { return "0.1"; }
 
 int egp_set_kmm_mode(int32_t mode) {
-  if (mode < EGP_KMM_FP32 || mode > EGP_KMM_FP32_SYM) return fail(EGP_ERR_ARG, "unknown kmm mode %d", mode);
+  if (mode < EGP_KMM_FP32 || mode > EGP_KMM_FP32_ONE_SIDED) return fail(EGP_ERR_ARG, "unknown kmm mode %d", mode);
   g_kmm_mode.store(mode);
   return EGP_OK;
 }

@@ -321,12 +321,12 @@ int prepare_points(const float* X, int64_t n, const egp_hyper_t* h, void* ws, Pr
 namespace {
 
 Plan plan_for_mode(int64_t npad_rows, int64_t npad_cols, int ks, int d, int nb, int extra, bool square = false) {
-  if (ks > 8) {      // d > 31: fp32 wide kernels in every mode
-    if (kmm_mode() == EGP_KMM_FP32_SYM && square && wide_sym_applies(npad_rows, npad_cols, ks, nb, extra))
+  if (ks > 8) {      // d > 31: fp32 wide kernels in every mode, symmetric where that applies unless switched off
+    if (kmm_mode() != EGP_KMM_FP32_ONE_SIDED && square && wide_sym_applies(npad_rows, npad_cols, ks, nb, extra))
       return make_plan_wide_sym(npad_rows, ks, extra);
     return make_plan_wide(npad_rows, npad_cols, ks, nb, extra);
   }
-  if (kmm_mode() == EGP_KMM_FP32_SYM) {     // fp32 arithmetic; shapes the symmetric kernel does not cover run the plain one
+  if (kmm_mode() == EGP_KMM_FP32) {     // shapes the symmetric kernel does not cover run the one-sided one
     const int r = square ? sym_row_tiles(npad_rows, npad_cols, ks, nb, extra) : 0;
     if (r > 0) return make_plan_sym(npad_rows, r, ks, nb, extra);
     return make_plan(npad_rows, npad_cols, ks, nb, extra);

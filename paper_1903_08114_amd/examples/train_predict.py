@@ -115,8 +115,8 @@ def main():
     ap.add_argument("--d", type=int, default=8)
     ap.add_argument("--nq", type=int, default=1000)
     ap.add_argument("--kernel", type=int, default=0, help="0 RBF, 1 Matern-3/2, 2 Matern-5/2, 3 Matern-1/2")
-    ap.add_argument("--kmm-mode", default="fp32", choices=["fp32", "fp32_sym", "split_bf16", "split_bf16_all"],
-                    help="arithmetic of the fused multiply: fp32 (bit-reproducible), fp32_sym (fastest fp32 path), "
+    ap.add_argument("--kmm-mode", default="fp32", choices=["fp32", "fp32_one_sided", "split_bf16", "split_bf16_all"],
+                    help="arithmetic of the fused multiply: fp32 (default), fp32_one_sided (no use of the symmetry), "
                          "split_bf16, split_bf16_all")
     ap.add_argument("--rank", type=int, default=512,
                     help="preconditioner rank (the paper uses 100; here an iteration costs far more than applying the "

@@ -206,7 +206,7 @@ def test_plan_check_pins_a_shape_with_two_row_tiles_and_short_stages(lib):
 
 def test_python_mode_switch_by_name(lib):
     import paper_1903_08114_amd as egp
-    prev = egp.set_kmm_mode("fp32_sym")
+    prev = egp.set_kmm_mode("fp32_one_sided")
     try:
         assert lib.egp_get_kmm_mode() == 3
         assert egp.set_kmm_mode(prev) == 3

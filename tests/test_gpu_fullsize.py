@@ -46,7 +46,7 @@ def test_c4_kmm_full_size_sampled_rows(egp):
     for cols in (slice(1, 17), slice(0, 17)):
         V = np.ascontiguousarray(w.V[:, cols])
         ref = orc.kmm_rows(w.X, V, h, rows)
-        for mode in (0, 3):      # the one-sided default and the symmetric mode bench.py's headline leg runs in
+        for mode in (0, 3):      # the default (symmetric kernels at this size, bench.py's headline) and one-sided
             try:
                 L.egp_set_kmm_mode(mode)
                 out = egp.kmm(X, _cuda(V), w.lengthscales, w.outputscale, w.noise, w.kernel_type)

@@ -161,9 +161,9 @@ def test_kmm_split_bf16_c2_recipe_rows(egp, mode):
                                    (33000, 18, 17), (34000, 25, 16), (32768, 31, 17), (40000, 2, 33), (33000, 8, 1), (40000, 25, 1),
                                    (32768, 11, 18), (33000, 11, 33), (33281, 25, 32), (32768, 31, 32), (34000, 18, 33),
                                    (33000, 11, 65)])
-def test_kmm_symmetric_mode_rows(egp, kind, n, d, t):
-    """The symmetric fp32 mode (every off-diagonal tile used for the row-side and the column-side output) against
-    rows computed exactly by the oracle: even and odd block counts, rows at the block edges and around the half-way
+def test_kmm_symmetric_kernels_rows(egp, kind, n, d, t):
+    """The default fp32 mode at sizes where the symmetric kernels run (every off-diagonal tile used for the row-side
+    and the column-side output) against rows computed exactly by the oracle: even and odd block counts, rows at the block edges and around the half-way
     block, several column groups (1, 16, 17, 32, 33 columns, ragged ones), every stage shape; a 33-column group
     beyond d = 11 takes the one-sided kernel."""
     rng = np.random.default_rng(11 * n + d + t + kind)
@@ -175,21 +175,21 @@ def test_kmm_symmetric_mode_rows(egp, kind, n, d, t):
     rows[:len(edges)] = edges
     rows = np.unique(rows)
     ref = orc.kmm_rows(X, V, orc.Hyper(kind, ls, 1.3, 0.2), rows)
-    base = _run(egp, X, V, ls, 1.3, 0.2, kind)
+    got = _run(egp, X, V, ls, 1.3, 0.2, kind)
     try:
-        _set_mode(egp, 3)
-        got = _run(egp, X, V, ls, 1.3, 0.2, kind)
+        _set_mode(egp, 3)      # every tile formed, no use of the symmetry
+        base = _run(egp, X, V, ls, 1.3, 0.2, kind)
     finally:
         _set_mode(egp, 0)
     assert np.isfinite(got).all()
     err = _rel(got[rows], ref)
-    print(f"symmetric mode n={n} d={d} t={t} kind={kind}: rel err {err:.2e}; vs one-sided kernel {_rel(got, base):.2e}")
+    print(f"symmetric kernels n={n} d={d} t={t} kind={kind}: rel err {err:.2e}; vs one-sided kernel {_rel(got, base):.2e}")
     assert err <= KMM_TOL
     assert _rel(got, base) <= 2e-5      # every row: same arithmetic, different summation order
 
 
 @pytest.mark.parametrize("n,d,t", [(33000, 11, 17), (40000, 14, 48), (33000, 8, 1), (33000, 40, 17)])
-def test_kmm_symmetric_mode_is_bit_reproducible(egp, n, d, t):
+def test_kmm_symmetric_kernels_are_bit_reproducible(egp, n, d, t):
     """The column-side sums travel between workgroups as 64-bit fixed-point atomic adds, which commute exactly: the
     same call gives the same bits every time, also with other work in between, and for right-hand sides whose columns
     differ by many orders of magnitude (each column has its own fixed-point scale)."""
@@ -199,13 +199,12 @@ def test_kmm_symmetric_mode_is_bit_reproducible(egp, n, d, t):
     V *= np.exp(rng.uniform(np.log(1e-12), np.log(1e12), t)).astype(np.float32)      # column scales 1e-12 .. 1e12
     ls = np.exp(rng.uniform(np.log(0.3), np.log(3.0), d)).astype(np.float32)
     try:
-        _set_mode(egp, 3)
         first = _run(egp, X, V, ls, 1.3, 0.2, orc.MATERN32)
         _run(egp, X, np.flipud(V).copy(), ls, 0.7, 0.1, orc.RBF)
         for _ in range(3):
             again = _run(egp, X, V, ls, 1.3, 0.2, orc.MATERN32)
             assert np.array_equal(first, again)
-        _set_mode(egp, 0)
+        _set_mode(egp, 3)
         base = _run(egp, X, V, ls, 1.3, 0.2, orc.MATERN32)
     finally:
         _set_mode(egp, 0)
@@ -215,17 +214,13 @@ def test_kmm_symmetric_mode_is_bit_reproducible(egp, n, d, t):
     # a zero column stays exactly zero beside non-zero ones
     V0 = V.copy()
     V0[:, 0] = 0.0
-    try:
-        _set_mode(egp, 3)
-        z = _run(egp, X, V0, ls, 1.3, 0.2, orc.MATERN32)
-    finally:
-        _set_mode(egp, 0)
+    z = _run(egp, X, V0, ls, 1.3, 0.2, orc.MATERN32)
     assert np.all(z[:, 0] == 0.0) and (t == 1 or np.array_equal(z[:, 1:], first[:, 1:]))
 
 
-def test_kmm_symmetric_mode_falls_back_on_other_shapes(egp):
-    """Shapes the symmetric kernels do not cover (small n, a group of 33 columns beyond d = 11) give the one-sided
-    kernel's bits."""
+def test_kmm_one_sided_kernels_on_other_shapes(egp):
+    """Shapes the symmetric kernels do not cover (small n, a group of 33 columns beyond d = 11) run the one-sided
+    kernels in the default mode: same bits as with the symmetry switched off."""
     for n, d, t in ((3000, 11, 16), (33000, 18, 33)):
         rng = np.random.default_rng(n + d)
         X = rng.uniform(-1, 1, (n, d)).astype(np.float32)

@@ -86,11 +86,11 @@ def test_train_adam_tracks_the_oracle_loop(egp):
 
 
 @pytest.mark.parametrize("kind,tp", [(orc.MATERN32, 16), (orc.RBF, 15), (orc.RBF, 32)])
-def test_mll_in_symmetric_mode_matches_default_mode(egp, kind, tp):
-    """At a size where the symmetric kernels run (17, 16 and 33 columns in the solver), the likelihood step gives the
-    default mode's value and gradient up to summation order and the stopping point of the solver: same probes, same
-    preconditioner. The default mode is the one checked against the dense oracle above; n = 33000 is out of reach of
-    a dense factorisation."""
+def test_mll_with_symmetric_kernels_matches_one_sided(egp, kind, tp):
+    """At a size where the default mode runs the symmetric kernels (17, 16 and 33 columns in the solver), the
+    likelihood step gives the one-sided kernels' value and gradient up to summation order and the stopping point of
+    the solver: same probes, same preconditioner. The one-sided kernels are the ones checked against the dense oracle
+    above; n = 33000 is out of reach of a dense factorisation."""
     n, d, rank = 33000, 11, 30
     rng = np.random.default_rng(900 + kind + tp)
     X = rng.uniform(0, 1, (n, d)).astype(np.float32)
@@ -99,13 +99,13 @@ def test_mll_in_symmetric_mode_matches_default_mode(egp, kind, tp):
     s, noise = 1.1, 0.5
     w1, w2 = _cuda(rademacher(rng, (rank, tp))), _cuda(rademacher(rng, (n, tp)))
     Xd, yd = _cuda(X), _cuda(y)
-    base = egp.mll(Xd, yd, w1, w2, ls, s, noise, kind, rank=rank, max_iter=300, tol=1e-3)
+    got = egp.mll(Xd, yd, w1, w2, ls, s, noise, kind, rank=rank, max_iter=300, tol=1e-3)
     try:
-        egp.set_kmm_mode("fp32_sym")
-        got = egp.mll(Xd, yd, w1, w2, ls, s, noise, kind, rank=rank, max_iter=300, tol=1e-3)
+        egp.set_kmm_mode("fp32_one_sided")
+        base = egp.mll(Xd, yd, w1, w2, ls, s, noise, kind, rank=rank, max_iter=300, tol=1e-3)
     finally:
         egp.set_kmm_mode("fp32")
-    print(f"mll at n={n} kind={kind} tp={tp}: default {base['mll']:.3f} ({base['iters']} it), symmetric {got['mll']:.3f} "
+    print(f"mll at n={n} kind={kind} tp={tp}: one-sided {base['mll']:.3f} ({base['iters']} it), default {got['mll']:.3f} "
           f"({got['iters']} it)")
     assert got["rel_resid_max"] <= 1e-3 and base["rel_resid_max"] <= 1e-3
     assert abs(got["iters"] - base["iters"]) <= 2

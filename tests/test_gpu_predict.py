@@ -44,9 +44,10 @@ def test_kmm_cross_matches_oracle(egp, kind, nq, n, d, t):
     assert _rel(got, ref) <= KMM_TOL
 
 
-def test_kmm_cross_equal_sizes_in_symmetric_mode(egp):
-    """Two different point sets of the same (large) size are not a symmetric product: the symmetric mode must leave
-    such a call to the one-sided kernel. Checked against oracle rows and against the default mode's bits."""
+def test_kmm_cross_equal_sizes_is_not_taken_for_symmetric(egp):
+    """Two different point sets of the same (large) size are not a symmetric product: the default mode must leave
+    such a call to the one-sided kernel. Checked against oracle rows and against the bits of the mode that never
+    uses the symmetry."""
     nq = n = 33000
     d, t, kind = 11, 16, orc.RBF
     rng = np.random.default_rng(2024)
@@ -54,10 +55,10 @@ def test_kmm_cross_equal_sizes_in_symmetric_mode(egp):
     Xq = rng.uniform(-1, 1, (nq, d)).astype(np.float32)
     V = rng.standard_normal((n, t)).astype(np.float32)
     ls = np.exp(rng.uniform(np.log(0.4), np.log(2.5), d)).astype(np.float32)
-    base = egp.kmm_cross(_cuda(Xq), _cuda(X), _cuda(V), ls, 1.1, kind).cpu().numpy()
+    got = egp.kmm_cross(_cuda(Xq), _cuda(X), _cuda(V), ls, 1.1, kind).cpu().numpy()
     try:
-        egp.set_kmm_mode("fp32_sym")
-        got = egp.kmm_cross(_cuda(Xq), _cuda(X), _cuda(V), ls, 1.1, kind).cpu().numpy()
+        egp.set_kmm_mode("fp32_one_sided")
+        base = egp.kmm_cross(_cuda(Xq), _cuda(X), _cuda(V), ls, 1.1, kind).cpu().numpy()
     finally:
         egp.set_kmm_mode("fp32")
     assert np.array_equal(got, base)

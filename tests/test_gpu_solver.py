@@ -244,10 +244,10 @@ def test_mbcg_slq_logdet_from_gpu_coefficients(egp):
 
 
 @pytest.mark.parametrize("t", [16, 17, 1, 32, 33])
-def test_mbcg_in_symmetric_mode(egp, t):
-    """The symmetric fp32 mode inside the solver (column-major state, t = 16 takes the two-sided kernel): same
-    iterates as the one-sided kernel up to summation order, and a true residual (rows computed exactly by the
-    oracle) at the level the recurrence reports."""
+def test_mbcg_with_symmetric_kernels(egp, t):
+    """The solver at a size where the default mode runs the symmetric kernels (column-major state): same iterates as
+    with the one-sided kernels up to summation order, a true residual (rows computed exactly by the oracle) at the
+    level the recurrence reports, and the same bits when the solve is repeated."""
     n, d = 33000, 11
     rng = np.random.default_rng(77 + t)
     X = rng.uniform(0, 1, (n, d)).astype(np.float32)
@@ -257,20 +257,17 @@ def test_mbcg_in_symmetric_mode(egp, t):
     s, noise, kind = 1.0, 0.5, orc.RBF
     Xd, Bd = _cuda(X), _cuda(B)
     P = egp.piv_chol_precond(Xd, ls, s, noise, kind, 50)
-    base = egp.mbcg(Xd, Bd, ls, s, noise, kind, precond=P, max_iter=200, tol=1e-3)
+    res = egp.mbcg(Xd, Bd, ls, s, noise, kind, precond=P, max_iter=200, tol=1e-3)
     L = egp.lib()
     try:
-        L.egp_set_kmm_mode(3)
-        res = egp.mbcg(Xd, Bd, ls, s, noise, kind, precond=P, max_iter=200, tol=1e-3)
+        L.egp_set_kmm_mode(3)      # one-sided kernels
+        base = egp.mbcg(Xd, Bd, ls, s, noise, kind, precond=P, max_iter=200, tol=1e-3)
     finally:
         L.egp_set_kmm_mode(0)
     assert res["rel_resid"].max() <= 1e-3
     assert abs(res["iters"] - base["iters"]) <= 2
-    try:      # the symmetric kernels are order-independent: the whole solve repeats bit for bit
-        L.egp_set_kmm_mode(3)
-        res2 = egp.mbcg(Xd, Bd, ls, s, noise, kind, precond=P, max_iter=200, tol=1e-3)
-    finally:
-        L.egp_set_kmm_mode(0)
+    # the column-side sums are order-independent: the whole solve repeats bit for bit
+    res2 = egp.mbcg(Xd, Bd, ls, s, noise, kind, precond=P, max_iter=200, tol=1e-3)
     assert res2["iters"] == res["iters"] and bool((res2["U"] == res["U"]).all())
     U = res["U"].cpu().numpy().astype(np.float64)
     Ub = base["U"].cpu().numpy().astype(np.float64)
@@ -281,7 +278,7 @@ def test_mbcg_in_symmetric_mode(egp, t):
     assert true_res.max() <= 5e-3
 
 
-@pytest.mark.parametrize("mode", ["fp32", "fp32_sym"])
+@pytest.mark.parametrize("mode", ["fp32", "fp32_one_sided"])
 def test_lanczos_three_term_recurrence_at_size(egp, mode):
     """Lanczos (single vector) and block Lanczos at a size where the symmetric kernels run: the basis is orthonormal
     and Khat q_j = beta_{j-1} q_{j-1} + alpha_j q_j + beta_j q_{j+1} holds on rows of Khat Q^T computed exactly by the

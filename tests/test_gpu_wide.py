@@ -187,7 +187,7 @@ def test_solver_and_prediction_wide(egp, d):
 @pytest.mark.parametrize("n,d,t,kind", [(32768, 40, 16, orc.RBF), (33000, 90, 16, orc.MATERN32), (34000, 164, 16, orc.RBF),
                                          (33000, 300, 32, orc.MATERN52), (33281, 77, 16, orc.MATERN12),
                                          (33000, 90, 17, orc.RBF), (32768, 36, 17, orc.MATERN52), (33000, 200, 33, orc.MATERN32)])
-def test_kmm_wide_symmetric_mode_rows(egp, n, d, t, kind):
+def test_kmm_wide_symmetric_kernel_rows(egp, n, d, t, kind):
     """The symmetric fp32 mode beyond d = 31 (groups of 16 or 17 columns; wider groups fall back): rows computed
     exactly by the oracle, both row-tile shapes, every stage size, even and odd block counts; and every row against
     the one-sided kernel."""
@@ -199,11 +199,13 @@ def test_kmm_wide_symmetric_mode_rows(egp, n, d, t, kind):
     rows = np.unique(rows)
     ref = orc.kmm_rows(X, V, orc.Hyper(kind, ls, 1.1, 0.3), rows)
     Xd, Vd = _cuda(X), _cuda(V)
-    base = egp.kmm(Xd, Vd, ls, 1.1, 0.3, kind).cpu().numpy().astype(np.float64)
+    got = egp.kmm(Xd, Vd, ls, 1.1, 0.3, kind).cpu().numpy().astype(np.float64)
+    again = egp.kmm(Xd, Vd, ls, 1.1, 0.3, kind).cpu().numpy().astype(np.float64)
+    assert np.array_equal(got, again)      # order-independent column-side sums
     L = egp.lib()
     try:
-        L.egp_set_kmm_mode(3)
-        got = egp.kmm(Xd, Vd, ls, 1.1, 0.3, kind).cpu().numpy().astype(np.float64)
+        L.egp_set_kmm_mode(3)      # every tile formed, no use of the symmetry
+        base = egp.kmm(Xd, Vd, ls, 1.1, 0.3, kind).cpu().numpy().astype(np.float64)
     finally:
         L.egp_set_kmm_mode(0)
     assert np.isfinite(got).all()
@@ -213,8 +215,9 @@ def test_kmm_wide_symmetric_mode_rows(egp, n, d, t, kind):
     assert _rel(got, base) <= 2e-5
 
 
-def test_kmm_wide_symmetric_mode_falls_back(egp):
-    """d = 385 does not fit the symmetric wide kernel's LDS budget; 32 columns are not built for it: one-sided bits."""
+def test_kmm_wide_one_sided_on_other_shapes(egp):
+    """d = 385 does not fit the symmetric wide kernel's LDS budget; 32 columns are not built for it: the default mode
+    runs the one-sided kernel there (same bits as with the symmetry switched off)."""
     for d, t in ((385, 16), (90, 32)):
         X, V, ls = _inputs(d + t, 33000, d, t)
         Xd, Vd = _cuda(X), _cuda(V)
@@ -229,18 +232,18 @@ def test_kmm_wide_symmetric_mode_falls_back(egp):
 
 
 @pytest.mark.parametrize("t", [16, 17])
-def test_mbcg_wide_in_symmetric_mode(egp, t):
-    """Solver at d = 90 with 16 / 17 right-hand sides: the symmetric wide kernel with the column-major state arrays
-    gives the one-sided kernel's iterates up to summation order."""
+def test_mbcg_wide_with_symmetric_kernels(egp, t):
+    """Solver at d = 90 with 16 / 17 right-hand sides: the symmetric wide kernel (default mode at this size) with the
+    column-major state arrays gives the one-sided kernel's iterates up to summation order."""
     n, d = 33000, 90
     X, B, ls = _inputs(901, n, d, t)
     s, noise, kind = 1.0, 0.5, orc.RBF
     Xd, Bd = _cuda(X), _cuda(B)
-    base = egp.mbcg(Xd, Bd, ls, s, noise, kind, max_iter=12, tol=0.0)
+    res = egp.mbcg(Xd, Bd, ls, s, noise, kind, max_iter=12, tol=0.0)
     L = egp.lib()
     try:
-        L.egp_set_kmm_mode(3)
-        res = egp.mbcg(Xd, Bd, ls, s, noise, kind, max_iter=12, tol=0.0)
+        L.egp_set_kmm_mode(3)      # one-sided kernels
+        base = egp.mbcg(Xd, Bd, ls, s, noise, kind, max_iter=12, tol=0.0)
     finally:
         L.egp_set_kmm_mode(0)
     assert np.allclose(res["alphas"][:3], base["alphas"][:3], rtol=1e-4)
