@@ -78,7 +78,8 @@ typedef struct {
 
 /* out = Khat V = K(X,X) V + noise V, K never materialised (paper, Method, "Partitioned kernel MVMs":
  * row blocks of the kernel matrix are formed, multiplied and discarded; here a block lives in
- * registers). noise = 0 gives K V. t in 1..EGP_T_MAX. Asynchronous on `stream`. */
+ * registers). noise = 0 gives K V. t in 1..EGP_T_MAX. Asynchronous on `stream`. The same call gives the same
+ * bits every time (fixed summation orders; sums that cross workgroups are exact integer adds). */
 int egp_kmm(const float* X /*device n x d*/, int64_t n, const float* V /*device n x t*/, int32_t t,
             const egp_hyper_t* h /*host*/, float* out /*device n x t*/, void* ws, size_t ws_bytes,
             void* stream);
