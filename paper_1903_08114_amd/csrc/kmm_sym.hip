@@ -199,8 +199,8 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
     }
     if (EXTRA) {
       // JT = 4: thread (wave, lane) takes tile `wave`; sum over the four waves, then over the 16 lanes of the DPP row
-      // (point index p). Every lane then holds the four sums of its row q; lane p adds component p & 3 (p >= 4: a
-      // zero, elsewhere), so that no thread is masked off (a divergent tail here cost the whole kernel ~60 registers).
+      // (point index p). Every lane then holds the four sums of its row q; lanes p < 4 add component p. (The threads
+      // stay uniform up to the add itself: a flush tail limited to some of the waves cost the kernel ~60 registers.)
       static_assert(!EXTRA || JT == 4, "one tile per wave in the flush of the 17th column");
       f4 v = CJE[0][wave][lane];
       v += CJE[1][wave][lane];
@@ -212,17 +212,12 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
       v.w = row_sum16(v.w);
       const int r = p & 3;
       float add = r == 0 ? v.x : (r == 1 ? v.y : (r == 2 ? v.z : v.w));
-      if (p >= 4) add = 0.f;
-      // the zero addends go to distinct elements of the same rows (columns 1..3): lanes of one instruction that
-      // hit one address are serialised (measured: 685 ms against 450 ms per launch)
       const int64_t j = ((int64_t)st * JT + wave) * 16 + 4 * q + r;
       if constexpr (NB > 0) {
         const int col = 16 * NB;
         if (p < 4) colside_add(cm ? slab + (int64_t)col * npad + j : slab + j * TS + col, add, cscale[16 * NB]);
       } else {
-        // a single column: the slab has no other elements to park the zeros on, and this shape has registers to
-        // spare for a masked add (slab is [npad] in both layouts)
-        if (p < 4) colside_add(slab + j, add, cscale[0]);
+        if (p < 4) colside_add(slab + j, add, cscale[0]);      // a single column: the slab is [npad] in both layouts
       }
     }
   };

@@ -160,8 +160,8 @@ __global__ __launch_bounds__(256) void kmm_kernel_wide_sym(const float* __restri
       }
     }
     if (EXTRA) {
-      // per tile: sum over the four waves, then over the 16 lanes of the DPP row (point index p); lane p adds
-      // component p & 3, lanes p >= 4 a zero to a distinct element (no lane masked off, no address hit twice)
+      // per tile: sum over the four waves, then over the 16 lanes of the DPP row (point index p); lanes p < 4 add
+      // component p
       for (int jt = wave; jt < jt_stage; jt += 4) {      // wave-uniform
         f4 v = CJE[(0 * jt_stage + jt) * 64 + lane];
         v += CJE[(1 * jt_stage + jt) * 64 + lane];
@@ -173,7 +173,6 @@ __global__ __launch_bounds__(256) void kmm_kernel_wide_sym(const float* __restri
         v.w = row_sum16w(v.w);
         const int r = p & 3;
         float add = r == 0 ? v.x : (r == 1 ? v.y : (r == 2 ? v.z : v.w));
-        if (p >= 4) add = 0.f;
         const int col = 16;
         const int64_t j = ((int64_t)st * jt_stage + jt) * 16 + 4 * q + r;
         if (p < 4) colside_add(cm ? slab + (int64_t)col * npad + j : slab + j * TS + col, add, cscale[16]);
