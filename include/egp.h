@@ -234,7 +234,8 @@ size_t egp_precond_apply_ws_bytes(int64_t n, int32_t t, int32_t rank);
  *                       of the kernel matrix is exploited (paper, Background: K is a covariance matrix): every tile
  *                       off the block diagonal is formed once and used for both the row-side and the column-side
  *                       output. The column-side sums travel between workgroups as 64-bit fixed-point atomic adds,
- *                       which commute exactly, so the order of the adds does not show in the result. This covers
+ *                       which commute exactly, so the order of the adds does not show in the result (one unit is
+ *                       2^-61 of the column's sum of |V|: far below the fp32 rounding of the sums themselves). This covers
  *                       d <= 355, groups of 1, 16 or 17 columns (1: d <= 31) and, up to d = 31, of 32 or 33 columns
  *                       (33: d <= 11); every other shape forms every tile (the kernels of EGP_KMM_FP32_ONE_SIDED).
  *   EGP_KMM_SPLIT_BF16  the kernel entries and V are each split into a high and a low bf16 part and

@@ -149,19 +149,19 @@ void launch_pack_rhs(const float* V, int64_t n, int64_t npad, int t, int c0, int
 }
 
 // out[row][c0 + c] = s * sum_split Part[split][row][c] + noise * V[row][c0 + c]. After a symmetric kernel the
-// column-side sums (cside: int64 fixed point [row][c], scale from colmax, see colside_exp) are added as well.
+// column-side sums (cside: int64 fixed point [row][c], scale from colsum, see colside_exp) are added as well.
 __global__ __launch_bounds__(256) void kmm_epilogue(const float* __restrict__ Part, int splits, int64_t npad,
                                                     int ts, const float* __restrict__ V, int64_t n, int t,
                                                     int c0, int tg, float s, float noise,
                                                     float* __restrict__ out, const long long* __restrict__ cside,
-                                                    const unsigned* __restrict__ colmax) {
+                                                    const unsigned* __restrict__ colsum) {
   int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (g >= n * tg) return;
   const int64_t row = g / tg;
   const int c = (int)(g % tg);
   float acc = 0.f;
   for (int sp = 0; sp < splits; ++sp) acc += Part[((int64_t)sp * npad + row) * ts + c];
-  if (cside != nullptr) acc += colside_value(cside[row * ts + c], colside_exp(colmax[c], npad));
+  if (cside != nullptr) acc += colside_value(cside[row * ts + c], colside_exp(colsum[c]));
   const int64_t o = row * t + c0 + c;
   out[o] = V ? __builtin_fmaf(s, acc, noise * V[o]) : s * acc;
 }
@@ -205,10 +205,10 @@ __global__ __launch_bounds__(256) void kmm_epilogue_cm(const float* __restrict__
                                                        float s, float noise, float* __restrict__ out,
                                                        float* __restrict__ dot_part, int dot_ld,
                                                        const long long* __restrict__ cside,
-                                                       const unsigned* __restrict__ colmax) {
+                                                       const unsigned* __restrict__ colsum) {
   __shared__ float red[4];
   const int c = blockIdx.y;
-  const int ce = cside != nullptr ? colside_exp(colmax[c], npad) : 0;
+  const int ce = cside != nullptr ? colside_exp(colsum[c]) : 0;
   const float4* v4 = reinterpret_cast<const float4*>(V + (int64_t)c * ld);
   float4* o4 = reinterpret_cast<float4*>(out + (int64_t)c * ld);
   float acc = 0.f;
@@ -429,7 +429,7 @@ size_t kmm_cross_ws_bytes(int64_t n_rows, int64_t n_cols, int t) {
   b += round_up((size_t)pcol * nb * 16 * sizeof(float), 256);                    // Vp
   b += round_up((size_t)pcol * sizeof(float), 256);                              // Ep
   // Part (+2 slabs and the column maxima: column-side region of the symmetric kernels)
-  b += round_up(((size_t)(splits + 2) * prow * widest_ts(t) + kmm_detail::kColmaxFloats) * sizeof(float), 256);
+  b += round_up(((size_t)(splits + 2) * prow * widest_ts(t) + kmm_detail::kColsideAuxFloats) * sizeof(float), 256);
   b += round_up((size_t)pcol * nb * 32 * sizeof(float), 256);                    // split V of the all-bf16 mode
   return b;
 }
@@ -455,7 +455,7 @@ int kmm_cross(const Prepared& P, const Prepared& Q, const float* V, int t, float
   float* Ep = reinterpret_cast<float*>(w);
   w += round_up((size_t)npad * sizeof(float), 256);
   float* Part = reinterpret_cast<float*>(w);
-  w += round_up(((size_t)(splits_max + 2) * Q.npad * widest_ts(t) + kColmaxFloats) * sizeof(float), 256);
+  w += round_up(((size_t)(splits_max + 2) * Q.npad * widest_ts(t) + kColsideAuxFloats) * sizeof(float), 256);
   void* Vb = w;
 
   int c0 = 0;
@@ -520,7 +520,7 @@ int kmm_core_cm(const Prepared& P, const float* V, int t, float* out, void* ws2,
   w += round_up((size_t)npad * (nb > 0 ? nb : 1) * 16 * sizeof(float), 256);
   w += round_up((size_t)npad * sizeof(float), 256);      // the row-major path's extra-column buffer (unused here)
   float* Part = reinterpret_cast<float*>(w);
-  w += round_up(((size_t)(splits_max + 2) * npad * widest_ts(t) + kColmaxFloats) * sizeof(float), 256);
+  w += round_up(((size_t)(splits_max + 2) * npad * widest_ts(t) + kColsideAuxFloats) * sizeof(float), 256);
   void* Vb = w;
   if (nb > 0) {
     ProfScope prof(kProfPack, stream);

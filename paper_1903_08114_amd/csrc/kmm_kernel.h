@@ -42,15 +42,15 @@ __device__ __forceinline__ void set_unit_diagonal(V4& k, int q, int p) {
 
 // Column-side sums of the symmetric kernels: 64-bit fixed point, so that the atomic adds from different workgroups
 // commute exactly and the result does not depend on their order (float atomics would make the last bits vary from
-// run to run). Column c of the right-hand sides gets the scale 2^e_c with e_c chosen from max_i |V_ic| (colmax, float
-// bits) such that n_pad * max|V| * 2^e_c <= 2^61: kernel values are at most 1, so no sum of contributions can leave
-// the int64 range, and one unit is 2^-61 of that bound (2^-37 or less of the fp32 rounding level of the result).
-__device__ __forceinline__ int colside_exp(unsigned maxbits, int64_t npad) {
-  int eb = (int)((maxbits >> 23) & 0xffu) - 127;      // max|V| < 2^(eb + 1)
+// run to run). Column c of the right-hand sides gets the scale 2^e_c with e_c chosen from S_c = sum_i |V_ic| (colsum,
+// a float computed in a fixed order) such that S_c * 2^e_c <= 2^61: kernel values are at most 1, so no sum of
+// contributions can leave the int64 range, and one unit is 2^-61 of that bound. A column-side sum of ~2000
+// contributions is therefore exact to 2^-50 S_c, against the 2^-24 sum_i |k_ij V_ic| of an fp32 accumulation.
+__device__ __forceinline__ int colside_exp(unsigned sumbits) {
+  int eb = (int)((sumbits >> 23) & 0xffu) - 127;      // S_c < 2^(eb + 1)
   if (eb < -126) eb = -126;
-  const int lg = 64 - __builtin_clzll((unsigned long long)(npad - 1));      // npad <= 2^lg
-  const int e = 60 - eb - lg;
-  return e > 120 ? 120 : e;      // never below -99: a float scale exists either way
+  const int e = 60 - eb;
+  return e > 120 ? 120 : e;      // never below -68: a float scale exists either way
 }
 __device__ __forceinline__ float colside_scale(int e) { return __uint_as_float((unsigned)(e + 127) << 23); }
 __device__ __forceinline__ float colside_value(long long sum, int e) {      // sum * 2^-e, rounded once to fp32
@@ -396,11 +396,13 @@ int launch_wide(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, in
                 float* Part, int cm, hipStream_t stream);
 // defined in kmm_sym.hip: square products that use every off-diagonal tile twice
 void launch_zero_slab(float* slab, size_t floats, hipStream_t stream);
-void launch_col_absmax(const f4* Vp, const float* Ep, int64_t npad, int nb, int extra, unsigned* colmax,
-                       hipStream_t stream);
+void launch_col_abs_sums(const f4* Vp, const float* Ep, int64_t npad, int nb, int extra, float* aux,
+                         hipStream_t stream);
 // The column-side region of the partial-sum buffer, after the pl.splits row-side slabs: an int64 slab (the room of
-// two float slabs) followed by the per-column maxima (kColmaxFloats floats of room).
-constexpr int kColmaxFloats = 64;
+// two float slabs) followed by kColsideAuxFloats floats: the per-column sums of |V| (first 64) and the per-wave
+// partial sums they are reduced from (kColsumBlocks blocks x 4 waves x 17).
+constexpr int kColsumBlocks = 256;
+constexpr int kColsideAuxFloats = 64 + kColsumBlocks * 4 * 17;
 int sym_row_tiles(int64_t npad_rows, int64_t npad_cols, int ks, int nb, int extra);
 Plan make_plan_sym(int64_t npad, int r, int ks, int nb, int extra);
 int launch_sym(const Prepared& P, const Plan& pl, int nb, int extra, const f4* Vp, const float* Ep, float* Part, int cm,

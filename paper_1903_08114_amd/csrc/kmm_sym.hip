@@ -156,7 +156,7 @@ __global__ __launch_bounds__(256, 2) void kmm_kernel_sym(const float* __restrict
   // the column-side sums of stage st (absolute), one partial per wave in CJ, leave as atomic adds into the extra slab
   long long* slab = reinterpret_cast<long long*>(Part + (int64_t)gridDim.y * npad * TS);
   if (tid < TS)
-    cscale[tid] = colside_scale(colside_exp(reinterpret_cast<const unsigned*>(slab + npad * TS)[tid], npad));
+    cscale[tid] = colside_scale(colside_exp(reinterpret_cast<const unsigned*>(slab + npad * TS)[tid]));
   // (visible to every thread after the barrier that follows the first stage's loads)
   auto flush = [&](int st) {
     if constexpr (NB == 0) {
@@ -468,38 +468,52 @@ void launch_zero_slab(float* slab, size_t floats, hipStream_t stream) {      // 
   hipLaunchKernelGGL(zero_slab, dim3((unsigned)blocks), dim3(256), 0, stream, reinterpret_cast<f4*>(slab), count);
 }
 
-// colmax[16 nb + p] = max over the points of |V| in column p of block nb, colmax[16 nb_count] the same for the extra
-// column, as float bits (non-negative floats order like unsigned integers, so an integer atomic max is exact and
-// independent of the order). colmax must be zero on entry. Every thread walks elements of one (block, lane) class.
-__global__ __launch_bounds__(256) void col_absmax(const f4* __restrict__ Vp, const float* __restrict__ Ep, int64_t npad,
-                                                  int nb_count, int extra, unsigned* __restrict__ colmax) {
-  const int lane = threadIdx.x & 63;
+// aux[16 nb + p] = sum over the points of |V| in column p of block nb, aux[16 nb_count] the same for the extra column
+// (slightly inflated: they only serve as bounds). Two steps with fixed summation orders, so that the value, and with
+// it the fixed-point scale of the column, is the same on every run: per-wave partial sums (every thread walks the
+// elements of one (block, lane) class), then one thread per column adds the partials up.
+__global__ __launch_bounds__(256) void col_abs_partial(const f4* __restrict__ Vp, const float* __restrict__ Ep,
+                                                       int64_t npad, int nb_count, int extra, float* __restrict__ part) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t stride = (int64_t)gridDim.x * 256;      // a multiple of 128: block and lane of an element stay fixed
+  float* mine = part + ((int64_t)blockIdx.x * 4 + wave) * 17;
+  float m = 0.f;
   if (nb_count > 0) {
     const int64_t total = (npad >> 4) * nb_count * 64;
-    const int64_t g0 = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    float m = 0.f;
-    for (int64_t g = g0; g < total; g += stride) {
+    for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < total; g += stride) {
       const f4 v = Vp[g];
-      m = __builtin_fmaxf(m, __builtin_fmaxf(__builtin_fmaxf(__builtin_fabsf(v.x), __builtin_fabsf(v.y)),
-                                             __builtin_fmaxf(__builtin_fabsf(v.z), __builtin_fabsf(v.w))));
+      m += (__builtin_fabsf(v.x) + __builtin_fabsf(v.y)) + (__builtin_fabsf(v.z) + __builtin_fabsf(v.w));
     }
-    m = __builtin_fmaxf(m, __shfl_xor(m, 16));
-    m = __builtin_fmaxf(m, __shfl_xor(m, 32));
-    const int nb = (int)((g0 >> 6) % nb_count);
-    if (lane < 16 && g0 < total) atomicMax(colmax + 16 * nb + lane, __float_as_uint(m));
+    m += __shfl_xor(m, 16);
+    m += __shfl_xor(m, 32);
   }
+  if (lane < 16) mine[lane] = m;      // column lane of block (blockIdx.x * 4 + wave) % nb_count
+  float e = 0.f;
   if (extra) {
-    float m = 0.f;
-    for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < npad; g += stride) m = __builtin_fmaxf(m, __builtin_fabsf(Ep[g]));
+    for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < npad; g += stride) e += __builtin_fabsf(Ep[g]);
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) m = __builtin_fmaxf(m, __shfl_xor(m, off));
-    if (lane == 0) atomicMax(colmax + 16 * nb_count, __float_as_uint(m));
+    for (int off = 32; off >= 1; off >>= 1) e += __shfl_xor(e, off);
   }
+  if (lane == 0) mine[16] = e;
 }
-void launch_col_absmax(const f4* Vp, const float* Ep, int64_t npad, int nb, int extra, unsigned* colmax,
-                       hipStream_t stream) {
-  hipLaunchKernelGGL(col_absmax, dim3(256), dim3(256), 0, stream, Vp, Ep, npad, nb, extra, colmax);
+__global__ __launch_bounds__(64) void col_abs_final(const float* __restrict__ part, int waves, int nb_count, int extra,
+                                                    float* __restrict__ colsum) {
+  const int c = threadIdx.x;
+  float s = 0.f;
+  if (c < 16 * nb_count) {
+    const int nb = c >> 4, p = c & 15;
+    for (int w = nb; w < waves; w += nb_count) s += part[(int64_t)w * 17 + p];
+  } else if (c == 16 * nb_count && extra) {
+    for (int w = 0; w < waves; ++w) s += part[(int64_t)w * 17 + 16];
+  } else {
+    return;
+  }
+  colsum[c] = s * 1.001f;      // covers the rounding of the sums above
+}
+void launch_col_abs_sums(const f4* Vp, const float* Ep, int64_t npad, int nb, int extra, float* aux,
+                         hipStream_t stream) {
+  hipLaunchKernelGGL(col_abs_partial, dim3(kColsumBlocks), dim3(256), 0, stream, Vp, Ep, npad, nb, extra, aux + 64);
+  hipLaunchKernelGGL(col_abs_final, dim3(1), dim3(64), 0, stream, aux + 64, kColsumBlocks * 4, nb, extra, aux);
 }
 
 // Row tiles per wave of the symmetric kernel for this shape, or 0 where it does not apply. Eight row tiles fit the
@@ -531,15 +545,15 @@ Plan make_plan_sym(int64_t npad, int r, int ks, int nb, int extra) {
   return pl;
 }
 
-// Part must hold pl.splits + 2 slabs of npad x (16 nb + extra) floats and kColmaxFloats more: the room of the last two
-// slabs is the int64 slab of the column-side sums, cleared here, followed by the column maxima, computed here.
+// Part must hold pl.splits + 2 slabs of npad x (16 nb + extra) floats and kColsideAuxFloats more: the room of the last
+// two slabs is the int64 slab of the column-side sums, cleared here, followed by the column sums of |V|, computed here.
 int launch_sym(const Prepared& P, const Plan& pl, int nb, int extra, const f4* Vp, const float* Ep, float* Part, int cm,
                hipStream_t stream) {
   ProfScope prof(kProfKmm, stream);
   const size_t slab = (size_t)P.npad * (16 * nb + extra);
   float* cside = Part + (size_t)pl.splits * slab;
-  launch_zero_slab(cside, 2 * slab + kColmaxFloats, stream);      // npad is a multiple of 512: a multiple of 4 floats
-  launch_col_absmax(Vp, Ep, P.npad, nb, extra, reinterpret_cast<unsigned*>(cside + 2 * slab), stream);
+  launch_zero_slab(cside, 2 * slab, stream);      // npad is a multiple of 512: a multiple of 4 floats
+  launch_col_abs_sums(Vp, Ep, P.npad, nb, extra, cside + 2 * slab, stream);
   switch (P.ks) {
     case 1: return launch_sym_kind<1>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
     case 2: return launch_sym_kind<2>(P, pl, nb, extra, Vp, Ep, Part, cm, stream);

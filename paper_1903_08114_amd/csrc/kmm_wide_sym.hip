@@ -132,7 +132,7 @@ __global__ __launch_bounds__(256) void kmm_kernel_wide_sym(const float* __restri
   __shared__ float cscale[18];
   long long* slab = reinterpret_cast<long long*>(Part + (int64_t)gridDim.y * npad * TS);
   if (tid < TS)
-    cscale[tid] = colside_scale(colside_exp(reinterpret_cast<const unsigned*>(slab + npad * TS)[tid], npad));
+    cscale[tid] = colside_scale(colside_exp(reinterpret_cast<const unsigned*>(slab + npad * TS)[tid]));
   auto flush = [&](int st) {
     if (cm) {
       const int c = tid >> 4, jrow = tid & 15;
@@ -443,8 +443,8 @@ Plan make_plan_wide_sym(int64_t npad, int ks, int extra) {
   return pl;
 }
 
-// Part must hold pl.splits + 2 slabs of npad x (16 + extra) floats and kColmaxFloats more: the int64 column-side slab,
-// cleared here, and the column maxima, computed here (as in launch_sym).
+// Part must hold pl.splits + 2 slabs of npad x (16 + extra) floats and kColsideAuxFloats more: the int64 column-side
+// slab, cleared here, and the column sums of |V|, computed here (as in launch_sym).
 int launch_wide_sym(const Prepared& P, const Plan& pl, int extra, const f4* Vp, const float* Ep, float* Part, int cm,
                     hipStream_t stream) {
   const WideSymShape sh = wide_sym_shape(P.ks, extra);
@@ -452,8 +452,8 @@ int launch_wide_sym(const Prepared& P, const Plan& pl, int extra, const f4* Vp, 
   ProfScope prof(kProfKmm, stream);
   const size_t slab = (size_t)P.npad * (16 + extra);
   float* cside = Part + (size_t)pl.splits * slab;
-  launch_zero_slab(cside, 2 * slab + kColmaxFloats, stream);
-  launch_col_absmax(Vp, Ep, P.npad, 1, extra, reinterpret_cast<unsigned*>(cside + 2 * slab), stream);
+  launch_zero_slab(cside, 2 * slab, stream);
+  launch_col_abs_sums(Vp, Ep, P.npad, 1, extra, cside + 2 * slab, stream);
   if (sh.rw == 2) {
     if (extra) return launch_wide_sym_kind<2, 1>(P, pl, sh, Vp, Ep, Part, cm, stream);
     return launch_wide_sym_kind<2, 0>(P, pl, sh, Vp, Ep, Part, cm, stream);

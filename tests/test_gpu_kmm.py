@@ -218,6 +218,34 @@ def test_kmm_symmetric_kernels_are_bit_reproducible(egp, n, d, t):
     assert np.all(z[:, 0] == 0.0) and (t == 1 or np.array_equal(z[:, 1:], first[:, 1:]))
 
 
+def test_kmm_symmetric_kernels_keep_small_entries_beside_an_outlier(egp):
+    """One entry of every right-hand-side column is 10^12 times the others, at a point so far from all others that
+    its kernel values with them vanish: no other row's result depends on it. The fixed-point scale of the column-side
+    sums comes from the column's sum of absolute values, so one unit is 2^-61 of about that entry (5e-7 here) and the
+    other rows still agree with the one-sided kernel entry by entry at fp32 summation-order level. (A scale taken from
+    n * max |V| would put the unit at 1e-2.)"""
+    n, d, t = 33000, 3, 16
+    rng = np.random.default_rng(99)
+    X = rng.uniform(-1, 1, (n, d)).astype(np.float32)
+    X[12345] = 10.0
+    V = rng.standard_normal((n, t)).astype(np.float32)
+    V[12345, :] = 1e12
+    ls = np.full(d, 0.5, np.float32)
+    got = _run(egp, X, V, ls, 1.0, 0.1, orc.RBF)
+    try:
+        _set_mode(egp, 3)
+        base = _run(egp, X, V, ls, 1.0, 0.1, orc.RBF)
+    finally:
+        _set_mode(egp, 0)
+    others = np.arange(n) != 12345
+    scale = np.abs(base[others]).mean()
+    assert scale < 1e3      # the outlier has not leaked into the other rows
+    worst = np.abs(got[others] - base[others]) / (3e-5 * np.abs(base[others]) + 3e-5 * scale)
+    print("outlier test: mean |entry| %.3g, worst difference ratio %.3g" % (scale, worst.max()))
+    assert worst.max() <= 1.0
+    assert abs(got[12345, 0] - base[12345, 0]) <= 1e-5 * abs(base[12345, 0])
+
+
 def test_kmm_one_sided_kernels_on_other_shapes(egp):
     """Shapes the symmetric kernels do not cover (small n, a group of 33 columns beyond d = 11) run the one-sided
     kernels in the default mode: same bits as with the symmetry switched off."""
