@@ -246,6 +246,22 @@ def test_kmm_symmetric_kernels_keep_small_entries_beside_an_outlier(egp):
     assert abs(got[12345, 0] - base[12345, 0]) <= 1e-5 * abs(base[12345, 0])
 
 
+@pytest.mark.parametrize("ls_value,bound", [(0.3, 3e-6), (0.1, 1.5e-5), (0.05, 5e-5)])
+def test_kmm_accuracy_envelope_at_short_lengthscales(egp, ls_value, bound):
+    """The distance step is the norm expansion accumulated in fp32: its error grows with the squared norm of the
+    centred, scaled points, i.e. with (extent / lengthscale)^2. The figures the design notes quote, with head room."""
+    n, d, t = 4000, 3, 16
+    rng = np.random.default_rng(5)
+    X = rng.uniform(-1, 1, (n, d)).astype(np.float32)
+    V = rng.standard_normal((n, t)).astype(np.float32)
+    ls = np.full(d, ls_value, np.float32)
+    ref = orc.kmm(X, V, orc.Hyper(orc.RBF, ls, 1.0, 0.0))
+    got = _run(egp, X, V, ls, 1.0, 0.0, orc.RBF)
+    err = _rel(got, ref)
+    print(f"lengthscale {ls_value}: rel err {err:.2e}")
+    assert err <= bound and err <= KMM_TOL
+
+
 def test_kmm_one_sided_kernels_on_other_shapes(egp):
     """Shapes the symmetric kernels do not cover (small n, a group of 33 columns beyond d = 11) run the one-sided
     kernels in the default mode: same bits as with the symmetry switched off."""
