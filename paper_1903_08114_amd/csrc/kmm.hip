@@ -474,7 +474,7 @@ int kmm_cross(const Prepared& P, const Prepared& Q, const float* V, int t, float
         hipLaunchKernelGGL(pack_rhs_cm, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, V + c0 * v_ld, v_ld,
                            npad, tg - extra, nb, Vp, P.n);
       if (extra) {
-        EGP_HIP(hipMemsetAsync(Ep, 0, npad * sizeof(float), stream));
+        launch_zero_slab(Ep, (size_t)npad, stream);      // a fill kernel, not a memset node (the stream may be captured)
         EGP_HIP(hipMemcpyAsync(Ep, V + (int64_t)(c0 + tg - 1) * v_ld, P.n * sizeof(float), hipMemcpyDeviceToDevice,
                                stream));
       }

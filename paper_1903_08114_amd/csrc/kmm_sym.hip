@@ -471,7 +471,7 @@ void launch_zero_slab(float* slab, size_t floats, hipStream_t stream) {      // 
 // aux[16 nb + p] = sum over the points of |V| in column p of block nb, aux[16 nb_count] the same for the extra column
 // (slightly inflated: they only serve as bounds). Two steps with fixed summation orders, so that the value, and with
 // it the fixed-point scale of the column, is the same on every run: per-wave partial sums (every thread walks the
-// elements of one (block, lane) class), then one thread per column adds the partials up.
+// elements of one (block, lane) class), then one wave per column adds the partials up.
 __global__ __launch_bounds__(256) void col_abs_partial(const f4* __restrict__ Vp, const float* __restrict__ Ep,
                                                        int64_t npad, int nb_count, int extra, float* __restrict__ part) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -498,22 +498,23 @@ __global__ __launch_bounds__(256) void col_abs_partial(const f4* __restrict__ Vp
 }
 __global__ __launch_bounds__(64) void col_abs_final(const float* __restrict__ part, int waves, int nb_count, int extra,
                                                     float* __restrict__ colsum) {
-  const int c = threadIdx.x;
+  const int c = blockIdx.x, lane = threadIdx.x;      // one wave per column; lane l takes every 64th partial of it
   float s = 0.f;
   if (c < 16 * nb_count) {
     const int nb = c >> 4, p = c & 15;
-    for (int w = nb; w < waves; w += nb_count) s += part[(int64_t)w * 17 + p];
-  } else if (c == 16 * nb_count && extra) {
-    for (int w = 0; w < waves; ++w) s += part[(int64_t)w * 17 + 16];
-  } else {
-    return;
+    for (int w = nb + lane * nb_count; w < waves; w += 64 * nb_count) s += part[(int64_t)w * 17 + p];
+  } else {      // the extra column
+    for (int w = lane; w < waves; w += 64) s += part[(int64_t)w * 17 + 16];
   }
-  colsum[c] = s * 1.001f;      // covers the rounding of the sums above
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
+  if (lane == 0) colsum[c] = s * 1.001f;      // covers the rounding of the sums above
 }
 void launch_col_abs_sums(const f4* Vp, const float* Ep, int64_t npad, int nb, int extra, float* aux,
                          hipStream_t stream) {
   hipLaunchKernelGGL(col_abs_partial, dim3(kColsumBlocks), dim3(256), 0, stream, Vp, Ep, npad, nb, extra, aux + 64);
-  hipLaunchKernelGGL(col_abs_final, dim3(1), dim3(64), 0, stream, aux + 64, kColsumBlocks * 4, nb, extra, aux);
+  hipLaunchKernelGGL(col_abs_final, dim3(16 * nb + extra), dim3(64), 0, stream, aux + 64, kColsumBlocks * 4, nb, extra,
+                     aux);
 }
 
 // Row tiles per wave of the symmetric kernel for this shape, or 0 where it does not apply. Eight row tiles fit the
