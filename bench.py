@@ -279,6 +279,15 @@ def main():
             result["mbcg"]["full_solve_tol1"] = {"s": time.perf_counter() - t0, "iters": full["iters"],
                                                  "rel_resid_max": float(full["rel_resid"].max()),
                                                  "resid_hist_max": [float(v) for v in full["resid_hist"].max(axis=1)]}
+            # the same solve with columns leaving the iteration once they have met the tolerance (egp_set_mbcg_shrink):
+            # the 16 probe columns pass tolerance 1 long before the y column does
+            t0 = time.perf_counter()
+            fulls = egp.mbcg(X, B17, w.lengthscales, w.outputscale, w.noise, w.kernel_type, precond=P,
+                             max_iter=w.max_iter, tol=w.tol, shrink=True)
+            torch.cuda.synchronize()
+            result["mbcg"]["full_solve_tol1_shrink"] = {
+                "s": time.perf_counter() - t0, "iters": fulls["iters"], "rel_resid_max": float(fulls["rel_resid"].max()),
+                "col_iters": [int(v) for v in fulls["col_iters"]]}
             lib.egp_set_kmm_mode(2)
             t0 = time.perf_counter()
             full2 = egp.mbcg(X, B17, w.lengthscales, w.outputscale, w.noise, w.kernel_type, precond=P,

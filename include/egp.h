@@ -126,7 +126,14 @@ size_t egp_piv_chol_precond_ws_bytes(int64_t n, int32_t d, int32_t rank);
  *   iters_done host, one int32
  *   rel_resid  host, t floats, relative residuals after the last iteration
  *   resid_hist host, [max_iter][t] floats: relative residuals after every iteration. May be NULL.
- * t in 1..33. Synchronises on `stream`. */
+ * t in 1..33. Synchronises on `stream`.
+ * With egp_set_mbcg_shrink(1) (process-wide, default 0) trailing columns that have met the tolerance leave the
+ * iteration: after each iteration the active columns are [0, 1 + last column still above tol), so with B = [y | probes]
+ * and y the slowest column the late iterations run on fewer columns (down to one). A column that has left keeps its
+ * solution and residual of that moment; its alpha_j, beta_j in cg_coef are 0 from then on (its own iteration count
+ * m_c is the number of non-zero alpha_j; beta_{m_c - 1} belongs to a step it did not take and is to be ignored). Columns are independent in CG, so every column's iterates are the ones it has
+ * without the switch; only the extra iterations that converged columns otherwise receive are skipped. egp_mll does
+ * not use the switch (its log-determinant probes keep all iterations). */
 int egp_mbcg(const float* X, int64_t n, const float* B, int32_t t, const egp_hyper_t* h,
              const egp_precond_t* P, int32_t max_iter, float tol, float* U, double* cg_coef,
              double* gamma0, int32_t* iters_done, float* rel_resid, float* resid_hist, void* ws,
@@ -253,6 +260,8 @@ size_t egp_precond_apply_ws_bytes(int64_t n, int32_t t, int32_t rank);
 typedef enum { EGP_KMM_FP32 = 0, EGP_KMM_SPLIT_BF16 = 1, EGP_KMM_SPLIT_BF16_ALL = 2, EGP_KMM_FP32_ONE_SIDED = 3 } egp_kmm_mode_t;
 int egp_set_kmm_mode(int32_t mode);
 int egp_get_kmm_mode(void);
+int egp_set_mbcg_shrink(int32_t on);      /* see egp_mbcg; returns EGP_OK */
+int egp_get_mbcg_shrink(void);
 
 /* Host-only self-check of the launch planning, for tests; touches no GPU. The fused kernel cuts the column points
  * into splits whose partial sums sit in the workspace before a deterministic reduction. For a product with

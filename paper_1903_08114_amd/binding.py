@@ -345,10 +345,14 @@ def precond_apply(P, R, noise=None, out=None, ws=None):
     return out
 
 
-def mbcg(X, B, lengthscales, outputscale, noise, kernel_type, precond=None, max_iter=100, tol=1e-2, ws=None):
+def mbcg(X, B, lengthscales, outputscale, noise, kernel_type, precond=None, max_iter=100, tol=1e-2, ws=None,
+         shrink=False):
     """Batched PCG solve of (K + noise I) U = B (egp_mbcg).
 
-    Returns dict: U (n,t) tensor, iters, rel_resid (t,), alphas/betas (iters,t) float64, gamma0 (t,)."""
+    shrink=True (egp_set_mbcg_shrink for the duration of the call): trailing columns that have met the tolerance leave
+    the iteration, so with B = [y | probes] and y the slowest column the late iterations run on fewer columns.
+    Returns dict: U (n,t) tensor, iters, rel_resid (t,), alphas/betas (iters,t) float64, gamma0 (t,), col_iters (t,)
+    = iterations each column took part in."""
     import numpy as np
     import torch
     L = lib()
@@ -366,15 +370,22 @@ def mbcg(X, B, lengthscales, outputscale, noise, kernel_type, precond=None, max_
     rel = np.zeros(t, dtype=np.float32)
     hist = np.zeros((max(max_iter, 1), t), dtype=np.float32)
     st = precond._struct(precond.rank) if precond is not None else None
-    _check(L.egp_mbcg(_dev(X, "X"), n, _dev(B, "B"), t, C.byref(h), C.byref(st) if st is not None else None,
-                      int(max_iter), float(tol), _dev(U, "U"), coef.ctypes.data_as(C.POINTER(C.c_double)),
-                      gamma0.ctypes.data_as(C.POINTER(C.c_double)), C.byref(iters),
-                      rel.ctypes.data_as(C.POINTER(C.c_float)), hist.ctypes.data_as(C.POINTER(C.c_float)),
-                      C.c_void_p(ws.data_ptr()), ws.numel(),
-                      _stream()))
+    prev = int(L.egp_get_mbcg_shrink())
+    L.egp_set_mbcg_shrink(C.c_int32(1 if shrink else 0))
+    try:
+        _check(L.egp_mbcg(_dev(X, "X"), n, _dev(B, "B"), t, C.byref(h), C.byref(st) if st is not None else None,
+                          int(max_iter), float(tol), _dev(U, "U"), coef.ctypes.data_as(C.POINTER(C.c_double)),
+                          gamma0.ctypes.data_as(C.POINTER(C.c_double)), C.byref(iters),
+                          rel.ctypes.data_as(C.POINTER(C.c_float)), hist.ctypes.data_as(C.POINTER(C.c_float)),
+                          C.c_void_p(ws.data_ptr()), ws.numel(),
+                          _stream()))
+    finally:
+        L.egp_set_mbcg_shrink(C.c_int32(prev))
     m = int(iters.value)
-    return {"U": U, "iters": m, "rel_resid": rel, "alphas": coef[:m, 0, :].copy(),
-            "betas": coef[:m, 1, :].copy(), "gamma0": gamma0, "resid_hist": hist[:m].copy()}
+    alphas = coef[:m, 0, :].copy()
+    return {"U": U, "iters": m, "rel_resid": rel, "alphas": alphas,
+            "betas": coef[:m, 1, :].copy(), "gamma0": gamma0, "resid_hist": hist[:m].copy(),
+            "col_iters": (alphas != 0.0).sum(axis=0).astype(np.int64)}
 
 
 def mll(X, y, W1, W2, lengthscales, outputscale, noise, kernel_type, rank=100, max_iter=100, tol=1.0, ws=None):

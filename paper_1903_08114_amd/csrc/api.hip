@@ -112,6 +112,13 @@ int egp_set_kmm_mode(int32_t mode) {
 }
 int egp_get_kmm_mode(void) { return g_kmm_mode.load(); }
 
+static std::atomic<int> g_mbcg_shrink{0};
+int egp_set_mbcg_shrink(int32_t on) {
+  g_mbcg_shrink.store(on ? 1 : 0);
+  return EGP_OK;
+}
+int egp_get_mbcg_shrink(void) { return g_mbcg_shrink.load(); }
+
 int egp_kmm_plan_splits(int64_t n_rows, int64_t n_cols, int32_t d, int32_t t, int32_t* used, int32_t* sized) {
   if (n_rows < 1 || n_cols < 1 || d < 1 || d > EGP_D_WIDE_MAX || t < 1 || t > EGP_T_MAX || !used || !sized)
     return fail(EGP_ERR_ARG, "egp_kmm_plan_splits: size out of range or null output");
@@ -497,7 +504,7 @@ int egp_mbcg(const float* X, int64_t n, const float* B, int32_t t, const egp_hyp
   const size_t need = mbcg_ws_bytes_core(n, h->d, t, P ? P->rank : 0, max_iter);
   if (ws_bytes < need) return fail(EGP_ERR_WS, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, need);
   return mbcg_core(X, n, B, t, h, P, max_iter, tol, U, cg_coef, gamma0, iters_done, rel_resid, resid_hist, ws,
-                   static_cast<hipStream_t>(stream));
+                   static_cast<hipStream_t>(stream), g_mbcg_shrink.load() != 0);
 }
 
 }  // extern "C"

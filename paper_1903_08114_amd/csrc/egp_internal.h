@@ -110,9 +110,10 @@ int kmm_cm_dot_blocks(int64_t npad);
 int kmm_core_cm(const Prepared& P, const float* V, int t, float* out, void* ws2, float* dot_part, int dot_ld,
                 hipStream_t stream);
 size_t mbcg_ws_bytes_core(int64_t n, int d, int t, int rank, int max_iter);
+// shrink: trailing columns that have met the tolerance leave the iteration (see egp_set_mbcg_shrink)
 int mbcg_core(const float* X, int64_t n, const float* B, int t, const egp_hyper_t* h, const egp_precond_t* P,
               int max_iter, float tol, float* U, double* cg_coef, double* gamma0, int32_t* iters_done,
-              float* rel_resid, float* resid_hist, void* ws, hipStream_t stream);
+              float* rel_resid, float* resid_hist, void* ws, hipStream_t stream, bool shrink = false);
 
 size_t mll_ws_bytes_core(int64_t n, int d, int tp, int rank, int max_iter);
 int mll_core(const float* X, int64_t n, const float* y, const float* W1, const float* W2, int tp,

@@ -184,7 +184,7 @@ size_t mbcg_ws_bytes_core(int64_t n, int d, int t, int rank, int max_iter) {
 
 int mbcg_core(const float* X, int64_t n, const float* B, int t, const egp_hyper_t* h, const egp_precond_t* P,
               int max_iter, float tol, float* U, double* cg_coef, double* gamma0, int32_t* iters_done,
-              float* rel_resid, float* resid_hist, void* ws, hipStream_t stream) {
+              float* rel_resid, float* resid_hist, void* ws, hipStream_t stream, bool shrink) {
   const int rank = P ? P->rank : 0;
   const MbcgWs lay = mbcg_layout(n, h->d, t, rank, max_iter);
   const int64_t ld = padded_points(n);
@@ -219,13 +219,14 @@ int mbcg_core(const float* X, int64_t n, const float* B, int t, const egp_hyper_
   w += lay.log;
   void* pre_ws = w;
 
-  const dim3 vgrid(kColBlocks, t);
   const int pblocks = precond_apply_blocks(n);
   const int dot_blocks = kmm_cm_dot_blocks(ld);
   int gparts[2];
 
   EGP_HIP(hipMemsetAsync(log.breakdown, 0, sizeof(int), stream));
-  hipLaunchKernelGGL(cg_init, vgrid, dim3(256), 0, stream, B, n, t, ld, Uc, R, Z, bb_part);   // Z = R also zeroes Z's padding
+  // the coefficient log starts at zero: a column that leaves the iteration early (shrink) keeps zeros from there on
+  EGP_HIP(hipMemsetAsync(log.alpha, 0, (size_t)2 * mi * t * sizeof(double), stream));
+  hipLaunchKernelGGL(cg_init, dim3(kColBlocks, t), dim3(256), 0, stream, B, n, t, ld, Uc, R, Z, bb_part);   // Z = R also zeroes Z's padding
   if (P) {
     rc = precond_apply_cm(P->L, rank, P->small_dev, n, h->noise, R, ld, t, Z, gam_part[0], kPartLd, pre_ws, stream);
     if (rc != EGP_OK) return rc;
@@ -247,8 +248,13 @@ int mbcg_core(const float* X, int64_t n, const float* B, int t, const egp_hyper_
   std::vector<float> rel(t, 0.f);
   int it = 0;
   int cur = 0;
+  // Columns [0, ta) take part in an iteration. Without `shrink` ta stays t (converged columns keep iterating, which
+  // is harmless); with it, trailing columns that have met the tolerance leave: every kernel below works on a prefix
+  // of the column-major state arrays, and t remains the stride of the coefficient log.
+  int ta = t;
   for (; it < max_iter;) {
-    rc = kmm_core_cm(prep, D, t, W, kmm_ws, delta_part, kPartLd, stream);
+    const dim3 vgrid(kColBlocks, ta);
+    rc = kmm_core_cm(prep, D, ta, W, kmm_ws, delta_part, kPartLd, stream);
     if (rc != EGP_OK) return rc;
     {
       ProfScope vprof(kProfCgVec, stream);
@@ -258,14 +264,14 @@ int mbcg_core(const float* X, int64_t n, const float* B, int t, const egp_hyper_
     const int nxt = cur ^ 1;
     const float* Zsrc;
     if (P) {
-      rc = precond_apply_cm(P->L, rank, P->small_dev, n, h->noise, R, ld, t, Z, gam_part[nxt], kPartLd, pre_ws,
+      rc = precond_apply_cm(P->L, rank, P->small_dev, n, h->noise, R, ld, ta, Z, gam_part[nxt], kPartLd, pre_ws,
                             stream);
       if (rc != EGP_OK) return rc;
       gparts[nxt] = pblocks;
       Zsrc = Z;
     } else {
       hipLaunchKernelGGL(cg_copy, dim3(64), dim3(256), 0, stream, reinterpret_cast<const float4*>(rr_part),
-                         (int64_t)t * kPartLd / 4, reinterpret_cast<float4*>(gam_part[nxt]));
+                         (int64_t)ta * kPartLd / 4, reinterpret_cast<float4*>(gam_part[nxt]));
       gparts[nxt] = kColBlocks;
       Zsrc = R;
     }
@@ -292,6 +298,8 @@ int mbcg_core(const float* X, int64_t n, const float* B, int t, const egp_hyper_
       return fail(EGP_ERR_BREAKDOWN, "non-finite residual at iteration %d", it);
     }
     if (worst <= tol) break;
+    if (shrink)
+      while (ta > 1 && rel[ta - 1] <= tol) --ta;
   }
   launch_to_rowmajor(Uc, n, t, ld, U, stream);
   EGP_HIP(hipGetLastError());

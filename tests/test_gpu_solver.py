@@ -320,3 +320,49 @@ def test_lanczos_three_term_recurrence_at_size(egp, mode):
     recon = Qb[:, rows].T @ T                                      # (rows, m): sum_i Q[i, row] T[i, j]
     inner = slice(0, 32)                                           # blocks whose successor is in the basis
     assert np.linalg.norm(KQb[:, inner] - recon[:, inner]) <= 3e-4 * np.abs(T).max() * np.linalg.norm(Qb[:32, rows])
+
+
+@pytest.mark.parametrize("n,t", [(3000, 17), (3000, 9), (33000, 17)])
+def test_mbcg_shrink_drops_converged_trailing_columns(egp, n, t):
+    """With the shrink switch, trailing columns leave the iteration once they have met the tolerance. B = [y | probes]
+    with a smooth y in front. Every column keeps a valid
+    solution (true residual at tolerance level: dense oracle at the small size, oracle rows at the large one) and takes
+    the same steps as without the switch."""
+    d = 3
+    rng = np.random.default_rng(50 + n + t)
+    X = rng.uniform(0, 1, (n, d)).astype(np.float32)
+    B = rademacher(rng, (n, t))
+    B[:, 0] = np.sin(3 * X[:, 0]) + np.cos(2 * X[:, 1])
+    ls = np.array([0.25, 0.3, 0.4], np.float32)
+    s, noise, kind, tol = 1.0, 0.05, orc.RBF, 1e-2
+    Xd, Bd = _cuda(X), _cuda(B)
+    P = egp.piv_chol_precond(Xd, ls, s, noise, kind, 20)
+    full = egp.mbcg(Xd, Bd, ls, s, noise, kind, precond=P, max_iter=400, tol=tol)
+    res = egp.mbcg(Xd, Bd, ls, s, noise, kind, precond=P, max_iter=400, tol=tol, shrink=True)
+    assert egp.lib().egp_get_mbcg_shrink() == 0                      # the switch is back off
+    assert np.array_equal(full["col_iters"], np.full(t, full["iters"]))
+    ci = res["col_iters"]
+    print(f"n={n} t={t}: {full['iters']} iterations without shrink; with it {res['iters']}, per column {ci.tolist()}")
+    assert res["iters"] <= full["iters"] and ci[0] == res["iters"]
+    assert np.all(np.diff(ci) <= 0)                                  # a column leaves only after all those behind it
+    assert ci[-1] < res["iters"]                                     # and some did leave early
+    assert np.all(res["rel_resid"] <= tol)
+    first = ci[-1]      # until the first column leaves both runs launch the same kernels: identical bits
+    assert np.array_equal(res["alphas"][:first], full["alphas"][:first])
+    for c in range(t):
+        m = ci[c]
+        # afterwards the multiply runs on fewer columns (other launch shapes, other summation order) and the
+        # coefficients drift apart the way CG coefficients do in fp32; the first steps after the change still agree
+        k = min(m, first + 3)
+        assert np.allclose(res["alphas"][:k, c], full["alphas"][:k, c], rtol=1e-3), c
+        assert np.all(res["alphas"][m:, c] == 0.0) and np.all(res["betas"][m:, c] == 0.0)
+    U = res["U"].cpu().numpy().astype(np.float64)
+    h = orc.Hyper(kind, ls, s, noise)
+    if n <= 4000:
+        KU = orc.khat(X, h) @ U
+        true_res = np.linalg.norm(KU - B, axis=0) / np.linalg.norm(B, axis=0)
+    else:
+        rows = rng.choice(n, 128, replace=False)
+        KU = orc.kmm_rows(X, U.astype(np.float32), h, rows)
+        true_res = np.linalg.norm(KU - B[rows], axis=0) / np.linalg.norm(B[rows], axis=0)
+    assert true_res.max() <= (1.3 if n <= 4000 else 2.0) * tol
