@@ -71,6 +71,8 @@ def main():
     ap.add_argument("--wide", action="store_true",
                     help="also time the d > 31 kernels: multiply and gradient forms at n=2^18, d=90 (the shape of the "
                          "paper's d=90 set), uniform points, RBF")
+    ap.add_argument("--mll-shrink", action="store_true",
+                    help="with --mll: let probe columns that have met the tolerance leave the solve (egp_set_mbcg_shrink)")
     ap.add_argument("--mll-rank", type=int, default=0, metavar="K",
                     help="preconditioner rank of the C5 step (default: the configuration's 100)")
     ap.add_argument("--predict", type=int, default=0, metavar="R",
@@ -484,7 +486,7 @@ def main():
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         r5 = egp.mll(X5, y5, W1, W2, w5.lengthscales, w5.outputscale, w5.noise, w5.kernel_type, rank=rank5,
-                     max_iter=args.mll, tol=w5.tol, ws=ws5)
+                     max_iter=args.mll, tol=w5.tol, ws=ws5, shrink=args.mll_shrink)
         torch.cuda.synchronize()
         result["c5_mll_step"] = {"s": time.perf_counter() - t0, "cg_iters": r5["iters"],
                                  "rel_resid_max": r5["rel_resid_max"], "mll": r5["mll"],

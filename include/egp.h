@@ -131,9 +131,11 @@ size_t egp_piv_chol_precond_ws_bytes(int64_t n, int32_t d, int32_t rank);
  * iteration: after each iteration the active columns are [0, 1 + last column still above tol), so with B = [y | probes]
  * and y the slowest column the late iterations run on fewer columns (down to one). A column that has left keeps its
  * solution and residual of that moment; its alpha_j, beta_j in cg_coef are 0 from then on (its own iteration count
- * m_c is the number of non-zero alpha_j; beta_{m_c - 1} belongs to a step it did not take and is to be ignored). Columns are independent in CG, so every column's iterates are the ones it has
- * without the switch; only the extra iterations that converged columns otherwise receive are skipped. egp_mll does
- * not use the switch (its log-determinant probes keep all iterations). */
+ * m_c is the number of non-zero alpha_j; beta_{m_c - 1} belongs to a step it did not take and is to be ignored).
+ * Columns are independent in CG, so every column's iterates are the ones it has without the switch; only the extra
+ * iterations that converged columns otherwise receive are skipped. egp_mll and egp_train_adam honour the switch as
+ * well: a probe's Lanczos tridiagonal then has as many steps as the probe needed to meet the tolerance, instead of as
+ * many as the slowest column. */
 int egp_mbcg(const float* X, int64_t n, const float* B, int32_t t, const egp_hyper_t* h,
              const egp_precond_t* P, int32_t max_iter, float tol, float* U, double* cg_coef,
              double* gamma0, int32_t* iters_done, float* rel_resid, float* resid_hist, void* ws,

@@ -183,6 +183,21 @@ def set_kmm_mode(mode):
     return prev
 
 
+class _shrinking:
+    """egp_set_mbcg_shrink(on) for the duration of a call, the previous setting afterwards."""
+
+    def __init__(self, L, on):
+        self.L, self.on = L, on
+
+    def __enter__(self):
+        self.prev = int(self.L.egp_get_mbcg_shrink())
+        self.L.egp_set_mbcg_shrink(C.c_int32(1 if self.on else 0))
+
+    def __exit__(self, *exc):
+        self.L.egp_set_mbcg_shrink(C.c_int32(self.prev))
+        return False
+
+
 def _hyper(kernel_type, lengthscales, outputscale, noise):
     ls = [float(v) for v in lengthscales]
     arr = (C.c_float * len(ls))(*ls)
@@ -370,17 +385,13 @@ def mbcg(X, B, lengthscales, outputscale, noise, kernel_type, precond=None, max_
     rel = np.zeros(t, dtype=np.float32)
     hist = np.zeros((max(max_iter, 1), t), dtype=np.float32)
     st = precond._struct(precond.rank) if precond is not None else None
-    prev = int(L.egp_get_mbcg_shrink())
-    L.egp_set_mbcg_shrink(C.c_int32(1 if shrink else 0))
-    try:
+    with _shrinking(L, shrink):
         _check(L.egp_mbcg(_dev(X, "X"), n, _dev(B, "B"), t, C.byref(h), C.byref(st) if st is not None else None,
                           int(max_iter), float(tol), _dev(U, "U"), coef.ctypes.data_as(C.POINTER(C.c_double)),
                           gamma0.ctypes.data_as(C.POINTER(C.c_double)), C.byref(iters),
                           rel.ctypes.data_as(C.POINTER(C.c_float)), hist.ctypes.data_as(C.POINTER(C.c_float)),
                           C.c_void_p(ws.data_ptr()), ws.numel(),
                           _stream()))
-    finally:
-        L.egp_set_mbcg_shrink(C.c_int32(prev))
     m = int(iters.value)
     alphas = coef[:m, 0, :].copy()
     return {"U": U, "iters": m, "rel_resid": rel, "alphas": alphas,
@@ -388,8 +399,10 @@ def mbcg(X, B, lengthscales, outputscale, noise, kernel_type, precond=None, max_
             "col_iters": (alphas != 0.0).sum(axis=0).astype(np.int64)}
 
 
-def mll(X, y, W1, W2, lengthscales, outputscale, noise, kernel_type, rank=100, max_iter=100, tol=1.0, ws=None):
+def mll(X, y, W1, W2, lengthscales, outputscale, noise, kernel_type, rank=100, max_iter=100, tol=1.0, ws=None,
+        shrink=False):
     """Log marginal likelihood and gradient w.r.t. (lengthscales, outputscale, noise) (egp_mll).
+    shrink: as in mbcg (a probe's Lanczos tridiagonal then ends where the probe met the tolerance).
 
     y: (n,), W1: (rank, tp) and W2: (n, tp) Rademacher draws, all float32 CUDA tensors. Returns a dict."""
     import numpy as np
@@ -401,9 +414,10 @@ def mll(X, y, W1, W2, lengthscales, outputscale, noise, kernel_type, rank=100, m
     if ws is None:
         ws = _workspace(need, X.device)
     res = _MllResult()
-    _check(L.egp_mll(_dev(X, "X"), n, _dev(y, "y"), _dev(W1, "W1") if rank > 0 else None, _dev(W2, "W2"), tp,
-                     C.byref(h), int(rank), int(max_iter), float(tol), C.byref(res),
-                     C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
+    with _shrinking(L, shrink):
+        _check(L.egp_mll(_dev(X, "X"), n, _dev(y, "y"), _dev(W1, "W1") if rank > 0 else None, _dev(W2, "W2"), tp,
+                         C.byref(h), int(rank), int(max_iter), float(tol), C.byref(res),
+                         C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
     return {"mll": res.mll, "logdet": res.logdet, "quad": res.quad,
             "grad": np.array(res.grad[:d + 2], dtype=np.float64), "iters": res.iters,
             "rank": res.precond_rank, "rel_resid_max": res.rel_resid_max}
@@ -528,8 +542,8 @@ def predict(Xq, X, a, lengthscales, outputscale, noise, kernel_type, cache=None,
 
 
 def train_adam(X, y, W1, W2, lengthscales, outputscale, noise, kernel_type, rank=100, max_iter=100, tol=1.0,
-               steps=3, lr=0.1, noise_floor=0.0, beta1=0.9, beta2=0.999, eps=1e-8, ws=None):
-    """`steps` Adam ascent steps on the log marginal likelihood (egp_train_adam).
+               steps=3, lr=0.1, noise_floor=0.0, beta1=0.9, beta2=0.999, eps=1e-8, ws=None, shrink=False):
+    """`steps` Adam ascent steps on the log marginal likelihood (egp_train_adam). shrink: as in mbcg.
     Returns dict: lengthscales, outputscale, noise (fitted), mll_history (steps + 1), last (final evaluation)."""
     import numpy as np
     L = lib()
@@ -542,10 +556,11 @@ def train_adam(X, y, W1, W2, lengthscales, outputscale, noise, kernel_type, rank
     hist = np.zeros(steps + 1, dtype=np.float64)
     if ws is None:
         ws = _workspace(L.egp_mll_ws_bytes(n, d, tp, rank, max_iter), X.device)
-    _check(L.egp_train_adam(_dev(X, "X"), n, _dev(y, "y"), _dev(W1, "W1") if rank > 0 else None, _dev(W2, "W2"), tp,
-                            int(kernel_type), d, ls, C.byref(s_io), C.byref(n_io), int(rank), int(max_iter),
-                            float(tol), C.byref(opt), C.byref(res), hist.ctypes.data_as(C.POINTER(C.c_double)),
-                            C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
+    with _shrinking(L, shrink):
+        _check(L.egp_train_adam(_dev(X, "X"), n, _dev(y, "y"), _dev(W1, "W1") if rank > 0 else None, _dev(W2, "W2"),
+                                tp, int(kernel_type), d, ls, C.byref(s_io), C.byref(n_io), int(rank), int(max_iter),
+                                float(tol), C.byref(opt), C.byref(res), hist.ctypes.data_as(C.POINTER(C.c_double)),
+                                C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
     return {"lengthscales": np.array(list(ls), dtype=np.float64), "outputscale": float(s_io.value),
             "noise": float(n_io.value), "mll_history": hist,
             "last": {"mll": res.mll, "grad": np.array(res.grad[:d + 2]), "iters": res.iters}}

@@ -118,6 +118,11 @@ int egp_set_mbcg_shrink(int32_t on) {
   return EGP_OK;
 }
 int egp_get_mbcg_shrink(void) { return g_mbcg_shrink.load(); }
+}  // extern "C"
+namespace egp {
+bool mbcg_shrink() { return g_mbcg_shrink.load() != 0; }
+}  // namespace egp
+extern "C" {
 
 int egp_kmm_plan_splits(int64_t n_rows, int64_t n_cols, int32_t d, int32_t t, int32_t* used, int32_t* sized) {
   if (n_rows < 1 || n_cols < 1 || d < 1 || d > EGP_D_WIDE_MAX || t < 1 || t > EGP_T_MAX || !used || !sized)

@@ -139,6 +139,7 @@ struct ProfScope {   // records an event pair around the launches made during it
   void* slot_;
 };
 
+bool mbcg_shrink();     // egp_set_mbcg_shrink
 int kmm_mode();     // EGP_KMM_FP32 or EGP_KMM_SPLIT_BF16 (egp_set_kmm_mode)
 
 int validate_hyper(const egp_hyper_t* h, int d_max = EGP_D_WIDE_MAX);

@@ -238,8 +238,9 @@ int mll_core(const float* X, int64_t n, const float* y, const float* W1, const f
   std::vector<double> coef((size_t)(max_iter > 0 ? max_iter : 1) * 2 * t, 0.0), gamma0(t, 0.0);
   std::vector<float> rel(t, 0.f);
   int32_t iters = 0;
+  // (with column shrinking on, a probe's tridiagonal below ends where the probe left the iteration)
   rc = mbcg_core(X, n, B, t, h, Pp, max_iter, tol, U, coef.data(), gamma0.data(), &iters, rel.data(), nullptr, sub,
-                 stream);
+                 stream, mbcg_shrink());
   if (rc != EGP_OK) return rc;
   res->iters = iters;
   res->precond_rank = rank;

@@ -114,3 +114,32 @@ def test_mll_with_symmetric_kernels_matches_one_sided(egp, kind, tp):
     assert abs(got["mll"] - base["mll"]) <= 1e-3 * abs(base["mll"]) + 0.5
     scale = np.abs(base["grad"]) + 0.02 * np.abs(base["grad"]).max()
     assert np.all(np.abs(got["grad"] - base["grad"]) <= 2e-2 * scale), (got["grad"], base["grad"])
+
+
+def test_mll_with_column_shrinking(egp):
+    """With the shrink switch the probe columns leave the solve once they meet the tolerance, so their Lanczos
+    tridiagonals are shorter. At a tight tolerance the estimate is the one without the switch (every column is
+    converged either way) and stays inside the Monte-Carlo band of the exact value; at a loose tolerance it remains a
+    usable estimate (the quadrature has fewer nodes, not wrong ones)."""
+    rng = np.random.default_rng(71)
+    n, d, tp, rank = 1200, 3, 16, 12
+    X = well_separated_points(77, n, d)
+    y = (np.sin(5 * X[:, 0]) + np.cos(3 * X[:, 1]) + 0.2 * rng.standard_normal(n)).astype(np.float32)
+    ls = np.array([0.6, 0.9, 1.4], np.float32)
+    s, noise, kind = 1.2, 0.15, orc.RBF
+    h = orc.Hyper(kind, ls, s, noise)
+    w1, w2 = _cuda(rademacher(rng, (rank, tp))), _cuda(rademacher(rng, (n, tp)))
+    Xd, yd = _cuda(X), _cuda(y)
+    exact = orc.mll(X, y, h)
+    gexact = orc.mll_grad(X, y, h)
+    for tol, band in ((1e-5, 1.0), (1e-1, 2.0)):
+        off = egp.mll(Xd, yd, w1, w2, ls, s, noise, kind, rank=rank, max_iter=400, tol=tol)
+        on = egp.mll(Xd, yd, w1, w2, ls, s, noise, kind, rank=rank, max_iter=400, tol=tol, shrink=True)
+        assert egp.lib().egp_get_mbcg_shrink() == 0
+        print(f"tol {tol}: mll {off['mll']:.3f} ({off['iters']} it) without, {on['mll']:.3f} ({on['iters']} it) with "
+              f"shrinking; exact {exact:.3f}")
+        assert on["rel_resid_max"] <= tol and on["iters"] <= off["iters"]
+        assert abs(on["mll"] - exact) <= band * (0.02 * abs(exact) + 2.0)
+        assert np.all(np.abs(on["grad"] - gexact) <= band * (0.25 * np.abs(gexact) + 0.1 * np.abs(gexact).max()))
+        if tol < 1e-4:
+            assert abs(on["mll"] - off["mll"]) <= 1e-3 * abs(off["mll"]) + 0.05
