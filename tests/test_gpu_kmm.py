@@ -277,3 +277,36 @@ def test_kmm_one_sided_kernels_on_other_shapes(egp):
         finally:
             _set_mode(egp, 0)
         assert np.array_equal(got, base)
+
+
+@pytest.mark.parametrize("n,d,t", [(4000, 8, 16), (33000, 11, 17), (33000, 40, 16)])
+def test_kmm_under_hip_graph_capture(egp, n, d, t):
+    """egp_kmm with a caller-provided workspace enqueues kernels only (no allocation, no memset node, no host
+    synchronisation), so a caller can capture it into a HIP graph. The graph is replayed several times with new
+    right-hand sides, with eager calls and synchronisations in between, and every replay must give the eager result
+    bit for bit (one-sided kernel, symmetric kernel with its fixed-point column-side sums, wide symmetric kernel)."""
+    import torch
+    L = egp.lib()
+    rng = np.random.default_rng(n + d)
+    X = torch.from_numpy(rng.uniform(0, 1, (n, d)).astype(np.float32)).cuda()
+    V = torch.from_numpy(rng.standard_normal((n, t)).astype(np.float32)).cuda()
+    ls = np.full(d, 0.7 * np.sqrt(d / 8), np.float32)
+    out = torch.empty_like(V)
+    ws = torch.empty(L.egp_kmm_ws_bytes(n, d, t), dtype=torch.uint8, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        egp.kmm(X, V, ls, 1.1, 0.2, orc.MATERN52, out=out, ws=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        egp.kmm(X, V, ls, 1.1, 0.2, orc.MATERN52, out=out, ws=ws)
+    for _ in range(3):
+        V.copy_(torch.from_numpy(rng.standard_normal((n, t)).astype(np.float32)).cuda())
+        want = egp.kmm(X, V, ls, 1.1, 0.2, orc.MATERN52).clone()
+        torch.cuda.synchronize()
+        out.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert bool((out == want).all())
