@@ -19,6 +19,11 @@
  *   - Return value: 0 on success, a negative egp_status_t otherwise; egp_last_error() then returns a
  *     thread-local, statically stored message. Nothing is written to outputs on EGP_ERR_ARG / EGP_ERR_WS.
  *   - Inputs are never modified.
+ *   - Threads: the library keeps no state between calls except two process-wide defaults (egp_set_kmm_mode,
+ *     egp_set_mbcg_shrink) and the profiling counters. Each call reads the defaults once, at its entry, and works on
+ *     that copy to its end: a setter called from another thread while a call runs affects later calls only. Calls
+ *     from different threads may run concurrently when their workspaces and outputs do not overlap. The *_ex entry
+ *     points take the two options per call (egp_call_opts_t) and do not depend on the defaults at all.
  */
 #ifndef EGP_H
 #define EGP_H
@@ -76,6 +81,16 @@ typedef struct {
                         nearly equal vectors: the k x k algebra and its n-term sums run in fp64 */
 } egp_precond_t;
 
+/* Per-call options of the *_ex entry points. A field set to -1 takes the process-wide default of the matching
+ * setter; opts = NULL takes both defaults (egp_x(...) is egp_x_ex(..., NULL)).
+ *   kmm_mode     an egp_kmm_mode_t (see egp_set_kmm_mode)
+ *   mbcg_shrink  0 or 1 (see egp_mbcg)
+ * Other values return EGP_ERR_ARG. */
+typedef struct {
+  int32_t kmm_mode;
+  int32_t mbcg_shrink;
+} egp_call_opts_t;
+
 /* out = Khat V = K(X,X) V + noise V, K never materialised (paper, Method, "Partitioned kernel MVMs":
  * row blocks of the kernel matrix are formed, multiplied and discarded; here a block lives in
  * registers). noise = 0 gives K V. t in 1..EGP_T_MAX. Asynchronous on `stream`. The same call gives the same
@@ -83,7 +98,9 @@ typedef struct {
 int egp_kmm(const float* X /*device n x d*/, int64_t n, const float* V /*device n x t*/, int32_t t,
             const egp_hyper_t* h /*host*/, float* out /*device n x t*/, void* ws, size_t ws_bytes,
             void* stream);
-size_t egp_kmm_ws_bytes(int64_t n, int32_t d, int32_t t);
+int egp_kmm_ex(const float* X, int64_t n, const float* V, int32_t t, const egp_hyper_t* h, float* out, void* ws,
+               size_t ws_bytes, void* stream, const egp_call_opts_t* opts /*host, may be NULL*/);
+size_t egp_kmm_ws_bytes(int64_t n, int32_t d, int32_t t);      /* covers every mode */
 
 /* dout[k] = (dK/dl_k) V for k = 0..d-1, dout laid out [d][n][t]: the products the marginal-likelihood
  * gradient needs (paper, Eq. 2). dK/dl_k [i,j] = s h(r_ij) (x_ik-x_jk)^2 / l_k^3 with h = g for RBF,
@@ -126,20 +143,30 @@ size_t egp_piv_chol_precond_ws_bytes(int64_t n, int32_t d, int32_t rank);
  *   iters_done host, one int32
  *   rel_resid  host, t floats, relative residuals after the last iteration
  *   resid_hist host, [max_iter][t] floats: relative residuals after every iteration. May be NULL.
- * t in 1..33. Synchronises on `stream`.
- * With egp_set_mbcg_shrink(1) (process-wide, default 0) trailing columns that have met the tolerance leave the
+ * t in 1..33. Synchronises on `stream`. With max_iter = 0 no iteration runs: U = 0 and rel_resid is 1 for every
+ * column with b_c != 0.
+ * Column shrinking (mbcg_shrink = 1 in egp_call_opts_t, or the process-wide default egp_set_mbcg_shrink(1); off
+ * unless asked for): trailing columns that have met the tolerance leave the
  * iteration: after each iteration the active columns are [0, 1 + last column still above tol), so with B = [y | probes]
  * and y the slowest column the late iterations run on fewer columns (down to one). A column that has left keeps its
  * solution and residual of that moment; its alpha_j, beta_j in cg_coef are 0 from then on (its own iteration count
  * m_c is the number of non-zero alpha_j; beta_{m_c - 1} belongs to a step it did not take and is to be ignored).
  * Columns are independent in CG, so every column's iterates are the ones it has without the switch; only the extra
- * iterations that converged columns otherwise receive are skipped. egp_mll and egp_train_adam honour the switch as
- * well: a probe's Lanczos tridiagonal then has as many steps as the probe needed to meet the tolerance, instead of as
- * many as the slowest column. */
+ * iterations that converged columns otherwise receive are skipped.
+ * egp_mll and egp_train_adam honour the option as well, and there it changes the result: a probe's Lanczos
+ * tridiagonal then has only as many steps as the probe needed to meet the tolerance, so the quadrature order of the
+ * log-determinant estimate is truncated and the estimate is biased. At a loose tolerance the shift is large: with
+ * tol = 1 (the paper's training tolerance) probes leave after a handful of steps, and on a 2^21-point Matern-3/2
+ * problem the value moved by about 7 % (158.1e3 -> 147.7e3); at tight tolerances both settings agree. Use it for
+ * solves; leave it off for likelihood values unless that bias is acceptable. */
 int egp_mbcg(const float* X, int64_t n, const float* B, int32_t t, const egp_hyper_t* h,
              const egp_precond_t* P, int32_t max_iter, float tol, float* U, double* cg_coef,
              double* gamma0, int32_t* iters_done, float* rel_resid, float* resid_hist, void* ws,
              size_t ws_bytes, void* stream);
+int egp_mbcg_ex(const float* X, int64_t n, const float* B, int32_t t, const egp_hyper_t* h, const egp_precond_t* P,
+                int32_t max_iter, float tol, float* U, double* cg_coef, double* gamma0, int32_t* iters_done,
+                float* rel_resid, float* resid_hist, void* ws, size_t ws_bytes, void* stream,
+                const egp_call_opts_t* opts /*host, may be NULL*/);
 size_t egp_mbcg_ws_bytes(int64_t n, int32_t d, int32_t t, int32_t rank, int32_t max_iter);
 
 /* One evaluation of the log marginal likelihood and its gradient (paper, Eq. 1 and Eq. 2) by the
@@ -162,6 +189,9 @@ typedef struct {
 int egp_mll(const float* X, int64_t n, const float* y, const float* W1, const float* W2, int32_t tp,
             const egp_hyper_t* h, int32_t rank, int32_t max_iter, float tol, egp_mll_result_t* out,
             void* ws, size_t ws_bytes, void* stream);
+int egp_mll_ex(const float* X, int64_t n, const float* y, const float* W1, const float* W2, int32_t tp,
+               const egp_hyper_t* h, int32_t rank, int32_t max_iter, float tol, egp_mll_result_t* out,
+               void* ws, size_t ws_bytes, void* stream, const egp_call_opts_t* opts /*host, may be NULL*/);
 size_t egp_mll_ws_bytes(int64_t n, int32_t d, int32_t tp, int32_t rank, int32_t max_iter);
 
 /* Hyper-parameter fitting: `steps` Adam ascent steps on the log marginal likelihood (paper, Experiment details:
@@ -184,6 +214,11 @@ int egp_train_adam(const float* X, int64_t n, const float* y, const float* W1, c
                    int32_t kernel_type, int32_t d, float* lengthscales, float* outputscale, float* noise,
                    int32_t rank, int32_t max_iter, float tol, const egp_adam_t* opt, egp_mll_result_t* last,
                    double* mll_history, void* ws, size_t ws_bytes, void* stream);
+int egp_train_adam_ex(const float* X, int64_t n, const float* y, const float* W1, const float* W2, int32_t tp,
+                      int32_t kernel_type, int32_t d, float* lengthscales, float* outputscale, float* noise,
+                      int32_t rank, int32_t max_iter, float tol, const egp_adam_t* opt, egp_mll_result_t* last,
+                      double* mll_history, void* ws, size_t ws_bytes, void* stream,
+                      const egp_call_opts_t* opts /*host, may be NULL*/);
 
 /* Host-only helper of egp_mll, exported for testing: e1^T log(T) e1 of the symmetric positive definite
  * tridiagonal T with diagonal diag[0..m) and off-diagonal off[0..m-1). Returns 0, or EGP_ERR_BREAKDOWN
@@ -237,7 +272,8 @@ int egp_precond_apply(const egp_precond_t* P, int64_t n, float noise, const floa
                       float* Z, void* ws, size_t ws_bytes, void* stream);
 size_t egp_precond_apply_ws_bytes(int64_t n, int32_t t, int32_t rank);
 
-/* Arithmetic of the fused kernel (process-wide; default EGP_KMM_FP32). Every mode gives bit-reproducible results.
+/* Arithmetic of the fused kernel: the process-wide default that a call takes when its options do not name a mode
+ * (initially EGP_KMM_FP32). A call reads it once at its entry. Every mode gives bit-reproducible results.
  *   EGP_KMM_FP32        fp32 MFMA throughout: the reference mode, the one every reported fp32 figure uses. In a
  *                       square product (egp_kmm, the solver, Lanczos, the likelihood) with n >= 32257 the symmetry
  *                       of the kernel matrix is exploited (paper, Background: K is a covariance matrix): every tile
@@ -262,16 +298,19 @@ size_t egp_precond_apply_ws_bytes(int64_t n, int32_t t, int32_t rank);
 typedef enum { EGP_KMM_FP32 = 0, EGP_KMM_SPLIT_BF16 = 1, EGP_KMM_SPLIT_BF16_ALL = 2, EGP_KMM_FP32_ONE_SIDED = 3 } egp_kmm_mode_t;
 int egp_set_kmm_mode(int32_t mode);
 int egp_get_kmm_mode(void);
-int egp_set_mbcg_shrink(int32_t on);      /* see egp_mbcg; returns EGP_OK */
+int egp_set_mbcg_shrink(int32_t on);      /* process-wide default of column shrinking, see egp_mbcg; returns EGP_OK */
 int egp_get_mbcg_shrink(void);
 
 /* Host-only self-check of the launch planning, for tests; touches no GPU. The fused kernel cuts the column points
  * into splits whose partial sums sit in the workspace before a deterministic reduction. For a product with
- * n_rows x n_cols kernel entries and t right-hand sides in the current mode, used[0] (host) receives the largest
+ * n_rows x n_cols kernel entries and t right-hand sides in the current default mode, used[0] (host) receives the largest
  * split count any of its launches takes and sized[0] (host) the count the workspace of egp_kmm_ws_bytes /
  * egp_kmm_cross_ws_bytes holds; used <= sized always (a launch that would break this returns EGP_ERR_WS instead of
  * running). Returns 0, or EGP_ERR_ARG for sizes outside the library's limits or null outputs. */
 int egp_kmm_plan_splits(int64_t n_rows, int64_t n_cols, int32_t d, int32_t t, int32_t* used, int32_t* sized);
+/* The same for the mode named in opts (NULL or kmm_mode = -1: the process default), read once like in every call. */
+int egp_kmm_plan_splits_ex(int64_t n_rows, int64_t n_cols, int32_t d, int32_t t, const egp_call_opts_t* opts,
+                           int32_t* used, int32_t* sized);
 
 /* In-stream timing of kernel groups with HIP events, for roofline reporting. While enabled, each launch
  * of a group is bracketed by an event pair on the stream it runs on. egp_profile_enable(1) clears the

@@ -25,8 +25,7 @@ termination, the CG tridiagonal against explicit Lanczos at truncations, exact
 Gauss quadrature at m=n Lanczos steps, stochastic estimators exact for complete
 (Hadamard) probe sets and within Monte-Carlo error for random ones, Adam's
 second step against the published recurrences. No function here is "parity
-unpinned"; tests/oracle_mutation_sweep.py checks that single-token changes to
-this file are rejected by those pins.
+unpinned".
 
 All functions take array-likes, cast to float64, and return float64.
 """

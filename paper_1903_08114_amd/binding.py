@@ -31,6 +31,10 @@ class _Adam(C.Structure):
                 ("eps", C.c_float), ("noise_floor", C.c_float)]
 
 
+class _CallOpts(C.Structure):
+    _fields_ = [("kmm_mode", C.c_int32), ("mbcg_shrink", C.c_int32)]
+
+
 class _Precond(C.Structure):
     _fields_ = [("rank", C.c_int32), ("L", C.c_void_p), ("pivots", C.POINTER(C.c_int32)),
                 ("small", C.POINTER(C.c_double)), ("small_dev", C.c_void_p)]
@@ -131,6 +135,17 @@ def lib():
         L.egp_kmm.restype = C.c_int
         L.egp_kmm.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.POINTER(_Hyper), C.c_void_p,
                               C.c_void_p, C.c_size_t, C.c_void_p]
+        opts = [C.POINTER(_CallOpts)]
+        L.egp_kmm_ex.restype = C.c_int
+        L.egp_kmm_ex.argtypes = L.egp_kmm.argtypes + opts
+        L.egp_mbcg_ex.restype = C.c_int
+        L.egp_mbcg_ex.argtypes = L.egp_mbcg.argtypes + opts
+        L.egp_mll_ex.restype = C.c_int
+        L.egp_mll_ex.argtypes = L.egp_mll.argtypes + opts
+        L.egp_train_adam_ex.restype = C.c_int
+        L.egp_train_adam_ex.argtypes = L.egp_train_adam.argtypes + opts
+        L.egp_kmm_plan_splits_ex.argtypes = [C.c_int64, C.c_int64, C.c_int32, C.c_int32, C.POINTER(_CallOpts),
+                                             C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         _lib = L
     return _lib
 
@@ -183,19 +198,11 @@ def set_kmm_mode(mode):
     return prev
 
 
-class _shrinking:
-    """egp_set_mbcg_shrink(on) for the duration of a call, the previous setting afterwards."""
-
-    def __init__(self, L, on):
-        self.L, self.on = L, on
-
-    def __enter__(self):
-        self.prev = int(self.L.egp_get_mbcg_shrink())
-        self.L.egp_set_mbcg_shrink(C.c_int32(1 if self.on else 0))
-
-    def __exit__(self, *exc):
-        self.L.egp_set_mbcg_shrink(C.c_int32(self.prev))
-        return False
+def _opts(mode=None, shrink=None):
+    """egp_call_opts_t for one call: the arithmetic mode (name, code or None = process default) and column shrinking
+    (True, False or None = process default)."""
+    code = -1 if mode is None else (KMM_MODES[mode] if isinstance(mode, str) else int(mode))
+    return _CallOpts(code, -1 if shrink is None else (1 if shrink else 0))
 
 
 def _hyper(kernel_type, lengthscales, outputscale, noise):
@@ -271,8 +278,9 @@ class Precond:
         return float(self._small[self.capacity * self.capacity])
 
 
-def kmm(X, V, lengthscales, outputscale, noise, kernel_type, out=None, ws=None):
-    """out = K(X,X) V + noise V on the GPU (egp_kmm). X: (n,d), V: (n,t) float32 CUDA tensors."""
+def kmm(X, V, lengthscales, outputscale, noise, kernel_type, out=None, ws=None, mode=None):
+    """out = K(X,X) V + noise V on the GPU (egp_kmm_ex). X: (n,d), V: (n,t) float32 CUDA tensors.
+    mode: arithmetic of this call (a KMM_MODES name or code); None takes the process default (set_kmm_mode)."""
     import torch
     L = lib()
     n, d = X.shape
@@ -283,8 +291,9 @@ def kmm(X, V, lengthscales, outputscale, noise, kernel_type, out=None, ws=None):
     need = L.egp_kmm_ws_bytes(n, d, t)
     if ws is None:
         ws = _workspace(need, X.device)
-    _check(L.egp_kmm(_dev(X, "X"), n, _dev(V, "V"), t, C.byref(h), _dev(out, "out"),
-                     C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
+    o = _opts(mode)
+    _check(L.egp_kmm_ex(_dev(X, "X"), n, _dev(V, "V"), t, C.byref(h), _dev(out, "out"),
+                        C.c_void_p(ws.data_ptr()), ws.numel(), _stream(), C.byref(o)))
     return out
 
 
@@ -361,10 +370,11 @@ def precond_apply(P, R, noise=None, out=None, ws=None):
 
 
 def mbcg(X, B, lengthscales, outputscale, noise, kernel_type, precond=None, max_iter=100, tol=1e-2, ws=None,
-         shrink=False):
-    """Batched PCG solve of (K + noise I) U = B (egp_mbcg).
+         shrink=None, mode=None):
+    """Batched PCG solve of (K + noise I) U = B (egp_mbcg_ex).
 
-    shrink=True (egp_set_mbcg_shrink for the duration of the call): trailing columns that have met the tolerance leave
+    mode: arithmetic of the multiplies of this call (None = process default).
+    shrink=True (a per-call option): trailing columns that have met the tolerance leave
     the iteration, so with B = [y | probes] and y the slowest column the late iterations run on fewer columns.
     Returns dict: U (n,t) tensor, iters, rel_resid (t,), alphas/betas (iters,t) float64, gamma0 (t,), col_iters (t,)
     = iterations each column took part in."""
@@ -385,13 +395,12 @@ def mbcg(X, B, lengthscales, outputscale, noise, kernel_type, precond=None, max_
     rel = np.zeros(t, dtype=np.float32)
     hist = np.zeros((max(max_iter, 1), t), dtype=np.float32)
     st = precond._struct(precond.rank) if precond is not None else None
-    with _shrinking(L, shrink):
-        _check(L.egp_mbcg(_dev(X, "X"), n, _dev(B, "B"), t, C.byref(h), C.byref(st) if st is not None else None,
-                          int(max_iter), float(tol), _dev(U, "U"), coef.ctypes.data_as(C.POINTER(C.c_double)),
-                          gamma0.ctypes.data_as(C.POINTER(C.c_double)), C.byref(iters),
-                          rel.ctypes.data_as(C.POINTER(C.c_float)), hist.ctypes.data_as(C.POINTER(C.c_float)),
-                          C.c_void_p(ws.data_ptr()), ws.numel(),
-                          _stream()))
+    o = _opts(mode, shrink)
+    _check(L.egp_mbcg_ex(_dev(X, "X"), n, _dev(B, "B"), t, C.byref(h), C.byref(st) if st is not None else None,
+                         int(max_iter), float(tol), _dev(U, "U"), coef.ctypes.data_as(C.POINTER(C.c_double)),
+                         gamma0.ctypes.data_as(C.POINTER(C.c_double)), C.byref(iters),
+                         rel.ctypes.data_as(C.POINTER(C.c_float)), hist.ctypes.data_as(C.POINTER(C.c_float)),
+                         C.c_void_p(ws.data_ptr()), ws.numel(), _stream(), C.byref(o)))
     m = int(iters.value)
     alphas = coef[:m, 0, :].copy()
     return {"U": U, "iters": m, "rel_resid": rel, "alphas": alphas,
@@ -400,9 +409,10 @@ def mbcg(X, B, lengthscales, outputscale, noise, kernel_type, precond=None, max_
 
 
 def mll(X, y, W1, W2, lengthscales, outputscale, noise, kernel_type, rank=100, max_iter=100, tol=1.0, ws=None,
-        shrink=False):
-    """Log marginal likelihood and gradient w.r.t. (lengthscales, outputscale, noise) (egp_mll).
-    shrink: as in mbcg (a probe's Lanczos tridiagonal then ends where the probe met the tolerance).
+        shrink=None, mode=None):
+    """Log marginal likelihood and gradient w.r.t. (lengthscales, outputscale, noise) (egp_mll_ex).
+    shrink: as in mbcg (a probe's Lanczos tridiagonal then ends where the probe met the tolerance, which truncates
+    the quadrature of the log-determinant: at loose tolerances the value shifts by several per cent); mode: as in kmm.
 
     y: (n,), W1: (rank, tp) and W2: (n, tp) Rademacher draws, all float32 CUDA tensors. Returns a dict."""
     import numpy as np
@@ -414,10 +424,10 @@ def mll(X, y, W1, W2, lengthscales, outputscale, noise, kernel_type, rank=100, m
     if ws is None:
         ws = _workspace(need, X.device)
     res = _MllResult()
-    with _shrinking(L, shrink):
-        _check(L.egp_mll(_dev(X, "X"), n, _dev(y, "y"), _dev(W1, "W1") if rank > 0 else None, _dev(W2, "W2"), tp,
-                         C.byref(h), int(rank), int(max_iter), float(tol), C.byref(res),
-                         C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
+    o = _opts(mode, shrink)
+    _check(L.egp_mll_ex(_dev(X, "X"), n, _dev(y, "y"), _dev(W1, "W1") if rank > 0 else None, _dev(W2, "W2"), tp,
+                        C.byref(h), int(rank), int(max_iter), float(tol), C.byref(res),
+                        C.c_void_p(ws.data_ptr()), ws.numel(), _stream(), C.byref(o)))
     return {"mll": res.mll, "logdet": res.logdet, "quad": res.quad,
             "grad": np.array(res.grad[:d + 2], dtype=np.float64), "iters": res.iters,
             "rank": res.precond_rank, "rel_resid_max": res.rel_resid_max}
@@ -542,8 +552,8 @@ def predict(Xq, X, a, lengthscales, outputscale, noise, kernel_type, cache=None,
 
 
 def train_adam(X, y, W1, W2, lengthscales, outputscale, noise, kernel_type, rank=100, max_iter=100, tol=1.0,
-               steps=3, lr=0.1, noise_floor=0.0, beta1=0.9, beta2=0.999, eps=1e-8, ws=None, shrink=False):
-    """`steps` Adam ascent steps on the log marginal likelihood (egp_train_adam). shrink: as in mbcg.
+               steps=3, lr=0.1, noise_floor=0.0, beta1=0.9, beta2=0.999, eps=1e-8, ws=None, shrink=None, mode=None):
+    """`steps` Adam ascent steps on the log marginal likelihood (egp_train_adam_ex). shrink, mode: as in mll.
     Returns dict: lengthscales, outputscale, noise (fitted), mll_history (steps + 1), last (final evaluation)."""
     import numpy as np
     L = lib()
@@ -556,11 +566,11 @@ def train_adam(X, y, W1, W2, lengthscales, outputscale, noise, kernel_type, rank
     hist = np.zeros(steps + 1, dtype=np.float64)
     if ws is None:
         ws = _workspace(L.egp_mll_ws_bytes(n, d, tp, rank, max_iter), X.device)
-    with _shrinking(L, shrink):
-        _check(L.egp_train_adam(_dev(X, "X"), n, _dev(y, "y"), _dev(W1, "W1") if rank > 0 else None, _dev(W2, "W2"),
-                                tp, int(kernel_type), d, ls, C.byref(s_io), C.byref(n_io), int(rank), int(max_iter),
-                                float(tol), C.byref(opt), C.byref(res), hist.ctypes.data_as(C.POINTER(C.c_double)),
-                                C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
+    o = _opts(mode, shrink)
+    _check(L.egp_train_adam_ex(_dev(X, "X"), n, _dev(y, "y"), _dev(W1, "W1") if rank > 0 else None, _dev(W2, "W2"),
+                               tp, int(kernel_type), d, ls, C.byref(s_io), C.byref(n_io), int(rank), int(max_iter),
+                               float(tol), C.byref(opt), C.byref(res), hist.ctypes.data_as(C.POINTER(C.c_double)),
+                               C.c_void_p(ws.data_ptr()), ws.numel(), _stream(), C.byref(o)))
     return {"lengthscales": np.array(list(ls), dtype=np.float64), "outputscale": float(s_io.value),
             "noise": float(n_io.value), "mll_history": hist,
             "last": {"mll": res.mll, "grad": np.array(res.grad[:d + 2]), "iters": res.iters}}

@@ -51,18 +51,28 @@ def build(verbose: bool = True) -> str:
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("link failed:\n" + res.stderr)
-    # instruction-mix microbenchmark (stand-alone executable, not linked into the library)
-    mb = os.path.join(HERE, "microbench")
-    res = subprocess.run(["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature",
-                          "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
-                          os.path.join(mb, "issue_mix.hip"), "-o", os.path.join(mb, "issue_mix")],
-                         capture_output=True, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("microbenchmark build failed:\n" + res.stderr)
     if verbose:
         print(f"built {LIB} from {len(srcs)} sources")
     return LIB
 
 
+def build_microbench(verbose: bool = True) -> str | None:
+    """The instruction-mix probe behind the roofline analysis: a stand-alone executable, no part of the library. A
+    failure here is reported and never fails the library build."""
+    mb = os.path.join(HERE, "microbench")
+    exe = os.path.join(mb, "issue_mix")
+    res = subprocess.run(["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature",
+                          "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
+                          os.path.join(mb, "issue_mix.hip"), "-o", exe], capture_output=True, text=True)
+    if res.returncode != 0:
+        sys.stderr.write("warning: the issue_mix microbenchmark did not build (the library is unaffected):\n" + res.stderr)
+        return None
+    if verbose:
+        print(f"built {exe}")
+    return exe
+
+
 if __name__ == "__main__":
     build()
+    if "--microbench" in sys.argv:
+        build_microbench()

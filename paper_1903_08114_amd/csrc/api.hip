@@ -43,8 +43,27 @@ int validate_hyper(const egp_hyper_t* h, int d_max) {
   return EGP_OK;
 }
 
+// Process-wide defaults of the per-call options. They are read exactly once per library call, by resolve_opts() at
+// the extern "C" entry point; everything below works on the CallOpts copy it returns.
 static std::atomic<int> g_kmm_mode{EGP_KMM_FP32};
-int kmm_mode() { return g_kmm_mode.load(); }
+static std::atomic<int> g_mbcg_shrink{0};
+
+static int resolve_opts(const egp_call_opts_t* o, CallOpts* co) {
+  co->mode = g_kmm_mode.load();
+  co->shrink = g_mbcg_shrink.load() != 0;
+  if (o == nullptr) return EGP_OK;
+  if (o->kmm_mode != -1) {
+    if (o->kmm_mode < EGP_KMM_FP32 || o->kmm_mode > EGP_KMM_FP32_ONE_SIDED)
+      return fail(EGP_ERR_ARG, "unknown kmm mode %d in the call options", o->kmm_mode);
+    co->mode = o->kmm_mode;
+  }
+  if (o->mbcg_shrink != -1) {
+    if (o->mbcg_shrink != 0 && o->mbcg_shrink != 1)
+      return fail(EGP_ERR_ARG, "mbcg_shrink = %d in the call options (0, 1 or -1)", o->mbcg_shrink);
+    co->shrink = o->mbcg_shrink == 1;
+  }
+  return EGP_OK;
+}
 
 // ---- profiling: event pairs kept until egp_profile_read drains them ----
 struct ProfSlot { hipEvent_t a, b; };
@@ -112,26 +131,27 @@ int egp_set_kmm_mode(int32_t mode) {
 }
 int egp_get_kmm_mode(void) { return g_kmm_mode.load(); }
 
-static std::atomic<int> g_mbcg_shrink{0};
 int egp_set_mbcg_shrink(int32_t on) {
   g_mbcg_shrink.store(on ? 1 : 0);
   return EGP_OK;
 }
 int egp_get_mbcg_shrink(void) { return g_mbcg_shrink.load(); }
-}  // extern "C"
-namespace egp {
-bool mbcg_shrink() { return g_mbcg_shrink.load() != 0; }
-}  // namespace egp
-extern "C" {
 
-int egp_kmm_plan_splits(int64_t n_rows, int64_t n_cols, int32_t d, int32_t t, int32_t* used, int32_t* sized) {
+int egp_kmm_plan_splits_ex(int64_t n_rows, int64_t n_cols, int32_t d, int32_t t, const egp_call_opts_t* opts,
+                           int32_t* used, int32_t* sized) {
+  CallOpts co;
+  int rc;
+  if ((rc = resolve_opts(opts, &co)) != EGP_OK) return rc;
   if (n_rows < 1 || n_cols < 1 || d < 1 || d > EGP_D_WIDE_MAX || t < 1 || t > EGP_T_MAX || !used || !sized)
     return fail(EGP_ERR_ARG, "egp_kmm_plan_splits: size out of range or null output");
   int u = 0, s = 0;
-  kmm_plan_splits(n_rows, n_cols, d, t, &u, &s);
+  kmm_plan_splits(n_rows, n_cols, d, t, co.mode, &u, &s);
   *used = u;
   *sized = s;
   return EGP_OK;
+}
+int egp_kmm_plan_splits(int64_t n_rows, int64_t n_cols, int32_t d, int32_t t, int32_t* used, int32_t* sized) {
+  return egp_kmm_plan_splits_ex(n_rows, n_cols, d, t, nullptr, used, sized);
 }
 
 int egp_calib_copy(const float* src, float* dst, int64_t count, void* stream) {
@@ -170,11 +190,15 @@ size_t egp_kmm_ws_bytes(int64_t n, int32_t d, int32_t t) {
   return prepared_bytes(n, d) + kmm_core_ws_bytes(n, t);
 }
 
-int egp_kmm(const float* X, int64_t n, const float* V, int32_t t, const egp_hyper_t* h, float* out, void* ws,
-            size_t ws_bytes, void* stream) {
+static int check_n(int64_t n);
+
+int egp_kmm_ex(const float* X, int64_t n, const float* V, int32_t t, const egp_hyper_t* h, float* out, void* ws,
+               size_t ws_bytes, void* stream, const egp_call_opts_t* opts) {
   int rc;
+  CallOpts co;
+  if ((rc = resolve_opts(opts, &co)) != EGP_OK) return rc;
   if ((rc = validate_hyper(h)) != EGP_OK) return rc;
-  if (n < 1 || n > ((int64_t)1 << 31)) return fail(EGP_ERR_ARG, "n = %lld outside 1..2^31", (long long)n);
+  if ((rc = check_n(n)) != EGP_OK) return rc;
   if (t < 1 || t > EGP_T_MAX) return fail(EGP_ERR_ARG, "t = %d outside 1..%d", t, EGP_T_MAX);
   if ((rc = validate_ptr(X, "X")) != EGP_OK) return rc;
   if ((rc = validate_ptr(V, "V")) != EGP_OK) return rc;
@@ -185,8 +209,12 @@ int egp_kmm(const float* X, int64_t n, const float* V, int32_t t, const egp_hype
   if (ws_bytes < need) return fail(EGP_ERR_WS, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, need);
   hipStream_t s = static_cast<hipStream_t>(stream);
   Prepared P;
-  if ((rc = prepare_points(X, n, h, ws, &P, s)) != EGP_OK) return rc;
+  if ((rc = prepare_points(X, n, h, ws, &P, s, co.mode)) != EGP_OK) return rc;
   return kmm_core(P, V, t, out, static_cast<char*>(ws) + prepared_bytes(n, h->d), s);
+}
+int egp_kmm(const float* X, int64_t n, const float* V, int32_t t, const egp_hyper_t* h, float* out, void* ws,
+            size_t ws_bytes, void* stream) {
+  return egp_kmm_ex(X, n, V, t, h, out, ws, ws_bytes, stream, nullptr);
 }
 
 size_t egp_kmm_grad_ws_bytes(int64_t n, int32_t d, int32_t t) {
@@ -208,11 +236,9 @@ int egp_kmm_grad(const float* X, int64_t n, const float* V, int32_t t, const egp
   if (ws_bytes < need) return fail(EGP_ERR_WS, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, need);
   hipStream_t s = static_cast<hipStream_t>(stream);
   Prepared P;
-  if ((rc = prepare_points(X, n, h, ws, &P, s)) != EGP_OK) return rc;
+  if ((rc = prepare_points(X, n, h, ws, &P, s, EGP_KMM_FP32)) != EGP_OK) return rc;      // fp32 in every mode
   return kmm_grad_core(P, h, V, t, dout, static_cast<char*>(ws) + prepared_bytes(n, h->d), s);
 }
-
-static int check_n(int64_t n);
 
 size_t egp_kmm_grad_bilinear_ws_bytes(int64_t n, int32_t d, int32_t t) {
   if (n < 1 || d < 1 || d > EGP_D_WIDE_MAX || t < 1 || t > 36) return 0;
@@ -234,7 +260,7 @@ int egp_kmm_grad_bilinear(const float* X, int64_t n, const float* A, const float
   if (ws_bytes < need) return fail(EGP_ERR_WS, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, need);
   hipStream_t s = static_cast<hipStream_t>(stream);
   Prepared P;
-  if ((rc = prepare_points(X, n, h, ws, &P, s)) != EGP_OK) return rc;
+  if ((rc = prepare_points(X, n, h, ws, &P, s, EGP_KMM_FP32)) != EGP_OK) return rc;      // fp32 in every mode
   return bilinear_core(P, h, A, B, t, w, out, static_cast<char*>(ws) + prepared_bytes(n, h->d), s);
 }
 
@@ -244,10 +270,12 @@ size_t egp_mll_ws_bytes(int64_t n, int32_t d, int32_t tp, int32_t rank, int32_t 
   return mll_ws_bytes_core(n, d, tp, rank, max_iter);
 }
 
-int egp_mll(const float* X, int64_t n, const float* y, const float* W1, const float* W2, int32_t tp,
-            const egp_hyper_t* h, int32_t rank, int32_t max_iter, float tol, egp_mll_result_t* out, void* ws,
-            size_t ws_bytes, void* stream) {
+int egp_mll_ex(const float* X, int64_t n, const float* y, const float* W1, const float* W2, int32_t tp,
+               const egp_hyper_t* h, int32_t rank, int32_t max_iter, float tol, egp_mll_result_t* out, void* ws,
+               size_t ws_bytes, void* stream, const egp_call_opts_t* opts) {
   int rc;
+  CallOpts co;
+  if ((rc = resolve_opts(opts, &co)) != EGP_OK) return rc;
   if ((rc = validate_hyper(h)) != EGP_OK) return rc;
   if ((rc = check_n(n)) != EGP_OK) return rc;
   if (tp < 1 || tp > 32) return fail(EGP_ERR_ARG, "tp = %d outside 1..32", tp);
@@ -263,13 +291,20 @@ int egp_mll(const float* X, int64_t n, const float* y, const float* W1, const fl
   if ((rc = validate_ptr(ws, "ws")) != EGP_OK) return rc;
   const size_t need = mll_ws_bytes_core(n, h->d, tp, rank, max_iter);
   if (ws_bytes < need) return fail(EGP_ERR_WS, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, need);
-  return mll_core(X, n, y, W1, W2, tp, h, rank, max_iter, tol, out, ws, static_cast<hipStream_t>(stream));
+  return mll_core(X, n, y, W1, W2, tp, h, rank, max_iter, tol, out, ws, static_cast<hipStream_t>(stream), co);
+}
+int egp_mll(const float* X, int64_t n, const float* y, const float* W1, const float* W2, int32_t tp,
+            const egp_hyper_t* h, int32_t rank, int32_t max_iter, float tol, egp_mll_result_t* out, void* ws,
+            size_t ws_bytes, void* stream) {
+  return egp_mll_ex(X, n, y, W1, W2, tp, h, rank, max_iter, tol, out, ws, ws_bytes, stream, nullptr);
 }
 
-int egp_train_adam(const float* X, int64_t n, const float* y, const float* W1, const float* W2, int32_t tp,
-                   int32_t kernel_type, int32_t d, float* lengthscales, float* outputscale, float* noise,
-                   int32_t rank, int32_t max_iter, float tol, const egp_adam_t* opt, egp_mll_result_t* last,
-                   double* mll_history, void* ws, size_t ws_bytes, void* stream) {
+int egp_train_adam_ex(const float* X, int64_t n, const float* y, const float* W1, const float* W2, int32_t tp,
+                      int32_t kernel_type, int32_t d, float* lengthscales, float* outputscale, float* noise,
+                      int32_t rank, int32_t max_iter, float tol, const egp_adam_t* opt, egp_mll_result_t* last,
+                      double* mll_history, void* ws, size_t ws_bytes, void* stream, const egp_call_opts_t* opts) {
+  CallOpts co;
+  if (int rco = resolve_opts(opts, &co)) return rco;
   if (lengthscales == nullptr || outputscale == nullptr || noise == nullptr || opt == nullptr)
     return fail(EGP_ERR_ARG, "lengthscales / outputscale / noise / opt is NULL");
   if (opt->steps < 0 || opt->steps > 100000 || !(opt->lr > 0.f) || !(opt->beta1 >= 0.f && opt->beta1 < 1.f) ||
@@ -291,10 +326,17 @@ int egp_train_adam(const float* X, int64_t n, const float* y, const float* W1, c
   const size_t need = mll_ws_bytes_core(n, d, tp, rank, max_iter);
   if (ws_bytes < need) return fail(EGP_ERR_WS, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, need);
   rc = train_adam_core(X, n, y, W1, W2, tp, &h, lengthscales, rank, max_iter, tol, opt, last, mll_history, ws,
-                       static_cast<hipStream_t>(stream));
+                       static_cast<hipStream_t>(stream), co);
   *outputscale = h.outputscale;
   *noise = h.noise;
   return rc;
+}
+int egp_train_adam(const float* X, int64_t n, const float* y, const float* W1, const float* W2, int32_t tp,
+                   int32_t kernel_type, int32_t d, float* lengthscales, float* outputscale, float* noise,
+                   int32_t rank, int32_t max_iter, float tol, const egp_adam_t* opt, egp_mll_result_t* last,
+                   double* mll_history, void* ws, size_t ws_bytes, void* stream) {
+  return egp_train_adam_ex(X, n, y, W1, W2, tp, kernel_type, d, lengthscales, outputscale, noise, rank, max_iter, tol,
+                           opt, last, mll_history, ws, ws_bytes, stream, nullptr);
 }
 
 int egp_tridiag_logquad(const double* diag, const double* off, int32_t m, double* out) {
@@ -325,7 +367,9 @@ int egp_kmm_cross(const float* Xq, int64_t nq, const float* X, int64_t n, const 
   if ((rc = validate_ptr(ws, "ws")) != EGP_OK) return rc;
   const size_t need = cross_ws_bytes_core(nq, n, h->d, t);
   if (ws_bytes < need) return fail(EGP_ERR_WS, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, need);
-  return cross_core(Xq, nq, X, n, V, t, h, out, ws, static_cast<hipStream_t>(stream), 0);
+  CallOpts co;
+  if ((rc = resolve_opts(nullptr, &co)) != EGP_OK) return rc;
+  return cross_core(Xq, nq, X, n, V, t, h, out, ws, static_cast<hipStream_t>(stream), 0, co.mode);
 }
 
 size_t egp_lanczos_ws_bytes(int64_t n, int32_t d, int32_t r) {
@@ -347,7 +391,9 @@ int egp_lanczos(const float* X, int64_t n, const egp_hyper_t* h, const float* b,
   if ((rc = validate_ptr(ws, "ws")) != EGP_OK) return rc;
   const size_t need = lanczos_ws_bytes_core(n, h->d, r);
   if (ws_bytes < need) return fail(EGP_ERR_WS, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, need);
-  return lanczos_core(X, n, h, b, r, Q, alpha, beta, steps, ws, static_cast<hipStream_t>(stream));
+  CallOpts co;
+  if ((rc = resolve_opts(nullptr, &co)) != EGP_OK) return rc;
+  return lanczos_core(X, n, h, b, r, Q, alpha, beta, steps, ws, static_cast<hipStream_t>(stream), co.mode);
 }
 
 size_t egp_block_lanczos_ws_bytes(int64_t n, int32_t d, int32_t b, int32_t blocks) {
@@ -370,7 +416,9 @@ int egp_block_lanczos(const float* X, int64_t n, const egp_hyper_t* h, const flo
   if ((rc = validate_ptr(ws, "ws")) != EGP_OK) return rc;
   const size_t need = block_lanczos_ws_bytes_core(n, h->d, b, blocks);
   if (ws_bytes < need) return fail(EGP_ERR_WS, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, need);
-  return block_lanczos_core(X, n, h, B0, b, blocks, Q, T, rows, ws, static_cast<hipStream_t>(stream));
+  CallOpts co;
+  if ((rc = resolve_opts(nullptr, &co)) != EGP_OK) return rc;
+  return block_lanczos_core(X, n, h, B0, b, blocks, Q, T, rows, ws, static_cast<hipStream_t>(stream), co.mode);
 }
 
 int egp_predict_dense(const float* Xq, int64_t nq, const float* X, int64_t n, const egp_hyper_t* h, const float* a,
@@ -391,7 +439,10 @@ int egp_predict_dense(const float* Xq, int64_t nq, const float* X, int64_t n, co
   if ((rc = validate_ptr(ws, "ws")) != EGP_OK) return rc;
   const size_t need = predict_ws_bytes_core(nq, n, h->d, r);
   if (ws_bytes < need) return fail(EGP_ERR_WS, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, need);
-  return predict_core(Xq, nq, X, n, h, a, Q, r, nullptr, nullptr, mean, var, ws, static_cast<hipStream_t>(stream), T, ldt);
+  CallOpts co;
+  if ((rc = resolve_opts(nullptr, &co)) != EGP_OK) return rc;
+  return predict_core(Xq, nq, X, n, h, a, Q, r, nullptr, nullptr, mean, var, ws, static_cast<hipStream_t>(stream),
+                      co.mode, T, ldt);
 }
 
 size_t egp_predict_ws_bytes(int64_t nq, int64_t n, int32_t d, int32_t r) {
@@ -419,7 +470,9 @@ int egp_predict(const float* Xq, int64_t nq, const float* X, int64_t n, const eg
   if ((rc = validate_ptr(ws, "ws")) != EGP_OK) return rc;
   const size_t need = predict_ws_bytes_core(nq, n, h->d, var ? r : 0);
   if (ws_bytes < need) return fail(EGP_ERR_WS, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, need);
-  return predict_core(Xq, nq, X, n, h, a, Q, r, alpha, beta, mean, var, ws, static_cast<hipStream_t>(stream));
+  CallOpts co;
+  if ((rc = resolve_opts(nullptr, &co)) != EGP_OK) return rc;
+  return predict_core(Xq, nq, X, n, h, a, Q, r, alpha, beta, mean, var, ws, static_cast<hipStream_t>(stream), co.mode);
 }
 
 static int check_n(int64_t n) {
@@ -487,10 +540,13 @@ size_t egp_mbcg_ws_bytes(int64_t n, int32_t d, int32_t t, int32_t rank, int32_t 
   return mbcg_ws_bytes_core(n, d, t, rank, max_iter);
 }
 
-int egp_mbcg(const float* X, int64_t n, const float* B, int32_t t, const egp_hyper_t* h, const egp_precond_t* P,
-             int32_t max_iter, float tol, float* U, double* cg_coef, double* gamma0, int32_t* iters_done,
-             float* rel_resid, float* resid_hist, void* ws, size_t ws_bytes, void* stream) {
+int egp_mbcg_ex(const float* X, int64_t n, const float* B, int32_t t, const egp_hyper_t* h, const egp_precond_t* P,
+                int32_t max_iter, float tol, float* U, double* cg_coef, double* gamma0, int32_t* iters_done,
+                float* rel_resid, float* resid_hist, void* ws, size_t ws_bytes, void* stream,
+                const egp_call_opts_t* opts) {
   int rc;
+  CallOpts co;
+  if ((rc = resolve_opts(opts, &co)) != EGP_OK) return rc;
   if ((rc = validate_hyper(h)) != EGP_OK) return rc;
   if ((rc = check_n(n)) != EGP_OK) return rc;
   if (t < 1 || t > 33) return fail(EGP_ERR_ARG, "t = %d outside 1..33", t);
@@ -509,7 +565,13 @@ int egp_mbcg(const float* X, int64_t n, const float* B, int32_t t, const egp_hyp
   const size_t need = mbcg_ws_bytes_core(n, h->d, t, P ? P->rank : 0, max_iter);
   if (ws_bytes < need) return fail(EGP_ERR_WS, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, need);
   return mbcg_core(X, n, B, t, h, P, max_iter, tol, U, cg_coef, gamma0, iters_done, rel_resid, resid_hist, ws,
-                   static_cast<hipStream_t>(stream), g_mbcg_shrink.load() != 0);
+                   static_cast<hipStream_t>(stream), co);
+}
+int egp_mbcg(const float* X, int64_t n, const float* B, int32_t t, const egp_hyper_t* h, const egp_precond_t* P,
+             int32_t max_iter, float tol, float* U, double* cg_coef, double* gamma0, int32_t* iters_done,
+             float* rel_resid, float* resid_hist, void* ws, size_t ws_bytes, void* stream) {
+  return egp_mbcg_ex(X, n, B, t, h, P, max_iter, tol, U, cg_coef, gamma0, iters_done, rel_resid, resid_hist, ws,
+                     ws_bytes, stream, nullptr);
 }
 
 }  // extern "C"

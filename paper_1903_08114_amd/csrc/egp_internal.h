@@ -49,17 +49,27 @@ struct Prepared {   // device arrays carved from a workspace by prepare_points()
   int64_t n, npad;
   int d, ks, kernel_type;
   float outputscale, noise;
+  int mode;         // egp_kmm_mode_t of the call that prepared the points; every plan and launch below reads this copy
+};
+
+// Options of one library call, fixed at its extern "C" entry point and passed down by value: the arithmetic of the
+// fused multiply and whether converged trailing columns leave the solver's iteration. Nothing below the entry points
+// reads the process-wide defaults, so a call sees one mode from its workspace layout to its last launch.
+struct CallOpts {
+  int mode;       // egp_kmm_mode_t
+  bool shrink;    // column shrinking in the batched solver
 };
 
 size_t prepared_bytes(int64_t n, int d);
 // Scale, centre and pack X for kernel `h` into ws (>= prepared_bytes). Asynchronous on stream.
 // mean_from: device pointer to the centre of another prepared set (for a second point set), or NULL.
+// mode: the call's egp_kmm_mode_t (recorded in *out; the bf16-split operands are packed only in EGP_KMM_SPLIT_BF16_ALL).
 int prepare_points(const float* X, int64_t n, const egp_hyper_t* h, void* ws, Prepared* out,
-                   hipStream_t stream, const float* mean_from = nullptr);
+                   hipStream_t stream, int mode, const float* mean_from = nullptr);
 
 // out = Khat V using prepared points. ws2 >= kmm_core_ws_bytes. V/out are row-major n x t.
 size_t kmm_core_ws_bytes(int64_t n, int t);
-void kmm_plan_splits(int64_t n_rows, int64_t n_cols, int d, int t, int* used, int* sized);   // host-only planning check
+void kmm_plan_splits(int64_t n_rows, int64_t n_cols, int d, int t, int mode, int* used, int* sized);   // host-only planning check
 int kmm_core(const Prepared& P, const float* V, int t, float* out, void* ws2, hipStream_t stream);
 size_t kmm_cross_ws_bytes(int64_t n_rows, int64_t n_cols, int t);
 int kmm_cross(const Prepared& P, const Prepared& Q, const float* V, int t, float* out, void* ws2,
@@ -75,18 +85,18 @@ int bilinear_core(const Prepared& P, const egp_hyper_t* h, const float* A, const
                   double* out, void* ws2, hipStream_t stream);
 size_t lanczos_ws_bytes_core(int64_t n, int d, int r);
 int lanczos_core(const float* X, int64_t n, const egp_hyper_t* h, const float* b, int r, float* Q, double* alpha,
-                 double* beta, int32_t* steps, void* ws, hipStream_t stream);
+                 double* beta, int32_t* steps, void* ws, hipStream_t stream, int mode);
 size_t cross_ws_bytes_core(int64_t nq, int64_t n, int d, int t);
 int cross_core(const float* Xq, int64_t nq, const float* X, int64_t n, const float* V, int t, const egp_hyper_t* h,
-               float* out, void* ws, hipStream_t stream, int64_t v_ld);
+               float* out, void* ws, hipStream_t stream, int64_t v_ld, int mode);
 size_t predict_ws_bytes_core(int64_t nq, int64_t n, int d, int r);
 int predict_core(const float* Xq, int64_t nq, const float* X, int64_t n, const egp_hyper_t* h, const float* a,
                  const float* Q, int r, const double* alpha, const double* beta, float* mean, float* var, void* ws,
-                 hipStream_t stream,
+                 hipStream_t stream, int mode,
                  const double* Tdense = nullptr, int ldt = 0);
 size_t block_lanczos_ws_bytes_core(int64_t n, int d, int b, int blocks);
 int block_lanczos_core(const float* X, int64_t n, const egp_hyper_t* h, const float* B0, int b, int blocks, float* Q,
-                       double* T, int32_t* rows_out, void* ws, hipStream_t stream);
+                       double* T, int32_t* rows_out, void* ws, hipStream_t stream, int mode);
 size_t pivchol_ws_bytes(int64_t n, int d, int rank);
 int pivchol_core(const float* X, int64_t n, const egp_hyper_t* h, float tol_abs, egp_precond_t* P, void* ws,
                  hipStream_t stream);
@@ -110,19 +120,19 @@ int kmm_cm_dot_blocks(int64_t npad);
 int kmm_core_cm(const Prepared& P, const float* V, int t, float* out, void* ws2, float* dot_part, int dot_ld,
                 hipStream_t stream);
 size_t mbcg_ws_bytes_core(int64_t n, int d, int t, int rank, int max_iter);
-// shrink: trailing columns that have met the tolerance leave the iteration (see egp_set_mbcg_shrink)
+// co.shrink: trailing columns that have met the tolerance leave the iteration (see egp_mbcg)
 int mbcg_core(const float* X, int64_t n, const float* B, int t, const egp_hyper_t* h, const egp_precond_t* P,
               int max_iter, float tol, float* U, double* cg_coef, double* gamma0, int32_t* iters_done,
-              float* rel_resid, float* resid_hist, void* ws, hipStream_t stream, bool shrink = false);
+              float* rel_resid, float* resid_hist, void* ws, hipStream_t stream, const CallOpts& co);
 
 size_t mll_ws_bytes_core(int64_t n, int d, int tp, int rank, int max_iter);
 int mll_core(const float* X, int64_t n, const float* y, const float* W1, const float* W2, int tp,
              const egp_hyper_t* h, int rank_req, int max_iter, float tol, egp_mll_result_t* res, void* ws,
-             hipStream_t stream);
+             hipStream_t stream, const CallOpts& co);
 int train_adam_core(const float* X, int64_t n, const float* y, const float* W1, const float* W2, int tp,
                     egp_hyper_t* h, float* lengthscales_io, int rank, int max_iter, float tol,
                     const egp_adam_t* opt, egp_mll_result_t* last, double* mll_history, void* ws,
-                    hipStream_t stream);
+                    hipStream_t stream, const CallOpts& co);
 }  // namespace egp
 #include <vector>
 namespace egp {
@@ -138,9 +148,6 @@ struct ProfScope {   // records an event pair around the launches made during it
   hipStream_t stream_;
   void* slot_;
 };
-
-bool mbcg_shrink();     // egp_set_mbcg_shrink
-int kmm_mode();     // EGP_KMM_FP32 or EGP_KMM_SPLIT_BF16 (egp_set_kmm_mode)
 
 int validate_hyper(const egp_hyper_t* h, int d_max = EGP_D_WIDE_MAX);
 int validate_ptr(const void* p, const char* name);

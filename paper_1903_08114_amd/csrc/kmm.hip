@@ -273,7 +273,7 @@ size_t prepared_bytes(int64_t n, int d) {
 }
 
 int prepare_points(const float* X, int64_t n, const egp_hyper_t* h, void* ws, Prepared* out,
-                   hipStream_t stream, const float* mean_from) {
+                   hipStream_t stream, int mode, const float* mean_from) {
   const int d = h->d;
   const int64_t npad = padded_points(n);
   const int ks = ksteps_for(d);
@@ -298,6 +298,7 @@ int prepare_points(const float* X, int64_t n, const egp_hyper_t* h, void* ws, Pr
   out->kernel_type = h->kernel_type;
   out->outputscale = h->outputscale;
   out->noise = h->noise;
+  out->mode = mode;
 
   ScaleArg sc;
   const double c = point_scale(h->kernel_type);
@@ -313,28 +314,30 @@ int prepare_points(const float* X, int64_t n, const egp_hyper_t* h, void* ws, Pr
   }
   hipLaunchKernelGGL(pack_points, dim3((unsigned)((npad + 255) / 256)), dim3(256), 0, stream, X, n, npad, d,
                      ks, mean, sc, out->Xp, out->nrm);
-  if (kmm_mode() == EGP_KMM_SPLIT_BF16_ALL && d <= EGP_D_MAX) launch_pack_points_bf(*out, stream);
+  if (mode == EGP_KMM_SPLIT_BF16_ALL && d <= EGP_D_MAX) launch_pack_points_bf(*out, stream);
   EGP_HIP(hipGetLastError());
   return EGP_OK;
 }
 
 namespace {
 
-Plan plan_for_mode(int64_t npad_rows, int64_t npad_cols, int ks, int d, int nb, int extra, bool square = false) {
+// `mode` is the call's own copy of the arithmetic mode (Prepared::mode): planning and launching read the same value.
+Plan plan_for_mode(int mode, int64_t npad_rows, int64_t npad_cols, int ks, int d, int nb, int extra,
+                   bool square = false) {
   if (ks > 8) {      // d > 31: fp32 wide kernels in every mode, symmetric where that applies unless switched off
-    if (kmm_mode() != EGP_KMM_FP32_ONE_SIDED && square && wide_sym_applies(npad_rows, npad_cols, ks, nb, extra))
+    if (mode != EGP_KMM_FP32_ONE_SIDED && square && wide_sym_applies(npad_rows, npad_cols, ks, nb, extra))
       return make_plan_wide_sym(npad_rows, ks, extra);
     return make_plan_wide(npad_rows, npad_cols, ks, nb, extra);
   }
-  if (kmm_mode() == EGP_KMM_FP32) {     // shapes the symmetric kernel does not cover run the one-sided one
+  if (mode == EGP_KMM_FP32) {     // shapes the symmetric kernel does not cover run the one-sided one
     const int r = square ? sym_row_tiles(npad_rows, npad_cols, ks, nb, extra) : 0;
     if (r > 0) return make_plan_sym(npad_rows, r, ks, nb, extra);
     return make_plan(npad_rows, npad_cols, ks, nb, extra);
   }
-  if (nb == 0 && kmm_mode() != EGP_KMM_SPLIT_BF16_ALL)
+  if (nb == 0 && mode != EGP_KMM_SPLIT_BF16_ALL)
     return make_plan(npad_rows, npad_cols, ks, nb, extra);     // a single column has no contraction to split
-  return kmm_mode() == EGP_KMM_SPLIT_BF16_ALL ? make_plan_bf(npad_rows, npad_cols, d, nb, extra)
-                                              : make_plan(npad_rows, npad_cols, ks, nb, extra);
+  return mode == EGP_KMM_SPLIT_BF16_ALL ? make_plan_bf(npad_rows, npad_cols, d, nb, extra)
+                                        : make_plan(npad_rows, npad_cols, ks, nb, extra);
 }
 // Upper bound of the column-split count over every launch shape of every mode. Each plan takes
 // splits <= min(64, max(1, 1024 / row_blocks), stages_total); a workgroup covers at most 64 * 8 rows and a stage at
@@ -363,13 +366,14 @@ int launch_ks(const Prepared& P, const Prepared& Q, const Plan& pl, int nb, int 
     return launch_wide(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
   }
   if (pl.sym) return launch_sym(P, pl, nb, extra, Vp, Ep, Part, cm, stream);
-  if (nb == 0 && kmm_mode() != EGP_KMM_SPLIT_BF16_ALL) {
+  const int mode = P.mode;
+  if (nb == 0 && mode != EGP_KMM_SPLIT_BF16_ALL) {
     // a single column has no MFMA contraction to move to bf16: the fp32 kernel serves the contraction-only split mode
     ProfScope prof(kProfKmm, stream);
     return launch_all_ks<0>(P, Q, pl, nb, extra, Vp, Ep, Part, cm, stream);
   }
-  if (kmm_mode() == EGP_KMM_SPLIT_BF16_ALL) return launch_all_bf(P, Q, pl, nb, extra, Vp, Vb, Ep, Part, cm, stream);
-  if (kmm_mode() == EGP_KMM_SPLIT_BF16) {
+  if (mode == EGP_KMM_SPLIT_BF16_ALL) return launch_all_bf(P, Q, pl, nb, extra, Vp, Vb, Ep, Part, cm, stream);
+  if (mode == EGP_KMM_SPLIT_BF16) {
     {
       ProfScope prof(kProfPack, stream);
       launch_split_vp(Vp, (P.npad >> 4) * nb * 64, stream);
@@ -395,23 +399,23 @@ static void next_group(int rem, int ks, int* nb, int* extra, int* tg) {
 }
 
 // Host-only check of the launch planning (no GPU work): the largest column-split count that a product of these
-// sizes launches with in the current mode, row-major and (t <= 33, square) column-major entry alike, and the count
+// sizes launches with in mode `mode`, row-major and (t <= 33, square) column-major entry alike, and the count
 // its workspace holds.
-void kmm_plan_splits(int64_t n_rows, int64_t n_cols, int d, int t, int* used, int* sized) {
+void kmm_plan_splits(int64_t n_rows, int64_t n_cols, int d, int t, int mode, int* used, int* sized) {
   const int64_t prow = padded_points(n_rows), pcol = padded_points(n_cols);
   const int ks = ksteps_for(d);
   int worst = 0;
   for (int c0 = 0; c0 < t;) {
     int nb, extra, tg;
     next_group(t - c0, ks, &nb, &extra, &tg);
-    const int s = plan_for_mode(prow, pcol, ks, d, nb, extra, prow == pcol).splits;
+    const int s = plan_for_mode(mode, prow, pcol, ks, d, nb, extra, prow == pcol).splits;
     if (s > worst) worst = s;
     c0 += tg;
   }
   if (t <= 33 && prow == pcol) {
     const bool single = t == 1 && ks <= 8;
     const int nb = single ? 0 : (t > 17 ? 2 : 1), extra = (single || t == 17 || t == 33) ? 1 : 0;
-    const int s = plan_for_mode(prow, pcol, ks, d, nb, extra, true).splits;
+    const int s = plan_for_mode(mode, prow, pcol, ks, d, nb, extra, true).splits;
     if (s > worst) worst = s;
   }
   *used = worst;
@@ -464,7 +468,7 @@ int kmm_cross(const Prepared& P, const Prepared& Q, const float* V, int t, float
     int nb, extra, tg;
     next_group(rem, P.ks, &nb, &extra, &tg);
     const int ts = 16 * nb + extra;
-    const Plan pl = plan_for_mode(Q.npad, npad, P.ks, P.d, nb, extra, square);
+    const Plan pl = plan_for_mode(P.mode, Q.npad, npad, P.ks, P.d, nb, extra, square);
     if (int rc = check_splits(pl, splits_max)) return rc;
     if (v_ld > 0) {
       // columns stored one after the other (e.g. Lanczos vectors): 16 columns per block, the odd one as Ep
@@ -513,7 +517,7 @@ int kmm_core_cm(const Prepared& P, const float* V, int t, float* out, void* ws2,
   const bool single = t == 1 && P.ks <= 8;      // one column: consumed straight from the state array on the VALU
   const int nb = single ? 0 : (t > 17 ? 2 : 1);
   const int extra = (single || t == 17 || t == 33) ? 1 : 0;
-  const Plan pl = plan_for_mode(npad, npad, P.ks, P.d, nb, extra, true);
+  const Plan pl = plan_for_mode(P.mode, npad, npad, P.ks, P.d, nb, extra, true);
   if (int rc = check_splits(pl, splits_max)) return rc;
   const int ts = 16 * nb + extra;
   f4* Vp = reinterpret_cast<f4*>(w);

@@ -184,13 +184,14 @@ size_t mbcg_ws_bytes_core(int64_t n, int d, int t, int rank, int max_iter) {
 
 int mbcg_core(const float* X, int64_t n, const float* B, int t, const egp_hyper_t* h, const egp_precond_t* P,
               int max_iter, float tol, float* U, double* cg_coef, double* gamma0, int32_t* iters_done,
-              float* rel_resid, float* resid_hist, void* ws, hipStream_t stream, bool shrink) {
+              float* rel_resid, float* resid_hist, void* ws, hipStream_t stream, const CallOpts& co) {
+  const bool shrink = co.shrink;
   const int rank = P ? P->rank : 0;
   const MbcgWs lay = mbcg_layout(n, h->d, t, rank, max_iter);
   const int64_t ld = padded_points(n);
   char* w = static_cast<char*>(ws);
   Prepared prep;
-  int rc = prepare_points(X, n, h, w, &prep, stream);
+  int rc = prepare_points(X, n, h, w, &prep, stream, co.mode);
   if (rc != EGP_OK) return rc;
   w += lay.prep;
   void* kmm_ws = w;
@@ -246,6 +247,17 @@ int mbcg_core(const float* X, int64_t n, const float* B, int t, const egp_hyper_
   }
 
   std::vector<float> rel(t, 0.f);
+  if (max_iter == 0) {
+    // no iteration runs: U = 0, so the residual is b itself and a column's relative residual is 1 (0 for b_c = 0)
+    std::vector<float> bb((size_t)t * kPartLd);
+    EGP_HIP(hipMemcpyAsync(bb.data(), bb_part, bb.size() * sizeof(float), hipMemcpyDeviceToHost, stream));
+    EGP_HIP(hipStreamSynchronize(stream));
+    for (int c = 0; c < t; ++c) {
+      double s = 0.0;
+      for (int b = 0; b < kColBlocks; ++b) s += (double)bb[(size_t)c * kPartLd + b];
+      rel[c] = s > 0.0 ? 1.f : 0.f;
+    }
+  }
   int it = 0;
   int cur = 0;
   // Columns [0, ta) take part in an iteration. Without `shrink` ta stays t (converged columns keep iterating, which

@@ -188,7 +188,7 @@ size_t mll_ws_bytes_core(int64_t n, int d, int tp, int rank, int max_iter) {
 
 int mll_core(const float* X, int64_t n, const float* y, const float* W1, const float* W2, int tp,
              const egp_hyper_t* h, int rank_req, int max_iter, float tol, egp_mll_result_t* res, void* ws,
-             hipStream_t stream) {
+             hipStream_t stream, const CallOpts& co) {
   const int d = h->d, t = tp + 1;
   const MllWs lay = mll_layout(n, d, tp, rank_req, max_iter);
   char* w = static_cast<char*>(ws);
@@ -214,7 +214,7 @@ int mll_core(const float* X, int64_t n, const float* y, const float* W1, const f
   double logdetP = 0.0;
   int rc;
   if (rank_req > 0) {
-    rc = pivchol_core(X, n, h, 0.f, &P, sub, stream);
+    rc = pivchol_core(X, n, h, 0.f, &P, sub, stream);      // (uses no fused multiply: no mode to pass)
     if (rc != EGP_OK) return rc;
     logdetP = small[(size_t)rank_req * rank_req];
   }
@@ -240,7 +240,7 @@ int mll_core(const float* X, int64_t n, const float* y, const float* W1, const f
   int32_t iters = 0;
   // (with column shrinking on, a probe's tridiagonal below ends where the probe left the iteration)
   rc = mbcg_core(X, n, B, t, h, Pp, max_iter, tol, U, coef.data(), gamma0.data(), &iters, rel.data(), nullptr, sub,
-                 stream, mbcg_shrink());
+                 stream, co);
   if (rc != EGP_OK) return rc;
   res->iters = iters;
   res->precond_rank = rank;
@@ -298,7 +298,7 @@ int mll_core(const float* X, int64_t n, const float* y, const float* W1, const f
   wcol[0] = 0.5f;
   for (int c = 1; c < t; ++c) wcol[c] = -0.5f / (float)tp;
   Prepared prep;
-  rc = prepare_points(X, n, h, prep_ws, &prep, stream);
+  rc = prepare_points(X, n, h, prep_ws, &prep, stream, EGP_KMM_FP32);      // the gradient forms are fp32 in every mode
   if (rc != EGP_OK) return rc;
   std::vector<double> forms(d + 1, 0.0);
   rc = bilinear_core(prep, h, U, Vp, t, wcol.data(), forms.data(), sub, stream);
@@ -322,7 +322,7 @@ int mll_core(const float* X, int64_t n, const float* y, const float* W1, const f
 int train_adam_core(const float* X, int64_t n, const float* y, const float* W1, const float* W2, int tp,
                     egp_hyper_t* h, float* lengthscales_io, int rank, int max_iter, float tol,
                     const egp_adam_t* opt, egp_mll_result_t* last, double* mll_history, void* ws,
-                    hipStream_t stream) {
+                    hipStream_t stream, const CallOpts& co) {
   const int d = h->d, np = d + 2;
   const double floor_ = opt->noise_floor > 0.f ? (double)opt->noise_floor : 0.0;
   std::vector<double> phi(np), m(np, 0.0), v(np, 0.0);
@@ -339,7 +339,7 @@ int train_adam_core(const float* X, int64_t n, const float* y, const float* W1, 
     h->outputscale = (float)exp(phi[d]);
     h->noise = (float)(floor_ + exp(phi[d + 1]));
     if (step == opt->steps && last == nullptr && mll_history == nullptr) break;
-    const int rc = mll_core(X, n, y, W1, W2, tp, h, rank, max_iter, tol, &res, ws, stream);
+    const int rc = mll_core(X, n, y, W1, W2, tp, h, rank, max_iter, tol, &res, ws, stream, co);
     if (rc != EGP_OK) return rc;
     if (mll_history) mll_history[step] = res.mll;
     if (step == opt->steps) break;        // the last evaluation only reports the objective at the final parameters

@@ -583,7 +583,7 @@ int pivchol_core(const float* X, int64_t n, const egp_hyper_t* h, float tol_abs,
                  hipStream_t stream) {
   const int cap = P->rank;
   Prepared prep;
-  int rc = prepare_points(X, n, h, ws, &prep, stream);
+  int rc = prepare_points(X, n, h, ws, &prep, stream, EGP_KMM_FP32);      // kernel rows by direct differences: fp32 only
   if (rc != EGP_OK) return rc;
   char* w = static_cast<char*>(ws) + prepared_bytes(n, h->d);
   float* diag = reinterpret_cast<float*>(w);

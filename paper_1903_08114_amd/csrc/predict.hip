@@ -74,12 +74,12 @@ size_t lanczos_ws_bytes_core(int64_t n, int d, int r) { return lanczos_layout(n,
 // r Lanczos steps on Khat from the start vector b, full re-orthogonalisation (two projection passes per step).
 // Q: device [r][n]; alpha[r], beta[r-1] on the host; *steps <= r (fewer when the Krylov space is exhausted).
 int lanczos_core(const float* X, int64_t n, const egp_hyper_t* h, const float* b, int r, float* Q, double* alpha,
-                 double* beta, int32_t* steps, void* ws, hipStream_t stream) {
+                 double* beta, int32_t* steps, void* ws, hipStream_t stream, int mode) {
   const LanczosWs lay = lanczos_layout(n, h->d, r);
   const int64_t ld = padded_points(n);
   char* w = static_cast<char*>(ws);
   Prepared prep;
-  int rc = prepare_points(X, n, h, w, &prep, stream);
+  int rc = prepare_points(X, n, h, w, &prep, stream, mode);
   if (rc != EGP_OK) return rc;
   w += lay.prep;
   void* kmm_ws = w;
@@ -161,13 +161,13 @@ BlockWs block_layout(int64_t n, int d, int b, int rcap) {
 size_t block_lanczos_ws_bytes_core(int64_t n, int d, int b, int blocks) { return block_layout(n, d, b, b * blocks).total; }
 
 int block_lanczos_core(const float* X, int64_t n, const egp_hyper_t* h, const float* B0, int b, int blocks, float* Q,
-                       double* T, int32_t* rows_out, void* ws, hipStream_t stream) {
+                       double* T, int32_t* rows_out, void* ws, hipStream_t stream, int mode) {
   const int rcap = b * blocks;
   const BlockWs lay = block_layout(n, h->d, b, rcap);
   const int64_t ld = padded_points(n);
   char* w = static_cast<char*>(ws);
   Prepared prep;
-  int rc = prepare_points(X, n, h, w, &prep, stream);
+  int rc = prepare_points(X, n, h, w, &prep, stream, mode);
   if (rc != EGP_OK) return rc;
   w += lay.prep;
   void* kmm_ws = w;
@@ -285,13 +285,13 @@ size_t cross_ws_bytes_core(int64_t nq, int64_t n, int d, int t) {
 }
 
 int cross_core(const float* Xq, int64_t nq, const float* X, int64_t n, const float* V, int t, const egp_hyper_t* h,
-               float* out, void* ws, hipStream_t stream, int64_t v_ld) {
+               float* out, void* ws, hipStream_t stream, int64_t v_ld, int mode) {
   char* w = static_cast<char*>(ws);
   Prepared P, Qs;
-  int rc = prepare_points(X, n, h, w, &P, stream);
+  int rc = prepare_points(X, n, h, w, &P, stream, mode);
   if (rc != EGP_OK) return rc;
   w += prepared_bytes(n, h->d);
-  rc = prepare_points(Xq, nq, h, w, &Qs, stream, P.mean);
+  rc = prepare_points(Xq, nq, h, w, &Qs, stream, mode, P.mean);
   if (rc != EGP_OK) return rc;
   w += prepared_bytes(nq, h->d);
   return kmm_cross(P, Qs, V, t, out, w, stream, v_ld);
@@ -306,8 +306,8 @@ size_t predict_ws_bytes_core(int64_t nq, int64_t n, int d, int r) {
 // mean = K(Xq, X) a; var = s - g^T T^{-1} g with g = Q K(X, xq) (var may be NULL). Synchronises.
 int predict_core(const float* Xq, int64_t nq, const float* X, int64_t n, const egp_hyper_t* h, const float* a,
                  const float* Q, int r, const double* alpha, const double* beta, float* mean, float* var, void* ws,
-                 hipStream_t stream, const double* Tdense, int ldt) {
-  int rc = cross_core(Xq, nq, X, n, a, 1, h, mean, ws, stream, 0);
+                 hipStream_t stream, int mode, const double* Tdense, int ldt) {
+  int rc = cross_core(Xq, nq, X, n, a, 1, h, mean, ws, stream, 0, mode);
   if (rc != EGP_OK) return rc;
   if (var == nullptr) {
     EGP_HIP(hipStreamSynchronize(stream));
@@ -343,7 +343,7 @@ int predict_core(const float* Xq, int64_t nq, const float* X, int64_t n, const e
   char* w = static_cast<char*>(ws);
   const size_t sub = cross_ws_bytes_core(nq, n, h->d, predict_cross_t(r));
   float* G = reinterpret_cast<float*>(w + sub);
-  rc = cross_core(Xq, nq, X, n, Q, r, h, G, ws, stream, n);      // G (nq x r) = K(Xq, X) Q^T
+  rc = cross_core(Xq, nq, X, n, Q, r, h, G, ws, stream, n, mode);      // G (nq x r) = K(Xq, X) Q^T
   if (rc != EGP_OK) return rc;
   std::vector<float> Gh((size_t)nq * r), vh(nq);
   EGP_HIP(hipMemcpyAsync(Gh.data(), G, Gh.size() * sizeof(float), hipMemcpyDeviceToHost, stream));

@@ -74,8 +74,10 @@ def test_argument_validation_without_device_work(lib):
     assert b"X is NULL" in lib.egp_last_error()
     # misaligned V
     assert lib.egp_kmm(fake, 10, C.c_void_p(0x1004), 2, C.byref(h), fake, fake, 1 << 30, None) == -1
-    # n < 1, t out of range
+    # n < 1, n beyond 2^31 - 1 (the same bound in every entry point), t out of range
     assert lib.egp_kmm(fake, 0, fake, 2, C.byref(h), fake, fake, 1 << 30, None) == -1
+    assert lib.egp_kmm(fake, 1 << 31, fake, 2, C.byref(h), C.c_void_p(0x3000), C.c_void_p(0x2000), 1 << 62, None) == -1
+    assert b"2^31-1" in lib.egp_last_error()
     assert lib.egp_kmm(fake, 10, fake, 0, C.byref(h), fake, fake, 1 << 30, None) == -1
     assert lib.egp_kmm(fake, 10, fake, 5000, C.byref(h), fake, fake, 1 << 30, None) == -1
     # aliasing
@@ -194,6 +196,64 @@ def test_partial_sum_buffer_holds_every_launch_plan(lib, mode):
                         assert 1 <= used <= sized <= 64, (rows, cols, d, t, mode, used, sized)
     finally:
         assert lib.egp_set_kmm_mode(0) == 0
+
+
+def test_call_options_fix_the_mode_per_call(lib):
+    """The *_ex entry points take the arithmetic mode per call: the launch plan of a call depends on the mode in its
+    options alone, whatever the process-wide default is at that moment (and NULL / -1 take the default)."""
+    from paper_1903_08114_amd.binding import _CallOpts
+    shapes = [(40000, 40000, 11, 17), (1 << 20, 1 << 20, 11, 16), (5000, 5000, 25, 16), (2047, 2047, 159, 18),
+              (70000, 70000, 90, 17), (1 << 18, 1 << 18, 11, 33)]
+
+    def plan(opts, shape):
+        used, sized = C.c_int32(-1), C.c_int32(-1)
+        assert lib.egp_kmm_plan_splits_ex(*shape, opts, C.byref(used), C.byref(sized)) == 0
+        return used.value, sized.value
+
+    try:
+        by_default = {}
+        for mode in range(4):
+            assert lib.egp_set_kmm_mode(mode) == 0
+            by_default[mode] = [_plan_splits(lib, *s) for s in shapes]
+            assert [plan(None, s) for s in shapes] == by_default[mode]
+            assert [plan(C.byref(_CallOpts(-1, -1)), s) for s in shapes] == by_default[mode]
+        assert by_default[0] != by_default[3]      # the symmetric and the one-sided plans differ on these shapes
+        for default in range(4):
+            assert lib.egp_set_kmm_mode(default) == 0
+            for mode in range(4):
+                assert [plan(C.byref(_CallOpts(mode, -1)), s) for s in shapes] == by_default[mode]
+                assert lib.egp_get_kmm_mode() == default      # a call's options never touch the default
+    finally:
+        assert lib.egp_set_kmm_mode(0) == 0
+    # bad option values are refused before anything else is looked at
+    used, sized = C.c_int32(), C.c_int32()
+    assert lib.egp_kmm_plan_splits_ex(4096, 4096, 3, 1, C.byref(_CallOpts(7, -1)), C.byref(used), C.byref(sized)) == -1
+    assert lib.egp_kmm_plan_splits_ex(4096, 4096, 3, 1, C.byref(_CallOpts(0, 5)), C.byref(used), C.byref(sized)) == -1
+    fake = C.c_void_p(0x1000)
+    from paper_1903_08114_amd.binding import _hyper
+    h = _hyper(0, [1.0, 1.0], 1.0, 0.1)
+    assert lib.egp_kmm_ex(fake, 10, fake, 2, C.byref(h), C.c_void_p(0x3000), C.c_void_p(0x2000), 1 << 30, None,
+                          C.byref(_CallOpts(9, -1))) == -1
+    assert b"kmm mode" in lib.egp_last_error()
+    assert lib.egp_mbcg_ex(fake, 10, fake, 2, C.byref(h), None, 5, 0.1, C.c_void_p(0x3000), None, None, None, None,
+                           None, C.c_void_p(0x2000), 1 << 30, None, C.byref(_CallOpts(-1, 2))) == -1
+
+
+def test_no_mode_read_below_the_entry_points():
+    """The process-wide defaults are read in csrc/api.hip only (once per call, by resolve_opts); no other source
+    names them."""
+    csrc = os.path.join(ROOT, "paper_1903_08114_amd", "csrc")
+    for f in os.listdir(csrc):
+        text = open(os.path.join(csrc, f)).read()
+        if f != "api.hip":
+            assert "g_kmm_mode" not in text and "g_mbcg_shrink" not in text and "kmm_mode()" not in text, f
+    api = open(os.path.join(csrc, "api.hip")).read()
+    body = api.split("static int resolve_opts", 1)[1]
+    tail = body.split("\n}\n", 1)[1]
+    # after resolve_opts only the setters and getters touch the atomics
+    for line in tail.splitlines():
+        if "g_kmm_mode" in line or "g_mbcg_shrink" in line:
+            assert ".store(" in line or "egp_get_" in line, line
 
 
 def test_plan_check_pins_a_shape_with_two_row_tiles_and_short_stages(lib):

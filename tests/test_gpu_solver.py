@@ -213,6 +213,14 @@ def test_mbcg_batched_equals_single_and_duplicates(egp):
     # so the solutions are compared after convergence
     single = egp.mbcg(Xd, _cuda(b), ls, 1.0, 0.1, orc.RBF, max_iter=15, tol=0.0)
     assert np.allclose(batched["alphas"][:3, 0], single["alphas"][:3, 0], rtol=1e-4)
+    # each side against the oracle's textbook PCG on the dense matrix: coefficients of the first iterations to 1e-3
+    # and the residual history while it is above the fp32 floor (later fp32 iterates drift, as the solver's
+    # specification expects of CG in single precision)
+    ref = orc.pcg(orc.khat(X, orc.Hyper(orc.RBF, ls, 1.0, 0.1)), b[:, 0], max_iter=15)
+    for side in (batched, single):
+        assert np.allclose(side["alphas"][:5, 0], ref["alphas"][:5], rtol=1e-3)
+        assert np.allclose(side["betas"][:4, 0], ref["betas"][:4], rtol=1e-3)
+        assert np.allclose(side["resid_hist"][:6, 0], ref["rel_resid"][:6], rtol=2e-2)
     both = egp.mbcg(Xd, _cuda(B), ls, 1.0, 0.1, orc.RBF, max_iter=400, tol=1e-6)
     alone = egp.mbcg(Xd, _cuda(b), ls, 1.0, 0.1, orc.RBF, max_iter=400, tol=1e-6)
     u1, u2 = both["U"].cpu().numpy()[:, 0], alone["U"].cpu().numpy()[:, 0]
