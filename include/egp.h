@@ -331,6 +331,22 @@ int egp_profile_read(int32_t group, double* total_ms /*host*/, int64_t* launches
  * Reads and writes exactly 4*count bytes each; used to calibrate hardware HBM-traffic counters. */
 int egp_calib_copy(const float* src /*device*/, float* dst /*device*/, int64_t count, void* stream);
 
+/* egp_kmm for callers that cannot allocate device memory or provide a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc. Same product, same kernels, same bits as egp_kmm in the
+ * process-default mode; the workspace is a device array built into the library (EGP_NOALLOC_SCRATCH_BYTES per GPU the
+ * library runs on, held until the process ends). The call allocates and frees nothing on the device.
+ *   - sizes whose egp_kmm_ws_bytes(n, d, t) exceeds EGP_NOALLOC_SCRATCH_BYTES return EGP_ERR_ARG (for d = 11, t = 17
+ *     that is n up to 146944; for d = 18, t = 17 up to 95744); use egp_kmm with a workspace beyond that;
+ *   - every call on a GPU shares that GPU's array: calls that overlap in time on one GPU (different streams or
+ *     threads) race; calls on one stream are ordered and safe. What the kernels need at zero is cleared by the call;
+ *   - the first call on a device looks up the array's address (hipGetSymbolAddress); make one call outside a
+ *     capture before capturing;
+ *   - keep profiling (egp_profile_enable) off around it: event brackets are host-side allocations.
+ * Asynchronous on `stream`. */
+#define EGP_NOALLOC_SCRATCH_BYTES (128u << 20)
+int egp_kmm_noalloc(const float* X /*device n x d*/, int64_t n, const float* V /*device n x t*/, int32_t t,
+                    const egp_hyper_t* h /*host*/, float* out /*device n x t*/, void* stream);
+
 /* Message of the last failing call on this thread ("" if none). */
 const char* egp_last_error(void);
 

@@ -146,6 +146,9 @@ def lib():
         L.egp_train_adam_ex.argtypes = L.egp_train_adam.argtypes + opts
         L.egp_kmm_plan_splits_ex.argtypes = [C.c_int64, C.c_int64, C.c_int32, C.c_int32, C.POINTER(_CallOpts),
                                              C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+        L.egp_kmm_noalloc.restype = C.c_int
+        L.egp_kmm_noalloc.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.POINTER(_Hyper), C.c_void_p,
+                                      C.c_void_p]
         _lib = L
     return _lib
 
@@ -294,6 +297,20 @@ def kmm(X, V, lengthscales, outputscale, noise, kernel_type, out=None, ws=None, 
     o = _opts(mode)
     _check(L.egp_kmm_ex(_dev(X, "X"), n, _dev(V, "V"), t, C.byref(h), _dev(out, "out"),
                         C.c_void_p(ws.data_ptr()), ws.numel(), _stream(), C.byref(o)))
+    return out
+
+
+def kmm_noalloc(X, V, lengthscales, outputscale, noise, kernel_type, out=None):
+    """egp_kmm_noalloc: the same product with the library's built-in scratch array as workspace (no workspace is
+    allocated or passed; sizes beyond the array raise EgpError). `out` is still the caller's."""
+    import torch
+    L = lib()
+    n, d = X.shape
+    t = V.shape[1]
+    h = _hyper(kernel_type, lengthscales, outputscale, noise)
+    if out is None:
+        out = torch.empty_like(V)
+    _check(L.egp_kmm_noalloc(_dev(X, "X"), n, _dev(V, "V"), t, C.byref(h), _dev(out, "out"), _stream()))
     return out
 
 
