@@ -149,7 +149,7 @@ def main():
     # contraction once per side; the diagonal block (and for an even block count the half-way block) one-sided
     npad = (n + 511) // 512 * 512
     sym_used = npad >= 32768 and d <= 31
-    nblk = npad // 512 if d <= 14 else npad // 256
+    nblk = npad // 512      # 512-row blocks: four waves of eight row tiles (every 16- and 17-column shape up to d = 14)
     even = nblk % 2 == 0
     plain_blocks = 1 + (1 if even else 0)
     dual_blocks = nblk // 2 - (1 if even else 0)

@@ -305,6 +305,7 @@ struct Plan {
   int splits, stages_per_split, stages_total, row_blocks;
   int extra_slabs = 0;      // float slabs of room behind the per-split ones (symmetric kernels: 2, one int64 slab)
   bool sym = false;         // launch the symmetric kernel
+  int waves = 4;            // waves per workgroup of the symmetric kernel (4 or 8)
 };
 
 // Launch shapes (row tiles per wave, column tiles per LDS stage). Up to 8 k-steps (d <= 31) the wide shape

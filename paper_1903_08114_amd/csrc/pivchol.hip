@@ -12,6 +12,8 @@
 
 #include <math.h>
 
+#include <atomic>
+#include <thread>
 #include <vector>
 
 #include "egp_internal.h"
@@ -19,6 +21,8 @@
 namespace egp {
 
 namespace {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
 
 constexpr int kPcBlocks = 1024;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -31,6 +35,12 @@ __device__ __forceinline__ float transform_rt(int kind, float acc) {
   if (kind == EGP_MATERN12) return e;
   return __builtin_fmaf(__builtin_fmaf(a, kLn2 * kLn2 / 3.0f, kLn2), a, 1.0f) * e;
 }
+
+__device__ __forceinline__ f4 fma4(f4 a, f4 b, f4 c) {
+  return (f4){__builtin_fmaf(a.x, b.x, c.x), __builtin_fmaf(a.y, b.y, c.y), __builtin_fmaf(a.z, b.z, c.z),
+              __builtin_fmaf(a.w, b.w, c.w)};
+}
+__device__ __forceinline__ f4 fma4(f4 a, float b, f4 c) { return fma4(a, (f4){b, b, b, b}, c); }
 
 struct Cand { float v; int i; };
 __device__ __forceinline__ Cand better(Cand a, Cand b) {
@@ -77,6 +87,7 @@ __global__ __launch_bounds__(256) void pc_init(float* __restrict__ diag, int64_t
 }
 
 // One step of the factorisation. Points are read from the packed MFMA-operand layout.
+template <bool VEC>
 __global__ __launch_bounds__(256) void pc_step(const float* __restrict__ Xp, int ks, int d, int kind, float s,
                                                int64_t n, float* __restrict__ L, float* __restrict__ diag, int m,
                                                float tol_abs, PcState st) {
@@ -115,6 +126,68 @@ __global__ __launch_bounds__(256) void pc_step(const float* __restrict__ Xp, int
   const float inv_root = 1.0f / root;
 
   Cand best = {-INFINITY, 0x7fffffff};
+  if (VEC) {
+    // Four consecutive points per thread (n a multiple of 4, L 16-byte aligned): every column of L is read with
+    // 16-byte loads, eight columns in flight per thread. The step is a matrix-vector product with the n x m factor
+    // (n (m + d + 3) floats of traffic), so what matters is how many bytes are in flight.
+    for (int64_t i0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4; i0 < n; i0 += (int64_t)gridDim.x * 1024) {
+      const f4 dg = *reinterpret_cast<const f4*>(diag + i0);
+      const float* xb = Xp + (i0 >> 4) * ks * 64;
+      const int pp = (int)(i0 & 15);
+      f4 r2 = {0.f, 0.f, 0.f, 0.f};
+      for (int f = 0; f < d; ++f) {
+        const float xp = xpiv[f];
+        const int o = xp_offset(ks, f, pp), st4 = xp_offset(ks, f, pp + 1) - o;      // stride between the tile's points
+        const f4 df = {xp - xb[o], xp - xb[o + st4], xp - xb[o + 2 * st4], xp - xb[o + 3 * st4]};
+        r2 = fma4(df, df, r2);
+      }
+      f4 acc = {s * transform_rt(kind, r2.x), s * transform_rt(kind, r2.y), s * transform_rt(kind, r2.z),
+                s * transform_rt(kind, r2.w)};
+      const float* Li = L + i0;
+      f4 a0 = {0.f, 0.f, 0.f, 0.f}, a1 = a0, a2 = a0, a3 = a0;
+      int c = 0;
+      for (; c + 8 <= m; c += 8) {
+        f4 l[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) l[u] = *reinterpret_cast<const f4*>(Li + (int64_t)(c + u) * n);
+        a0 = fma4(l[0], lrow[c + 0], a0);      // (the same four interleaved sums, in the same order, as the scalar path)
+        a1 = fma4(l[1], lrow[c + 1], a1);
+        a2 = fma4(l[2], lrow[c + 2], a2);
+        a3 = fma4(l[3], lrow[c + 3], a3);
+        a0 = fma4(l[4], lrow[c + 4], a0);
+        a1 = fma4(l[5], lrow[c + 5], a1);
+        a2 = fma4(l[6], lrow[c + 6], a2);
+        a3 = fma4(l[7], lrow[c + 7], a3);
+      }
+      if (c + 4 <= m) {
+        a0 = fma4(*reinterpret_cast<const f4*>(Li + (int64_t)(c + 0) * n), lrow[c + 0], a0);
+        a1 = fma4(*reinterpret_cast<const f4*>(Li + (int64_t)(c + 1) * n), lrow[c + 1], a1);
+        a2 = fma4(*reinterpret_cast<const f4*>(Li + (int64_t)(c + 2) * n), lrow[c + 2], a2);
+        a3 = fma4(*reinterpret_cast<const f4*>(Li + (int64_t)(c + 3) * n), lrow[c + 3], a3);
+        c += 4;
+      }
+      for (; c < m; ++c) a0 = fma4(*reinterpret_cast<const f4*>(Li + (int64_t)c * n), lrow[c], a0);
+      acc -= (a0 + a1) + (a2 + a3);
+      const float dgv[4] = {dg.x, dg.y, dg.z, dg.w}, accv[4] = {acc.x, acc.y, acc.z, acc.w};
+      float colv[4], newv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (i0 + u == piv) {
+          colv[u] = root;
+          newv[u] = -INFINITY;
+        } else if (dgv[u] == -INFINITY) {      // chosen earlier
+          colv[u] = 0.f;
+          newv[u] = -INFINITY;
+        } else {
+          colv[u] = accv[u] * inv_root;
+          newv[u] = dgv[u] - colv[u] * colv[u];
+        }
+        best = better(best, (Cand){newv[u], (int)(i0 + u)});
+      }
+      *reinterpret_cast<f4*>(L + (int64_t)m * n + i0) = (f4){colv[0], colv[1], colv[2], colv[3]};
+      *reinterpret_cast<f4*>(diag + i0) = (f4){newv[0], newv[1], newv[2], newv[3]};
+    }
+  } else
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
     const float dg = diag[i];
     float col;
@@ -166,12 +239,11 @@ __global__ __launch_bounds__(256) void pc_step(const float* __restrict__ Xp, int
 // inputs are fp32 values; their products and sums are carried in fp64 (v_mfma_f64_16x16x4_f64, 78.6 TFLOP/s: the
 // kernel stays HBM-bound).
 // grid = (blocks, ceil(ra/64), ceil(rb/32)), 4 waves per block; a wave owns 4 x 2 output tiles of 16 x 16
-// and walks groups of 16 points: lane (q,p) loads points 16 g + 4 q .. + 3 of row p of each operand tile
-// (one 16-byte load) and feeds component s to MFMA step s. Both operands use the same point-to-step map, so
+// and walks groups of 32 points: lane (q,p) loads points 32 g + 8 q .. + 7 of row p of each operand tile
+// (two 16-byte loads) and feeds component s to MFMA step s. Both operands use the same point-to-step map, so
 // the pairing is consistent; the order of a sum is free. Every wave writes its own partial result
 // Cp[ra][rb][4 * block + wave] (the chunk index contiguous, so that reduce_chunks reads coalesced); reduce_chunks
 // sums them in a fixed order.
-typedef float f4 __attribute__((ext_vector_type(4)));
 typedef double d4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ f4 load4_guarded(const float* __restrict__ row, int64_t i, int64_t n, int vec) {
@@ -201,32 +273,64 @@ __global__ __launch_bounds__(256) void gram_mfma(const float* __restrict__ A, in
   for (int ta = 0; ta < kGramTa; ++ta)
 #pragma unroll
     for (int tb = 0; tb < 2; ++tb) acc[ta][tb] = (d4){0.0, 0.0, 0.0, 0.0};
-  const int64_t groups = (n + 15) / 16;
-  for (int64_t g = (int64_t)blockIdx.x * 4 + wave; g < groups; g += (int64_t)gridDim.x * 4) {
-    const int64_t i = g * 16 + q * 4;
-    f4 av[kGramTa], bv[2];
+  // A wave walks groups of 32 points: lane (q, p) loads points 32 g + 8 q .. + 7 of row p of each operand tile (two
+  // 16-byte loads: the four lanes of a row cover one 128-byte line) and feeds its eight values to eight MFMA steps.
+  const int64_t groups = (n + 31) / 32;
+  const int64_t gstep = (int64_t)gridDim.x * 4;
+  // The operands of a group are loaded one group ahead of the MFMAs that consume them: the kernel streams both
+  // matrices once and is bound by how many bytes it keeps in flight.
+  auto load = [&](int64_t g, f4 (&av)[kGramTa][2], f4 (&bv)[2][2]) {
+    const int64_t i = g * 32 + q * 8;
 #pragma unroll
     for (int ta = 0; ta < kGramTa; ++ta) {
       const int row = a_base + ta * 16 + p;
-      av[ta] = (ta < nta && row < ra) ? load4_guarded(A + (int64_t)row * lda, i, n, vecA) : (f4){0.f, 0.f, 0.f, 0.f};
+      const bool on = ta < nta && row < ra;
+      av[ta][0] = on ? load4_guarded(A + (int64_t)row * lda, i, n, vecA) : (f4){0.f, 0.f, 0.f, 0.f};
+      av[ta][1] = on ? load4_guarded(A + (int64_t)row * lda, i + 4, n, vecA) : (f4){0.f, 0.f, 0.f, 0.f};
     }
 #pragma unroll
     for (int tb = 0; tb < 2; ++tb) {
       const int row = b_base + tb * 16 + p;
-      bv[tb] = (tb < ntb && row < rb) ? load4_guarded(B + (int64_t)row * ldb, i, n, vecB) : (f4){0.f, 0.f, 0.f, 0.f};
+      const bool on = tb < ntb && row < rb;
+      bv[tb][0] = on ? load4_guarded(B + (int64_t)row * ldb, i, n, vecB) : (f4){0.f, 0.f, 0.f, 0.f};
+      bv[tb][1] = on ? load4_guarded(B + (int64_t)row * ldb, i + 4, n, vecB) : (f4){0.f, 0.f, 0.f, 0.f};
     }
+  };
+  f4 av[kGramTa][2], bv[2][2];
+  int64_t g = (int64_t)blockIdx.x * 4 + wave;
+  if (g < groups) load(g, av, bv);
+  for (; g < groups; g += gstep) {
+    f4 an[kGramTa][2], bn[2][2];
+    const bool more = g + gstep < groups;
+    if (more) load(g + gstep, an, bn);
 #pragma unroll
     for (int ta = 0; ta < kGramTa; ++ta) {
       if (ta < nta) {
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb) {
           if (tb < ntb) {
-            acc[ta][tb] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)av[ta].x, (double)bv[tb].x, acc[ta][tb], 0, 0, 0);
-            acc[ta][tb] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)av[ta].y, (double)bv[tb].y, acc[ta][tb], 0, 0, 0);
-            acc[ta][tb] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)av[ta].z, (double)bv[tb].z, acc[ta][tb], 0, 0, 0);
-            acc[ta][tb] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)av[ta].w, (double)bv[tb].w, acc[ta][tb], 0, 0, 0);
+#pragma unroll
+            for (int hlf = 0; hlf < 2; ++hlf) {
+              const f4 a4 = av[ta][hlf], b4 = bv[tb][hlf];
+              acc[ta][tb] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a4.x, (double)b4.x, acc[ta][tb], 0, 0, 0);
+              acc[ta][tb] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a4.y, (double)b4.y, acc[ta][tb], 0, 0, 0);
+              acc[ta][tb] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a4.z, (double)b4.z, acc[ta][tb], 0, 0, 0);
+              acc[ta][tb] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a4.w, (double)b4.w, acc[ta][tb], 0, 0, 0);
+            }
           }
         }
+      }
+    }
+    if (more) {
+#pragma unroll
+      for (int ta = 0; ta < kGramTa; ++ta) {
+        av[ta][0] = an[ta][0];
+        av[ta][1] = an[ta][1];
+      }
+#pragma unroll
+      for (int tb = 0; tb < 2; ++tb) {
+        bv[tb][0] = bn[tb][0];
+        bv[tb][1] = bn[tb][1];
       }
     }
   }
@@ -299,13 +403,17 @@ __global__ __launch_bounds__(256) void woodbury_finish_cm(const float* __restric
     for (int c = 0; c < TT; ++c) acc[c] = 0.0;
     const float* Li = L + i;
     int m = 0;
-    for (; m + 2 <= k; m += 2) {
-      const double l0 = (double)Li[(int64_t)(m + 0) * ldl], l1 = (double)Li[(int64_t)(m + 1) * ldl];
+    // eight columns of L in flight per thread (the sums stay in the order m = 0, 1, 2, ...)
+    for (; m + 8 <= k; m += 8) {
+      float l[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) l[u] = Li[(int64_t)(m + u) * ldl];
       const double* y = Y + m * TT;
 #pragma unroll
-      for (int c = 0; c < TT; ++c) {
-        acc[c] = fma(l0, y[c], acc[c]);
-        acc[c] = fma(l1, y[TT + c], acc[c]);
+      for (int u = 0; u < 8; ++u) {
+        const double lu = (double)l[u];
+#pragma unroll
+        for (int c = 0; c < TT; ++c) acc[c] = fma(lu, y[u * TT + c], acc[c]);
       }
     }
     for (; m < k; ++m) {
@@ -359,7 +467,7 @@ __global__ __launch_bounds__(256) void to_rowmajor(const float* __restrict__ src
 
 // number of partial results the Gram kernel leaves: 4 waves per block, blocks sized to the point count
 int gram_blocks(int64_t n) {
-  int64_t b = (n / 16 + 4 * 16 - 1) / (4 * 16);     // at least 16 point groups per wave
+  int64_t b = (n / 32 + 4 * 8 - 1) / (4 * 8);     // at least 8 point groups (of 32) per wave
   if (b < 1) b = 1;
   if (b > 1024) b = 1024;
   return (int)b;
@@ -531,51 +639,101 @@ size_t pivchol_ws_bytes(int64_t n, int d, int rank) {
 }
 
 // Factor noise*I + G (fp64, host), write the lower factor + log|P| to `small`, its inverse to `inv`.
-static int small_factor(const std::vector<double>& G, int k, int cap, double noise, int64_t n, double* small,
-                        std::vector<double>* inv) {
-  std::vector<double> A((size_t)k * k), Lc((size_t)k * k, 0.0);
-  for (int a = 0; a < k; ++a)
-    for (int b = 0; b < k; ++b) A[a * k + b] = 0.5 * (G[a * k + b] + G[b * k + a]) + (a == b ? noise : 0.0);
-  double logdet = 0.0;
-  for (int j = 0; j < k; ++j) {
-    double s = A[j * k + j];
-    for (int c = 0; c < j; ++c) s -= Lc[j * k + c] * Lc[j * k + c];
-    if (!(s > 0.0)) return fail(EGP_ERR_BREAKDOWN, "noise*I + L^T L is not positive definite at column %d", j);
-    const double dj = sqrt(s);
-    Lc[j * k + j] = dj;
-    logdet += 2.0 * log(dj);
-    for (int i = j + 1; i < k; ++i) {
-      double v = A[i * k + j];
-      for (int c = 0; c < j; ++c) v -= Lc[i * k + c] * Lc[j * k + c];
-      Lc[i * k + j] = v / dj;
+// O(k^3) work on a k x k matrix: at the ranks the paper uses (100) it is a fraction of a millisecond; at rank 512 to
+// 1024 it would be 0.04 to 0.3 s on one core, so from k = 128 on the rows of each Cholesky column and the columns of the
+// inverse are dealt to a few host threads (the arithmetic of every entry is the same as in the serial order).
+namespace {
+struct SpinBarrier {
+  explicit SpinBarrier(int n) : n_(n) {}
+  void wait() {
+    const int gen = gen_.load(std::memory_order_acquire);
+    if (count_.fetch_add(1, std::memory_order_acq_rel) + 1 == n_) {
+      count_.store(0, std::memory_order_relaxed);
+      gen_.store(gen + 1, std::memory_order_release);
+    } else {
+      while (gen_.load(std::memory_order_acquire) == gen) std::this_thread::yield();
     }
   }
+  const int n_;
+  std::atomic<int> count_{0}, gen_{0};
+};
+}  // namespace
+
+static int small_factor(const std::vector<double>& G, int k, int cap, double noise, int64_t n, double* small,
+                        std::vector<double>* inv) {
+  std::vector<double> A((size_t)k * k), Lc((size_t)k * k, 0.0), Lt((size_t)k * k);
+  for (int a = 0; a < k; ++a)
+    for (int b = 0; b < k; ++b) A[a * k + b] = 0.5 * (G[a * k + b] + G[b * k + a]) + (a == b ? noise : 0.0);
+  inv->assign((size_t)k * k, 0.0);
+  int threads = 1;
+  if (k >= 128) {
+    const unsigned hw = std::thread::hardware_concurrency();
+    threads = (int)(hw == 0 ? 4 : (hw > 16 ? 16 : hw));
+    if (threads > k / 32) threads = k / 32;
+    if (threads < 1) threads = 1;
+  }
+  std::atomic<int> bad_col{-1};
+  SpinBarrier bar(threads);
+  auto worker = [&](int tid) {
+    // ---- Cholesky, column by column: the diagonal entry by thread 0, the rows below dealt round-robin ----
+    for (int j = 0; j < k; ++j) {
+      if (tid == 0) {
+        double s = A[(size_t)j * k + j];
+        for (int c = 0; c < j; ++c) s -= Lc[(size_t)j * k + c] * Lc[(size_t)j * k + c];
+        if (!(s > 0.0)) bad_col.store(j);
+        Lc[(size_t)j * k + j] = s > 0.0 ? sqrt(s) : 1.0;
+      }
+      if (threads > 1) bar.wait();
+      if (bad_col.load() >= 0) return;
+      const double dj = Lc[(size_t)j * k + j];
+      const double* lj = &Lc[(size_t)j * k];
+      for (int i = j + 1 + tid; i < k; i += threads) {
+        double v = A[(size_t)i * k + j];
+        const double* li = &Lc[(size_t)i * k];
+        for (int c = 0; c < j; ++c) v -= li[c] * lj[c];
+        Lc[(size_t)i * k + j] = v / dj;
+      }
+      if (threads > 1) bar.wait();
+    }
+    // ---- inverse: solve (Lc Lc^T) x = e_col, columns dealt round-robin ----
+    for (int a = tid; a < k; a += threads)
+      for (int b = 0; b < k; ++b) Lt[(size_t)b * k + a] = Lc[(size_t)a * k + b];      // contiguous rows for the back substitution
+    if (threads > 1) bar.wait();
+    std::vector<double> y(k), x(k);
+    for (int col = tid; col < k; col += threads) {
+      for (int i = 0; i < col; ++i) y[i] = 0.0;                                       // e_col starts with zeros
+      for (int i = col; i < k; ++i) {
+        double v = (i == col) ? 1.0 : 0.0;
+        const double* li = &Lc[(size_t)i * k];
+        for (int c = col; c < i; ++c) v -= li[c] * y[c];
+        y[i] = v / li[i];
+      }
+      for (int i = k - 1; i >= 0; --i) {
+        double v = y[i];
+        const double* lt = &Lt[(size_t)i * k];
+        for (int c = i + 1; c < k; ++c) v -= lt[c] * x[c];
+        x[i] = v / lt[i];
+      }
+      for (int i = 0; i < k; ++i) (*inv)[(size_t)i * k + col] = x[i];
+    }
+  };
+  if (threads > 1) {
+    std::vector<std::thread> pool;
+    for (int t = 1; t < threads; ++t) pool.emplace_back(worker, t);
+    worker(0);
+    for (std::thread& th : pool) th.join();
+  } else {
+    worker(0);
+  }
+  if (bad_col.load() >= 0)
+    return fail(EGP_ERR_BREAKDOWN, "noise*I + L^T L is not positive definite at column %d", bad_col.load());
+  double logdet = 0.0;
+  for (int j = 0; j < k; ++j) logdet += 2.0 * log(Lc[(size_t)j * k + j]);
   logdet += (double)(n - k) * log(noise);
   for (int i = 0; i < cap * cap + 1; ++i) small[i] = 0.0;
   for (int a = 0; a < k; ++a)
     for (int b = 0; b < k; ++b) small[a * k + b] = Lc[a * k + b];
   small[(size_t)cap * cap] = logdet;
-  // inverse: solve (Lc Lc^T) Xcol = e_col
-  inv->assign((size_t)k * k, 0.0);
-  std::vector<double> y(k), x(k), Lt((size_t)k * k);
-  for (int a = 0; a < k; ++a)
-    for (int b = 0; b < k; ++b) Lt[(size_t)b * k + a] = Lc[(size_t)a * k + b];      // contiguous rows for the back substitution
-  for (int col = 0; col < k; ++col) {
-    for (int i = 0; i < col; ++i) y[i] = 0.0;                                       // e_col starts with zeros
-    for (int i = col; i < k; ++i) {
-      double v = (i == col) ? 1.0 : 0.0;
-      const double* li = &Lc[(size_t)i * k];
-      for (int c = col; c < i; ++c) v -= li[c] * y[c];
-      y[i] = v / li[i];
-    }
-    for (int i = k - 1; i >= 0; --i) {
-      double v = y[i];
-      const double* lt = &Lt[(size_t)i * k];
-      for (int c = i + 1; c < k; ++c) v -= lt[c] * x[c];
-      x[i] = v / lt[i];
-    }
-    for (int i = 0; i < k; ++i) (*inv)[(size_t)i * k + col] = x[i];
-  }
   return EGP_OK;
 }
 
@@ -607,9 +765,17 @@ int pivchol_core(const float* X, int64_t n, const egp_hyper_t* h, float tol_abs,
   {
     ProfScope prof(kProfPivChol, stream);
     hipLaunchKernelGGL(pc_init, dim3((unsigned)nb), dim3(256), 0, stream, diag, n, h->outputscale, st, cap);
-    for (int m = 0; m < cap; ++m)
-      hipLaunchKernelGGL(pc_step, dim3(blocks), dim3(256), 0, stream, prep.Xp, prep.ks, prep.d, h->kernel_type,
-                         h->outputscale, n, P->L, diag, m, tol_abs, st);
+    // 16-byte accesses to L and the residual diagonal where the layout allows them (four points per thread)
+    const bool vec = (n & 3) == 0 && (reinterpret_cast<uintptr_t>(P->L) & 15) == 0 && n >= 4096;
+    const int vblocks = (int)((n / 4 + 255) / 256 > kPcBlocks ? kPcBlocks : (n / 4 + 255) / 256);
+    for (int m = 0; m < cap; ++m) {
+      if (vec)
+        hipLaunchKernelGGL(pc_step<true>, dim3(vblocks), dim3(256), 0, stream, prep.Xp, prep.ks, prep.d,
+                           h->kernel_type, h->outputscale, n, P->L, diag, m, tol_abs, st);
+      else
+        hipLaunchKernelGGL(pc_step<false>, dim3(blocks), dim3(256), 0, stream, prep.Xp, prep.ks, prep.d,
+                           h->kernel_type, h->outputscale, n, P->L, diag, m, tol_abs, st);
+    }
   }
   EGP_HIP(hipGetLastError());
   int rank = 0;

@@ -203,7 +203,7 @@ def test_call_options_fix_the_mode_per_call(lib):
     options alone, whatever the process-wide default is at that moment (and NULL / -1 take the default)."""
     from paper_1903_08114_amd.binding import _CallOpts
     shapes = [(40000, 40000, 11, 17), (1 << 20, 1 << 20, 11, 16), (5000, 5000, 25, 16), (2047, 2047, 159, 18),
-              (70000, 70000, 90, 17), (1 << 18, 1 << 18, 11, 33)]
+              (70000, 70000, 90, 17), (1 << 18, 1 << 18, 11, 33), (33000, 33000, 31, 17), (40000, 40000, 20, 17)]
 
     def plan(opts, shape):
         used, sized = C.c_int32(-1), C.c_int32(-1)
@@ -217,7 +217,8 @@ def test_call_options_fix_the_mode_per_call(lib):
             by_default[mode] = [_plan_splits(lib, *s) for s in shapes]
             assert [plan(None, s) for s in shapes] == by_default[mode]
             assert [plan(C.byref(_CallOpts(-1, -1)), s) for s in shapes] == by_default[mode]
-        assert by_default[0] != by_default[3]      # the symmetric and the one-sided plans differ on these shapes
+        # the symmetric, the one-sided and the all-bf16 plans differ on these shapes
+        assert by_default[0] != by_default[3] and by_default[0] != by_default[2] and by_default[2] != by_default[3]
         for default in range(4):
             assert lib.egp_set_kmm_mode(default) == 0
             for mode in range(4):
