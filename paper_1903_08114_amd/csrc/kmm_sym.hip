@@ -116,6 +116,11 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void kmm_kernel_sym(
   float b[R][KS];
   f4 cq[R], o[R][NBA], vrow[R][NBA];
   float eacc[R], erow[kErLds ? 1 : R];
+  // Second accumulation level: in device memory for the shapes that only fit eight row tiles without it (17 columns;
+  // 16 columns beyond 4 distance k-steps), in registers for the others (no extra traffic).
+  constexpr bool kFoldMem = NB == 1 && R == 8 && (EXTRA || KS > 4);
+  f4 o2[kFoldMem ? 1 : R][NBA];
+  float eacc2[kFoldMem ? 1 : R];
   constexpr int kFlushStages = 4096 / (16 * JT);
   const int ds = d >> 2, dq = d & 3;
 #pragma unroll
@@ -132,22 +137,24 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void kmm_kernel_sym(
 #pragma unroll
     for (int nb = 0; nb < NBA; ++nb) {
       o[it][nb] = (f4){0.f, 0.f, 0.f, 0.f};
+      if constexpr (!kFoldMem) o2[it][nb] = (f4){0.f, 0.f, 0.f, 0.f};
       vrow[it][nb] = NB ? Vp[((row_tile0 + it) * NBA + nb) * 64 + lane] : (f4){0.f, 0.f, 0.f, 0.f};
     }
     eacc[it] = 0.f;
+    if constexpr (!kFoldMem) eacc2[it] = 0.f;
     if constexpr (kErLds) {
       if (q == 0) Er[wave][it][p] = Ep[(row_tile0 + it) * 16 + p];      // (read by this wave only, after the barrier below)
     } else {
       erow[it] = EXTRA ? Ep[(row_tile0 + it) * 16 + p] : 0.f;
     }
   }
-  // Second accumulation level in device memory: this wave's rows of the row-side slab of its split. Lane (q, p),
-  // register r of o[it][nb] is out[row 4q + r of tile it][column 16 nb + p]; the slab's content on entry is not
-  // read (the first fold stores). The same lanes touch the same addresses at every fold, so program order is all
-  // the ordering this needs.
+  // Adding the register sums to this wave's rows of the row-side slab of its split. Lane (q, p), register r of
+  // o[it][nb] is out[row 4q + r of tile it][column 16 nb + p]; the slab's content on entry is not read (the first
+  // call stores). The same lanes touch the same addresses at every call, so program order is all the ordering this
+  // needs. With kFoldMem this is the second accumulation level itself; otherwise it runs once, at the end.
   float* const rdst = Part + (int64_t)blockIdx.y * npad * TS;
   bool first_fold = true;
-  auto fold = [&]() {
+  auto fold_to_slab = [&]() {
 #pragma unroll
     for (int it = 0; it < R; ++it) {
       const int64_t row0 = (row_tile0 + it) * 16;
@@ -185,6 +192,22 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void kmm_kernel_sym(
     }
     first_fold = false;
   };
+  auto fold_to_regs = [&]() {
+    if constexpr (!kFoldMem) {
+#pragma unroll
+      for (int it = 0; it < R; ++it) {
+#pragma unroll
+        for (int nb = 0; nb < NBA; ++nb) {
+          o2[it][nb] += o[it][nb];
+          o[it][nb] = (f4){0.f, 0.f, 0.f, 0.f};
+        }
+        if (EXTRA) {
+          eacc2[it] += eacc[it];
+          eacc[it] = 0.f;
+        }
+      }
+    }
+  };
   // transposition patch: lane (q,p) holds M[4q + r][p] in register r and wants M[p][4q + r]
   float* patch = &Ts[NB ? wave : 0][0][0];
   // 16-byte slot of writer (q, p = 4a + b): 18 q + (a & 1) + 8 (a >> 1) + 2 b. Free of bank conflicts for 32 banks
@@ -193,7 +216,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void kmm_kernel_sym(
   // q 16 + p made the column-major flush below (a thread reads row 4q + r of column c across the waves) hit each bank
   // four times; with the swizzle both that read and the 16-byte writes are conflict-free for 32 and for 64 banks
   // (enumerated on the CPU).
-  const int cjslot = q * 16 + (p ^ ((q & 1) * 10 ^ (q >> 1) * 4));
+  const int cjslot = cm ? q * 16 + (p ^ ((q & 1) * 10 ^ (q >> 1) * 4)) : lane;      // (the row-major flush reads its own slot)
   const int woff = 4 * (18 * q + ((p >> 2) & 1) + 8 * (p >> 3) + 2 * (p & 3));
   const int roff = 72 * (p >> 2) + 4 * (q & 1) + 32 * (q >> 1) + (p & 3);      // + 8 r: the value for step r
 
@@ -499,7 +522,10 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void kmm_kernel_sym(
         }
       }
     }
-    if ((k - k_begin) % kFlushStages == kFlushStages - 1) fold();
+    if ((k - k_begin) % kFlushStages == kFlushStages - 1) {
+      if constexpr (kFoldMem) fold_to_slab();
+      else fold_to_regs();
+    }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (dual) {      // uniform over the workgroup
@@ -507,7 +533,16 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void kmm_kernel_sym(
       __syncthreads();             // the per-wave sums are free again
     }
   }
-  fold();      // the last partial block (stores zeros for a split without stages)
+  if constexpr (!kFoldMem) {      // the last partial block joins the second level, which then is what gets written
+    fold_to_regs();
+#pragma unroll
+    for (int it = 0; it < R; ++it) {
+#pragma unroll
+      for (int nb = 0; nb < NBA; ++nb) o[it][nb] = o2[it][nb];
+      eacc[it] = eacc2[it];
+    }
+  }
+  fold_to_slab();      // (zeros for a split without stages; with registers as second level the only write)
 }
 
 template <int KS, int R, int KIND, int NB, int EXTRA, int NW>
