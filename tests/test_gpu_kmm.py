@@ -310,3 +310,42 @@ def test_kmm_under_hip_graph_capture(egp, n, d, t):
         graph.replay()
         torch.cuda.synchronize()
         assert bool((out == want).all())
+
+
+def test_per_call_mode_equals_the_process_default_and_leaves_it_alone(egp):
+    """The arithmetic mode as a per-call option (egp_kmm_ex / egp_mbcg_ex) gives the bits that the same mode gives as
+    process-wide default, whatever the default is while the call runs, and never changes the default."""
+    import torch
+    rng = np.random.default_rng(5)
+    n, d, t = 33000, 5, 17      # large enough for the symmetric kernels in the default mode
+    X = rng.uniform(-1, 1, (n, d)).astype(np.float32)
+    V = rng.standard_normal((n, t)).astype(np.float32)
+    ls = np.full(d, 0.7, np.float32)
+    Xd, Vd = torch.from_numpy(X).cuda(), torch.from_numpy(V).cuda()
+    L = egp.lib()
+    by_default = {}
+    try:
+        for mode in range(4):
+            egp.set_kmm_mode(mode)
+            by_default[mode] = egp.kmm(Xd, Vd, ls, 1.0, 0.1, orc.RBF).clone()
+        for default in (0, 2):
+            egp.set_kmm_mode(default)
+            for mode in range(4):
+                out = egp.kmm(Xd, Vd, ls, 1.0, 0.1, orc.RBF, mode=mode)
+                assert torch.equal(out, by_default[mode]), (default, mode)
+                assert L.egp_get_kmm_mode() == default
+    finally:
+        egp.set_kmm_mode(0)
+    assert not torch.equal(by_default[0], by_default[3])      # symmetric and one-sided sums differ in the last bits
+    rows = np.random.default_rng(6).choice(n, 64, replace=False)
+    ref = orc.kmm_rows(X, V, orc.Hyper(orc.RBF, ls, 1.0, 0.1), rows)
+    for mode in range(4):
+        assert _rel(by_default[mode].cpu().numpy().astype(np.float64)[rows], ref) <= KMM_TOL
+    # the solver takes both options per call
+    a = egp.mbcg(Xd, Vd, ls, 1.0, 0.1, orc.RBF, max_iter=5, tol=0.0, mode=3, shrink=False)
+    egp.set_kmm_mode(3)
+    try:
+        b = egp.mbcg(Xd, Vd, ls, 1.0, 0.1, orc.RBF, max_iter=5, tol=0.0)
+    finally:
+        egp.set_kmm_mode(0)
+    assert torch.equal(a["U"], b["U"]) and L.egp_get_mbcg_shrink() == 0
