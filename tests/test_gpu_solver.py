@@ -374,3 +374,17 @@ def test_mbcg_shrink_drops_converged_trailing_columns(egp, n, t):
         KU = orc.kmm_rows(X, U.astype(np.float32), h, rows)
         true_res = np.linalg.norm(KU - B[rows], axis=0) / np.linalg.norm(B[rows], axis=0)
     assert true_res.max() <= (1.3 if n <= 4000 else 2.0) * tol
+
+
+def test_mbcg_without_iterations_reports_the_start_residual(egp):
+    """max_iter = 0: no iteration runs, U = 0, and the relative residual of the start vector is 1 for every column with
+    b != 0 (0 for a zero column)."""
+    rng = np.random.default_rng(40)
+    n, d = 700, 3
+    X = rng.uniform(0, 1, (n, d)).astype(np.float32)
+    B = rng.standard_normal((n, 4)).astype(np.float32)
+    B[:, 2] = 0.0
+    res = egp.mbcg(_cuda(X), _cuda(B), np.full(d, 0.5, np.float32), 1.0, 0.1, orc.RBF, max_iter=0, tol=0.5)
+    assert res["iters"] == 0
+    assert res["rel_resid"].tolist() == [1.0, 1.0, 0.0, 1.0]
+    assert float(res["U"].abs().max()) == 0.0
