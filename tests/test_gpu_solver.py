@@ -24,9 +24,10 @@ def _cuda(a):
 
 
 @pytest.mark.parametrize("kind", [orc.RBF, orc.MATERN32, orc.MATERN52, orc.MATERN12])
-@pytest.mark.parametrize("n,d,rank", [(64, 2, 8), (300, 3, 20), (1000, 2, 12)])
+@pytest.mark.parametrize("n,d,rank", [(64, 2, 8), (300, 3, 20), (1000, 2, 12), (4100, 2, 12), (4101, 2, 12)])
 def test_pivots_bit_exact_and_factor(egp, kind, n, d, rank):
-    """Pivot order must equal the oracle's exactly on well-separated tiny inputs (no near-ties)."""
+    """Pivot order must equal the oracle's exactly on well-separated tiny inputs (no near-ties). n = 4100 takes the
+    step kernel's four-points-per-thread path (n a multiple of 4, at least 4096), n = 4101 the scalar one."""
     X = well_separated_points(100 + n + kind, n, d)
     ls = np.full(d, 0.3, np.float32)
     s, noise = 1.5, 0.05
