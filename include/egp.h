@@ -125,7 +125,9 @@ size_t egp_kmm_grad_bilinear_ws_bytes(int64_t n, int32_t d, int32_t t);
  * Method, "Preconditioning": a rank-k preconditioner needs only k kernel rows and is built once
  * before CG). Greedy diagonal pivoting, ties to the lowest index; stops early when the largest
  * remaining residual diagonal is <= tol_abs. Fills P (see egp_precond_t; P->rank must hold the
- * capacity = requested rank on entry, 1..min(n, EGP_RANK_MAX)). Synchronises on `stream`. */
+ * capacity = requested rank on entry, 1..min(n, EGP_RANK_MAX)). Synchronises on `stream`. The k x k factor and
+ * inverse are fp64 work on the host; from rank 128 on it is spread over up to 16 host threads for the duration of
+ * the call. */
 int egp_piv_chol_precond(const float* X, int64_t n, const egp_hyper_t* h, float tol_abs,
                          egp_precond_t* P, void* ws, size_t ws_bytes, void* stream);
 size_t egp_piv_chol_precond_ws_bytes(int64_t n, int32_t d, int32_t rank);
