@@ -33,8 +33,9 @@ def _inputs(seed, n, d, t):
 def test_noalloc_matches_workspace_entry_point_on_two_calls_in_a_row(egp):
     import torch
     # first call: n_pad >= 32768, so the default mode runs the symmetric kernel, whose int64 column-side slab lives in
-    # the scratch array and must start at zero; second call: a smaller problem (one-sided kernel, other layout)
-    cases = [(7, 40000, 11, 17, orc.RBF), (8, 5000, 7, 16, orc.MATERN32)]
+    # the scratch array and must start at zero; second call: a smaller problem (one-sided kernel, other layout);
+    # third call: d > 31 (the wide symmetric kernel: row operands in LDS, another workspace layout again)
+    cases = [(7, 40000, 11, 17, orc.RBF), (8, 5000, 7, 16, orc.MATERN32), (9, 33000, 40, 16, orc.MATERN52)]
     dev = []
     for seed, n, d, t, kind in cases:
         X, V, ls = _inputs(seed, n, d, t)
