@@ -276,7 +276,9 @@ __global__ __launch_bounds__(256) void gram_mfma(const float* __restrict__ A, in
   // A wave walks groups of 32 points: lane (q, p) loads points 32 g + 8 q .. + 7 of row p of each operand tile (two
   // 16-byte loads: the four lanes of a row cover one 128-byte line) and feeds its eight values to eight MFMA steps.
   const int64_t groups = (n + 31) / 32;
-  const int64_t gstep = (int64_t)gridDim.x * 4;
+  // A wave takes a contiguous run of groups (consecutive 128-byte lines of every row it reads) rather than every
+  // (4 gridDim.x)-th group.
+  const int64_t gper = (groups + (int64_t)gridDim.x * 4 - 1) / ((int64_t)gridDim.x * 4);
   // The operands of a group are loaded one group ahead of the MFMAs that consume them: the kernel streams both
   // matrices once and is bound by how many bytes it keeps in flight.
   auto load = [&](int64_t g, f4 (&av)[kGramTa][2], f4 (&bv)[2][2]) {
@@ -297,12 +299,14 @@ __global__ __launch_bounds__(256) void gram_mfma(const float* __restrict__ A, in
     }
   };
   f4 av[kGramTa][2], bv[2][2];
-  int64_t g = (int64_t)blockIdx.x * 4 + wave;
-  if (g < groups) load(g, av, bv);
-  for (; g < groups; g += gstep) {
+  int64_t g = ((int64_t)blockIdx.x * 4 + wave) * gper;
+  int64_t g_end = g + gper;
+  if (g_end > groups) g_end = groups;
+  if (g < g_end) load(g, av, bv);
+  for (; g < g_end; ++g) {
     f4 an[kGramTa][2], bn[2][2];
-    const bool more = g + gstep < groups;
-    if (more) load(g + gstep, an, bn);
+    const bool more = g + 1 < g_end;
+    if (more) load(g + 1, an, bn);
 #pragma unroll
     for (int ta = 0; ta < kGramTa; ++ta) {
       if (ta < nta) {
