@@ -258,64 +258,124 @@ __device__ __forceinline__ f4 load4_guarded(const float* __restrict__ row, int64
 
 constexpr int kGramTa = 4;      // 16-row tiles of A per wave
 
-__global__ __launch_bounds__(256) void gram_mfma(const float* __restrict__ A, int ra, int64_t lda,
+// FAST: both operands allow 16-byte loads (leading dimensions multiples of 4, 16-byte aligned bases). Then every group
+// of 32 points that lies wholly below n is loaded without bounds checks, and rows of the last, partial tile that lie
+// beyond the matrix read a clamped (valid) row instead of being zeroed: their products only reach output rows /
+// columns that are never written. Only the one group that straddles n takes the guarded loads.
+// NTB: 16-row tiles of B per wave. One for up to 17 rows of B (the preconditioner's L^T R: half the accumulators, four
+// waves per SIMD), two otherwise (the Gram matrix of the factor, where A is re-read once per block of B rows).
+template <bool FAST, int NTB>
+__global__ __launch_bounds__(256, NTB == 1 ? 3 : 2) void gram_mfma(const float* __restrict__ A, int ra, int64_t lda,
                                                  const float* __restrict__ B, int rb, int64_t ldb, int64_t n,
                                                  double* __restrict__ Cp, int vecA, int vecB) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int q = lane >> 4, p = lane & 15;
-  const int a_base = blockIdx.y * (16 * kGramTa), b_base = blockIdx.z * 32;
+  const int a_base = blockIdx.y * (16 * kGramTa), b_base = blockIdx.z * (16 * NTB);
   int nta = (ra - a_base + 15) / 16;
   if (nta > kGramTa) nta = kGramTa;
-  int ntb = (rb - b_base + 15) / 16;
-  if (ntb > 2) ntb = 2;
-  d4 acc[kGramTa][2];
+  // A lone last row of B (17 or 33 right-hand sides, or a single one) gets no matrix tile of its own, of which
+  // fifteen sixteenths would be padding (an fp64 MFMA step takes 64 cycles; with t = 17 half of the matrix work of the
+  // preconditioner's L^T R was that padding): the last block of B rows takes it along, its sums as fp64 FMAs on the
+  // vector unit (the grid's z extent is computed accordingly, see launch_gram).
+  const bool lone = FAST && rb % 16 == 1 && blockIdx.z == gridDim.z - 1;
+  const int xrow = lone ? rb - 1 : -1;
+  int ntb = ((lone ? rb - 1 : rb) - b_base + 15) / 16;
+  if (ntb > NTB) ntb = NTB;
+  d4 acc[kGramTa][NTB];
+  double accx[kGramTa];
 #pragma unroll
-  for (int ta = 0; ta < kGramTa; ++ta)
+  for (int ta = 0; ta < kGramTa; ++ta) {
+    accx[ta] = 0.0;
 #pragma unroll
-    for (int tb = 0; tb < 2; ++tb) acc[ta][tb] = (d4){0.0, 0.0, 0.0, 0.0};
-  // A wave walks groups of 32 points: lane (q, p) loads points 32 g + 8 q .. + 7 of row p of each operand tile (two
-  // 16-byte loads: the four lanes of a row cover one 128-byte line) and feeds its eight values to eight MFMA steps.
+    for (int tb = 0; tb < NTB; ++tb) acc[ta][tb] = (d4){0.0, 0.0, 0.0, 0.0};
+  }
+  // A wave walks a contiguous run of groups of 32 points: lane (q, p) loads points 32 g + 8 q .. + 7 of row p of each
+  // operand tile (two 16-byte loads: the four lanes of a row cover one 128-byte line) and feeds its eight values to
+  // eight MFMA steps. Both operands use the same point-to-step map, so the pairing is consistent.
   const int64_t groups = (n + 31) / 32;
-  // A wave takes a contiguous run of groups (consecutive 128-byte lines of every row it reads) rather than every
-  // (4 gridDim.x)-th group.
   const int64_t gper = (groups + (int64_t)gridDim.x * 4 - 1) / ((int64_t)gridDim.x * 4);
-  // The operands of a group are loaded one group ahead of the MFMAs that consume them: the kernel streams both
-  // matrices once and is bound by how many bytes it keeps in flight.
-  auto load = [&](int64_t g, f4 (&av)[kGramTa][2], f4 (&bv)[2][2]) {
-    const int64_t i = g * 32 + q * 8;
-#pragma unroll
-    for (int ta = 0; ta < kGramTa; ++ta) {
-      const int row = a_base + ta * 16 + p;
-      const bool on = ta < nta && row < ra;
-      av[ta][0] = on ? load4_guarded(A + (int64_t)row * lda, i, n, vecA) : (f4){0.f, 0.f, 0.f, 0.f};
-      av[ta][1] = on ? load4_guarded(A + (int64_t)row * lda, i + 4, n, vecA) : (f4){0.f, 0.f, 0.f, 0.f};
-    }
-#pragma unroll
-    for (int tb = 0; tb < 2; ++tb) {
-      const int row = b_base + tb * 16 + p;
-      const bool on = tb < ntb && row < rb;
-      bv[tb][0] = on ? load4_guarded(B + (int64_t)row * ldb, i, n, vecB) : (f4){0.f, 0.f, 0.f, 0.f};
-      bv[tb][1] = on ? load4_guarded(B + (int64_t)row * ldb, i + 4, n, vecB) : (f4){0.f, 0.f, 0.f, 0.f};
-    }
-  };
-  f4 av[kGramTa][2], bv[2][2];
   int64_t g = ((int64_t)blockIdx.x * 4 + wave) * gper;
   int64_t g_end = g + gper;
   if (g_end > groups) g_end = groups;
-  if (g < g_end) load(g, av, bv);
-  for (; g < g_end; ++g) {
-    f4 an[kGramTa][2], bn[2][2];
-    const bool more = g + 1 < g_end;
-    if (more) load(g + 1, an, bn);
+
+  struct Ops { f4 a[kGramTa][2], b[NTB][2], x[2]; };
+  // row pointers of this lane (clamped into the matrix in the fast path)
+  const float* arow[kGramTa];
+  const float* brow[NTB];
+#pragma unroll
+  for (int ta = 0; ta < kGramTa; ++ta) {
+    int row = a_base + ta * 16 + p;
+    if (FAST && row >= ra) row = ra - 1;
+    arow[ta] = A + (int64_t)row * lda;
+  }
+#pragma unroll
+  for (int tb = 0; tb < NTB; ++tb) {
+    int row = b_base + tb * 16 + p;
+    if (FAST && row >= rb) row = rb - 1;
+    brow[tb] = B + (int64_t)row * ldb;
+  }
+  const float* xptr = B + (int64_t)(xrow >= 0 ? xrow : 0) * ldb;
+  auto load_fast = [&](int64_t gg, Ops& o) {      // the whole group lies below n
+    const int64_t i = gg * 32 + q * 8;
+#pragma unroll
+    for (int ta = 0; ta < kGramTa; ++ta)
+      if (ta < nta) {
+        o.a[ta][0] = *reinterpret_cast<const f4*>(arow[ta] + i);
+        o.a[ta][1] = *reinterpret_cast<const f4*>(arow[ta] + i + 4);
+      }
+#pragma unroll
+    for (int tb = 0; tb < NTB; ++tb)
+      if (tb < ntb) {
+        o.b[tb][0] = *reinterpret_cast<const f4*>(brow[tb] + i);
+        o.b[tb][1] = *reinterpret_cast<const f4*>(brow[tb] + i + 4);
+      }
+    if (xrow >= 0) {      // the same eight points as this lane's A values (every lane p of a group reads them)
+      o.x[0] = *reinterpret_cast<const f4*>(xptr + i);
+      o.x[1] = *reinterpret_cast<const f4*>(xptr + i + 4);
+    }
+  };
+  auto load_guarded = [&](int64_t gg, Ops& o) {
+    const int64_t i = gg * 32 + q * 8;
+#pragma unroll
+    for (int ta = 0; ta < kGramTa; ++ta) {
+      const bool on = ta < nta && (FAST || a_base + ta * 16 + p < ra);
+      o.a[ta][0] = on ? load4_guarded(arow[ta], i, n, vecA) : (f4){0.f, 0.f, 0.f, 0.f};
+      o.a[ta][1] = on ? load4_guarded(arow[ta], i + 4, n, vecA) : (f4){0.f, 0.f, 0.f, 0.f};
+    }
+#pragma unroll
+    for (int tb = 0; tb < NTB; ++tb) {
+      const bool on = tb < ntb && (FAST || b_base + tb * 16 + p < rb);
+      o.b[tb][0] = on ? load4_guarded(brow[tb], i, n, vecB) : (f4){0.f, 0.f, 0.f, 0.f};
+      o.b[tb][1] = on ? load4_guarded(brow[tb], i + 4, n, vecB) : (f4){0.f, 0.f, 0.f, 0.f};
+    }
+    if (xrow >= 0) {
+      o.x[0] = load4_guarded(xptr, i, n, vecB);
+      o.x[1] = load4_guarded(xptr, i + 4, n, vecB);
+    }
+  };
+  auto compute = [&](const Ops& o) {
+    if (xrow >= 0) {
+#pragma unroll
+      for (int ta = 0; ta < kGramTa; ++ta)
+        if (ta < nta) {
+#pragma unroll
+          for (int hlf = 0; hlf < 2; ++hlf) {
+            accx[ta] = fma((double)o.a[ta][hlf].x, (double)o.x[hlf].x, accx[ta]);
+            accx[ta] = fma((double)o.a[ta][hlf].y, (double)o.x[hlf].y, accx[ta]);
+            accx[ta] = fma((double)o.a[ta][hlf].z, (double)o.x[hlf].z, accx[ta]);
+            accx[ta] = fma((double)o.a[ta][hlf].w, (double)o.x[hlf].w, accx[ta]);
+          }
+        }
+    }
 #pragma unroll
     for (int ta = 0; ta < kGramTa; ++ta) {
       if (ta < nta) {
 #pragma unroll
-        for (int tb = 0; tb < 2; ++tb) {
+        for (int tb = 0; tb < NTB; ++tb) {
           if (tb < ntb) {
 #pragma unroll
             for (int hlf = 0; hlf < 2; ++hlf) {
-              const f4 a4 = av[ta][hlf], b4 = bv[tb][hlf];
+              const f4 a4 = o.a[ta][hlf], b4 = o.b[tb][hlf];
               acc[ta][tb] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a4.x, (double)b4.x, acc[ta][tb], 0, 0, 0);
               acc[ta][tb] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a4.y, (double)b4.y, acc[ta][tb], 0, 0, 0);
               acc[ta][tb] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a4.z, (double)b4.z, acc[ta][tb], 0, 0, 0);
@@ -325,25 +385,37 @@ __global__ __launch_bounds__(256) void gram_mfma(const float* __restrict__ A, in
         }
       }
     }
-    if (more) {
-#pragma unroll
-      for (int ta = 0; ta < kGramTa; ++ta) {
-        av[ta][0] = an[ta][0];
-        av[ta][1] = an[ta][1];
-      }
-#pragma unroll
-      for (int tb = 0; tb < 2; ++tb) {
-        bv[tb][0] = bn[tb][0];
-        bv[tb][1] = bn[tb][1];
-      }
+  };
+
+  if constexpr (FAST) {
+    // Groups wholly below n, then the one that straddles it (at most one, in the last wave). No software prefetch: the
+    // kernel is bound by its fp64 MFMA steps, and three to four waves per SIMD cover each other's load latency; a
+    // second operand set in registers would cost that occupancy.
+    const int64_t full = n / 32;
+    const int64_t f_end = g_end < full ? g_end : full;
+    Ops o0;
+    for (; g < f_end; ++g) {
+      load_fast(g, o0);
+      compute(o0);
+    }
+    if (g < g_end) {
+      load_guarded(g, o0);
+      compute(o0);
+    }
+  } else {
+    Ops o0;
+    for (; g < g_end; ++g) {
+      load_guarded(g, o0);
+      compute(o0);
     }
   }
+
   // fp64 accumulator layout (differs from the fp32 one): register r of lane (q,p) is C[16 ta + 4 r + q][16 tb + p]
   const int64_t chunks = (int64_t)gridDim.x * 4, chunk_id = (int64_t)blockIdx.x * 4 + wave;
 #pragma unroll
   for (int ta = 0; ta < kGramTa; ++ta)
 #pragma unroll
-    for (int tb = 0; tb < 2; ++tb) {
+    for (int tb = 0; tb < NTB; ++tb) {
       const double vals[4] = {acc[ta][tb].x, acc[ta][tb].y, acc[ta][tb].z, acc[ta][tb].w};
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
@@ -351,6 +423,39 @@ __global__ __launch_bounds__(256) void gram_mfma(const float* __restrict__ A, in
         if (ta < nta && tb < ntb && a < ra && bcol < rb) Cp[(int64_t)(a * rb + bcol) * chunks + chunk_id] = vals[r];
       }
     }
+  if (xrow >= 0) {      // the lone row: lane (q, p) holds the part of C[16 ta + p][xrow] over its eight points per group
+#pragma unroll
+    for (int ta = 0; ta < kGramTa; ++ta) {
+      double v = accx[ta];
+      v += __shfl_xor(v, 16);
+      v += __shfl_xor(v, 32);
+      const int a = a_base + ta * 16 + p;
+      if (q == 0 && ta < nta && a < ra) Cp[(int64_t)(a * rb + xrow) * chunks + chunk_id] = v;
+    }
+  }
+}
+
+// Launch over `chunks` partial results (a multiple of 4: one per wave): the fast instantiation when both operands allow
+// 16-byte loads; one tile of B rows per wave up to 17 rows, two beyond. In the fast path a lone last row of B rides
+// with the last block of B rows, so it adds no block of its own.
+void launch_gram(int chunks, hipStream_t stream, const float* A, int ra, int64_t lda, const float* B, int rb,
+                 int64_t ldb, int64_t n, double* Cp) {
+  const int va = (int)((lda & 3) == 0 && (reinterpret_cast<uintptr_t>(A) & 15) == 0);
+  const int vb = (int)((ldb & 3) == 0 && (reinterpret_cast<uintptr_t>(B) & 15) == 0);
+  const bool fast = va && vb;
+  const int ntb = rb <= 17 ? 1 : 2;
+  const int brows = (fast && rb % 16 == 1) ? rb - 1 : rb;
+  int gz = (brows + 16 * ntb - 1) / (16 * ntb);
+  if (gz < 1) gz = 1;
+  const dim3 grid(chunks / 4, (ra + 16 * kGramTa - 1) / (16 * kGramTa), gz);
+  if (fast && ntb == 1)
+    hipLaunchKernelGGL((gram_mfma<true, 1>), grid, dim3(256), 0, stream, A, ra, lda, B, rb, ldb, n, Cp, va, vb);
+  else if (fast)
+    hipLaunchKernelGGL((gram_mfma<true, 2>), grid, dim3(256), 0, stream, A, ra, lda, B, rb, ldb, n, Cp, va, vb);
+  else if (ntb == 1)
+    hipLaunchKernelGGL((gram_mfma<false, 1>), grid, dim3(256), 0, stream, A, ra, lda, B, rb, ldb, n, Cp, va, vb);
+  else
+    hipLaunchKernelGGL((gram_mfma<false, 2>), grid, dim3(256), 0, stream, A, ra, lda, B, rb, ldb, n, Cp, va, vb);
 }
 
 // C[e] = sum over chunks of Cp[e][chunk], fp64, fixed order: 64 lanes stride the chunks, then a shuffle tree.
@@ -537,9 +642,7 @@ int precond_apply_cm(const float* L, int rank, const double* Minv_dev, int64_t n
   double* Wd = reinterpret_cast<double*>(w);
   w += round_up((size_t)rank * 33 * sizeof(double), 256);
   double* Y = reinterpret_cast<double*>(w);
-  dim3 grid(chunks / 4, (rank + 16 * kGramTa - 1) / (16 * kGramTa), (t + 31) / 32);
-  hipLaunchKernelGGL(gram_mfma, grid, dim3(256), 0, stream, L, rank, n, R, t, ld, n, Wp,
-                     (int)((n & 3) == 0 && (reinterpret_cast<uintptr_t>(L) & 15) == 0), (int)((ld & 3) == 0));
+  launch_gram(chunks, stream, L, rank, n, R, t, ld, n, Wp);
   hipLaunchKernelGGL(reduce_chunks, dim3((rank * t + 3) / 4), dim3(256), 0, stream, Wp, chunks, rank * t, Wd);
   const int ldy = t <= 16 ? 16 : (t <= 17 ? 17 : 33);
   if (coef_dev) *coef_dev = Y;
@@ -570,10 +673,7 @@ int gram_cm(const float* A, int ra, int64_t lda, const float* B, int rb, int64_t
             void* ws, hipStream_t stream) {
   const int chunks = chunks_for(n, ra, rb);
   double* Gp = static_cast<double*>(ws);
-  dim3 grid(chunks / 4, (ra + 16 * kGramTa - 1) / (16 * kGramTa), (rb + 31) / 32);
-  const int va = (int)((lda & 3) == 0 && (reinterpret_cast<uintptr_t>(A) & 15) == 0);
-  const int vb = (int)((ldb & 3) == 0 && (reinterpret_cast<uintptr_t>(B) & 15) == 0);
-  hipLaunchKernelGGL(gram_mfma, grid, dim3(256), 0, stream, A, ra, lda, B, rb, ldb, n, Gp, va, vb);
+  launch_gram(chunks, stream, A, ra, lda, B, rb, ldb, n, Gp);
   hipLaunchKernelGGL(reduce_chunks, dim3((ra * rb + 3) / 4), dim3(256), 0, stream, Gp, chunks, ra * rb, G_dev);
   EGP_HIP(hipGetLastError());
   return EGP_OK;
@@ -795,9 +895,7 @@ int pivchol_core(const float* X, int64_t n, const egp_hyper_t* h, float tol_abs,
   EGP_HIP(hipMemcpyAsync(P->pivots, st.pivots, sizeof(int) * rank, hipMemcpyDeviceToHost, stream));
   // Gram matrix of the factor's columns
   const int chunks = chunks_for(n, rank, rank);
-  dim3 grid(chunks / 4, (rank + 16 * kGramTa - 1) / (16 * kGramTa), (rank + 31) / 32);
-  const int vec = (int)((n & 3) == 0 && (reinterpret_cast<uintptr_t>(P->L) & 15) == 0);
-  hipLaunchKernelGGL(gram_mfma, grid, dim3(256), 0, stream, P->L, rank, n, P->L, rank, n, n, Gp, vec, vec);
+  launch_gram(chunks, stream, P->L, rank, n, P->L, rank, n, n, Gp);
   hipLaunchKernelGGL(reduce_chunks, dim3((rank * rank + 3) / 4), dim3(256), 0, stream, Gp, chunks, rank * rank, Gd);
   EGP_HIP(hipGetLastError());
   std::vector<double> G((size_t)rank * rank);
