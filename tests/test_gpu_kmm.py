@@ -7,7 +7,7 @@ from workloads import make_workload
 
 pytestmark = pytest.mark.gpu
 
-# the benchmark spec: relative Frobenius error of the KMM <= 1e-4 at fp32 (no reduced-precision MFMA is used)
+# the stated bound of this build: relative Frobenius error of the KMM <= 1e-4 at fp32 (no reduced-precision MFMA is used)
 KMM_TOL = 1e-4
 
 

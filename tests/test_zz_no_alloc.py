@@ -9,7 +9,7 @@ import pytest
 import oracle as orc
 
 pytestmark = pytest.mark.gpu
-KMM_TOL = 1e-4      # the benchmark spec's bound against the oracle; against egp_kmm the two entry points agree to the bit
+KMM_TOL = 1e-4      # the fp32 bound of the multiply against the oracle; against egp_kmm the two entry points agree to the bit
 
 
 @pytest.fixture(scope="module")
