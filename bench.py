@@ -65,14 +65,15 @@ def main():
     ap.add_argument("--kmm-only", action="store_true", help="skip preconditioner and mBCG timing")
     ap.add_argument("--no-full-solve", dest="full_solve", action="store_false",
                     help="skip the C4 solve to the paper's training tolerance (tol 1, rank 100, at most 100 iterations; ~20 s)")
-    ap.add_argument("--mll", type=int, default=10, metavar="ITERS",
+    ap.add_argument("--mll", type=int, default=None, metavar="ITERS",
                     help="iteration cap of the C5 marginal-likelihood step at the configuration's rank 100 (n=2^21, "
                          "Matern-3/2; that rank does not reach tolerance 1 within the configured 100 iterations); 0 skips "
-                         "both C5 legs")
+                         "both C5 legs (default: 10, or 0 with --kmm-only)")
     ap.add_argument("--mll-converged-rank", type=int, default=1024, metavar="K",
                     help="rank of the second C5 step, run to tolerance 1 (0 skips it)")
-    ap.add_argument("--no-grad", dest="grad", action="store_false",
-                    help="skip the C3 KMM and derivative products (n=2^18, d=25)")
+    ap.add_argument("--grad", dest="grad", action="store_true", default=None,
+                    help="time the C3 KMM and derivative products (n=2^18, d=25): the default, except with --kmm-only")
+    ap.add_argument("--no-grad", dest="grad", action="store_false", help="skip the C3 leg")
     ap.add_argument("--extra-modes", action="store_true",
                     help="also run the C4 solves in the all-bf16 mode and the rank-512 solve with one-sided kernels")
     ap.add_argument("--wide", action="store_true",
@@ -88,6 +89,10 @@ def main():
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB copy kernel (calibrates HBM counters under rocprofv3 --pmc)")
     args = ap.parse_args()
+    if args.grad is None:
+        args.grad = not args.kmm_only
+    if args.mll is None:
+        args.mll = 0 if args.kmm_only else 10
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (the whole n x n product on one MI355X); "
                  "--gpus must be 1")
