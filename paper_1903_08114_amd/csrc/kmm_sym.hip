@@ -10,14 +10,16 @@
 //   column side  needs the tile transposed relative to that layout. Each wave passes the tile through a private
 //                LDS patch (one 16-byte write, four 4-byte reads per lane, both free of bank conflicts), and
 //                contracts it with the packed V of its own row tiles (resident in registers). The column-side sums
-//                of a wave's R row tiles go to LDS; at the end of a stage the four waves' sums are added up and
+//                of a wave's R row tiles go to LDS; at the end of a stage the waves' sums are added up and
 //                leave the workgroup as 64-bit fixed-point atomic adds (colside_add, kmm_kernel.h) into an extra slab
 //                of the partial-sum buffer.
 //                (LDS float atomics were measured far too slow for the first step: plain stores, one patch per wave.)
-// Row-side accumulation has two levels, as in kmm_kernel, but the second level is not held in registers: after every
-// block of 4096 column points a wave adds its register accumulators to its own rows of the partial-sum slab in device
-// memory (plain loads and stores: a wave owns its rows of its split's slab) and clears them. That frees R * 16 NB
-// registers, which is what lets every 16- and 17-column shape keep eight row tiles per wave up to 8 distance k-steps.
+// Row-side accumulation has two levels, as in kmm_kernel. Where both fit the register file with eight row tiles per
+// wave (16 columns up to 4 distance k-steps, a single column) or the shape runs four row tiles anyway (32 / 33 columns),
+// the second level is a register set; for 17 columns (up to 4 k-steps) and for 16 columns beyond 4 k-steps it lives in
+// device memory instead: after every block of 4096 column points a wave adds its register accumulators to its own rows
+// of the partial-sum slab (plain loads and stores: a wave owns its rows of its split's slab) and clears them. That
+// frees R * 16 NB registers, which is what lets those shapes keep eight row tiles per wave.
 // The diagonal block and (for an even block count) the half-way block are computed one-sided, as in kmm_kernel.
 // Results differ from kmm_kernel's only in summation order. Within a workgroup that order is fixed, and the integer
 // atomic adds between workgroups commute exactly: results are reproducible bit for bit.
