@@ -76,3 +76,34 @@ def test_noalloc_rejects_sizes_beyond_the_scratch_array(egp):
     assert rc == -1 and b"scratch" in L.egp_last_error()
     assert L.egp_kmm_noalloc(C.c_void_p(X.data_ptr()), 0, C.c_void_p(V.data_ptr()), 17, C.byref(h),
                              C.c_void_p(V.data_ptr()), None) == -1
+
+
+def test_noalloc_under_hip_graph_capture(egp):
+    """What the entry point is for: a caller that cannot allocate captures it into a HIP graph (after one call outside
+    the capture, which looks up the scratch array's address). Every replay, with new right-hand sides and eager work
+    in between, gives the bits of an eager egp_kmm call (symmetric kernel: its column-side slab in the scratch array is
+    cleared by a fill kernel inside the graph, not by a memset node)."""
+    import torch
+    rng = np.random.default_rng(21)
+    n, d, t = 33000, 11, 17
+    X = torch.from_numpy(rng.uniform(0, 1, (n, d)).astype(np.float32)).cuda()
+    V = torch.from_numpy(rng.standard_normal((n, t)).astype(np.float32)).cuda()
+    ls = np.full(d, 0.8, np.float32)
+    out = torch.empty_like(V)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        egp.kmm_noalloc(X, V, ls, 1.1, 0.2, orc.RBF, out=out)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        egp.kmm_noalloc(X, V, ls, 1.1, 0.2, orc.RBF, out=out)
+    for _ in range(3):
+        V.copy_(torch.from_numpy(rng.standard_normal((n, t)).astype(np.float32)).cuda())
+        want = egp.kmm(X, V, ls, 1.1, 0.2, orc.RBF).clone()
+        torch.cuda.synchronize()
+        out.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want)
